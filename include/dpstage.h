@@ -1,0 +1,233 @@
+/*
+ * dpstage - forward+backward training step of one pipeline stage under a
+ * per-tensor keep / recompute / swap plan, for AMD MI355X (gfx950).
+ *
+ * The paper models a stage x as a node set N_x whose time is the sum of the
+ * nodes' forward and backward times (Section 4.1, Eq. 1), run within a device
+ * memory capacity M (Algorithm 1, feasibility test of AdjacentPartition), under
+ * a memory-optimisation result "mopt" that assigns swap or recomputation to
+ * individual saved tensors (Section 4.3).  This library is the executor of that
+ * statement for a stage made of transformer layers:
+ *
+ *   dp_stage_init    (layer config, weights)            -> stage handle
+ *   dp_stage_step    (micro-batch, plan, memory budget) -> Y, dX, dTheta
+ *   dp_plan_validate (config, plan, budget)             -> peak-memory report
+ *
+ * Plain C ABI: POD structs, raw pointers, sizes.  "device pointer" means memory
+ * of the current HIP device; "host pointer" ordinary process memory.  No call
+ * throws; every call returns a dp_status and dp_last_error() gives the text.
+ */
+#ifndef DPSTAGE_H
+#define DPSTAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dp_stage dp_stage; /* opaque, library-owned */
+
+typedef enum {
+  DP_OK = 0,
+  DP_E_INVAL = -1,       /* null pointer, bad enum, bad length, bad shape        */
+  DP_E_PLAN = -2,        /* plan asks for something impossible                    */
+  DP_E_BUDGET = -3,      /* inflight x peak_bytes exceeds budget_bytes            */
+  DP_E_DEVMEM = -4,      /* device allocation failed                              */
+  DP_E_HOSTMEM = -5,     /* pinned host allocation failed                         */
+  DP_E_HIP = -6,         /* a HIP runtime call or launch failed                   */
+  DP_E_UNSUPPORTED = -7  /* shape outside what the kernels were written for       */
+} dp_status;
+
+/* Plan actions, one byte per saved tensor.  Section 4.3: the candidates of the
+ * memory optimisation are the entries of every node's saved-tensor list, each
+ * left alone, swapped or recomputed. */
+typedef enum { DP_KEEP = 0, DP_RECOMPUTE = 1, DP_SWAP = 2 } dp_action;
+
+typedef enum { DP_POST_LN = 0, DP_PRE_LN = 1 } dp_norm_style;
+typedef enum { DP_GELU_ERF = 0, DP_GELU_TANH = 1 } dp_gelu_kind;
+typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+
+/* Saved tensors ("slots") of one layer, in plan order.  T = micro_batch*seq.
+ *   X_IN      [T,H]   layer input (stage input for layer 0; caller memory there)
+ *   LN1_STATS [T,2]   fp32 (mean, 1/sqrt(var+eps)) of LayerNorm 1
+ *   LN1_OUT   [T,H]
+ *   QKV       [T,3H]  columns [Q | K | V], head h = columns h*dh..(h+1)*dh-1
+ *   ATTN_LSE  [B,nh,S] fp32 log-sum-exp of the scaled logits
+ *   ATTN_OUT  [T,H]
+ *   RES1      [T,H]   X_IN + ATTN_OUT*Wo + bo
+ *   LN2_STATS [T,2]
+ *   LN2_OUT   [T,H]   pre-LN only (post-LN: it is the layer output; ignored)
+ *   FC1_OUT   [T,F]
+ *   GELU_OUT  [T,F]
+ *   RES2      [T,H]   post-LN only (pre-LN: it is the layer output; ignored)
+ */
+enum {
+  DP_SLOT_X_IN = 0, DP_SLOT_LN1_STATS, DP_SLOT_LN1_OUT, DP_SLOT_QKV, DP_SLOT_ATTN_LSE,
+  DP_SLOT_ATTN_OUT, DP_SLOT_RES1, DP_SLOT_LN2_STATS, DP_SLOT_LN2_OUT, DP_SLOT_FC1_OUT,
+  DP_SLOT_GELU_OUT, DP_SLOT_RES2, DP_SLOTS_PER_LAYER
+};
+
+/* A stage = n_layers identical transformer layers on one micro-batch.
+ *   pre-LN : a=LN1(x); m=x+Attn(a*Wqkv+b)*Wo+bo; c=LN2(m); y=m+GELU(c*W1+b1)*W2+b2
+ *   post-LN: r1=x+Attn(x*Wqkv+b)*Wo+bo; m=LN1(r1); r2=m+GELU(m*W1+b1)*W2+b2; y=LN2(r2)
+ * The paper names the workloads only (BERT, GPT-2; Section 5.1); the layer
+ * mathematics is the textbook one.  No dropout, no padding mask.
+ * dtype DP_BF16: weights, slots, outputs and gradients are bf16, accumulation
+ * and statistics fp32.  DP_F32: everything fp32 (debug mode). */
+typedef struct {
+  int32_t n_layers, hidden, n_heads, ffn, seq, micro_batch;
+  int32_t norm_style; /* dp_norm_style */
+  int32_t causal;     /* 0: full attention, 1: causal mask */
+  int32_t gelu_kind;  /* dp_gelu_kind */
+  int32_t dtype;      /* dp_dtype */
+  float ln_eps;
+} dp_stage_config;
+
+/* Device pointers.  Linear weights are [in, out] row-major (y = x*W + b);
+ * w_qkv is [H, 3H]; element type = config dtype.  Caller-owned. */
+typedef struct {
+  const void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+  const void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} dp_layer_weights;
+
+/* Device pointers receiving the weight gradients: same shapes, layouts and
+ * dtype as the weights; overwritten, not accumulated.  Caller-owned. */
+typedef struct {
+  void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+  void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} dp_layer_grads;
+
+/* Memory report of one plan.  peak_bytes follows the running-peak walk of
+ * Algorithm 2 (add what a node allocates, take the max, subtract what it
+ * releases), carried over forward, replay and backward:
+ *   peak_bytes = fixed_bytes + arena_peak_bytes, where
+ *   fixed_bytes      = library weight copies + caller's weights, gradients, x, dy, y, dx
+ *   arena_peak_bytes = high-water mark of the library's activation arena under
+ *                      the same offset allocator dp_stage_step uses
+ *   live_peak_bytes  = fixed_bytes + max over time of the sum of live arena
+ *                      blocks (the walk without fragmentation) */
+typedef struct {
+  uint64_t peak_bytes, live_peak_bytes, fixed_bytes, arena_peak_bytes;
+  uint64_t weight_bytes, grad_bytes, kept_act_bytes;
+  uint64_t swap_out_bytes, swap_in_bytes, host_pinned_bytes;
+  double replay_flops, step_flops;
+  int32_t n_replayed_ops, n_swapped_slots;
+  int32_t first_bad_layer, first_bad_slot; /* -1 if none */
+} dp_plan_report;
+
+typedef struct {
+  float step_ms, fwd_ms, bwd_ms;
+  uint64_t d2h_bytes, h2d_bytes, arena_high_water, peak_bytes;
+  int32_t n_kernel_launches, n_replayed_ops;
+} dp_step_stats;
+
+/* Kernel classes for dp_stage_op_times. */
+enum {
+  DP_OPC_GEMM_FWD = 0, DP_OPC_GEMM_DGRAD, DP_OPC_GEMM_WGRAD, DP_OPC_ATTN_FWD, DP_OPC_ATTN_BWD,
+  DP_OPC_LN_FWD, DP_OPC_LN_BWD, DP_OPC_GELU_FWD, DP_OPC_GELU_BWD, DP_OPC_REDUCE, DP_OPC_COUNT
+};
+
+/* Number of plan bytes: n_layers * DP_SLOTS_PER_LAYER; 0 if cfg is invalid.
+ * plan[l*DP_SLOTS_PER_LAYER + slot] is a dp_action. */
+size_t dp_plan_len(const dp_stage_config *cfg);
+
+/* Pure host code: walks the step's schedule under `plan` and fills `report`
+ * (nullable).  Feasible iff inflight * peak_bytes <= budget_bytes (Algorithm 1's
+ * test (l-x+1)*M_x against M; a budget equal to the peak must run);
+ * budget_bytes == 0 means "no limit"; inflight >= 1 is the number of
+ * micro-batches whose activations the stage holds at once.
+ * Errors: DP_E_INVAL (null cfg/plan, wrong plan_len, action > 2, bad config),
+ * DP_E_PLAN (X_IN of layer 0 marked RECOMPUTE: it has no producer in the stage;
+ * report->first_bad_* name it), DP_E_UNSUPPORTED (shape), DP_E_BUDGET.
+ * Plan bytes of slots without storage (see the slot list) are ignored; SWAP on
+ * X_IN of layer 0 is treated as KEEP because that buffer is the caller's. */
+dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len,
+                           uint64_t budget_bytes, uint32_t inflight, dp_plan_report *report);
+
+/* Creates a stage on the current HIP device.  `layers` is a host array of
+ * n_layers structs of device pointers; the weights are copied (and re-laid
+ * out) into library-owned device memory before the call returns, so the caller
+ * may free theirs.  arena_bytes_hint: initial size of the activation arena
+ * (0 = size it on first use; it grows when a plan needs more).  The library
+ * owns the arena (hipMalloc), the pinned host pool (hipHostMalloc, sized by the
+ * first plan that swaps), two copy streams and its events. */
+dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *layers,
+                        uint64_t arena_bytes_hint, dp_stage **out);
+
+/* One forward+backward step of the stage on one micro-batch.
+ *   x_in  [T,H] device, read     dy     [T,H] device, read (gradient of y_out)
+ *   y_out [T,H] device, written  dx_out [T,H] device, written
+ *   dw: host array of n_layers structs of device pointers, all written.
+ * All four activations and all gradients have the config dtype, row-major,
+ * token t = b*seq + s.  Buffers must not overlap each other.
+ * The plan is validated first: any error (see dp_plan_validate; inflight = 1)
+ * is returned before anything is enqueued.  Work is enqueued on `hip_stream`
+ * (a hipStream_t; NULL = the default stream) and on the library's copy streams,
+ * which are joined back into hip_stream before return; the call does not wait
+ * for the device unless `stats` is non-NULL.  DP_E_HIP after a partial enqueue
+ * leaves the outputs undefined.  One step at a time per handle.
+ * The results are bit-identical for every plan. */
+dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const uint8_t *plan,
+                        size_t plan_len, uint64_t budget_bytes, void *y_out, void *dx_out,
+                        const dp_layer_grads *dw, void *hip_stream, dp_step_stats *stats);
+
+/* Per-kernel-class timing of later steps: when enabled, every kernel launch is
+ * bracketed by HIP events on the stream it runs on.  dp_stage_op_times waits
+ * for the device, then returns (and clears) the summed milliseconds and launch
+ * counts per class since the last call; arrays of DP_OPC_COUNT entries. */
+dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled);
+dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches_by_class);
+
+/* Debug switches, all default 0: bit 0 = serialise (copies on the compute
+ * stream, no overlap); bit 1 = poison arena blocks with NaN patterns when they
+ * are released (catches use-after-release and late swap-in). */
+dp_status dp_stage_set_debug(dp_stage *st, uint32_t flags);
+
+void dp_stage_destroy(dp_stage *st);
+
+/* Text of the calling thread's last error ("" if none); static storage. */
+const char *dp_last_error(void);
+
+/* Standalone operator entry points (device pointers, row-major, enqueue on
+ * `hip_stream`, no host wait).  They run the same kernels dp_stage_step uses
+ * and exist for operator-level parity tests and microbenchmarks.
+ * `ws` is a device workspace of at least dp_op_workspace_bytes(...) bytes
+ * (needed by the ops that reduce over rows; may be NULL otherwise). */
+size_t dp_op_workspace_bytes(int32_t rows, int32_t cols);
+
+/* y = LayerNorm(x)*gamma+beta per row of [rows, cols]; stats [rows,2] fp32
+ * (mean, rstd); y or stats may be NULL (not written). */
+dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x,
+                              const void *gamma, const void *beta, void *y, float *stats, void *hip_stream);
+/* dx = [dres +] LayerNorm-backward(dy); dgamma, dbeta over all rows. */
+dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
+                              const float *stats, const void *gamma, const void *dres /*nullable*/,
+                              void *dx, void *dgamma, void *dbeta, void *ws, void *hip_stream);
+dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream);
+/* dx = dy * gelu'(x) */
+dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,
+                         void *hip_stream);
+/* C[M,N] = op(A)*op(B) (+bias[N]) (+res[M,N]).  mode 0 ("NT"): A [M,K], B [N,K]
+ * (both contraction-contiguous: forward with the transposed weight copy, and
+ * dX = dY*W^T with W as stored); mode 1 ("TN"): A [K,M], B [K,N] (contraction
+ * over the leading dimension of both: dW = X^T*dY). */
+dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
+                     const void *bias, const void *res, void *C, void *hip_stream);
+/* out[cols] = sum over rows of x[rows, cols] */
+dp_status dp_op_colsum(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out, void *ws,
+                       void *hip_stream);
+/* o [T,H], lse [B,nh,S] from qkv [T,3H]; o or lse may be NULL. */
+dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
+                              const void *qkv, void *o, float *lse, void *hip_stream);
+/* dqkv [T,3H] from qkv, o, lse, d_o; ws: device workspace of
+ * dp_op_workspace_bytes(T, nh) bytes. */
+dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
+                              const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv,
+                              void *ws, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPSTAGE_H */

@@ -1,0 +1,260 @@
+"""ctypes binding of libdpstage.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the
+`dp_` prefix) and does nothing but turn torch tensors / numpy arrays into the
+pointers and sizes the C ABI takes.  torch supplies device memory and the
+stream; all computation happens in the library's kernels.  There is no
+fallback: a missing library is an ImportError-like RuntimeError.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdpstage.so")
+
+WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+SLOTS_PER_LAYER = 12
+OP_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd",
+              "ln_fwd", "ln_bwd", "gelu_fwd", "gelu_bwd", "reduce")
+STATUS = {0: "DP_OK", -1: "DP_E_INVAL", -2: "DP_E_PLAN", -3: "DP_E_BUDGET", -4: "DP_E_DEVMEM",
+          -5: "DP_E_HOSTMEM", -6: "DP_E_HIP", -7: "DP_E_UNSUPPORTED"}
+
+
+class DpError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"{STATUS.get(code, code)}: {text}")
+        self.code = code
+        self.status = STATUS.get(code, str(code))
+
+
+class StageConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "micro_batch",
+                                         "norm_style", "causal", "gelu_kind", "dtype")] + [("ln_eps", C.c_float)]
+
+
+class LayerPtrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class PlanReport(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("peak_bytes", "live_peak_bytes", "fixed_bytes", "arena_peak_bytes",
+                                          "weight_bytes", "grad_bytes", "kept_act_bytes", "swap_out_bytes",
+                                          "swap_in_bytes", "host_pinned_bytes")] + \
+               [("replay_flops", C.c_double), ("step_flops", C.c_double)] + \
+               [(n, C.c_int32) for n in ("n_replayed_ops", "n_swapped_slots", "first_bad_layer", "first_bad_slot")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class StepStats(C.Structure):
+    _fields_ = [("step_ms", C.c_float), ("fwd_ms", C.c_float), ("bwd_ms", C.c_float)] + \
+               [(n, C.c_uint64) for n in ("d2h_bytes", "h2d_bytes", "arena_high_water", "peak_bytes")] + \
+               [("n_kernel_launches", C.c_int32), ("n_replayed_ops", C.c_int32)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the library (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_05856_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, u64, sz = C.c_void_p, C.c_int32, C.c_uint64, C.c_size_t
+    L.dp_last_error.restype = C.c_char_p
+    L.dp_plan_len.restype = sz
+    L.dp_plan_len.argtypes = [C.POINTER(StageConfig)]
+    L.dp_plan_validate.argtypes = [C.POINTER(StageConfig), vp, sz, u64, C.c_uint32, C.POINTER(PlanReport)]
+    L.dp_stage_init.argtypes = [C.POINTER(StageConfig), C.POINTER(LayerPtrs), u64, C.POINTER(vp)]
+    L.dp_stage_step.argtypes = [vp, vp, vp, vp, sz, u64, vp, vp, C.POINTER(LayerPtrs), vp, C.POINTER(StepStats)]
+    L.dp_stage_set_profiling.argtypes = [vp, i32]
+    L.dp_stage_op_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(u64)]
+    L.dp_stage_set_debug.argtypes = [vp, C.c_uint32]
+    L.dp_stage_destroy.argtypes = [vp]
+    L.dp_stage_destroy.restype = None
+    L.dp_op_workspace_bytes.restype = sz
+    L.dp_op_workspace_bytes.argtypes = [i32, i32]
+    L.dp_op_layernorm_fwd.argtypes = [i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
+    L.dp_op_layernorm_bwd.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.dp_op_gelu_fwd.argtypes = [i32, i32, sz, vp, vp, vp]
+    L.dp_op_gelu_bwd.argtypes = [i32, i32, sz, vp, vp, vp, vp]
+    L.dp_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    L.dp_op_colsum.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+    L.dp_op_attention_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    L.dp_op_attention_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    for name in ("dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_set_profiling",
+                 "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
+                 "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
+                 "dp_op_attention_bwd"):
+        getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+def _check(code: int):
+    if code != 0:
+        raise DpError(code, lib().dp_last_error().decode())
+
+
+def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, norm_style="post", causal=False,
+                gelu="erf", dtype="bf16", ln_eps=1e-5) -> StageConfig:
+    return StageConfig(n_layers, hidden, n_heads, ffn, seq, micro_batch,
+                       {"post": 0, "pre": 1}[norm_style], int(bool(causal)), {"erf": 0, "tanh": 1}[gelu],
+                       {"f32": 0, "bf16": 1}[dtype], ln_eps)
+
+
+def _plan_buf(plan):
+    a = np.ascontiguousarray(np.asarray(plan, dtype=np.uint8))
+    return a, a.ctypes.data_as(C.c_void_p), a.size
+
+
+def plan_len(cfg: StageConfig) -> int:
+    return int(lib().dp_plan_len(C.byref(cfg)))
+
+
+def plan_validate(cfg: StageConfig, plan, budget_bytes: int = 0, inflight: int = 1, raise_on_error=True):
+    """Returns (status_code, report dict)."""
+    rep = PlanReport()
+    if plan is None:
+        code = lib().dp_plan_validate(C.byref(cfg), None, 0, budget_bytes, inflight, C.byref(rep))
+    else:
+        keep, p, n = _plan_buf(plan)
+        code = lib().dp_plan_validate(C.byref(cfg), p, n, budget_bytes, inflight, C.byref(rep))
+    if raise_on_error:
+        _check(code)
+    return code, rep.as_dict()
+
+
+def last_error() -> str:
+    return lib().dp_last_error().decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _layer_array(layers: Sequence[Dict[str, "object"]]):
+    arr = (LayerPtrs * len(layers))()
+    for i, d in enumerate(layers):
+        for n in WEIGHT_FIELDS:
+            setattr(arr[i], n, d[n].data_ptr())
+    return arr
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Stage:
+    """Owns a dp_stage handle."""
+
+    def __init__(self, handle: int, cfg: StageConfig):
+        self.handle, self.cfg = handle, cfg
+
+    def close(self):
+        if self.handle:
+            lib().dp_stage_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def stage_init(cfg: StageConfig, weights: Sequence[Dict[str, "object"]], arena_bytes_hint: int = 0) -> Stage:
+    """weights: per layer, a dict of contiguous device tensors named as WEIGHT_FIELDS."""
+    out = C.c_void_p()
+    _check(lib().dp_stage_init(C.byref(cfg), _layer_array(weights), arena_bytes_hint, C.byref(out)))
+    return Stage(out.value, cfg)
+
+
+def stage_step(stage: Stage, x_in, dy, plan, budget_bytes, y_out, dx_out, grads: Sequence[Dict[str, "object"]],
+               stream=None, want_stats: bool = False):
+    keep, p, n = _plan_buf(plan)
+    stats = StepStats() if want_stats else None
+    _check(lib().dp_stage_step(stage.handle, _ptr(x_in), _ptr(dy), p, n, budget_bytes, _ptr(y_out), _ptr(dx_out),
+                               _layer_array(grads), _stream_ptr(stream),
+                               C.byref(stats) if want_stats else None))
+    return stats.as_dict() if want_stats else None
+
+
+def stage_set_profiling(stage: Stage, enabled: bool):
+    _check(lib().dp_stage_set_profiling(stage.handle, int(enabled)))
+
+
+def stage_op_times(stage: Stage):
+    ms = (C.c_float * len(OP_CLASSES))()
+    cnt = (C.c_uint64 * len(OP_CLASSES))()
+    _check(lib().dp_stage_op_times(stage.handle, ms, cnt))
+    return {n: (float(ms[i]), int(cnt[i])) for i, n in enumerate(OP_CLASSES)}
+
+
+def stage_set_debug(stage: Stage, flags: int):
+    _check(lib().dp_stage_set_debug(stage.handle, flags))
+
+
+# ---------------------------------------------------------------- standalone ops
+def _dt(t) -> int:
+    import torch
+    return {torch.float32: 0, torch.bfloat16: 1}[t.dtype]
+
+
+def op_workspace_bytes(rows: int, cols: int) -> int:
+    return int(lib().dp_op_workspace_bytes(rows, cols))
+
+
+def op_layernorm_fwd(x, gamma, beta, eps, y, stats, stream=None):
+    _check(lib().dp_op_layernorm_fwd(_dt(x), x.shape[0], x.shape[1], eps, _ptr(x), _ptr(gamma), _ptr(beta),
+                                     _ptr(y), _ptr(stats), _stream_ptr(stream)))
+
+
+def op_layernorm_bwd(dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, stream=None):
+    _check(lib().dp_op_layernorm_bwd(_dt(x), x.shape[0], x.shape[1], _ptr(dy), _ptr(x), _ptr(stats), _ptr(gamma),
+                                     _ptr(dres), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(ws),
+                                     _stream_ptr(stream)))
+
+
+def op_gelu_fwd(x, y, kind=0, stream=None):
+    _check(lib().dp_op_gelu_fwd(_dt(x), kind, x.numel(), _ptr(x), _ptr(y), _stream_ptr(stream)))
+
+
+def op_gelu_bwd(dy, x, dx, kind=0, stream=None):
+    _check(lib().dp_op_gelu_bwd(_dt(x), kind, x.numel(), _ptr(dy), _ptr(x), _ptr(dx), _stream_ptr(stream)))
+
+
+def op_gemm(mode, M, N, K, A, B, bias, res, Cout, stream=None):
+    _check(lib().dp_op_gemm(_dt(A), mode, M, N, K, _ptr(A), _ptr(B), _ptr(bias), _ptr(res), _ptr(Cout),
+                            _stream_ptr(stream)))
+
+
+def op_colsum(x, out, ws, stream=None):
+    _check(lib().dp_op_colsum(_dt(x), x.shape[0], x.shape[1], _ptr(x), _ptr(out), _ptr(ws), _stream_ptr(stream)))
+
+
+def op_attention_fwd(qkv, B, S, nh, dh, causal, o, lse, stream=None):
+    _check(lib().dp_op_attention_fwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv), _ptr(o), _ptr(lse),
+                                     _stream_ptr(stream)))
+
+
+def op_attention_bwd(qkv, o, lse, d_o, B, S, nh, dh, causal, dqkv, ws, stream=None):
+    _check(lib().dp_op_attention_bwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o),
+                                     _ptr(dqkv), _ptr(ws), _stream_ptr(stream)))

@@ -1,0 +1,399 @@
+// HBM-bound kernels of the stage step: LayerNorm forward/backward, GELU
+// forward/backward, column sums (bias gradients), transposes, fills.
+//
+// LayerNorm works one wavefront per row: a lane owns the same 8-element column
+// groups in every row, so the row statistics are wave reductions and the
+// dgamma/dbeta column sums accumulate in registers over the rows a block
+// visits.  Cross-row reductions are two-pass and ordered (no float atomics), so
+// results do not depend on scheduling.
+#include "common.h"
+#include "kernels.h"
+
+namespace dp {
+
+// ------------------------------------------------------------------ LayerNorm
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
+                                                     const T *__restrict__ beta, T *__restrict__ y,
+                                                     float *__restrict__ stats, int rows, int cols, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T *xr = x + (size_t)row * cols;
+  float v[NC][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int col = (c * 64 + lane) * 8;
+    if (col < cols) {
+      load8(xr + col, v[c]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += v[c][i];
+    }
+  }
+  const float inv_n = 1.0f / (float)cols;
+  const float mean = wave_sum(sum) * inv_n;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int col = (c * 64 + lane) * 8;
+    if (col < cols) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float d = v[c][i] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float var = wave_sum(sq) * inv_n;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  if (stats != nullptr && lane == 0) {
+    stats[2 * (size_t)row] = mean;
+    stats[2 * (size_t)row + 1] = rstd;
+  }
+  if (y == nullptr) return;
+  T *yr = y + (size_t)row * cols;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int col = (c * 64 + lane) * 8;
+    if (col < cols) {
+      float g[8], b[8], o[8];
+      load8(gamma + col, g);
+      load8(beta + col, b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = g[i] * ((v[c][i] - mean) * rstd) + b[i];
+      store8(yr + col, o);
+    }
+  }
+}
+
+// Pass 1 of LayerNorm backward.  Block b handles rows [b*rpb, (b+1)*rpb), one
+// wave per row; writes dx and the block's partial (dgamma | dbeta) row into
+// part[b][2*cols].
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
+                                                     const float *__restrict__ stats, const T *__restrict__ gamma,
+                                                     const T *__restrict__ dres, T *dx,
+                                                     float *__restrict__ part, int rows, int cols, int rpb) {
+  __shared__ float red[4][2][512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row_end = min(rows, (int)(blockIdx.x + 1) * rpb);
+  float dg[NC][8], db[NC][8], gm[NC][8];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    const int col = (c * 64 + lane) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dg[c][i] = 0.f; db[c][i] = 0.f; gm[c][i] = 0.f; }
+    if (col < cols) load8(gamma + col, gm[c]);
+  }
+  const float inv_n = 1.0f / (float)cols;
+  for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
+    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+    const size_t base = (size_t)row * cols;
+    float xh[NC][8], g[NC][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int col = (c * 64 + lane) * 8;
+      if (col < cols) {
+        float d[8];
+        load8(x + base + col, xh[c]);
+        load8(dy + base + col, d);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          xh[c][i] = (xh[c][i] - mean) * rstd;
+          dg[c][i] += d[i] * xh[c][i];
+          db[c][i] += d[i];
+          g[c][i] = d[i] * gm[c][i];
+          s1 += g[c][i];
+          s2 += g[c][i] * xh[c][i];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int col = (c * 64 + lane) * 8;
+      if (col < cols) {
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = rstd * (g[c][i] - m1 - xh[c][i] * m2);
+        if (dres != nullptr) {
+          float r[8];
+          load8(dres + base + col, r);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] += r[i];
+        }
+        store8(dx + base + col, o);
+      }
+    }
+  }
+  // ordered block reduction of the four waves' column partials, 512 columns at a time
+  float *prow = part + (size_t)blockIdx.x * 2 * cols;
+#pragma unroll
+  for (int c = 0; c < NC; ++c) {
+    if (c * 512 >= cols) break;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      red[wave][0][lane * 8 + i] = dg[c][i];
+      red[wave][1][lane * 8 + i] = db[c][i];
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < 1024; j += 256) {
+      const int which = j >> 9, k = j & 511;
+      const int col = c * 512 + k;
+      if (col < cols) {
+        const float s = ((red[0][which][k] + red[1][which][k]) + red[2][which][k]) + red[3][which][k];
+        prow[(size_t)which * cols + col] = s;
+      }
+    }
+  }
+}
+
+// Pass 2: out[j] = sum_{b<nb} part[b][j], summed in a fixed order.
+// Block = 64 columns x 16 row groups.
+template <typename T>
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nb, int width,
+                                                               T *__restrict__ out0, T *__restrict__ out1,
+                                                               int split) {
+  __shared__ float red[16][64];
+  const int cx = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cx;
+  float s = 0.f;
+  if (col < width)
+    for (int b = g; b < nb; b += 16) s += part[(size_t)b * width + col];
+  red[g][cx] = s;
+  __syncthreads();
+  if (g == 0 && col < width) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][cx];
+    if (col < split) stf(out0 + col, t);
+    else stf(out1 + (col - split), t);
+  }
+}
+
+// Column sums of x [rows, cols]: block (cx, rb) covers 512 columns and rows
+// [rb*rpb, (rb+1)*rpb); partial row rb of part[nrb][cols].
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, float *__restrict__ part, int rows,
+                                                     int cols, int rpb) {
+  __shared__ float red[4][512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = (blockIdx.x * 64 + lane) * 8;
+  const int row_end = min(rows, (int)(blockIdx.y + 1) * rpb);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < cols) {
+    for (int row = blockIdx.y * rpb + wave; row < row_end; row += 4) {
+      float v[8];
+      load8(x + (size_t)row * cols + col, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += v[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) red[wave][lane * 8 + i] = acc[i];
+  __syncthreads();
+  for (int k = threadIdx.x; k < 512; k += 256) {
+    const int c = blockIdx.x * 512 + k;
+    if (c < cols) part[(size_t)blockIdx.y * cols + c] = ((red[0][k] + red[1][k]) + red[2][k]) + red[3][k];
+  }
+}
+
+// ------------------------------------------------------------------ GELU
+__device__ __forceinline__ float gelu_f(float x, int kind) {
+  if (kind == 0) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+  const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+  return 0.5f * x * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float gelu_df(float x, int kind) {
+  if (kind == 0) {
+    const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+    const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
+    return cdf + x * pdf;
+  }
+  const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+  const float t = tanhf(u);
+  const float du = 0.79788456080286536f * (1.0f + 0.134145f * x * x);
+  return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * du;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, size_t n8,
+                                                       int kind) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float v[8];
+    load8(x + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = gelu_f(v[k], kind);
+    store8(y + i * 8, v);
+  }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
+                                                       T *dx, size_t n8, int kind) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float v[8], d[8];
+    load8(x + i * 8, v);
+    load8(dy + i * 8, d);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = d[k] * gelu_df(v[k], kind);
+    store8(dx + i * 8, v);
+  }
+}
+
+// ------------------------------------------------------------------ misc
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int rows,
+                                                        int cols) {
+  __shared__ T tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  for (int i = ty; i < 32; i += 8)
+    if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(size_t)(r0 + i) * cols + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8)
+    if (c0 + i < cols && r0 + tx < rows) dst[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, size_t n, uint32_t pattern) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = pattern;
+}
+
+// ------------------------------------------------------------------ launchers
+bool ln_supported(int dtype, int cols) {
+  (void)dtype;
+  return cols > 0 && cols % 8 == 0 && cols <= 8192;
+}
+
+static int ln_chunks(int cols) {
+  const int c = (cols + 511) / 512;
+  return c <= 1 ? 1 : c <= 2 ? 2 : c <= 4 ? 4 : c <= 8 ? 8 : 16;
+}
+
+template <typename T>
+static hipError_t ln_fwd_t(int rows, int cols, float eps, const void *x, const void *gamma, const void *beta,
+                           void *y, float *stats, hipStream_t s) {
+  const dim3 grid((rows + 3) / 4), block(256);
+#define DP_LN_FWD(NC)                                                                                       \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, NC>), grid, block, 0, s, (const T *)x, (const T *)gamma,             \
+                     (const T *)beta, (T *)y, stats, rows, cols, eps)
+  switch (ln_chunks(cols)) {
+    case 1: DP_LN_FWD(1); break;
+    case 2: DP_LN_FWD(2); break;
+    case 4: DP_LN_FWD(4); break;
+    case 8: DP_LN_FWD(8); break;
+    default: DP_LN_FWD(16); break;
+  }
+#undef DP_LN_FWD
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x, const void *gamma,
+                         const void *beta, void *y, float *stats, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  return dtype == kBF16 ? ln_fwd_t<bf16>(rows, cols, eps, x, gamma, beta, y, stats, s)
+                        : ln_fwd_t<float>(rows, cols, eps, x, gamma, beta, y, stats, s);
+}
+
+template <typename T>
+static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, const float *stats,
+                           const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *ws,
+                           hipStream_t s) {
+  int rpb;
+  const int nb = row_blocks(rows, 8, &rpb);
+  float *part = (float *)ws;
+#define DP_LN_BWD(NC)                                                                                      \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NC>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, stats, \
+                     (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
+  switch (ln_chunks(cols)) {
+    case 1: DP_LN_BWD(1); break;
+    case 2: DP_LN_BWD(2); break;
+    case 4: DP_LN_BWD(4); break;
+    case 8: DP_LN_BWD(8); break;
+    default: DP_LN_BWD(16); break;
+  }
+#undef DP_LN_BWD
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((2 * cols + 63) / 64), dim3(1024), 0, s, part, nb,
+                     2 * cols, (T *)dgamma, (T *)dbeta, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
+                         const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *ws,
+                         hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  return dtype == kBF16 ? ln_bwd_t<bf16>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, s)
+                        : ln_bwd_t<float>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, s);
+}
+
+static int ew_grid(size_t n8) {
+  size_t g = (n8 + 255) / 256;
+  if (g > 256 * 16) g = 256 * 16;
+  return g < 1 ? 1 : (int)g;
+}
+
+hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const size_t n8 = n / 8;
+  if (dtype == kBF16)
+    hipLaunchKernelGGL((gelu_fwd_kernel<bf16>), dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16 *)x, (bf16 *)y, n8,
+                       kind);
+  else
+    hipLaunchKernelGGL((gelu_fwd_kernel<float>), dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)x, (float *)y,
+                       n8, kind);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const size_t n8 = n / 8;
+  if (dtype == kBF16)
+    hipLaunchKernelGGL((gelu_bwd_kernel<bf16>), dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16 *)dy,
+                       (const bf16 *)x, (bf16 *)dx, n8, kind);
+  else
+    hipLaunchKernelGGL((gelu_bwd_kernel<float>), dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)dy,
+                       (const float *)x, (float *)dx, n8, kind);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t colsum_t(int rows, int cols, const void *x, void *out, void *ws, hipStream_t s) {
+  int rpb;
+  const int nb = row_blocks(rows, 16, &rpb);
+  float *part = (float *)ws;
+  hipLaunchKernelGGL((colsum_kernel<T>), dim3((cols + 511) / 512, nb), dim3(256), 0, s, (const T *)x, part, rows,
+                     cols, rpb);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((cols + 63) / 64), dim3(1024), 0, s, part, nb, cols,
+                     (T *)out, (T *)out, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  return dtype == kBF16 ? colsum_t<bf16>(rows, cols, x, out, ws, s) : colsum_t<float>(rows, cols, x, out, ws, s);
+}
+
+hipError_t launch_transpose(int dtype, int rows, int cols, const void *src, void *dst, hipStream_t s) {
+  const dim3 grid((cols + 31) / 32, (rows + 31) / 32), block(256);
+  if (dtype == kBF16)
+    hipLaunchKernelGGL((transpose_kernel<bf16>), grid, block, 0, s, (const bf16 *)src, (bf16 *)dst, rows, cols);
+  else
+    hipLaunchKernelGGL((transpose_kernel<float>), grid, block, 0, s, (const float *)src, (float *)dst, rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(void *p, size_t n_words, uint32_t pattern, hipStream_t s) {
+  if (n_words == 0) return hipSuccess;
+  size_t g = (n_words + 255) / 256;
+  if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((int)g), dim3(256), 0, s, (uint32_t *)p, n_words, pattern);
+  return hipGetLastError();
+}
+
+}  // namespace dp

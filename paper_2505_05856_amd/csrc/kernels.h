@@ -1,0 +1,77 @@
+// Internal launcher interface between the step executor and the HIP kernels.
+// Every launcher enqueues on `s` and returns hipGetLastError(); none waits.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dp {
+
+enum { kF32 = 0, kBF16 = 1 };
+enum { kGemmNT = 0, kGemmTN = 1 };
+
+inline size_t dtype_size(int dtype) { return dtype == kBF16 ? 2 : 4; }
+
+// Upper bound of row-blocks used by the two-pass column reductions.
+constexpr int kMaxRowBlocks = 512;
+// Row blocks of a two-pass column reduction: at least `min_rows` rows a block, at
+// most kMaxRowBlocks blocks.  Returns the block count, *rpb = rows per block.
+inline int row_blocks(int rows, int min_rows, int *rpb) {
+  int nb = (rows + min_rows - 1) / min_rows;
+  if (nb > kMaxRowBlocks) nb = kMaxRowBlocks;
+  if (nb < 1) nb = 1;
+  *rpb = (rows + nb - 1) / nb;
+  return (rows + *rpb - 1) / *rpb;
+}
+// Bytes of fp32 partials a column reduction over [rows, cols] needs (x2: LayerNorm
+// backward reduces two vectors at once).
+inline size_t reduce_ws_bytes(int rows, int cols) {
+  int rpb;
+  return (size_t)row_blocks(rows, 8, &rpb) * 2 * (size_t)cols * sizeof(float);
+}
+
+struct GemmArgs {
+  int mode;            // kGemmNT: A [M,K], B [N,K];  kGemmTN: A [K,M], B [K,N]
+  int M, N, K;
+  const void *A, *B;
+  const void *bias;    // [N] or null
+  const void *res;     // [M,N] or null, added after bias
+  void *C;             // [M,N]
+};
+
+// ---- shape support (host checks; the launchers assume they passed) ----------
+bool ln_supported(int dtype, int cols);                 // cols % 8 == 0, cols <= 8192
+bool gemm_mfma_supported(const GemmArgs &a);            // bf16 MFMA path preconditions
+bool attn_mfma_supported(int S, int dh);
+
+// ---- elementwise / reductions ----------------------------------------------
+hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x, const void *gamma,
+                         const void *beta, void *y, float *stats, hipStream_t s);
+hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
+                         const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *ws,
+                         hipStream_t s);
+hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s);
+hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s);
+hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s);
+// dst[c, r] = src[r, c]
+hipError_t launch_transpose(int dtype, int rows, int cols, const void *src, void *dst, hipStream_t s);
+hipError_t launch_fill_u32(void *p, size_t n_words, uint32_t pattern, hipStream_t s);
+
+// ---- GEMM -------------------------------------------------------------------
+hipError_t launch_gemm_simple(int dtype, const GemmArgs &a, hipStream_t s);
+hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
+
+// ---- attention ----------------------------------------------------------------
+// qkv [T,3H]; o [T,H] (nullable); lse [B,nh,S] fp32 (nullable)
+hipError_t launch_attn_fwd_simple(int dtype, int B, int S, int nh, int dh, int causal, const void *qkv, void *o,
+                                  float *lse, hipStream_t s);
+// ws: fp32 [T, nh] row dots D_i = <dO_i, O_i>
+hipError_t launch_attn_bwd_simple(int dtype, int B, int S, int nh, int dh, int causal, const void *qkv,
+                                  const void *o, const float *lse, const void *d_o, void *dqkv, float *ws,
+                                  hipStream_t s);
+hipError_t launch_attn_fwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, void *o, float *lse,
+                                hipStream_t s);
+hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o,
+                                const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s);
+
+}  // namespace dp

@@ -1,0 +1,1030 @@
+// Step executor, static memory walk and C ABI of dpstage.
+//
+// One routine, Walk, plays a step's schedule: forward ops, plan actions at each
+// saved tensor's last forward use, swap-in prefetch, on-demand replay and the
+// backward ops, allocating every buffer from one offset allocator.  Run "dry"
+// it launches nothing and yields the memory report (dp_plan_validate); run
+// "live" the same walk, hence the same offsets and the same peak, enqueues the
+// kernels and copies (dp_stage_step).
+#include "../../include/dpstage.h"
+#include "kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+dp_status fail(dp_status code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// ------------------------------------------------------------------ shapes
+struct Cfg {
+  int L, H, nh, dh, F, S, B;
+  long T;
+  bool pre, causal;
+  int gelu, dtype;
+  float eps;
+  size_t esz;
+};
+
+dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
+  if (c == nullptr) return fail(DP_E_INVAL, "config is null");
+  if (c->n_layers <= 0 || c->hidden <= 0 || c->n_heads <= 0 || c->ffn <= 0 || c->seq <= 0 || c->micro_batch <= 0)
+    return fail(DP_E_INVAL, "config extents must be positive");
+  if (c->norm_style != DP_POST_LN && c->norm_style != DP_PRE_LN) return fail(DP_E_INVAL, "bad norm_style");
+  if (c->gelu_kind != DP_GELU_ERF && c->gelu_kind != DP_GELU_TANH) return fail(DP_E_INVAL, "bad gelu_kind");
+  if (c->dtype != DP_F32 && c->dtype != DP_BF16) return fail(DP_E_INVAL, "bad dtype");
+  if (c->hidden % c->n_heads != 0) return fail(DP_E_INVAL, "hidden must be a multiple of n_heads");
+  if (!(c->ln_eps > 0.f)) return fail(DP_E_INVAL, "ln_eps must be positive");
+  o->L = c->n_layers; o->H = c->hidden; o->nh = c->n_heads; o->dh = c->hidden / c->n_heads;
+  o->F = c->ffn; o->S = c->seq; o->B = c->micro_batch; o->T = (long)c->micro_batch * c->seq;
+  o->pre = c->norm_style == DP_PRE_LN; o->causal = c->causal != 0; o->gelu = c->gelu_kind;
+  o->dtype = c->dtype; o->eps = c->ln_eps; o->esz = dp::dtype_size(c->dtype);
+  if (o->H % 8 || o->F % 8 || o->dh % 8)
+    return fail(DP_E_UNSUPPORTED, "hidden, ffn and head_dim must be multiples of 8");
+  if (!dp::ln_supported(o->dtype, o->H)) return fail(DP_E_UNSUPPORTED, "hidden > 8192 is not supported");
+  if (o->S > 4096 && !(o->dtype == DP_BF16 && dp::attn_mfma_supported(o->S, o->dh)))
+    return fail(DP_E_UNSUPPORTED, "seq > 4096 is not supported for this head_dim/dtype");
+  if (o->T > (1L << 24) || (long)o->T * std::max(o->F, 3 * o->H) > (1L << 40))
+    return fail(DP_E_UNSUPPORTED, "micro_batch*seq too large");
+  return DP_OK;
+}
+
+// ------------------------------------------------------------------ op tables
+enum Op { OP_LN1, OP_QKV, OP_ATTN, OP_PROJ, OP_LN2, OP_FC1, OP_GELU, OP_FC2, N_OPS };
+// A slot reference relative to a layer: dl = 1 means "X_IN of the next layer".
+struct Ref { int dl, slot; };
+struct OpDef { Op op; int n_in; Ref in[2]; int n_out; Ref out[2]; };
+
+const OpDef kPreOps[N_OPS] = {
+    {OP_LN1, 1, {{0, DP_SLOT_X_IN}}, 2, {{0, DP_SLOT_LN1_OUT}, {0, DP_SLOT_LN1_STATS}}},
+    {OP_QKV, 1, {{0, DP_SLOT_LN1_OUT}}, 1, {{0, DP_SLOT_QKV}}},
+    {OP_ATTN, 1, {{0, DP_SLOT_QKV}}, 2, {{0, DP_SLOT_ATTN_OUT}, {0, DP_SLOT_ATTN_LSE}}},
+    {OP_PROJ, 2, {{0, DP_SLOT_ATTN_OUT}, {0, DP_SLOT_X_IN}}, 1, {{0, DP_SLOT_RES1}}},
+    {OP_LN2, 1, {{0, DP_SLOT_RES1}}, 2, {{0, DP_SLOT_LN2_OUT}, {0, DP_SLOT_LN2_STATS}}},
+    {OP_FC1, 1, {{0, DP_SLOT_LN2_OUT}}, 1, {{0, DP_SLOT_FC1_OUT}}},
+    {OP_GELU, 1, {{0, DP_SLOT_FC1_OUT}}, 1, {{0, DP_SLOT_GELU_OUT}}},
+    {OP_FC2, 2, {{0, DP_SLOT_GELU_OUT}, {0, DP_SLOT_RES1}}, 1, {{1, DP_SLOT_X_IN}}},
+};
+const OpDef kPostOps[N_OPS] = {
+    {OP_QKV, 1, {{0, DP_SLOT_X_IN}}, 1, {{0, DP_SLOT_QKV}}},
+    {OP_ATTN, 1, {{0, DP_SLOT_QKV}}, 2, {{0, DP_SLOT_ATTN_OUT}, {0, DP_SLOT_ATTN_LSE}}},
+    {OP_PROJ, 2, {{0, DP_SLOT_ATTN_OUT}, {0, DP_SLOT_X_IN}}, 1, {{0, DP_SLOT_RES1}}},
+    {OP_LN1, 1, {{0, DP_SLOT_RES1}}, 2, {{0, DP_SLOT_LN1_OUT}, {0, DP_SLOT_LN1_STATS}}},
+    {OP_FC1, 1, {{0, DP_SLOT_LN1_OUT}}, 1, {{0, DP_SLOT_FC1_OUT}}},
+    {OP_GELU, 1, {{0, DP_SLOT_FC1_OUT}}, 1, {{0, DP_SLOT_GELU_OUT}}},
+    {OP_FC2, 2, {{0, DP_SLOT_GELU_OUT}, {0, DP_SLOT_LN1_OUT}}, 1, {{0, DP_SLOT_RES2}}},
+    {OP_LN2, 1, {{0, DP_SLOT_RES2}}, 2, {{1, DP_SLOT_X_IN}, {0, DP_SLOT_LN2_STATS}}},
+};
+
+inline bool slot_is_alias(const Cfg &c, int slot) {
+  return c.pre ? slot == DP_SLOT_RES2 : slot == DP_SLOT_LN2_OUT;
+}
+
+size_t slot_bytes(const Cfg &c, int slot) {
+  switch (slot) {
+    case DP_SLOT_LN1_STATS: case DP_SLOT_LN2_STATS: return (size_t)c.T * 2 * sizeof(float);
+    case DP_SLOT_ATTN_LSE: return (size_t)c.B * c.nh * c.S * sizeof(float);
+    case DP_SLOT_QKV: return (size_t)c.T * 3 * c.H * c.esz;
+    case DP_SLOT_FC1_OUT: case DP_SLOT_GELU_OUT: return (size_t)c.T * c.F * c.esz;
+    default: return slot_is_alias(c, slot) ? 0 : (size_t)c.T * c.H * c.esz;
+  }
+}
+
+double op_flops(const Cfg &c, Op op) {
+  const double T = (double)c.T, H = c.H, F = c.F;
+  switch (op) {
+    case OP_QKV: return 2 * T * H * 3 * H;
+    case OP_PROJ: return 2 * T * H * H;
+    case OP_FC1: case OP_FC2: return 2 * T * H * F;
+    case OP_ATTN: return (c.causal ? 2.0 : 4.0) * T * c.S * H;
+    default: return 0;
+  }
+}
+
+// ------------------------------------------------------------------ allocator
+// First-fit offset allocator over an unbounded address space; the high-water
+// mark is the arena size a step needs.  Blocks released by a swap-out carry the
+// copy's completion event: whoever is handed overlapping memory waits for it.
+struct Arena {
+  static constexpr uint64_t kAlign = 256;
+  struct Free { uint64_t off, size; };
+  struct Pending { uint64_t off, size; int event; };
+  std::vector<Free> free_;   // sorted by offset, coalesced; last entry is the open tail
+  std::vector<Pending> pending_;
+  uint64_t high_water = 0, live = 0, live_peak = 0;
+
+  Arena() { free_.push_back({0, UINT64_MAX}); }
+  static uint64_t round(uint64_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+  uint64_t alloc(uint64_t bytes, std::vector<int> *wait_events) {
+    const uint64_t n = round(std::max<uint64_t>(bytes, 1));
+    for (size_t i = 0; i < free_.size(); ++i) {
+      if (free_[i].size < n) continue;
+      const uint64_t off = free_[i].off;
+      if (free_[i].size == n) free_.erase(free_.begin() + (long)i);
+      else { free_[i].off += n; if (free_[i].size != UINT64_MAX) free_[i].size -= n; }
+      high_water = std::max(high_water, off + n);
+      live += n;
+      live_peak = std::max(live_peak, live);
+      for (size_t p = 0; p < pending_.size();) {
+        if (pending_[p].off < off + n && off < pending_[p].off + pending_[p].size) {
+          if (wait_events) wait_events->push_back(pending_[p].event);
+          pending_.erase(pending_.begin() + (long)p);
+        } else ++p;
+      }
+      return off;
+    }
+    return UINT64_MAX;  // unreachable: the tail is unbounded
+  }
+
+  void release(uint64_t off, uint64_t bytes, int pending_event = -1) {
+    const uint64_t n = round(std::max<uint64_t>(bytes, 1));
+    live -= n;
+    if (pending_event >= 0) pending_.push_back({off, n, pending_event});
+    size_t i = 0;
+    while (i < free_.size() && free_[i].off < off) ++i;
+    free_.insert(free_.begin() + (long)i, {off, n});
+    // merge with next, then with previous
+    if (i + 1 < free_.size() && free_[i].off + free_[i].size == free_[i + 1].off) {
+      free_[i].size = free_[i + 1].size == UINT64_MAX ? UINT64_MAX : free_[i].size + free_[i + 1].size;
+      free_.erase(free_.begin() + (long)i + 1);
+    }
+    if (i > 0 && free_[i - 1].off + free_[i - 1].size == free_[i].off) {
+      free_[i - 1].size = free_[i].size == UINT64_MAX ? UINT64_MAX : free_[i - 1].size + free_[i].size;
+      free_.erase(free_.begin() + (long)i);
+    }
+  }
+};
+
+// ------------------------------------------------------------------ stage
+struct LayerW {  // library-owned device copies
+  void *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc1, *b_fc2;
+  void *w_qkv, *w_o, *w_fc1, *w_fc2;       // as given: [in, out]
+  void *wt_qkv, *wt_o, *wt_fc1, *wt_fc2;   // transposed: [out, in]
+};
+
+}  // namespace
+
+struct dp_stage {
+  Cfg c;
+  dp_stage_config pub;
+  std::vector<LayerW> w;
+  void *weight_slab = nullptr;
+  uint64_t weight_bytes = 0;
+  void *arena = nullptr;
+  uint64_t arena_bytes = 0;
+  void *host_pool = nullptr;
+  uint64_t host_bytes = 0;
+  hipStream_t d2h = nullptr, h2d = nullptr;
+  std::vector<hipEvent_t> events;       // sync events (no timing)
+  bool profiling = false;
+  std::vector<hipEvent_t> prof_events;  // timing pairs
+  std::vector<int> prof_class;
+  size_t prof_used = 0;
+  uint32_t debug = 0;
+  bool use_mfma = true;
+};
+
+namespace {
+
+enum SlotWhere { ABSENT = 0, RESIDENT = 1, ON_HOST = 2 };
+struct SlotState {
+  int where = ABSENT;
+  uint64_t off = 0;        // arena offset when RESIDENT
+  uint64_t host_off = 0;   // pinned-pool offset when ON_HOST (kept after swap-in)
+  int ready_event = -1;    // swap-in completion the compute stream has not waited for yet
+  bool consumed = false;   // its last backward consumer has run
+  bool ever_produced = false;
+};
+
+struct Buf { uint64_t off = UINT64_MAX, bytes = 0; };
+
+struct Walk {
+  const Cfg &c;
+  const uint8_t *plan;
+  const bool live;
+  dp_stage *st;             // live only
+  hipStream_t cs = nullptr; // compute stream (caller's)
+  hipStream_t d2h = nullptr, h2d = nullptr;
+  const void *x_in = nullptr, *dy = nullptr;
+  void *y_out = nullptr, *dx_out = nullptr;
+  const dp_layer_grads *dw = nullptr;
+
+  Arena arena;
+  std::vector<SlotState> slots;  // (L+1) * DP_SLOTS_PER_LAYER
+  uint64_t host_top = 0;
+  int next_event = 0;
+  hipError_t herr = hipSuccess;
+  bool in_backward = false;
+  // report
+  uint64_t d2h_bytes = 0, h2d_bytes = 0, kept_bytes = 0;
+  double replay_flops = 0, step_flops = 0;
+  int n_replayed = 0, n_swapped = 0, n_launch = 0;
+
+  Walk(const Cfg &cfg, const uint8_t *p, bool is_live, dp_stage *s)
+      : c(cfg), plan(p), live(is_live), st(s), slots((size_t)(cfg.L + 1) * DP_SLOTS_PER_LAYER) {}
+
+  // ---- helpers ------------------------------------------------------------
+  SlotState &S(int l, int slot) { return slots[(size_t)l * DP_SLOTS_PER_LAYER + slot]; }
+  const OpDef *ops() const { return c.pre ? kPreOps : kPostOps; }
+  bool caller_owned(int l, int slot) const { return slot == DP_SLOT_X_IN && (l == 0 || l == c.L); }
+  int action(int l, int slot) const {
+    if (l >= c.L || slot_is_alias(c, slot) || caller_owned(l, slot)) return DP_KEEP;
+    return plan[(size_t)l * DP_SLOTS_PER_LAYER + slot];
+  }
+  char *base() const { return live ? (char *)st->arena : nullptr; }
+  void *ptr(int l, int slot) {
+    if (slot == DP_SLOT_X_IN && l == 0) return const_cast<void *>(x_in);
+    if (slot == DP_SLOT_X_IN && l == c.L) return y_out;
+    return live ? base() + S(l, slot).off : nullptr;
+  }
+  void *bptr(const Buf &b) const { return live ? base() + b.off : nullptr; }
+  void check(hipError_t e) { if (herr == hipSuccess && e != hipSuccess) herr = e; }
+
+  int new_event() {
+    const int id = next_event++;
+    if (live) {
+      while ((int)st->events.size() <= id) {
+        hipEvent_t e;
+        check(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        st->events.push_back(e);
+      }
+    }
+    return id;
+  }
+  void record(int ev, hipStream_t s) { if (live) check(hipEventRecord(st->events[(size_t)ev], s)); }
+  void wait(hipStream_t s, int ev) { if (live) check(hipStreamWaitEvent(s, st->events[(size_t)ev], 0)); }
+
+  uint64_t arena_alloc(uint64_t bytes) {
+    std::vector<int> waits;
+    const uint64_t off = arena.alloc(bytes, &waits);
+    for (int ev : waits) wait(cs, ev);
+    return off;
+  }
+  void arena_release(uint64_t off, uint64_t bytes, int pending_event = -1) {
+    if (live && (st->debug & 2u)) {
+      if (pending_event >= 0) wait(cs, pending_event);
+      check(dp::launch_fill_u32(base() + off, Arena::round(bytes) / 4, 0xFFFFFFFFu, cs));
+    }
+    arena.release(off, bytes, pending_event);
+  }
+  Buf tmp(uint64_t bytes) { Buf b; b.bytes = bytes; b.off = arena_alloc(bytes); return b; }
+  void drop(Buf &b) { if (b.off != UINT64_MAX) arena_release(b.off, b.bytes); b.off = UINT64_MAX; }
+
+  void slot_alloc(int l, int slot) {
+    SlotState &s = S(l, slot);
+    if (caller_owned(l, slot)) { s.where = RESIDENT; return; }
+    s.off = arena_alloc(slot_bytes(c, slot));
+    s.where = RESIDENT;
+  }
+  void slot_free(int l, int slot) {
+    SlotState &s = S(l, slot);
+    if (s.where != RESIDENT) return;
+    // a prefetched copy may still be in flight into this block
+    if (s.ready_event >= 0) { wait(cs, s.ready_event); s.ready_event = -1; }
+    if (!caller_owned(l, slot)) arena_release(s.off, slot_bytes(c, slot));
+    s.where = ABSENT;
+  }
+
+  // ---- profiling brackets ---------------------------------------------------
+  void prof_begin(int cls) {
+    ++n_launch;
+    if (!live || !st->profiling) return;
+    if (st->prof_used + 2 > st->prof_events.size()) {
+      for (int i = 0; i < 2; ++i) { hipEvent_t e; check(hipEventCreate(&e)); st->prof_events.push_back(e); }
+    }
+    st->prof_class.push_back(cls);
+    check(hipEventRecord(st->prof_events[st->prof_used], cs));
+  }
+  void prof_end() {
+    if (!live || !st->profiling) return;
+    check(hipEventRecord(st->prof_events[st->prof_used + 1], cs));
+    st->prof_used += 2;
+  }
+
+  // ---- kernels ----------------------------------------------------------------
+  void gemm(int cls, int mode, long M, long N, long K, const void *A, const void *B, const void *bias,
+            const void *res, void *C) {
+    prof_begin(cls);
+    if (live) {
+      dp::GemmArgs a{mode, (int)M, (int)N, (int)K, A, B, bias, res, C};
+      if (c.dtype == DP_BF16 && st->use_mfma && dp::gemm_mfma_supported(a)) check(dp::launch_gemm_mfma(a, cs));
+      else check(dp::launch_gemm_simple(c.dtype, a, cs));
+    }
+    prof_end();
+  }
+  void colsum(long rows, long cols, const void *x, void *out) {
+    Buf ws = tmp(dp::reduce_ws_bytes((int)rows, (int)cols));
+    prof_begin(DP_OPC_REDUCE);
+    if (live) check(dp::launch_colsum(c.dtype, (int)rows, (int)cols, x, out, bptr(ws), cs));
+    prof_end();
+    drop(ws);
+  }
+  void ln_bwd(const void *dyp, const void *x, const void *stats, const void *gamma, const void *dres, void *dx,
+              void *dgamma, void *dbeta) {
+    Buf ws = tmp(dp::reduce_ws_bytes((int)c.T, c.H));
+    prof_begin(DP_OPC_LN_BWD);
+    if (live)
+      check(dp::launch_ln_bwd(c.dtype, (int)c.T, c.H, dyp, x, (const float *)stats, gamma, dres, dx, dgamma, dbeta,
+                              bptr(ws), cs));
+    prof_end();
+    drop(ws);
+  }
+
+  // Runs forward op `d` of layer l; out_ptr[i] is where output i goes (null = not written).
+  void run_op(int l, const OpDef &d, void *out0, void *out1) {
+    const LayerW *w = live ? &st->w[(size_t)l] : nullptr;
+    const long T = c.T, H = c.H, F = c.F;
+    auto in = [&](int i) { return ptr(l + d.in[i].dl, d.in[i].slot); };
+    switch (d.op) {
+      case OP_LN1: case OP_LN2: {
+        prof_begin(DP_OPC_LN_FWD);
+        if (live) {
+          const void *g = d.op == OP_LN1 ? w->ln1_g : w->ln2_g, *b = d.op == OP_LN1 ? w->ln1_b : w->ln2_b;
+          check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), g, b, out0, (float *)out1, cs));
+        }
+        prof_end();
+        break;
+      }
+      case OP_QKV:
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, 3 * H, H, in(0), live ? w->wt_qkv : nullptr,
+             live ? w->b_qkv : nullptr, nullptr, out0);
+        break;
+      case OP_ATTN:
+        prof_begin(DP_OPC_ATTN_FWD);
+        if (live) {
+          if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.S, c.dh))
+            check(dp::launch_attn_fwd_mfma(c.B, c.S, c.nh, c.dh, c.causal, in(0), out0, (float *)out1, cs));
+          else
+            check(dp::launch_attn_fwd_simple(c.dtype, c.B, c.S, c.nh, c.dh, c.causal, in(0), out0, (float *)out1,
+                                             cs));
+        }
+        prof_end();
+        break;
+      case OP_PROJ:
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? w->wt_o : nullptr, live ? w->b_o : nullptr, in(1),
+             out0);
+        break;
+      case OP_FC1:
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, F, H, in(0), live ? w->wt_fc1 : nullptr, live ? w->b_fc1 : nullptr,
+             nullptr, out0);
+        break;
+      case OP_GELU:
+        prof_begin(DP_OPC_GELU_FWD);
+        if (live) check(dp::launch_gelu_fwd(c.dtype, c.gelu, (size_t)T * F, in(0), out0, cs));
+        prof_end();
+        break;
+      case OP_FC2:
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, F, in(0), live ? w->wt_fc2 : nullptr, live ? w->b_fc2 : nullptr,
+             in(1), out0);
+        break;
+      default: break;
+    }
+  }
+
+  // ---- swap engine --------------------------------------------------------------
+  void swap_out(int l, int slot) {
+    SlotState &s = S(l, slot);
+    const uint64_t bytes = slot_bytes(c, slot);
+    s.host_off = host_top;
+    host_top += Arena::round(bytes);
+    const int done = new_event();
+    if (live) {
+      const int produced = new_event();
+      record(produced, cs);
+      wait(d2h, produced);
+      check(hipMemcpyAsync((char *)st->host_pool + s.host_off, base() + s.off, bytes, hipMemcpyDeviceToHost, d2h));
+      record(done, d2h);
+    }
+    d2h_bytes += bytes;
+    ++n_swapped;
+    arena_release(s.off, bytes, done);
+    s.where = ON_HOST;
+  }
+  void swap_in(int l, int slot) {
+    SlotState &s = S(l, slot);
+    if (s.where != ON_HOST) return;
+    const uint64_t bytes = slot_bytes(c, slot);
+    s.off = arena_alloc(bytes);
+    const int done = new_event();
+    if (live) {
+      const int region_free = new_event();
+      record(region_free, cs);
+      wait(h2d, region_free);
+      check(hipMemcpyAsync(base() + s.off, (char *)st->host_pool + s.host_off, bytes, hipMemcpyHostToDevice, h2d));
+      record(done, h2d);
+    }
+    h2d_bytes += bytes;
+    s.ready_event = done;
+    s.where = RESIDENT;
+  }
+  void prefetch_layer(int l) {
+    if (l < 0) return;
+    for (int slot = 0; slot < DP_SLOTS_PER_LAYER; ++slot) swap_in(l, slot);
+  }
+
+  // Makes slot (l, slot) readable by the compute stream: waits for its swap-in,
+  // or fetches it, or replays its producer (inputs first).
+  void ensure(int l, int slot) {
+    SlotState &s = S(l, slot);
+    if (s.where == ON_HOST) swap_in(l, slot);
+    if (s.where == RESIDENT) {
+      if (s.ready_event >= 0) { wait(cs, s.ready_event); s.ready_event = -1; }
+      return;
+    }
+    // ABSENT: replay.  X_IN of layer l is produced by the last op of layer l-1.
+    const int pl = slot == DP_SLOT_X_IN ? l - 1 : l;
+    const OpDef *d = nullptr;
+    for (int i = 0; i < N_OPS && d == nullptr; ++i)
+      for (int o = 0; o < ops()[i].n_out; ++o)
+        if (pl + ops()[i].out[o].dl == l && ops()[i].out[o].slot == slot) d = &ops()[i];
+    for (int i = 0; i < d->n_in; ++i) ensure(pl + d->in[i].dl, d->in[i].slot);
+    void *outp[2] = {nullptr, nullptr};
+    for (int o = 0; o < d->n_out; ++o) {
+      const int ol = pl + d->out[o].dl, os = d->out[o].slot;
+      SlotState &t = S(ol, os);
+      // a sibling output is written only if it is gone and still has a backward consumer ahead
+      if (t.where == ABSENT && !t.consumed) { slot_alloc(ol, os); outp[o] = ptr(ol, os); }
+    }
+    run_op(pl, *d, outp[0], outp[1]);
+    ++n_replayed;
+    replay_flops += op_flops(c, d->op);
+  }
+  void need(int l, std::initializer_list<int> list) { for (int s : list) ensure(l, s); }
+  void done_with(int l, std::initializer_list<int> list) {
+    for (int s : list) { slot_free(l, s); S(l, s).consumed = true; }
+  }
+
+  // ---- forward -------------------------------------------------------------------
+  void forward() {
+    S(0, DP_SLOT_X_IN).where = RESIDENT;
+    for (int l = 0; l < c.L; ++l) {
+      // last forward reader of every slot of this layer (producer if nobody reads it)
+      int last[DP_SLOTS_PER_LAYER];
+      for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) last[s] = -1;
+      for (int i = 0; i < N_OPS; ++i) {
+        const OpDef &d = ops()[i];
+        for (int k = 0; k < d.n_in; ++k) if (d.in[k].dl == 0) last[d.in[k].slot] = i;
+        for (int k = 0; k < d.n_out; ++k) if (d.out[k].dl == 0) last[d.out[k].slot] = i;
+      }
+      for (int i = 0; i < N_OPS; ++i) {
+        const OpDef &d = ops()[i];
+        void *outp[2] = {nullptr, nullptr};
+        for (int o = 0; o < d.n_out; ++o) {
+          slot_alloc(l + d.out[o].dl, d.out[o].slot);
+          outp[o] = ptr(l + d.out[o].dl, d.out[o].slot);
+        }
+        run_op(l, d, outp[0], outp[1]);
+        step_flops += op_flops(c, d.op);
+        for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) {
+          if (last[s] != i || S(l, s).where != RESIDENT) continue;
+          const int a = action(l, s);
+          if (a == DP_RECOMPUTE) slot_free(l, s);
+          else if (a == DP_SWAP) swap_out(l, s);
+          else if (!caller_owned(l, s)) kept_bytes += slot_bytes(c, s);
+        }
+      }
+    }
+  }
+
+  // ---- backward ------------------------------------------------------------------
+  void backward() {
+    in_backward = true;
+    const long T = c.T, H = c.H, F = c.F;
+    const size_t th = (size_t)T * H * c.esz, tf = (size_t)T * F * c.esz;
+    const void *dcur = dy;   // gradient of the current layer's output
+    Buf dcur_buf;            // its arena block, if the library owns it
+    prefetch_layer(c.L - 1);
+    for (int l = c.L - 1; l >= 0; --l) {
+      prefetch_layer(l - 1);
+      const LayerW *w = live ? &st->w[(size_t)l] : nullptr;
+      const dp_layer_grads *g = live ? &dw[l] : nullptr;
+#define W_(f) (live ? w->f : nullptr)
+#define G_(f) (live ? g->f : nullptr)
+      if (c.pre) {
+        // FC2: dG = dY W2^T, dW2 = GELU_OUT^T dY, db2 = colsum(dY)
+        need(l, {DP_SLOT_GELU_OUT});
+        Buf dg = tmp(tf);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, dcur, W_(w_fc2), nullptr, nullptr, bptr(dg));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), dcur, nullptr, nullptr, G_(w_fc2));
+        colsum(T, H, dcur, G_(b_fc2));
+        done_with(l, {DP_SLOT_GELU_OUT});
+        // GELU: dF = dG * gelu'(FC1_OUT), in place
+        need(l, {DP_SLOT_FC1_OUT});
+        prof_begin(DP_OPC_GELU_BWD);
+        if (live)
+          check(dp::launch_gelu_bwd(c.dtype, c.gelu, (size_t)T * F, bptr(dg), ptr(l, DP_SLOT_FC1_OUT), bptr(dg), cs));
+        prof_end();
+        colsum(T, F, bptr(dg), G_(b_fc1));
+        done_with(l, {DP_SLOT_FC1_OUT});
+        // FC1: dC = dF W1^T, dW1 = LN2_OUT^T dF
+        need(l, {DP_SLOT_LN2_OUT});
+        Buf dc = tmp(th);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, F, bptr(dg), W_(w_fc1), nullptr, nullptr, bptr(dc));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, F, T, ptr(l, DP_SLOT_LN2_OUT), bptr(dg), nullptr, nullptr,
+             G_(w_fc1));
+        drop(dg);
+        done_with(l, {DP_SLOT_LN2_OUT});
+        // LN2: dM = dY + LN2'(dC), in place in dC
+        need(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
+        ln_bwd(bptr(dc), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), dcur, bptr(dc), G_(ln2_g),
+               G_(ln2_b));
+        drop(dcur_buf);
+        done_with(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
+        Buf dm = dc;
+        colsum(T, H, bptr(dm), G_(b_o));
+        // out-projection: dO = dM Wo^T, dWo = ATTN_OUT^T dM
+        need(l, {DP_SLOT_ATTN_OUT});
+        Buf dob = tmp(th);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dm), W_(w_o), nullptr, nullptr, bptr(dob));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_OUT), bptr(dm), nullptr, nullptr, G_(w_o));
+        Buf dqkv = attention_bwd(l, dob);
+        // QKV: dA = dQKV Wqkv^T, dWqkv = LN1_OUT^T dQKV
+        need(l, {DP_SLOT_LN1_OUT});
+        Buf da = tmp(th);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, 3 * H, bptr(dqkv), W_(w_qkv), nullptr, nullptr, bptr(da));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, 3 * H, T, ptr(l, DP_SLOT_LN1_OUT), bptr(dqkv), nullptr, nullptr,
+             G_(w_qkv));
+        drop(dqkv);
+        done_with(l, {DP_SLOT_LN1_OUT});
+        // LN1: dX = dM + LN1'(dA)
+        need(l, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS});
+        void *dxp = l == 0 ? dx_out : bptr(da);
+        ln_bwd(bptr(da), ptr(l, DP_SLOT_X_IN), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), bptr(dm), dxp, G_(ln1_g),
+               G_(ln1_b));
+        drop(dm);
+        done_with(l, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS});
+        if (l == 0) drop(da); else { dcur_buf = da; dcur = bptr(da); }
+      } else {
+        // LN2: dR2 = LN2'(dY)
+        need(l, {DP_SLOT_RES2, DP_SLOT_LN2_STATS});
+        Buf dr2 = tmp(th);
+        ln_bwd(dcur, ptr(l, DP_SLOT_RES2), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), nullptr, bptr(dr2), G_(ln2_g),
+               G_(ln2_b));
+        drop(dcur_buf);
+        done_with(l, {DP_SLOT_RES2, DP_SLOT_LN2_STATS});
+        // FC2
+        need(l, {DP_SLOT_GELU_OUT});
+        Buf dg = tmp(tf);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, bptr(dr2), W_(w_fc2), nullptr, nullptr, bptr(dg));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), bptr(dr2), nullptr, nullptr,
+             G_(w_fc2));
+        colsum(T, H, bptr(dr2), G_(b_fc2));
+        done_with(l, {DP_SLOT_GELU_OUT});
+        // GELU
+        need(l, {DP_SLOT_FC1_OUT});
+        prof_begin(DP_OPC_GELU_BWD);
+        if (live)
+          check(dp::launch_gelu_bwd(c.dtype, c.gelu, (size_t)T * F, bptr(dg), ptr(l, DP_SLOT_FC1_OUT), bptr(dg), cs));
+        prof_end();
+        colsum(T, F, bptr(dg), G_(b_fc1));
+        done_with(l, {DP_SLOT_FC1_OUT});
+        // FC1: dM = dR2 + dF W1^T, dW1 = LN1_OUT^T dF
+        need(l, {DP_SLOT_LN1_OUT});
+        Buf dm = tmp(th);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, F, bptr(dg), W_(w_fc1), nullptr, bptr(dr2), bptr(dm));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, F, T, ptr(l, DP_SLOT_LN1_OUT), bptr(dg), nullptr, nullptr,
+             G_(w_fc1));
+        drop(dg);
+        drop(dr2);
+        done_with(l, {DP_SLOT_LN1_OUT});
+        // LN1: dR1 = LN1'(dM), in place
+        need(l, {DP_SLOT_RES1, DP_SLOT_LN1_STATS});
+        ln_bwd(bptr(dm), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), nullptr, bptr(dm), G_(ln1_g),
+               G_(ln1_b));
+        done_with(l, {DP_SLOT_RES1, DP_SLOT_LN1_STATS});
+        Buf dr1 = dm;
+        colsum(T, H, bptr(dr1), G_(b_o));
+        // out-projection
+        need(l, {DP_SLOT_ATTN_OUT});
+        Buf dob = tmp(th);
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dr1), W_(w_o), nullptr, nullptr, bptr(dob));
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_OUT), bptr(dr1), nullptr, nullptr,
+             G_(w_o));
+        Buf dqkv = attention_bwd(l, dob);
+        // QKV: dX = dR1 + dQKV Wqkv^T, dWqkv = X_IN^T dQKV
+        need(l, {DP_SLOT_X_IN});
+        Buf dxb;
+        void *dxp = dx_out;
+        if (l > 0) { dxb = tmp(th); dxp = bptr(dxb); }
+        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, 3 * H, bptr(dqkv), W_(w_qkv), nullptr, bptr(dr1), dxp);
+        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, 3 * H, T, ptr(l, DP_SLOT_X_IN), bptr(dqkv), nullptr, nullptr,
+             G_(w_qkv));
+        drop(dqkv);
+        drop(dr1);
+        done_with(l, {DP_SLOT_X_IN});
+        if (l > 0) { dcur_buf = dxb; dcur = dxp; }
+      }
+#undef W_
+#undef G_
+      // whatever a replay left behind in this layer goes now
+      for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) { slot_free(l, s); S(l, s).consumed = true; }
+    }
+  }
+
+  // dQKV from dO; frees dO and the attention slots; also the QKV bias gradient.
+  Buf attention_bwd(int l, Buf &dob) {
+    const long T = c.T, H = c.H;
+    need(l, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE});
+    Buf dqkv = tmp((size_t)T * 3 * H * c.esz);
+    Buf ws = tmp((size_t)c.B * c.nh * c.S * sizeof(float));
+    prof_begin(DP_OPC_ATTN_BWD);
+    if (live) {
+      const dp_layer_grads *g = &dw[l];
+      (void)g;
+      if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.S, c.dh))
+        check(dp::launch_attn_bwd_mfma(c.B, c.S, c.nh, c.dh, c.causal, ptr(l, DP_SLOT_QKV), ptr(l, DP_SLOT_ATTN_OUT),
+                                       (const float *)ptr(l, DP_SLOT_ATTN_LSE), bptr(dob), bptr(dqkv),
+                                       (float *)bptr(ws), cs));
+      else
+        check(dp::launch_attn_bwd_simple(c.dtype, c.B, c.S, c.nh, c.dh, c.causal, ptr(l, DP_SLOT_QKV),
+                                         ptr(l, DP_SLOT_ATTN_OUT), (const float *)ptr(l, DP_SLOT_ATTN_LSE),
+                                         bptr(dob), bptr(dqkv), (float *)bptr(ws), cs));
+    }
+    prof_end();
+    drop(ws);
+    drop(dob);
+    done_with(l, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE});
+    colsum(T, 3 * H, bptr(dqkv), live ? dw[l].b_qkv : nullptr);
+    return dqkv;
+  }
+};
+
+uint64_t weight_elems_per_layer(const Cfg &c, uint64_t *matrix_elems) {
+  const uint64_t H = (uint64_t)c.H, F = (uint64_t)c.F;
+  const uint64_t mats = H * 3 * H + H * H + 2 * H * F;
+  const uint64_t vecs = 2 * H + 3 * H + H + 2 * H + F + H;
+  if (matrix_elems) *matrix_elems = mats;
+  return mats + vecs;
+}
+
+dp_status check_plan(const Cfg &c, const uint8_t *plan, size_t plan_len, dp_plan_report *rep) {
+  if (plan == nullptr) return fail(DP_E_INVAL, "plan is null");
+  if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER)
+    return fail(DP_E_INVAL, "plan_len is %zu, expected %zu", plan_len, (size_t)c.L * DP_SLOTS_PER_LAYER);
+  for (size_t i = 0; i < plan_len; ++i)
+    if (plan[i] > DP_SWAP) {
+      if (rep) { rep->first_bad_layer = (int)(i / DP_SLOTS_PER_LAYER); rep->first_bad_slot = (int)(i % DP_SLOTS_PER_LAYER); }
+      return fail(DP_E_INVAL, "plan[%zu] = %u is not an action", i, (unsigned)plan[i]);
+    }
+  if (plan[DP_SLOT_X_IN] == DP_RECOMPUTE) {
+    if (rep) { rep->first_bad_layer = 0; rep->first_bad_slot = DP_SLOT_X_IN; }
+    return fail(DP_E_PLAN, "X_IN of layer 0 cannot be recomputed: it has no producer inside the stage");
+  }
+  return DP_OK;
+}
+
+void fill_report(const Cfg &c, const Walk &w, dp_plan_report *r) {
+  uint64_t mats;
+  const uint64_t per_layer = weight_elems_per_layer(c, &mats);
+  r->weight_bytes = (uint64_t)c.L * (per_layer + mats) * c.esz;  // given + transposed matrices
+  r->grad_bytes = (uint64_t)c.L * per_layer * c.esz;
+  r->fixed_bytes = r->weight_bytes + r->grad_bytes + 4 * (uint64_t)c.T * c.H * c.esz;
+  r->arena_peak_bytes = w.arena.high_water;
+  r->peak_bytes = r->fixed_bytes + w.arena.high_water;
+  r->live_peak_bytes = r->fixed_bytes + w.arena.live_peak;
+  r->kept_act_bytes = w.kept_bytes;
+  r->swap_out_bytes = w.d2h_bytes;
+  r->swap_in_bytes = w.h2d_bytes;
+  r->host_pinned_bytes = w.host_top;
+  r->replay_flops = w.replay_flops;
+  r->step_flops = 3.0 * w.step_flops;
+  r->n_replayed_ops = w.n_replayed;
+  r->n_swapped_slots = w.n_swapped;
+}
+
+dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
+                   dp_plan_report *rep) {
+  dp_plan_report local;
+  dp_plan_report *r = rep ? rep : &local;
+  memset(r, 0, sizeof *r);
+  r->first_bad_layer = r->first_bad_slot = -1;
+  dp_status s = check_plan(c, plan, plan_len, r);
+  if (s != DP_OK) return s;
+  if (inflight < 1) return fail(DP_E_INVAL, "inflight must be >= 1");
+  Walk w(c, plan, false, nullptr);
+  w.forward();
+  w.backward();
+  fill_report(c, w, r);
+  if (budget != 0 && (long double)inflight * (long double)r->peak_bytes > (long double)budget)
+    return fail(DP_E_BUDGET, "plan needs %u x %llu bytes, budget is %llu", inflight,
+                (unsigned long long)r->peak_bytes, (unsigned long long)budget);
+  return DP_OK;
+}
+
+#define HIP_TRY(expr, code)                                                                     \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) return fail(code, "%s failed: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+}  // namespace
+
+// ====================================================================== C ABI
+extern "C" {
+
+const char *dp_last_error(void) { return g_err; }
+
+size_t dp_plan_len(const dp_stage_config *cfg) {
+  Cfg c;
+  if (parse_cfg(cfg, &c) != DP_OK) return 0;
+  return (size_t)c.L * DP_SLOTS_PER_LAYER;
+}
+
+dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len, uint64_t budget_bytes,
+                           uint32_t inflight, dp_plan_report *report) {
+  Cfg c;
+  dp_status s = parse_cfg(cfg, &c);
+  if (s != DP_OK) return s;
+  return validate(c, plan, plan_len, budget_bytes, inflight, report);
+}
+
+dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *layers, uint64_t arena_bytes_hint,
+                        dp_stage **out) {
+  if (out == nullptr) return fail(DP_E_INVAL, "out is null");
+  *out = nullptr;
+  Cfg c;
+  dp_status s = parse_cfg(cfg, &c);
+  if (s != DP_OK) return s;
+  if (layers == nullptr) return fail(DP_E_INVAL, "layers is null");
+  for (int l = 0; l < c.L; ++l) {
+    const void *const *p = reinterpret_cast<const void *const *>(&layers[l]);
+    for (int i = 0; i < 12; ++i)
+      if (p[i] == nullptr) return fail(DP_E_INVAL, "weight pointer %d of layer %d is null", i, l);
+  }
+  dp_stage *st = new dp_stage();
+  st->c = c;
+  st->pub = *cfg;
+  const char *env = getenv("DPSTAGE_KERNELS");
+  st->use_mfma = !(env != nullptr && strcmp(env, "simple") == 0);
+  uint64_t mats;
+  const uint64_t per_layer = weight_elems_per_layer(c, &mats);
+  // every tensor starts on a 256-byte boundary
+  const uint64_t slab = ((per_layer + mats) * c.esz + 16 * 256) * (uint64_t)c.L;
+  if (hipMalloc(&st->weight_slab, slab) != hipSuccess) {
+    delete st;
+    return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the weights", (unsigned long long)slab);
+  }
+  st->weight_bytes = slab;
+  char *cur = (char *)st->weight_slab;
+  auto take = [&](uint64_t elems) { void *p = cur; cur += (elems * c.esz + 255) / 256 * 256; return p; };
+  st->w.resize((size_t)c.L);
+  const uint64_t H = (uint64_t)c.H, F = (uint64_t)c.F;
+  hipError_t e = hipSuccess;
+  auto copy_vec = [&](void **dst, const void *src, uint64_t n) {
+    *dst = take(n);
+    if (e == hipSuccess) e = hipMemcpyAsync(*dst, src, n * c.esz, hipMemcpyDeviceToDevice, nullptr);
+  };
+  auto copy_mat = [&](void **dst, void **dst_t, const void *src, uint64_t rows, uint64_t cols) {
+    copy_vec(dst, src, rows * cols);
+    *dst_t = take(rows * cols);
+    if (e == hipSuccess) e = dp::launch_transpose(c.dtype, (int)rows, (int)cols, src, *dst_t, nullptr);
+  };
+  for (int l = 0; l < c.L; ++l) {
+    LayerW &w = st->w[(size_t)l];
+    const dp_layer_weights &s0 = layers[l];
+    copy_vec(&w.ln1_g, s0.ln1_g, H); copy_vec(&w.ln1_b, s0.ln1_b, H);
+    copy_vec(&w.b_qkv, s0.b_qkv, 3 * H); copy_vec(&w.b_o, s0.b_o, H);
+    copy_vec(&w.ln2_g, s0.ln2_g, H); copy_vec(&w.ln2_b, s0.ln2_b, H);
+    copy_vec(&w.b_fc1, s0.b_fc1, F); copy_vec(&w.b_fc2, s0.b_fc2, H);
+    copy_mat(&w.w_qkv, &w.wt_qkv, s0.w_qkv, H, 3 * H);
+    copy_mat(&w.w_o, &w.wt_o, s0.w_o, H, H);
+    copy_mat(&w.w_fc1, &w.wt_fc1, s0.w_fc1, H, F);
+    copy_mat(&w.w_fc2, &w.wt_fc2, s0.w_fc2, F, H);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->d2h, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->h2d, hipStreamNonBlocking);
+  if (e == hipSuccess && arena_bytes_hint > 0) {
+    if (hipMalloc(&st->arena, arena_bytes_hint) == hipSuccess) st->arena_bytes = arena_bytes_hint;
+    else { dp_stage_destroy(st); return fail(DP_E_DEVMEM, "cannot allocate the arena hint"); }
+  }
+  if (e != hipSuccess) {
+    dp_stage_destroy(st);
+    return fail(DP_E_HIP, "stage_init: %s", hipGetErrorString(e));
+  }
+  *out = st;
+  return DP_OK;
+}
+
+dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const uint8_t *plan, size_t plan_len,
+                        uint64_t budget_bytes, void *y_out, void *dx_out, const dp_layer_grads *dw, void *hip_stream,
+                        dp_step_stats *stats) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  if (!x_in || !dy || !y_out || !dx_out || !dw) return fail(DP_E_INVAL, "null buffer argument");
+  const Cfg &c = st->c;
+  for (int l = 0; l < c.L; ++l) {
+    void *const *p = reinterpret_cast<void *const *>(&dw[l]);
+    for (int i = 0; i < 12; ++i)
+      if (p[i] == nullptr) return fail(DP_E_INVAL, "gradient pointer %d of layer %d is null", i, l);
+  }
+  dp_plan_report rep;
+  dp_status s = validate(c, plan, plan_len, budget_bytes, 1, &rep);
+  if (s != DP_OK) return s;
+  // memory the walk needs (a resize waits for the device first)
+  if (rep.arena_peak_bytes > st->arena_bytes) {
+    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
+    if (st->arena) HIP_TRY(hipFree(st->arena), DP_E_HIP);
+    st->arena = nullptr; st->arena_bytes = 0;
+    if (hipMalloc(&st->arena, rep.arena_peak_bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(DP_E_DEVMEM, "cannot allocate a %llu-byte arena", (unsigned long long)rep.arena_peak_bytes);
+    }
+    st->arena_bytes = rep.arena_peak_bytes;
+  }
+  if (rep.host_pinned_bytes > st->host_bytes) {
+    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
+    if (st->host_pool) HIP_TRY(hipHostFree(st->host_pool), DP_E_HIP);
+    st->host_pool = nullptr; st->host_bytes = 0;
+    if (hipHostMalloc(&st->host_pool, rep.host_pinned_bytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(DP_E_HOSTMEM, "cannot pin %llu bytes of host memory", (unsigned long long)rep.host_pinned_bytes);
+    }
+    st->host_bytes = rep.host_pinned_bytes;
+  }
+  hipStream_t cs = (hipStream_t)hip_stream;
+  Walk w(c, plan, true, st);
+  w.cs = cs;
+  const bool serial = (st->debug & 1u) != 0;
+  w.d2h = serial ? cs : st->d2h;
+  w.h2d = serial ? cs : st->h2d;
+  w.x_in = x_in; w.dy = dy; w.y_out = y_out; w.dx_out = dx_out; w.dw = dw;
+  hipEvent_t t0 = nullptr, t1 = nullptr, t2 = nullptr;
+  if (stats) {
+    HIP_TRY(hipEventCreate(&t0), DP_E_HIP); HIP_TRY(hipEventCreate(&t1), DP_E_HIP); HIP_TRY(hipEventCreate(&t2), DP_E_HIP);
+    HIP_TRY(hipEventRecord(t0, cs), DP_E_HIP);
+  }
+  w.forward();
+  if (stats) HIP_TRY(hipEventRecord(t1, cs), DP_E_HIP);
+  w.backward();
+  // join the copy streams: every swap-out must have landed before the step is over
+  if (!serial) {
+    const int j1 = w.new_event(); w.record(j1, st->d2h); w.wait(cs, j1);
+    const int j2 = w.new_event(); w.record(j2, st->h2d); w.wait(cs, j2);
+  }
+  if (w.herr != hipSuccess) return fail(DP_E_HIP, "stage_step: %s", hipGetErrorString(w.herr));
+  if (w.arena.high_water != rep.arena_peak_bytes)
+    return fail(DP_E_HIP, "internal: live walk peak %llu differs from the validated %llu",
+                (unsigned long long)w.arena.high_water, (unsigned long long)rep.arena_peak_bytes);
+  if (stats) {
+    HIP_TRY(hipEventRecord(t2, cs), DP_E_HIP);
+    HIP_TRY(hipEventSynchronize(t2), DP_E_HIP);
+    memset(stats, 0, sizeof *stats);
+    HIP_TRY(hipEventElapsedTime(&stats->fwd_ms, t0, t1), DP_E_HIP);
+    HIP_TRY(hipEventElapsedTime(&stats->bwd_ms, t1, t2), DP_E_HIP);
+    stats->step_ms = stats->fwd_ms + stats->bwd_ms;
+    stats->d2h_bytes = w.d2h_bytes; stats->h2d_bytes = w.h2d_bytes;
+    stats->arena_high_water = w.arena.high_water; stats->peak_bytes = rep.peak_bytes;
+    stats->n_kernel_launches = w.n_launch; stats->n_replayed_ops = w.n_replayed;
+    (void)hipEventDestroy(t0); (void)hipEventDestroy(t1); (void)hipEventDestroy(t2);
+  }
+  return DP_OK;
+}
+
+dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  st->profiling = enabled != 0;
+  return DP_OK;
+}
+
+dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches_by_class) {
+  if (st == nullptr || ms_by_class == nullptr || launches_by_class == nullptr)
+    return fail(DP_E_INVAL, "null argument");
+  HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
+  for (int i = 0; i < DP_OPC_COUNT; ++i) { ms_by_class[i] = 0.f; launches_by_class[i] = 0; }
+  for (size_t i = 0; i + 1 < st->prof_used; i += 2) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, st->prof_events[i], st->prof_events[i + 1]), DP_E_HIP);
+    const int cls = st->prof_class[i / 2];
+    ms_by_class[cls] += ms;
+    launches_by_class[cls] += 1;
+  }
+  st->prof_used = 0;
+  st->prof_class.clear();
+  return DP_OK;
+}
+
+dp_status dp_stage_set_debug(dp_stage *st, uint32_t flags) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  st->debug = flags;
+  return DP_OK;
+}
+
+void dp_stage_destroy(dp_stage *st) {
+  if (st == nullptr) return;
+  (void)hipDeviceSynchronize();
+  for (hipEvent_t e : st->events) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->prof_events) (void)hipEventDestroy(e);
+  if (st->d2h) (void)hipStreamDestroy(st->d2h);
+  if (st->h2d) (void)hipStreamDestroy(st->h2d);
+  if (st->arena) (void)hipFree(st->arena);
+  if (st->host_pool) (void)hipHostFree(st->host_pool);
+  if (st->weight_slab) (void)hipFree(st->weight_slab);
+  delete st;
+}
+
+// ---------------------------------------------------------------- standalone ops
+size_t dp_op_workspace_bytes(int32_t rows, int32_t cols) {
+  return std::max(dp::reduce_ws_bytes(rows, cols), (size_t)rows * (size_t)cols * sizeof(float));
+}
+
+static dp_status op_done(hipError_t e, const char *what) {
+  return e == hipSuccess ? DP_OK : fail(DP_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+static bool bad_dtype(int32_t d) { return d != DP_F32 && d != DP_BF16; }
+
+dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x, const void *gamma,
+                              const void *beta, void *y, float *stats, void *hip_stream) {
+  if (bad_dtype(dtype) || rows < 0 || !x || !gamma || !beta) return fail(DP_E_INVAL, "layernorm_fwd: bad argument");
+  if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
+  return op_done(dp::launch_ln_fwd(dtype, rows, cols, eps, x, gamma, beta, y, stats, (hipStream_t)hip_stream),
+                 "layernorm_fwd");
+}
+
+dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
+                              const float *stats, const void *gamma, const void *dres, void *dx, void *dgamma,
+                              void *dbeta, void *ws, void *hip_stream) {
+  if (bad_dtype(dtype) || rows < 0 || !dy || !x || !stats || !gamma || !dx || !dgamma || !dbeta || !ws)
+    return fail(DP_E_INVAL, "layernorm_bwd: bad argument");
+  if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
+  return op_done(dp::launch_ln_bwd(dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws,
+                                   (hipStream_t)hip_stream), "layernorm_bwd");
+}
+
+dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream) {
+  if (bad_dtype(dtype) || !x || !y || (gelu_kind != 0 && gelu_kind != 1)) return fail(DP_E_INVAL, "gelu_fwd: bad argument");
+  if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
+  return op_done(dp::launch_gelu_fwd(dtype, gelu_kind, n, x, y, (hipStream_t)hip_stream), "gelu_fwd");
+}
+
+dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,
+                         void *hip_stream) {
+  if (bad_dtype(dtype) || !x || !dy || !dx || (gelu_kind != 0 && gelu_kind != 1))
+    return fail(DP_E_INVAL, "gelu_bwd: bad argument");
+  if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
+  return op_done(dp::launch_gelu_bwd(dtype, gelu_kind, n, dy, x, dx, (hipStream_t)hip_stream), "gelu_bwd");
+}
+
+dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
+                     const void *bias, const void *res, void *C, void *hip_stream) {
+  if (bad_dtype(dtype) || (mode != 0 && mode != 1) || M < 0 || N < 0 || K < 0 || !A || !B || !C)
+    return fail(DP_E_INVAL, "gemm: bad argument");
+  dp::GemmArgs a{mode, M, N, K, A, B, bias, res, C};
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::gemm_mfma_supported(a))
+    return op_done(dp::launch_gemm_mfma(a, (hipStream_t)hip_stream), "gemm");
+  return op_done(dp::launch_gemm_simple(dtype, a, (hipStream_t)hip_stream), "gemm");
+}
+
+dp_status dp_op_colsum(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out, void *ws,
+                       void *hip_stream) {
+  if (bad_dtype(dtype) || rows < 0 || cols <= 0 || !x || !out || !ws) return fail(DP_E_INVAL, "colsum: bad argument");
+  if (cols % 8) return fail(DP_E_UNSUPPORTED, "colsum: cols must be a multiple of 8");
+  return op_done(dp::launch_colsum(dtype, rows, cols, x, out, ws, (hipStream_t)hip_stream), "colsum");
+}
+
+dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
+                              const void *qkv, void *o, float *lse, void *hip_stream) {
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv) return fail(DP_E_INVAL, "attention_fwd: bad argument");
+  if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
+    return op_done(dp::launch_attn_fwd_mfma(B, S, nh, dh, causal, qkv, o, lse, (hipStream_t)hip_stream), "attention_fwd");
+  if (S > 4096) return fail(DP_E_UNSUPPORTED, "attention: seq > 4096 needs the MFMA path");
+  return op_done(dp::launch_attn_fwd_simple(dtype, B, S, nh, dh, causal, qkv, o, lse, (hipStream_t)hip_stream),
+                 "attention_fwd");
+}
+
+dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
+                              const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv, void *ws,
+                              void *hip_stream) {
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv || !o || !lse || !d_o || !dqkv || !ws)
+    return fail(DP_E_INVAL, "attention_bwd: bad argument");
+  if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
+    return op_done(dp::launch_attn_bwd_mfma(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
+                                            (hipStream_t)hip_stream), "attention_bwd");
+  if (S > 4096) return fail(DP_E_UNSUPPORTED, "attention: seq > 4096 needs the MFMA path");
+  return op_done(dp::launch_attn_bwd_simple(dtype, B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
+                                            (hipStream_t)hip_stream), "attention_bwd");
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+"""Device-buffer plumbing around the binding for tests and the benchmark:
+uploads seeded inputs with torch, allocates outputs, downloads results.
+No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import Dict, List
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def to_binding_config(cfg) -> B.StageConfig:
+    """`cfg` is a synthetic.StageConfig (duck-typed)."""
+    return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
+                         cfg.norm_style, cfg.causal, cfg.gelu, cfg.dtype, cfg.ln_eps)
+
+
+def torch_dtype(cfg):
+    return torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+
+def upload(a: np.ndarray, cfg, device="cuda:0") -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device).to(torch_dtype(cfg)).contiguous()
+
+
+def download(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+class StageRunner:
+    """Holds a stage handle plus its device inputs/outputs."""
+
+    def __init__(self, cfg, weights: List[Dict[str, np.ndarray]], x: np.ndarray, dy: np.ndarray,
+                 device="cuda:0", arena_bytes_hint: int = 0):
+        self.cfg, self.device = cfg, device
+        self.bcfg = to_binding_config(cfg)
+        self.w = [{k: upload(v, cfg, device) for k, v in layer.items()} for layer in weights]
+        self.x, self.dy = upload(x, cfg, device), upload(dy, cfg, device)
+        self.y = torch.empty_like(self.x)
+        self.dx = torch.empty_like(self.x)
+        self.g = [{k: torch.empty_like(v) for k, v in layer.items()} for layer in self.w]
+        torch.cuda.synchronize()
+        self.stage = B.stage_init(self.bcfg, self.w, arena_bytes_hint)
+
+    def poison_outputs(self):
+        for t in [self.y, self.dx] + [v for layer in self.g for v in layer.values()]:
+            t.fill_(float("nan"))
+
+    def step(self, plan, budget_bytes: int = 0, want_stats: bool = False, stream=None):
+        return B.stage_step(self.stage, self.x, self.dy, plan, budget_bytes, self.y, self.dx, self.g,
+                            stream=stream, want_stats=want_stats)
+
+    def results(self):
+        torch.cuda.synchronize()
+        return download(self.y), download(self.dx), [{k: download(v) for k, v in layer.items()} for layer in self.g]
+
+    def raw_results(self):
+        """Bit patterns of every output, for bit-exactness checks."""
+        torch.cuda.synchronize()
+        outs = [self.y, self.dx] + [layer[k] for layer in self.g for k in B.WEIGHT_FIELDS]
+        return [t.detach().clone().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu() for t in outs]
+
+    def close(self):
+        self.stage.close()

@@ -1,0 +1,151 @@
+"""Operator-level parity of the HIP kernels against the CPU oracle, through the
+C ABI.  Tolerances: max|gpu-ref| / max|ref| <= 1e-4 in fp32 and <= 2e-2 in bf16
+(the bounds the stage step has to meet); most operators are far inside them and
+are held to tighter figures derived from one rounding of the output."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic as syn
+from oracle import stage as O
+from paper_2505_05856_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {torch.float32: 2e-5, torch.bfloat16: 8e-3}   # one output rounding: 2^-8 relative in bf16
+
+
+def dev(a, dt):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(dt).contiguous()
+
+
+def host(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def rnd(shape, seed, dt, scale=1.0):
+    a = scale * syn.normal(seed, 0, int(np.prod(shape))).reshape(shape)
+    a = a.astype(np.float32)
+    return syn.round_to_bf16(a) if dt == torch.bfloat16 else a
+
+
+def ws_for(rows, cols):
+    return torch.empty(B.op_workspace_bytes(rows, cols), dtype=torch.uint8, device=DEV)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("rows,cols", [(1, 8), (7, 16), (130, 128), (37, 1600), (9, 4096), (5, 8192)])
+def test_layernorm(dt, rows, cols):
+    x = rnd((rows, cols), 11, dt, 2.0) + 0.5
+    x = syn.round_to_bf16(x) if dt == torch.bfloat16 else x
+    g = rnd((cols,), 12, dt) * 0.1 + 1
+    g = syn.round_to_bf16(g) if dt == torch.bfloat16 else g
+    b = rnd((cols,), 13, dt, 0.1)
+    dy = rnd((rows, cols), 14, dt)
+    dres = rnd((rows, cols), 15, dt)
+    y_ref, mu, r = O.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)
+    dx_ref, dg_ref, db_ref = O.layernorm_bwd(dy.astype(np.float64), x.astype(np.float64), mu, r, g.astype(np.float64))
+    tx, tg, tb, tdy, tres = (dev(a, dt) for a in (x, g, b, dy, dres))
+    y = torch.empty_like(tx); stats = torch.empty(rows, 2, dtype=torch.float32, device=DEV)
+    B.op_layernorm_fwd(tx, tg, tb, 1e-5, y, stats)
+    assert O.max_rel_err(host(y), y_ref) < TOL[dt]
+    assert np.allclose(host(stats)[:, 0], mu, atol=1e-5) and np.allclose(host(stats)[:, 1], r, rtol=1e-5)
+    # stats only / y only
+    stats2 = torch.zeros_like(stats)
+    B.op_layernorm_fwd(tx, tg, tb, 1e-5, None, stats2)
+    assert torch.equal(stats, stats2)
+    dx = torch.empty_like(tx); dg = torch.empty_like(tg); db = torch.empty_like(tb)
+    ws = ws_for(rows, cols)
+    B.op_layernorm_bwd(tdy, tx, stats, tg, None, dx, dg, db, ws)
+    assert O.max_rel_err(host(dx), dx_ref) < TOL[dt]
+    assert O.max_rel_err(host(dg), dg_ref) < TOL[dt] and O.max_rel_err(host(db), db_ref) < TOL[dt]
+    # with the residual gradient added, written in place over dy
+    dy2 = tdy.clone()
+    B.op_layernorm_bwd(dy2, tx, stats, tg, tres, dy2, dg, db, ws)
+    assert O.max_rel_err(host(dy2), dx_ref + dres) < TOL[dt]
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("kind", [0, 1])
+def test_gelu(dt, kind):
+    n = 8 * 1237
+    x = rnd((n,), 21, dt, 2.5)
+    dy = rnd((n,), 22, dt)
+    name = "erf" if kind == 0 else "tanh"
+    tx, tdy = dev(x, dt), dev(dy, dt)
+    y = torch.empty_like(tx); dx = torch.empty_like(tx)
+    B.op_gelu_fwd(tx, y, kind)
+    B.op_gelu_bwd(tdy, tx, dx, kind)
+    assert O.max_rel_err(host(y), O.gelu_fwd(x.astype(np.float64), name)) < TOL[dt]
+    assert O.max_rel_err(host(dx), dy * O.gelu_grad(x.astype(np.float64), name)) < TOL[dt]
+    B.op_gelu_bwd(tdy, tx, tdy, kind)     # in place
+    assert torch.equal(tdy, dx)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("rows,cols", [(1, 8), (33, 24), (1000, 1600), (4096, 520)])
+def test_colsum(dt, rows, cols):
+    x = rnd((rows, cols), 31, dt)
+    tx = dev(x, dt)
+    out = torch.empty(cols, dtype=dt, device=DEV)
+    B.op_colsum(tx, out, ws_for(rows, cols))
+    assert O.max_rel_err(host(out), x.astype(np.float64).sum(axis=0)) < TOL[dt]
+
+
+GEMM_SHAPES = [(1, 8, 8), (5, 16, 24), (64, 64, 64), (100, 72, 40), (128, 384, 128), (257, 136, 520),
+               (300, 1600, 96), (512, 256, 1024)]
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm(dt, mode, M, N, K):
+    a = rnd((M, K), 41, dt); b = rnd((K, N), 42, dt)
+    bias = rnd((N,), 43, dt); res = rnd((M, N), 44, dt)
+    ref = a.astype(np.float64) @ b.astype(np.float64)
+    if mode == 0:     # A [M,K], B given as [N,K]
+        ta, tb = dev(a, dt), dev(b.T, dt)
+    else:             # A given as [K,M], B [K,N]
+        ta, tb = dev(a.T, dt), dev(b, dt)
+    c = torch.empty(M, N, dtype=dt, device=DEV)
+    B.op_gemm(mode, M, N, K, ta, tb, None, None, c)
+    assert O.max_rel_err(host(c), ref) < TOL[dt]
+    B.op_gemm(mode, M, N, K, ta, tb, dev(bias, dt), dev(res, dt), c)
+    assert O.max_rel_err(host(c), ref + bias + res) < TOL[dt]
+
+
+ATTN_SHAPES = [(1, 8, 1, 8), (2, 5, 2, 16), (2, 64, 2, 64), (1, 200, 3, 64), (2, 96, 2, 128), (1, 384, 2, 64)]
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("Bn,S,nh,dh", ATTN_SHAPES)
+@pytest.mark.parametrize("sharp", [False, True])
+def test_attention(dt, causal, Bn, S, nh, dh, sharp):
+    H = nh * dh
+    qkv = rnd((Bn * S, 3 * H), 51, dt)
+    if sharp:     # logits with a standard deviation of a few units
+        qkv[:, :2 * H] *= 2.0
+        qkv = syn.round_to_bf16(qkv) if dt == torch.bfloat16 else qkv
+    d_o = rnd((Bn * S, H), 52, dt)
+    q64 = qkv.astype(np.float64)
+    o_ref, lse_ref = O.attention_fwd(q64, Bn, S, nh, causal)
+    dq_ref = O.attention_bwd(d_o.astype(np.float64), q64, Bn, S, nh, causal)
+    tq, tdo = dev(qkv, dt), dev(d_o, dt)
+    o = torch.empty(Bn * S, H, dtype=dt, device=DEV)
+    lse = torch.empty(Bn, nh, S, dtype=torch.float32, device=DEV)
+    B.op_attention_fwd(tq, Bn, S, nh, dh, causal, o, lse)
+    tol = TOL[dt] * (2 if dt == torch.bfloat16 else 1)     # P is rounded to bf16 as well
+    assert O.max_rel_err(host(o), o_ref) < tol
+    assert np.allclose(host(lse), lse_ref, atol=2e-5 if dt == torch.float32 else 2e-3)
+    # single outputs
+    lse2 = torch.zeros_like(lse)
+    B.op_attention_fwd(tq, Bn, S, nh, dh, causal, None, lse2)
+    assert torch.equal(lse, lse2)
+    dqkv = torch.empty_like(tq)
+    ws = ws_for(Bn * S, nh)
+    # the backward is fed the oracle-consistent O the kernel itself produced
+    B.op_attention_bwd(tq, o, lse, tdo, Bn, S, nh, dh, causal, dqkv, ws)
+    got = host(dqkv)
+    for blk in range(3):
+        assert O.max_rel_err(got[:, blk * H:(blk + 1) * H], dq_ref[:, blk * H:(blk + 1) * H]) < 2 * tol, blk

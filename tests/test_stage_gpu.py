@@ -1,0 +1,140 @@
+"""Parity of dp_stage_step against the CPU oracle and bit-exactness across
+plans, through the C ABI.  Metric: max|gpu-ref| / max|ref| per output tensor;
+bounds 1e-4 (fp32 debug mode) and 2e-2 (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic as syn
+from oracle import stage as O
+from paper_2505_05856_amd import binding as B
+from paper_2505_05856_amd.harness import StageRunner
+
+pytestmark = pytest.mark.gpu
+BOUND = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def oracle_step(cfg, w, x, dy, dtype=np.float64):
+    st = O.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
+                 cfg.causal, cfg.gelu, cfg.ln_eps)
+    return O.stage_step(st, w, x, dy, dtype=dtype)
+
+
+def compare(cfg, got, ref, bound=None):
+    bound = bound or BOUND[cfg.dtype]
+    y, dx, g = got
+    yr, dxr, gr = ref
+    worst = {"Y": O.max_rel_err(y, yr), "dX": O.max_rel_err(dx, dxr)}
+    for l in range(cfg.n_layers):
+        for n in syn.WEIGHT_NAMES:
+            worst[f"L{l}.{n}"] = O.max_rel_err(g[l][n], gr[l][n])
+    bad = {k: v for k, v in worst.items() if not (v <= bound)}
+    assert not bad, f"over {bound}: {bad}"
+    return max(worst.values())
+
+
+def make(cfg, sharp=False, sigma=0.02):
+    w = syn.make_weights(cfg, sigma=sigma)
+    if sharp:
+        w = syn.sharpen_attention(cfg, w)
+    x, dy = syn.make_activations(cfg)
+    return w, x, dy
+
+
+def test_c1_fp32_keep_all_then_all_recompute():
+    cfg = syn.CONFIGS["C1"]
+    w, x, dy = make(cfg)
+    ref = oracle_step(cfg, w, x, dy)
+    run = StageRunner(cfg, w, x, dy)
+    bits = []
+    for name, mk in syn.PLANS["C1"]:
+        run.poison_outputs()
+        run.step(mk(cfg))
+        compare(cfg, run.results(), ref)
+        bits.append(run.raw_results())
+    assert all(torch.equal(a, b) for a, b in zip(*bits))
+    run.close()
+
+
+SMALL = [
+    syn.StageConfig(2, 64, 2, 128, 40, 3, "pre", True, "erf", "f32"),
+    syn.StageConfig(2, 64, 2, 128, 40, 3, "post", False, "tanh", "f32"),
+    syn.StageConfig(3, 128, 2, 256, 96, 2, "pre", True, "erf", "bf16"),
+    syn.StageConfig(3, 128, 2, 256, 96, 2, "post", False, "erf", "bf16"),
+    syn.StageConfig(2, 256, 2, 520, 130, 2, "pre", True, "tanh", "bf16"),     # dh 128, ragged extents
+    syn.StageConfig(2, 192, 3, 384, 200, 1, "post", True, "erf", "bf16"),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.norm_style}-{c.dtype}-H{c.hidden}-S{c.seq}")
+@pytest.mark.parametrize("sharp", [False, True])
+def test_small_stages_every_plan(cfg, sharp):
+    w, x, dy = make(cfg, sharp=sharp, sigma=0.05)
+    ref = oracle_step(cfg, w, x, dy)
+    run = StageRunner(cfg, w, x, dy)
+    B.stage_set_debug(run.stage, 2)      # poison released arena blocks
+    plans = [("keep", syn.plan_keep_all(cfg)), ("recompute", syn.plan_all_recompute(cfg)),
+             ("recompute-all", syn.plan_uniform(cfg, syn.RECOMPUTE)), ("swap", syn.plan_all_swap(cfg)),
+             ("attn", syn.plan_recompute_attention(cfg)), ("c4", syn.plan_swap_ffn_recompute_norm_gelu(cfg))]
+    plans += [(f"seed{s}", syn.plan_seeded(cfg, s)) for s in range(12)]
+    first = None
+    for name, p in plans:
+        run.poison_outputs()
+        stats = run.step(p, want_stats=True)
+        _, rep = B.plan_validate(run.bcfg, p)
+        assert stats["arena_high_water"] == rep["arena_peak_bytes"], name
+        assert stats["d2h_bytes"] == rep["swap_out_bytes"] and stats["h2d_bytes"] == rep["swap_in_bytes"]
+        bits = run.raw_results()
+        if first is None:
+            compare(cfg, run.results(), ref)
+            first = bits
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, bits)), f"plan {name} changed the bits"
+    # serialised copies give the same bits as overlapped ones
+    B.stage_set_debug(run.stage, 1)
+    run.poison_outputs()
+    run.step(plans[3][1])
+    assert all(torch.equal(a, b) for a, b in zip(first, run.raw_results()))
+    run.close()
+
+
+def test_runs_inside_exact_budget_and_rejects_less():
+    cfg = SMALL[2]
+    w, x, dy = make(cfg)
+    run = StageRunner(cfg, w, x, dy)
+    p = syn.plan_all_recompute(cfg)
+    _, rep = B.plan_validate(run.bcfg, p)
+    run.step(p, budget_bytes=rep["peak_bytes"])
+    good = run.raw_results()
+    run.poison_outputs()
+    with pytest.raises(B.DpError) as e:
+        run.step(p, budget_bytes=rep["peak_bytes"] - 1)
+    assert e.value.status == "DP_E_BUDGET"
+    torch.cuda.synchronize()
+    assert torch.isnan(run.y.float()).all()          # nothing was enqueued
+    with pytest.raises(B.DpError) as e:
+        run.step(syn.plan_keep_all(cfg), budget_bytes=rep["peak_bytes"])   # keep-all needs more
+    assert e.value.status == "DP_E_BUDGET"
+    bad = syn.plan_keep_all(cfg); bad[0] = syn.RECOMPUTE
+    with pytest.raises(B.DpError) as e:
+        run.step(bad)
+    assert e.value.status == "DP_E_PLAN"
+    run.step(p, budget_bytes=rep["peak_bytes"])
+    assert all(torch.equal(a, b) for a, b in zip(good, run.raw_results()))
+    run.close()
+
+
+def test_non_default_stream_and_repeatability():
+    cfg = SMALL[3]
+    w, x, dy = make(cfg)
+    run = StageRunner(cfg, w, x, dy)
+    p = syn.plan_seeded(cfg, 3)
+    run.step(p)
+    a = run.raw_results()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        for _ in range(3):
+            run.step(p, stream=s)
+    s.synchronize()
+    assert all(torch.equal(u, v) for u, v in zip(a, run.raw_results()))
+    run.close()

@@ -1,0 +1,169 @@
+"""Host-only tests: the library loads, exports what the header declares, and the
+plan validator's memory walk obeys the accounting rule of Algorithm 2 (add what
+is allocated, take the running maximum, subtract what is released) and the
+feasibility test of Algorithm 1 (inflight x peak against the capacity)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synthetic as syn
+from paper_2505_05856_amd import binding as B
+from paper_2505_05856_amd.harness import to_binding_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "dpstage.h")).read()
+    names = sorted(set(re.findall(r"\b(dp_[a-z_]+)\s*\(", hdr)))
+    assert "dp_stage_step" in names and "dp_plan_validate" in names and len(names) >= 17
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def small(style="pre", L=2):
+    return syn.StageConfig(L, 64, 2, 128, 16, 2, style, style == "pre", "erf", "bf16")
+
+
+def test_argument_errors():
+    cfg = small()
+    bc = to_binding_config(cfg)
+    n = syn.plan_len(cfg)
+    assert B.plan_len(bc) == n == cfg.n_layers * 12
+    code, _ = B.plan_validate(bc, None, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_INVAL"
+    code, _ = B.plan_validate(bc, np.zeros(n - 1, np.uint8), raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_INVAL" and "plan_len" in B.last_error()
+    p = syn.plan_keep_all(cfg); p[5] = 3
+    code, rep = B.plan_validate(bc, p, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_INVAL" and rep["first_bad_slot"] == 5
+    p = syn.plan_keep_all(cfg); p[syn.SLOT["X_IN"]] = syn.RECOMPUTE
+    code, rep = B.plan_validate(bc, p, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_PLAN" and (rep["first_bad_layer"], rep["first_bad_slot"]) == (0, 0)
+    code, _ = B.plan_validate(bc, syn.plan_keep_all(cfg), inflight=0, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_INVAL"
+    bad = B.make_config(1, 60, 4, 128, 16, 2)   # head_dim 15
+    assert B.plan_len(bad) == 0
+    code, _ = B.plan_validate(bad, np.zeros(12, np.uint8), raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_UNSUPPORTED"
+    bad = B.make_config(1, 64, 3, 128, 16, 2)   # hidden not a multiple of heads
+    code, _ = B.plan_validate(bad, np.zeros(12, np.uint8), raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_INVAL"
+
+
+def r256(n):
+    return (n + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("style", ["pre", "post"])
+def test_keep_all_peak_by_hand(style):
+    """Keep-all: every slot of every layer is live at the forward/backward
+    turnaround; on top of that sits the largest transient set of the last
+    layer's backward."""
+    cfg = small(style, L=3)
+    bc = to_binding_config(cfg)
+    _, rep = B.plan_validate(bc, syn.plan_keep_all(cfg))
+    T, H, F, e = cfg.tokens, cfg.hidden, cfg.ffn, 2
+    th, tf, st, lse = r256(T * H * e), r256(T * F * e), r256(T * 8), r256(cfg.micro_batch * cfg.n_heads * cfg.seq * 4)
+    per_layer = 4 * th + r256(3 * T * H * e) + 2 * tf + 2 * st + lse     # LN1_OUT,ATTN_OUT,RES1,(LN2_OUT|RES2); QKV; FC1,GELU
+    slots = cfg.n_layers * per_layer + (cfg.n_layers - 1) * th          # + X_IN of layers 1..L-1
+    assert rep["kept_act_bytes"] == cfg.n_layers * (per_layer - 4 * th - r256(3 * T * H * e) - 2 * tf - 2 * st - lse) + \
+        cfg.n_layers * (4 * T * H * e + 3 * T * H * e + 2 * T * F * e + 2 * T * 8 + cfg.micro_batch * cfg.n_heads * cfg.seq * 4) + \
+        (cfg.n_layers - 1) * T * H * e
+    # the walk's peak is at least all slots plus the first backward transient (dG or dR2)
+    assert rep["live_peak_bytes"] - rep["fixed_bytes"] >= slots + min(th, tf)
+    assert rep["live_peak_bytes"] - rep["fixed_bytes"] <= slots + 2 * tf + 2 * th + r256(T // 8 * 2 * max(F, 3 * H) * 4)
+    assert rep["arena_peak_bytes"] >= rep["live_peak_bytes"] - rep["fixed_bytes"]
+    assert rep["peak_bytes"] == rep["fixed_bytes"] + rep["arena_peak_bytes"]
+    # fixed part: weights (as given + transposed matrices), gradients, x/dy/y/dx
+    mats = 3 * H * H + H * H + 2 * H * F
+    vecs = 9 * H + F
+    assert rep["weight_bytes"] == cfg.n_layers * (2 * mats + vecs) * e
+    assert rep["grad_bytes"] == cfg.n_layers * (mats + vecs) * e
+    assert rep["fixed_bytes"] == rep["weight_bytes"] + rep["grad_bytes"] + 4 * T * H * e
+    assert rep["n_replayed_ops"] == 0 and rep["swap_out_bytes"] == 0 and rep["replay_flops"] == 0
+    assert abs(rep["step_flops"] - cfg.model_flops()) < 1e-6 * cfg.model_flops()
+
+
+@pytest.mark.parametrize("style", ["pre", "post"])
+def test_plans_reduce_peak_and_account_traffic(style):
+    cfg = small(style, L=4)
+    bc = to_binding_config(cfg)
+    _, keep = B.plan_validate(bc, syn.plan_keep_all(cfg))
+    _, rec = B.plan_validate(bc, syn.plan_all_recompute(cfg))
+    _, swp = B.plan_validate(bc, syn.plan_all_swap(cfg))
+    assert rec["live_peak_bytes"] < keep["live_peak_bytes"] and swp["live_peak_bytes"] < keep["live_peak_bytes"]
+    assert rec["peak_bytes"] < keep["peak_bytes"] and swp["peak_bytes"] < keep["peak_bytes"]
+    # all-recompute replays each layer's forward: all but the last op in pre-LN (its
+    # output is the kept next-layer input); post-LN also reruns LN2 for its statistics
+    assert rec["n_replayed_ops"] == cfg.n_layers * (7 if style == "pre" else 8)
+    fwd = cfg.model_flops() / 3
+    last_gemm = 2 * cfg.tokens * cfg.hidden * cfg.ffn * cfg.n_layers      # FC2 (pre) is never replayed
+    expect = fwd - last_gemm if style == "pre" else fwd
+    assert abs(rec["replay_flops"] - expect) < 1e-6 * fwd
+    # all-swap: every stored slot goes out once and comes back once
+    assert swp["swap_out_bytes"] == swp["swap_in_bytes"] == keep["kept_act_bytes"]
+    assert swp["host_pinned_bytes"] >= swp["swap_out_bytes"] and swp["n_replayed_ops"] == 0
+    assert swp["n_swapped_slots"] == cfg.n_layers * 11 - 1
+
+
+def test_single_slot_monotonicity():
+    """Turning one more slot from KEEP to RECOMPUTE or SWAP never raises the walk's peak."""
+    cfg = small("pre", L=3)
+    bc = to_binding_config(cfg)
+    base = syn.plan_keep_all(cfg)
+    _, rb = B.plan_validate(bc, base)
+    for i in range(len(base)):
+        l, s = divmod(i, 12)
+        if s in cfg.alias_slots() or (l == 0 and s == 0):
+            continue
+        for a in (syn.RECOMPUTE, syn.SWAP):
+            p = base.copy(); p[i] = a
+            _, r = B.plan_validate(bc, p)
+            assert r["live_peak_bytes"] <= rb["live_peak_bytes"], (l, s, a)
+
+
+def test_budget_predicate():
+    cfg = small("pre", L=2)
+    bc = to_binding_config(cfg)
+    p = syn.plan_keep_all(cfg)
+    _, rep = B.plan_validate(bc, p)
+    peak = rep["peak_bytes"]
+    assert B.plan_validate(bc, p, budget_bytes=peak)[0] == 0            # equal budget must run
+    code, rep2 = B.plan_validate(bc, p, budget_bytes=peak - 1, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_BUDGET" and rep2["peak_bytes"] == peak
+    assert B.plan_validate(bc, p, budget_bytes=4 * peak, inflight=4)[0] == 0
+    code, _ = B.plan_validate(bc, p, budget_bytes=4 * peak - 1, inflight=4, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_BUDGET"
+    # a plan that frees memory fits where keep-all does not
+    _, rr = B.plan_validate(bc, syn.plan_all_recompute(cfg))
+    assert B.plan_validate(bc, syn.plan_all_recompute(cfg), budget_bytes=rr["peak_bytes"])[0] == 0
+    assert rr["peak_bytes"] < peak
+
+
+def test_ignored_plan_bytes_and_random_plans():
+    cfg = small("post", L=3)
+    bc = to_binding_config(cfg)
+    a = syn.plan_keep_all(cfg)
+    b = a.copy()
+    b.reshape(3, 12)[:, syn.SLOT["LN2_OUT"]] = syn.SWAP     # no storage in post-LN
+    b[syn.SLOT["X_IN"]] = syn.SWAP                          # caller memory
+    assert B.plan_validate(bc, a)[1] == B.plan_validate(bc, b)[1]
+    for seed in range(200):
+        for c in (cfg, small("pre", L=3)):
+            code, rep = B.plan_validate(to_binding_config(c), syn.plan_seeded(c, seed))
+            assert code == 0 and rep["arena_peak_bytes"] >= rep["live_peak_bytes"] - rep["fixed_bytes"] > 0
+            assert rep["swap_in_bytes"] <= rep["swap_out_bytes"]
+
+
+def test_full_size_configs_fit_their_budgets():
+    for name, cfg in syn.CONFIGS.items():
+        bc = to_binding_config(cfg)
+        for pname, mk in syn.PLANS[name]:
+            code, rep = B.plan_validate(bc, mk(cfg), budget_bytes=syn.BUDGETS.get(name, 0))
+            assert code == 0, (name, pname, B.last_error())
+            assert rep["peak_bytes"] < 288 * 10**9
