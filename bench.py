@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage step: one step = forward+backward of the whole stage
+(every kernel of the hot path) on one synthetic micro-batch resident in HBM.
+
+Prints ONE JSON line.  `value` = samples/s of the whole job on one MI355X.
+`roofline` is for the kernel class that dominates the step (the NT-form GEMM
+that runs the forward and input-gradient contractions), timed with HIP events
+on the stream the kernels run on.  `cpu_baseline` times the CPU oracle on a
+bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector ALUs)
+
+
+def gemm_flops(cfg):
+    """Algorithmic FLOP per step of the three GEMM classes (2*M*N*K each)."""
+    T, H, F, L = cfg.tokens, cfg.hidden, cfg.ffn, cfg.n_layers
+    per_layer = 2.0 * T * (3 * H * H + H * H + 2 * H * F)
+    return {"gemm_fwd": L * per_layer, "gemm_dgrad": L * per_layer, "gemm_wgrad": L * per_layer}
+
+
+def cpu_baseline(cfg, weights, x, dy, budget_s=30.0):
+    """Oracle as it stands, on a bounded sample: the first layer of the stage on
+    the full micro-batch (every layer costs the same), scaled by n_layers."""
+    import numpy as np
+    from oracle import stage as O
+    import dataclasses
+    one = dataclasses.replace(cfg, n_layers=1)
+    st = O.Stage(1, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style, cfg.causal,
+                 cfg.gelu, cfg.ln_eps)
+    t0 = time.perf_counter()
+    O.stage_step(st, weights[:1], x, dy, dtype=np.float64)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": cfg.micro_batch / (dt * cfg.n_layers), "unit": "samples/s", "cores": int(cores),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"1 of {cfg.n_layers} layers on the full micro-batch (fp64 numpy), time scaled by {cfg.n_layers}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C2", help="workload name from synthetic.CONFIGS")
+    ap.add_argument("--plan", default=None, help="plan name (default: the config's own)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-op-times", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synthetic as syn
+    from paper_2505_05856_amd import binding as B
+    from paper_2505_05856_amd.harness import StageRunner
+
+    B.lib()   # fails loudly if the HIP library is not built
+    cfg = syn.CONFIGS[args.config]
+    plan_name, mk = syn.PLANS[args.config][0]
+    if args.plan:
+        plan_name, mk = {"keep-all": ("keep-all", syn.plan_keep_all),
+                         "all-recompute": ("all-recompute", syn.plan_all_recompute),
+                         "all-swap": ("all-swap", syn.plan_all_swap),
+                         "recompute-attention": ("recompute-attention", syn.plan_recompute_attention),
+                         "swap-fc1-recompute-ln-gelu": ("swap-fc1-recompute-ln-gelu",
+                                                        syn.plan_swap_ffn_recompute_norm_gelu),
+                         "seed7-mixed": ("seed7-mixed", lambda c: syn.plan_seeded(c, 7))}[args.plan]
+    plan = mk(cfg)
+    budget = syn.BUDGETS.get(args.config, 0)
+    weights = syn.make_weights(cfg)
+    x, dy = syn.make_activations(cfg)
+    run = StageRunner(cfg, weights, x, dy)
+    _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
+
+    for _ in range(args.warmup):
+        run.step(plan, budget)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run.step(plan, budget)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel-class times: the same steps again with HIP event brackets on the launch stream
+    roof, op_ms = None, None
+    if not args.no_op_times:
+        B.stage_set_profiling(run.stage, True)
+        k = max(1, min(args.steps, 10))
+        for _ in range(k):
+            run.step(plan, budget)
+        times = B.stage_op_times(run.stage)
+        B.stage_set_profiling(run.stage, False)
+        op_ms = {n: round(v[0] / k, 4) for n, v in times.items()}
+        gf = gemm_flops(cfg)
+        nt_ms = (times["gemm_fwd"][0] + times["gemm_dgrad"][0]) / k
+        nt_launches = (times["gemm_fwd"][1] + times["gemm_dgrad"][1]) / k
+        nt_flops = gf["gemm_fwd"] + gf["gemm_dgrad"]
+        peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+        achieved = nt_flops / (nt_ms * 1e-3) / 1e12
+        roof = {"kernel": "gemm_nt (forward + input-gradient GEMMs)", "bound": "mfma" if cfg.dtype == "bf16" else "alu",
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "avg_launch_us": round(nt_ms * 1e3 / max(nt_launches, 1), 2), "launches_per_step": nt_launches,
+                "traffic": None}
+    stats = run.step(plan, budget, want_stats=True)
+
+    out = {
+        "metric": "stage fwd+bwd samples/sec + MFMA util % at fixed memory budget",
+        "value": round(cfg.micro_batch / (ms * 1e-3), 3), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.config}: {cfg.n_layers} {cfg.norm_style}-LN layers, hidden {cfg.hidden}, "
+                               f"{cfg.n_heads} heads, ffn {cfg.ffn}, seq {cfg.seq}, micro-batch {cfg.micro_batch}, "
+                               f"{'causal' if cfg.causal else 'full'} attention",
+                   "plan": plan_name, "budget_bytes": budget, "validator_peak_bytes": rep["peak_bytes"],
+                   "arena_peak_bytes": rep["arena_peak_bytes"]},
+        "model_tflops": round(cfg.model_flops() / (ms * 1e-3) / 1e12, 2),
+        "mfma_peak_frac": round(cfg.model_flops() / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "fwd_ms": round(stats["fwd_ms"], 4), "bwd_ms": round(stats["bwd_ms"], 4),
+        "swap_bytes": {"d2h": stats["d2h_bytes"], "h2d": stats["h2d_bytes"]},
+        "replayed_ops": stats["n_replayed_ops"], "kernel_launches": stats["n_kernel_launches"],
+        "op_ms": op_ms, "roofline": roof,
+    }
+    run.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, x, dy)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

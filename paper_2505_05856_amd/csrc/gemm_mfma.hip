@@ -1,8 +1,223 @@
-// bf16 MFMA GEMM (placeholder until the tiled kernels land: nothing is supported,
-// so callers take the vector-ALU path).
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32
+// accumulation, fused bias / residual epilogue, bf16 output.
+//
+//   NT: C[M,N] = A[M,K] * B[N,K]^T   both operands contraction-contiguous
+//       (forward with the transposed weight copy; dX = dY * W^T with W as stored)
+//   TN: C[M,N] = A[K,M]^T * B[K,N]   contraction over the leading dimension
+//       (dW = X^T * dY); tiles are staged in LDS as loaded and handed to the
+//       matrix cores through the LDS transpose read (ds_read_b64_tr_b16).
+//
+// A block of 256 threads (4 waves, 2x2) owns a BM x BN tile of C; every wave
+// owns (BM/2) x (BN/2) of it as 32x32 MFMA accumulators.  K advances in steps
+// of 64 through a double-buffered LDS stage: global loads for step k+1 are in
+// flight while step k feeds the MFMAs, one barrier per step.  No split-K, so
+// the summation order is fixed and results do not depend on scheduling.
 #include "common.h"
 #include "kernels.h"
+
 namespace dp {
-bool gemm_mfma_supported(const GemmArgs &) { return false; }
-hipError_t launch_gemm_mfma(const GemmArgs &, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr int BK = 64;
+
+// LDS row strides in elements.  NT rows hold BK (+8) contraction elements: the
+// 144-byte stride spreads the 16-byte fragment reads of 8 consecutive rows over
+// all banks.  TN rows hold BM/BN (+16) elements: the 32-byte skew does the same
+// for the four rows one transpose read touches.
+template <int BMN, bool TN> struct Lds {
+  static constexpr int kStride = TN ? BMN + 16 : BK + 8;
+  static constexpr int kRows = TN ? BK : BMN;
+  static constexpr int kElems = kStride * kRows;
+};
+
+__device__ __forceinline__ uint4 ld16(const bf16 *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+// Global -> registers for one operand tile.  NT: tile is [BMN rows][BK], row r
+// of the operand at p + r*ld.  TN: tile is [BK][BMN], contraction row k at
+// p + k*ld.  Out-of-range chunks read as zero.
+template <int BMN, bool TN>
+__device__ __forceinline__ void load_tile(uint4 (&st)[BMN * BK / 8 / 256], const bf16 *__restrict__ p, long ld,
+                                          int row0, int rows, int k0, int K, int tid) {
+  constexpr int NCH = BMN * BK / 8 / 256;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = tid + i * 256;
+    int r, kk;
+    if (TN) { kk = c / (BMN / 8); r = (c % (BMN / 8)) * 8; }
+    else { r = c / (BK / 8); kk = (c % (BK / 8)) * 8; }
+    const int gr = row0 + r, gk = k0 + kk;
+    const bool ok = TN ? (gk < K && gr < rows) : (gr < rows && gk < K);
+    st[i] = ok ? ld16(TN ? p + (long)gk * ld + gr : p + (long)gr * ld + gk) : make_uint4(0, 0, 0, 0);
+  }
+}
+
+template <int BMN, bool TN>
+__device__ __forceinline__ void store_tile(bf16 *lds, const uint4 (&st)[BMN * BK / 8 / 256], int tid) {
+  constexpr int NCH = BMN * BK / 8 / 256;
+  constexpr int S = Lds<BMN, TN>::kStride;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = tid + i * 256;
+    int off;
+    if (TN) off = (c / (BMN / 8)) * S + (c % (BMN / 8)) * 8;
+    else off = (c / (BK / 8)) * S + (c % (BK / 8)) * 8;
+    *reinterpret_cast<uint4 *>(lds + off) = st[i];
+  }
+}
+
+// One 32 x 16 MFMA operand fragment: row (lane%32) of the 32-row block at
+// `row0`, contraction elements k16 + 8*(lane/32) .. +7.
+template <int BMN, bool TN>
+__device__ __forceinline__ bf16x8 load_frag(const bf16 *lds, int row0, int k16, int lane) {
+  constexpr int S = Lds<BMN, TN>::kStride;
+  if (!TN) return *reinterpret_cast<const bf16x8 *>(lds + (row0 + (lane & 31)) * S + k16 + 8 * (lane >> 5));
+  // transpose read: a 16-lane group fetches 4 contraction rows x 16 columns; lane i of
+  // the group supplies the address of row i/4, columns 4*(i%4).. and receives column i
+  // of all four rows.
+  const int i = lane & 15;
+  const bf16 *p = lds + (k16 + 8 * (lane >> 5) + (i >> 2)) * S + row0 + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+  union { s16x4 h[2]; bf16x8 v; } u;
+  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * S));
+  return u.v;
+}
+
+template <int BM, int BN, bool TN>
+__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
+                                                           const bf16 *__restrict__ bias,
+                                                           const bf16 *__restrict__ res, bf16 *__restrict__ C, int M,
+                                                           int N, int K, int tiles_m, int tiles_n) {
+  constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
+  constexpr int AE = Lds<BM, TN>::kElems, BE = Lds<BN, TN>::kElems;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16 *smem = reinterpret_cast<bf16 *>(smem_raw);
+  bf16 *As[2] = {smem, smem + AE + BE};
+  bf16 *Bs[2] = {smem + AE, smem + 2 * AE + BE};
+
+  // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run
+  // of tiles, and walk tiles in groups of 8 tile-rows so that a run shares A and B
+  // panels in that XCD's L2.
+  const int nt = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int xcd = pid & 7, idx = pid >> 3, base = nt >> 3, rem = nt & 7;
+    pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  }
+  constexpr int GM = 8;
+  const int group = pid / (GM * tiles_n);
+  const int first_m = group * GM;
+  const int gsz = min(tiles_m - first_m, GM);
+  const int tm = first_m + (pid % (GM * tiles_n)) % gsz;
+  const int tn = (pid % (GM * tiles_n)) / gsz;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+  const long lda = TN ? M : K, ldb = TN ? N : K;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  uint4 sa[BM * BK / 8 / 256], sb[BN * BK / 8 / 256];
+  load_tile<BM, TN>(sa, A, lda, m0, M, 0, K, tid);
+  load_tile<BN, TN>(sb, B, ldb, n0, N, 0, K, tid);
+  store_tile<BM, TN>(As[0], sa, tid);
+  store_tile<BN, TN>(Bs[0], sb, tid);
+  __syncthreads();
+
+  const int nk = (K + BK - 1) / BK;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      load_tile<BM, TN>(sa, A, lda, m0, M, (kt + 1) * BK, K, tid);
+      load_tile<BN, TN>(sb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
+    }
+#pragma unroll
+    for (int k16 = 0; k16 < BK; k16 += 16) {
+      bf16x8 a[FM], b[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) a[i] = load_frag<BM, TN>(As[cur], wm + i * 32, k16, lane);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) b[j] = load_frag<BN, TN>(Bs[cur], wn + j * 32, k16, lane);
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      store_tile<BM, TN>(As[cur ^ 1], sa, tid);
+      store_tile<BN, TN>(Bs[cur ^ 1], sb, tid);
+    }
+    __syncthreads();
+  }
+
+  // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int col = n0 + wn + j * 32 + (lane & 31);
+    if (col >= N) continue;
+    const float bv = bias != nullptr ? (float)bias[col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (row >= M) continue;
+        float v = acc[i][j][e] + bv;
+        if (res != nullptr) v += (float)res[(long)row * N + col];
+        C[(long)row * N + col] = (bf16)v;
+      }
+    }
+  }
+}
+
+template <int BM, int BN, bool TN>
+hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
+  constexpr size_t smem = 2 * (size_t)(Lds<BM, TN>::kElems + Lds<BN, TN>::kElems) * sizeof(bf16);
+  static bool attr_set = false;
+  auto kern = gemm_mfma_kernel<BM, BN, TN>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16 *)a.A, (const bf16 *)a.B,
+                     (const bf16 *)a.bias, (const bf16 *)a.res, (bf16 *)a.C, a.M, a.N, a.K, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+template <bool TN>
+hipError_t launch_mode(const GemmArgs &a, hipStream_t s) {
+  auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+  // the largest tile that still gives every CU a workgroup
+  if (tiles(128, 128) >= 256) return launch_cfg<128, 128, TN>(a, s);
+  if (tiles(64, 128) >= 256) return launch_cfg<64, 128, TN>(a, s);
+  return launch_cfg<64, 64, TN>(a, s);
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(const GemmArgs &a) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
+  const bool aligned = (((uintptr_t)a.A | (uintptr_t)a.B) & 15) == 0;
+  if (a.mode == kGemmNT) return aligned && a.K % 8 == 0;
+  return aligned && a.M % 8 == 0 && a.N % 8 == 0;   // TN: rows of A and B are M and N long
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s) {
+  return a.mode == kGemmNT ? launch_mode<false>(a, s) : launch_mode<true>(a, s);
+}
+
 }  // namespace dp
