@@ -1,13 +1,553 @@
-// bf16 MFMA attention (placeholder until the fused kernels land).
+// Fused softmax attention on the gfx950 matrix cores (bf16 in, fp32 accumulate).
+//
+// Forward: a block owns 128 query rows of one (batch, head); each of its 4 waves
+// owns 32 of them.  K/V tiles of 64 keys stream through a double-buffered LDS
+// stage.  A wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a
+// lane holds one query row's logits for 16 keys of every 32-key block: the
+// softmax row reductions are in-lane plus one exchange between the two half
+// waves, and the probabilities already sit in the register layout the second
+// MFMA (O^T = V^T P^T) wants as its B operand.  V^T fragments come from the V
+// tile as loaded ([key][d]) through the LDS transpose read.  Only O and the
+// per-row log-sum-exp leave the chip; no S x S tensor is ever stored.
+//
+// Backward recomputes P from Q, K and the log-sum-exp, in two kernels so that
+// every output element has exactly one owner (no float atomics, fixed order):
+//   dK/dV: block per 128 keys (32 per wave), loops over query tiles;
+//   dQ:    block per 128 queries (32 per wave), loops over key tiles.
 #include "common.h"
 #include "kernels.h"
+
 namespace dp {
-bool attn_mfma_supported(int, int) { return false; }
-hipError_t launch_attn_fwd_mfma(int, int, int, int, int, const void *, void *, float *, hipStream_t) {
-  return hipErrorNotSupported;
+
+namespace {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int BKV = 64;    // keys (forward, dQ) or queries (dK/dV) per LDS stage
+constexpr int BROWS = 128; // rows a block owns (4 waves x 32)
+
+__device__ __forceinline__ uint4 ld16(const bf16 *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ __forceinline__ bf16x8 as_frag(uint4 v) {
+  union { uint4 u; bf16x8 f; } c;
+  c.u = v;
+  return c.f;
 }
-hipError_t launch_attn_bwd_mfma(int, int, int, int, int, const void *, const void *, const float *, const void *,
-                                void *, float *, hipStream_t) {
-  return hipErrorNotSupported;
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// 32 x 16 operand fragment with the contraction along a row of a [rows][stride] LDS tile.
+__device__ __forceinline__ bf16x8 frag_rows(const bf16 *lds, int stride, int row0, int k0, int lane) {
+  return *reinterpret_cast<const bf16x8 *>(lds + (row0 + (lane & 31)) * stride + k0 + 8 * (lane >> 5));
 }
+
+// 32 x 16 operand fragment with the contraction DOWN the rows of a [rows][stride] tile:
+// lane l gets column col0 + l%32 for the 8 rows
+//   r0 + 4*(l/32) + {0,1,2,3}  and  r0 + 8 + 4*(l/32) + {0,1,2,3},
+// which is the order in which a 32x32 MFMA result holds 16 consecutive rows
+// (elements e = 0..7) of one column, so products of MFMA results need no shuffling.
+__device__ __forceinline__ bf16x8 frag_cols(const bf16 *lds, int stride, int r0, int col0, int lane) {
+  const int i = lane & 15;
+  const bf16 *p = lds + (r0 + 4 * (lane >> 5) + (i >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+  union { s16x4 h[2]; bf16x8 v; } u;
+  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * stride));
+  return u.v;
+}
+
+// elements e0..e0+7 of an MFMA result as a bf16 operand fragment
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int e0) {
+  bf16x8 r;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) r[t] = (bf16)v[e0 + t];
+  return r;
+}
+
+// Row index, inside its 32-row block, of element e of a 32x32 MFMA result held by `lane`.
+__device__ __forceinline__ int acc_row(int e, int lane) { return 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3); }
+
+// Cooperative global -> register -> LDS copy of a [64][DH] tile (rows beyond `nrows` read as zero).
+template <int DH>
+__device__ __forceinline__ void tile_load(uint4 (&st)[DH / 32], const bf16 *__restrict__ src, long ld, int row0,
+                                          int nrows, int tid) {
+#pragma unroll
+  for (int i = 0; i < DH / 32; ++i) {
+    const int c = tid + i * 256, r = c / (DH / 8), k = (c % (DH / 8)) * 8;
+    st[i] = (row0 + r < nrows) ? ld16(src + (long)(row0 + r) * ld + k) : make_uint4(0, 0, 0, 0);
+  }
+}
+template <int DH>
+__device__ __forceinline__ void tile_store(bf16 *lds, int stride, const uint4 (&st)[DH / 32], int tid) {
+#pragma unroll
+  for (int i = 0; i < DH / 32; ++i) {
+    const int c = tid + i * 256, r = c / (DH / 8), k = (c % (DH / 8)) * 8;
+    *reinterpret_cast<uint4 *>(lds + r * stride + k) = st[i];
+  }
+}
+
+// ------------------------------------------------------------------ forward
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
+                                                               float *__restrict__ lse, int S, int nh, float scale) {
+  constexpr int KS = DH + 8, VS = DH + 16, ND = DH / 32, NK = DH / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16 *Ks[2], *Vs[2];
+  Ks[0] = reinterpret_cast<bf16 *>(smem_raw);
+  Ks[1] = Ks[0] + BKV * KS;
+  Vs[0] = Ks[1] + BKV * KS;
+  Vs[1] = Vs[0] + BKV * VS;
+
+  const int qt = gridDim.x - 1 - blockIdx.x;   // heavy (late) causal tiles first
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int H = nh * DH;
+  const long ld = 3L * H;
+  const bf16 *qb = qkv + (long)b * S * ld + (long)h * DH;
+  const bf16 *kb = qb + H, *vb = qb + 2 * H;
+  const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
+  const float c = scale * kLog2e;
+
+  bf16x8 qf[NK];
+#pragma unroll
+  for (int kd = 0; kd < NK; ++kd)
+    qf[kd] = qi < S ? as_frag(ld16(qb + (long)qi * ld + kd * 16 + 8 * hh)) : as_frag(make_uint4(0, 0, 0, 0));
+
+  int nkv = (S + BKV - 1) / BKV;
+  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, S) - 1) / BKV + 1);
+
+  f32x16 acc[ND];
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
+  float m = -1e30f, l = 0.f;
+
+  uint4 sk[DH / 32], sv[DH / 32];
+  tile_load<DH>(sk, kb, ld, 0, S, tid);
+  tile_load<DH>(sv, vb, ld, 0, S, tid);
+  tile_store<DH>(Ks[0], KS, sk, tid);
+  tile_store<DH>(Vs[0], VS, sv, tid);
+  __syncthreads();
+
+  for (int t = 0; t < nkv; ++t) {
+    const int cur = t & 1, j0 = t * BKV;
+    if (t + 1 < nkv) {
+      tile_load<DH>(sk, kb, ld, j0 + BKV, S, tid);
+      tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
+    }
+    if (!CAUSAL || j0 <= iw0 + 31) {
+      f32x16 s[2];
+      float mx = -1e30f;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[sub][e] = 0.f;
+#pragma unroll
+        for (int kd = 0; kd < NK; ++kd)
+          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks[cur], KS, sub * 32, kd * 16, lane), qf[kd],
+                                                           s[sub], 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = j0 + sub * 32 + acc_row(e, lane);
+          const bool masked = j >= S || (CAUSAL && j > qi);
+          s[sub][e] = masked ? -INFINITY : s[sub][e] * c;
+          mx = fmaxf(mx, s[sub][e]);
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - m_new);
+      m = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          s[sub][e] = fast_exp2(s[sub][e] - m_new);
+          ps += s[sub][e];
+        }
+      l = l * alpha + ps;
+#pragma unroll
+      for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[d][e] *= alpha;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const bf16x8 pf = pack8(s[sub], half * 8);
+#pragma unroll
+          for (int d = 0; d < ND; ++d)
+            acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols(Vs[cur], VS, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
+        }
+    }
+    if (t + 1 < nkv) {
+      tile_store<DH>(Ks[cur ^ 1], KS, sk, tid);
+      tile_store<DH>(Vs[cur ^ 1], VS, sv, tid);
+    }
+    __syncthreads();
+  }
+
+  l += __shfl_xor(l, 32, 64);
+  if (qi >= S) return;
+  if (lse != nullptr && hh == 0) lse[((long)b * nh + h) * S + qi] = (m + __log2f(l)) * kLn2;
+  if (o == nullptr) return;
+  const float inv = 1.0f / l;
+  bf16 *orow = o + ((long)b * S + qi) * H + (long)h * DH;
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+      bf16x4 v;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] = (bf16)(acc[d][e4 * 4 + t] * inv);
+      *reinterpret_cast<bf16x4 *>(orow + d * 32 + 8 * e4 + 4 * hh) = v;
+    }
+}
+
+template <int DH>
+hipError_t fwd_launch(int B, int S, int nh, int causal, const void *qkv, void *o, float *lse, hipStream_t s) {
+  constexpr size_t smem = 2 * (size_t)BKV * ((DH + 8) + (DH + 16)) * sizeof(bf16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_mfma_kernel<DH, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_mfma_kernel<DH, false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid((S + BROWS - 1) / BROWS, nh, B), block(256);
+  const float scale = 1.0f / sqrtf((float)DH);
+  if (causal)
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH, true>), grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S,
+                       nh, scale);
+  else
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH, false>), grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S,
+                       nh, scale);
+  return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------------ backward
+// D[b,h,i] = <dO_i, O_i> over the head's DH columns; one thread per 8 columns.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_rowdot_kernel(const bf16 *__restrict__ o, const bf16 *__restrict__ d_o,
+                                                          float *__restrict__ drow, long T, int S, int nh) {
+  const long c = (long)blockIdx.x * 256 + threadIdx.x;   // chunk of 8 columns
+  const int cpr = nh * DH / 8;                           // chunks per row
+  const bool ok = c < T * cpr;
+  float sum = 0.f;
+  if (ok) {
+    float a[8], g[8];
+    load8(o + c * 8, a);
+    load8(d_o + c * 8, g);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += a[i] * g[i];
+  }
+#pragma unroll
+  for (int m = 1; m < DH / 8; m <<= 1) sum += __shfl_xor(sum, m, 64);
+  if (ok && (c % (DH / 8)) == 0) {
+    const long t = c / cpr;
+    const int h = (int)(c % cpr) / (DH / 8);
+    drow[((t / S) * nh + h) * S + (t % S)] = sum;
+  }
+}
+
+// dK, dV: the block owns 128 keys (32 per wave) and streams 64-query tiles of Q and dO.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
+                                                              const float *__restrict__ lse,
+                                                              const bf16 *__restrict__ d_o,
+                                                              const float *__restrict__ drow,
+                                                              bf16 *__restrict__ dqkv, int S, int nh, float scale) {
+  constexpr int QS = DH + 16, ND = DH / 32, NK = DH / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16 *Qs[2], *Os[2];
+  float *Ls[2], *Ds[2];
+  Qs[0] = reinterpret_cast<bf16 *>(smem_raw);
+  Qs[1] = Qs[0] + BKV * QS;
+  Os[0] = Qs[1] + BKV * QS;
+  Os[1] = Os[0] + BKV * QS;
+  Ls[0] = reinterpret_cast<float *>(Os[1] + BKV * QS);
+  Ls[1] = Ls[0] + BKV;
+  Ds[0] = Ls[1] + BKV;
+  Ds[1] = Ds[0] + BKV;
+
+  const int kt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int H = nh * DH;
+  const long ld = 3L * H;
+  const bf16 *qb = qkv + (long)b * S * ld + (long)h * DH;
+  const bf16 *kb = qb + H, *vb = qb + 2 * H;
+  const bf16 *dob = d_o + (long)b * S * H + (long)h * DH;
+  const float *lrow = lse + ((long)b * nh + h) * S, *drw = drow + ((long)b * nh + h) * S;
+  const int j0 = kt * BROWS, jw0 = j0 + wave * 32, kj = jw0 + (lane & 31);
+  const float c = scale * kLog2e;
+
+  bf16x8 kf[NK], vf[NK];
+#pragma unroll
+  for (int kd = 0; kd < NK; ++kd) {
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    kf[kd] = as_frag(kj < S ? ld16(kb + (long)kj * ld + kd * 16 + 8 * hh) : z);
+    vf[kd] = as_frag(kj < S ? ld16(vb + (long)kj * ld + kd * 16 + 8 * hh) : z);
+  }
+  f32x16 dk[ND], dv[ND];
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[d][e] = 0.f; dv[d][e] = 0.f; }
+
+  const int nq = (S + BKV - 1) / BKV;
+  const int t0 = CAUSAL ? j0 / BKV : 0;   // query tiles before the block's first key see none of its keys
+
+  uint4 sq[DH / 32], so[DH / 32];
+  float sl = 0.f;
+  auto fetch = [&](int t) {
+    const int i0 = t * BKV;
+    tile_load<DH>(sq, qb, ld, i0, S, tid);
+    tile_load<DH>(so, dob, H, i0, S, tid);
+    if (tid < 64) sl = (i0 + tid < S) ? lrow[i0 + tid] * kLog2e : INFINITY;   // +inf: P = 0 for padding rows
+    else if (tid < 128) sl = (i0 + tid - 64 < S) ? drw[i0 + tid - 64] : 0.f;
+  };
+  auto stash = [&](int buf) {
+    tile_store<DH>(Qs[buf], QS, sq, tid);
+    tile_store<DH>(Os[buf], QS, so, tid);
+    if (tid < 64) Ls[buf][tid] = sl;
+    else if (tid < 128) Ds[buf][tid - 64] = sl;
+  };
+  if (t0 < nq) { fetch(t0); stash(0); }
+  __syncthreads();
+
+  for (int t = t0; t < nq; ++t) {
+    const int cur = (t - t0) & 1, i0 = t * BKV;
+    if (t + 1 < nq) fetch(t + 1);
+    if (!CAUSAL || i0 + BKV - 1 >= jw0) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int kd = 0; kd < NK; ++kd) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs[cur], QS, sub * 32, kd * 16, lane), kf[kd], s, 0,
+                                                      0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Os[cur], QS, sub * 32, kd * 16, lane), vf[kd], dp,
+                                                       0, 0, 0);
+        }
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int r = sub * 32 + 8 * e4 + 4 * hh;
+          const float4 l4 = *reinterpret_cast<const float4 *>(Ls[cur] + r);
+          const float4 d4 = *reinterpret_cast<const float4 *>(Ds[cur] + r);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int t4 = 0; t4 < 4; ++t4) {
+            const int e = e4 * 4 + t4, i = i0 + r + t4;
+            float p = fast_exp2(s[e] * c - lv[t4]);
+            if (CAUSAL && kj > i) p = 0.f;
+            s[e] = p;
+            dp[e] = p * (dp[e] - dvv[t4]);
+          }
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const bf16x8 pf = pack8(s, half * 8), dsf = pack8(dp, half * 8);
+#pragma unroll
+          for (int d = 0; d < ND; ++d) {
+            dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols(Os[cur], QS, sub * 32 + half * 16, d * 32, lane), pf, dv[d], 0, 0, 0);
+            dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols(Qs[cur], QS, sub * 32 + half * 16, d * 32, lane), dsf, dk[d], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (t + 1 < nq) stash(cur ^ 1);
+    __syncthreads();
+  }
+
+  if (kj >= S) return;
+  bf16 *krow = dqkv + ((long)b * S + kj) * ld + H + (long)h * DH;
+  bf16 *vrow = krow + H;
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+      bf16x4 a, g;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { a[t] = (bf16)(dk[d][e4 * 4 + t] * scale); g[t] = (bf16)dv[d][e4 * 4 + t]; }
+      *reinterpret_cast<bf16x4 *>(krow + d * 32 + 8 * e4 + 4 * hh) = a;
+      *reinterpret_cast<bf16x4 *>(vrow + d * 32 + 8 * e4 + 4 * hh) = g;
+    }
+}
+
+// dQ: the block owns 128 queries (32 per wave) and streams 64-key tiles of K and V.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv,
+                                                             const float *__restrict__ lse,
+                                                             const bf16 *__restrict__ d_o,
+                                                             const float *__restrict__ drow,
+                                                             bf16 *__restrict__ dqkv, int S, int nh, float scale) {
+  constexpr int KS = DH + 16, VS = DH + 8, ND = DH / 32, NK = DH / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16 *Ks[2], *Vs[2];
+  Ks[0] = reinterpret_cast<bf16 *>(smem_raw);
+  Ks[1] = Ks[0] + BKV * KS;
+  Vs[0] = Ks[1] + BKV * KS;
+  Vs[1] = Vs[0] + BKV * VS;
+
+  const int qt = gridDim.x - 1 - blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int H = nh * DH;
+  const long ld = 3L * H;
+  const bf16 *qb = qkv + (long)b * S * ld + (long)h * DH;
+  const bf16 *kb = qb + H, *vb = qb + 2 * H;
+  const bf16 *dob = d_o + (long)b * S * H + (long)h * DH;
+  const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
+  const float c = scale * kLog2e;
+
+  bf16x8 qf[NK], gf[NK];
+#pragma unroll
+  for (int kd = 0; kd < NK; ++kd) {
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    qf[kd] = as_frag(qi < S ? ld16(qb + (long)qi * ld + kd * 16 + 8 * hh) : z);
+    gf[kd] = as_frag(qi < S ? ld16(dob + (long)qi * H + kd * 16 + 8 * hh) : z);
+  }
+  const float lq = qi < S ? lse[((long)b * nh + h) * S + qi] * kLog2e : INFINITY;
+  const float dq_i = qi < S ? drow[((long)b * nh + h) * S + qi] : 0.f;
+
+  f32x16 dq[ND];
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[d][e] = 0.f;
+
+  int nkv = (S + BKV - 1) / BKV;
+  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, S) - 1) / BKV + 1);
+
+  uint4 sk[DH / 32], sv[DH / 32];
+  tile_load<DH>(sk, kb, ld, 0, S, tid);
+  tile_load<DH>(sv, vb, ld, 0, S, tid);
+  tile_store<DH>(Ks[0], KS, sk, tid);
+  tile_store<DH>(Vs[0], VS, sv, tid);
+  __syncthreads();
+
+  for (int t = 0; t < nkv; ++t) {
+    const int cur = t & 1, j0 = t * BKV;
+    if (t + 1 < nkv) {
+      tile_load<DH>(sk, kb, ld, j0 + BKV, S, tid);
+      tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
+    }
+    if (!CAUSAL || j0 <= iw0 + 31) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int kd = 0; kd < NK; ++kd) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks[cur], KS, sub * 32, kd * 16, lane), qf[kd], s, 0,
+                                                      0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs[cur], VS, sub * 32, kd * 16, lane), gf[kd], dp,
+                                                       0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int j = j0 + sub * 32 + acc_row(e, lane);
+          float p = fast_exp2(s[e] * c - lq);
+          if (j >= S || (CAUSAL && j > qi)) p = 0.f;
+          dp[e] = p * (dp[e] - dq_i);
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const bf16x8 dsf = pack8(dp, half * 8);
+#pragma unroll
+          for (int d = 0; d < ND; ++d)
+            dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols(Ks[cur], KS, sub * 32 + half * 16, d * 32, lane), dsf, dq[d], 0, 0, 0);
+        }
+      }
+    }
+    if (t + 1 < nkv) {
+      tile_store<DH>(Ks[cur ^ 1], KS, sk, tid);
+      tile_store<DH>(Vs[cur ^ 1], VS, sv, tid);
+    }
+    __syncthreads();
+  }
+
+  if (qi >= S) return;
+  bf16 *qrow = dqkv + ((long)b * S + qi) * ld + (long)h * DH;
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+      bf16x4 a;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) a[t] = (bf16)(dq[d][e4 * 4 + t] * scale);
+      *reinterpret_cast<bf16x4 *>(qrow + d * 32 + 8 * e4 + 4 * hh) = a;
+    }
+}
+
+template <typename K>
+hipError_t set_smem(K kern, size_t smem) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)smem);
+}
+
+template <int DH>
+hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const void *o, const float *lse,
+                      const void *d_o, void *dqkv, float *ws, hipStream_t s) {
+  constexpr size_t smem_kv = 4 * (size_t)BKV * (DH + 16) * sizeof(bf16) + 4 * BKV * sizeof(float);
+  constexpr size_t smem_q = 2 * (size_t)BKV * ((DH + 16) + (DH + 8)) * sizeof(bf16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = set_smem(attn_bwd_dkv_kernel<DH, true>, smem_kv);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<DH, false>, smem_kv);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, true>, smem_q);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, false>, smem_q);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const long T = (long)B * S;
+  const long chunks = T * nh * DH / 8;
+  hipLaunchKernelGGL((attn_rowdot_kernel<DH>), dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
+                     (const bf16 *)o, (const bf16 *)d_o, ws, T, S, nh);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const dim3 grid((S + BROWS - 1) / BROWS, nh, B), block(256);
+  const float scale = 1.0f / sqrtf((float)DH);
+#define DP_BWD(KERN, SMEM)                                                                              \
+  hipLaunchKernelGGL(KERN, grid, block, SMEM, s, (const bf16 *)qkv, lse, (const bf16 *)d_o, (const float *)ws, \
+                     (bf16 *)dqkv, S, nh, scale)
+  if (causal) DP_BWD((attn_bwd_dkv_kernel<DH, true>), smem_kv); else DP_BWD((attn_bwd_dkv_kernel<DH, false>), smem_kv);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (causal) DP_BWD((attn_bwd_dq_kernel<DH, true>), smem_q); else DP_BWD((attn_bwd_dq_kernel<DH, false>), smem_q);
+#undef DP_BWD
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attn_mfma_supported(int S, int dh) { return S >= 1 && (dh == 64 || dh == 128); }
+
+hipError_t launch_attn_fwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, void *o, float *lse,
+                                hipStream_t s) {
+  if ((long)B * S * nh == 0) return hipSuccess;
+  return dh == 64 ? fwd_launch<64>(B, S, nh, causal, qkv, o, lse, s)
+                  : fwd_launch<128>(B, S, nh, causal, qkv, o, lse, s);
+}
+
+hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o,
+                                const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s) {
+  if ((long)B * S * nh == 0) return hipSuccess;
+  return dh == 64 ? bwd_launch<64>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, s)
+                  : bwd_launch<128>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, s);
+}
+
 }  // namespace dp
