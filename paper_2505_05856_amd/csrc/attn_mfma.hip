@@ -91,12 +91,10 @@ template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
                                                                float *__restrict__ lse, int S, int nh, float scale) {
   constexpr int KS = DH + 8, VS = DH + 16, ND = DH / 32, NK = DH / 16;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16 *Ks[2], *Vs[2];
-  Ks[0] = reinterpret_cast<bf16 *>(smem_raw);
-  Ks[1] = Ks[0] + BKV * KS;
-  Vs[0] = Ks[1] + BKV * KS;
-  Vs[1] = Vs[0] + BKV * VS;
+  // LDS stages are picked by integer offsets into one array: selecting them through
+  // pointer arrays makes the pointers generic and the fragment reads flat loads.
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
 
   const int qt = gridDim.x - 1 - blockIdx.x;   // heavy (late) causal tiles first
   const int h = blockIdx.y, b = blockIdx.z;
@@ -126,12 +124,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
   uint4 sk[DH / 32], sv[DH / 32];
   tile_load<DH>(sk, kb, ld, 0, S, tid);
   tile_load<DH>(sv, vb, ld, 0, S, tid);
-  tile_store<DH>(Ks[0], KS, sk, tid);
-  tile_store<DH>(Vs[0], VS, sv, tid);
+  tile_store<DH>(smem, KS, sk, tid);
+  tile_store<DH>(smem + VOFF, VS, sv, tid);
   __syncthreads();
 
   for (int t = 0; t < nkv; ++t) {
-    const int cur = t & 1, j0 = t * BKV;
+    const int cur = (t & 1) * STAGE, nxt = STAGE - cur, j0 = t * BKV;
     if (t + 1 < nkv) {
       tile_load<DH>(sk, kb, ld, j0 + BKV, S, tid);
       tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
@@ -145,7 +143,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
         for (int e = 0; e < 16; ++e) s[sub][e] = 0.f;
 #pragma unroll
         for (int kd = 0; kd < NK; ++kd)
-          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks[cur], KS, sub * 32, kd * 16, lane), qf[kd],
+          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, KS, sub * 32, kd * 16, lane), qf[kd],
                                                            s[sub], 0, 0, 0);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -180,12 +178,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
 #pragma unroll
           for (int d = 0; d < ND; ++d)
             acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(Vs[cur], VS, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
+                frag_cols(smem + cur + VOFF, VS, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
         }
     }
     if (t + 1 < nkv) {
-      tile_store<DH>(Ks[cur ^ 1], KS, sk, tid);
-      tile_store<DH>(Vs[cur ^ 1], VS, sv, tid);
+      tile_store<DH>(smem + nxt, KS, sk, tid);
+      tile_store<DH>(smem + nxt + VOFF, VS, sv, tid);
     }
     __syncthreads();
   }
@@ -265,17 +263,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
                                                               const float *__restrict__ drow,
                                                               bf16 *__restrict__ dqkv, int S, int nh, float scale) {
   constexpr int QS = DH + 16, ND = DH / 32, NK = DH / 16;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16 *Qs[2], *Os[2];
-  float *Ls[2], *Ds[2];
-  Qs[0] = reinterpret_cast<bf16 *>(smem_raw);
-  Qs[1] = Qs[0] + BKV * QS;
-  Os[0] = Qs[1] + BKV * QS;
-  Os[1] = Os[0] + BKV * QS;
-  Ls[0] = reinterpret_cast<float *>(Os[1] + BKV * QS);
-  Ls[1] = Ls[0] + BKV;
-  Ds[0] = Ls[1] + BKV;
-  Ds[1] = Ds[0] + BKV;
+  // stage s: Q tile, dO tile (bf16), then 64 log-sum-exp and 64 row-dot floats
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  constexpr int OOFF = BKV * QS, FOFF = 2 * BKV * QS, STAGE = 2 * BKV * QS + 4 * BKV;   // in bf16 elements
 
   const int kt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
@@ -313,17 +303,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
     if (tid < 64) sl = (i0 + tid < S) ? lrow[i0 + tid] * kLog2e : INFINITY;   // +inf: P = 0 for padding rows
     else if (tid < 128) sl = (i0 + tid - 64 < S) ? drw[i0 + tid - 64] : 0.f;
   };
-  auto stash = [&](int buf) {
-    tile_store<DH>(Qs[buf], QS, sq, tid);
-    tile_store<DH>(Os[buf], QS, so, tid);
-    if (tid < 64) Ls[buf][tid] = sl;
-    else if (tid < 128) Ds[buf][tid - 64] = sl;
+  auto stash = [&](int buf) {   // buf = element offset of the stage
+    tile_store<DH>(smem + buf, QS, sq, tid);
+    tile_store<DH>(smem + buf + OOFF, QS, so, tid);
+    if (tid < 128) reinterpret_cast<float *>(smem + buf + FOFF)[tid] = sl;   // [0,64): lse, [64,128): row dots
   };
   if (t0 < nq) { fetch(t0); stash(0); }
   __syncthreads();
 
   for (int t = t0; t < nq; ++t) {
-    const int cur = (t - t0) & 1, i0 = t * BKV;
+    const int cur = ((t - t0) & 1) * STAGE, nxt = STAGE - cur, i0 = t * BKV;
+    const float *lds_f = reinterpret_cast<const float *>(smem + cur + FOFF);
     if (t + 1 < nq) fetch(t + 1);
     if (!CAUSAL || i0 + BKV - 1 >= jw0) {
 #pragma unroll
@@ -333,16 +323,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kd = 0; kd < NK; ++kd) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs[cur], QS, sub * 32, kd * 16, lane), kf[kd], s, 0,
-                                                      0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Os[cur], QS, sub * 32, kd * 16, lane), vf[kd], dp,
-                                                       0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, QS, sub * 32, kd * 16, lane), kf[kd], s,
+                                                      0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur + OOFF, QS, sub * 32, kd * 16, lane),
+                                                       vf[kd], dp, 0, 0, 0);
         }
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
           const int r = sub * 32 + 8 * e4 + 4 * hh;
-          const float4 l4 = *reinterpret_cast<const float4 *>(Ls[cur] + r);
-          const float4 d4 = *reinterpret_cast<const float4 *>(Ds[cur] + r);
+          const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r);
+          const float4 d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r);
           const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
           for (int t4 = 0; t4 < 4; ++t4) {
@@ -359,14 +349,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
 #pragma unroll
           for (int d = 0; d < ND; ++d) {
             dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(Os[cur], QS, sub * 32 + half * 16, d * 32, lane), pf, dv[d], 0, 0, 0);
+                frag_cols(smem + cur + OOFF, QS, sub * 32 + half * 16, d * 32, lane), pf, dv[d], 0, 0, 0);
             dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(Qs[cur], QS, sub * 32 + half * 16, d * 32, lane), dsf, dk[d], 0, 0, 0);
+                frag_cols(smem + cur, QS, sub * 32 + half * 16, d * 32, lane), dsf, dk[d], 0, 0, 0);
           }
         }
       }
     }
-    if (t + 1 < nq) stash(cur ^ 1);
+    if (t + 1 < nq) stash(nxt);
     __syncthreads();
   }
 
@@ -393,12 +383,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
                                                              const float *__restrict__ drow,
                                                              bf16 *__restrict__ dqkv, int S, int nh, float scale) {
   constexpr int KS = DH + 16, VS = DH + 8, ND = DH / 32, NK = DH / 16;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16 *Ks[2], *Vs[2];
-  Ks[0] = reinterpret_cast<bf16 *>(smem_raw);
-  Ks[1] = Ks[0] + BKV * KS;
-  Vs[0] = Ks[1] + BKV * KS;
-  Vs[1] = Vs[0] + BKV * VS;
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
 
   const int qt = gridDim.x - 1 - blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z;
@@ -433,12 +419,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
   uint4 sk[DH / 32], sv[DH / 32];
   tile_load<DH>(sk, kb, ld, 0, S, tid);
   tile_load<DH>(sv, vb, ld, 0, S, tid);
-  tile_store<DH>(Ks[0], KS, sk, tid);
-  tile_store<DH>(Vs[0], VS, sv, tid);
+  tile_store<DH>(smem, KS, sk, tid);
+  tile_store<DH>(smem + VOFF, VS, sv, tid);
   __syncthreads();
 
   for (int t = 0; t < nkv; ++t) {
-    const int cur = t & 1, j0 = t * BKV;
+    const int cur = (t & 1) * STAGE, nxt = STAGE - cur, j0 = t * BKV;
     if (t + 1 < nkv) {
       tile_load<DH>(sk, kb, ld, j0 + BKV, S, tid);
       tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
@@ -451,10 +437,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kd = 0; kd < NK; ++kd) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks[cur], KS, sub * 32, kd * 16, lane), qf[kd], s, 0,
-                                                      0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs[cur], VS, sub * 32, kd * 16, lane), gf[kd], dp,
-                                                       0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, KS, sub * 32, kd * 16, lane), qf[kd], s,
+                                                      0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur + VOFF, VS, sub * 32, kd * 16, lane),
+                                                       gf[kd], dp, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -469,13 +455,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
 #pragma unroll
           for (int d = 0; d < ND; ++d)
             dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(Ks[cur], KS, sub * 32 + half * 16, d * 32, lane), dsf, dq[d], 0, 0, 0);
+                frag_cols(smem + cur, KS, sub * 32 + half * 16, d * 32, lane), dsf, dq[d], 0, 0, 0);
         }
       }
     }
     if (t + 1 < nkv) {
-      tile_store<DH>(Ks[cur ^ 1], KS, sk, tid);
-      tile_store<DH>(Vs[cur ^ 1], VS, sv, tid);
+      tile_store<DH>(smem + nxt, KS, sk, tid);
+      tile_store<DH>(smem + nxt + VOFF, VS, sv, tid);
     }
     __syncthreads();
   }

@@ -93,10 +93,12 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restric
                                                            int N, int K, int tiles_m, int tiles_n) {
   constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
   constexpr int AE = Lds<BM, TN>::kElems, BE = Lds<BN, TN>::kElems;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16 *smem = reinterpret_cast<bf16 *>(smem_raw);
-  bf16 *As[2] = {smem, smem + AE + BE};
-  bf16 *Bs[2] = {smem + AE, smem + 2 * AE + BE};
+  // One LDS array addressed by integer offsets: stage s holds A at s*(AE+BE) and B
+  // right after it.  (Picking a stage through an array of pointers turns the LDS
+  // pointers generic, and the fragment reads then compile to flat loads that wait on
+  // the global-load counter as well.)
+  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
+  constexpr int STAGE = AE + BE;
 
   // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run
   // of tiles, and walk tiles in groups of 8 tile-rows so that a run shares A and B
@@ -130,13 +132,13 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restric
   uint4 sa[BM * BK / 8 / 256], sb[BN * BK / 8 / 256];
   load_tile<BM, TN>(sa, A, lda, m0, M, 0, K, tid);
   load_tile<BN, TN>(sb, B, ldb, n0, N, 0, K, tid);
-  store_tile<BM, TN>(As[0], sa, tid);
-  store_tile<BN, TN>(Bs[0], sb, tid);
+  store_tile<BM, TN>(smem, sa, tid);
+  store_tile<BN, TN>(smem + AE, sb, tid);
   __syncthreads();
 
   const int nk = (K + BK - 1) / BK;
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
+    const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
     if (kt + 1 < nk) {
       load_tile<BM, TN>(sa, A, lda, m0, M, (kt + 1) * BK, K, tid);
       load_tile<BN, TN>(sb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
@@ -145,9 +147,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restric
     for (int k16 = 0; k16 < BK; k16 += 16) {
       bf16x8 a[FM], b[FN];
 #pragma unroll
-      for (int i = 0; i < FM; ++i) a[i] = load_frag<BM, TN>(As[cur], wm + i * 32, k16, lane);
+      for (int i = 0; i < FM; ++i) a[i] = load_frag<BM, TN>(smem + cur, wm + i * 32, k16, lane);
 #pragma unroll
-      for (int j = 0; j < FN; ++j) b[j] = load_frag<BN, TN>(Bs[cur], wn + j * 32, k16, lane);
+      for (int j = 0; j < FN; ++j) b[j] = load_frag<BN, TN>(smem + cur + AE, wn + j * 32, k16, lane);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -155,8 +157,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restric
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
-      store_tile<BM, TN>(As[cur ^ 1], sa, tid);
-      store_tile<BN, TN>(Bs[cur ^ 1], sb, tid);
+      store_tile<BM, TN>(smem + nxt, sa, tid);
+      store_tile<BN, TN>(smem + nxt + AE, sb, tid);
     }
     __syncthreads();
   }
