@@ -1,0 +1,84 @@
+"""Full-size workloads through the C ABI, in the launch configuration bench.py
+times: parity with the CPU oracle where the oracle finishes in seconds (C2 in
+full; the wider stages on a reduced layer count / micro-batch at full width),
+and at every full size the property that holds at any size: the plan does not
+change a single bit of Y, dX or any weight gradient."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import synthetic as syn
+from oracle import stage as O
+from paper_2505_05856_amd import binding as B
+from paper_2505_05856_amd.harness import StageRunner
+from test_stage_gpu import compare, oracle_step
+
+pytestmark = pytest.mark.gpu
+
+
+def make(cfg):
+    w = syn.make_weights(cfg)
+    x, dy = syn.make_activations(cfg)
+    return w, x, dy
+
+
+def test_c2_full_parity_keep_all():
+    cfg = syn.CONFIGS["C2"]
+    w, x, dy = make(cfg)
+    run = StageRunner(cfg, w, x, dy)
+    run.poison_outputs()
+    run.step(syn.plan_keep_all(cfg))
+    got = run.results()
+    keep_bits = run.raw_results()
+    ref = oracle_step(cfg, w, x, dy, dtype=np.float32)     # fp32 oracle: ~1e-6, far inside 2e-2
+    worst = compare(cfg, got, ref)
+    print(f"C2 worst max-rel-err {worst:.3e}")
+    for p in (syn.plan_all_recompute(cfg), syn.plan_all_swap(cfg), syn.plan_seeded(cfg, 7)):
+        run.poison_outputs()
+        run.step(p)
+        assert all(torch.equal(a, b) for a, b in zip(keep_bits, run.raw_results()))
+    run.close()
+
+
+@pytest.mark.parametrize("name,reduced", [("C3", dict(n_layers=2)), ("C5", dict(n_layers=1, micro_batch=1))])
+def test_wide_stage_parity_on_reduced_copy(name, reduced):
+    full = syn.CONFIGS[name]
+    cfg = dataclasses.replace(full, **reduced)
+    w, x, dy = make(cfg)
+    run = StageRunner(cfg, w, x, dy)
+    plan = syn.PLANS[name][0][1](cfg)
+    run.poison_outputs()
+    run.step(plan)
+    ref = oracle_step(cfg, w, x, dy, dtype=np.float32)
+    worst = compare(cfg, run.results(), ref)
+    print(f"{name} reduced: worst max-rel-err {worst:.3e}")
+    run.close()
+
+
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+def test_full_size_plan_is_bit_exact_and_fits_budget(name):
+    cfg = syn.CONFIGS[name]
+    budget = syn.BUDGETS.get(name, 0)
+    w, x, dy = make(cfg)
+    run = StageRunner(cfg, w, x, dy)
+    del w, x, dy
+    pname, mk = syn.PLANS[name][0]
+    plan = mk(cfg)
+    _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
+    run.poison_outputs()
+    stats = run.step(plan, budget_bytes=budget, want_stats=True)
+    assert stats["arena_high_water"] == rep["arena_peak_bytes"] and stats["peak_bytes"] == rep["peak_bytes"]
+    assert stats["d2h_bytes"] == rep["swap_out_bytes"] and stats["h2d_bytes"] == rep["swap_in_bytes"]
+    planned = run.raw_results()
+    assert not any(torch.isnan(run.y.float()).any().item() for _ in [0])
+    run.poison_outputs()
+    run.step(syn.plan_keep_all(cfg), budget_bytes=budget)
+    kept = run.raw_results()
+    assert all(torch.equal(a, b) for a, b in zip(planned, kept)), f"{name}: plan {pname} changed the bits"
+    # the plan also runs inside exactly its own validated peak
+    run.poison_outputs()
+    run.step(plan, budget_bytes=rep["peak_bytes"])
+    assert all(torch.equal(a, b) for a, b in zip(planned, run.raw_results()))
+    run.close()

@@ -29,6 +29,8 @@ def compare(cfg, got, ref, bound=None):
         for n in syn.WEIGHT_NAMES:
             worst[f"L{l}.{n}"] = O.max_rel_err(g[l][n], gr[l][n])
     bad = {k: v for k, v in worst.items() if not (v <= bound)}
+    top = sorted(worst.items(), key=lambda kv: -kv[1])[:4]
+    print("largest errors:", ", ".join(f"{k}={v:.2e}" for k, v in top))
     assert not bad, f"over {bound}: {bad}"
     return max(worst.values())
 
