@@ -15,6 +15,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace dp {
 
 namespace {
@@ -39,7 +41,10 @@ __device__ __forceinline__ uint4 ld16(const bf16 *p) { return *reinterpret_cast<
 // Global -> registers for one operand tile.  NT: tile is [BMN rows][BK], row r
 // of the operand at p + r*ld.  TN: tile is [BK][BMN], contraction row k at
 // p + k*ld.  Out-of-range chunks read as zero.
-template <int BMN, bool TN>
+// FULL: the whole tile lies inside the operand, so the loads carry no guard at all (a
+// guard's select would sit right behind its load and make the wave wait for it at once,
+// which would undo the prefetch).  Otherwise out-of-range chunks read as zero.
+template <int BMN, bool TN, bool FULL>
 __device__ __forceinline__ void load_tile(uint4 (&st)[BMN * BK / 8 / 256], const bf16 *__restrict__ p, long ld,
                                           int row0, int rows, int k0, int K, int tid) {
   constexpr int NCH = BMN * BK / 8 / 256;
@@ -50,8 +55,9 @@ __device__ __forceinline__ void load_tile(uint4 (&st)[BMN * BK / 8 / 256], const
     if (TN) { kk = c / (BMN / 8); r = (c % (BMN / 8)) * 8; }
     else { r = c / (BK / 8); kk = (c % (BK / 8)) * 8; }
     const int gr = row0 + r, gk = k0 + kk;
-    const bool ok = TN ? (gk < K && gr < rows) : (gr < rows && gk < K);
-    st[i] = ok ? ld16(TN ? p + (long)gk * ld + gr : p + (long)gr * ld + gk) : make_uint4(0, 0, 0, 0);
+    const long off = TN ? (long)gk * ld + gr : (long)gr * ld + gk;
+    if (FULL) st[i] = ld16(p + off);
+    else st[i] = (gr < rows && gk < K) ? ld16(p + off) : make_uint4(0, 0, 0, 0);
   }
 }
 
@@ -87,7 +93,7 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16 *lds, int row0, int k16, 
 }
 
 template <int BM, int BN, bool TN>
-__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
+__global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                            const bf16 *__restrict__ bias,
                                                            const bf16 *__restrict__ res, bf16 *__restrict__ C, int M,
                                                            int N, int K, int tiles_m, int tiles_n) {
@@ -129,39 +135,72 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(const bf16 *__restric
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 sa[BM * BK / 8 / 256], sb[BN * BK / 8 / 256];
-  load_tile<BM, TN>(sa, A, lda, m0, M, 0, K, tid);
-  load_tile<BN, TN>(sb, B, ldb, n0, N, 0, K, tid);
-  store_tile<BM, TN>(smem, sa, tid);
-  store_tile<BN, TN>(smem + AE, sb, tid);
+  auto main_loop = [&](auto full_tag) {
+  constexpr bool FULL = decltype(full_tag)::value;
+  // Two register stages of global loads are in flight: tile t+2 is requested while tile
+  // t is multiplied and tile t+1 waits in registers for its LDS slot, which gives every
+  // load about two k-steps to come back.
+  constexpr int NA = BM * BK / 8 / 256, NB = BN * BK / 8 / 256;
+  uint4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+  const int nk = (K + BK - 1) / BK;
+  load_tile<BM, TN, FULL>(ra0, A, lda, m0, M, 0, K, tid);
+  load_tile<BN, TN, FULL>(rb0, B, ldb, n0, N, 0, K, tid);
+  if (nk > 1) {
+    load_tile<BM, TN, FULL>(ra1, A, lda, m0, M, BK, K, tid);
+    load_tile<BN, TN, FULL>(rb1, B, ldb, n0, N, BK, K, tid);
+  }
+  store_tile<BM, TN>(smem, ra0, tid);
+  store_tile<BN, TN>(smem + AE, rb0, tid);
   __syncthreads();
 
-  const int nk = (K + BK - 1) / BK;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = (kt & 1) * STAGE, nxt = STAGE - cur;
-    if (kt + 1 < nk) {
-      load_tile<BM, TN>(sa, A, lda, m0, M, (kt + 1) * BK, K, tid);
-      load_tile<BN, TN>(sb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
+  // one k-step: request tile kt+2 into (la, lb), multiply the LDS stage at `cur`, then move
+  // tile kt+1 from (sa, sb) into the other stage
+  auto step = [&](int kt, int cur, uint4 (&la)[NA], uint4 (&lb)[NB], const uint4 (&sa)[NA], const uint4 (&sb)[NB]) {
+    if (kt + 2 < nk) {
+      load_tile<BM, TN, FULL>(la, A, lda, m0, M, (kt + 2) * BK, K, tid);
+      load_tile<BN, TN, FULL>(lb, B, ldb, n0, N, (kt + 2) * BK, K, tid);
     }
+    bf16x8 a[2][FM], b[2][FN];
 #pragma unroll
-    for (int k16 = 0; k16 < BK; k16 += 16) {
-      bf16x8 a[FM], b[FN];
+    for (int i = 0; i < FM; ++i) a[0][i] = load_frag<BM, TN>(smem + cur, wm + i * 32, 0, lane);
 #pragma unroll
-      for (int i = 0; i < FM; ++i) a[i] = load_frag<BM, TN>(smem + cur, wm + i * 32, k16, lane);
+    for (int j = 0; j < FN; ++j) b[0][j] = load_frag<BN, TN>(smem + cur + AE, wn + j * 32, 0, lane);
 #pragma unroll
-      for (int j = 0; j < FN; ++j) b[j] = load_frag<BN, TN>(smem + cur + AE, wn + j * 32, k16, lane);
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int c = ks & 1;
+      if (ks + 1 < BK / 16) {   // fragments of the next 16-slice are fetched under this slice's MFMAs
+#pragma unroll
+        for (int i = 0; i < FM; ++i) a[c ^ 1][i] = load_frag<BM, TN>(smem + cur, wm + i * 32, (ks + 1) * 16, lane);
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          b[c ^ 1][j] = load_frag<BN, TN>(smem + cur + AE, wn + j * 32, (ks + 1) * 16, lane);
+      }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+      // keep the next slice's LDS reads under this slice's MFMAs: MFMA, read, MFMA, read, ...
+#pragma unroll
+      for (int g = 0; g < FM * FN; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, TN ? 2 : 1, 0);
+      }
     }
     if (kt + 1 < nk) {
-      store_tile<BM, TN>(smem + nxt, sa, tid);
-      store_tile<BN, TN>(smem + nxt + AE, sb, tid);
+      store_tile<BM, TN>(smem + (STAGE - cur), sa, tid);
+      store_tile<BN, TN>(smem + (STAGE - cur) + AE, sb, tid);
     }
     __syncthreads();
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    step(kt, 0, ra0, rb0, ra1, rb1);
+    if (kt + 1 < nk) step(kt + 1, STAGE, ra1, rb1, ra0, rb0);
   }
+
+  };
+  if (m0 + BM <= M && n0 + BN <= N && K % BK == 0) main_loop(std::true_type{});
+  else main_loop(std::false_type{});
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block
 #pragma unroll
