@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector ALUs)
+# HBM bytes per launch of the dominant kernel (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a 256 MiB
+# device copy gives), from the rocprofv3 --pmc runs summarised in profiles/c2_step_hbm_traffic_pmc.md.
+MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 87.0e6}
 
 
 def gemm_flops(cfg):
@@ -62,6 +65,8 @@ def main():
     ap.add_argument("--plan", default=None, help="plan name (default: the config's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-op-times", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 4 times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -90,6 +95,13 @@ def main():
     x, dy = syn.make_activations(cfg)
     run = StageRunner(cfg, weights, x, dy)
     _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
+    if args.copy_calibration:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         run.step(plan, budget)
@@ -119,7 +131,7 @@ def main():
         roof = {"kernel": "gemm_nt (forward + input-gradient GEMMs)", "bound": "mfma" if cfg.dtype == "bf16" else "alu",
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "avg_launch_us": round(nt_ms * 1e3 / max(nt_launches, 1), 2), "launches_per_step": nt_launches,
-                "traffic": None}
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, plan_name))}
     stats = run.step(plan, budget, want_stats=True)
 
     out = {

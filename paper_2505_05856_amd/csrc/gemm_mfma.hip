@@ -15,6 +15,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <cstdlib>
+#include <cstring>
 #include <type_traits>
 
 namespace dp {
@@ -93,7 +95,7 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16 *lds, int row0, int k16, 
 }
 
 template <int BM, int BN, bool TN>
-__global__ __launch_bounds__(256, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM * BN > 128 * 128 ? 1 : 2, BM * BN > 128 * 128 ? 1 : 2))) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                            const bf16 *__restrict__ bias,
                                                            const bf16 *__restrict__ res, bf16 *__restrict__ C, int M,
                                                            int N, int K, int tiles_m, int tiles_n) {
@@ -242,7 +244,16 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
 template <bool TN>
 hipError_t launch_mode(const GemmArgs &a, hipStream_t s) {
   auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-  // the largest tile that still gives every CU a workgroup
+  // Interior-heavy problems take 256x256 tiles (one workgroup a CU, 128x128 a wave: half
+  // the LDS traffic per flop); otherwise the largest tile that still gives every CU a
+  // workgroup.  DPSTAGE_GEMM_TILE=256x256|128x128|64x64 overrides the choice (tuning aid).
+  static const char *force = getenv("DPSTAGE_GEMM_TILE");
+  if (force != nullptr) {
+    if (!TN && !strcmp(force, "256x256")) return launch_cfg<256, 256, false>(a, s);
+    if (!strcmp(force, "128x128")) return launch_cfg<128, 128, TN>(a, s);
+    if (!strcmp(force, "64x64")) return launch_cfg<64, 64, TN>(a, s);
+  }
+  if (!TN && tiles(256, 256) >= 1024) return launch_cfg<256, 256, false>(a, s);
   if (tiles(128, 128) >= 256) return launch_cfg<128, 128, TN>(a, s);
   if (tiles(64, 128) >= 256) return launch_cfg<64, 128, TN>(a, s);
   return launch_cfg<64, 64, TN>(a, s);
