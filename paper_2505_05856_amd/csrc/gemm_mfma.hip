@@ -7,11 +7,11 @@
 //       (dW = X^T * dY); tiles are staged in LDS as loaded and handed to the
 //       matrix cores through the LDS transpose read (ds_read_b64_tr_b16).
 //
-// A block of 256 threads (4 waves, 2x2) owns a BM x BN tile of C; every wave
-// owns (BM/2) x (BN/2) of it as 32x32 MFMA accumulators.  K advances in steps
-// of 64 through a double-buffered LDS stage: global loads for step k+1 are in
-// flight while step k feeds the MFMAs, one barrier per step.  No split-K, so
-// the summation order is fixed and results do not depend on scheduling.
+// A block of WGM x WGN waves owns a BM x BN tile of C; every wave owns
+// (BM/WGM) x (BN/WGN) of it as 32x32 MFMA accumulators.  K advances in steps of
+// 64 through a double-buffered LDS stage with two k-steps of global loads in
+// flight, one barrier per step.  No split-K, so the summation order is fixed
+// and results do not depend on scheduling.
 #include "common.h"
 #include "kernels.h"
 
@@ -26,13 +26,12 @@ namespace {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-constexpr int BK = 64;
 
 // LDS row strides in elements.  NT rows hold BK (+8) contraction elements: the
 // 144-byte stride spreads the 16-byte fragment reads of 8 consecutive rows over
 // all banks.  TN rows hold BM/BN (+16) elements: the 32-byte skew does the same
 // for the four rows one transpose read touches.
-template <int BMN, bool TN> struct Lds {
+template <int BMN, bool TN, int BK> struct Lds {
   static constexpr int kStride = TN ? BMN + 16 : BK + 8;
   static constexpr int kRows = TN ? BK : BMN;
   static constexpr int kElems = kStride * kRows;
@@ -40,19 +39,33 @@ template <int BMN, bool TN> struct Lds {
 
 __device__ __forceinline__ uint4 ld16(const bf16 *p) { return *reinterpret_cast<const uint4 *>(p); }
 
+// ---- explicitly counted global loads ----------------------------------------------
+// The main loop keeps two k-steps of global loads in flight.  Written as ordinary loads
+// the compiler's wait-count insertion drains all of them at every loop back-edge, so the
+// loads are issued as inline asm (invisible to that pass) and waited for with explicit
+// s_waitcnt vmcnt(n): the counter retires in order, so "at most n outstanding" means every
+// load older than the n youngest has landed.  touch() makes the registers look rewritten
+// by the wait, which pins their consumers behind it.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void gload16(u32x4 &d, unsigned byte_off, const void *uniform_base) {
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=&v"(d) : "v"(byte_off), "s"(uniform_base));
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N)); }
+__device__ __forceinline__ void touch(u32x4 &d) { asm volatile("" : "+v"(d)); }
+
 // Global -> registers for one operand tile.  NT: tile is [BMN rows][BK], row r
 // of the operand at p + r*ld.  TN: tile is [BK][BMN], contraction row k at
 // p + k*ld.  Out-of-range chunks read as zero.
 // FULL: the whole tile lies inside the operand, so the loads carry no guard at all (a
 // guard's select would sit right behind its load and make the wave wait for it at once,
 // which would undo the prefetch).  Otherwise out-of-range chunks read as zero.
-template <int BMN, bool TN, bool FULL>
-__device__ __forceinline__ void load_tile(uint4 (&st)[BMN * BK / 8 / 256], const bf16 *__restrict__ p, long ld,
+template <int BMN, bool TN, bool FULL, int BK, int NTHR>
+__device__ __forceinline__ void load_tile(uint4 (&st)[BMN * BK / 8 / NTHR], const bf16 *__restrict__ p, long ld,
                                           int row0, int rows, int k0, int K, int tid) {
-  constexpr int NCH = BMN * BK / 8 / 256;
+  constexpr int NCH = BMN * BK / 8 / NTHR;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int c = tid + i * 256;
+    const int c = tid + i * NTHR;
     int r, kk;
     if (TN) { kk = c / (BMN / 8); r = (c % (BMN / 8)) * 8; }
     else { r = c / (BK / 8); kk = (c % (BK / 8)) * 8; }
@@ -63,25 +76,25 @@ __device__ __forceinline__ void load_tile(uint4 (&st)[BMN * BK / 8 / 256], const
   }
 }
 
-template <int BMN, bool TN>
-__device__ __forceinline__ void store_tile(bf16 *lds, const uint4 (&st)[BMN * BK / 8 / 256], int tid) {
-  constexpr int NCH = BMN * BK / 8 / 256;
-  constexpr int S = Lds<BMN, TN>::kStride;
+template <int BMN, bool TN, int BK, int NTHR, typename V>
+__device__ __forceinline__ void store_tile(bf16 *lds, const V (&st)[BMN * BK / 8 / NTHR], int tid) {
+  constexpr int NCH = BMN * BK / 8 / NTHR;
+  constexpr int S = Lds<BMN, TN, BK>::kStride;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int c = tid + i * 256;
+    const int c = tid + i * NTHR;
     int off;
     if (TN) off = (c / (BMN / 8)) * S + (c % (BMN / 8)) * 8;
     else off = (c / (BK / 8)) * S + (c % (BK / 8)) * 8;
-    *reinterpret_cast<uint4 *>(lds + off) = st[i];
+    *reinterpret_cast<V *>(lds + off) = st[i];
   }
 }
 
 // One 32 x 16 MFMA operand fragment: row (lane%32) of the 32-row block at
 // `row0`, contraction elements k16 + 8*(lane/32) .. +7.
-template <int BMN, bool TN>
+template <int BMN, bool TN, int BK>
 __device__ __forceinline__ bf16x8 load_frag(const bf16 *lds, int row0, int k16, int lane) {
-  constexpr int S = Lds<BMN, TN>::kStride;
+  constexpr int S = Lds<BMN, TN, BK>::kStride;
   if (!TN) return *reinterpret_cast<const bf16x8 *>(lds + (row0 + (lane & 31)) * S + k16 + 8 * (lane >> 5));
   // transpose read: a 16-lane group fetches 4 contraction rows x 16 columns; lane i of
   // the group supplies the address of row i/4, columns 4*(i%4).. and receives column i
@@ -94,13 +107,14 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16 *lds, int row0, int k16, 
   return u.v;
 }
 
-template <int BM, int BN, bool TN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM * BN > 128 * 128 ? 1 : 2, BM * BN > 128 * 128 ? 1 : 2))) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
+template <int BM, int BN, bool TN, int BK, int WPE, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                            const bf16 *__restrict__ bias,
                                                            const bf16 *__restrict__ res, bf16 *__restrict__ C, int M,
                                                            int N, int K, int tiles_m, int tiles_n) {
-  constexpr int WM = BM / 2, WN = BN / 2, FM = WM / 32, FN = WN / 32;
-  constexpr int AE = Lds<BM, TN>::kElems, BE = Lds<BN, TN>::kElems;
+  constexpr int NTHR = 64 * WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+  constexpr int AE = Lds<BM, TN, BK>::kElems, BE = Lds<BN, TN, BK>::kElems;
   // One LDS array addressed by integer offsets: stage s holds A at s*(AE+BE) and B
   // right after it.  (Picking a stage through an array of pointers turns the LDS
   // pointers generic, and the fragment reads then compile to flat loads that wait on
@@ -126,7 +140,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM * BN > 1
   const int m0 = tm * BM, n0 = tn * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
+  const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
   const long lda = TN ? M : K, ldb = TN ? N : K;
 
   f32x16 acc[FM][FN];
@@ -137,45 +151,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM * BN > 1
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  auto main_loop = [&](auto full_tag) {
-  constexpr bool FULL = decltype(full_tag)::value;
-  // Two register stages of global loads are in flight: tile t+2 is requested while tile
-  // t is multiplied and tile t+1 waits in registers for its LDS slot, which gives every
-  // load about two k-steps to come back.
-  constexpr int NA = BM * BK / 8 / 256, NB = BN * BK / 8 / 256;
-  uint4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
-  const int nk = (K + BK - 1) / BK;
-  load_tile<BM, TN, FULL>(ra0, A, lda, m0, M, 0, K, tid);
-  load_tile<BN, TN, FULL>(rb0, B, ldb, n0, N, 0, K, tid);
-  if (nk > 1) {
-    load_tile<BM, TN, FULL>(ra1, A, lda, m0, M, BK, K, tid);
-    load_tile<BN, TN, FULL>(rb1, B, ldb, n0, N, BK, K, tid);
-  }
-  store_tile<BM, TN>(smem, ra0, tid);
-  store_tile<BN, TN>(smem + AE, rb0, tid);
-  __syncthreads();
-
-  // one k-step: request tile kt+2 into (la, lb), multiply the LDS stage at `cur`, then move
-  // tile kt+1 from (sa, sb) into the other stage
-  auto step = [&](int kt, int cur, uint4 (&la)[NA], uint4 (&lb)[NB], const uint4 (&sa)[NA], const uint4 (&sb)[NB]) {
-    if (kt + 2 < nk) {
-      load_tile<BM, TN, FULL>(la, A, lda, m0, M, (kt + 2) * BK, K, tid);
-      load_tile<BN, TN, FULL>(lb, B, ldb, n0, N, (kt + 2) * BK, K, tid);
-    }
+  // multiply the LDS stage at element offset `cur` into the accumulators
+  auto compute = [&](int cur) {
     bf16x8 a[2][FM], b[2][FN];
 #pragma unroll
-    for (int i = 0; i < FM; ++i) a[0][i] = load_frag<BM, TN>(smem + cur, wm + i * 32, 0, lane);
+    for (int i = 0; i < FM; ++i) a[0][i] = load_frag<BM, TN, BK>(smem + cur, wm + i * 32, 0, lane);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) b[0][j] = load_frag<BN, TN>(smem + cur + AE, wn + j * 32, 0, lane);
+    for (int j = 0; j < FN; ++j) b[0][j] = load_frag<BN, TN, BK>(smem + cur + AE, wn + j * 32, 0, lane);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const int c = ks & 1;
       if (ks + 1 < BK / 16) {   // fragments of the next 16-slice are fetched under this slice's MFMAs
 #pragma unroll
-        for (int i = 0; i < FM; ++i) a[c ^ 1][i] = load_frag<BM, TN>(smem + cur, wm + i * 32, (ks + 1) * 16, lane);
+        for (int i = 0; i < FM; ++i) a[c ^ 1][i] = load_frag<BM, TN, BK>(smem + cur, wm + i * 32, (ks + 1) * 16, lane);
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          b[c ^ 1][j] = load_frag<BN, TN>(smem + cur + AE, wn + j * 32, (ks + 1) * 16, lane);
+          b[c ^ 1][j] = load_frag<BN, TN, BK>(smem + cur + AE, wn + j * 32, (ks + 1) * 16, lane);
       }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
@@ -189,20 +180,92 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM * BN > 1
         __builtin_amdgcn_sched_group_barrier(0x100, TN ? 2 : 1, 0);
       }
     }
-    if (kt + 1 < nk) {
-      store_tile<BM, TN>(smem + (STAGE - cur), sa, tid);
-      store_tile<BN, TN>(smem + (STAGE - cur) + AE, sb, tid);
-    }
-    __syncthreads();
   };
-  for (int kt = 0; kt < nk; kt += 2) {
-    step(kt, 0, ra0, rb0, ra1, rb1);
-    if (kt + 1 < nk) step(kt + 1, STAGE, ra1, rb1, ra0, rb0);
-  }
+  constexpr int NA = BM * BK / 8 / NTHR, NB = BN * BK / 8 / NTHR;
 
-  };
-  if (m0 + BM <= M && n0 + BN <= N && K % BK == 0) main_loop(std::true_type{});
-  else main_loop(std::false_type{});
+  if (K % BK == 0) {
+    // ---- two-deep software pipeline with explicitly counted loads -----------------
+    // Rows beyond M / N are clamped onto the last valid row instead of zero-filled: they
+    // only feed accumulators whose results are never stored.
+    u32x4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
+    unsigned offa[NA], offb[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      const int c = tid + i * NTHR;
+      if (TN) offa[i] = (unsigned)(((c / (BM / 8)) * lda + min((c % (BM / 8)) * 8, M - 8 - m0)) * 2);
+      else offa[i] = (unsigned)((min(c / (BK / 8), M - 1 - m0) * lda + (c % (BK / 8)) * 8) * 2);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int c = tid + i * NTHR;
+      if (TN) offb[i] = (unsigned)(((c / (BN / 8)) * ldb + min((c % (BN / 8)) * 8, N - 8 - n0)) * 2);
+      else offb[i] = (unsigned)((min(c / (BK / 8), N - 1 - n0) * ldb + (c % (BK / 8)) * 8) * 2);
+    }
+    const bf16 *pa = TN ? A + m0 : A + (long)m0 * lda;   // uniform: advanced one k-step per issue
+    const bf16 *pb = TN ? B + n0 : B + (long)n0 * ldb;
+    const long step_a = TN ? (long)BK * lda : BK, step_b = TN ? (long)BK * ldb : BK;
+    auto issue = [&](u32x4 (&xa)[NA], u32x4 (&xb)[NB]) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) gload16(xa[i], offa[i], pa);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) gload16(xb[i], offb[i], pb);
+      pa += step_a;
+      pb += step_b;
+    };
+    auto landed = [&](u32x4 (&xa)[NA], u32x4 (&xb)[NB]) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) touch(xa[i]);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) touch(xb[i]);
+    };
+    const int nk = K / BK;
+    issue(ra0, rb0);
+    if (nk > 1) { issue(ra1, rb1); wait_vmcnt<NA + NB>(); } else { wait_vmcnt<0>(); }
+    landed(ra0, rb0);
+    store_tile<BM, TN, BK, NTHR>(smem, ra0, tid);
+    store_tile<BN, TN, BK, NTHR>(smem + AE, rb0, tid);
+    __syncthreads();
+    // k-step kt: request tile kt+2 into (la, lb), multiply stage `cur`, then move tile kt+1
+    // (requested one step ago, in (sa, sb)) into the other stage
+    auto step = [&](int kt, int cur, u32x4 (&la)[NA], u32x4 (&lb)[NB], u32x4 (&sa)[NA], u32x4 (&sb)[NB]) {
+      const bool more = kt + 2 < nk;
+      if (more) issue(la, lb);
+      compute(cur);
+      if (kt + 1 < nk) {
+        if (more) wait_vmcnt<NA + NB>(); else wait_vmcnt<0>();
+        landed(sa, sb);
+        store_tile<BM, TN, BK, NTHR>(smem + (STAGE - cur), sa, tid);
+        store_tile<BN, TN, BK, NTHR>(smem + (STAGE - cur) + AE, sb, tid);
+      }
+      __syncthreads();
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+      step(kt, 0, ra0, rb0, ra1, rb1);
+      if (kt + 1 < nk) step(kt + 1, STAGE, ra1, rb1, ra0, rb0);
+    }
+  } else {
+    // ---- K tail present: guarded loads (zero-filled), one k-step of prefetch ------
+    uint4 ra[NA], rb[NB];
+    const int nk = (K + BK - 1) / BK;
+    load_tile<BM, TN, false, BK, NTHR>(ra, A, lda, m0, M, 0, K, tid);
+    load_tile<BN, TN, false, BK, NTHR>(rb, B, ldb, n0, N, 0, K, tid);
+    store_tile<BM, TN, BK, NTHR>(smem, ra, tid);
+    store_tile<BN, TN, BK, NTHR>(smem + AE, rb, tid);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = (kt & 1) * STAGE;
+      if (kt + 1 < nk) {
+        load_tile<BM, TN, false, BK, NTHR>(ra, A, lda, m0, M, (kt + 1) * BK, K, tid);
+        load_tile<BN, TN, false, BK, NTHR>(rb, B, ldb, n0, N, (kt + 1) * BK, K, tid);
+      }
+      compute(cur);
+      if (kt + 1 < nk) {
+        store_tile<BM, TN, BK, NTHR>(smem + (STAGE - cur), ra, tid);
+        store_tile<BN, TN, BK, NTHR>(smem + (STAGE - cur) + AE, rb, tid);
+      }
+      __syncthreads();
+    }
+  }
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block
 #pragma unroll
@@ -224,11 +287,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BM * BN > 1
   }
 }
 
-template <int BM, int BN, bool TN>
+template <int BM, int BN, bool TN, int BK = 64, int WPE = (BM * BN > 128 * 128 ? 1 : 2), int WGM = 2, int WGN = 2>
 hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
-  constexpr size_t smem = 2 * (size_t)(Lds<BM, TN>::kElems + Lds<BN, TN>::kElems) * sizeof(bf16);
+  constexpr size_t smem = 2 * (size_t)(Lds<BM, TN, BK>::kElems + Lds<BN, TN, BK>::kElems) * sizeof(bf16);
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<BM, BN, TN>;
+  auto kern = gemm_mfma_kernel<BM, BN, TN, BK, WPE, WGM, WGN>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -236,7 +299,7 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
     attr_set = true;
   }
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, (const bf16 *)a.A, (const bf16 *)a.B,
+  hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WGM * WGN), smem, s, (const bf16 *)a.A, (const bf16 *)a.B,
                      (const bf16 *)a.bias, (const bf16 *)a.res, (bf16 *)a.C, a.M, a.N, a.K, tiles_m, tiles_n);
   return hipGetLastError();
 }
@@ -244,16 +307,17 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
 template <bool TN>
 hipError_t launch_mode(const GemmArgs &a, hipStream_t s) {
   auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-  // Interior-heavy problems take 256x256 tiles (one workgroup a CU, 128x128 a wave: half
-  // the LDS traffic per flop); otherwise the largest tile that still gives every CU a
-  // workgroup.  DPSTAGE_GEMM_TILE=256x256|128x128|64x64 overrides the choice (tuning aid).
+  // Tile choice: 256x256 (8 waves, 128x64 a wave) halves the L1/L2 traffic per flop of
+  // 128x128 and is taken whenever it still gives nearly every CU a workgroup; below that
+  // the largest tile that does.  DPSTAGE_GEMM_TILE=256x256|128x128|64x64 overrides
+  // the choice (tuning aid).
   static const char *force = getenv("DPSTAGE_GEMM_TILE");
   if (force != nullptr) {
-    if (!TN && !strcmp(force, "256x256")) return launch_cfg<256, 256, false>(a, s);
+    if (!strcmp(force, "256x256")) return launch_cfg<256, 256, TN, 64, 2, 4, 2>(a, s);
     if (!strcmp(force, "128x128")) return launch_cfg<128, 128, TN>(a, s);
     if (!strcmp(force, "64x64")) return launch_cfg<64, 64, TN>(a, s);
   }
-  if (!TN && tiles(256, 256) >= 1024) return launch_cfg<256, 256, false>(a, s);
+  if (tiles(256, 256) >= 240) return launch_cfg<256, 256, TN, 64, 2, 4, 2>(a, s);
   if (tiles(128, 128) >= 256) return launch_cfg<128, 128, TN>(a, s);
   if (tiles(64, 128) >= 256) return launch_cfg<64, 128, TN>(a, s);
   return launch_cfg<64, 64, TN>(a, s);
