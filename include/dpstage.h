@@ -201,10 +201,12 @@ size_t dp_op_workspace_bytes(int32_t rows, int32_t cols);
  * (mean, rstd); y or stats may be NULL (not written). */
 dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x,
                               const void *gamma, const void *beta, void *y, float *stats, void *hip_stream);
-/* dx = [dres +] LayerNorm-backward(dy); dgamma, dbeta over all rows. */
+/* dx = [dres +] LayerNorm-backward(dy); dgamma, dbeta over all rows; dx_colsum
+ * (nullable, [cols]) receives the column sums of dx as stored.  dy may be dx. */
 dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
                               const float *stats, const void *gamma, const void *dres /*nullable*/,
-                              void *dx, void *dgamma, void *dbeta, void *ws, void *hip_stream);
+                              void *dx, void *dgamma, void *dbeta, void *dx_colsum /*nullable*/, void *ws,
+                              void *hip_stream);
 dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream);
 /* dx = dy * gelu'(x) */
 dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,

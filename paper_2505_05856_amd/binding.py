@@ -89,7 +89,7 @@ def lib() -> C.CDLL:
     L.dp_op_workspace_bytes.restype = sz
     L.dp_op_workspace_bytes.argtypes = [i32, i32]
     L.dp_op_layernorm_fwd.argtypes = [i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
-    L.dp_op_layernorm_bwd.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.dp_op_layernorm_bwd.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dp_op_gelu_fwd.argtypes = [i32, i32, sz, vp, vp, vp]
     L.dp_op_gelu_bwd.argtypes = [i32, i32, sz, vp, vp, vp, vp]
     L.dp_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -227,9 +227,9 @@ def op_layernorm_fwd(x, gamma, beta, eps, y, stats, stream=None):
                                      _ptr(y), _ptr(stats), _stream_ptr(stream)))
 
 
-def op_layernorm_bwd(dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, stream=None):
+def op_layernorm_bwd(dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, dx_colsum=None, stream=None):
     _check(lib().dp_op_layernorm_bwd(_dt(x), x.shape[0], x.shape[1], _ptr(dy), _ptr(x), _ptr(stats), _ptr(gamma),
-                                     _ptr(dres), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(ws),
+                                     _ptr(dres), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum), _ptr(ws),
                                      _stream_ptr(stream)))
 
 

@@ -64,6 +64,15 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int e0) {
   return r;
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin by launch index.  This maps the launch
+// index to a work index so that each XCD gets one contiguous run of work items: the
+// row tiles of one (batch, head) then share K/V (or Q/dO) in a single XCD's L2
+// instead of being fetched from HBM once per XCD.
+__device__ __forceinline__ int xcd_contiguous(int pid, int n) {
+  const int xcd = pid & 7, idx = pid >> 3, base = n >> 3, rem = n & 7;
+  return xcd * base + (xcd < rem ? xcd : rem) + idx;
+}
+
 // Row index, inside its 32-row block, of element e of a 32x32 MFMA result held by `lane`.
 __device__ __forceinline__ int acc_row(int e, int lane) { return 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3); }
 
@@ -96,8 +105,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
 
-  const int qt = gridDim.x - 1 - blockIdx.x;   // heavy (late) causal tiles first
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int nqt = (S + BROWS - 1) / BROWS;
+  const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int qt = nqt - 1 - wid % nqt;   // heavy (late) causal tiles first
+  const int h = (wid / nqt) % nh, b = wid / (nqt * nh);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
   const int H = nh * DH;
   const long ld = 3L * H;
@@ -218,7 +229,7 @@ hipError_t fwd_launch(int B, int S, int nh, int causal, const void *qkv, void *o
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid((S + BROWS - 1) / BROWS, nh, B), block(256);
+  const dim3 grid(((S + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
   if (causal)
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH, true>), grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S,
@@ -267,7 +278,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int OOFF = BKV * QS, FOFF = 2 * BKV * QS, STAGE = 2 * BKV * QS + 4 * BKV;   // in bf16 elements
 
-  const int kt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int nkt = (S + BROWS - 1) / BROWS;
+  const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int kt = wid % nkt, h = (wid / nkt) % nh, b = wid / (nkt * nh);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
   const int H = nh * DH;
   const long ld = 3L * H;
@@ -386,8 +399,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
 
-  const int qt = gridDim.x - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int nqt = (S + BROWS - 1) / BROWS;
+  const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int qt = nqt - 1 - wid % nqt;
+  const int h = (wid / nqt) % nh, b = wid / (nqt * nh);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
   const int H = nh * DH;
   const long ld = 3L * H;
@@ -505,7 +520,7 @@ hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const v
                      (const bf16 *)o, (const bf16 *)d_o, ws, T, S, nh);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const dim3 grid((S + BROWS - 1) / BROWS, nh, B), block(256);
+  const dim3 grid(((S + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
 #define DP_BWD(KERN, SMEM)                                                                              \
   hipLaunchKernelGGL(KERN, grid, block, SMEM, s, (const bf16 *)qkv, lse, (const bf16 *)d_o, (const float *)ws, \

@@ -68,24 +68,23 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, co
 }
 
 // Pass 1 of LayerNorm backward.  Block b handles rows [b*rpb, (b+1)*rpb), one
-// wave per row; writes dx and the block's partial (dgamma | dbeta) row into
-// part[b][2*cols].
-template <typename T, int NC>
+// wave per row; writes dx and the block's partial row (dgamma | dbeta [| colsum(dx)])
+// into part[b][NV*cols], NV = 3 with SUMDX (the column sums of the stored dx are the
+// bias gradient of the linear layer that produced LayerNorm's input).
+template <typename T, int NC, bool SUMDX>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
                                                      const float *__restrict__ stats, const T *__restrict__ gamma,
                                                      const T *__restrict__ dres, T *dx,
                                                      float *__restrict__ part, int rows, int cols, int rpb) {
-  __shared__ float red[4][2][512];
+  constexpr int NV = SUMDX ? 3 : 2;
+  __shared__ float red[4][NV][512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row_end = min(rows, (int)(blockIdx.x + 1) * rpb);
-  float dg[NC][8], db[NC][8], gm[NC][8];
+  float dg[NC][8], db[NC][8], ds[SUMDX ? NC : 1][8];
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    const int col = (c * 64 + lane) * 8;
+  for (int c = 0; c < NC; ++c)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { dg[c][i] = 0.f; db[c][i] = 0.f; gm[c][i] = 0.f; }
-    if (col < cols) load8(gamma + col, gm[c]);
-  }
+    for (int i = 0; i < 8; ++i) { dg[c][i] = 0.f; db[c][i] = 0.f; if (SUMDX) ds[c][i] = 0.f; }
   const float inv_n = 1.0f / (float)cols;
   for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
     const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
@@ -96,15 +95,16 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
     for (int c = 0; c < NC; ++c) {
       const int col = (c * 64 + lane) * 8;
       if (col < cols) {
-        float d[8];
+        float d[8], gm[8];
         load8(x + base + col, xh[c]);
         load8(dy + base + col, d);
+        load8(gamma + col, gm);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           xh[c][i] = (xh[c][i] - mean) * rstd;
           dg[c][i] += d[i] * xh[c][i];
           db[c][i] += d[i];
-          g[c][i] = d[i] * gm[c][i];
+          g[c][i] = d[i] * gm[i];
           s1 += g[c][i];
           s2 += g[c][i] * xh[c][i];
         }
@@ -125,11 +125,15 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
           for (int i = 0; i < 8; ++i) o[i] += r[i];
         }
         store8(dx + base + col, o);
+        if (SUMDX) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) ds[c][i] += (float)(T)o[i];   // the value as stored
+        }
       }
     }
   }
   // ordered block reduction of the four waves' column partials, 512 columns at a time
-  float *prow = part + (size_t)blockIdx.x * 2 * cols;
+  float *prow = part + (size_t)blockIdx.x * NV * cols;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
     if (c * 512 >= cols) break;
@@ -138,25 +142,26 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
     for (int i = 0; i < 8; ++i) {
       red[wave][0][lane * 8 + i] = dg[c][i];
       red[wave][1][lane * 8 + i] = db[c][i];
+      if (SUMDX) red[wave][NV - 1][lane * 8 + i] = ds[c][i];
     }
     __syncthreads();
-    for (int j = threadIdx.x; j < 1024; j += 256) {
+    for (int j = threadIdx.x; j < NV * 512; j += 256) {
       const int which = j >> 9, k = j & 511;
       const int col = c * 512 + k;
       if (col < cols) {
-        const float s = ((red[0][which][k] + red[1][which][k]) + red[2][which][k]) + red[3][which][k];
-        prow[(size_t)which * cols + col] = s;
+        const float t = ((red[0][which][k] + red[1][which][k]) + red[2][which][k]) + red[3][which][k];
+        prow[(size_t)which * cols + col] = t;
       }
     }
   }
 }
 
-// Pass 2: out[j] = sum_{b<nb} part[b][j], summed in a fixed order.
-// Block = 64 columns x 16 row groups.
+// Pass 2: out[j] = sum_{b<nb} part[b][j], summed in a fixed order; column j of the
+// `width`-wide partial rows goes to out[j / seg][j % seg].  Block = 64 columns x 16 row groups.
 template <typename T>
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, int nb, int width,
                                                                T *__restrict__ out0, T *__restrict__ out1,
-                                                               int split) {
+                                                               T *__restrict__ out2, int seg) {
   __shared__ float red[16][64];
   const int cx = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cx;
@@ -169,8 +174,8 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
     float t = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) t += red[i][cx];
-    if (col < split) stf(out0 + col, t);
-    else stf(out1 + (col - split), t);
+    const int which = col / seg, k = col - which * seg;
+    stf((which == 0 ? out0 : which == 1 ? out1 : out2) + k, t);
   }
 }
 
@@ -243,6 +248,42 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *dy /* may alias 
   }
 }
 
+// dx = dy * gelu'(x) over [rows, cols] plus the column sums of the stored dx (the bias
+// gradient of the linear layer in front of the GELU): block (cx, rb) covers 512 columns
+// and rows [rb*rpb, (rb+1)*rpb); its partial sums go to part[rb][cols].
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_colsum_kernel(const T *dy /* may alias dx */,
+                                                              const T *__restrict__ x, T *dx,
+                                                              float *__restrict__ part, int rows, int cols, int rpb,
+                                                              int kind) {
+  __shared__ float red[4][512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = (blockIdx.x * 64 + lane) * 8;
+  const int row_end = min(rows, (int)(blockIdx.y + 1) * rpb);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < cols) {
+    for (int row = blockIdx.y * rpb + wave; row < row_end; row += 4) {
+      const size_t at = (size_t)row * cols + col;
+      float v[8], d[8];
+      load8(x + at, v);
+      load8(dy + at, d);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        v[i] = d[i] * gelu_df(v[i], kind);
+        acc[i] += (float)(T)v[i];
+      }
+      store8(dx + at, v);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) red[wave][lane * 8 + i] = acc[i];
+  __syncthreads();
+  for (int k = threadIdx.x; k < 512; k += 256) {
+    const int c = blockIdx.x * 512 + k;
+    if (c < cols) part[(size_t)blockIdx.y * cols + c] = ((red[0][k] + red[1][k]) + red[2][k]) + red[3][k];
+  }
+}
+
 // ------------------------------------------------------------------ misc
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int rows,
@@ -297,16 +338,17 @@ hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x
                         : ln_fwd_t<float>(rows, cols, eps, x, gamma, beta, y, stats, s);
 }
 
-template <typename T>
+template <typename T, bool SUMDX>
 static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, const float *stats,
-                           const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *ws,
-                           hipStream_t s) {
+                           const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
+                           void *ws, hipStream_t s) {
   int rpb;
   const int nb = row_blocks(rows, 8, &rpb);
+  const int nv = SUMDX ? 3 : 2;
   float *part = (float *)ws;
-#define DP_LN_BWD(NC)                                                                                      \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NC>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, stats, \
-                     (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
+#define DP_LN_BWD(NC)                                                                                       \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NC, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, \
+                     stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
   switch (ln_chunks(cols)) {
     case 1: DP_LN_BWD(1); break;
     case 2: DP_LN_BWD(2); break;
@@ -317,17 +359,44 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
 #undef DP_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((2 * cols + 63) / 64), dim3(1024), 0, s, part, nb,
-                     2 * cols, (T *)dgamma, (T *)dbeta, cols);
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((nv * cols + 63) / 64), dim3(1024), 0, s, part, nb,
+                     nv * cols, (T *)dgamma, (T *)dbeta, (T *)dxsum, cols);
   return hipGetLastError();
 }
 
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
-                         const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *ws,
-                         hipStream_t s) {
+                         const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
+                         void *ws, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  return dtype == kBF16 ? ln_bwd_t<bf16>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, s)
-                        : ln_bwd_t<float>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, s);
+  if (dxsum != nullptr)
+    return dtype == kBF16
+               ? ln_bwd_t<bf16, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s)
+               : ln_bwd_t<float, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s);
+  return dtype == kBF16
+             ? ln_bwd_t<bf16, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s)
+             : ln_bwd_t<float, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s);
+}
+
+template <typename T>
+static hipError_t gelu_bwd_colsum_t(int kind, int rows, int cols, const void *dy, const void *x, void *dx,
+                                    void *dbias, void *ws, hipStream_t s) {
+  int rpb;
+  const int nb = row_blocks(rows, 16, &rpb);
+  float *part = (float *)ws;
+  hipLaunchKernelGGL((gelu_bwd_colsum_kernel<T>), dim3((cols + 511) / 512, nb), dim3(256), 0, s, (const T *)dy,
+                     (const T *)x, (T *)dx, part, rows, cols, rpb, kind);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((cols + 63) / 64), dim3(1024), 0, s, part, nb, cols,
+                     (T *)dbias, (T *)dbias, (T *)dbias, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
+                                  void *dbias, void *ws, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  return dtype == kBF16 ? gelu_bwd_colsum_t<bf16>(kind, rows, cols, dy, x, dx, dbias, ws, s)
+                        : gelu_bwd_colsum_t<float>(kind, rows, cols, dy, x, dx, dbias, ws, s);
 }
 
 static int ew_grid(size_t n8) {
@@ -370,7 +439,7 @@ static hipError_t colsum_t(int rows, int cols, const void *x, void *out, void *w
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((cols + 63) / 64), dim3(1024), 0, s, part, nb, cols,
-                     (T *)out, (T *)out, cols);
+                     (T *)out, (T *)out, (T *)out, cols);
   return hipGetLastError();
 }
 

@@ -23,11 +23,11 @@ inline int row_blocks(int rows, int min_rows, int *rpb) {
   *rpb = (rows + nb - 1) / nb;
   return (rows + *rpb - 1) / *rpb;
 }
-// Bytes of fp32 partials a column reduction over [rows, cols] needs (x2: LayerNorm
-// backward reduces two vectors at once).
+// Bytes of fp32 partials a column reduction over [rows, cols] needs (x3: LayerNorm
+// backward reduces up to three vectors at once).
 inline size_t reduce_ws_bytes(int rows, int cols) {
   int rpb;
-  return (size_t)row_blocks(rows, 8, &rpb) * 2 * (size_t)cols * sizeof(float);
+  return (size_t)row_blocks(rows, 8, &rpb) * 3 * (size_t)cols * sizeof(float);
 }
 
 struct GemmArgs {
@@ -47,9 +47,13 @@ bool attn_mfma_supported(int S, int dh);
 // ---- elementwise / reductions ----------------------------------------------
 hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x, const void *gamma,
                          const void *beta, void *y, float *stats, hipStream_t s);
+// dxsum (nullable): receives the column sums of the stored dx
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
-                         const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *ws,
-                         hipStream_t s);
+                         const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
+                         void *ws, hipStream_t s);
+// dx = dy * gelu'(x) over [rows, cols] and dbias = column sums of the stored dx
+hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
+                                  void *dbias, void *ws, hipStream_t s);
 hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s);
 hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s);
 hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s);

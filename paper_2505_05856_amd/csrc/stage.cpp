@@ -335,12 +335,22 @@ struct Walk {
     drop(ws);
   }
   void ln_bwd(const void *dyp, const void *x, const void *stats, const void *gamma, const void *dres, void *dx,
-              void *dgamma, void *dbeta) {
+              void *dgamma, void *dbeta, void *dxsum) {
     Buf ws = tmp(dp::reduce_ws_bytes((int)c.T, c.H));
     prof_begin(DP_OPC_LN_BWD);
     if (live)
       check(dp::launch_ln_bwd(c.dtype, (int)c.T, c.H, dyp, x, (const float *)stats, gamma, dres, dx, dgamma, dbeta,
-                              bptr(ws), cs));
+                              dxsum, bptr(ws), cs));
+    prof_end();
+    drop(ws);
+  }
+
+  // dF = dG * gelu'(FC1_OUT) in place, plus db1 = column sums of dF
+  void gelu_bwd(void *dg, const void *fc1_out, void *db1) {
+    Buf ws = tmp(dp::reduce_ws_bytes((int)c.T, c.F));
+    prof_begin(DP_OPC_GELU_BWD);
+    if (live)
+      check(dp::launch_gelu_bwd_colsum(c.dtype, c.gelu, (int)c.T, c.F, dg, fc1_out, dg, db1, bptr(ws), cs));
     prof_end();
     drop(ws);
   }
@@ -521,15 +531,13 @@ struct Walk {
         Buf dg = tmp(tf);
         gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, dcur, W_(w_fc2), nullptr, nullptr, bptr(dg));
         gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), dcur, nullptr, nullptr, G_(w_fc2));
-        colsum(T, H, dcur, G_(b_fc2));
+        // db2 = column sums of dY: below the top layer they come out of the LayerNorm backward
+        // that produced dY (layer l+1's LN1)
+        if (l == c.L - 1) colsum(T, H, dcur, G_(b_fc2));
         done_with(l, {DP_SLOT_GELU_OUT});
         // GELU: dF = dG * gelu'(FC1_OUT), in place
         need(l, {DP_SLOT_FC1_OUT});
-        prof_begin(DP_OPC_GELU_BWD);
-        if (live)
-          check(dp::launch_gelu_bwd(c.dtype, c.gelu, (size_t)T * F, bptr(dg), ptr(l, DP_SLOT_FC1_OUT), bptr(dg), cs));
-        prof_end();
-        colsum(T, F, bptr(dg), G_(b_fc1));
+        gelu_bwd(bptr(dg), ptr(l, DP_SLOT_FC1_OUT), G_(b_fc1));
         done_with(l, {DP_SLOT_FC1_OUT});
         // FC1: dC = dF W1^T, dW1 = LN2_OUT^T dF
         need(l, {DP_SLOT_LN2_OUT});
@@ -542,11 +550,10 @@ struct Walk {
         // LN2: dM = dY + LN2'(dC), in place in dC
         need(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
         ln_bwd(bptr(dc), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), dcur, bptr(dc), G_(ln2_g),
-               G_(ln2_b));
+               G_(ln2_b), G_(b_o));   // dbo = column sums of dM
         drop(dcur_buf);
         done_with(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
         Buf dm = dc;
-        colsum(T, H, bptr(dm), G_(b_o));
         // out-projection: dO = dM Wo^T, dWo = ATTN_OUT^T dM
         need(l, {DP_SLOT_ATTN_OUT});
         Buf dob = tmp(th);
@@ -565,7 +572,7 @@ struct Walk {
         need(l, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS});
         void *dxp = l == 0 ? dx_out : bptr(da);
         ln_bwd(bptr(da), ptr(l, DP_SLOT_X_IN), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), bptr(dm), dxp, G_(ln1_g),
-               G_(ln1_b));
+               G_(ln1_b), (live && l > 0) ? dw[l - 1].b_fc2 : nullptr);   // = db2 of the layer below
         drop(dm);
         done_with(l, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS});
         if (l == 0) drop(da); else { dcur_buf = da; dcur = bptr(da); }
@@ -574,7 +581,7 @@ struct Walk {
         need(l, {DP_SLOT_RES2, DP_SLOT_LN2_STATS});
         Buf dr2 = tmp(th);
         ln_bwd(dcur, ptr(l, DP_SLOT_RES2), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), nullptr, bptr(dr2), G_(ln2_g),
-               G_(ln2_b));
+               G_(ln2_b), G_(b_fc2));   // db2 = column sums of dR2
         drop(dcur_buf);
         done_with(l, {DP_SLOT_RES2, DP_SLOT_LN2_STATS});
         // FC2
@@ -583,15 +590,10 @@ struct Walk {
         gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, bptr(dr2), W_(w_fc2), nullptr, nullptr, bptr(dg));
         gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), bptr(dr2), nullptr, nullptr,
              G_(w_fc2));
-        colsum(T, H, bptr(dr2), G_(b_fc2));
         done_with(l, {DP_SLOT_GELU_OUT});
         // GELU
         need(l, {DP_SLOT_FC1_OUT});
-        prof_begin(DP_OPC_GELU_BWD);
-        if (live)
-          check(dp::launch_gelu_bwd(c.dtype, c.gelu, (size_t)T * F, bptr(dg), ptr(l, DP_SLOT_FC1_OUT), bptr(dg), cs));
-        prof_end();
-        colsum(T, F, bptr(dg), G_(b_fc1));
+        gelu_bwd(bptr(dg), ptr(l, DP_SLOT_FC1_OUT), G_(b_fc1));
         done_with(l, {DP_SLOT_FC1_OUT});
         // FC1: dM = dR2 + dF W1^T, dW1 = LN1_OUT^T dF
         need(l, {DP_SLOT_LN1_OUT});
@@ -605,10 +607,9 @@ struct Walk {
         // LN1: dR1 = LN1'(dM), in place
         need(l, {DP_SLOT_RES1, DP_SLOT_LN1_STATS});
         ln_bwd(bptr(dm), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), nullptr, bptr(dm), G_(ln1_g),
-               G_(ln1_b));
+               G_(ln1_b), G_(b_o));   // dbo = column sums of dR1
         done_with(l, {DP_SLOT_RES1, DP_SLOT_LN1_STATS});
         Buf dr1 = dm;
-        colsum(T, H, bptr(dr1), G_(b_o));
         // out-projection
         need(l, {DP_SLOT_ATTN_OUT});
         Buf dob = tmp(th);
@@ -957,11 +958,11 @@ dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float e
 
 dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
                               const float *stats, const void *gamma, const void *dres, void *dx, void *dgamma,
-                              void *dbeta, void *ws, void *hip_stream) {
+                              void *dbeta, void *dx_colsum, void *ws, void *hip_stream) {
   if (bad_dtype(dtype) || rows < 0 || !dy || !x || !stats || !gamma || !dx || !dgamma || !dbeta || !ws)
     return fail(DP_E_INVAL, "layernorm_bwd: bad argument");
   if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
-  return op_done(dp::launch_ln_bwd(dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws,
+  return op_done(dp::launch_ln_bwd(dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dx_colsum, ws,
                                    (hipStream_t)hip_stream), "layernorm_bwd");
 }
 

@@ -61,8 +61,12 @@ def test_layernorm(dt, rows, cols):
     assert O.max_rel_err(host(dg), dg_ref) < TOL[dt] and O.max_rel_err(host(db), db_ref) < TOL[dt]
     # with the residual gradient added, written in place over dy
     dy2 = tdy.clone()
-    B.op_layernorm_bwd(dy2, tx, stats, tg, tres, dy2, dg, db, ws)
+    dsum = torch.empty_like(tg)
+    B.op_layernorm_bwd(dy2, tx, stats, tg, tres, dy2, dg, db, ws, dx_colsum=dsum)
     assert O.max_rel_err(host(dy2), dx_ref + dres) < TOL[dt]
+    assert O.max_rel_err(host(dg), dg_ref) < TOL[dt] and O.max_rel_err(host(db), db_ref) < TOL[dt]
+    # column sums of dx as stored (a bias gradient): exact sum of the kernel's own output up to fp32 ordering
+    assert O.max_rel_err(host(dsum), host(dy2).sum(axis=0)) < TOL[dt]
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
