@@ -166,8 +166,18 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
   const int cx = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cx;
   float s = 0.f;
-  if (col < width)
-    for (int b = g; b < nb; b += 16) s += part[(size_t)b * width + col];
+  if (col < width) {
+    // batches of 8 independent loads: the kernel is latency-bound, not bandwidth-bound
+    int b = g;
+    for (; b + 7 * 16 < nb; b += 8 * 16) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(b + u * 16) * width + col];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; b < nb; b += 16) s += part[(size_t)b * width + col];
+  }
   red[g][cx] = s;
   __syncthreads();
   if (g == 0 && col < width) {

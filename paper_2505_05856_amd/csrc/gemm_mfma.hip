@@ -204,14 +204,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
     const bf16 *pa = TN ? A + m0 : A + (long)m0 * lda;   // uniform: advanced one k-step per issue
     const bf16 *pb = TN ? B + n0 : B + (long)n0 * ldb;
     const long step_a = TN ? (long)BK * lda : BK, step_b = TN ? (long)BK * ldb : BK;
-    auto issue = [&](u32x4 (&xa)[NA], u32x4 (&xb)[NB]) {
+    auto issue_a = [&](u32x4 (&xa)[NA]) {
 #pragma unroll
       for (int i = 0; i < NA; ++i) gload16(xa[i], offa[i], pa);
+      pa += step_a;
+    };
+    auto issue_b = [&](u32x4 (&xb)[NB]) {
 #pragma unroll
       for (int i = 0; i < NB; ++i) gload16(xb[i], offb[i], pb);
-      pa += step_a;
       pb += step_b;
     };
+    auto issue = [&](u32x4 (&xa)[NA], u32x4 (&xb)[NB]) { issue_a(xa); issue_b(xb); };
     auto landed = [&](u32x4 (&xa)[NA], u32x4 (&xb)[NB]) {
 #pragma unroll
       for (int i = 0; i < NA; ++i) touch(xa[i]);
@@ -228,9 +231,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
     // k-step kt: request tile kt+2 into (la, lb), multiply stage `cur`, then move tile kt+1
     // (requested one step ago, in (sa, sb)) into the other stage
     auto step = [&](int kt, int cur, u32x4 (&la)[NA], u32x4 (&lb)[NB], u32x4 (&sa)[NA], u32x4 (&sb)[NB]) {
+      // The requests for tile kt+2 go out in two bursts, A before and B after the multiply:
+      // a wave sits in the issue stage until the texture path has taken its requests
+      // (16 clocks per 1 KB request, every wave of the CU queueing at once), so a burst
+      // half as long at the top of the step leaves the MFMA pipes idle half as long.
       const bool more = kt + 2 < nk;
-      if (more) issue(la, lb);
+      if (more) issue_a(la);
       compute(cur);
+      if (more) issue_b(lb);
       if (kt + 1 < nk) {
         if (more) wait_vmcnt<NA + NB>(); else wait_vmcnt<0>();
         landed(sa, sb);

@@ -97,7 +97,8 @@ def test_colsum(dt, rows, cols):
 
 
 GEMM_SHAPES = [(1, 8, 8), (5, 16, 24), (64, 64, 64), (100, 72, 40), (128, 384, 128), (257, 136, 520),
-               (300, 1600, 96), (512, 256, 1024), (1000, 520, 1032), (264, 136, 4104), (2048, 1024, 512)]
+               (300, 1600, 96), (512, 256, 1024), (1000, 520, 1032), (264, 136, 4104), (2048, 1024, 512),
+               (4096, 4096, 192), (3900, 4200, 128)]   # the last two take the 256x256-tile path
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
