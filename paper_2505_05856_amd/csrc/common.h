@@ -56,4 +56,27 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// ---- GELU ----------------------------------------------------------------------------
+// One definition for every kernel that applies it (the standalone kernels and the GEMM
+// epilogue must agree to the bit, so that a recomputed GELU_OUT equals the fused one);
+// contraction is off so that no context-dependent fma formation can change a result.
+__device__ __forceinline__ float gelu_f(float x, int kind) {
+#pragma clang fp contract(off)
+  if (kind == 0) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+  const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+  return 0.5f * x * (1.0f + tanhf(u));
+}
+__device__ __forceinline__ float gelu_df(float x, int kind) {
+#pragma clang fp contract(off)
+  if (kind == 0) {
+    const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
+    const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
+    return cdf + x * pdf;
+  }
+  const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+  const float t = tanhf(u);
+  const float du = 0.79788456080286536f * (1.0f + 0.134145f * x * x);
+  return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * du;
+}
+
 }  // namespace dp

@@ -217,23 +217,6 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, fl
 }
 
 // ------------------------------------------------------------------ GELU
-__device__ __forceinline__ float gelu_f(float x, int kind) {
-  if (kind == 0) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
-  const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
-  return 0.5f * x * (1.0f + tanhf(u));
-}
-__device__ __forceinline__ float gelu_df(float x, int kind) {
-  if (kind == 0) {
-    const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
-    const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
-    return cdf + x * pdf;
-  }
-  const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
-  const float t = tanhf(u);
-  const float du = 0.79788456080286536f * (1.0f + 0.134145f * x * x);
-  return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * du;
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, size_t n8,
                                                        int kind) {

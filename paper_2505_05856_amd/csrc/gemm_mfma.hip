@@ -110,7 +110,8 @@ __device__ __forceinline__ bf16x8 load_frag(const bf16 *lds, int row0, int k16, 
 template <int BM, int BN, bool TN, int BK, int WPE, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void gemm_mfma_kernel(const bf16 *__restrict__ A, const bf16 *__restrict__ B,
                                                            const bf16 *__restrict__ bias,
-                                                           const bf16 *__restrict__ res, bf16 *__restrict__ C, int M,
+                                                           const bf16 *__restrict__ res, bf16 *__restrict__ C,
+                                                           bf16 *__restrict__ C2, int gelu_kind, int M,
                                                            int N, int K, int tiles_m, int tiles_n) {
   constexpr int NTHR = 64 * WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
@@ -289,7 +290,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
         if (row >= M) continue;
         float v = acc[i][j][e] + bv;
         if (res != nullptr) v += (float)res[(long)row * N + col];
-        C[(long)row * N + col] = (bf16)v;
+        const bf16 stored = (bf16)v;
+        C[(long)row * N + col] = stored;
+        // fused activation: computed from the value as stored, so that a later standalone
+        // GELU of C gives the same bits
+        if (C2 != nullptr) C2[(long)row * N + col] = (bf16)gelu_f((float)stored, gelu_kind);
       }
     }
   }
@@ -308,7 +313,8 @@ hipError_t launch_cfg(const GemmArgs &a, hipStream_t s) {
   }
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WGM * WGN), smem, s, (const bf16 *)a.A, (const bf16 *)a.B,
-                     (const bf16 *)a.bias, (const bf16 *)a.res, (bf16 *)a.C, a.M, a.N, a.K, tiles_m, tiles_n);
+                     (const bf16 *)a.bias, (const bf16 *)a.res, (bf16 *)a.C, (bf16 *)a.C2, a.gelu_kind, a.M, a.N, a.K,
+                     tiles_m, tiles_n);
   return hipGetLastError();
 }
 

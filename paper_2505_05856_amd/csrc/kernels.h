@@ -37,6 +37,9 @@ struct GemmArgs {
   const void *bias;    // [N] or null
   const void *res;     // [M,N] or null, added after bias
   void *C;             // [M,N]
+  // optional second output (MFMA path only): C2[m,n] = gelu(C[m,n] as stored), gelu_kind 0 erf / 1 tanh
+  void *C2 = nullptr;
+  int gelu_kind = 0;
 };
 
 // ---- shape support (host checks; the launchers assume they passed) ----------

@@ -230,6 +230,8 @@ struct Walk {
   int next_event = 0;
   hipError_t herr = hipSuccess;
   bool in_backward = false;
+  // kernel-selection switches; the dry walk must be given the same values as the live one
+  bool mfma_enabled = true, fuse_gelu_enabled = true;
   // report
   uint64_t d2h_bytes = 0, h2d_bytes = 0, kept_bytes = 0;
   double replay_flops = 0, step_flops = 0;
@@ -317,11 +319,19 @@ struct Walk {
   }
 
   // ---- kernels ----------------------------------------------------------------
+  // true if a GEMM of this shape runs on the matrix-core kernel (which can also emit GELU(C))
+  bool gemm_on_mfma(int mode, long M, long N, long K) const {
+    if (c.dtype != DP_BF16 || !mfma_enabled) return false;
+    dp::GemmArgs a{mode, (int)M, (int)N, (int)K, (const void *)16, (const void *)16, nullptr, nullptr, nullptr};
+    return dp::gemm_mfma_supported(a);
+  }
   void gemm(int cls, int mode, long M, long N, long K, const void *A, const void *B, const void *bias,
-            const void *res, void *C) {
+            const void *res, void *C, void *gelu_out = nullptr) {
     prof_begin(cls);
     if (live) {
       dp::GemmArgs a{mode, (int)M, (int)N, (int)K, A, B, bias, res, C};
+      a.C2 = gelu_out;
+      a.gelu_kind = c.gelu;
       if (c.dtype == DP_BF16 && st->use_mfma && dp::gemm_mfma_supported(a)) check(dp::launch_gemm_mfma(a, cs));
       else check(dp::launch_gemm_simple(c.dtype, a, cs));
     }
@@ -389,9 +399,9 @@ struct Walk {
         gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? w->wt_o : nullptr, live ? w->b_o : nullptr, in(1),
              out0);
         break;
-      case OP_FC1:
+      case OP_FC1:   // out1: GELU_OUT when the activation rides the epilogue (forward only)
         gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, F, H, in(0), live ? w->wt_fc1 : nullptr, live ? w->b_fc1 : nullptr,
-             nullptr, out0);
+             nullptr, out0, out1);
         break;
       case OP_GELU:
         prof_begin(DP_OPC_GELU_FWD);
@@ -491,14 +501,22 @@ struct Walk {
         for (int k = 0; k < d.n_in; ++k) if (d.in[k].dl == 0) last[d.in[k].slot] = i;
         for (int k = 0; k < d.n_out; ++k) if (d.out[k].dl == 0) last[d.out[k].slot] = i;
       }
+      // In forward the GELU rides the FC1 epilogue when FC1 runs on the matrix cores (both
+      // tensors are written by one kernel; the GELU op then only does its bookkeeping).
+      const bool fuse_gelu = fuse_gelu_enabled && gemm_on_mfma(dp::kGemmNT, c.T, c.F, c.H);
       for (int i = 0; i < N_OPS; ++i) {
         const OpDef &d = ops()[i];
         void *outp[2] = {nullptr, nullptr};
-        for (int o = 0; o < d.n_out; ++o) {
+        const bool produced_already = fuse_gelu && d.op == OP_GELU;
+        for (int o = 0; o < d.n_out && !produced_already; ++o) {
           slot_alloc(l + d.out[o].dl, d.out[o].slot);
           outp[o] = ptr(l + d.out[o].dl, d.out[o].slot);
         }
-        run_op(l, d, outp[0], outp[1]);
+        if (fuse_gelu && d.op == OP_FC1) {
+          slot_alloc(l, DP_SLOT_GELU_OUT);
+          outp[1] = ptr(l, DP_SLOT_GELU_OUT);
+        }
+        if (!produced_already) run_op(l, d, outp[0], outp[1]);
         step_flops += op_flops(c, d.op);
         for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) {
           if (last[s] != i || S(l, s).where != RESIDENT) continue;
@@ -708,8 +726,13 @@ void fill_report(const Cfg &c, const Walk &w, dp_plan_report *r) {
   r->n_swapped_slots = w.n_swapped;
 }
 
+bool env_mfma_enabled() {
+  const char *env = getenv("DPSTAGE_KERNELS");
+  return !(env != nullptr && strcmp(env, "simple") == 0);
+}
+
 dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
-                   dp_plan_report *rep) {
+                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled) {
   dp_plan_report local;
   dp_plan_report *r = rep ? rep : &local;
   memset(r, 0, sizeof *r);
@@ -718,6 +741,8 @@ dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t 
   if (s != DP_OK) return s;
   if (inflight < 1) return fail(DP_E_INVAL, "inflight must be >= 1");
   Walk w(c, plan, false, nullptr);
+  w.mfma_enabled = mfma_enabled;
+  w.fuse_gelu_enabled = fuse_gelu_enabled;
   w.forward();
   w.backward();
   fill_report(c, w, r);
@@ -751,7 +776,7 @@ dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size
   Cfg c;
   dp_status s = parse_cfg(cfg, &c);
   if (s != DP_OK) return s;
-  return validate(c, plan, plan_len, budget_bytes, inflight, report);
+  return validate(c, plan, plan_len, budget_bytes, inflight, report, env_mfma_enabled(), true);
 }
 
 dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *layers, uint64_t arena_bytes_hint,
@@ -770,8 +795,7 @@ dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *laye
   dp_stage *st = new dp_stage();
   st->c = c;
   st->pub = *cfg;
-  const char *env = getenv("DPSTAGE_KERNELS");
-  st->use_mfma = !(env != nullptr && strcmp(env, "simple") == 0);
+  st->use_mfma = env_mfma_enabled();
   uint64_t mats;
   const uint64_t per_layer = weight_elems_per_layer(c, &mats);
   // every tensor starts on a 256-byte boundary
@@ -834,7 +858,8 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
       if (p[i] == nullptr) return fail(DP_E_INVAL, "gradient pointer %d of layer %d is null", i, l);
   }
   dp_plan_report rep;
-  dp_status s = validate(c, plan, plan_len, budget_bytes, 1, &rep);
+  const bool fuse_gelu = (st->debug & 4u) == 0;
+  dp_status s = validate(c, plan, plan_len, budget_bytes, 1, &rep, st->use_mfma, fuse_gelu);
   if (s != DP_OK) return s;
   // memory the walk needs (a resize waits for the device first)
   if (rep.arena_peak_bytes > st->arena_bytes) {
@@ -859,6 +884,8 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   }
   hipStream_t cs = (hipStream_t)hip_stream;
   Walk w(c, plan, true, st);
+  w.mfma_enabled = st->use_mfma;
+  w.fuse_gelu_enabled = fuse_gelu;
   w.cs = cs;
   const bool serial = (st->debug & 1u) != 0;
   w.d2h = serial ? cs : st->d2h;
