@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--plan", default=None, help="plan name (default: the config's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-op-times", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="also time the plan with its SWAP slots kept (compute only) and its copies alone")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 4 times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -134,6 +136,44 @@ def main():
                 "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, plan_name))}
     stats = run.step(plan, budget, want_stats=True)
 
+    overlap = None
+    if args.overlap and stats["d2h_bytes"] > 0:
+        # compute only: the same plan with every SWAP turned into KEEP
+        import numpy as np
+        kept = np.where(plan == syn.SWAP, syn.KEEP, plan).astype(np.uint8)
+        for _ in range(2):
+            run.step(kept, 0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run.step(kept, 0)
+        torch.cuda.synchronize()
+        t_comp = (time.perf_counter() - t0) * 1e3 / args.steps
+        # copies only: the plan's swap bytes out, then back in, through pinned host memory in slot-sized pieces
+        nslots = max(1, int((plan == syn.SWAP).sum()))
+        piece = stats["d2h_bytes"] // nslots
+        dev = torch.empty(piece, dtype=torch.uint8, device="cuda:0")
+        host = torch.empty(piece * nslots, dtype=torch.uint8).pin_memory()
+        def copies():
+            for i in range(nslots):
+                host[i * piece:(i + 1) * piece].copy_(dev, non_blocking=True)
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            for i in range(nslots):
+                dev.copy_(host[i * piece:(i + 1) * piece], non_blocking=True)
+            torch.cuda.synchronize()
+            return a
+        copies()
+        t0 = time.perf_counter(); mid = copies(); t1 = time.perf_counter()
+        t_out, t_in = (mid - t0) * 1e3, (t1 - mid) * 1e3
+        t_copy = t_out + t_in
+        ov = (t_comp + t_copy - ms) / min(t_comp, t_copy)
+        overlap = {"step_ms": round(ms, 3), "compute_only_ms": round(t_comp, 3), "copy_only_ms": round(t_copy, 3),
+                   "d2h_GBps": round(stats["d2h_bytes"] / t_out / 1e6, 2), "h2d_GBps": round(stats["h2d_bytes"] / t_in / 1e6, 2),
+                   "overlap_frac": round(max(0.0, min(1.0, ov)), 4),
+                   "definition": "(compute_only + copy_only - step) / min(compute_only, copy_only), clipped to [0,1]"}
+        del dev, host
+
     out = {
         "metric": "stage fwd+bwd samples/sec + MFMA util % at fixed memory budget",
         "value": round(cfg.micro_batch / (ms * 1e-3), 3), "unit": "samples/s",
@@ -152,6 +192,8 @@ def main():
         "replayed_ops": stats["n_replayed_ops"], "kernel_launches": stats["n_kernel_launches"],
         "op_ms": op_ms, "roofline": roof,
     }
+    if overlap is not None:
+        out["swap_overlap"] = overlap
     run.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, weights, x, dy)

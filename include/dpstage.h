@@ -142,7 +142,13 @@ size_t dp_plan_len(const dp_stage_config *cfg);
  * DP_E_PLAN (X_IN of layer 0 marked RECOMPUTE: it has no producer in the stage;
  * report->first_bad_* name it), DP_E_UNSUPPORTED (shape), DP_E_BUDGET.
  * Plan bytes of slots without storage (see the slot list) are ignored; SWAP on
- * X_IN of layer 0 is treated as KEEP because that buffer is the caller's. */
+ * X_IN of layer 0 is treated as KEEP because that buffer is the caller's.
+ * Arena policy for swapped-out blocks: with budget_bytes == 0 a block returns to
+ * the allocator as soon as its copy-out is queued (smallest peak; its next user
+ * waits for the copy).  With a budget the walk first tries to hold such blocks
+ * back until forward is over, then for two layers, then not at all, and takes
+ * the first policy whose peak fits: forward compute then never waits for the
+ * host link when memory allows.  dp_stage_step makes the same choice. */
 dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len,
                            uint64_t budget_bytes, uint32_t inflight, dp_plan_report *report);
 

@@ -123,12 +123,37 @@ struct Arena {
   static constexpr uint64_t kAlign = 256;
   struct Free { uint64_t off, size; };
   struct Pending { uint64_t off, size; int event; };
+  struct Held { uint64_t off, size; int event; long ready_at; };
   std::vector<Free> free_;   // sorted by offset, coalesced; last entry is the open tail
   std::vector<Pending> pending_;
+  // Blocks released by a swap-out are held back for a while before they return to the
+  // free list: handing one out at once would make its next user wait for the whole
+  // device-to-host copy, which serialises forward compute behind the copy engine.
+  std::vector<Held> held_;
+  long now = 0;         // advanced by the walk, one tick per kernel launch site
   uint64_t high_water = 0, live = 0, live_peak = 0;
 
   Arena() { free_.push_back({0, UINT64_MAX}); }
   static uint64_t round(uint64_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+
+  void tick() {
+    ++now;
+    for (size_t i = 0; i < held_.size();) {
+      if (held_[i].ready_at <= now) {
+        insert_free(held_[i].off, held_[i].size);
+        pending_.push_back({held_[i].off, held_[i].size, held_[i].event});
+        held_.erase(held_.begin() + (long)i);
+      } else ++i;
+    }
+  }
+
+  void release_all_held() {
+    for (const Held &h : held_) {
+      insert_free(h.off, h.size);
+      pending_.push_back({h.off, h.size, h.event});
+    }
+    held_.clear();
+  }
 
   uint64_t alloc(uint64_t bytes, std::vector<int> *wait_events) {
     const uint64_t n = round(std::max<uint64_t>(bytes, 1));
@@ -151,10 +176,17 @@ struct Arena {
     return UINT64_MAX;  // unreachable: the tail is unbounded
   }
 
-  void release(uint64_t off, uint64_t bytes, int pending_event = -1) {
+  // hold_ticks > 0: the block (whose copy-out `pending_event` marks) rejoins the free list
+  // only that many ticks from now
+  void release(uint64_t off, uint64_t bytes, int pending_event = -1, long hold_ticks = 0) {
     const uint64_t n = round(std::max<uint64_t>(bytes, 1));
     live -= n;
+    if (pending_event >= 0 && hold_ticks > 0) { held_.push_back({off, n, pending_event, now + hold_ticks}); return; }
     if (pending_event >= 0) pending_.push_back({off, n, pending_event});
+    insert_free(off, n);
+  }
+
+  void insert_free(uint64_t off, uint64_t n) {
     size_t i = 0;
     while (i < free_.size() && free_[i].off < off) ++i;
     free_.insert(free_.begin() + (long)i, {off, n});
@@ -207,6 +239,7 @@ struct SlotState {
   uint64_t off = 0;        // arena offset when RESIDENT
   uint64_t host_off = 0;   // pinned-pool offset when ON_HOST (kept after swap-in)
   int ready_event = -1;    // swap-in completion the compute stream has not waited for yet
+  int out_event = -1;      // swap-out completion: the host copy is whole only after it
   bool consumed = false;   // its last backward consumer has run
   bool ever_produced = false;
 };
@@ -232,6 +265,7 @@ struct Walk {
   bool in_backward = false;
   // kernel-selection switches; the dry walk must be given the same values as the live one
   bool mfma_enabled = true, fuse_gelu_enabled = true;
+  long swap_hold_ticks = 0;   // how long a swapped-out block stays out of the free list (launch sites)
   // report
   uint64_t d2h_bytes = 0, h2d_bytes = 0, kept_bytes = 0;
   double replay_flops = 0, step_flops = 0;
@@ -282,7 +316,7 @@ struct Walk {
       if (pending_event >= 0) wait(cs, pending_event);
       check(dp::launch_fill_u32(base() + off, Arena::round(bytes) / 4, 0xFFFFFFFFu, cs));
     }
-    arena.release(off, bytes, pending_event);
+    arena.release(off, bytes, pending_event, pending_event >= 0 ? swap_hold_ticks : 0);
   }
   Buf tmp(uint64_t bytes) { Buf b; b.bytes = bytes; b.off = arena_alloc(bytes); return b; }
   void drop(Buf &b) { if (b.off != UINT64_MAX) arena_release(b.off, b.bytes); b.off = UINT64_MAX; }
@@ -305,6 +339,7 @@ struct Walk {
   // ---- profiling brackets ---------------------------------------------------
   void prof_begin(int cls) {
     ++n_launch;
+    arena.tick();
     if (!live || !st->profiling) return;
     if (st->prof_used + 2 > st->prof_events.size()) {
       for (int i = 0; i < 2; ++i) { hipEvent_t e; check(hipEventCreate(&e)); st->prof_events.push_back(e); }
@@ -433,6 +468,7 @@ struct Walk {
     d2h_bytes += bytes;
     ++n_swapped;
     arena_release(s.off, bytes, done);
+    s.out_event = done;
     s.where = ON_HOST;
   }
   void swap_in(int l, int slot) {
@@ -445,6 +481,7 @@ struct Walk {
       const int region_free = new_event();
       record(region_free, cs);
       wait(h2d, region_free);
+      wait(h2d, s.out_event);   // the copy-out of this slot must have landed in the host pool
       check(hipMemcpyAsync(base() + s.off, (char *)st->host_pool + s.host_off, bytes, hipMemcpyHostToDevice, h2d));
       record(done, h2d);
     }
@@ -532,6 +569,7 @@ struct Walk {
   // ---- backward ------------------------------------------------------------------
   void backward() {
     in_backward = true;
+    arena.release_all_held();   // forward is over: nothing is gained by holding blocks back any longer
     const long T = c.T, H = c.H, F = c.F;
     const size_t th = (size_t)T * H * c.esz, tf = (size_t)T * F * c.esz;
     const void *dcur = dy;   // gradient of the current layer's output
@@ -731,8 +769,14 @@ bool env_mfma_enabled() {
   return !(env != nullptr && strcmp(env, "simple") == 0);
 }
 
+// How long (in launch sites) a swapped-out block stays out of the free list, tried in
+// this order until the plan fits the budget: for the rest of forward (forward compute never
+// waits for a copy-out; forward memory is not reduced, backward memory is), two layers,
+// not at all (least memory; the next user of the block waits for the copy).
+const long kSwapHolds[3] = {1L << 40, 16, 0};
+
 dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
-                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled) {
+                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled, long *hold_out = nullptr) {
   dp_plan_report local;
   dp_plan_report *r = rep ? rep : &local;
   memset(r, 0, sizeof *r);
@@ -740,16 +784,22 @@ dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t 
   dp_status s = check_plan(c, plan, plan_len, r);
   if (s != DP_OK) return s;
   if (inflight < 1) return fail(DP_E_INVAL, "inflight must be >= 1");
-  Walk w(c, plan, false, nullptr);
-  w.mfma_enabled = mfma_enabled;
-  w.fuse_gelu_enabled = fuse_gelu_enabled;
-  w.forward();
-  w.backward();
-  fill_report(c, w, r);
-  if (budget != 0 && (long double)inflight * (long double)r->peak_bytes > (long double)budget)
-    return fail(DP_E_BUDGET, "plan needs %u x %llu bytes, budget is %llu", inflight,
-                (unsigned long long)r->peak_bytes, (unsigned long long)budget);
-  return DP_OK;
+  for (int attempt = 0; attempt < 3; ++attempt) {
+    Walk w(c, plan, false, nullptr);
+    w.mfma_enabled = mfma_enabled;
+    w.fuse_gelu_enabled = fuse_gelu_enabled;
+    w.swap_hold_ticks = kSwapHolds[attempt];
+    w.forward();
+    w.backward();
+    fill_report(c, w, r);
+    if (hold_out) *hold_out = kSwapHolds[attempt];
+    const bool fits = budget == 0 || (long double)inflight * (long double)r->peak_bytes <= (long double)budget;
+    // without a budget the caller wants the plan's memory saving: take the tightest policy
+    if (budget == 0 && attempt < 2 && w.n_swapped > 0) continue;
+    if (fits) return DP_OK;
+  }
+  return fail(DP_E_BUDGET, "plan needs %u x %llu bytes, budget is %llu", inflight,
+              (unsigned long long)r->peak_bytes, (unsigned long long)budget);
 }
 
 #define HIP_TRY(expr, code)                                                                     \
@@ -859,7 +909,8 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   }
   dp_plan_report rep;
   const bool fuse_gelu = (st->debug & 4u) == 0;
-  dp_status s = validate(c, plan, plan_len, budget_bytes, 1, &rep, st->use_mfma, fuse_gelu);
+  long swap_hold = 0;
+  dp_status s = validate(c, plan, plan_len, budget_bytes, 1, &rep, st->use_mfma, fuse_gelu, &swap_hold);
   if (s != DP_OK) return s;
   // memory the walk needs (a resize waits for the device first)
   if (rep.arena_peak_bytes > st->arena_bytes) {
@@ -886,6 +937,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   Walk w(c, plan, true, st);
   w.mfma_enabled = st->use_mfma;
   w.fuse_gelu_enabled = fuse_gelu;
+  w.swap_hold_ticks = swap_hold;
   w.cs = cs;
   const bool serial = (st->debug & 1u) != 0;
   w.d2h = serial ? cs : st->d2h;
