@@ -138,7 +138,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
   const int gsz = min(tiles_m - first_m, GM);
   const int tm = first_m + (pid % (GM * tiles_n)) % gsz;
   const int tn = (pid % (GM * tiles_n)) / gsz;
-  const int m0 = tm * BM, n0 = tn * BN;
+  // Ragged last tiles are shifted back inside the matrix (they overlap their neighbour and
+  // store the same values twice) whenever the matrix is at least one tile tall/wide: then no
+  // load of the fast path needs a guard.  Smaller matrices keep their origin and take the
+  // guarded path below.
+  const bool interior = M >= BM && N >= BN;
+  const int m0 = interior ? min(tm * BM, M - BM) : tm * BM, n0 = interior ? min(tn * BN, N - BN) : tn * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
@@ -184,35 +189,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
   };
   constexpr int NA = BM * BK / 8 / NTHR, NB = BN * BK / 8 / NTHR;
 
-  if (K % BK == 0) {
+  if (K % BK == 0 && interior) {
     // ---- two-deep software pipeline with explicitly counted loads -----------------
-    // Rows beyond M / N are clamped onto the last valid row instead of zero-filled: they
-    // only feed accumulators whose results are never stored.
     u32x4 ra0[NA], rb0[NB], ra1[NA], rb1[NB];
-    unsigned offa[NA], offb[NB];
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-      const int c = tid + i * NTHR;
-      if (TN) offa[i] = (unsigned)(((c / (BM / 8)) * lda + min((c % (BM / 8)) * 8, M - 8 - m0)) * 2);
-      else offa[i] = (unsigned)((min(c / (BK / 8), M - 1 - m0) * lda + (c % (BK / 8)) * 8) * 2);
-    }
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int c = tid + i * NTHR;
-      if (TN) offb[i] = (unsigned)(((c / (BN / 8)) * ldb + min((c % (BN / 8)) * 8, N - 8 - n0)) * 2);
-      else offb[i] = (unsigned)((min(c / (BK / 8), N - 1 - n0) * ldb + (c % (BK / 8)) * 8) * 2);
-    }
+    // A thread's NA (NB) chunks of a tile sit a fixed, uniform distance apart, so one VGPR
+    // byte offset per operand plus uniform (SGPR) base pointers address all of them.
+    constexpr int RA = TN ? NTHR / (BM / 8) : NTHR / (BK / 8);   // rows between a thread's consecutive chunks
+    constexpr int RB = TN ? NTHR / (BN / 8) : NTHR / (BK / 8);
+    const unsigned offa = TN ? (unsigned)(((tid / (BM / 8)) * lda + (tid % (BM / 8)) * 8) * 2)
+                             : (unsigned)(((tid / (BK / 8)) * lda + (tid % (BK / 8)) * 8) * 2);
+    const unsigned offb = TN ? (unsigned)(((tid / (BN / 8)) * ldb + (tid % (BN / 8)) * 8) * 2)
+                             : (unsigned)(((tid / (BK / 8)) * ldb + (tid % (BK / 8)) * 8) * 2);
     const bf16 *pa = TN ? A + m0 : A + (long)m0 * lda;   // uniform: advanced one k-step per issue
     const bf16 *pb = TN ? B + n0 : B + (long)n0 * ldb;
     const long step_a = TN ? (long)BK * lda : BK, step_b = TN ? (long)BK * ldb : BK;
+    const long gap_a = (long)RA * lda, gap_b = (long)RB * ldb;
     auto issue_a = [&](u32x4 (&xa)[NA]) {
 #pragma unroll
-      for (int i = 0; i < NA; ++i) gload16(xa[i], offa[i], pa);
+      for (int i = 0; i < NA; ++i) gload16(xa[i], offa, pa + i * gap_a);
       pa += step_a;
     };
     auto issue_b = [&](u32x4 (&xb)[NB]) {
 #pragma unroll
-      for (int i = 0; i < NB; ++i) gload16(xb[i], offb[i], pb);
+      for (int i = 0; i < NB; ++i) gload16(xb[i], offb, pb + i * gap_b);
       pb += step_b;
     };
     auto issue = [&](u32x4 (&xa)[NA], u32x4 (&xb)[NB]) { issue_a(xa); issue_b(xb); };
