@@ -172,7 +172,9 @@ dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *laye
  * is returned before anything is enqueued.  Work is enqueued on `hip_stream`
  * (a hipStream_t; NULL = the default stream) and on the library's copy streams,
  * which are joined back into hip_stream before return; the call does not wait
- * for the device unless `stats` is non-NULL.  DP_E_HIP after a partial enqueue
+ * for this step unless `stats` is non-NULL, but it first waits (on the host) for
+ * the step issued two calls earlier on the same handle, so that at most two
+ * steps are in flight.  DP_E_HIP after a partial enqueue
  * leaves the outputs undefined.  One step at a time per handle.
  * The results are bit-identical for every plan. */
 dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const uint8_t *plan,

@@ -229,6 +229,11 @@ struct dp_stage {
   size_t prof_used = 0;
   uint32_t debug = 0;
   bool use_mfma = true;
+  // The host may run at most kStepsInFlight steps ahead of the device: deeper command
+  // backlogs made the runtime's copy path several times slower on plans that swap.
+  static constexpr int kStepsInFlight = 2;
+  hipEvent_t step_end[kStepsInFlight] = {nullptr, nullptr};
+  uint64_t steps_issued = 0;
 };
 
 namespace {
@@ -934,6 +939,9 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     st->host_bytes = rep.host_pinned_bytes;
   }
   hipStream_t cs = (hipStream_t)hip_stream;
+  hipEvent_t &step_end = st->step_end[st->steps_issued % dp_stage::kStepsInFlight];
+  if (step_end == nullptr) HIP_TRY(hipEventCreateWithFlags(&step_end, hipEventDisableTiming), DP_E_HIP);
+  else HIP_TRY(hipEventSynchronize(step_end), DP_E_HIP);   // the step issued kStepsInFlight calls ago
   Walk w(c, plan, true, st);
   w.mfma_enabled = st->use_mfma;
   w.fuse_gelu_enabled = fuse_gelu;
@@ -957,6 +965,8 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     const int j2 = w.new_event(); w.record(j2, st->h2d); w.wait(cs, j2);
   }
   if (w.herr != hipSuccess) return fail(DP_E_HIP, "stage_step: %s", hipGetErrorString(w.herr));
+  HIP_TRY(hipEventRecord(step_end, cs), DP_E_HIP);
+  ++st->steps_issued;
   if (w.arena.high_water != rep.arena_peak_bytes)
     return fail(DP_E_HIP, "internal: live walk peak %llu differs from the validated %llu",
                 (unsigned long long)w.arena.high_water, (unsigned long long)rep.arena_peak_bytes);
@@ -1009,6 +1019,7 @@ void dp_stage_destroy(dp_stage *st) {
   (void)hipDeviceSynchronize();
   for (hipEvent_t e : st->events) (void)hipEventDestroy(e);
   for (hipEvent_t e : st->prof_events) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->step_end) if (e) (void)hipEventDestroy(e);
   if (st->d2h) (void)hipStreamDestroy(st->d2h);
   if (st->h2d) (void)hipStreamDestroy(st->h2d);
   if (st->arena) (void)hipFree(st->arena);
