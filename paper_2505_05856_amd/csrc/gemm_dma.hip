@@ -1,21 +1,28 @@
-// bf16 NT GEMM on the gfx950 matrix cores with operand tiles brought into LDS by the
+// bf16 GEMM on the gfx950 matrix cores with operand tiles brought into LDS by the
 // load unit itself (global_load_lds_dwordx4): no staging registers, no LDS store
 // instructions, and the requests can be spread between the MFMAs of a k-step.
 //
-//   C[M,N] = A[M,K] * B[N,K]^T (+ bias, + residual), fp32 accumulation, bf16 out.
+//   NT: C[M,N] = A[M,K] * B[N,K]^T (+ bias, + residual, optional second output gelu(C))
+//   TN: C[M,N] = A[K,M]^T * B[K,N]
+// fp32 accumulation, bf16 out.
 //
 // Preconditions (checked by gemm_dma_supported): K % 64 == 0, M >= BM, N >= BN for the
-// tile chosen, 16-byte aligned operands.  Ragged edge tiles are shifted back inside the
-// matrix, so no load is ever guarded.  No split-K: the summation order is fixed.
+// tile chosen, 16-byte aligned operands and rows.  Ragged edge tiles are shifted back
+// inside the matrix, so no load is ever guarded.  No split-K: the summation order is fixed.
 //
-// LDS layout.  A stage holds the A tile [BM rows][64 k] and the B tile [BN rows][64 k]
-// as 128-byte rows without padding (the load unit writes the 64 lanes of a request to
-// 1 KB of consecutive LDS, i.e. 8 whole rows).  Bank conflicts of the 16-byte fragment
-// reads are avoided by a swizzle instead: the 16-byte chunk c of row r sits at chunk
-// position c ^ ((r >> 1) & 7), which spreads any 16 consecutive rows of one logical
-// chunk over all 16 chunk positions of the 256-byte bank period.  The swizzle costs
-// nothing on the way in: a lane simply fetches the global chunk that belongs at its
-// fixed LDS position.
+// LDS layout.  The load unit writes the 64 lanes of a request to 1 KB of consecutive LDS,
+// so rows cannot be padded; bank conflicts are avoided by swizzling 16-byte chunks
+// instead, which costs nothing on the way in: a lane simply fetches the global chunk
+// that belongs at its fixed LDS position.
+//   NT: a stage holds the A tile [BM rows][64 k] and the B tile [BN rows][64 k] as
+//       128-byte rows; chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), which
+//       spreads any 16 consecutive rows of one logical chunk (one 16-byte fragment read)
+//       over all 16 chunk positions of the 256-byte bank period.
+//   TN: a stage holds the tiles as loaded, [64 k rows][BM] and [64 k rows][BN]; fragments
+//       come through the transpose read (ds_read_b64_tr_b16), one of which touches four
+//       consecutive k rows x 64 bytes per half wave.  Chunk c of k row r sits at
+//       c ^ ((r & 3) << 2): the four rows land in the four 64-byte quarters of the bank
+//       period.
 #include "common.h"
 #include "kernels.h"
 
@@ -28,7 +35,10 @@ namespace dp {
 namespace {
 
 constexpr int kBK = 64;          // contraction elements per stage
-constexpr int kRowBytes = 128;   // one LDS row: 64 bf16
+constexpr int kRowBytes = 128;   // NT: one LDS row, 64 bf16
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 // One request: lane l fetches 16 bytes from uniform_base + byte_off and the unit stores
 // them at LDS byte lds_base + 16*l.  Invisible to the compiler's wait-count pass; the
@@ -48,16 +58,16 @@ __device__ __forceinline__ const char *uniform_ptr(const char *p) {
   return (const char *)(((uint64_t)hi << 32) | lo);
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT>
-__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4))) void gemm_dma_nt_kernel(
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN>
+__global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amdgpu_flat_work_group_size(64 * WGM * WGN, 64 * WGM * WGN))) void gemm_dma_kernel(
     const bf16 *__restrict__ A, const bf16 *__restrict__ B, const bf16 *__restrict__ bias,
     const bf16 *__restrict__ res, bf16 *__restrict__ C, bf16 *__restrict__ C2, int gelu_kind, int M, int N, int K,
     int tiles_m, int tiles_n) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
   constexpr int A_BYTES = BM * kRowBytes, B_BYTES = BN * kRowBytes, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int ROWB_A = BM * 2, ROWB_B = BN * 2;   // TN: bytes of one k row of a tile
   constexpr int NIA = BM / 8 / NW, NIB = BN / 8 / NW;   // requests per wave per stage
-  static_assert(NIA % 2 == 0 && NIB % 2 == 0, "a wave's row groups must start on an even group");
   constexpr int NI = NIA + NIB;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -81,38 +91,78 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
   const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
 
   // ---- request addressing -------------------------------------------------------------
-  // Request j of this wave for operand A fills LDS rows 8*(wave*NIA + j) .. +7; lane l is
-  // row l/8, chunk position l%8 of them and fetches logical chunk (l%8) ^ swizzle(row).
-  // Even and odd row groups differ in swizzle bit 2, hence two lane offsets.
-  const int r8 = lane >> 3, pc = lane & 7;
-  const unsigned ldk = (unsigned)K * 2u;   // bytes per operand row
-  unsigned voff_even = (unsigned)r8 * ldk + (unsigned)((pc ^ (r8 >> 1)) << 4);
-  unsigned voff_odd = (unsigned)r8 * ldk + (unsigned)((pc ^ (r8 >> 1) ^ 4) << 4);
+  // Request j of this wave for operand A fills LDS bytes 1024*(wave*NIA + j) .. +1023 of
+  // the A tile.  Consecutive requests alternate between two lane offsets ("even"/"odd"
+  // request groups) wherever the swizzle depends on the group's parity.
+  //   NT: a request is 8 operand rows x 128 bytes; lane l is row l/8, chunk position l%8
+  //       and fetches logical chunk (l%8) ^ ((row >> 1) & 7).
+  //   TN: a request is RPR = 1024/ROWB k rows of ROWB bytes; lane l is k row l/(64/RPR),
+  //       chunk position l%(64/RPR) and fetches logical chunk position ^ ((krow & 3) << 2).
+  const unsigned lda = (unsigned)(TN ? M : K) * 2u, ldb = (unsigned)(TN ? N : K) * 2u;   // operand row bytes
+  unsigned voa[2], vob[2];
+  if (!TN) {
+    const int r8 = lane >> 3, pc = lane & 7;
+    voa[0] = vob[0] = (unsigned)r8 * lda + (unsigned)((pc ^ (r8 >> 1)) << 4);
+    voa[1] = vob[1] = (unsigned)r8 * lda + (unsigned)((pc ^ (r8 >> 1) ^ 4) << 4);
+  } else {
+    constexpr int RPA = 1024 / ROWB_A, RPB = 1024 / ROWB_B;
+    static_assert(RPA == 2 || RPA == 4, "tile width 128 or 256");
+    static_assert(RPB == 2 || RPB == 4, "tile width 128 or 256");
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const int ka = lane / (64 / RPA), pa_ = lane % (64 / RPA);
+      voa[v] = (unsigned)ka * lda + (unsigned)((pa_ ^ (((RPA * v + ka) & 3) << 2)) << 4);
+      const int kb = lane / (64 / RPB), pb_ = lane % (64 / RPB);
+      vob[v] = (unsigned)kb * ldb + (unsigned)((pb_ ^ (((RPB * v + kb) & 3) << 2)) << 4);
+    }
+  }
   const char *pa[NIA], *pb[NIB];
 #pragma unroll
   for (int j = 0; j < NIA; ++j)
-    pa[j] = uniform_ptr((const char *)A + (size_t)(m0 + 8 * (wave * NIA + j)) * ldk);
+    pa[j] = TN ? uniform_ptr((const char *)A + (size_t)((1024 / ROWB_A) * (wave * NIA + j)) * lda + (size_t)m0 * 2)
+               : uniform_ptr((const char *)A + (size_t)(m0 + 8 * (wave * NIA + j)) * lda);
 #pragma unroll
   for (int j = 0; j < NIB; ++j)
-    pb[j] = uniform_ptr((const char *)B + (size_t)(n0 + 8 * (wave * NIB + j)) * ldk);
+    pb[j] = TN ? uniform_ptr((const char *)B + (size_t)((1024 / ROWB_B) * (wave * NIB + j)) * ldb + (size_t)n0 * 2)
+               : uniform_ptr((const char *)B + (size_t)(n0 + 8 * (wave * NIB + j)) * ldb);
   const unsigned lds_a = (unsigned)(wave * NIA) * 1024u, lds_b = (unsigned)A_BYTES + (unsigned)(wave * NIB) * 1024u;
 
   // request i (0 .. NI-1) of this wave for the stage at LDS byte `sb`
   auto request = [&](int i, unsigned sb) {
-    if (i < NIA) dma16(sb + lds_a + (unsigned)i * 1024u, (i & 1) ? voff_odd : voff_even, pa[i]);
-    else dma16(sb + lds_b + (unsigned)(i - NIA) * 1024u, ((i - NIA) & 1) ? voff_odd : voff_even, pb[i - NIA]);
+    if (i < NIA) dma16(sb + lds_a + (unsigned)i * 1024u, voa[(wave * NIA + i) & 1], pa[i]);
+    else dma16(sb + lds_b + (unsigned)(i - NIA) * 1024u, vob[(wave * NIB + i - NIA) & 1], pb[i - NIA]);
   };
-  auto advance_k = [&]() { voff_even += kBK * 2; voff_odd += kBK * 2; };
+  auto advance_k = [&]() {
+    const unsigned da = TN ? kBK * lda : kBK * 2, db = TN ? kBK * ldb : kBK * 2;
+    voa[0] += da; voa[1] += da; vob[0] += db; vob[1] += db;
+  };
 
   // ---- fragment addressing --------------------------------------------------------------
-  // lane l reads row (l%32) of a 32-row block, logical chunk 2*ks + l/32 of slice ks; with
-  // the swizzle that is byte ((row*128) + x0) ^ (ks << 5) of the tile.
+  // NT: lane l reads row (l%32) of a 32-row block, logical chunk 2*ks + l/32 of slice ks; with
+  //     the swizzle that is byte ((row*128) + x0) ^ (ks << 5) of the tile.
+  // TN: a 16-lane group fetches 4 k rows x 16 columns per transpose read; lane i of the group
+  //     supplies the address of k row i/4, columns 4*(i%4).. and receives column i of all
+  //     four rows.  Lanes 16..31 take the next 16 columns, lanes 32..63 the k rows 8 further;
+  //     a second read 4 rows on completes the 8 contraction elements of the operand.
   const unsigned x0 = (unsigned)(((lane >> 5) ^ ((lane >> 1) & 7)) << 4);
   const unsigned fa = (unsigned)(wm + (lane & 31)) * kRowBytes + x0;
   const unsigned fb = (unsigned)A_BYTES + (unsigned)(wn + (lane & 31)) * kRowBytes + x0;
-  auto frag = [&](unsigned base, int blk, int ks) {
-    // the block offset has no bits below 128, so it can stay outside the xor (an immediate of the read)
-    return *reinterpret_cast<const bf16x8 *>(lds + ((base ^ (unsigned)(ks << 5)) + (unsigned)blk * 32u * kRowBytes));
+  const int ti = lane & 15, tt = ti >> 2;                                    // TN: k row within the four
+  const unsigned tlow = (unsigned)((2 * ((lane >> 4) & 1) + ((ti & 3) >> 1)) * 16 + (ti & 1) * 8);
+  const unsigned trow = (unsigned)(8 * (lane >> 5) + tt);
+  auto frag = [&](unsigned base, int blk, int ks, bool is_b) -> bf16x8 {
+    if (!TN) {
+      // the block offset has no bits below 128, so it can stay outside the xor (an immediate of the read)
+      return *reinterpret_cast<const bf16x8 *>(lds + (((base + (is_b ? fb : fa)) ^ (unsigned)(ks << 5)) + (unsigned)blk * 32u * kRowBytes));
+    }
+    const unsigned rowb = is_b ? ROWB_B : ROWB_A;
+    const unsigned cw = (unsigned)((is_b ? wn : wm) / 8 + blk * 4);        // first chunk of the 32-column block
+    const unsigned off = base + (is_b ? (unsigned)A_BYTES : 0u) + trow * rowb + ((cw ^ (unsigned)(tt << 2)) << 4) + tlow +
+                         (unsigned)ks * 16u * rowb;
+    union { s16x4 h[2]; bf16x8 v; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + off));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + off + 4u * rowb));
+    return u.v;
   };
 
   f32x16 acc[FM][FN];
@@ -145,29 +195,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
     const unsigned sb = (unsigned)cur * STAGE_BYTES, nb = (unsigned)nxt * STAGE_BYTES;
     bf16x8 a[2][FM], b[2][FN];
 #pragma unroll
-    for (int i = 0; i < FM; ++i) a[0][i] = frag(sb + fa, i, 0);
+    for (int i = 0; i < FM; ++i) a[0][i] = frag(sb, i, 0, false);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) b[0][j] = frag(sb + fb, j, 0);
+    for (int j = 0; j < FN; ++j) b[0][j] = frag(sb, j, 0, true);
     constexpr int KS = kBK / 16;
     constexpr int TOTAL = KS * FM * FN;       // MFMAs of the step
-    static_assert(TOTAL % NI == 0, "requests are spread evenly between the MFMAs");
-    constexpr int EVERY = TOTAL / NI;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int c = ks & 1;
       if (ks + 1 < KS) {   // fragments of the next 16-slice are fetched under this slice's MFMAs
 #pragma unroll
-        for (int i = 0; i < FM; ++i) a[c ^ 1][i] = frag(sb + fa, i, ks + 1);
+        for (int i = 0; i < FM; ++i) a[c ^ 1][i] = frag(sb, i, ks + 1, false);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) b[c ^ 1][j] = frag(sb + fb, j, ks + 1);
+        for (int j = 0; j < FN; ++j) b[c ^ 1][j] = frag(sb, j, ks + 1, true);
       }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+          // request q goes out behind MFMA ceil((q+1)*SPAN/NI) - 1: evenly spread over the first
+          // 1/WIN of the step (a shallow ring needs them out early, a deep one can take its time)
           const int g = (ks * FM + i) * FN + j;
-          if (MORE && g % EVERY == EVERY - 1) request(g / EVERY, nb);
+          if (MORE) {
+            constexpr int SPAN = TOTAL / WIN > 0 ? TOTAL / WIN : 1;
+#pragma unroll
+            for (int q = 0; q < NI; ++q)
+              if (((q + 1) * SPAN + NI - 1) / NI - 1 == g) request(q, nb);
+          }
         }
     }
     if (MORE) advance_k();
@@ -204,12 +259,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN = (STAGES == 2 ? 2 : 1), bool TN = false>
 hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * kRowBytes;
   static_assert(smem <= 160 * 1024, "LDS of one CU");
   static bool attr_set = false;
-  auto kern = gemm_dma_nt_kernel<BM, BN, WGM, WGN, STAGES, ACT>;
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, WIN, TN>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -223,30 +278,45 @@ hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int WIN, bool TN>
 hipError_t launch_dma_cfg(const GemmArgs &a, hipStream_t s) {
-  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true>(a, s)
-                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false>(a, s);
+  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, TN>(a, s);   // no epilogue extras in this form
+  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, WIN, false>(a, s)
+                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, false>(a, s);
+}
+
+template <bool TN>
+hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
+  auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+  // DPSTAGE_GEMM_TILE overrides the tile choice (tuning aid)
+  static const char *force = getenv("DPSTAGE_GEMM_TILE");
+  const bool big_ok = a.M >= 256 && a.N >= 256;
+  if (force != nullptr) {
+    if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
+    if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
+    if (!strcmp(force, "128x128w4")) return launch_dma_cfg<128, 128, 2, 2, 4, 1, TN>(a, s);
+  }
+  // 256x256 (8 waves, 64x128 a wave; two stages fill the LDS, so its requests go out in the
+  // first quarter of a k-step) halves the L1 traffic per flop of 128x128 and wins as soon as
+  // it gives most CUs a workgroup; below that 128x128 with 8 waves and a four-stage ring.
+  if (big_ok && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
+  return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
 }
 
 }  // namespace
 
 bool gemm_dma_supported(const GemmArgs &a) {
-  if (a.mode != kGemmNT || a.M < 128 || a.N < 128 || a.K <= 0 || a.K % kBK != 0) return false;
-  if ((uint64_t)a.K * 2 * 8 + 4096 > 0xffffffffull) return false;   // lane offsets are 32-bit
-  return (((uintptr_t)a.A | (uintptr_t)a.B) & 15) == 0;
+  if (a.M < 128 || a.N < 128 || a.K <= 0 || a.K % kBK != 0) return false;
+  if ((((uintptr_t)a.A | (uintptr_t)a.B) & 15) != 0) return false;
+  // lane offsets are 32-bit
+  if (a.mode == kGemmNT) return (uint64_t)a.K * 2 * 9 + 4096 <= 0xffffffffull;
+  if (a.M % 8 != 0 || a.N % 8 != 0) return false;   // 16-byte rows and tile origins
+  const uint64_t ld = (uint64_t)(a.M > a.N ? a.M : a.N) * 2;
+  return ((uint64_t)a.K + 4) * ld + 4096 <= 0xffffffffull;
 }
 
 hipError_t launch_gemm_dma(const GemmArgs &a, hipStream_t s) {
-  auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-  static const char *force = getenv("DPSTAGE_GEMM_TILE");
-  const bool big_ok = a.M >= 256 && a.N >= 256;
-  if (force != nullptr) {
-    if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2>(a, s);
-    if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 2, 2, 4>(a, s);
-  }
-  if (big_ok && tiles(256, 256) >= 240) return launch_dma_cfg<256, 256, 4, 2, 2>(a, s);
-  return launch_dma_cfg<128, 128, 2, 2, 4>(a, s);
+  return a.mode == kGemmNT ? launch_dma_mode<false>(a, s) : launch_dma_mode<true>(a, s);
 }
 
 }  // namespace dp

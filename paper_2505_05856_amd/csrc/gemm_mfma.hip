@@ -346,9 +346,10 @@ bool gemm_mfma_supported(const GemmArgs &a) {
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s) {
-  // DPSTAGE_GEMM_NT=reg keeps the NT form on the register-staged kernel of this file (tuning aid)
-  static const char *nt = getenv("DPSTAGE_GEMM_NT");
-  if (a.mode == kGemmNT && gemm_dma_supported(a) && !(nt != nullptr && !strcmp(nt, "reg"))) return launch_gemm_dma(a, s);
+  // DPSTAGE_GEMM_NT=reg / DPSTAGE_GEMM_TN=reg keep that form on the register-staged kernel of this file (tuning aid)
+  static const char *nt = getenv("DPSTAGE_GEMM_NT"), *tn = getenv("DPSTAGE_GEMM_TN");
+  const char *keep = a.mode == kGemmNT ? nt : tn;
+  if (gemm_dma_supported(a) && !(keep != nullptr && !strcmp(keep, "reg"))) return launch_gemm_dma(a, s);
   return a.mode == kGemmNT ? launch_mode<false>(a, s) : launch_mode<true>(a, s);
 }
 

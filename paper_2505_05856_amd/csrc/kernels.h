@@ -67,7 +67,7 @@ hipError_t launch_fill_u32(void *p, size_t n_words, uint32_t pattern, hipStream_
 // ---- GEMM -------------------------------------------------------------------
 hipError_t launch_gemm_simple(int dtype, const GemmArgs &a, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
-// NT form with LDS-direct operand loads; launch_gemm_mfma routes to it when supported
+// kernels with LDS-direct operand loads; launch_gemm_mfma routes to them when the shape is supported
 bool gemm_dma_supported(const GemmArgs &a);
 hipError_t launch_gemm_dma(const GemmArgs &a, hipStream_t s);
 
