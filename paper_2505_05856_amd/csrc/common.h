@@ -59,19 +59,40 @@ __device__ __forceinline__ float wave_max(float v) {
 // ---- GELU ----------------------------------------------------------------------------
 // One definition for every kernel that applies it (the standalone kernels and the GEMM
 // epilogue must agree to the bit, so that a recomputed GELU_OUT equals the fused one);
-// contraction is off so that no context-dependent fma formation can change a result.
+// contraction is off and every fused multiply-add is written out, so that no
+// context-dependent fma formation can change a result.
+//
+// The normal distribution function comes from the rational approximation of erf by
+// Abramowitz & Stegun (formula 7.1.26, |error| <= 1.5e-7): with z = |x|/sqrt(2),
+// t = 1/(1 + p z), 1 - erf(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2).
+// The lower tail q = Phi(-|x|) is formed directly (no cancellation) and Phi(x) is q or
+// 1 - q; exp(-x^2/2) is shared with the density in the derivative.  About a third of the
+// instructions of erff, which matters where the activation rides a GEMM epilogue.
+__device__ __forceinline__ float normal_cdf_parts(float x, float *density_exp) {
+#pragma clang fp contract(off)
+  const float z = fabsf(x) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+  float p = __builtin_fmaf(t, 1.061405429f, -1.453152027f);
+  p = __builtin_fmaf(t, p, 1.421413741f);
+  p = __builtin_fmaf(t, p, -0.284496736f);
+  p = __builtin_fmaf(t, p, 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(x * x * -0.72134752044448170f);   // exp(-x^2/2)
+  *density_exp = e;
+  const float q = 0.5f * (p * t) * e;
+  return x < 0.f ? q : 1.0f - q;
+}
 __device__ __forceinline__ float gelu_f(float x, int kind) {
 #pragma clang fp contract(off)
-  if (kind == 0) return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f));
+  if (kind == 0) { float e; return x * normal_cdf_parts(x, &e); }
   const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
   return 0.5f * x * (1.0f + tanhf(u));
 }
 __device__ __forceinline__ float gelu_df(float x, int kind) {
 #pragma clang fp contract(off)
   if (kind == 0) {
-    const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752f));
-    const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
-    return cdf + x * pdf;
+    float e;
+    const float cdf = normal_cdf_parts(x, &e);
+    return cdf + x * (0.39894228040143268f * e);
   }
   const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
   const float t = tanhf(u);

@@ -34,8 +34,7 @@ namespace dp {
 
 namespace {
 
-constexpr int kBK = 64;          // contraction elements per stage
-constexpr int kRowBytes = 128;   // NT: one LDS row, 64 bf16
+constexpr int kKAlign = 64;      // K must be a multiple of this (every stage depth divides it)
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -58,16 +57,20 @@ __device__ __forceinline__ const char *uniform_ptr(const char *p) {
   return (const char *)(((uint64_t)hi << 32) | lo);
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK>
 __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amdgpu_flat_work_group_size(64 * WGM * WGN, 64 * WGM * WGN))) void gemm_dma_kernel(
     const bf16 *__restrict__ A, const bf16 *__restrict__ B, const bf16 *__restrict__ bias,
     const bf16 *__restrict__ res, bf16 *__restrict__ C, bf16 *__restrict__ C2, int gelu_kind, int M, int N, int K,
     int tiles_m, int tiles_n) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+  static_assert(BK == 64 || BK == 32, "stage depth");
+  constexpr int kRowBytes = BK * 2;                  // NT: one LDS row
+  constexpr int CPR = BK / 8, RP = 16 / CPR;         // NT: chunks per row, rows per 256-byte bank period
   constexpr int A_BYTES = BM * kRowBytes, B_BYTES = BN * kRowBytes, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int ROWB_A = BM * 2, ROWB_B = BN * 2;   // TN: bytes of one k row of a tile
-  constexpr int NIA = BM / 8 / NW, NIB = BN / 8 / NW;   // requests per wave per stage
+  constexpr int NIA = A_BYTES / 1024 / NW, NIB = B_BYTES / 1024 / NW;   // requests per wave per stage
+  static_assert(NIA >= 1 && NIB >= 1, "every wave issues requests for both operands");
   constexpr int NI = NIA + NIB;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -101,9 +104,12 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   const unsigned lda = (unsigned)(TN ? M : K) * 2u, ldb = (unsigned)(TN ? N : K) * 2u;   // operand row bytes
   unsigned voa[2], vob[2];
   if (!TN) {
-    const int r8 = lane >> 3, pc = lane & 7;
-    voa[0] = vob[0] = (unsigned)r8 * lda + (unsigned)((pc ^ (r8 >> 1)) << 4);
-    voa[1] = vob[1] = (unsigned)r8 * lda + (unsigned)((pc ^ (r8 >> 1) ^ 4) << 4);
+    constexpr int RPQ = 64 / CPR;   // operand rows per request
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const int r = lane / CPR, pc = lane % CPR;
+      voa[v] = vob[v] = (unsigned)r * lda + (unsigned)((pc ^ (((RPQ * v + r) / RP) % CPR)) << 4);
+    }
   } else {
     constexpr int RPA = 1024 / ROWB_A, RPB = 1024 / ROWB_B;
     static_assert(RPA == 2 || RPA == 4, "tile width 128 or 256");
@@ -120,11 +126,11 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
 #pragma unroll
   for (int j = 0; j < NIA; ++j)
     pa[j] = TN ? uniform_ptr((const char *)A + (size_t)((1024 / ROWB_A) * (wave * NIA + j)) * lda + (size_t)m0 * 2)
-               : uniform_ptr((const char *)A + (size_t)(m0 + 8 * (wave * NIA + j)) * lda);
+               : uniform_ptr((const char *)A + (size_t)(m0 + (64 / CPR) * (wave * NIA + j)) * lda);
 #pragma unroll
   for (int j = 0; j < NIB; ++j)
     pb[j] = TN ? uniform_ptr((const char *)B + (size_t)((1024 / ROWB_B) * (wave * NIB + j)) * ldb + (size_t)n0 * 2)
-               : uniform_ptr((const char *)B + (size_t)(n0 + 8 * (wave * NIB + j)) * ldb);
+               : uniform_ptr((const char *)B + (size_t)(n0 + (64 / CPR) * (wave * NIB + j)) * ldb);
   const unsigned lds_a = (unsigned)(wave * NIA) * 1024u, lds_b = (unsigned)A_BYTES + (unsigned)(wave * NIB) * 1024u;
 
   // request i (0 .. NI-1) of this wave for the stage at LDS byte `sb`
@@ -133,7 +139,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
     else dma16(sb + lds_b + (unsigned)(i - NIA) * 1024u, vob[(wave * NIB + i - NIA) & 1], pb[i - NIA]);
   };
   auto advance_k = [&]() {
-    const unsigned da = TN ? kBK * lda : kBK * 2, db = TN ? kBK * ldb : kBK * 2;
+    const unsigned da = TN ? BK * lda : BK * 2, db = TN ? BK * ldb : BK * 2;
     voa[0] += da; voa[1] += da; vob[0] += db; vob[1] += db;
   };
 
@@ -144,7 +150,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   //     supplies the address of k row i/4, columns 4*(i%4).. and receives column i of all
   //     four rows.  Lanes 16..31 take the next 16 columns, lanes 32..63 the k rows 8 further;
   //     a second read 4 rows on completes the 8 contraction elements of the operand.
-  const unsigned x0 = (unsigned)(((lane >> 5) ^ ((lane >> 1) & 7)) << 4);
+  const unsigned x0 = (unsigned)(((lane >> 5) ^ (((lane & 31) / RP) % CPR)) << 4);
   const unsigned fa = (unsigned)(wm + (lane & 31)) * kRowBytes + x0;
   const unsigned fb = (unsigned)A_BYTES + (unsigned)(wn + (lane & 31)) * kRowBytes + x0;
   const int ti = lane & 15, tt = ti >> 2;                                    // TN: k row within the four
@@ -173,7 +179,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk = K / kBK;
+  const int nk = K / BK;
   // prologue: stages 0 .. STAGES-2
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) {
@@ -186,20 +192,36 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
 
   int cur = 0;                 // ring slot of k-step kt
   int nxt = STAGES - 1;        // ring slot the requests of this step go to
-  // One k-step.  MORE: k-step kt+STAGES-1 exists and is requested under this step's MFMAs.
-  auto step = [&](auto more_tag) {
-    constexpr bool MORE = decltype(more_tag)::value;
-    // k-step kt must have landed: at most the requests of the later steps may be pending
-    if (MORE) wait_vmcnt_mem<(STAGES - 2) * NI>(); else wait_vmcnt_mem<0>();
-    __syncthreads();   // everyone's part of this stage is in, and everyone is done with the previous slot
-    const unsigned sb = (unsigned)cur * STAGE_BYTES, nb = (unsigned)nxt * STAGE_BYTES;
-    bf16x8 a[2][FM], b[2][FN];
+  constexpr int KS = BK / 16;
+  constexpr int TOTAL = KS * FM * FN;       // MFMAs of a step
+  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across steps");
+  // LA (rings of three or more stages): the barrier at the top of step kt also covers stage
+  // kt+1, so the last slice of a step can already fetch the first fragments of the next
+  // one and the MFMAs run on across the barrier instead of waiting for LDS reads behind it.
+  constexpr bool LA = STAGES >= 3;
+  bf16x8 a[2][FM], b[2][FN];
+  auto first_frags = [&](unsigned sb) {
 #pragma unroll
     for (int i = 0; i < FM; ++i) a[0][i] = frag(sb, i, 0, false);
 #pragma unroll
     for (int j = 0; j < FN; ++j) b[0][j] = frag(sb, j, 0, true);
-    constexpr int KS = kBK / 16;
-    constexpr int TOTAL = KS * FM * FN;       // MFMAs of the step
+  };
+  if (LA) {
+    if (nk - 1 >= STAGES - 2) wait_vmcnt_mem<(STAGES - 2) * NI>(); else wait_vmcnt_mem<0>();
+    __syncthreads();
+    first_frags(0);
+  }
+  // One k-step.  MORE: k-step kt+STAGES-1 exists and is requested under this step's MFMAs.
+  // NEXT: k-step kt+1 exists.
+  auto step = [&](auto more_tag, auto next_tag) {
+    constexpr bool MORE = decltype(more_tag)::value, NEXT = decltype(next_tag)::value;
+    // what must have landed (k-step kt, with LA also kt+1) leaves at most the requests of the
+    // later steps pending
+    if (MORE) wait_vmcnt_mem<(STAGES - (LA ? 3 : 2)) * NI>(); else wait_vmcnt_mem<0>();
+    __syncthreads();   // everyone's part is in, and everyone is done with the previous slot
+    const unsigned sb = (unsigned)cur * STAGE_BYTES, nb = (unsigned)nxt * STAGE_BYTES;
+    const unsigned sb1 = (unsigned)(cur + 1 == STAGES ? 0 : cur + 1) * STAGE_BYTES;
+    if (!LA) first_frags(sb);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int c = ks & 1;
@@ -208,6 +230,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
         for (int i = 0; i < FM; ++i) a[c ^ 1][i] = frag(sb, i, ks + 1, false);
 #pragma unroll
         for (int j = 0; j < FN; ++j) b[c ^ 1][j] = frag(sb, j, ks + 1, true);
+      } else if (LA && NEXT) {
+        first_frags(sb1);
       }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
@@ -230,8 +254,9 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
     nxt = nxt + 1 == STAGES ? 0 : nxt + 1;
   };
   int kt = 0;
-  for (; kt + STAGES - 1 < nk; ++kt) step(std::true_type{});
-  for (; kt < nk; ++kt) step(std::false_type{});
+  for (; kt + STAGES - 1 < nk; ++kt) step(std::true_type{}, std::true_type{});
+  for (; kt + 1 < nk; ++kt) step(std::false_type{}, std::true_type{});
+  if (kt < nk) step(std::false_type{}, std::false_type{});
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block.
   // Addresses are a uniform pointer (scalar registers) per row plus one 32-bit lane offset, which
@@ -259,12 +284,12 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN = (STAGES == 2 ? 2 : 1), bool TN = false>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK>
 hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
-  constexpr size_t smem = (size_t)STAGES * (BM + BN) * kRowBytes;
+  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
   static_assert(smem <= 160 * 1024, "LDS of one CU");
   static bool attr_set = false;
-  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, WIN, TN>;
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, WIN, TN, BK>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -278,11 +303,11 @@ hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int WIN, bool TN>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int WIN, bool TN, int BK = 64>
 hipError_t launch_dma_cfg(const GemmArgs &a, hipStream_t s) {
-  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, TN>(a, s);   // no epilogue extras in this form
-  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, WIN, false>(a, s)
-                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, false>(a, s);
+  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, TN, BK>(a, s);   // no epilogue extras in this form
+  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, WIN, false, BK>(a, s)
+                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, false, BK>(a, s);
 }
 
 template <bool TN>
@@ -295,6 +320,11 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
     if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
     if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
     if (!strcmp(force, "128x128w4")) return launch_dma_cfg<128, 128, 2, 2, 4, 1, TN>(a, s);
+    if (!strcmp(force, "256x256k32") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 4, 1, TN, 32>(a, s);
+    if (!strcmp(force, "128x128s5")) return launch_dma_cfg<128, 128, 4, 2, 5, 1, TN>(a, s);
+    if (!strcmp(force, "128x128s3")) return launch_dma_cfg<128, 128, 4, 2, 3, 1, TN>(a, s);
+    if (!strcmp(force, "256x128")) return launch_dma_cfg<256, 128, 4, 2, 3, 1, TN>(a, s);
+    if (!strcmp(force, "128x256")) return launch_dma_cfg<128, 256, 2, 4, 3, 1, TN>(a, s);
   }
   // 256x256 (8 waves, 64x128 a wave; two stages fill the LDS, so its requests go out in the
   // first quarter of a k-step) halves the L1 traffic per flop of 128x128 and wins as soon as
@@ -306,7 +336,7 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
 }  // namespace
 
 bool gemm_dma_supported(const GemmArgs &a) {
-  if (a.M < 128 || a.N < 128 || a.K <= 0 || a.K % kBK != 0) return false;
+  if (a.M < 128 || a.N < 128 || a.K <= 0 || a.K % kKAlign != 0) return false;
   if ((((uintptr_t)a.A | (uintptr_t)a.B) & 15) != 0) return false;
   // lane offsets are 32-bit
   if (a.mode == kGemmNT) return (uint64_t)a.K * 2 * 9 + 4096 <= 0xffffffffull;
