@@ -190,9 +190,9 @@ dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches
 
 /* Debug switches, all default 0: bit 0 = serialise (copies on the compute
  * stream, no overlap); bit 1 = poison arena blocks with NaN patterns when they
- * are released (catches use-after-release and late swap-in); bit 2 = run the
- * forward GELU as its own kernel instead of in the FC1 epilogue (results must be
- * the same bits either way). */
+ * are released (catches use-after-release and late swap-in); bit 2 = produce the
+ * forward GELU in the FC1 GEMM epilogue instead of as its own kernel (results must
+ * be the same bits either way). */
 dp_status dp_stage_set_debug(dp_stage *st, uint32_t flags);
 
 void dp_stage_destroy(dp_stage *st);

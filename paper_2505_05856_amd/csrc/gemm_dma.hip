@@ -258,27 +258,64 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   for (; kt + 1 < nk; ++kt) step(std::false_type{}, std::true_type{});
   if (kt < nk) step(std::false_type{}, std::false_type{});
 
-  // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block.
-  // Addresses are a uniform pointer (scalar registers) per row plus one 32-bit lane offset, which
-  // keeps the address arithmetic off the vector registers the accumulators fill.
-  const unsigned lane_off = ((unsigned)(4 * (lane >> 5)) * (unsigned)N + (unsigned)(lane & 31)) * 2u;
+  // ---- epilogue ---------------------------------------------------------------------------
+  // Accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block:
+  // single elements per lane, 64 contiguous bytes per row and store.  Each wave therefore
+  // turns its tile through LDS, 32 rows at a time (fp32, so that bias and residual are added
+  // before the one rounding): written as held, read back as runs of four columns per lane,
+  // so that the global accesses are 8 bytes a lane and 256..512 contiguous bytes a row.
+  // Column c of row r sits at c ^ (32 * ((r >> 2) & 1)): rows r and r+4, which one write
+  // instruction touches, land in different halves of the banks.
+  constexpr int LPR = WN / 4;            // lanes per row on the way out
+  constexpr int RPI = 64 / LPR;          // rows per read/store instruction
+  constexpr int EPI_BYTES = 32 * WN * 4; // one wave's 32 x WN fp32 block
+  static_assert(NW * EPI_BYTES <= STAGES * STAGE_BYTES, "the epilogue reuses the operand stages");
+  __syncthreads();                       // every wave is done with the operand stages
+  unsigned char *ew = lds + (unsigned)wave * EPI_BYTES;
+  const int orow = lane / LPR, oc4 = (lane % LPR) * 4;
+  const unsigned lane_off = ((unsigned)orow * (unsigned)N + (unsigned)oc4) * 2u;
+  float bv[4] = {0.f, 0.f, 0.f, 0.f};
+  if (bias != nullptr) {
+    const bf16x4 b4 = *reinterpret_cast<const bf16x4 *>(bias + n0 + wn + oc4);
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int col0 = n0 + wn + j * 32;
-    const float bv = bias != nullptr ? (float)bias[col0 + (lane & 31)] : 0.f;
+    for (int q = 0; q < 4; ++q) bv[q] = (float)b4[q];
+  }
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+  for (int i = 0; i < FM; ++i) {
+    // write: element e of block j -> row 8*(e/4) + 4*(l/32) + e%4, column 32*j + l%32
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const size_t urow = (size_t)(m0 + wm + i * 32 + 8 * (e >> 2) + (e & 3));
-        const size_t uoff = (urow * (size_t)N + (size_t)col0) * 2 + lane_off;
-        float v = acc[i][j][e] + bv;
-        if (res != nullptr) v += (float)*reinterpret_cast<const bf16 *>((const char *)res + uoff);
-        const bf16 stored = (bf16)v;
-        *reinterpret_cast<bf16 *>((char *)C + uoff) = stored;
+        const int r = 8 * (e >> 2) + (e & 3);            // + 4*(l/32)
+        const unsigned rr = (unsigned)r + 4u * (unsigned)(lane >> 5);
+        const unsigned cc = (unsigned)(32 * j + (lane & 31)) ^ (32u * ((rr >> 2) & 1u));
+        *reinterpret_cast<float *>(ew + (rr * WN + cc) * 4u) = acc[i][j][e];
+      }
+    // read back and store
+#pragma unroll
+    for (int g = 0; g < 32 / RPI; ++g) {
+      const unsigned rr = (unsigned)(g * RPI + orow);
+      const unsigned cc = (unsigned)oc4 ^ (32u * ((rr >> 2) & 1u));
+      const f32x4 t = *reinterpret_cast<const f32x4 *>(ew + (rr * WN + cc) * 4u);
+      const size_t uoff = ((size_t)(m0 + wm + i * 32 + g * RPI) * (size_t)N + (size_t)(n0 + wn)) * 2 + lane_off;
+      float v[4] = {t[0] + bv[0], t[1] + bv[1], t[2] + bv[2], t[3] + bv[3]};
+      if (res != nullptr) {
+        const bf16x4 r4 = *reinterpret_cast<const bf16x4 *>((const char *)res + uoff);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] += (float)r4[q];
+      }
+      bf16x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o[q] = (bf16)v[q];
+      *reinterpret_cast<bf16x4 *>((char *)C + uoff) = o;
+      if (ACT) {
         // fused activation: computed from the value as stored, so that a later standalone
         // GELU of C gives the same bits
-        if (ACT) *reinterpret_cast<bf16 *>((char *)C2 + uoff) = (bf16)gelu_f((float)stored, gelu_kind);
+        bf16x4 o2;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o2[q] = (bf16)gelu_f((float)o[q], gelu_kind);
+        *reinterpret_cast<bf16x4 *>((char *)C2 + uoff) = o2;
       }
     }
   }
@@ -338,6 +375,8 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
 bool gemm_dma_supported(const GemmArgs &a) {
   if (a.M < 128 || a.N < 128 || a.K <= 0 || a.K % kKAlign != 0) return false;
   if ((((uintptr_t)a.A | (uintptr_t)a.B) & 15) != 0) return false;
+  // the epilogue moves runs of four columns (8 bytes)
+  if (a.N % 4 != 0 || (((uintptr_t)a.C | (uintptr_t)a.C2 | (uintptr_t)a.res | (uintptr_t)a.bias) & 7) != 0) return false;
   // lane offsets are 32-bit
   if (a.mode == kGemmNT) return (uint64_t)a.K * 2 * 9 + 4096 <= 0xffffffffull;
   if (a.M % 8 != 0 || a.N % 8 != 0) return false;   // 16-byte rows and tile origins

@@ -211,6 +211,11 @@ struct LayerW {  // library-owned device copies
 
 }  // namespace
 
+// Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  The epilogue
+// stores single elements per lane, and a second output doubles those stores: measured, the
+// separate kernel with its 16-byte accesses is the faster of the two, so it is the default.
+constexpr bool kFuseGeluDefault = false;
+
 struct dp_stage {
   Cfg c;
   dp_stage_config pub;
@@ -831,7 +836,7 @@ dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size
   Cfg c;
   dp_status s = parse_cfg(cfg, &c);
   if (s != DP_OK) return s;
-  return validate(c, plan, plan_len, budget_bytes, inflight, report, env_mfma_enabled(), true);
+  return validate(c, plan, plan_len, budget_bytes, inflight, report, env_mfma_enabled(), kFuseGeluDefault);
 }
 
 dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *layers, uint64_t arena_bytes_hint,
@@ -913,7 +918,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
       if (p[i] == nullptr) return fail(DP_E_INVAL, "gradient pointer %d of layer %d is null", i, l);
   }
   dp_plan_report rep;
-  const bool fuse_gelu = (st->debug & 4u) == 0;
+  const bool fuse_gelu = ((st->debug & 4u) != 0) != kFuseGeluDefault;   // debug bit 2 flips the default
   long swap_hold = 0;
   dp_status s = validate(c, plan, plan_len, budget_bytes, 1, &rep, st->use_mfma, fuse_gelu, &swap_hold);
   if (s != DP_OK) return s;

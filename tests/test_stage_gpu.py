@@ -102,12 +102,12 @@ def test_small_stages_every_plan(cfg, sharp):
     run.poison_outputs()
     run.step(plans[3][1])
     assert all(torch.equal(a, b) for a, b in zip(first, run.raw_results()))
-    # and so does the forward GELU as its own kernel instead of in the FC1 epilogue
+    # and so does the forward GELU in the FC1 epilogue instead of as its own kernel
     B.stage_set_debug(run.stage, 4)
     for name, p in plans[:2]:
         run.poison_outputs()
         run.step(p)
-        assert all(torch.equal(a, b) for a, b in zip(first, run.raw_results())), f"unfused GELU, plan {name}"
+        assert all(torch.equal(a, b) for a, b in zip(first, run.raw_results())), f"fused GELU, plan {name}"
     run.close()
 
 
