@@ -24,7 +24,7 @@ PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector ALUs)
 # HBM bytes per launch of the dominant kernel (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a 256 MiB
 # device copy gives), from the rocprofv3 --pmc runs summarised in profiles/c2_step_hbm_traffic_pmc.md.
-MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 89.3e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 80.3e6}
 
 
 def gemm_flops(cfg):

@@ -57,6 +57,13 @@ __device__ __forceinline__ const char *uniform_ptr(const char *p) {
   return (const char *)(((uint64_t)hi << 32) | lo);
 }
 
+// TN: chunk-position swizzle of k row r of a tile whose rows are ROWB bytes.  256- and
+// 512-byte rows: the four rows of a transpose read go to the four 64-byte quarters of the
+// bank period.  128-byte rows (two rows a period): rows r and r+2 swap 64-byte halves.
+template <int ROWB> __device__ __forceinline__ constexpr int tn_swizzle(int r) {
+  return ROWB == 128 ? ((r >> 1) & 1) << 2 : (r & 3) << 2;
+}
+
 template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK>
 __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amdgpu_flat_work_group_size(64 * WGM * WGN, 64 * WGM * WGN))) void gemm_dma_kernel(
     const bf16 *__restrict__ A, const bf16 *__restrict__ B, const bf16 *__restrict__ bias,
@@ -112,14 +119,14 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
     }
   } else {
     constexpr int RPA = 1024 / ROWB_A, RPB = 1024 / ROWB_B;
-    static_assert(RPA == 2 || RPA == 4, "tile width 128 or 256");
-    static_assert(RPB == 2 || RPB == 4, "tile width 128 or 256");
+    static_assert(RPA == 2 || RPA == 4 || RPA == 8, "tile width 64, 128 or 256");
+    static_assert(RPB == 2 || RPB == 4 || RPB == 8, "tile width 64, 128 or 256");
 #pragma unroll
     for (int v = 0; v < 2; ++v) {
       const int ka = lane / (64 / RPA), pa_ = lane % (64 / RPA);
-      voa[v] = (unsigned)ka * lda + (unsigned)((pa_ ^ (((RPA * v + ka) & 3) << 2)) << 4);
+      voa[v] = (unsigned)ka * lda + (unsigned)((pa_ ^ tn_swizzle<ROWB_A>(RPA * v + ka)) << 4);
       const int kb = lane / (64 / RPB), pb_ = lane % (64 / RPB);
-      vob[v] = (unsigned)kb * ldb + (unsigned)((pb_ ^ (((RPB * v + kb) & 3) << 2)) << 4);
+      vob[v] = (unsigned)kb * ldb + (unsigned)((pb_ ^ tn_swizzle<ROWB_B>(RPB * v + kb)) << 4);
     }
   }
   const char *pa[NIA], *pb[NIB];
@@ -163,7 +170,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
     }
     const unsigned rowb = is_b ? ROWB_B : ROWB_A;
     const unsigned cw = (unsigned)((is_b ? wn : wm) / 8 + blk * 4);        // first chunk of the 32-column block
-    const unsigned off = base + (is_b ? (unsigned)A_BYTES : 0u) + trow * rowb + ((cw ^ (unsigned)(tt << 2)) << 4) + tlow +
+    const unsigned sw = is_b ? (unsigned)tn_swizzle<ROWB_B>(tt) : (unsigned)tn_swizzle<ROWB_A>(tt);
+    const unsigned off = base + (is_b ? (unsigned)A_BYTES : 0u) + trow * rowb + ((cw ^ sw) << 4) + tlow +
                          (unsigned)ks * 16u * rowb;
     union { s16x4 h[2]; bf16x8 v; } u;
     u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(lds + off));
@@ -269,6 +277,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   constexpr int LPR = WN / 4;            // lanes per row on the way out
   constexpr int RPI = 64 / LPR;          // rows per read/store instruction
   constexpr int EPI_BYTES = 32 * WN * 4; // one wave's 32 x WN fp32 block
+  constexpr unsigned ESW = WN >= 64 ? 32u : 0u;   // (a 32-column block has no second half to swap with)
   static_assert(NW * EPI_BYTES <= STAGES * STAGE_BYTES, "the epilogue reuses the operand stages");
   __syncthreads();                       // every wave is done with the operand stages
   unsigned char *ew = lds + (unsigned)wave * EPI_BYTES;
@@ -289,14 +298,14 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
       for (int e = 0; e < 16; ++e) {
         const int r = 8 * (e >> 2) + (e & 3);            // + 4*(l/32)
         const unsigned rr = (unsigned)r + 4u * (unsigned)(lane >> 5);
-        const unsigned cc = (unsigned)(32 * j + (lane & 31)) ^ (32u * ((rr >> 2) & 1u));
+        const unsigned cc = (unsigned)(32 * j + (lane & 31)) ^ (ESW * ((rr >> 2) & 1u));
         *reinterpret_cast<float *>(ew + (rr * WN + cc) * 4u) = acc[i][j][e];
       }
     // read back and store
 #pragma unroll
     for (int g = 0; g < 32 / RPI; ++g) {
       const unsigned rr = (unsigned)(g * RPI + orow);
-      const unsigned cc = (unsigned)oc4 ^ (32u * ((rr >> 2) & 1u));
+      const unsigned cc = (unsigned)oc4 ^ (ESW * ((rr >> 2) & 1u));
       const f32x4 t = *reinterpret_cast<const f32x4 *>(ew + (rr * WN + cc) * 4u);
       const size_t uoff = ((size_t)(m0 + wm + i * 32 + g * RPI) * (size_t)N + (size_t)(n0 + wn)) * 2 + lane_off;
       float v[4] = {t[0] + bv[0], t[1] + bv[1], t[2] + bv[2], t[3] + bv[3]};
@@ -357,16 +366,16 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
     if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
     if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
     if (!strcmp(force, "128x128w4")) return launch_dma_cfg<128, 128, 2, 2, 4, 1, TN>(a, s);
-    if (!strcmp(force, "256x256k32") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 4, 1, TN, 32>(a, s);
-    if (!strcmp(force, "128x128s5")) return launch_dma_cfg<128, 128, 4, 2, 5, 1, TN>(a, s);
-    if (!strcmp(force, "128x128s3")) return launch_dma_cfg<128, 128, 4, 2, 3, 1, TN>(a, s);
-    if (!strcmp(force, "256x128")) return launch_dma_cfg<256, 128, 4, 2, 3, 1, TN>(a, s);
-    if (!strcmp(force, "128x256")) return launch_dma_cfg<128, 256, 2, 4, 3, 1, TN>(a, s);
+    if (!strcmp(force, "64x64")) return launch_dma_cfg<64, 64, 2, 2, 8, 1, TN>(a, s);
+
   }
   // 256x256 (8 waves, 64x128 a wave; two stages fill the LDS, so its requests go out in the
   // first quarter of a k-step) halves the L1 traffic per flop of 128x128 and wins as soon as
   // it gives most CUs a workgroup; below that 128x128 with 8 waves and a four-stage ring.
   if (big_ok && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
+  // a small output with a long contraction (the out-projection weight gradient) leaves most
+  // CUs without a 128x128 tile: 64x64 tiles, several workgroups a CU, then run faster
+  if (tiles(128, 128) <= 96) return launch_dma_cfg<64, 64, 2, 2, 8, 1, TN>(a, s);
   return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
 }
 
