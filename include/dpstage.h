@@ -146,11 +146,74 @@ size_t dp_plan_len(const dp_stage_config *cfg);
  * Arena policy for swapped-out blocks: with budget_bytes == 0 a block returns to
  * the allocator as soon as its copy-out is queued (smallest peak; its next user
  * waits for the copy).  With a budget the walk first tries to hold such blocks
- * back until forward is over, then for two layers, then not at all, and takes
+ * back until forward is over, then for ever shorter spans, then not at all, and takes
  * the first policy whose peak fits: forward compute then never waits for the
  * host link when memory allows.  dp_stage_step makes the same choice. */
 dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len,
                            uint64_t budget_bytes, uint32_t inflight, dp_plan_report *report);
+
+/* ---- plan generator: the memory-optimisation step in front of the stage step -----------
+ * Section 4.3: the candidates are the saved tensors; they are rated by FreeTime and by
+ * memory saving per second, the two quantities of the cost model the section cites;
+ * swapping is applied while the transfers still overlap with computation, after that every
+ * step takes the cheaper of swapping and recomputation; the plan must fit the device
+ * (Algorithm 1's test) and a stage is judged by T_x + T_x^moo (Section 4.2).
+ *
+ * Cost model of one layer (all layers of a stage are alike).  Node order, forward:
+ *   pre-LN  LN1, QKV, ATTN, PROJ, LN2, FC1, GELU, FC2     post-LN  QKV, ATTN, PROJ, LN1, FC1, GELU, FC2, LN2
+ * backward (execution order):
+ *   pre-LN  FC2, GELU, FC1, LN2, PROJ, ATTN, QKV, LN1     post-LN  LN2, FC2, GELU, FC1, LN1, PROJ, ATTN, QKV
+ * A backward node's time covers all its kernels (input and weight gradients, reductions). */
+typedef struct {
+  int64_t fwd_ns[8], bwd_ns[8];                /* nanoseconds per node */
+  uint64_t d2h_bytes_per_us, h2d_bytes_per_us; /* host link speed each way */
+} dp_cost_model;
+
+typedef struct {
+  int64_t step_ns;      /* modelled step time */
+  uint64_t peak_bytes;  /* fixed_bytes + running peak of the saved tensors (Algorithm 2's walk) */
+  uint64_t d2h_bytes, h2d_bytes;
+  int32_t n_replayed_ops;
+} dp_plan_cost_report;
+
+typedef struct {
+  int32_t feasible;
+  int64_t base_ns, moo_ns;        /* T_x of the unoptimised step and T_x^moo the plan adds (model) */
+  uint64_t peak_bytes;            /* model peak of the plan */
+  int32_t n_free_swaps, n_paid_swaps, n_recomputed;
+  /* DP_MEMOPT_VALIDATE only: */
+  uint64_t validated_peak_bytes;  /* dp_plan_validate's peak_bytes of the plan */
+  int64_t exact_step_ns;          /* the model's clocks on the executor's own arena and hold policy */
+  int32_t refine_rounds;
+} dp_memopt_report;
+
+enum { DP_MEMOPT_VALIDATE = 1 };
+
+/* Pure host code.  Plays one step under `plan` on three clocks (compute, copy-out, copy-in)
+ * with the executor's event rules: a swap-out starts when its tensor's last forward reader
+ * is done and the copy-out stream is free; the swap-ins of layer l-1 are issued when the
+ * backward of layer l starts, each behind its own copy-out; a backward node waits for the
+ * swap-ins it reads; recomputed tensors are regenerated on the compute clock before their
+ * first backward reader.  Memory is the saved tensors only (no transient gradients, no
+ * fragmentation); fixed_bytes is added to the peak.  Errors as dp_plan_validate, plus
+ * DP_E_INVAL for a null or negative cost model or a zero link speed. */
+dp_status dp_plan_cost(const dp_stage_config *cfg, const dp_cost_model *cm, const uint8_t *plan,
+                       size_t plan_len, uint64_t fixed_bytes, dp_plan_cost_report *report);
+
+/* Pure host code.  Writes a plan to plan_out[plan_len] (host) whose inflight * peak fits
+ * budget_bytes (0 = no limit: the all-KEEP plan):
+ *   1. candidates by decreasing FreeTime = (first backward use - copy-in time) - (last
+ *      forward use + copy-out time) on the unoptimised timeline; each is swapped if that
+ *      does not lengthen the modelled step; the first that does ends the phase;
+ *   2. until it fits: over all remaining candidates and both actions, the one with the
+ *      largest (peak reduction) / (added time), ties to the smaller added time, then SWAP.
+ * flags = 0: peak = fixed_bytes + saved tensors, as dp_plan_cost (the planner of the model).
+ * flags = DP_MEMOPT_VALIDATE: fixed_bytes is ignored; the plan is checked with
+ * dp_plan_validate and the model's budget lowered by the difference until the true peak fits.
+ * DP_E_BUDGET if nothing fits (plan_out then holds the last attempt, report->feasible = 0). */
+dp_status dp_plan_generate(const dp_stage_config *cfg, const dp_cost_model *cm, uint64_t budget_bytes,
+                           uint32_t inflight, uint64_t fixed_bytes, uint32_t flags, uint8_t *plan_out,
+                           size_t plan_len, dp_memopt_report *report);
 
 /* Creates a stage on the current HIP device.  `layers` is a host array of
  * n_layers structs of device pointers; the weights are copied (and re-laid
@@ -174,7 +237,7 @@ dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *laye
  * which are joined back into hip_stream before return; the call does not wait
  * for this step unless `stats` is non-NULL, but it first waits (on the host) for
  * the step issued two calls earlier on the same handle, so that at most two
- * steps are in flight.  DP_E_HIP after a partial enqueue
+ * steps are in flight; a plan that swaps waits for the previous step as well.  DP_E_HIP after a partial enqueue
  * leaves the outputs undefined.  One step at a time per handle.
  * The results are bit-identical for every plan. */
 dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const uint8_t *plan,
@@ -187,6 +250,14 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
  * counts per class since the last call; arrays of DP_OPC_COUNT entries. */
 dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled);
 dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches_by_class);
+
+/* Fills a cost model from this stage on this machine: `steps` all-KEEP steps with every
+ * launch bracketed (node times averaged over layers and steps), then a block of FC1_OUT's
+ * size copied four times each way through pinned host memory on the library's copy
+ * streams.  Buffers as dp_stage_step (they are overwritten).  Waits for the device. */
+dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void *dy, void *y_out,
+                                      void *dx_out, const dp_layer_grads *dw, void *hip_stream,
+                                      int32_t steps, dp_cost_model *out);
 
 /* Debug switches, all default 0: bit 0 = serialise (copies on the compute
  * stream, no overlap); bit 1 = poison arena blocks with NaN patterns when they

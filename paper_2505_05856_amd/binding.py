@@ -62,6 +62,34 @@ class StepStats(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class CostModel(C.Structure):
+    _fields_ = [("fwd_ns", C.c_int64 * 8), ("bwd_ns", C.c_int64 * 8),
+                ("d2h_bytes_per_us", C.c_uint64), ("h2d_bytes_per_us", C.c_uint64)]
+
+    def as_dict(self):
+        return {"fwd_ns": list(self.fwd_ns), "bwd_ns": list(self.bwd_ns),
+                "d2h_bytes_per_us": self.d2h_bytes_per_us, "h2d_bytes_per_us": self.h2d_bytes_per_us}
+
+
+class PlanCostReport(C.Structure):
+    _fields_ = [("step_ns", C.c_int64), ("peak_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64),
+                ("h2d_bytes", C.c_uint64), ("n_replayed_ops", C.c_int32)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class MemoptReport(C.Structure):
+    _fields_ = [("feasible", C.c_int32), ("base_ns", C.c_int64), ("moo_ns", C.c_int64), ("peak_bytes", C.c_uint64),
+                ("n_free_swaps", C.c_int32), ("n_paid_swaps", C.c_int32), ("n_recomputed", C.c_int32),
+                ("validated_peak_bytes", C.c_uint64), ("exact_step_ns", C.c_int64), ("refine_rounds", C.c_int32)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+MEMOPT_VALIDATE = 1
+
 _lib = None
 
 
@@ -96,7 +124,11 @@ def lib() -> C.CDLL:
     L.dp_op_colsum.argtypes = [i32, i32, i32, vp, vp, vp, vp]
     L.dp_op_attention_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.dp_op_attention_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
-    for name in ("dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_set_profiling",
+    L.dp_plan_cost.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), vp, sz, u64, C.POINTER(PlanCostReport)]
+    L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
+                                   sz, C.POINTER(MemoptReport)]
+    L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
+    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd"):
@@ -137,6 +169,34 @@ def plan_validate(cfg: StageConfig, plan, budget_bytes: int = 0, inflight: int =
     if raise_on_error:
         _check(code)
     return code, rep.as_dict()
+
+
+def make_cost_model(fwd_ns, bwd_ns, d2h_bytes_per_us, h2d_bytes_per_us) -> CostModel:
+    cm = CostModel()
+    for i in range(8):
+        cm.fwd_ns[i], cm.bwd_ns[i] = int(fwd_ns[i]), int(bwd_ns[i])
+    cm.d2h_bytes_per_us, cm.h2d_bytes_per_us = int(d2h_bytes_per_us), int(h2d_bytes_per_us)
+    return cm
+
+
+def plan_cost(cfg: StageConfig, cm: CostModel, plan, fixed_bytes: int = 0):
+    keep, p, n = _plan_buf(plan)
+    rep = PlanCostReport()
+    _check(lib().dp_plan_cost(C.byref(cfg), C.byref(cm), p, n, fixed_bytes, C.byref(rep)))
+    return rep.as_dict()
+
+
+def plan_generate(cfg: StageConfig, cm: CostModel, budget_bytes: int, inflight: int = 1, fixed_bytes: int = 0,
+                  flags: int = 0, raise_on_error=True):
+    """Returns (status_code, plan as uint8 array, report dict)."""
+    n = plan_len(cfg)
+    out = np.zeros(n, dtype=np.uint8)
+    rep = MemoptReport()
+    code = lib().dp_plan_generate(C.byref(cfg), C.byref(cm), budget_bytes, inflight, fixed_bytes, flags,
+                                  out.ctypes.data_as(C.c_void_p), n, C.byref(rep))
+    if raise_on_error:
+        _check(code)
+    return code, out, rep.as_dict()
 
 
 def last_error() -> str:
@@ -206,6 +266,13 @@ def stage_op_times(stage: Stage):
     cnt = (C.c_uint64 * len(OP_CLASSES))()
     _check(lib().dp_stage_op_times(stage.handle, ms, cnt))
     return {n: (float(ms[i]), int(cnt[i])) for i, n in enumerate(OP_CLASSES)}
+
+
+def stage_measure_cost_model(stage: Stage, x_in, dy, y_out, dx_out, grads, steps: int = 3, stream=None) -> CostModel:
+    cm = CostModel()
+    _check(lib().dp_stage_measure_cost_model(stage.handle, _ptr(x_in), _ptr(dy), _ptr(y_out), _ptr(dx_out),
+                                             _layer_array(grads), _stream_ptr(stream), steps, C.byref(cm)))
+    return cm
 
 
 def stage_set_debug(stage: Stage, flags: int):
