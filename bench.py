@@ -71,7 +71,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="C2", help="workload name from synthetic.CONFIGS")
-    ap.add_argument("--plan", default=None, help="plan name (default: the config's own)")
+    ap.add_argument("--plan", default=None, help="plan name (default: the config's own); 'memopt' generates one")
+    ap.add_argument("--budget-frac", type=float, default=0.5,
+                    help="with --plan memopt: budget as a fraction of the way from the all-recompute to the all-KEEP peak")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-op-times", action="store_true")
     ap.add_argument("--overlap", action="store_true",
@@ -99,12 +101,26 @@ def main():
                          "recompute-attention": ("recompute-attention", syn.plan_recompute_attention),
                          "swap-fc1-recompute-ln-gelu": ("swap-fc1-recompute-ln-gelu",
                                                         syn.plan_swap_ffn_recompute_norm_gelu),
-                         "seed7-mixed": ("seed7-mixed", lambda c: syn.plan_seeded(c, 7))}[args.plan]
+                         "seed7-mixed": ("seed7-mixed", lambda c: syn.plan_seeded(c, 7)),
+                         "memopt": ("memopt", syn.plan_keep_all)}[args.plan]
     plan = mk(cfg)
     budget = syn.BUDGETS.get(args.config, 0)
     weights = syn.make_weights(cfg)
     x, dy = syn.make_activations(cfg)
     run = StageRunner(cfg, weights, x, dy)
+    memopt = None
+    if plan_name == "memopt":
+        # the plan generator in front of the path: cost model measured here, plan for the budget, prediction
+        cm = B.stage_measure_cost_model(run.stage, run.x, run.dy, run.y, run.dx, run.g, steps=3)
+        _, hi = B.plan_validate(run.bcfg, syn.plan_keep_all(cfg))
+        _, lo = B.plan_validate(run.bcfg, syn.plan_all_recompute(cfg))
+        budget = int(lo["peak_bytes"] + args.budget_frac * (hi["peak_bytes"] - lo["peak_bytes"]))
+        _, plan, mrep = B.plan_generate(run.bcfg, cm, budget, flags=B.MEMOPT_VALIDATE)
+        memopt = {"cost_model": cm.as_dict(), "budget_frac": args.budget_frac,
+                  "base_ms": mrep["base_ns"] / 1e6, "model_moo_ms": mrep["moo_ns"] / 1e6,
+                  "predicted_ms": mrep["exact_step_ns"] / 1e6,
+                  "free_swaps": mrep["n_free_swaps"], "paid_swaps": mrep["n_paid_swaps"],
+                  "recomputed": mrep["n_recomputed"], "refine_rounds": mrep["refine_rounds"]}
     _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
     if args.copy_calibration:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
@@ -203,6 +219,9 @@ def main():
     }
     if overlap is not None:
         out["swap_overlap"] = overlap
+    if memopt is not None:
+        memopt["measured_ms"] = round(ms, 4)
+        out["memopt"] = memopt
     run.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, weights, x, dy)
