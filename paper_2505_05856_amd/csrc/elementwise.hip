@@ -189,6 +189,46 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
   }
 }
 
+// The same pass for up to kMaxReduceJobs reductions in one launch: block b belongs to the job
+// whose block range contains it and does exactly what reduce_partials_kernel does for it.
+struct ReduceJobTable {
+  ReduceJob job[kMaxReduceJobs];
+  int first_block[kMaxReduceJobs + 1];
+  int n;
+};
+template <typename T>
+__global__ __launch_bounds__(1024) void reduce_jobs_kernel(ReduceJobTable t) {
+  __shared__ float red[16][64];
+  int j = 0;
+  while (j + 1 < t.n && (int)blockIdx.x >= t.first_block[j + 1]) ++j;
+  const ReduceJob &job = t.job[j];
+  const float *__restrict__ part = job.part;
+  const int nb = job.nb, width = job.width;
+  const int cx = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int col = ((int)blockIdx.x - t.first_block[j]) * 64 + cx;
+  float s = 0.f;
+  if (col < width) {
+    int b = g;
+    for (; b + 7 * 16 < nb; b += 8 * 16) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(b + u * 16) * width + col];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; b < nb; b += 16) s += part[(size_t)b * width + col];
+  }
+  red[g][cx] = s;
+  __syncthreads();
+  if (g == 0 && col < width) {
+    float tsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tsum += red[i][cx];
+    const int which = col / job.seg, k = col - which * job.seg;
+    stf((T *)(which == 0 ? job.out0 : which == 1 ? job.out1 : job.out2) + k, tsum);
+  }
+}
+
 // Column sums of x [rows, cols]: block (cx, rb) covers 512 columns and rows
 // [rb*rpb, (rb+1)*rpb); partial row rb of part[nrb][cols].
 template <typename T>
@@ -331,10 +371,20 @@ hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x
                         : ln_fwd_t<float>(rows, cols, eps, x, gamma, beta, y, stats, s);
 }
 
+// second pass now, or left to the caller as a job
+template <typename T>
+static hipError_t reduce_or_defer(const float *part, int nb, int width, int seg, void *o0, void *o1, void *o2,
+                                  hipStream_t s, ReduceJob *job) {
+  if (job != nullptr) { *job = ReduceJob{part, nb, width, seg, o0, o1, o2}; return hipSuccess; }
+  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((width + 63) / 64), dim3(1024), 0, s, part, nb, width, (T *)o0,
+                     (T *)o1, (T *)o2, seg);
+  return hipGetLastError();
+}
+
 template <typename T, bool SUMDX>
 static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, const float *stats,
                            const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
-                           void *ws, hipStream_t s) {
+                           void *ws, hipStream_t s, ReduceJob *job) {
   int rpb;
   const int nb = row_blocks(rows, 8, &rpb);
   const int nv = SUMDX ? 3 : 2;
@@ -352,27 +402,26 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
 #undef DP_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((nv * cols + 63) / 64), dim3(1024), 0, s, part, nb,
-                     nv * cols, (T *)dgamma, (T *)dbeta, (T *)dxsum, cols);
-  return hipGetLastError();
+  return reduce_or_defer<T>(part, nb, nv * cols, cols, dgamma, dbeta, dxsum, s, job);
 }
 
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
                          const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
-                         void *ws, hipStream_t s) {
+                         void *ws, hipStream_t s, ReduceJob *job) {
+  if (job != nullptr) job->nb = 0;
   if (rows <= 0) return hipSuccess;
   if (dxsum != nullptr)
     return dtype == kBF16
-               ? ln_bwd_t<bf16, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s)
-               : ln_bwd_t<float, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s);
+               ? ln_bwd_t<bf16, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job)
+               : ln_bwd_t<float, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job);
   return dtype == kBF16
-             ? ln_bwd_t<bf16, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s)
-             : ln_bwd_t<float, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s);
+             ? ln_bwd_t<bf16, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s, job)
+             : ln_bwd_t<float, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s, job);
 }
 
 template <typename T>
 static hipError_t gelu_bwd_colsum_t(int kind, int rows, int cols, const void *dy, const void *x, void *dx,
-                                    void *dbias, void *ws, hipStream_t s) {
+                                    void *dbias, void *ws, hipStream_t s, ReduceJob *job) {
   int rpb;
   const int nb = row_blocks(rows, 16, &rpb);
   float *part = (float *)ws;
@@ -380,16 +429,15 @@ static hipError_t gelu_bwd_colsum_t(int kind, int rows, int cols, const void *dy
                      (const T *)x, (T *)dx, part, rows, cols, rpb, kind);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((cols + 63) / 64), dim3(1024), 0, s, part, nb, cols,
-                     (T *)dbias, (T *)dbias, (T *)dbias, cols);
-  return hipGetLastError();
+  return reduce_or_defer<T>(part, nb, cols, cols, dbias, dbias, dbias, s, job);
 }
 
 hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
-                                  void *dbias, void *ws, hipStream_t s) {
+                                  void *dbias, void *ws, hipStream_t s, ReduceJob *job) {
+  if (job != nullptr) job->nb = 0;
   if (rows <= 0) return hipSuccess;
-  return dtype == kBF16 ? gelu_bwd_colsum_t<bf16>(kind, rows, cols, dy, x, dx, dbias, ws, s)
-                        : gelu_bwd_colsum_t<float>(kind, rows, cols, dy, x, dx, dbias, ws, s);
+  return dtype == kBF16 ? gelu_bwd_colsum_t<bf16>(kind, rows, cols, dy, x, dx, dbias, ws, s, job)
+                        : gelu_bwd_colsum_t<float>(kind, rows, cols, dy, x, dx, dbias, ws, s, job);
 }
 
 static int ew_grid(size_t n8) {
@@ -423,7 +471,7 @@ hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const 
 }
 
 template <typename T>
-static hipError_t colsum_t(int rows, int cols, const void *x, void *out, void *ws, hipStream_t s) {
+static hipError_t colsum_t(int rows, int cols, const void *x, void *out, void *ws, hipStream_t s, ReduceJob *job) {
   int rpb;
   const int nb = row_blocks(rows, 16, &rpb);
   float *part = (float *)ws;
@@ -431,14 +479,32 @@ static hipError_t colsum_t(int rows, int cols, const void *x, void *out, void *w
                      cols, rpb);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((cols + 63) / 64), dim3(1024), 0, s, part, nb, cols,
-                     (T *)out, (T *)out, (T *)out, cols);
-  return hipGetLastError();
+  return reduce_or_defer<T>(part, nb, cols, cols, out, out, out, s, job);
 }
 
-hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s) {
+hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s,
+                         ReduceJob *job) {
+  if (job != nullptr) job->nb = 0;
   if (rows <= 0) return hipSuccess;
-  return dtype == kBF16 ? colsum_t<bf16>(rows, cols, x, out, ws, s) : colsum_t<float>(rows, cols, x, out, ws, s);
+  return dtype == kBF16 ? colsum_t<bf16>(rows, cols, x, out, ws, s, job) : colsum_t<float>(rows, cols, x, out, ws, s, job);
+}
+
+hipError_t launch_reduce_jobs(int dtype, const ReduceJob *jobs, int n, hipStream_t s) {
+  ReduceJobTable t;
+  t.n = 0;
+  int blocks = 0;
+  for (int i = 0; i < n && t.n < kMaxReduceJobs; ++i) {
+    if (jobs[i].nb <= 0 || jobs[i].width <= 0) continue;
+    t.job[t.n] = jobs[i];
+    t.first_block[t.n] = blocks;
+    blocks += (jobs[i].width + 63) / 64;
+    ++t.n;
+  }
+  t.first_block[t.n] = blocks;
+  if (t.n == 0) return hipSuccess;
+  if (dtype == kBF16) hipLaunchKernelGGL((reduce_jobs_kernel<bf16>), dim3(blocks), dim3(1024), 0, s, t);
+  else hipLaunchKernelGGL((reduce_jobs_kernel<float>), dim3(blocks), dim3(1024), 0, s, t);
+  return hipGetLastError();
 }
 
 hipError_t launch_transpose(int dtype, int rows, int cols, const void *src, void *dst, hipStream_t s) {

@@ -48,18 +48,31 @@ bool gemm_mfma_supported(const GemmArgs &a);            // bf16 MFMA path precon
 bool attn_mfma_supported(int S, int dh);
 
 // ---- elementwise / reductions ----------------------------------------------
+// Second pass of a two-pass column reduction: out[j / seg][j % seg] = sum over the nb
+// partial rows of part[.][j], j < width, in a fixed order.  The launchers below run it
+// themselves unless they are handed a ReduceJob to fill in: then the caller runs it later
+// with launch_reduce_jobs (several jobs in one launch; same arithmetic, same bits).
+struct ReduceJob {
+  const float *part;
+  int nb, width, seg;
+  void *out0, *out1, *out2;
+};
+constexpr int kMaxReduceJobs = 8;
+hipError_t launch_reduce_jobs(int dtype, const ReduceJob *jobs, int n, hipStream_t s);
+
 hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x, const void *gamma,
                          const void *beta, void *y, float *stats, hipStream_t s);
 // dxsum (nullable): receives the column sums of the stored dx
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
                          const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
-                         void *ws, hipStream_t s);
+                         void *ws, hipStream_t s, ReduceJob *job = nullptr);
 // dx = dy * gelu'(x) over [rows, cols] and dbias = column sums of the stored dx
 hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
-                                  void *dbias, void *ws, hipStream_t s);
+                                  void *dbias, void *ws, hipStream_t s, ReduceJob *job = nullptr);
 hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s);
 hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s);
-hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s);
+hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s,
+                         ReduceJob *job = nullptr);
 // dst[c, r] = src[r, c]
 hipError_t launch_transpose(int dtype, int rows, int cols, const void *src, void *dst, hipStream_t s);
 hipError_t launch_fill_u32(void *p, size_t n_words, uint32_t pattern, hipStream_t s);

@@ -428,32 +428,54 @@ struct Walk {
     }
     prof_end();
   }
+  // The second passes of the backward's column reductions (bias and LayerNorm parameter
+  // gradients) only feed the caller's gradient buffers, so they are collected and run as one
+  // launch per layer instead of one small launch each; their partial buffers live until then.
+  std::vector<dp::ReduceJob> red_jobs;
+  std::vector<Buf> red_ws;
+  void defer_reduce(const dp::ReduceJob &j, const Buf &ws) {
+    red_jobs.push_back(j);
+    red_ws.push_back(ws);
+    if ((int)red_ws.size() == dp::kMaxReduceJobs) flush_reduces();
+  }
+  void flush_reduces() {
+    if (red_ws.empty()) return;
+    prof_begin(DP_OPC_REDUCE);
+    if (live) check(dp::launch_reduce_jobs(c.dtype, red_jobs.data(), (int)red_jobs.size(), cs));
+    prof_end();
+    for (Buf &b : red_ws) drop(b);
+    red_jobs.clear();
+    red_ws.clear();
+  }
   void colsum(long rows, long cols, const void *x, void *out) {
     Buf ws = tmp(dp::reduce_ws_bytes((int)rows, (int)cols));
+    dp::ReduceJob job{};
     prof_begin(DP_OPC_REDUCE);
-    if (live) check(dp::launch_colsum(c.dtype, (int)rows, (int)cols, x, out, bptr(ws), cs));
+    if (live) check(dp::launch_colsum(c.dtype, (int)rows, (int)cols, x, out, bptr(ws), cs, &job));
     prof_end();
-    drop(ws);
+    defer_reduce(job, ws);
   }
   void ln_bwd(const void *dyp, const void *x, const void *stats, const void *gamma, const void *dres, void *dx,
               void *dgamma, void *dbeta, void *dxsum) {
     Buf ws = tmp(dp::reduce_ws_bytes((int)c.T, c.H));
+    dp::ReduceJob job{};
     prof_begin(DP_OPC_LN_BWD);
     if (live)
       check(dp::launch_ln_bwd(c.dtype, (int)c.T, c.H, dyp, x, (const float *)stats, gamma, dres, dx, dgamma, dbeta,
-                              dxsum, bptr(ws), cs));
+                              dxsum, bptr(ws), cs, &job));
     prof_end();
-    drop(ws);
+    defer_reduce(job, ws);
   }
 
   // dF = dG * gelu'(FC1_OUT) in place, plus db1 = column sums of dF
   void gelu_bwd(void *dg, const void *fc1_out, void *db1) {
     Buf ws = tmp(dp::reduce_ws_bytes((int)c.T, c.F));
+    dp::ReduceJob job{};
     prof_begin(DP_OPC_GELU_BWD);
     if (live)
-      check(dp::launch_gelu_bwd_colsum(c.dtype, c.gelu, (int)c.T, c.F, dg, fc1_out, dg, db1, bptr(ws), cs));
+      check(dp::launch_gelu_bwd_colsum(c.dtype, c.gelu, (int)c.T, c.F, dg, fc1_out, dg, db1, bptr(ws), cs, &job));
     prof_end();
-    drop(ws);
+    defer_reduce(job, ws);
   }
 
   // Runs forward op `d` of layer l; out_ptr[i] is where output i goes (null = not written).
@@ -768,7 +790,9 @@ struct Walk {
 #undef G_
       // whatever a replay left behind in this layer goes now
       for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) { slot_free(l, s); S(l, s).consumed = true; }
+      flush_reduces();
     }
+    flush_reduces();
   }
 
   // dQKV from dO; frees dO and the attention slots; also the QKV bias gradient.

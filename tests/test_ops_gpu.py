@@ -98,7 +98,9 @@ def test_colsum(dt, rows, cols):
 
 GEMM_SHAPES = [(1, 8, 8), (5, 16, 24), (64, 64, 64), (100, 72, 40), (128, 384, 128), (257, 136, 520),
                (300, 1600, 96), (512, 256, 1024), (1000, 520, 1032), (264, 136, 4104), (2048, 1024, 512),
-               (4096, 4096, 192), (3900, 4200, 128)]   # the last two take the 256x256-tile path
+               (4096, 4096, 192), (3900, 4200, 128),   # these two take the 256x256-tile path
+               # ragged edges on each tile size of the LDS-direct kernel, both forms (rows of 8 elements for TN)
+               (200, 328, 192), (1096, 1304, 256), (3904, 4200, 128)]
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
