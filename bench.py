@@ -122,6 +122,7 @@ def main():
                   "free_swaps": mrep["n_free_swaps"], "paid_swaps": mrep["n_paid_swaps"],
                   "recomputed": mrep["n_recomputed"], "refine_rounds": mrep["refine_rounds"]}
     _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
+    _, tight = B.plan_validate(run.bcfg, plan, budget_bytes=0)   # no budget: the tightest arena policy
     if args.copy_calibration:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
@@ -209,7 +210,8 @@ def main():
                                f"{cfg.n_heads} heads, ffn {cfg.ffn}, seq {cfg.seq}, micro-batch {cfg.micro_batch}, "
                                f"{'causal' if cfg.causal else 'full'} attention",
                    "plan": plan_name, "budget_bytes": budget, "validator_peak_bytes": rep["peak_bytes"],
-                   "arena_peak_bytes": rep["arena_peak_bytes"]},
+                   "arena_peak_bytes": rep["arena_peak_bytes"],
+                   "min_feasible_budget_bytes": tight["peak_bytes"]},
         "model_tflops": round(cfg.model_flops() / (ms * 1e-3) / 1e12, 2),
         "mfma_peak_frac": round(cfg.model_flops() / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "fwd_ms": round(stats["fwd_ms"], 4), "bwd_ms": round(stats["bwd_ms"], 4),
