@@ -64,7 +64,7 @@ template <int ROWB> __device__ __forceinline__ constexpr int tn_swizzle(int r) {
   return ROWB == 128 ? ((r >> 1) & 1) << 2 : (r & 3) << 2;
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK, bool SPLIT>
 __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amdgpu_flat_work_group_size(64 * WGM * WGN, 64 * WGM * WGN))) void gemm_dma_kernel(
     const bf16 *__restrict__ A, const bf16 *__restrict__ B, const bf16 *__restrict__ bias,
     const bf16 *__restrict__ res, bf16 *__restrict__ C, bf16 *__restrict__ C2, int gelu_kind, int M, int N, int K,
@@ -188,6 +188,89 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
+  constexpr int KS = BK / 16;
+  constexpr int TOTAL = KS * FM * FN;       // MFMAs of a step
+  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across steps");
+  bf16x8 a[2][FM], b[2][FN];
+  if constexpr (SPLIT) {
+    // ---- ring of five operand tiles ---------------------------------------------------
+    // A 256x256 k-step fills 64 KB of LDS, so only two whole stages fit, and the requests of
+    // a step then have less than one step to land.  With the A and B tiles as separate ring
+    // entries a fifth tile fits: slot (2k) % 5 holds A(k), slot (2k+1) % 5 holds B(k).  Step k
+    // reads A(k), B(k); B(k+1) goes, right at its start, into the slot A(k-1) has left, and
+    // A(k+2), spread over the rest of the step, into B(k-1)'s.  Half of the requests so have
+    // two steps to land and the other half is out early and short.
+    static_assert(BM == BN, "the ring entries are of one size");
+    constexpr unsigned TILE = A_BYTES;
+    auto req_a = [&](int i, unsigned slot) {
+      dma16(slot * TILE + lds_a + (unsigned)i * 1024u, voa[(wave * NIA + i) & 1], pa[i]);
+    };
+    auto req_b = [&](int i, unsigned slot) {
+      dma16(slot * TILE + (lds_b - (unsigned)A_BYTES) + (unsigned)i * 1024u, vob[(wave * NIB + i) & 1], pb[i]);
+    };
+    const unsigned da = TN ? BK * lda : BK * 2, db = TN ? BK * ldb : BK * 2;
+    auto adv_a = [&]() { voa[0] += da; voa[1] += da; };
+    auto adv_b = [&]() { vob[0] += db; vob[1] += db; };
+#pragma unroll
+    for (int i = 0; i < NIA; ++i) req_a(i, 0);
+    adv_a();
+#pragma unroll
+    for (int i = 0; i < NIB; ++i) req_b(i, 1);
+    adv_b();
+    if (nk > 1) {
+#pragma unroll
+      for (int i = 0; i < NIA; ++i) req_a(i, 2);
+      adv_a();
+    }
+    unsigned sa = 0, sbk = 1;   // slots of A(kt), B(kt)
+    // MORE_B: k-step kt+1 exists (its B tile is requested now; its A tile is already under way);
+    // MORE_A: k-step kt+2 exists (its A tile is requested now)
+    auto step = [&](auto more_b_tag, auto more_a_tag) {
+      constexpr bool MORE_B = decltype(more_b_tag)::value, MORE_A = decltype(more_a_tag)::value;
+      // A(kt) and B(kt) must have landed; A(kt+1), requested after B(kt), may still be pending
+      if (MORE_B) wait_vmcnt_mem<NIA>(); else wait_vmcnt_mem<0>();
+      __syncthreads();   // everyone's part is in, and everyone is done with A(kt-1), B(kt-1)
+      const unsigned base_a = sa * TILE, base_b = sbk * TILE - (unsigned)A_BYTES;   // (frag adds A_BYTES for B)
+      const unsigned to_b = (sbk + 2 >= 5 ? sbk + 2 - 5 : sbk + 2), to_a = (sa + 4 >= 5 ? sa + 4 - 5 : sa + 4);
+#pragma unroll
+      for (int i = 0; i < FM; ++i) a[0][i] = frag(base_a, i, 0, false);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) b[0][j] = frag(base_b, j, 0, true);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int c = ks & 1;
+        if (ks + 1 < KS) {
+#pragma unroll
+          for (int i = 0; i < FM; ++i) a[c ^ 1][i] = frag(base_a, i, ks + 1, false);
+#pragma unroll
+          for (int j = 0; j < FN; ++j) b[c ^ 1][j] = frag(base_b, j, ks + 1, true);
+        }
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+            const int g = (ks * FM + i) * FN + j;
+            // B(kt+1): one request behind each of the first NIB MFMAs; A(kt+2): evenly over the rest
+            if (MORE_B && g < NIB) req_b(g, to_b);
+            if (MORE_A) {
+              constexpr int SPAN = TOTAL - NIB;
+#pragma unroll
+              for (int q = 0; q < NIA; ++q)
+                if (NIB + ((q + 1) * SPAN + NIA - 1) / NIA - 1 == g) req_a(q, to_a);
+            }
+          }
+      }
+      if (MORE_B) adv_b();
+      if (MORE_A) adv_a();
+      sa = sa + 2 >= 5 ? sa + 2 - 5 : sa + 2;
+      sbk = sbk + 2 >= 5 ? sbk + 2 - 5 : sbk + 2;
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) step(std::true_type{}, std::true_type{});
+    if (kt + 1 < nk) { step(std::true_type{}, std::false_type{}); ++kt; }
+    if (kt < nk) step(std::false_type{}, std::false_type{});
+  } else {
   // prologue: stages 0 .. STAGES-2
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) {
@@ -200,14 +283,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
 
   int cur = 0;                 // ring slot of k-step kt
   int nxt = STAGES - 1;        // ring slot the requests of this step go to
-  constexpr int KS = BK / 16;
-  constexpr int TOTAL = KS * FM * FN;       // MFMAs of a step
-  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across steps");
   // LA (rings of three or more stages): the barrier at the top of step kt also covers stage
   // kt+1, so the last slice of a step can already fetch the first fragments of the next
   // one and the MFMAs run on across the barrier instead of waiting for LDS reads behind it.
   constexpr bool LA = STAGES >= 3;
-  bf16x8 a[2][FM], b[2][FN];
   auto first_frags = [&](unsigned sb) {
 #pragma unroll
     for (int i = 0; i < FM; ++i) a[0][i] = frag(sb, i, 0, false);
@@ -266,6 +345,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   for (; kt + 1 < nk; ++kt) step(std::false_type{}, std::true_type{});
   if (kt < nk) step(std::false_type{}, std::false_type{});
 
+  }
+
   // ---- epilogue ---------------------------------------------------------------------------
   // Accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block:
   // single elements per lane, 64 contiguous bytes per row and store.  Each wave therefore
@@ -278,7 +359,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   constexpr int RPI = 64 / LPR;          // rows per read/store instruction
   constexpr int EPI_BYTES = 32 * WN * 4; // one wave's 32 x WN fp32 block
   constexpr unsigned ESW = WN >= 64 ? 32u : 0u;   // (a 32-column block has no second half to swap with)
-  static_assert(NW * EPI_BYTES <= STAGES * STAGE_BYTES, "the epilogue reuses the operand stages");
+  static_assert(NW * EPI_BYTES <= (SPLIT ? 5 * A_BYTES : STAGES * STAGE_BYTES), "the epilogue reuses the operand stages");
   __syncthreads();                       // every wave is done with the operand stages
   unsigned char *ew = lds + (unsigned)wave * EPI_BYTES;
   const int orow = lane / LPR, oc4 = (lane % LPR) * 4;
@@ -330,12 +411,12 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK, bool SPLIT>
 hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
-  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * 2;
+  constexpr size_t smem = SPLIT ? (size_t)5 * BM * BK * 2 : (size_t)STAGES * (BM + BN) * BK * 2;
   static_assert(smem <= 160 * 1024, "LDS of one CU");
   static bool attr_set = false;
-  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, WIN, TN, BK>;
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, WIN, TN, BK, SPLIT>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -349,11 +430,11 @@ hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int WIN, bool TN, int BK = 64>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int WIN, bool TN, int BK = 64, bool SPLIT = false>
 hipError_t launch_dma_cfg(const GemmArgs &a, hipStream_t s) {
-  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, TN, BK>(a, s);   // no epilogue extras in this form
-  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, WIN, false, BK>(a, s)
-                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, false, BK>(a, s);
+  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, TN, BK, SPLIT>(a, s);   // no epilogue extras in this form
+  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, WIN, false, BK, SPLIT>(a, s)
+                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, false, BK, SPLIT>(a, s);
 }
 
 template <bool TN>
@@ -363,16 +444,17 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
   static const char *force = getenv("DPSTAGE_GEMM_TILE");
   const bool big_ok = a.M >= 256 && a.N >= 256;
   if (force != nullptr) {
-    if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
+    if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 1, TN, 64, true>(a, s);
+    if (!strcmp(force, "256x256s2") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
     if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
     if (!strcmp(force, "128x128w4")) return launch_dma_cfg<128, 128, 2, 2, 4, 1, TN>(a, s);
     if (!strcmp(force, "64x64")) return launch_dma_cfg<64, 64, 2, 2, 8, 1, TN>(a, s);
 
   }
-  // 256x256 (8 waves, 64x128 a wave; two stages fill the LDS, so its requests go out in the
-  // first quarter of a k-step) halves the L1 traffic per flop of 128x128 and wins as soon as
-  // it gives most CUs a workgroup; below that 128x128 with 8 waves and a four-stage ring.
-  if (big_ok && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
+  // 256x256 (8 waves, 64x128 a wave, ring of five operand tiles) halves the L1 traffic per
+  // flop of 128x128 and wins as soon as it gives most CUs a workgroup; below that 128x128
+  // with 8 waves and a four-stage ring.
+  if (big_ok && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, 1, TN, 64, true>(a, s);
   // a small output with a long contraction (the out-projection weight gradient) leaves most
   // CUs without a 128x128 tile: 64x64 tiles, several workgroups a CU, then run faster
   if (tiles(128, 128) <= 96) return launch_dma_cfg<64, 64, 2, 2, 8, 1, TN>(a, s);
