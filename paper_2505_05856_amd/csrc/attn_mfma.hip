@@ -17,6 +17,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace dp {
 
 namespace {
@@ -97,7 +99,7 @@ __device__ __forceinline__ void tile_store(bf16 *lds, int stride, const uint4 (&
 
 // ------------------------------------------------------------------ forward
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
+__global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
                                                                float *__restrict__ lse, int S, int nh, float scale) {
   constexpr int KS = DH + 8, VS = DH + 16, ND = DH / 32, NK = DH / 16;
   // LDS stages are picked by integer offsets into one array: selecting them through
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
   for (int d = 0; d < ND; ++d)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
-  float m = -1e30f, l = 0.f;
+  float m = -1e30f, l = 0.f;   // m: running maximum of the scaled logits (log2 domain)
 
   uint4 sk[DH / 32], sv[DH / 32];
   tile_load<DH>(sk, kb, ld, 0, S, tid);
@@ -146,51 +148,64 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
       tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
     }
     if (!CAUSAL || j0 <= iw0 + 31) {
-      f32x16 s[2];
-      float mx = -1e30f;
+      // MASK = false: every key of the tile exists and is visible to every query of the wave,
+      // so the per-element bounds and causal tests (a third of the softmax instructions) go
+      auto tile = [&](auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
+        f32x16 s[2];
+        float mx = -INFINITY;   // of the raw logits; the scale c > 0 is folded into the exponent below
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
+        for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s[sub][e] = 0.f;
+          for (int e = 0; e < 16; ++e) s[sub][e] = 0.f;
 #pragma unroll
-        for (int kd = 0; kd < NK; ++kd)
-          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, KS, sub * 32, kd * 16, lane), qf[kd],
-                                                           s[sub], 0, 0, 0);
+          for (int kd = 0; kd < NK; ++kd)
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, KS, sub * 32, kd * 16, lane), qf[kd],
+                                                             s[sub], 0, 0, 0);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int j = j0 + sub * 32 + acc_row(e, lane);
-          const bool masked = j >= S || (CAUSAL && j > qi);
-          s[sub][e] = masked ? -INFINITY : s[sub][e] * c;
-          mx = fmaxf(mx, s[sub][e]);
+          for (int e = 0; e < 16; ++e) {
+            if (MASK) {
+              const int j = j0 + sub * 32 + acc_row(e, lane);
+              if (j >= S || (CAUSAL && j > qi)) s[sub][e] = -INFINITY;
+            }
+            mx = fmaxf(mx, s[sub][e]);
+          }
         }
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);
-      const float alpha = fast_exp2(m - m_new);
-      m = m_new;
-      float ps = 0.f;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          s[sub][e] = fast_exp2(s[sub][e] - m_new);
-          ps += s[sub][e];
-        }
-      l = l * alpha + ps;
-#pragma unroll
-      for (int d = 0; d < ND; ++d)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[d][e] *= alpha;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 pf = pack8(s[sub], half * 8);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx * c);
+        // the running maximum moves in the first tiles and then hardly ever: skip the rescaling
+        // of the accumulators when it stayed put for every query of the wave
+        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+          const float alpha = fast_exp2(m - m_new);
+          l *= alpha;
 #pragma unroll
           for (int d = 0; d < ND; ++d)
-            acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(smem + cur + VOFF, VS, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[d][e] *= alpha;
+          m = m_new;
         }
+        float ps = 0.f;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            s[sub][e] = fast_exp2(__builtin_fmaf(s[sub][e], c, -m));
+            ps += s[sub][e];
+          }
+        l += ps;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const bf16x8 pf = pack8(s[sub], half * 8);
+#pragma unroll
+            for (int d = 0; d < ND; ++d)
+              acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  frag_cols(smem + cur + VOFF, VS, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
+          }
+      };
+      const bool interior = j0 + BKV <= S && (!CAUSAL || j0 + BKV - 1 <= iw0);
+      if (interior) tile(std::false_type{}); else tile(std::true_type{});
     }
     if (t + 1 < nkv) {
       tile_store<DH>(smem + nxt, KS, sk, tid);
@@ -267,8 +282,11 @@ __global__ __launch_bounds__(256) void attn_rowdot_kernel(const bf16 *__restrict
 }
 
 // dK, dV: the block owns 128 keys (32 per wave) and streams 64-query tiles of Q and dO.
+// (head dimension 128: both accumulators and both key-side fragments need more than the 256
+// registers two blocks a CU leave each wave, and spills on this path cost more than the
+// lost occupancy)
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
+__global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
                                                               const float *__restrict__ lse,
                                                               const bf16 *__restrict__ d_o,
                                                               const float *__restrict__ drow,
@@ -329,6 +347,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
     const float *lds_f = reinterpret_cast<const float *>(smem + cur + FOFF);
     if (t + 1 < nq) fetch(t + 1);
     if (!CAUSAL || i0 + BKV - 1 >= jw0) {
+      // MASK = false: the tile lies wholly below the diagonal for this wave's keys (or there is
+      // no mask), so the per-element causal test goes
+      auto tile = [&](auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         f32x16 s, dp;
@@ -351,7 +373,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
           for (int t4 = 0; t4 < 4; ++t4) {
             const int e = e4 * 4 + t4, i = i0 + r + t4;
             float p = fast_exp2(s[e] * c - lv[t4]);
-            if (CAUSAL && kj > i) p = 0.f;
+            if (MASK && kj > i) p = 0.f;   // (rows past the end carry lse = +inf: p = 0 by itself)
             s[e] = p;
             dp[e] = p * (dp[e] - dvv[t4]);
           }
@@ -368,6 +390,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(const bf16 *__rest
           }
         }
       }
+      };
+      if (CAUSAL && i0 < jw0 + 31) tile(std::true_type{}); else tile(std::false_type{});
     }
     if (t + 1 < nq) stash(nxt);
     __syncthreads();
@@ -445,6 +469,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
       tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
     }
     if (!CAUSAL || j0 <= iw0 + 31) {
+      // MASK = false: every key of the tile exists and is visible to every query of the wave
+      auto tile = [&](auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         f32x16 s, dp;
@@ -459,9 +486,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int j = j0 + sub * 32 + acc_row(e, lane);
           float p = fast_exp2(s[e] * c - lq);
-          if (j >= S || (CAUSAL && j > qi)) p = 0.f;
+          if (MASK) {
+            const int j = j0 + sub * 32 + acc_row(e, lane);
+            if (j >= S || (CAUSAL && j > qi)) p = 0.f;
+          }
           dp[e] = p * (dp[e] - dq_i);
         }
 #pragma unroll
@@ -473,6 +502,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
                 frag_cols(smem + cur, KS, sub * 32 + half * 16, d * 32, lane), dsf, dq[d], 0, 0, 0);
         }
       }
+      };
+      // (with head dimension 128 a second copy of the tile code costs more registers than there are)
+      if (DH != 64 || j0 + BKV > S || (CAUSAL && j0 + BKV - 1 > iw0)) tile(std::true_type{}); else tile(std::false_type{});
     }
     if (t + 1 < nkv) {
       tile_store<DH>(smem + nxt, KS, sk, tid);
