@@ -244,6 +244,41 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
                         size_t plan_len, uint64_t budget_bytes, void *y_out, void *dx_out,
                         const dp_layer_grads *dw, void *hip_stream, dp_step_stats *stats);
 
+/* The step split at the point where a one-forward-one-backward pipeline schedule
+ * splits it (Sections 1 and 4.1, Algorithm 1: stage x of l holds l - x micro-batches
+ * between their forward and their backward, and a partition is feasible when
+ * inflight * peak fits the device).
+ *
+ * dp_stage_forward runs the forward pass of one micro-batch under `plan` and
+ * leaves its saved tensors (kept on the device, or on their way to pinned host
+ * memory) in the micro-batch slot `slot` (0 <= slot < inflight <= 64).  Every
+ * slot owns an arena of the plan's validated size, a pinned pool and its events,
+ * allocated on first use and grown when a later plan needs more, so the device
+ * memory the slots hold is inflight * arena_peak_bytes; the plan is validated
+ * with this `inflight` against `budget_bytes` before anything is enqueued.
+ * dp_stage_backward runs the backward pass of the micro-batch in `slot` and
+ * frees the slot.  flags = 0 overwrites the gradients; DP_GRAD_ACCUMULATE adds
+ * this micro-batch's gradients to what `dw` holds (in fp32, rounded once to the
+ * config dtype), which is what a schedule does for every micro-batch after the
+ * first of an optimiser step.
+ *
+ * Buffers and layouts as dp_stage_step.  x_in may be reused once the forward's
+ * work on `hip_stream` has run; dy, dx_out and dw belong to the backward call.
+ * Errors: DP_E_INVAL for a slot that is out of range, still occupied (forward)
+ * or empty (backward), unknown flags, null buffers; the validator's errors
+ * from the forward.  Calls on one handle are made from one thread; a backward
+ * given another stream than its forward is ordered after it by an event.
+ * The forward first waits (on the host) for the backward that last used the
+ * slot, which bounds how far the host runs ahead to `inflight` micro-batches.
+ * y_out and dx_out are bit-identical to dp_stage_step's for every plan; so are
+ * the gradients of a backward with flags = 0. */
+enum { DP_GRAD_ACCUMULATE = 1 };
+dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const void *x_in,
+                           const uint8_t *plan, size_t plan_len, uint64_t budget_bytes, void *y_out,
+                           void *hip_stream);
+dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *dx_out,
+                            const dp_layer_grads *dw, uint32_t flags, void *hip_stream);
+
 /* Per-kernel-class timing of later steps: when enabled, every kernel launch is
  * bracketed by HIP events on the stream it runs on.  dp_stage_op_times waits
  * for the device, then returns (and clears) the summed milliseconds and launch
@@ -295,7 +330,8 @@ dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void 
 /* C[M,N] = op(A)*op(B) (+bias[N]) (+res[M,N]).  mode 0 ("NT"): A [M,K], B [N,K]
  * (both contraction-contiguous: forward with the transposed weight copy, and
  * dX = dY*W^T with W as stored); mode 1 ("TN"): A [K,M], B [K,N] (contraction
- * over the leading dimension of both: dW = X^T*dY). */
+ * over the leading dimension of both: dW = X^T*dY).  res may be C itself
+ * (C += op(A)*op(B), how gradients are accumulated); no other overlap. */
 dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
                      const void *bias, const void *res, void *C, void *hip_stream);
 /* out[cols] = sum over rows of x[rows, cols] */

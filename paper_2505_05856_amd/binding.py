@@ -109,6 +109,8 @@ def lib() -> C.CDLL:
     L.dp_plan_validate.argtypes = [C.POINTER(StageConfig), vp, sz, u64, C.c_uint32, C.POINTER(PlanReport)]
     L.dp_stage_init.argtypes = [C.POINTER(StageConfig), C.POINTER(LayerPtrs), u64, C.POINTER(vp)]
     L.dp_stage_step.argtypes = [vp, vp, vp, vp, sz, u64, vp, vp, C.POINTER(LayerPtrs), vp, C.POINTER(StepStats)]
+    L.dp_stage_forward.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, sz, u64, vp, vp]
+    L.dp_stage_backward.argtypes = [vp, C.c_uint32, vp, vp, C.POINTER(LayerPtrs), C.c_uint32, vp]
     L.dp_stage_set_profiling.argtypes = [vp, i32]
     L.dp_stage_op_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(u64)]
     L.dp_stage_set_debug.argtypes = [vp, C.c_uint32]
@@ -128,7 +130,7 @@ def lib() -> C.CDLL:
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
-    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_set_profiling",
+    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd"):
@@ -255,6 +257,21 @@ def stage_step(stage: Stage, x_in, dy, plan, budget_bytes, y_out, dx_out, grads:
                                _layer_array(grads), _stream_ptr(stream),
                                C.byref(stats) if want_stats else None))
     return stats.as_dict() if want_stats else None
+
+
+GRAD_ACCUMULATE = 1
+
+
+def stage_forward(stage: Stage, slot: int, inflight: int, x_in, plan, budget_bytes, y_out, stream=None):
+    keep, p, n = _plan_buf(plan)
+    _check(lib().dp_stage_forward(stage.handle, slot, inflight, _ptr(x_in), p, n, budget_bytes, _ptr(y_out),
+                                  _stream_ptr(stream)))
+
+
+def stage_backward(stage: Stage, slot: int, dy, dx_out, grads: Sequence[Dict[str, "object"]], flags: int = 0,
+                   stream=None):
+    _check(lib().dp_stage_backward(stage.handle, slot, _ptr(dy), _ptr(dx_out), _layer_array(grads), flags,
+                                   _stream_ptr(stream)))
 
 
 def stage_set_profiling(stage: Stage, enabled: bool):

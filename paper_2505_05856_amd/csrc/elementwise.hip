@@ -225,7 +225,8 @@ __global__ __launch_bounds__(1024) void reduce_jobs_kernel(ReduceJobTable t) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) tsum += red[i][cx];
     const int which = col / job.seg, k = col - which * job.seg;
-    stf((T *)(which == 0 ? job.out0 : which == 1 ? job.out1 : job.out2) + k, tsum);
+    T *dst = (T *)(which == 0 ? job.out0 : which == 1 ? job.out1 : job.out2) + k;
+    stf(dst, job.accumulate ? tsum + ldf(dst) : tsum);
   }
 }
 
@@ -375,7 +376,7 @@ hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x
 template <typename T>
 static hipError_t reduce_or_defer(const float *part, int nb, int width, int seg, void *o0, void *o1, void *o2,
                                   hipStream_t s, ReduceJob *job) {
-  if (job != nullptr) { *job = ReduceJob{part, nb, width, seg, o0, o1, o2}; return hipSuccess; }
+  if (job != nullptr) { *job = ReduceJob{part, nb, width, seg, o0, o1, o2, 0}; return hipSuccess; }
   hipLaunchKernelGGL((reduce_partials_kernel<T>), dim3((width + 63) / 64), dim3(1024), 0, s, part, nb, width, (T *)o0,
                      (T *)o1, (T *)o2, seg);
   return hipGetLastError();

@@ -364,6 +364,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   unsigned char *ew = lds + (unsigned)wave * EPI_BYTES;
   const int orow = lane / LPR, oc4 = (lane % LPR) * 4;
   const unsigned lane_off = ((unsigned)orow * (unsigned)N + (unsigned)oc4) * 2u;
+  // A tile that was shifted back stores only the part its unshifted position covers: the rest
+  // is its neighbour's (written once, so that C may also be the residual operand).
+  const int skip_rows = tm * BM - m0;
+  const bool col_owned = n0 + wn + oc4 >= tn * BN;
   float bv[4] = {0.f, 0.f, 0.f, 0.f};
   if (bias != nullptr) {
     const bf16x4 b4 = *reinterpret_cast<const bf16x4 *>(bias + n0 + wn + oc4);
@@ -389,6 +393,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
       const unsigned cc = (unsigned)oc4 ^ (ESW * ((rr >> 2) & 1u));
       const f32x4 t = *reinterpret_cast<const f32x4 *>(ew + (rr * WN + cc) * 4u);
       const size_t uoff = ((size_t)(m0 + wm + i * 32 + g * RPI) * (size_t)N + (size_t)(n0 + wn)) * 2 + lane_off;
+      if (!col_owned || wm + i * 32 + g * RPI + orow < skip_rows) continue;
       float v[4] = {t[0] + bv[0], t[1] + bv[1], t[2] + bv[2], t[3] + bv[3]};
       if (res != nullptr) {
         const bf16x4 r4 = *reinterpret_cast<const bf16x4 *>((const char *)res + uoff);

@@ -138,8 +138,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
   const int gsz = min(tiles_m - first_m, GM);
   const int tm = first_m + (pid % (GM * tiles_n)) % gsz;
   const int tn = (pid % (GM * tiles_n)) / gsz;
-  // Ragged last tiles are shifted back inside the matrix (they overlap their neighbour and
-  // store the same values twice) whenever the matrix is at least one tile tall/wide: then no
+  // Ragged last tiles are shifted back inside the matrix (they overlap their neighbour; each
+  // element is still stored once, by the tile whose unshifted position covers it) whenever the matrix is at least one tile tall/wide: then no
   // load of the fast path needs a guard.  Smaller matrices keep their origin and take the
   // guarded path below.
   const bool interior = M >= BM && N >= BN;
@@ -279,14 +279,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
     const int col = n0 + wn + j * 32 + (lane & 31);
-    if (col >= N) continue;
+    if (col >= N || col < tn * BN) continue;   // a shifted tile leaves its neighbour's part alone
     const float bv = bias != nullptr ? (float)bias[col] : 0.f;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = m0 + wm + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (row >= M) continue;
+        if (row >= M || row < tm * BM) continue;
         float v = acc[i][j][e] + bv;
         if (res != nullptr) v += (float)res[(long)row * N + col];
         const bf16 stored = (bf16)v;

@@ -56,6 +56,7 @@ struct ReduceJob {
   const float *part;
   int nb, width, seg;
   void *out0, *out1, *out2;
+  int accumulate = 0;   // add to what the outputs hold instead of overwriting (batched launch only)
 };
 constexpr int kMaxReduceJobs = 8;
 hipError_t launch_reduce_jobs(int dtype, const ReduceJob *jobs, int n, hipStream_t s);

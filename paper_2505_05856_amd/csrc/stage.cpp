@@ -17,6 +17,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <vector>
 
 namespace {
@@ -216,6 +217,22 @@ struct LayerW {  // library-owned device copies
 // separate kernel with its 16-byte accesses is the faster of the two, so it is the default.
 constexpr bool kFuseGeluDefault = false;
 
+namespace { struct Walk; }
+
+// One micro-batch between its forward and its backward (dp_stage_forward / dp_stage_backward):
+// its own arena, pinned pool and events, and the walk that holds where every saved tensor is.
+struct Flight {
+  Walk *walk = nullptr;          // non-null from forward to backward
+  std::vector<uint8_t> plan;
+  void *arena = nullptr;
+  uint64_t arena_bytes = 0;
+  void *host_pool = nullptr;
+  uint64_t host_bytes = 0;
+  std::vector<hipEvent_t> events;
+  uint64_t arena_peak = 0;
+  hipEvent_t done = nullptr;     // end of the slot's last backward
+};
+
 struct dp_stage {
   Cfg c;
   dp_stage_config pub;
@@ -235,6 +252,7 @@ struct dp_stage {
   size_t prof_used = 0;
   uint32_t debug = 0;
   bool use_mfma = true;
+  std::vector<std::unique_ptr<Flight>> flights;   // indexed by the caller's micro-batch slot
   // result of the last successful plan validation (a training loop repeats one plan)
   std::vector<uint8_t> cached_plan;
   uint64_t cached_budget = 0;
@@ -268,6 +286,10 @@ struct Walk {
   const uint8_t *plan;
   const bool live;
   dp_stage *st;             // live only
+  char *arena_base = nullptr;   // live only: where this walk's blocks and swapped copies live
+  char *host_base = nullptr;
+  std::vector<hipEvent_t> *evs = nullptr;
+  bool accumulate = false;      // weight gradients are added to what the caller's buffers hold
   hipStream_t cs = nullptr; // compute stream (caller's)
   hipStream_t d2h = nullptr, h2d = nullptr;
   const void *x_in = nullptr, *dy = nullptr;
@@ -318,7 +340,7 @@ struct Walk {
     if (l >= c.L || slot_is_alias(c, slot) || caller_owned(l, slot)) return DP_KEEP;
     return plan[(size_t)l * DP_SLOTS_PER_LAYER + slot];
   }
-  char *base() const { return live ? (char *)st->arena : nullptr; }
+  char *base() const { return live ? arena_base : nullptr; }
   void *ptr(int l, int slot) {
     if (slot == DP_SLOT_X_IN && l == 0) return const_cast<void *>(x_in);
     if (slot == DP_SLOT_X_IN && l == c.L) return y_out;
@@ -330,21 +352,21 @@ struct Walk {
   int new_event() {
     const int id = next_event++;
     if (live) {
-      while ((int)st->events.size() <= id) {
+      while ((int)evs->size() <= id) {
         hipEvent_t e;
         check(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        st->events.push_back(e);
+        evs->push_back(e);
       }
     }
     return id;
   }
   static int clock_of(hipStream_t s) { return (int)(intptr_t)s - 1; }
   void record(int ev, hipStream_t s) {
-    if (live) check(hipEventRecord(st->events[(size_t)ev], s));
+    if (live) check(hipEventRecord((*evs)[(size_t)ev], s));
     else if (cm) { if ((int)ev_ns.size() <= ev) ev_ns.resize((size_t)ev + 1, 0); ev_ns[(size_t)ev] = clk[clock_of(s)]; }
   }
   void wait(hipStream_t s, int ev) {
-    if (live) check(hipStreamWaitEvent(s, st->events[(size_t)ev], 0));
+    if (live) check(hipStreamWaitEvent(s, (*evs)[(size_t)ev], 0));
     else if (cm && ev < (int)ev_ns.size()) clk[clock_of(s)] = std::max(clk[clock_of(s)], ev_ns[(size_t)ev]);
   }
   static int64_t copy_ns(uint64_t bytes, uint64_t bytes_per_us) {
@@ -421,6 +443,7 @@ struct Walk {
     prof_begin(cls);
     if (live) {
       dp::GemmArgs a{mode, (int)M, (int)N, (int)K, A, B, bias, res, C};
+      if (cls == DP_OPC_GEMM_WGRAD && accumulate) a.res = C;   // dW += X^T dY
       a.C2 = gelu_out;
       a.gelu_kind = c.gelu;
       if (c.dtype == DP_BF16 && st->use_mfma && dp::gemm_mfma_supported(a)) check(dp::launch_gemm_mfma(a, cs));
@@ -433,7 +456,8 @@ struct Walk {
   // launch per layer instead of one small launch each; their partial buffers live until then.
   std::vector<dp::ReduceJob> red_jobs;
   std::vector<Buf> red_ws;
-  void defer_reduce(const dp::ReduceJob &j, const Buf &ws) {
+  void defer_reduce(dp::ReduceJob j, const Buf &ws) {
+    j.accumulate = accumulate ? 1 : 0;
     red_jobs.push_back(j);
     red_ws.push_back(ws);
     if ((int)red_ws.size() == dp::kMaxReduceJobs) flush_reduces();
@@ -540,7 +564,7 @@ struct Walk {
       const int produced = new_event();
       record(produced, cs);
       wait(d2h, produced);
-      if (live) check(hipMemcpyAsync((char *)st->host_pool + s.host_off, base() + s.off, bytes, hipMemcpyDeviceToHost, d2h));
+      if (live) check(hipMemcpyAsync(host_base + s.host_off, base() + s.off, bytes, hipMemcpyDeviceToHost, d2h));
       else clk[1] += copy_ns(bytes, cm->d2h_bytes_per_us);
       record(done, d2h);
     }
@@ -565,7 +589,7 @@ struct Walk {
       record(region_free, cs);
       wait(h2d, region_free);
       wait(h2d, s.out_event);   // the copy-out of this slot must have landed in the host pool
-      if (live) check(hipMemcpyAsync(base() + s.off, (char *)st->host_pool + s.host_off, bytes, hipMemcpyHostToDevice, h2d));
+      if (live) check(hipMemcpyAsync(base() + s.off, host_base + s.host_off, bytes, hipMemcpyHostToDevice, h2d));
       else clk[2] += copy_ns(bytes, cm->h2d_bytes_per_us);
       record(done, h2d);
     }
@@ -1204,6 +1228,34 @@ dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *laye
   return DP_OK;
 }
 
+// Memory a live walk needs; a resize waits for the device first.
+static dp_status ensure_memory(void **arena, uint64_t *arena_bytes, void **host_pool, uint64_t *host_bytes,
+                               const dp_plan_report &rep) {
+  if (rep.arena_peak_bytes > *arena_bytes) {
+    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
+    if (*arena) HIP_TRY(hipFree(*arena), DP_E_HIP);
+    *arena = nullptr; *arena_bytes = 0;
+    if (hipMalloc(arena, rep.arena_peak_bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      *arena = nullptr;
+      return fail(DP_E_DEVMEM, "cannot allocate a %llu-byte arena", (unsigned long long)rep.arena_peak_bytes);
+    }
+    *arena_bytes = rep.arena_peak_bytes;
+  }
+  if (rep.host_pinned_bytes > *host_bytes) {
+    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
+    if (*host_pool) HIP_TRY(hipHostFree(*host_pool), DP_E_HIP);
+    *host_pool = nullptr; *host_bytes = 0;
+    if (hipHostMalloc(host_pool, rep.host_pinned_bytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      *host_pool = nullptr;
+      return fail(DP_E_HOSTMEM, "cannot pin %llu bytes of host memory", (unsigned long long)rep.host_pinned_bytes);
+    }
+    *host_bytes = rep.host_pinned_bytes;
+  }
+  return DP_OK;
+}
+
 dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const uint8_t *plan, size_t plan_len,
                         uint64_t budget_bytes, void *y_out, void *dx_out, const dp_layer_grads *dw, void *hip_stream,
                         dp_step_stats *stats) {
@@ -1230,26 +1282,9 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     st->cached_budget = budget_bytes; st->cached_switches = switches;
     st->cached_report = rep; st->cached_hold = swap_hold;
   }
-  // memory the walk needs (a resize waits for the device first)
-  if (rep.arena_peak_bytes > st->arena_bytes) {
-    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
-    if (st->arena) HIP_TRY(hipFree(st->arena), DP_E_HIP);
-    st->arena = nullptr; st->arena_bytes = 0;
-    if (hipMalloc(&st->arena, rep.arena_peak_bytes) != hipSuccess) {
-      (void)hipGetLastError();
-      return fail(DP_E_DEVMEM, "cannot allocate a %llu-byte arena", (unsigned long long)rep.arena_peak_bytes);
-    }
-    st->arena_bytes = rep.arena_peak_bytes;
-  }
-  if (rep.host_pinned_bytes > st->host_bytes) {
-    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
-    if (st->host_pool) HIP_TRY(hipHostFree(st->host_pool), DP_E_HIP);
-    st->host_pool = nullptr; st->host_bytes = 0;
-    if (hipHostMalloc(&st->host_pool, rep.host_pinned_bytes, hipHostMallocDefault) != hipSuccess) {
-      (void)hipGetLastError();
-      return fail(DP_E_HOSTMEM, "cannot pin %llu bytes of host memory", (unsigned long long)rep.host_pinned_bytes);
-    }
-    st->host_bytes = rep.host_pinned_bytes;
+  {
+    const dp_status ms = ensure_memory(&st->arena, &st->arena_bytes, &st->host_pool, &st->host_bytes, rep);
+    if (ms != DP_OK) return ms;
   }
   hipStream_t cs = (hipStream_t)hip_stream;
   hipEvent_t &step_end = st->step_end[st->steps_issued % dp_stage::kStepsInFlight];
@@ -1261,6 +1296,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   if (rep.n_swapped_slots > 0)
     for (hipEvent_t e : st->step_end) if (e != nullptr && e != step_end) HIP_TRY(hipEventSynchronize(e), DP_E_HIP);
   Walk w(c, plan, true, st);
+  w.arena_base = (char *)st->arena; w.host_base = (char *)st->host_pool; w.evs = &st->events;
   w.mfma_enabled = st->use_mfma;
   w.fuse_gelu_enabled = fuse_gelu;
   w.swap_hold_ticks = swap_hold;
@@ -1300,6 +1336,91 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     stats->n_kernel_launches = w.n_launch; stats->n_replayed_ops = w.n_replayed;
     (void)hipEventDestroy(t0); (void)hipEventDestroy(t1); (void)hipEventDestroy(t2);
   }
+  return DP_OK;
+}
+
+// ---------------------------------------------------------------- forward and backward as separate calls
+namespace { constexpr uint32_t kMaxInflight = 64; }
+
+dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const void *x_in, const uint8_t *plan,
+                           size_t plan_len, uint64_t budget_bytes, void *y_out, void *hip_stream) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  if (!x_in || !y_out) return fail(DP_E_INVAL, "null buffer argument");
+  if (inflight < 1 || inflight > kMaxInflight) return fail(DP_E_INVAL, "inflight must be 1..%u", kMaxInflight);
+  if (slot >= inflight) return fail(DP_E_INVAL, "slot %u is not below inflight %u", slot, inflight);
+  const Cfg &c = st->c;
+  if (st->flights.size() <= slot) st->flights.resize((size_t)slot + 1);
+  if (!st->flights[slot]) st->flights[slot].reset(new Flight);
+  Flight &f = *st->flights[slot];
+  if (f.walk != nullptr) return fail(DP_E_INVAL, "slot %u still holds a micro-batch whose backward has not been called", slot);
+  const bool fuse_gelu = ((st->debug & 4u) != 0) != kFuseGeluDefault;
+  dp_plan_report rep;
+  long swap_hold = 0;
+  dp_status s = validate(c, plan, plan_len, budget_bytes, inflight, &rep, st->use_mfma, fuse_gelu, &swap_hold);
+  if (s != DP_OK) return s;
+  // the slot's last micro-batch has left its arena before the host runs further ahead
+  if (f.done != nullptr) HIP_TRY(hipEventSynchronize(f.done), DP_E_HIP);
+  s = ensure_memory(&f.arena, &f.arena_bytes, &f.host_pool, &f.host_bytes, rep);
+  if (s != DP_OK) return s;
+  f.plan.assign(plan, plan + plan_len);
+  f.arena_peak = rep.arena_peak_bytes;
+  Walk *w = new Walk(c, f.plan.data(), true, st);
+  w->arena_base = (char *)f.arena; w->host_base = (char *)f.host_pool; w->evs = &f.events;
+  w->mfma_enabled = st->use_mfma;
+  w->fuse_gelu_enabled = fuse_gelu;
+  w->swap_hold_ticks = swap_hold;
+  w->cs = (hipStream_t)hip_stream;
+  const bool serial = (st->debug & 1u) != 0;
+  w->d2h = serial ? w->cs : st->d2h;
+  w->h2d = serial ? w->cs : st->h2d;
+  w->x_in = x_in; w->y_out = y_out;
+  w->forward();
+  if (w->herr != hipSuccess) {
+    const hipError_t e = w->herr;
+    delete w;
+    return fail(DP_E_HIP, "stage_forward: %s", hipGetErrorString(e));
+  }
+  f.walk = w;
+  return DP_OK;
+}
+
+dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *dx_out, const dp_layer_grads *dw,
+                            uint32_t flags, void *hip_stream) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  if (!dy || !dx_out || !dw) return fail(DP_E_INVAL, "null buffer argument");
+  if ((flags & ~(uint32_t)DP_GRAD_ACCUMULATE) != 0) return fail(DP_E_INVAL, "unknown flag bits 0x%x", flags);
+  if (slot >= st->flights.size() || !st->flights[slot] || st->flights[slot]->walk == nullptr)
+    return fail(DP_E_INVAL, "slot %u holds no micro-batch (call dp_stage_forward first)", slot);
+  const Cfg &c = st->c;
+  for (int l = 0; l < c.L; ++l) {
+    void *const *p = reinterpret_cast<void *const *>(&dw[l]);
+    for (int i = 0; i < 12; ++i)
+      if (p[i] == nullptr) return fail(DP_E_INVAL, "gradient pointer %d of layer %d is null", i, l);
+  }
+  Flight &f = *st->flights[slot];
+  std::unique_ptr<Walk> w(f.walk);
+  f.walk = nullptr;                       // the slot is free again whatever happens below
+  hipStream_t cs = (hipStream_t)hip_stream;
+  const bool serial = (st->debug & 1u) != 0;
+  if (serial) { w->d2h = cs; w->h2d = cs; }
+  else if (cs != w->cs) {
+    // swap-outs and kernels of the forward were ordered on its stream; this one must follow them
+    const int j = w->new_event(); w->record(j, w->cs); w->wait(cs, j);
+  }
+  w->cs = cs;
+  w->dy = dy; w->dx_out = dx_out; w->dw = dw;
+  w->accumulate = (flags & DP_GRAD_ACCUMULATE) != 0;
+  w->backward();
+  if (!serial) {
+    const int j1 = w->new_event(); w->record(j1, st->d2h); w->wait(cs, j1);
+    const int j2 = w->new_event(); w->record(j2, st->h2d); w->wait(cs, j2);
+  }
+  if (w->herr != hipSuccess) return fail(DP_E_HIP, "stage_backward: %s", hipGetErrorString(w->herr));
+  if (f.done == nullptr) HIP_TRY(hipEventCreateWithFlags(&f.done, hipEventDisableTiming), DP_E_HIP);
+  HIP_TRY(hipEventRecord(f.done, cs), DP_E_HIP);
+  if (w->arena.high_water != f.arena_peak)
+    return fail(DP_E_HIP, "internal: live walk peak %llu differs from the validated %llu",
+                (unsigned long long)w->arena.high_water, (unsigned long long)f.arena_peak);
   return DP_OK;
 }
 
@@ -1409,6 +1530,14 @@ void dp_stage_destroy(dp_stage *st) {
   if (st->h2d) (void)hipStreamDestroy(st->h2d);
   if (st->arena) (void)hipFree(st->arena);
   if (st->host_pool) (void)hipHostFree(st->host_pool);
+  for (auto &f : st->flights) {
+    if (!f) continue;
+    delete f->walk;
+    for (hipEvent_t e : f->events) (void)hipEventDestroy(e);
+    if (f->done) (void)hipEventDestroy(f->done);
+    if (f->arena) (void)hipFree(f->arena);
+    if (f->host_pool) (void)hipHostFree(f->host_pool);
+  }
   if (st->weight_slab) (void)hipFree(st->weight_slab);
   delete st;
 }

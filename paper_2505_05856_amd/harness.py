@@ -64,3 +64,59 @@ class StageRunner:
 
     def close(self):
         self.stage.close()
+
+
+class ScheduleRunner:
+    """A stage handle plus device buffers for several micro-batches, driven event by event
+    through dp_stage_forward / dp_stage_backward.  Slot bookkeeping only."""
+
+    def __init__(self, cfg, weights: List[Dict[str, np.ndarray]], xs, dys, device="cuda:0"):
+        self.cfg, self.device = cfg, device
+        self.bcfg = to_binding_config(cfg)
+        self.w = [{k: upload(v, cfg, device) for k, v in layer.items()} for layer in weights]
+        self.x = [upload(x, cfg, device) for x in xs]
+        self.dy = [upload(d, cfg, device) for d in dys]
+        self.y = [torch.empty_like(x) for x in self.x]
+        self.dx = [torch.empty_like(x) for x in self.x]
+        self.g = [{k: torch.empty_like(v) for k, v in layer.items()} for layer in self.w]
+        torch.cuda.synchronize()
+        self.stage = B.stage_init(self.bcfg, self.w, 0)
+        self.slot_of: Dict[int, int] = {}
+
+    def poison_outputs(self):
+        for t in self.y + self.dx + [v for layer in self.g for v in layer.values()]:
+            t.fill_(float("nan"))
+
+    def forward(self, m: int, inflight: int, plan, budget_bytes: int = 0, stream=None):
+        slot = min(s for s in range(inflight + 1) if s not in self.slot_of.values())
+        B.stage_forward(self.stage, slot, inflight, self.x[m], plan, budget_bytes, self.y[m], stream=stream)
+        self.slot_of[m] = slot
+
+    def backward(self, m: int, accumulate: bool, stream=None):
+        slot = self.slot_of.pop(m)
+        B.stage_backward(self.stage, slot, self.dy[m], self.dx[m], self.g, B.GRAD_ACCUMULATE if accumulate else 0,
+                         stream=stream)
+
+    def run(self, order, inflight: int, plan, budget_bytes: int = 0):
+        """`order`: ("F", m) / ("B", m) events; `plan` one plan or one per micro-batch.
+        The first backward overwrites the gradients, the later ones accumulate."""
+        first = True
+        for kind, m in order:
+            if kind == "F":
+                self.forward(m, inflight, plan[m] if isinstance(plan, (list, tuple)) else plan, budget_bytes)
+            else:
+                self.backward(m, accumulate=not first)
+                first = False
+
+    def results(self):
+        torch.cuda.synchronize()
+        return ([download(t) for t in self.y], [download(t) for t in self.dx],
+                [{k: download(v) for k, v in layer.items()} for layer in self.g])
+
+    def raw_results(self):
+        torch.cuda.synchronize()
+        outs = self.y + self.dx + [layer[k] for layer in self.g for k in B.WEIGHT_FIELDS]
+        return [t.detach().clone().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu() for t in outs]
+
+    def close(self):
+        self.stage.close()

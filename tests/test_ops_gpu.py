@@ -119,6 +119,10 @@ def test_gemm(dt, mode, M, N, K):
     assert O.max_rel_err(host(c), ref) < TOL[dt]
     B.op_gemm(mode, M, N, K, ta, tb, dev(bias, dt), dev(res, dt), c)
     assert O.max_rel_err(host(c), ref + bias + res) < TOL[dt]
+    # res may be C itself (C += A B): every element is read and written by one lane, once
+    c = dev(res, dt)
+    B.op_gemm(mode, M, N, K, ta, tb, None, c, c)
+    assert O.max_rel_err(host(c), ref + res) < TOL[dt]
 
 
 ATTN_SHAPES = [(1, 8, 1, 8), (2, 5, 2, 16), (2, 64, 2, 64), (1, 200, 3, 64), (2, 96, 2, 128), (1, 384, 2, 64)]
