@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--no-op-times", action="store_true")
     ap.add_argument("--overlap", action="store_true",
                     help="also time the plan with its SWAP slots kept (compute only) and its copies alone")
+    ap.add_argument("--inflight", type=int, default=0,
+                    help="also time the steady state of a one-forward-one-backward schedule with this many "
+                         "micro-batches between forward and backward (dp_stage_forward / dp_stage_backward)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 4 times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -200,6 +203,32 @@ def main():
                    "definition": "(compute_only + copy_only - step) / min(compute_only, copy_only), clipped to [0,1]"}
         del dev, host
 
+    schedule = None
+    if args.inflight > 0:
+        # steady state of the schedule: backward of the oldest micro-batch, then the forward of the next into
+        # the slot it left; the budget covers every micro-batch in flight
+        k = args.inflight
+        for s in range(k):
+            B.stage_forward(run.stage, s, k, run.x, plan, k * budget, run.y)
+        def turn(i):
+            B.stage_backward(run.stage, i % k, run.dy, run.dx, run.g, B.GRAD_ACCUMULATE if i else 0)
+            B.stage_forward(run.stage, i % k, k, run.x, plan, k * budget, run.y)
+        for i in range(args.warmup):
+            turn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            turn(args.warmup + i)
+        torch.cuda.synchronize()
+        sms = (time.perf_counter() - t0) * 1e3 / args.steps
+        for s in range(k):
+            B.stage_backward(run.stage, s, run.dy, run.dx, run.g, B.GRAD_ACCUMULATE)
+        torch.cuda.synchronize()
+        schedule = {"inflight": k, "ms_per_micro_batch": round(sms, 4),
+                    "samples_per_s": round(cfg.micro_batch / (sms * 1e-3), 3),
+                    "budget_bytes": k * budget, "device_bytes_held": k * rep["arena_peak_bytes"],
+                    "vs_fused_step": round(ms / sms, 4)}
+
     out = {
         "metric": "stage fwd+bwd samples/sec + MFMA util % at fixed memory budget",
         "value": round(cfg.micro_batch / (ms * 1e-3), 3), "unit": "samples/s",
@@ -221,6 +250,8 @@ def main():
     }
     if overlap is not None:
         out["swap_overlap"] = overlap
+    if schedule is not None:
+        out["schedule"] = schedule
     if memopt is not None:
         memopt["measured_ms"] = round(ms, 4)
         out["memopt"] = memopt

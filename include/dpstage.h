@@ -268,8 +268,10 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
  * or empty (backward), unknown flags, null buffers; the validator's errors
  * from the forward.  Calls on one handle are made from one thread; a backward
  * given another stream than its forward is ordered after it by an event.
- * The forward first waits (on the host) for the backward that last used the
- * slot, which bounds how far the host runs ahead to `inflight` micro-batches.
+ * The forward is ordered (on the device) after the backward that last used the
+ * slot, and first waits on the host for the backward issued two calls earlier
+ * (under a plan that swaps: for the slot's last backward), which bounds how far
+ * the host runs ahead.
  * y_out and dx_out are bit-identical to dp_stage_step's for every plan; so are
  * the gradients of a backward with flags = 0. */
 enum { DP_GRAD_ACCUMULATE = 1 };
