@@ -281,6 +281,21 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
 dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *dx_out,
                             const dp_layer_grads *dw, uint32_t flags, void *hip_stream);
 
+/* New parameter values for the stage (an optimiser step happened).  The values
+ * are copied, on `hip_stream`, into a parameter version of the library's own
+ * (layout and pointers as dp_stage_init); every later dp_stage_step and
+ * dp_stage_forward uses it.  A micro-batch that is between its forward and its
+ * backward keeps the version its forward used, so that both passes see the same
+ * parameters while an asynchronous schedule updates them in between (Section 1:
+ * stage x of l keeps l - x parameter versions for that reason); a version's
+ * memory is reused once no slot holds it.  With no micro-batch in flight the
+ * current version is overwritten in place (ordered after its last reader).
+ * dp_stage_weight_versions returns how many versions are alive (held by a slot,
+ * or current): at most the micro-batches in flight plus one, each of
+ * dp_plan_report.weight_bytes. */
+dp_status dp_stage_set_weights(dp_stage *st, const dp_layer_weights *layers, void *hip_stream);
+int32_t dp_stage_weight_versions(const dp_stage *st);
+
 /* Per-kernel-class timing of later steps: when enabled, every kernel launch is
  * bracketed by HIP events on the stream it runs on.  dp_stage_op_times waits
  * for the device, then returns (and clears) the summed milliseconds and launch

@@ -111,6 +111,9 @@ def lib() -> C.CDLL:
     L.dp_stage_step.argtypes = [vp, vp, vp, vp, sz, u64, vp, vp, C.POINTER(LayerPtrs), vp, C.POINTER(StepStats)]
     L.dp_stage_forward.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, sz, u64, vp, vp]
     L.dp_stage_backward.argtypes = [vp, C.c_uint32, vp, vp, C.POINTER(LayerPtrs), C.c_uint32, vp]
+    L.dp_stage_set_weights.argtypes = [vp, C.POINTER(LayerPtrs), vp]
+    L.dp_stage_weight_versions.argtypes = [vp]
+    L.dp_stage_weight_versions.restype = i32
     L.dp_stage_set_profiling.argtypes = [vp, i32]
     L.dp_stage_op_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(u64)]
     L.dp_stage_set_debug.argtypes = [vp, C.c_uint32]
@@ -130,7 +133,7 @@ def lib() -> C.CDLL:
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
-    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_profiling",
+    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd"):
@@ -272,6 +275,14 @@ def stage_backward(stage: Stage, slot: int, dy, dx_out, grads: Sequence[Dict[str
                    stream=None):
     _check(lib().dp_stage_backward(stage.handle, slot, _ptr(dy), _ptr(dx_out), _layer_array(grads), flags,
                                    _stream_ptr(stream)))
+
+
+def stage_set_weights(stage: Stage, weights: Sequence[Dict[str, "object"]], stream=None):
+    _check(lib().dp_stage_set_weights(stage.handle, _layer_array(weights), _stream_ptr(stream)))
+
+
+def stage_weight_versions(stage: Stage) -> int:
+    return int(lib().dp_stage_weight_versions(stage.handle))
 
 
 def stage_set_profiling(stage: Stage, enabled: bool):

@@ -210,6 +210,17 @@ struct LayerW {  // library-owned device copies
   void *wt_qkv, *wt_o, *wt_fc1, *wt_fc2;   // transposed: [out, in]
 };
 
+// One version of the stage's parameters.  A micro-batch in flight keeps the version its forward
+// used (Section 1: an asynchronous schedule updates the parameters between a micro-batch's
+// forward and its backward, so a stage keeps one version per micro-batch in flight).
+struct WeightSet {
+  void *slab = nullptr;
+  std::vector<LayerW> w;
+  int refs = 0;                  // micro-batch slots holding this version
+  hipEvent_t ready = nullptr;    // upload finished
+  hipEvent_t last_use = nullptr; // end of the last pass that read it
+};
+
 }  // namespace
 
 // Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  The epilogue
@@ -223,6 +234,7 @@ namespace { struct Walk; }
 // its own arena, pinned pool and events, and the walk that holds where every saved tensor is.
 struct Flight {
   Walk *walk = nullptr;          // non-null from forward to backward
+  WeightSet *weights = nullptr;  // the parameter version its forward used
   std::vector<uint8_t> plan;
   void *arena = nullptr;
   uint64_t arena_bytes = 0;
@@ -240,9 +252,9 @@ struct Flight {
 struct dp_stage {
   Cfg c;
   dp_stage_config pub;
-  std::vector<LayerW> w;
-  void *weight_slab = nullptr;
-  uint64_t weight_bytes = 0;
+  std::vector<std::unique_ptr<WeightSet>> versions;
+  WeightSet *current = nullptr;     // what the next forward uses
+  uint64_t weight_bytes = 0;        // of one version
   void *arena = nullptr;
   uint64_t arena_bytes = 0;
   void *host_pool = nullptr;
@@ -295,6 +307,7 @@ struct Walk {
   char *arena_base = nullptr;   // live only: where this walk's blocks and swapped copies live
   char *host_base = nullptr;
   std::vector<hipEvent_t> *evs = nullptr;
+  const WeightSet *wts = nullptr;   // live only: the parameter version this micro-batch uses
   bool accumulate = false;      // weight gradients are added to what the caller's buffers hold
   hipStream_t cs = nullptr; // compute stream (caller's)
   hipStream_t d2h = nullptr, h2d = nullptr;
@@ -510,7 +523,7 @@ struct Walk {
 
   // Runs forward op `d` of layer l; out_ptr[i] is where output i goes (null = not written).
   void run_op(int l, const OpDef &d, void *out0, void *out1) {
-    const LayerW *w = live ? &st->w[(size_t)l] : nullptr;
+    const LayerW *w = live ? &wts->w[(size_t)l] : nullptr;
     const long T = c.T, H = c.H, F = c.F;
     auto in = [&](int i) { return ptr(l + d.in[i].dl, d.in[i].slot); };
     switch (d.op) {
@@ -693,7 +706,7 @@ struct Walk {
     prefetch_layer(c.L - 1);
     for (int l = c.L - 1; l >= 0; --l) {
       prefetch_layer(l - 1);
-      const LayerW *w = live ? &st->w[(size_t)l] : nullptr;
+      const LayerW *w = live ? &wts->w[(size_t)l] : nullptr;
       const dp_layer_grads *g = live ? &dw[l] : nullptr;
 #define W_(f) (live ? w->f : nullptr)
 #define G_(f) (live ? g->f : nullptr)
@@ -1167,48 +1180,48 @@ dp_status dp_plan_generate(const dp_stage_config *cfg, const dp_cost_model *cm, 
               (unsigned long long)r->validated_peak_bytes);
 }
 
-dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *layers, uint64_t arena_bytes_hint,
-                        dp_stage **out) {
-  if (out == nullptr) return fail(DP_E_INVAL, "out is null");
-  *out = nullptr;
-  Cfg c;
-  dp_status s = parse_cfg(cfg, &c);
-  if (s != DP_OK) return s;
-  if (layers == nullptr) return fail(DP_E_INVAL, "layers is null");
-  for (int l = 0; l < c.L; ++l) {
-    const void *const *p = reinterpret_cast<const void *const *>(&layers[l]);
-    for (int i = 0; i < 12; ++i)
-      if (p[i] == nullptr) return fail(DP_E_INVAL, "weight pointer %d of layer %d is null", i, l);
-  }
-  dp_stage *st = new dp_stage();
-  st->c = c;
-  st->pub = *cfg;
-  st->use_mfma = env_mfma_enabled();
+// Copies the caller's parameters (and the transposed matrices the kernels want) into a version
+// of their own, on `stream`; recycles a version nothing refers to any more, else allocates one.
+static dp_status upload_weights(dp_stage *st, const dp_layer_weights *layers, hipStream_t stream, WeightSet **out) {
+  const Cfg &c = st->c;
   uint64_t mats;
   const uint64_t per_layer = weight_elems_per_layer(c, &mats);
   // every tensor starts on a 256-byte boundary
   const uint64_t slab = ((per_layer + mats) * c.esz + 16 * 256) * (uint64_t)c.L;
-  if (hipMalloc(&st->weight_slab, slab) != hipSuccess) {
-    delete st;
-    return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the weights", (unsigned long long)slab);
-  }
   st->weight_bytes = slab;
-  char *cur = (char *)st->weight_slab;
+  WeightSet *ws = nullptr;
+  for (auto &v : st->versions)
+    if (v->refs == 0) { ws = v.get(); break; }   // also the current one: no micro-batch needs it any more
+  if (ws == nullptr) {
+    std::unique_ptr<WeightSet> fresh(new WeightSet);
+    if (hipMalloc(&fresh->slab, slab) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the weights", (unsigned long long)slab);
+    }
+    st->versions.push_back(std::move(fresh));
+    ws = st->versions.back().get();
+    HIP_TRY(hipEventCreateWithFlags(&ws->ready, hipEventDisableTiming), DP_E_HIP);
+    HIP_TRY(hipEventCreateWithFlags(&ws->last_use, hipEventDisableTiming), DP_E_HIP);
+  } else {
+    // its last reader may have run on another stream
+    HIP_TRY(hipStreamWaitEvent(stream, ws->last_use, 0), DP_E_HIP);
+  }
+  char *cur = (char *)ws->slab;
   auto take = [&](uint64_t elems) { void *p = cur; cur += (elems * c.esz + 255) / 256 * 256; return p; };
-  st->w.resize((size_t)c.L);
+  ws->w.assign((size_t)c.L, LayerW{});
   const uint64_t H = (uint64_t)c.H, F = (uint64_t)c.F;
   hipError_t e = hipSuccess;
   auto copy_vec = [&](void **dst, const void *src, uint64_t n) {
     *dst = take(n);
-    if (e == hipSuccess) e = hipMemcpyAsync(*dst, src, n * c.esz, hipMemcpyDeviceToDevice, nullptr);
+    if (e == hipSuccess) e = hipMemcpyAsync(*dst, src, n * c.esz, hipMemcpyDeviceToDevice, stream);
   };
   auto copy_mat = [&](void **dst, void **dst_t, const void *src, uint64_t rows, uint64_t cols) {
     copy_vec(dst, src, rows * cols);
     *dst_t = take(rows * cols);
-    if (e == hipSuccess) e = dp::launch_transpose(c.dtype, (int)rows, (int)cols, src, *dst_t, nullptr);
+    if (e == hipSuccess) e = dp::launch_transpose(c.dtype, (int)rows, (int)cols, src, *dst_t, stream);
   };
   for (int l = 0; l < c.L; ++l) {
-    LayerW &w = st->w[(size_t)l];
+    LayerW &w = ws->w[(size_t)l];
     const dp_layer_weights &s0 = layers[l];
     copy_vec(&w.ln1_g, s0.ln1_g, H); copy_vec(&w.ln1_b, s0.ln1_b, H);
     copy_vec(&w.b_qkv, s0.b_qkv, 3 * H); copy_vec(&w.b_o, s0.b_o, H);
@@ -1219,7 +1232,44 @@ dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *laye
     copy_mat(&w.w_fc1, &w.wt_fc1, s0.w_fc1, H, F);
     copy_mat(&w.w_fc2, &w.wt_fc2, s0.w_fc2, F, H);
   }
-  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e == hipSuccess) e = hipEventRecord(ws->ready, stream);
+  if (e == hipSuccess) e = hipEventRecord(ws->last_use, stream);
+  if (e != hipSuccess) return fail(DP_E_HIP, "weight upload: %s", hipGetErrorString(e));
+  *out = ws;
+  return DP_OK;
+}
+
+static dp_status check_layer_pointers(const Cfg &c, const dp_layer_weights *layers) {
+  if (layers == nullptr) return fail(DP_E_INVAL, "layers is null");
+  for (int l = 0; l < c.L; ++l) {
+    const void *const *p = reinterpret_cast<const void *const *>(&layers[l]);
+    for (int i = 0; i < 12; ++i)
+      if (p[i] == nullptr) return fail(DP_E_INVAL, "weight pointer %d of layer %d is null", i, l);
+  }
+  return DP_OK;
+}
+
+dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *layers, uint64_t arena_bytes_hint,
+                        dp_stage **out) {
+  if (out == nullptr) return fail(DP_E_INVAL, "out is null");
+  *out = nullptr;
+  Cfg c;
+  dp_status s = parse_cfg(cfg, &c);
+  if (s != DP_OK) return s;
+  s = check_layer_pointers(c, layers);
+  if (s != DP_OK) return s;
+  dp_stage *st = new dp_stage();
+  st->c = c;
+  st->pub = *cfg;
+  st->use_mfma = env_mfma_enabled();
+  hipError_t e = hipSuccess;
+  {
+    WeightSet *ws = nullptr;
+    s = upload_weights(st, layers, nullptr, &ws);
+    if (s != DP_OK) { dp_stage_destroy(st); return s; }
+    st->current = ws;
+    e = hipStreamSynchronize(nullptr);
+  }
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->d2h, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->h2d, hipStreamNonBlocking);
   if (e == hipSuccess && arena_bytes_hint > 0) {
@@ -1303,6 +1353,8 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     for (hipEvent_t e : st->step_end) if (e != nullptr && e != step_end) HIP_TRY(hipEventSynchronize(e), DP_E_HIP);
   Walk w(c, plan, true, st);
   w.arena_base = (char *)st->arena; w.host_base = (char *)st->host_pool; w.evs = &st->events;
+  w.wts = st->current;
+  HIP_TRY(hipStreamWaitEvent(cs, st->current->ready, 0), DP_E_HIP);
   w.mfma_enabled = st->use_mfma;
   w.fuse_gelu_enabled = fuse_gelu;
   w.swap_hold_ticks = swap_hold;
@@ -1326,6 +1378,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   }
   if (w.herr != hipSuccess) return fail(DP_E_HIP, "stage_step: %s", hipGetErrorString(w.herr));
   HIP_TRY(hipEventRecord(step_end, cs), DP_E_HIP);
+  HIP_TRY(hipEventRecord(st->current->last_use, cs), DP_E_HIP);
   ++st->steps_issued;
   if (w.arena.high_water != rep.arena_peak_bytes)
     return fail(DP_E_HIP, "internal: live walk peak %llu differs from the validated %llu",
@@ -1389,6 +1442,8 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   f.arena_peak = rep.arena_peak_bytes;
   Walk *w = new Walk(c, f.plan.data(), true, st);
   w->arena_base = (char *)f.arena; w->host_base = (char *)f.host_pool; w->evs = &f.events;
+  w->wts = st->current;
+  HIP_TRY(hipStreamWaitEvent((hipStream_t)hip_stream, st->current->ready, 0), DP_E_HIP);
   w->mfma_enabled = st->use_mfma;
   w->fuse_gelu_enabled = fuse_gelu;
   w->swap_hold_ticks = swap_hold;
@@ -1404,6 +1459,8 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
     return fail(DP_E_HIP, "stage_forward: %s", hipGetErrorString(e));
   }
   f.walk = w;
+  f.weights = st->current;       // held until the backward has been issued
+  ++f.weights->refs;
   return DP_OK;
 }
 
@@ -1423,6 +1480,9 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
   Flight &f = *st->flights[slot];
   std::unique_ptr<Walk> w(f.walk);
   f.walk = nullptr;                       // the slot is free again whatever happens below
+  WeightSet *wset = f.weights;
+  f.weights = nullptr;
+  --wset->refs;
   hipStream_t cs = (hipStream_t)hip_stream;
   const bool serial = (st->debug & 1u) != 0;
   if (serial) { w->d2h = cs; w->h2d = cs; }
@@ -1441,6 +1501,7 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
   if (w->herr != hipSuccess) return fail(DP_E_HIP, "stage_backward: %s", hipGetErrorString(w->herr));
   if (f.done == nullptr) HIP_TRY(hipEventCreateWithFlags(&f.done, hipEventDisableTiming), DP_E_HIP);
   HIP_TRY(hipEventRecord(f.done, cs), DP_E_HIP);
+  HIP_TRY(hipEventRecord(wset->last_use, cs), DP_E_HIP);
   hipEvent_t &ring = st->bwd_end[st->bwd_issued % 2];
   if (ring == nullptr) HIP_TRY(hipEventCreateWithFlags(&ring, hipEventDisableTiming), DP_E_HIP);
   HIP_TRY(hipEventRecord(ring, cs), DP_E_HIP);
@@ -1449,6 +1510,24 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
     return fail(DP_E_HIP, "internal: live walk peak %llu differs from the validated %llu",
                 (unsigned long long)w->arena.high_water, (unsigned long long)f.arena_peak);
   return DP_OK;
+}
+
+dp_status dp_stage_set_weights(dp_stage *st, const dp_layer_weights *layers, void *hip_stream) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  dp_status s = check_layer_pointers(st->c, layers);
+  if (s != DP_OK) return s;
+  WeightSet *ws = nullptr;
+  s = upload_weights(st, layers, (hipStream_t)hip_stream, &ws);
+  if (s != DP_OK) return s;
+  st->current = ws;
+  return DP_OK;
+}
+
+int32_t dp_stage_weight_versions(const dp_stage *st) {
+  if (st == nullptr) return 0;
+  int32_t n = 0;
+  for (const auto &v : st->versions) n += (v->refs > 0 || v.get() == st->current) ? 1 : 0;
+  return n;
 }
 
 dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled) {
@@ -1566,7 +1645,11 @@ void dp_stage_destroy(dp_stage *st) {
     if (f->arena) (void)hipFree(f->arena);
     if (f->host_pool) (void)hipHostFree(f->host_pool);
   }
-  if (st->weight_slab) (void)hipFree(st->weight_slab);
+  for (auto &v : st->versions) {
+    if (v->ready) (void)hipEventDestroy(v->ready);
+    if (v->last_use) (void)hipEventDestroy(v->last_use);
+    if (v->slab) (void)hipFree(v->slab);
+  }
   delete st;
 }
 

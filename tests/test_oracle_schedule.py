@@ -82,3 +82,62 @@ def test_a_schedule_with_a_missing_backward_is_rejected():
     cfg, st, w, xs, dys = micro_batches(2)
     with pytest.raises(AssertionError):
         O.stage_schedule(st, w, xs, dys, [("F", 0), ("F", 1), ("B", 0)])
+
+
+# ---------------------------------------------------------------- parameter versions (asynchronous schedule)
+def two_versions(n=2):
+    cfg, st, w0, xs, dys = micro_batches(n)
+    w1 = [{k: v.astype(np.float64) for k, v in d.items()} for d in syn.make_weights(cfg, seed=5, sigma=0.3)]
+    return cfg, st, [w0, w1], xs, dys
+
+
+def test_backward_differentiates_the_version_its_forward_used():
+    """Micro-batch 0 is fed under version 0, version 1 becomes current before its backward:
+    dX must be the gradient of <Y, dY> with version 0's parameters (central differences), and
+    is measurably not the gradient under version 1."""
+    cfg, st, vs, xs, dys = two_versions()
+    order = [("W", 0), ("F", 0), ("W", 1), ("F", 1), ("B", 0), ("B", 1)]
+    ys, dxs, grads, used, most = O.stage_schedule_async(st, vs, xs, dys, order)
+    assert used == [0, 1] and most == 2
+    rng = np.random.default_rng(3)
+    h = 1e-6
+    for m in (0, 1):
+        u = rng.normal(size=xs[m].shape)
+        def loss(ws, xx):
+            return float((O.stage_forward(st, ws, xx) * dys[m]).sum())
+        fd = {v: (loss(vs[v], xs[m] + h * u) - loss(vs[v], xs[m] - h * u)) / (2 * h) for v in (0, 1)}
+        got = float((dxs[m] * u).sum())
+        assert np.isclose(got, fd[used[m]], rtol=2e-6, atol=1e-7)
+        assert not np.isclose(got, fd[1 - used[m]], rtol=1e-3)
+        # and a parameter gradient, along a random direction of one matrix
+        d = rng.normal(size=vs[0][0]["w_fc1"].shape)
+        def shifted(ws, t):
+            out = [dict(layer) for layer in ws]
+            out[0]["w_fc1"] = out[0]["w_fc1"] + t * d
+            return out
+        fdw = (loss(shifted(vs[used[m]], h), xs[m]) - loss(shifted(vs[used[m]], -h), xs[m])) / (2 * h)
+        assert np.isclose(float((grads[m][0]["w_fc1"] * d).sum()), fdw, rtol=2e-6, atol=1e-7)
+
+
+def test_without_updates_in_flight_one_version_suffices():
+    cfg, st, vs, xs, dys = two_versions()
+    order = [("W", 0), ("F", 0), ("B", 0), ("W", 1), ("F", 1), ("B", 1)]
+    *_, used, most = O.stage_schedule_async(st, vs, xs, dys, order)
+    assert used == [0, 1] and most == 1
+
+
+@pytest.mark.parametrize("inflight", [1, 2, 3])
+def test_an_update_after_every_backward_needs_one_version_per_micro_batch_in_flight(inflight):
+    """Section 1: a stage with k micro-batches in flight keeps k parameter versions."""
+    n = 6
+    cfg, st, w, xs, dys = micro_batches(n, L=1, S=3, B=1)
+    versions = [w] * (n + 1)           # the values do not matter for the count
+    order, v = [("W", 0)], 0
+    for kind, m in O.one_f_one_b(n, inflight):
+        order.append((kind, m))
+        if kind == "B":
+            v += 1
+            order.append(("W", v))
+    *_, used, most = O.stage_schedule_async(st, versions, xs, dys, order)
+    assert most == inflight
+    assert used == [max(0, m - inflight + 1) for m in range(n)]

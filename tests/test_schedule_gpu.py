@@ -192,3 +192,73 @@ def test_c2_full_size_schedule():
     run.run(O.one_f_one_b(n, 3), 3, syn.plan_keep_all(cfg))
     assert all(torch.equal(a, b) for a, b in zip(bits, run.raw_results()))
     run.close()
+
+
+# ---------------------------------------------------------------- parameter versions
+def test_micro_batches_keep_the_parameter_version_of_their_forward():
+    """An update after every backward, three micro-batches in flight: every micro-batch's y, dx
+    and gradients are those of the version its forward saw (oracle), to the bit those of a fresh
+    stage built from that version; the library holds exactly `inflight` versions at steady state."""
+    cfg = SMALL[2]
+    n, inflight = 6, 3
+    _, xs, dys = make(cfg, n)
+    versions = [syn.make_weights(cfg, seed=20 + v, sigma=0.05) for v in range(n + 1)]
+    st = O.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
+                 cfg.causal, cfg.gelu, cfg.ln_eps)
+    order, v = [("W", 0)], 0
+    for kind, m in O.one_f_one_b(n, inflight):
+        order.append((kind, m))
+        if kind == "B":
+            v += 1
+            order.append(("W", v))
+    ref_y, ref_dx, ref_g, used, most = O.stage_schedule_async(st, versions, xs, dys, order)
+    assert most == inflight
+
+    from paper_2505_05856_amd.harness import upload
+    run = ScheduleRunner(cfg, versions[0], xs, dys)
+    plan = syn.plan_swap_ffn_recompute_norm_gelu(cfg)
+    dev_versions = [[{k: upload(a, cfg) for k, a in layer.items()} for layer in ver] for ver in versions]
+    grads_of = {}
+    alive = []
+    for kind, m in order:
+        if kind == "W":
+            B.stage_set_weights(run.stage, dev_versions[m])
+        elif kind == "F":
+            run.forward(m, inflight, plan)
+        else:
+            run.backward(m, accumulate=False)
+            torch.cuda.synchronize()
+            grads_of[m] = [{k: t.clone() for k, t in layer.items()} for layer in run.g]
+        alive.append(B.stage_weight_versions(run.stage))
+    assert max(alive) == inflight and alive[-1] == 1
+    torch.cuda.synchronize()
+    from paper_2505_05856_amd.harness import download
+    for m in range(n):
+        got = ([download(run.y[m])], [download(run.dx[m])], [{k: download(t) for k, t in layer.items()} for layer in grads_of[m]])
+        compare(cfg, got, ([ref_y[m]], [ref_dx[m]], ref_g[m]))
+        one = StageRunner(cfg, versions[used[m]], xs[m], dys[m])
+        one.step(plan)
+        torch.cuda.synchronize()
+        assert torch.equal(one.y, run.y[m]) and torch.equal(one.dx, run.dx[m])
+        assert all(torch.equal(one.g[l][k], grads_of[m][l][k]) for l in range(cfg.n_layers) for k in B.WEIGHT_FIELDS)
+        one.close()
+    run.close()
+
+
+def test_set_weights_with_nothing_in_flight_updates_in_place():
+    cfg = SMALL[0]
+    w0, xs, dys = make(cfg, 1)
+    w1 = syn.make_weights(cfg, seed=9, sigma=0.05)
+    from paper_2505_05856_amd.harness import upload
+    run = StageRunner(cfg, w0, xs[0], dys[0])
+    run.step(syn.plan_keep_all(cfg))
+    B.stage_set_weights(run.stage, [{k: upload(a, cfg) for k, a in layer.items()} for layer in w1])
+    assert B.stage_weight_versions(run.stage) == 1
+    run.poison_outputs()
+    run.step(syn.plan_all_recompute(cfg))
+    st = O.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
+                 cfg.causal, cfg.gelu, cfg.ln_eps)
+    y, dx, g = O.stage_step(st, w1, xs[0], dys[0])
+    gy, gdx, gg = run.results()
+    compare(cfg, ([gy], [gdx], gg), ([y], [dx], g))
+    run.close()
