@@ -73,7 +73,12 @@ enum {
  *   pre-LN : a=LN1(x); m=x+Attn(a*Wqkv+b)*Wo+bo; c=LN2(m); y=m+GELU(c*W1+b1)*W2+b2
  *   post-LN: r1=x+Attn(x*Wqkv+b)*Wo+bo; m=LN1(r1); r2=m+GELU(m*W1+b1)*W2+b2; y=LN2(r2)
  * The paper names the workloads only (BERT, GPT-2; Section 5.1); the layer
- * mathematics is the textbook one.  No dropout, no padding mask.
+ * mathematics is the textbook one.  No padding mask.  Dropout (off when both rates
+ * are 0) acts where those models apply it: on the attention probabilities
+ * (p_attn) and on the outputs of the attention projection and of FC2 before the
+ * residual add (p_hidden).  Whether an element is kept is a pure function of
+ * (seed, micro-batch counter, layer, site, position) -- see dp_stage_set_rng --
+ * so a recomputed tensor and the backward pass see the mask the forward saw.
  * dtype DP_BF16: weights, slots, outputs and gradients are bf16, accumulation
  * and statistics fp32.  DP_F32: everything fp32 (debug mode). */
 typedef struct {
@@ -83,6 +88,7 @@ typedef struct {
   int32_t gelu_kind;  /* dp_gelu_kind */
   int32_t dtype;      /* dp_dtype */
   float ln_eps;
+  float p_attn, p_hidden; /* dropout rates in [0, 1); 0 = none */
 } dp_stage_config;
 
 /* Device pointers.  Linear weights are [in, out] row-major (y = x*W + b);
@@ -126,7 +132,7 @@ typedef struct {
 /* Kernel classes for dp_stage_op_times. */
 enum {
   DP_OPC_GEMM_FWD = 0, DP_OPC_GEMM_DGRAD, DP_OPC_GEMM_WGRAD, DP_OPC_ATTN_FWD, DP_OPC_ATTN_BWD,
-  DP_OPC_LN_FWD, DP_OPC_LN_BWD, DP_OPC_GELU_FWD, DP_OPC_GELU_BWD, DP_OPC_REDUCE, DP_OPC_COUNT
+  DP_OPC_LN_FWD, DP_OPC_LN_BWD, DP_OPC_GELU_FWD, DP_OPC_GELU_BWD, DP_OPC_REDUCE, DP_OPC_DROPOUT, DP_OPC_COUNT
 };
 
 /* Number of plan bytes: n_layers * DP_SLOTS_PER_LAYER; 0 if cfg is invalid.
@@ -296,6 +302,15 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
 dp_status dp_stage_set_weights(dp_stage *st, const dp_layer_weights *layers, void *hip_stream);
 int32_t dp_stage_weight_versions(const dp_stage *st);
 
+/* Dropout state (only matters when the configuration has a non-zero rate).  A mask is a
+ * pure function of (seed, micro-batch number, layer, site, position): every dp_stage_step and
+ * dp_stage_forward takes the current micro-batch number and increments it, so successive
+ * micro-batches draw different masks, and a caller that sets (seed, counter) again gets the
+ * same masks again.  The generator (a keyed 32-bit integer mixer over the element index; an
+ * element is kept when its 32 bits are >= floor(p * 2^32), kept values are scaled by
+ * 1/(1-p)) is stated in full in csrc/common.h.  Defaults: seed 0, counter 0. */
+dp_status dp_stage_set_rng(dp_stage *st, uint64_t seed, uint64_t counter);
+
 /* Per-kernel-class timing of later steps: when enabled, every kernel launch is
  * bracketed by HIP events on the stream it runs on.  dp_stage_op_times waits
  * for the device, then returns (and clears) the summed milliseconds and launch
@@ -362,6 +377,28 @@ dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, i
 dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                               const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv,
                               void *ws, void *hip_stream);
+
+/* The same operations with dropout, as the stage applies it.  `drop` names the mask: rate,
+ * seed, micro-batch number and layer (see dp_stage_set_rng); p = 0 gives the plain operation.
+ * dp_op_dropout: y = (res ? res : 0) + mask * x / (1-p) over n elements (n a multiple of 8,
+ * below 2^32; x and res may be y), site 1 = after the attention projection, 2 = after FC2; the
+ * backward of a site is the same call on the gradient with res = NULL.
+ * Attention: the probabilities are masked and scaled after the softmax (lse is that of the
+ * plain softmax); the backward masks the same positions. */
+typedef struct {
+  float p;
+  uint64_t seed, micro_batch;
+  int32_t layer;
+} dp_dropout;
+dp_status dp_op_dropout(int32_t dtype, size_t n, const void *x, const void *res, void *y,
+                        const dp_dropout *drop, int32_t site, void *hip_stream);
+dp_status dp_op_attention_dropout_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh,
+                                      int32_t causal, const void *qkv, void *o, float *lse,
+                                      const dp_dropout *drop, void *hip_stream);
+dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh,
+                                      int32_t causal, const void *qkv, const void *o, const float *lse,
+                                      const void *d_o, void *dqkv, void *ws, const dp_dropout *drop,
+                                      void *hip_stream);
 
 #ifdef __cplusplus
 }

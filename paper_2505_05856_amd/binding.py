@@ -21,7 +21,7 @@ WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 SLOTS_PER_LAYER = 12
 OP_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd",
-              "ln_fwd", "ln_bwd", "gelu_fwd", "gelu_bwd", "reduce")
+              "ln_fwd", "ln_bwd", "gelu_fwd", "gelu_bwd", "reduce", "dropout")
 STATUS = {0: "DP_OK", -1: "DP_E_INVAL", -2: "DP_E_PLAN", -3: "DP_E_BUDGET", -4: "DP_E_DEVMEM",
           -5: "DP_E_HOSTMEM", -6: "DP_E_HIP", -7: "DP_E_UNSUPPORTED"}
 
@@ -35,7 +35,8 @@ class DpError(RuntimeError):
 
 class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "micro_batch",
-                                         "norm_style", "causal", "gelu_kind", "dtype")] + [("ln_eps", C.c_float)]
+                                         "norm_style", "causal", "gelu_kind", "dtype")] + [("ln_eps", C.c_float), ("p_attn", C.c_float),
+                                                                                 ("p_hidden", C.c_float)]
 
 
 class LayerPtrs(C.Structure):
@@ -111,6 +112,7 @@ def lib() -> C.CDLL:
     L.dp_stage_step.argtypes = [vp, vp, vp, vp, sz, u64, vp, vp, C.POINTER(LayerPtrs), vp, C.POINTER(StepStats)]
     L.dp_stage_forward.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, sz, u64, vp, vp]
     L.dp_stage_backward.argtypes = [vp, C.c_uint32, vp, vp, C.POINTER(LayerPtrs), C.c_uint32, vp]
+    L.dp_stage_set_rng.argtypes = [vp, u64, u64]
     L.dp_stage_set_weights.argtypes = [vp, C.POINTER(LayerPtrs), vp]
     L.dp_stage_weight_versions.argtypes = [vp]
     L.dp_stage_weight_versions.restype = i32
@@ -129,14 +131,17 @@ def lib() -> C.CDLL:
     L.dp_op_colsum.argtypes = [i32, i32, i32, vp, vp, vp, vp]
     L.dp_op_attention_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.dp_op_attention_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.dp_op_dropout.argtypes = [i32, sz, vp, vp, vp, vp, i32, vp]
+    L.dp_op_attention_dropout_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.dp_op_attention_dropout_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dp_plan_cost.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), vp, sz, u64, C.POINTER(PlanCostReport)]
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
-    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_profiling",
+    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
-                 "dp_op_attention_bwd"):
+                 "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd"):
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -148,10 +153,10 @@ def _check(code: int):
 
 
 def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, norm_style="post", causal=False,
-                gelu="erf", dtype="bf16", ln_eps=1e-5) -> StageConfig:
+                gelu="erf", dtype="bf16", ln_eps=1e-5, p_attn=0.0, p_hidden=0.0) -> StageConfig:
     return StageConfig(n_layers, hidden, n_heads, ffn, seq, micro_batch,
                        {"post": 0, "pre": 1}[norm_style], int(bool(causal)), {"erf": 0, "tanh": 1}[gelu],
-                       {"f32": 0, "bf16": 1}[dtype], ln_eps)
+                       {"f32": 0, "bf16": 1}[dtype], ln_eps, p_attn, p_hidden)
 
 
 def _plan_buf(plan):
@@ -281,6 +286,10 @@ def stage_set_weights(stage: Stage, weights: Sequence[Dict[str, "object"]], stre
     _check(lib().dp_stage_set_weights(stage.handle, _layer_array(weights), _stream_ptr(stream)))
 
 
+def stage_set_rng(stage: Stage, seed: int, counter: int):
+    _check(lib().dp_stage_set_rng(stage.handle, seed, counter))
+
+
 def stage_weight_versions(stage: Stage) -> int:
     return int(lib().dp_stage_weight_versions(stage.handle))
 
@@ -353,3 +362,28 @@ def op_attention_fwd(qkv, B, S, nh, dh, causal, o, lse, stream=None):
 def op_attention_bwd(qkv, o, lse, d_o, B, S, nh, dh, causal, dqkv, ws, stream=None):
     _check(lib().dp_op_attention_bwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv), _ptr(o), _ptr(lse), _ptr(d_o),
                                      _ptr(dqkv), _ptr(ws), _stream_ptr(stream)))
+
+
+class Dropout(C.Structure):
+    """Which mask: rate, seed, micro-batch number, layer (dp_dropout)."""
+    _fields_ = [("p", C.c_float), ("seed", C.c_uint64), ("micro_batch", C.c_uint64), ("layer", C.c_int32)]
+
+
+SITE_PROJ, SITE_FC2 = 1, 2
+
+
+def op_dropout(x, res, y, drop: Dropout, site: int, stream=None):
+    _check(lib().dp_op_dropout(_dt(x), x.numel(), _ptr(x), _ptr(res) if res is not None else None, _ptr(y),
+                               C.byref(drop), site, _stream_ptr(stream)))
+
+
+def op_attention_dropout_fwd(qkv, B, S, nh, dh, causal, o, lse, drop: Dropout, stream=None):
+    _check(lib().dp_op_attention_dropout_fwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv),
+                                             _ptr(o) if o is not None else None,
+                                             _ptr(lse) if lse is not None else None, C.byref(drop),
+                                             _stream_ptr(stream)))
+
+
+def op_attention_dropout_bwd(qkv, o, lse, d_o, B, S, nh, dh, causal, dqkv, ws, drop: Dropout, stream=None):
+    _check(lib().dp_op_attention_dropout_bwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv), _ptr(o), _ptr(lse),
+                                             _ptr(d_o), _ptr(dqkv), _ptr(ws), C.byref(drop), _stream_ptr(stream)))

@@ -98,9 +98,12 @@ __device__ __forceinline__ void tile_store(bf16 *lds, int stride, const uint4 (&
 }
 
 // ------------------------------------------------------------------ forward
-template <int DH, bool CAUSAL>
+// DROP: the probabilities are masked after the softmax (the row sums and the log-sum-exp are
+// those of the plain softmax); the scale 1/(1-p) goes into the final normalisation.
+template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
-                                                               float *__restrict__ lse, int S, int nh, float scale) {
+                                                               float *__restrict__ lse, int S, int nh, float scale,
+                                                               DropArgs da) {
   constexpr int KS = DH + 8, VS = DH + 16, ND = DH / 32, NK = DH / 16;
   // LDS stages are picked by integer offsets into one array: selecting them through
   // pointer arrays makes the pointers generic and the fragment reads flat loads.
@@ -118,6 +121,8 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
   const bf16 *kb = qb + H, *vb = qb + 2 * H;
   const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
   const float c = scale * kLog2e;
+  const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
+  const uint32_t qidx = (uint32_t)qi * (uint32_t)S;   // index of (query qi, key 0) in the head's S x S matrix
 
   bf16x8 qf[NK];
 #pragma unroll
@@ -193,6 +198,14 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
             ps += s[sub][e];
           }
         l += ps;
+        if (DROP) {
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              if (drop_bits(qidx + (uint32_t)(j0 + sub * 32 + acc_row(e, lane)), keys.k0, keys.k1) < da.thr)
+                s[sub][e] = 0.f;
+        }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -218,7 +231,7 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
   if (qi >= S) return;
   if (lse != nullptr && hh == 0) lse[((long)b * nh + h) * S + qi] = (m + __log2f(l)) * kLn2;
   if (o == nullptr) return;
-  const float inv = 1.0f / l;
+  const float inv = (DROP ? da.scale : 1.0f) / l;
   bf16 *orow = o + ((long)b * S + qi) * H + (long)h * DH;
 #pragma unroll
   for (int d = 0; d < ND; ++d)
@@ -231,30 +244,35 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
     }
 }
 
+template <typename K>
+hipError_t set_smem(K kern, size_t smem) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)smem);
+}
+
 template <int DH>
-hipError_t fwd_launch(int B, int S, int nh, int causal, const void *qkv, void *o, float *lse, hipStream_t s) {
+hipError_t fwd_launch(int B, int S, int nh, int causal, const void *qkv, void *o, float *lse, const DropArgs *drop,
+                      hipStream_t s) {
   constexpr size_t smem = 2 * (size_t)BKV * ((DH + 8) + (DH + 16)) * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_mfma_kernel<DH, true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_mfma_kernel<DH, false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = set_smem(attn_fwd_mfma_kernel<DH, true, false>, smem);
+    if (e == hipSuccess) e = set_smem(attn_fwd_mfma_kernel<DH, false, false>, smem);
+    if (e == hipSuccess) e = set_smem(attn_fwd_mfma_kernel<DH, true, true>, smem);
+    if (e == hipSuccess) e = set_smem(attn_fwd_mfma_kernel<DH, false, true>, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const dim3 grid(((S + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
-  if (causal)
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH, true>), grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S,
-                       nh, scale);
-  else
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<DH, false>), grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S,
-                       nh, scale);
+  const bool dropping = drop != nullptr && drop->thr != 0;
+  const DropArgs da = dropping ? *drop : DropArgs{0u, 0u, 1.f};
+#define DP_FWD(KERN) hipLaunchKernelGGL(KERN, grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S, nh, scale, da)
+  if (dropping) { if (causal) DP_FWD((attn_fwd_mfma_kernel<DH, true, true>)); else DP_FWD((attn_fwd_mfma_kernel<DH, false, true>)); }
+  else { if (causal) DP_FWD((attn_fwd_mfma_kernel<DH, true, false>)); else DP_FWD((attn_fwd_mfma_kernel<DH, false, false>)); }
+#undef DP_FWD
   return hipGetLastError();
 }
-
 
 // ------------------------------------------------------------------ backward
 // D[b,h,i] = <dO_i, O_i> over the head's DH columns; one thread per 8 columns.
@@ -285,12 +303,13 @@ __global__ __launch_bounds__(256) void attn_rowdot_kernel(const bf16 *__restrict
 // (head dimension 128: both accumulators and both key-side fragments need more than the 256
 // registers two blocks a CU leave each wave, and spills on this path cost more than the
 // lost occupancy)
-template <int DH, bool CAUSAL>
+template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
                                                               const float *__restrict__ lse,
                                                               const bf16 *__restrict__ d_o,
                                                               const float *__restrict__ drow,
-                                                              bf16 *__restrict__ dqkv, int S, int nh, float scale) {
+                                                              bf16 *__restrict__ dqkv, int S, int nh, float scale,
+                                                              DropArgs da) {
   constexpr int QS = DH + 16, ND = DH / 32, NK = DH / 16;
   // stage s: Q tile, dO tile (bf16), then 64 log-sum-exp and 64 row-dot floats
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
@@ -308,6 +327,9 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
   const float *lrow = lse + ((long)b * nh + h) * S, *drw = drow + ((long)b * nh + h) * S;
   const int j0 = kt * BROWS, jw0 = j0 + wave * 32, kj = jw0 + (lane & 31);
   const float c = scale * kLog2e;
+  // DROP: the forward multiplied V by P' = mask * P / (1-p): dV takes P', and dP is masked and
+  // scaled the same way before the softmax derivative (which is that of the plain P).
+  const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
 
   bf16x8 kf[NK], vf[NK];
 #pragma unroll
@@ -374,8 +396,14 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
             const int e = e4 * 4 + t4, i = i0 + r + t4;
             float p = fast_exp2(s[e] * c - lv[t4]);
             if (MASK && kj > i) p = 0.f;   // (rows past the end carry lse = +inf: p = 0 by itself)
-            s[e] = p;
-            dp[e] = p * (dp[e] - dvv[t4]);
+            if (DROP) {
+              const bool keep = drop_bits((uint32_t)i * (uint32_t)S + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
+              s[e] = keep ? p * da.scale : 0.f;
+              dp[e] = p * ((keep ? dp[e] * da.scale : 0.f) - dvv[t4]);
+            } else {
+              s[e] = p;
+              dp[e] = p * (dp[e] - dvv[t4]);
+            }
           }
         }
 #pragma unroll
@@ -413,12 +441,13 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
 }
 
 // dQ: the block owns 128 queries (32 per wave) and streams 64-key tiles of K and V.
-template <int DH, bool CAUSAL>
+template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv,
                                                              const float *__restrict__ lse,
                                                              const bf16 *__restrict__ d_o,
                                                              const float *__restrict__ drow,
-                                                             bf16 *__restrict__ dqkv, int S, int nh, float scale) {
+                                                             bf16 *__restrict__ dqkv, int S, int nh, float scale,
+                                                             DropArgs da) {
   constexpr int KS = DH + 16, VS = DH + 8, ND = DH / 32, NK = DH / 16;
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
@@ -443,6 +472,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
     qf[kd] = as_frag(qi < S ? ld16(qb + (long)qi * ld + kd * 16 + 8 * hh) : z);
     gf[kd] = as_frag(qi < S ? ld16(dob + (long)qi * H + kd * 16 + 8 * hh) : z);
   }
+  const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
+  const uint32_t qidx = (uint32_t)qi * (uint32_t)S;
   const float lq = qi < S ? lse[((long)b * nh + h) * S + qi] * kLog2e : INFINITY;
   const float dq_i = qi < S ? drow[((long)b * nh + h) * S + qi] : 0.f;
 
@@ -491,7 +522,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
             const int j = j0 + sub * 32 + acc_row(e, lane);
             if (j >= S || (CAUSAL && j > qi)) p = 0.f;
           }
-          dp[e] = p * (dp[e] - dq_i);
+          if (DROP) {
+            const bool keep =
+                drop_bits(qidx + (uint32_t)(j0 + sub * 32 + acc_row(e, lane)), keys.k0, keys.k1) >= da.thr;
+            dp[e] = p * ((keep ? dp[e] * da.scale : 0.f) - dq_i);
+          } else {
+            dp[e] = p * (dp[e] - dq_i);
+          }
         }
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
@@ -526,23 +563,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
     }
 }
 
-template <typename K>
-hipError_t set_smem(K kern, size_t smem) {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)smem);
-}
-
 template <int DH>
 hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const void *o, const float *lse,
-                      const void *d_o, void *dqkv, float *ws, hipStream_t s) {
+                      const void *d_o, void *dqkv, float *ws, const DropArgs *drop, hipStream_t s) {
   constexpr size_t smem_kv = 4 * (size_t)BKV * (DH + 16) * sizeof(bf16) + 4 * BKV * sizeof(float);
   constexpr size_t smem_q = 2 * (size_t)BKV * ((DH + 16) + (DH + 8)) * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = set_smem(attn_bwd_dkv_kernel<DH, true>, smem_kv);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<DH, false>, smem_kv);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, true>, smem_q);
-    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, false>, smem_q);
+    hipError_t e = set_smem(attn_bwd_dkv_kernel<DH, true, false>, smem_kv);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<DH, false, false>, smem_kv);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<DH, true, true>, smem_kv);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<DH, false, true>, smem_kv);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, true, false>, smem_q);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, false, false>, smem_q);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, true, true>, smem_q);
+    if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<DH, false, true>, smem_q);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -554,13 +589,19 @@ hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const v
   if (e != hipSuccess) return e;
   const dim3 grid(((S + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
+  const bool dropping = drop != nullptr && drop->thr != 0;
+  const DropArgs da = dropping ? *drop : DropArgs{0u, 0u, 1.f};
 #define DP_BWD(KERN, SMEM)                                                                              \
   hipLaunchKernelGGL(KERN, grid, block, SMEM, s, (const bf16 *)qkv, lse, (const bf16 *)d_o, (const float *)ws, \
-                     (bf16 *)dqkv, S, nh, scale)
-  if (causal) DP_BWD((attn_bwd_dkv_kernel<DH, true>), smem_kv); else DP_BWD((attn_bwd_dkv_kernel<DH, false>), smem_kv);
+                     (bf16 *)dqkv, S, nh, scale, da)
+#define DP_BWD4(NAME, SMEM)                                                                             \
+  if (dropping) { if (causal) DP_BWD((NAME<DH, true, true>), SMEM); else DP_BWD((NAME<DH, false, true>), SMEM); } \
+  else { if (causal) DP_BWD((NAME<DH, true, false>), SMEM); else DP_BWD((NAME<DH, false, false>), SMEM); }
+  DP_BWD4(attn_bwd_dkv_kernel, smem_kv)
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (causal) DP_BWD((attn_bwd_dq_kernel<DH, true>), smem_q); else DP_BWD((attn_bwd_dq_kernel<DH, false>), smem_q);
+  DP_BWD4(attn_bwd_dq_kernel, smem_q)
+#undef DP_BWD4
 #undef DP_BWD
   return hipGetLastError();
 }
@@ -570,17 +611,18 @@ hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const v
 bool attn_mfma_supported(int S, int dh) { return S >= 1 && (dh == 64 || dh == 128); }
 
 hipError_t launch_attn_fwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, void *o, float *lse,
-                                hipStream_t s) {
+                                hipStream_t s, const DropArgs *drop) {
   if ((long)B * S * nh == 0) return hipSuccess;
-  return dh == 64 ? fwd_launch<64>(B, S, nh, causal, qkv, o, lse, s)
-                  : fwd_launch<128>(B, S, nh, causal, qkv, o, lse, s);
+  return dh == 64 ? fwd_launch<64>(B, S, nh, causal, qkv, o, lse, drop, s)
+                  : fwd_launch<128>(B, S, nh, causal, qkv, o, lse, drop, s);
 }
 
 hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o,
-                                const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s) {
+                                const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s,
+                                const DropArgs *drop) {
   if ((long)B * S * nh == 0) return hipSuccess;
-  return dh == 64 ? bwd_launch<64>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, s)
-                  : bwd_launch<128>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, s);
+  return dh == 64 ? bwd_launch<64>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, drop, s)
+                  : bwd_launch<128>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, drop, s);
 }
 
 }  // namespace dp

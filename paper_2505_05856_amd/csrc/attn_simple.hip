@@ -2,6 +2,9 @@
 // (forward, dQ) or per key row (dK, dV).  This is the fp32 debug mode's
 // attention and the fallback for shapes the MFMA kernels do not take.
 // Scores of one row live in LDS (4 bytes x S per wave), so S <= 4096.
+// Dropout (da.thr != 0): element (i, j) of head (b, h) is kept when
+// drop_bits(i*S + j, keys of unit b*nh + h) >= da.thr; kept probabilities are scaled by
+// da.scale after the softmax, and the backward masks and scales dP the same way.
 #include "common.h"
 #include "kernels.h"
 
@@ -23,7 +26,7 @@ __device__ __forceinline__ float dot_row(const float *__restrict__ qs, const T *
 template <typename T>
 __global__ __launch_bounds__(256) void attn_fwd_simple_kernel(const T *__restrict__ qkv, T *__restrict__ o,
                                                               float *__restrict__ lse, int B, int S, int nh, int dh,
-                                                              int causal, float scale) {
+                                                              int causal, float scale, DropArgs da) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float *sc = smem + (size_t)wave * (S + dh);
@@ -54,11 +57,16 @@ __global__ __launch_bounds__(256) void attn_fwd_simple_kernel(const T *__restric
     l += p;
   }
   l = wave_sum(l);
+  if (da.thr != 0) {
+    const DropKeys keys = drop_keys(da.base, (uint32_t)(b * nh + h));
+    for (int j = lane; j < jn; j += 64)
+      if (drop_bits((uint32_t)i * (uint32_t)S + (uint32_t)j, keys.k0, keys.k1) < da.thr) sc[j] = 0.f;
+  }
   __syncthreads();
   if (!active) return;
   if (lse != nullptr && lane == 0) lse[((size_t)b * nh + h) * S + i] = m + logf(l);
   if (o == nullptr) return;
-  const float inv = 1.0f / l;
+  const float inv = da.scale / l;
   for (int d = lane; d < dh; d += 64) {
     float acc = 0.f;
     const T *v = base + 2 * (size_t)H + d;
@@ -73,7 +81,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple_kernel(const T *__rest
                                                                  const float *__restrict__ lse,
                                                                  const T *__restrict__ d_o, T *__restrict__ dqkv,
                                                                  float *__restrict__ drow, int B, int S, int nh,
-                                                                 int dh, int causal, float scale) {
+                                                                 int dh, int causal, float scale, DropArgs da) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float *sc = smem + (size_t)wave * (S + 2 * dh);
@@ -101,9 +109,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_simple_kernel(const T *__rest
   const float L = lse[((size_t)b * nh + h) * S + i];
   if (active && lane == 0) drow[((size_t)b * nh + h) * S + i] = dsum;
   const int jn = !active ? 0 : causal ? i + 1 : S;
+  const DropKeys keys = drop_keys(da.base, (uint32_t)(b * nh + h));
   for (int j = lane; j < jn; j += 64) {
     const float p = expf(scale * dot_row(qs, base + (size_t)j * ld + H, dh) - L);
-    const float dp = dot_row(dos, base + (size_t)j * ld + 2 * (size_t)H, dh);
+    float dp = dot_row(dos, base + (size_t)j * ld + 2 * (size_t)H, dh);
+    if (da.thr != 0)
+      dp = drop_bits((uint32_t)i * (uint32_t)S + (uint32_t)j, keys.k0, keys.k1) >= da.thr ? dp * da.scale : 0.f;
     sc[j] = p * (dp - dsum);
   }
   __syncthreads();
@@ -123,7 +134,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_simple_kernel(const T *__res
                                                                   const T *__restrict__ d_o,
                                                                   const float *__restrict__ drow,
                                                                   T *__restrict__ dqkv, int B, int S, int nh, int dh,
-                                                                  int causal, float scale) {
+                                                                  int causal, float scale, DropArgs drop) {
   extern __shared__ float smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float *pa = smem + (size_t)wave * (2 * S + 2 * dh);
@@ -148,10 +159,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_simple_kernel(const T *__res
   const int i0 = !active ? S : causal ? j : 0;
   const float *Lr = lse + ((size_t)b * nh + h) * S;
   const float *Dr = drow + ((size_t)b * nh + h) * S;
+  const DropKeys keys = drop_keys(drop.base, (uint32_t)(b * nh + h));
   for (int i = i0 + lane; i < S; i += 64) {
     const float p = expf(scale * dot_row(ks, base + (size_t)i * ld, dh) - Lr[i]);
-    const float dp = dot_row(vs, dob + (size_t)i * H, dh);
-    pa[i] = p;
+    float dp = dot_row(vs, dob + (size_t)i * H, dh);
+    float pv = p;   // what multiplied V in the forward
+    if (drop.thr != 0) {
+      const bool keep = drop_bits((uint32_t)i * (uint32_t)S + (uint32_t)j, keys.k0, keys.k1) >= drop.thr;
+      pv = keep ? p * drop.scale : 0.f;
+      dp = keep ? dp * drop.scale : 0.f;
+    }
+    pa[i] = pv;
     da[i] = p * (dp - Dr[i]);
   }
   __syncthreads();
@@ -169,42 +187,44 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_simple_kernel(const T *__res
 
 template <typename T>
 static hipError_t fwd_t(int B, int S, int nh, int dh, int causal, const void *qkv, void *o, float *lse,
-                        hipStream_t s) {
+                        const DropArgs &da, hipStream_t s) {
   const long rows = (long)B * nh * S;
   const size_t smem = 4 * (size_t)(S + dh) * sizeof(float);
   hipLaunchKernelGGL((attn_fwd_simple_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), smem, s,
-                     (const T *)qkv, (T *)o, lse, B, S, nh, dh, causal, 1.0f / sqrtf((float)dh));
+                     (const T *)qkv, (T *)o, lse, B, S, nh, dh, causal, 1.0f / sqrtf((float)dh), da);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_fwd_simple(int dtype, int B, int S, int nh, int dh, int causal, const void *qkv, void *o,
-                                  float *lse, hipStream_t s) {
+                                  float *lse, hipStream_t s, const DropArgs *drop) {
   if ((long)B * S * nh == 0) return hipSuccess;
-  return dtype == kBF16 ? fwd_t<bf16>(B, S, nh, dh, causal, qkv, o, lse, s)
-                        : fwd_t<float>(B, S, nh, dh, causal, qkv, o, lse, s);
+  const DropArgs da = drop != nullptr && drop->thr != 0 ? *drop : DropArgs{0u, 0u, 1.f};
+  return dtype == kBF16 ? fwd_t<bf16>(B, S, nh, dh, causal, qkv, o, lse, da, s)
+                        : fwd_t<float>(B, S, nh, dh, causal, qkv, o, lse, da, s);
 }
 
 template <typename T>
 static hipError_t bwd_t(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o, const float *lse,
-                        const void *d_o, void *dqkv, float *ws, hipStream_t s) {
+                        const void *d_o, void *dqkv, float *ws, const DropArgs &da, hipStream_t s) {
   const long rows = (long)B * nh * S;
   const float scale = 1.0f / sqrtf((float)dh);
   const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
   hipLaunchKernelGGL((attn_bwd_dq_simple_kernel<T>), grid, block, 4 * (size_t)(S + 2 * dh) * sizeof(float), s,
-                     (const T *)qkv, (const T *)o, lse, (const T *)d_o, (T *)dqkv, ws, B, S, nh, dh, causal, scale);
+                     (const T *)qkv, (const T *)o, lse, (const T *)d_o, (T *)dqkv, ws, B, S, nh, dh, causal, scale, da);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_dkv_simple_kernel<T>), grid, block, 4 * (size_t)(2 * S + 2 * dh) * sizeof(float), s,
-                     (const T *)qkv, lse, (const T *)d_o, ws, (T *)dqkv, B, S, nh, dh, causal, scale);
+                     (const T *)qkv, lse, (const T *)d_o, ws, (T *)dqkv, B, S, nh, dh, causal, scale, da);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_simple(int dtype, int B, int S, int nh, int dh, int causal, const void *qkv,
                                   const void *o, const float *lse, const void *d_o, void *dqkv, float *ws,
-                                  hipStream_t s) {
+                                  hipStream_t s, const DropArgs *drop) {
   if ((long)B * S * nh == 0) return hipSuccess;
-  return dtype == kBF16 ? bwd_t<bf16>(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, ws, s)
-                        : bwd_t<float>(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, ws, s);
+  const DropArgs da = drop != nullptr && drop->thr != 0 ? *drop : DropArgs{0u, 0u, 1.f};
+  return dtype == kBF16 ? bwd_t<bf16>(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, ws, da, s)
+                        : bwd_t<float>(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, ws, da, s);
 }
 
 }  // namespace dp

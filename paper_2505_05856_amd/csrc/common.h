@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kernels.h"
+
 namespace dp {
 
 typedef __bf16 bf16;
@@ -98,6 +100,31 @@ __device__ __forceinline__ float gelu_df(float x, int kind) {
   const float t = tanhf(u);
   const float du = 0.79788456080286536f * (1.0f + 0.134145f * x * x);
   return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * du;
+}
+
+// ---- dropout masks ----------------------------------------------------------------------
+// Whether an element is kept is a pure function of where it sits (counter-based), so that a
+// recomputed tensor and the backward pass get the mask of the forward pass without any state:
+//   mix(x): the 32-bit integer mixer x^=x>>16, x*=0x7feb352d, x^=x>>15, x*=0x846ca68b, x^=x>>16
+//   base  = mix chain over (seed, micro-batch counter, 4*layer + site)   [host, per launch]
+//   k0    = mix(base ^ unit*0x9e3779b1), k1 = mix(k0 ^ 0x85ebca6b)       [per batch*head / tensor]
+//   bits(i) = the mixer on i ^ k0 with k1 xored in between its two multiplications
+//   keep(i) = bits(i) >= floor(p * 2^32); kept values are scaled by 1/(1-p).
+__host__ __device__ __forceinline__ uint32_t drop_mix(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+__host__ __device__ __forceinline__ uint32_t drop_bits(uint32_t idx, uint32_t k0, uint32_t k1) {
+  uint32_t x = idx ^ k0;
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x ^= k1; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+struct DropKeys { uint32_t k0, k1; };
+__host__ __device__ __forceinline__ DropKeys drop_keys(uint32_t base, uint32_t unit) {
+  DropKeys k;
+  k.k0 = drop_mix(base ^ (unit * 0x9e3779b1u));
+  k.k1 = drop_mix(k.k0 ^ 0x85ebca6bu);
+  return k;
 }
 
 }  // namespace dp

@@ -257,6 +257,28 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ x, fl
   }
 }
 
+// ------------------------------------------------------------------ dropout of a hidden state
+// y = (res ? res : 0) + keep * scale * x over n elements (8 a thread); element i's decision is
+// drop_bits(i, keys of unit 0).  Forward: x is a linear layer's output, res the residual
+// branch.  Backward: x is the gradient of y, no res.
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_kernel(const T *x /* may alias y */, const T *res /* may alias y */,
+                                                      T *y, size_t n8, DropArgs a) {
+  const DropKeys k = drop_keys(a.base, 0u);
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    float v[8], r[8];
+    load8(x + i * 8, v);
+    if (res != nullptr) load8(res + i * 8, r);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const bool keep = drop_bits((uint32_t)(i * 8 + q), k.k0, k.k1) >= a.thr;
+      const float d = keep ? v[q] * a.scale : 0.f;
+      v[q] = res != nullptr ? r[q] + d : d;
+    }
+    store8(y + i * 8, v);
+  }
+}
+
 // ------------------------------------------------------------------ GELU
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, size_t n8,
@@ -456,6 +478,19 @@ hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y
   else
     hipLaunchKernelGGL((gelu_fwd_kernel<float>), dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)x, (float *)y,
                        n8, kind);
+  return hipGetLastError();
+}
+
+hipError_t launch_dropout(int dtype, size_t n, const void *x, const void *res, void *y, const DropArgs &a,
+                          hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const size_t n8 = n / 8;
+  if (dtype == kBF16)
+    hipLaunchKernelGGL((dropout_kernel<bf16>), dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16 *)x, (const bf16 *)res,
+                       (bf16 *)y, n8, a);
+  else
+    hipLaunchKernelGGL((dropout_kernel<float>), dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)x,
+                       (const float *)res, (float *)y, n8, a);
   return hipGetLastError();
 }
 

@@ -7,6 +7,33 @@
 
 namespace dp {
 
+// ---- dropout masks ------------------------------------------------------------
+// What a kernel needs to draw one site's mask (the generator is described in common.h).
+// thr == 0 keeps everything.
+struct DropArgs {
+  uint32_t base;    // of (seed, micro-batch, layer, site)
+  uint32_t thr;     // floor(p * 2^32)
+  float scale;      // 1 / (1 - p)
+};
+enum DropSite { kSiteAttn = 0, kSiteProj = 1, kSiteFc2 = 2 };
+inline uint32_t drop_mix_host(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+inline DropArgs make_drop_args(uint64_t seed, uint64_t mb, int layer, int site, float p) {
+  uint32_t s = drop_mix_host((uint32_t)seed ^ 0x9e3779b9u);
+  s = drop_mix_host(s ^ (uint32_t)(seed >> 32));
+  s = drop_mix_host(s ^ (uint32_t)mb);
+  s = drop_mix_host(s ^ (uint32_t)(mb >> 32));
+  s = drop_mix_host(s ^ (uint32_t)(4 * layer + site));
+  DropArgs a;
+  a.base = s;
+  a.thr = (uint32_t)((double)p * 4294967296.0);   // p < 1: the product is below 2^32; the cast truncates
+  a.scale = 1.0f / (1.0f - p);
+  return a;
+}
+
+
 enum { kF32 = 0, kBF16 = 1 };
 enum { kGemmNT = 0, kGemmTN = 1 };
 
@@ -70,6 +97,9 @@ hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const vo
 // dx = dy * gelu'(x) over [rows, cols] and dbias = column sums of the stored dx
 hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
                                   void *dbias, void *ws, hipStream_t s, ReduceJob *job = nullptr);
+// y = (res ? res : 0) + keep * scale * x, n a multiple of 8 and below 2^32; x and res may be y
+hipError_t launch_dropout(int dtype, size_t n, const void *x, const void *res, void *y, const DropArgs &a,
+                          hipStream_t s);
 hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s);
 hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s);
 hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s,
@@ -86,16 +116,18 @@ bool gemm_dma_supported(const GemmArgs &a);
 hipError_t launch_gemm_dma(const GemmArgs &a, hipStream_t s);
 
 // ---- attention ----------------------------------------------------------------
-// qkv [T,3H]; o [T,H] (nullable); lse [B,nh,S] fp32 (nullable)
+// qkv [T,3H]; o [T,H] (nullable); lse [B,nh,S] fp32 (nullable); drop: dropout of the
+// probabilities (null or thr == 0: none; needs S*S < 2^32)
 hipError_t launch_attn_fwd_simple(int dtype, int B, int S, int nh, int dh, int causal, const void *qkv, void *o,
-                                  float *lse, hipStream_t s);
+                                  float *lse, hipStream_t s, const DropArgs *drop = nullptr);
 // ws: fp32 [T, nh] row dots D_i = <dO_i, O_i>
 hipError_t launch_attn_bwd_simple(int dtype, int B, int S, int nh, int dh, int causal, const void *qkv,
                                   const void *o, const float *lse, const void *d_o, void *dqkv, float *ws,
-                                  hipStream_t s);
+                                  hipStream_t s, const DropArgs *drop = nullptr);
 hipError_t launch_attn_fwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, void *o, float *lse,
-                                hipStream_t s);
+                                hipStream_t s, const DropArgs *drop = nullptr);
 hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o,
-                                const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s);
+                                const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s,
+                                const DropArgs *drop = nullptr);
 
 }  // namespace dp

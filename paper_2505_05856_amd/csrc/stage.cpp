@@ -39,6 +39,8 @@ struct Cfg {
   int gelu, dtype;
   float eps;
   size_t esz;
+  float p_attn, p_hidden;          // dropout rates
+  bool drop_attn, drop_hidden;     // rate > 0
 };
 
 dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
@@ -54,6 +56,15 @@ dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
   o->F = c->ffn; o->S = c->seq; o->B = c->micro_batch; o->T = (long)c->micro_batch * c->seq;
   o->pre = c->norm_style == DP_PRE_LN; o->causal = c->causal != 0; o->gelu = c->gelu_kind;
   o->dtype = c->dtype; o->eps = c->ln_eps; o->esz = dp::dtype_size(c->dtype);
+  if (!(c->p_attn >= 0.f && c->p_attn < 1.f) || !(c->p_hidden >= 0.f && c->p_hidden < 1.f))
+    return fail(DP_E_INVAL, "dropout rates must be in [0, 1)");
+  o->p_attn = c->p_attn; o->p_hidden = c->p_hidden;
+  o->drop_attn = c->p_attn > 0.f; o->drop_hidden = c->p_hidden > 0.f;
+  // a mask position is a 32-bit index into the tensor it belongs to
+  if (o->drop_attn && (long)c->seq * c->seq >= (1L << 32))
+    return fail(DP_E_UNSUPPORTED, "attention dropout needs seq*seq < 2^32");
+  if (o->drop_hidden && (long)c->micro_batch * c->seq * c->hidden >= (1L << 32))
+    return fail(DP_E_UNSUPPORTED, "hidden dropout needs tokens*hidden < 2^32");
   if (o->H % 8 || o->F % 8 || o->dh % 8)
     return fail(DP_E_UNSUPPORTED, "hidden, ffn and head_dim must be multiples of 8");
   if (!dp::ln_supported(o->dtype, o->H)) return fail(DP_E_UNSUPPORTED, "hidden > 8192 is not supported");
@@ -269,6 +280,7 @@ struct dp_stage {
   uint32_t debug = 0;
   bool use_mfma = true;
   std::vector<std::unique_ptr<Flight>> flights;   // indexed by the caller's micro-batch slot
+  uint64_t rng_seed = 0, rng_counter = 0;         // dropout: the seed, and the micro-batch number the next forward takes
   hipEvent_t bwd_end[2] = {nullptr, nullptr};     // ends of the last two dp_stage_backward calls
   uint64_t bwd_issued = 0;
   // result of the last successful plan validation (a training loop repeats one plan)
@@ -308,6 +320,7 @@ struct Walk {
   char *host_base = nullptr;
   std::vector<hipEvent_t> *evs = nullptr;
   const WeightSet *wts = nullptr;   // live only: the parameter version this micro-batch uses
+  uint64_t rng_seed = 0, rng_mb = 0; // what this micro-batch's dropout masks are a function of
   bool accumulate = false;      // weight gradients are added to what the caller's buffers hold
   hipStream_t cs = nullptr; // compute stream (caller's)
   hipStream_t d2h = nullptr, h2d = nullptr;
@@ -498,6 +511,23 @@ struct Walk {
     prof_end();
     defer_reduce(job, ws);
   }
+  // y = (res ? res : 0) + mask * scale * x at one of a layer's two hidden-state dropout sites
+  void hidden_dropout(int l, int site, const void *x, const void *res, void *y) {
+    prof_begin(DP_OPC_DROPOUT);
+    if (live)
+      check(dp::launch_dropout(c.dtype, (size_t)c.T * c.H, x, res, y,
+                               dp::make_drop_args(rng_seed, rng_mb, l, site, c.p_hidden), cs));
+    prof_end();
+  }
+  // The gradient that enters a linear layer whose output was dropped: dy through the mask, in a
+  // block of its own (dy itself goes on along the residual branch), plus its column sums, which
+  // are that layer's bias gradient.
+  Buf masked_grad(int l, int site, const void *dyp, void *dbias) {
+    Buf m = tmp((size_t)c.T * c.H * c.esz);
+    hidden_dropout(l, site, dyp, nullptr, bptr(m));
+    colsum(c.T, c.H, bptr(m), dbias);
+    return m;
+  }
   void ln_bwd(const void *dyp, const void *x, const void *stats, const void *gamma, const void *dres, void *dx,
               void *dgamma, void *dbeta, void *dxsum) {
     Buf ws = tmp(dp::reduce_ws_bytes((int)c.T, c.H));
@@ -543,17 +573,19 @@ struct Walk {
       case OP_ATTN:
         prof_begin(DP_OPC_ATTN_FWD);
         if (live) {
+          const dp::DropArgs da = dp::make_drop_args(rng_seed, rng_mb, l, dp::kSiteAttn, c.p_attn);
           if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.S, c.dh))
-            check(dp::launch_attn_fwd_mfma(c.B, c.S, c.nh, c.dh, c.causal, in(0), out0, (float *)out1, cs));
+            check(dp::launch_attn_fwd_mfma(c.B, c.S, c.nh, c.dh, c.causal, in(0), out0, (float *)out1, cs, &da));
           else
             check(dp::launch_attn_fwd_simple(c.dtype, c.B, c.S, c.nh, c.dh, c.causal, in(0), out0, (float *)out1,
-                                             cs));
+                                             cs, &da));
         }
         prof_end();
         break;
-      case OP_PROJ:
-        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? w->wt_o : nullptr, live ? w->b_o : nullptr, in(1),
-             out0);
+      case OP_PROJ:   // with dropout: the linear layer alone, then residual + dropped output in place
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? w->wt_o : nullptr, live ? w->b_o : nullptr,
+             c.drop_hidden ? nullptr : in(1), out0);
+        if (c.drop_hidden) hidden_dropout(l, dp::kSiteProj, out0, in(1), out0);
         break;
       case OP_FC1:   // out1: GELU_OUT when the activation rides the epilogue (forward only)
         gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, F, H, in(0), live ? w->wt_fc1 : nullptr, live ? w->b_fc1 : nullptr,
@@ -566,7 +598,8 @@ struct Walk {
         break;
       case OP_FC2:
         gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, F, in(0), live ? w->wt_fc2 : nullptr, live ? w->b_fc2 : nullptr,
-             in(1), out0);
+             c.drop_hidden ? nullptr : in(1), out0);
+        if (c.drop_hidden) hidden_dropout(l, dp::kSiteFc2, out0, in(1), out0);
         break;
       default: break;
     }
@@ -715,11 +748,19 @@ struct Walk {
         need(l, {DP_SLOT_GELU_OUT});
         begin_node(TAG_BWD, l, 0);
         Buf dg = tmp(tf);
-        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, dcur, W_(w_fc2), nullptr, nullptr, bptr(dg));
-        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), dcur, nullptr, nullptr, G_(w_fc2));
-        // db2 = column sums of dY: below the top layer they come out of the LayerNorm backward
-        // that produced dY (layer l+1's LN1)
-        if (l == c.L - 1) colsum(T, H, dcur, G_(b_fc2));
+        if (c.drop_hidden) {
+          Buf dym = masked_grad(l, dp::kSiteFc2, dcur, G_(b_fc2));
+          gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, bptr(dym), W_(w_fc2), nullptr, nullptr, bptr(dg));
+          gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), bptr(dym), nullptr, nullptr,
+               G_(w_fc2));
+          drop(dym);
+        } else {
+          gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, dcur, W_(w_fc2), nullptr, nullptr, bptr(dg));
+          gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), dcur, nullptr, nullptr, G_(w_fc2));
+          // db2 = column sums of dY: below the top layer they come out of the LayerNorm backward
+          // that produced dY (layer l+1's LN1)
+          if (l == c.L - 1) colsum(T, H, dcur, G_(b_fc2));
+        }
         done_with(l, {DP_SLOT_GELU_OUT});
         // GELU: dF = dG * gelu'(FC1_OUT), in place
         need(l, {DP_SLOT_FC1_OUT});
@@ -739,7 +780,7 @@ struct Walk {
         need(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
         begin_node(TAG_BWD, l, 3);
         ln_bwd(bptr(dc), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), dcur, bptr(dc), G_(ln2_g),
-               G_(ln2_b), G_(b_o));   // dbo = column sums of dM
+               G_(ln2_b), c.drop_hidden ? nullptr : G_(b_o));   // dbo = column sums of dM (of the masked dM with dropout)
         drop(dcur_buf);
         done_with(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
         Buf dm = dc;
@@ -747,8 +788,14 @@ struct Walk {
         need(l, {DP_SLOT_ATTN_OUT});
         begin_node(TAG_BWD, l, 4);
         Buf dob = tmp(th);
-        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dm), W_(w_o), nullptr, nullptr, bptr(dob));
-        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_OUT), bptr(dm), nullptr, nullptr, G_(w_o));
+        {
+          Buf dmm;
+          if (c.drop_hidden) dmm = masked_grad(l, dp::kSiteProj, bptr(dm), G_(b_o));
+          const void *dmp = c.drop_hidden ? bptr(dmm) : bptr(dm);
+          gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, dmp, W_(w_o), nullptr, nullptr, bptr(dob));
+          gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_OUT), dmp, nullptr, nullptr, G_(w_o));
+          if (c.drop_hidden) drop(dmm);
+        }
         Buf dqkv = attention_bwd(l, dob);
         // QKV: dA = dQKV Wqkv^T, dWqkv = LN1_OUT^T dQKV
         need(l, {DP_SLOT_LN1_OUT});
@@ -764,7 +811,7 @@ struct Walk {
         begin_node(TAG_BWD, l, 7);
         void *dxp = l == 0 ? dx_out : bptr(da);
         ln_bwd(bptr(da), ptr(l, DP_SLOT_X_IN), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), bptr(dm), dxp, G_(ln1_g),
-               G_(ln1_b), (live && l > 0) ? dw[l - 1].b_fc2 : nullptr);   // = db2 of the layer below
+               G_(ln1_b), (live && l > 0 && !c.drop_hidden) ? dw[l - 1].b_fc2 : nullptr);   // = db2 of the layer below
         drop(dm);
         done_with(l, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS});
         if (l == 0) drop(da); else { dcur_buf = da; dcur = bptr(da); }
@@ -774,16 +821,21 @@ struct Walk {
         begin_node(TAG_BWD, l, 0);
         Buf dr2 = tmp(th);
         ln_bwd(dcur, ptr(l, DP_SLOT_RES2), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), nullptr, bptr(dr2), G_(ln2_g),
-               G_(ln2_b), G_(b_fc2));   // db2 = column sums of dR2
+               G_(ln2_b), c.drop_hidden ? nullptr : G_(b_fc2));   // db2 = column sums of dR2 (masked with dropout)
         drop(dcur_buf);
         done_with(l, {DP_SLOT_RES2, DP_SLOT_LN2_STATS});
         // FC2
         need(l, {DP_SLOT_GELU_OUT});
         begin_node(TAG_BWD, l, 1);
         Buf dg = tmp(tf);
-        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, bptr(dr2), W_(w_fc2), nullptr, nullptr, bptr(dg));
-        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), bptr(dr2), nullptr, nullptr,
-             G_(w_fc2));
+        {
+          Buf dr2m;
+          if (c.drop_hidden) dr2m = masked_grad(l, dp::kSiteFc2, bptr(dr2), G_(b_fc2));
+          const void *dp2 = c.drop_hidden ? bptr(dr2m) : bptr(dr2);
+          gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, F, H, dp2, W_(w_fc2), nullptr, nullptr, bptr(dg));
+          gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, F, H, T, ptr(l, DP_SLOT_GELU_OUT), dp2, nullptr, nullptr, G_(w_fc2));
+          if (c.drop_hidden) drop(dr2m);
+        }
         done_with(l, {DP_SLOT_GELU_OUT});
         // GELU
         need(l, {DP_SLOT_FC1_OUT});
@@ -804,16 +856,21 @@ struct Walk {
         need(l, {DP_SLOT_RES1, DP_SLOT_LN1_STATS});
         begin_node(TAG_BWD, l, 4);
         ln_bwd(bptr(dm), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), nullptr, bptr(dm), G_(ln1_g),
-               G_(ln1_b), G_(b_o));   // dbo = column sums of dR1
+               G_(ln1_b), c.drop_hidden ? nullptr : G_(b_o));   // dbo = column sums of dR1 (masked with dropout)
         done_with(l, {DP_SLOT_RES1, DP_SLOT_LN1_STATS});
         Buf dr1 = dm;
         // out-projection
         need(l, {DP_SLOT_ATTN_OUT});
         begin_node(TAG_BWD, l, 5);
         Buf dob = tmp(th);
-        gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dr1), W_(w_o), nullptr, nullptr, bptr(dob));
-        gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_OUT), bptr(dr1), nullptr, nullptr,
-             G_(w_o));
+        {
+          Buf dr1m;
+          if (c.drop_hidden) dr1m = masked_grad(l, dp::kSiteProj, bptr(dr1), G_(b_o));
+          const void *dp1 = c.drop_hidden ? bptr(dr1m) : bptr(dr1);
+          gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, dp1, W_(w_o), nullptr, nullptr, bptr(dob));
+          gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_OUT), dp1, nullptr, nullptr, G_(w_o));
+          if (c.drop_hidden) drop(dr1m);
+        }
         Buf dqkv = attention_bwd(l, dob);
         // QKV: dX = dR1 + dQKV Wqkv^T, dWqkv = X_IN^T dQKV
         need(l, {DP_SLOT_X_IN});
@@ -849,14 +906,15 @@ struct Walk {
     if (live) {
       const dp_layer_grads *g = &dw[l];
       (void)g;
+      const dp::DropArgs da = dp::make_drop_args(rng_seed, rng_mb, l, dp::kSiteAttn, c.p_attn);
       if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.S, c.dh))
         check(dp::launch_attn_bwd_mfma(c.B, c.S, c.nh, c.dh, c.causal, ptr(l, DP_SLOT_QKV), ptr(l, DP_SLOT_ATTN_OUT),
                                        (const float *)ptr(l, DP_SLOT_ATTN_LSE), bptr(dob), bptr(dqkv),
-                                       (float *)bptr(ws), cs));
+                                       (float *)bptr(ws), cs, &da));
       else
         check(dp::launch_attn_bwd_simple(c.dtype, c.B, c.S, c.nh, c.dh, c.causal, ptr(l, DP_SLOT_QKV),
                                          ptr(l, DP_SLOT_ATTN_OUT), (const float *)ptr(l, DP_SLOT_ATTN_LSE),
-                                         bptr(dob), bptr(dqkv), (float *)bptr(ws), cs));
+                                         bptr(dob), bptr(dqkv), (float *)bptr(ws), cs, &da));
     }
     prof_end();
     drop(ws);
@@ -1354,6 +1412,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   Walk w(c, plan, true, st);
   w.arena_base = (char *)st->arena; w.host_base = (char *)st->host_pool; w.evs = &st->events;
   w.wts = st->current;
+  w.rng_seed = st->rng_seed; w.rng_mb = st->rng_counter++;
   HIP_TRY(hipStreamWaitEvent(cs, st->current->ready, 0), DP_E_HIP);
   w.mfma_enabled = st->use_mfma;
   w.fuse_gelu_enabled = fuse_gelu;
@@ -1443,6 +1502,7 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   Walk *w = new Walk(c, f.plan.data(), true, st);
   w->arena_base = (char *)f.arena; w->host_base = (char *)f.host_pool; w->evs = &f.events;
   w->wts = st->current;
+  w->rng_seed = st->rng_seed; w->rng_mb = st->rng_counter++;
   HIP_TRY(hipStreamWaitEvent((hipStream_t)hip_stream, st->current->ready, 0), DP_E_HIP);
   w->mfma_enabled = st->use_mfma;
   w->fuse_gelu_enabled = fuse_gelu;
@@ -1520,6 +1580,13 @@ dp_status dp_stage_set_weights(dp_stage *st, const dp_layer_weights *layers, voi
   s = upload_weights(st, layers, (hipStream_t)hip_stream, &ws);
   if (s != DP_OK) return s;
   st->current = ws;
+  return DP_OK;
+}
+
+dp_status dp_stage_set_rng(dp_stage *st, uint64_t seed, uint64_t counter) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  st->rng_seed = seed;
+  st->rng_counter = counter;
   return DP_OK;
 }
 
@@ -1742,5 +1809,64 @@ dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, i
   return op_done(dp::launch_attn_bwd_simple(dtype, B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
                                             (hipStream_t)hip_stream), "attention_bwd");
 }
+
+// ---- dropout forms of the standalone operations
+static dp_status drop_args_of(const dp_dropout *d, int site, dp::DropArgs *out) {
+  if (d == nullptr) return fail(DP_E_INVAL, "dropout description is null");
+  if (!(d->p >= 0.f && d->p < 1.f)) return fail(DP_E_INVAL, "dropout rate must be in [0, 1)");
+  if (d->layer < 0) return fail(DP_E_INVAL, "dropout layer must be >= 0");
+  *out = dp::make_drop_args(d->seed, d->micro_batch, d->layer, site, d->p);
+  return DP_OK;
+}
+
+dp_status dp_op_dropout(int32_t dtype, size_t n, const void *x, const void *res, void *y, const dp_dropout *drop,
+                        int32_t site, void *hip_stream) {
+  if (bad_dtype(dtype) || !x || !y || (site != dp::kSiteProj && site != dp::kSiteFc2))
+    return fail(DP_E_INVAL, "dropout: bad argument");
+  if (n % 8 || n >= ((size_t)1 << 32)) return fail(DP_E_UNSUPPORTED, "dropout: n must be a multiple of 8 below 2^32");
+  dp::DropArgs a;
+  const dp_status s = drop_args_of(drop, site, &a);
+  if (s != DP_OK) return s;
+  return op_done(dp::launch_dropout(dtype, n, x, res, y, a, (hipStream_t)hip_stream), "dropout");
+}
+
+dp_status dp_op_attention_dropout_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
+                                      const void *qkv, void *o, float *lse, const dp_dropout *drop, void *hip_stream) {
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv) return fail(DP_E_INVAL, "attention_fwd: bad argument");
+  if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
+  if ((long)S * S >= (1L << 32)) return fail(DP_E_UNSUPPORTED, "attention dropout needs seq*seq < 2^32");
+  dp::DropArgs a;
+  const dp_status st = drop_args_of(drop, dp::kSiteAttn, &a);
+  if (st != DP_OK) return st;
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
+    return op_done(dp::launch_attn_fwd_mfma(B, S, nh, dh, causal, qkv, o, lse, (hipStream_t)hip_stream, &a),
+                   "attention_fwd");
+  if (S > 4096) return fail(DP_E_UNSUPPORTED, "attention: seq > 4096 needs the MFMA path");
+  return op_done(dp::launch_attn_fwd_simple(dtype, B, S, nh, dh, causal, qkv, o, lse, (hipStream_t)hip_stream, &a),
+                 "attention_fwd");
+}
+
+dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
+                                      const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv,
+                                      void *ws, const dp_dropout *drop, void *hip_stream) {
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv || !o || !lse || !d_o || !dqkv || !ws)
+    return fail(DP_E_INVAL, "attention_bwd: bad argument");
+  if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
+  if ((long)S * S >= (1L << 32)) return fail(DP_E_UNSUPPORTED, "attention dropout needs seq*seq < 2^32");
+  dp::DropArgs a;
+  const dp_status st = drop_args_of(drop, dp::kSiteAttn, &a);
+  if (st != DP_OK) return st;
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
+    return op_done(dp::launch_attn_bwd_mfma(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
+                                            (hipStream_t)hip_stream, &a), "attention_bwd");
+  if (S > 4096) return fail(DP_E_UNSUPPORTED, "attention: seq > 4096 needs the MFMA path");
+  return op_done(dp::launch_attn_bwd_simple(dtype, B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
+                                            (hipStream_t)hip_stream, &a), "attention_bwd");
+}
+
 
 }  // extern "C"

@@ -14,7 +14,7 @@ from . import binding as B
 def to_binding_config(cfg) -> B.StageConfig:
     """`cfg` is a synthetic.StageConfig (duck-typed)."""
     return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
-                         cfg.norm_style, cfg.causal, cfg.gelu, cfg.dtype, cfg.ln_eps)
+                         cfg.norm_style, cfg.causal, cfg.gelu, cfg.dtype, cfg.ln_eps, cfg.p_attn, cfg.p_hidden)
 
 
 def torch_dtype(cfg):

@@ -49,6 +49,8 @@ class StageConfig:
     gelu: str = "erf"          # "erf" or "tanh"
     dtype: str = "bf16"        # "f32" or "bf16"
     ln_eps: float = 1e-5
+    p_attn: float = 0.0        # dropout rate on the attention probabilities
+    p_hidden: float = 0.0      # dropout rate after the attention projection and after FC2
 
     @property
     def tokens(self) -> int:
