@@ -43,7 +43,7 @@ def cpu_baseline(cfg, weights, x, dy, budget_s=30.0):
 
     def run(n_layers):
         st = O.Stage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
-                     cfg.causal, cfg.gelu, cfg.ln_eps)
+                     cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden)
         t0 = time.perf_counter()
         O.stage_step(st, weights[:n_layers], x, dy, dtype=np.float64)
         return time.perf_counter() - t0
@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--inflight", type=int, default=0,
                     help="also time the steady state of a one-forward-one-backward schedule with this many "
                          "micro-batches between forward and backward (dp_stage_forward / dp_stage_backward)")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout rate on the attention probabilities and after the projection and FC2 (default: none)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 4 times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -96,6 +98,9 @@ def main():
 
     B.lib()   # fails loudly if the HIP library is not built
     cfg = syn.CONFIGS[args.config]
+    if args.dropout > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, p_attn=args.dropout, p_hidden=args.dropout)
     plan_name, mk = syn.PLANS[args.config][0]
     if args.plan:
         plan_name, mk = {"keep-all": ("keep-all", syn.plan_keep_all),
@@ -237,7 +242,8 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{args.config}: {cfg.n_layers} {cfg.norm_style}-LN layers, hidden {cfg.hidden}, "
                                f"{cfg.n_heads} heads, ffn {cfg.ffn}, seq {cfg.seq}, micro-batch {cfg.micro_batch}, "
-                               f"{'causal' if cfg.causal else 'full'} attention",
+                               f"{'causal' if cfg.causal else 'full'} attention"
+                               + (f", dropout {cfg.p_attn}" if cfg.p_attn > 0 else ""),
                    "plan": plan_name, "budget_bytes": budget, "validator_peak_bytes": rep["peak_bytes"],
                    "arena_peak_bytes": rep["arena_peak_bytes"],
                    "min_feasible_budget_bytes": tight["peak_bytes"]},
