@@ -318,6 +318,42 @@ dp_status dp_stage_set_rng(dp_stage *st, uint64_t seed, uint64_t counter);
 dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled);
 dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches_by_class);
 
+/* The pipeline partition search (Section 4.2, Algorithm 1: AdjacentPartition and BiPar; the
+ * compute- and memory-balanced positions of Appendix B.1, Algorithm 2; dp_plan_generate's
+ * planner as MemOpt) for a chain of chain_cfg->n_layers identical layers cut into n_stages
+ * stages between layers.  Host only.
+ *   A layer costs the sum of the cost model's node times plus extra_ns[l] (nullable: work tied
+ *   to layer l that memory optimisation cannot touch, e.g. an embedding or an output head) and
+ *   holds fixed_per_layer + extra_bytes[l] (nullable) bytes of parameters, gradients and
+ *   optimiser state besides its saved tensors; a stage holds fixed_per_stage more.  Stage x of
+ *   l keeps l - x + 1 micro-batches and parameter versions (Appendix B.1) and fits when
+ *   (l - x + 1) * peak <= budget_bytes (0 = no limit).
+ *   Both traversals run from the compute-balanced to the memory-balanced cut and stop where
+ *   no memory optimisation was needed; if no position of that interval fits, they go on past
+ *   the memory-balanced cut to the first one that does (beyond the paper, whose theorem
+ *   assumes that memory can be optimised away evenly).
+ * Outputs: cuts_out[n_stages-1] (first layer of stages 2..l), plan_out (the stages' plans one
+ * after the other, n_layers * DP_SLOTS_PER_LAYER bytes; each stage's first X_IN is KEEP),
+ * stages_out[n_stages], report (nullable).  The objective is time_ns = max over stages of
+ * T_x + T_x^moo.  Returns DP_E_BUDGET, with the outputs of the last position tried, if nothing
+ * fits; DP_E_INVAL for n_stages outside 1..min(32, n_layers), null outputs, negative extras. */
+typedef struct {
+  int32_t first_layer, n_layers, inflight, used_memopt;
+  int64_t time_ns, base_ns, moo_ns;  /* time = base (Eq. 1 plus extras) + moo; INT64_MAX: does not fit */
+  uint64_t peak_bytes;               /* model peak of one micro-batch */
+} dp_partition_stage;
+typedef struct {
+  int32_t feasible, any_memopt;
+  int64_t time_ns;
+  int32_t rho_cb, rho_mb;            /* outermost level: cut after stage n_stages/2 */
+  int32_t n_memopt, n_positions;     /* MemOpt runs and positions visited */
+} dp_partition_report;
+dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm, int32_t n_stages,
+                       uint64_t budget_bytes, uint64_t fixed_per_layer, uint64_t fixed_per_stage,
+                       const int64_t *extra_ns, const uint64_t *extra_bytes, int32_t *cuts_out,
+                       uint8_t *plan_out, size_t plan_len, dp_partition_stage *stages_out,
+                       dp_partition_report *report);
+
 /* Fills a cost model from this stage on this machine: `steps` all-KEEP steps with every
  * launch bracketed (node times averaged over layers and steps), then a block of FC1_OUT's
  * size copied four times each way through pinned host memory on the library's copy

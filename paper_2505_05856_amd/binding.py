@@ -134,11 +134,14 @@ def lib() -> C.CDLL:
     L.dp_op_dropout.argtypes = [i32, sz, vp, vp, vp, vp, i32, vp]
     L.dp_op_attention_dropout_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     L.dp_op_attention_dropout_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.dp_partition.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), i32, u64, u64, u64, C.POINTER(C.c_int64),
+                               C.POINTER(u64), C.POINTER(i32), vp, sz, C.POINTER(PartitionStage),
+                               C.POINTER(PartitionReport)]
     L.dp_plan_cost.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), vp, sz, u64, C.POINTER(PlanCostReport)]
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
-    for name in ("dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
+    for name in ("dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd"):
@@ -207,6 +210,47 @@ def plan_generate(cfg: StageConfig, cm: CostModel, budget_bytes: int, inflight: 
     if raise_on_error:
         _check(code)
     return code, out, rep.as_dict()
+
+
+class PartitionStage(C.Structure):
+    _fields_ = [("first_layer", C.c_int32), ("n_layers", C.c_int32), ("inflight", C.c_int32), ("used_memopt", C.c_int32),
+                ("time_ns", C.c_int64), ("base_ns", C.c_int64), ("moo_ns", C.c_int64), ("peak_bytes", C.c_uint64)]
+
+
+class PartitionReport(C.Structure):
+    _fields_ = [("feasible", C.c_int32), ("any_memopt", C.c_int32), ("time_ns", C.c_int64), ("rho_cb", C.c_int32),
+                ("rho_mb", C.c_int32), ("n_memopt", C.c_int32), ("n_positions", C.c_int32)]
+
+
+def partition(chain_cfg: StageConfig, cm: CostModel, n_stages: int, budget_bytes: int, fixed_per_layer: int,
+              fixed_per_stage: int, extra_ns=None, extra_bytes=None, raise_on_error=True):
+    """dp_partition.  Returns (status, dict): feasible, time_ns, cuts, rho_cb, rho_mb, counters, stages (list of
+    dicts with the stage's plan as a uint8 array)."""
+    L = chain_cfg.n_layers
+    n = plan_len(chain_cfg)
+    plan = np.zeros(n, dtype=np.uint8)
+    cuts = (C.c_int32 * max(1, n_stages - 1))()
+    stages = (PartitionStage * max(1, n_stages))()
+    rep = PartitionReport()
+    ens = (C.c_int64 * L)(*[int(v) for v in extra_ns]) if extra_ns is not None else None
+    eby = (C.c_uint64 * L)(*[int(v) for v in extra_bytes]) if extra_bytes is not None else None
+    code = lib().dp_partition(C.byref(chain_cfg), C.byref(cm), n_stages, budget_bytes, fixed_per_layer,
+                              fixed_per_stage, ens, eby, cuts, plan.ctypes.data_as(C.c_void_p), n, stages,
+                              C.byref(rep))
+    if raise_on_error:
+        _check(code)
+    out = {f: getattr(rep, f) for f, _ in PartitionReport._fields_}
+    out["feasible"], out["any_memopt"] = bool(rep.feasible), bool(rep.any_memopt)
+    if code in (0, -3):
+        out["cuts"] = [int(cuts[i]) for i in range(n_stages - 1)]
+        out["stages"] = []
+        for x in range(n_stages):
+            d = {f: getattr(stages[x], f) for f, _ in PartitionStage._fields_}
+            a = d["first_layer"] * SLOTS_PER_LAYER
+            d["plan"] = plan[a:a + d["n_layers"] * SLOTS_PER_LAYER].copy()
+            d["memopt"] = bool(d.pop("used_memopt"))
+            out["stages"].append(d)
+    return code, out
 
 
 def last_error() -> str:

@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <array>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -1619,6 +1620,235 @@ dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches
   st->prof_class.clear();
   st->prof_tag.clear();
   return DP_OK;
+}
+
+// ------------------------------------------------------------------ partition search
+// Section 4.2 (Algorithm 1: AdjacentPartition, BiPar) over a chain of identical layers, with
+// Appendix B.1's balance walks (Algorithm 2) for the two ends of every traversal and memopt()
+// above as the MemOpt step.  Cuts fall between layers.  Stage x of l keeps l - x + 1
+// micro-batches and fits when (l - x + 1) * peak <= M.
+extern "C++" {
+namespace {
+
+constexpr int64_t kNever = INT64_MAX;   // a stage MemOpt cannot fit
+
+struct StageRes {
+  int64_t t = 0, base = 0, moo = 0;     // t = T_x + T_x^moo, kNever if it cannot fit
+  bool mopt = false;                    // memory optimisation was needed
+  uint64_t peak = 0;
+  std::vector<uint8_t> plan;
+};
+struct SearchRes {
+  int64_t t = kNever;
+  bool mopt = false;
+  std::vector<int> cuts;
+  std::vector<std::shared_ptr<const StageRes>> stages;
+};
+
+// Algorithm 2's walk: item i adds amounts[i]; stage x's share of the total is weights[x] / sum.
+// The item that reaches the target closes the stage unless the boundary in front of it is
+// nearer (items are whole layers); every stage keeps at least one item.
+std::vector<int> balanced_cuts(const std::vector<uint64_t> &amounts, const std::vector<uint64_t> &weights) {
+  typedef unsigned __int128 u128;
+  const int n = (int)amounts.size(), k = (int)weights.size();
+  u128 total = 0, wsum = 0;
+  for (uint64_t a : amounts) total += a;
+  for (uint64_t w : weights) wsum += w;
+  std::vector<int> cuts;
+  int x = 0, i = 0, start = 0;
+  u128 cur = 0;
+  while (i < n && x < k - 1) {
+    const u128 a = amounts[(size_t)i], target = total * weights[(size_t)x];
+    const bool reached = (cur + a) * wsum >= target;
+    if (reached && i > start && (cur + a) * wsum - target > target - cur * wsum) {
+      cuts.push_back(i);
+      ++x; cur = 0; start = i;
+      continue;   // item i opens the next stage
+    }
+    cur += a;
+    const bool must = n - (i + 1) == k - (x + 1);
+    if (reached || must) { cuts.push_back(i + 1); ++x; cur = 0; start = i + 1; }
+    ++i;
+  }
+  return cuts;
+}
+
+struct Partitioner {
+  Cfg layer;                    // the layer shape; L is set per stage
+  const dp_cost_model *cm;
+  int n, ell;
+  uint64_t M, fixed_per_layer, fixed_per_stage;
+  std::vector<int64_t> extra_ns;
+  std::vector<uint64_t> extra_bytes;
+  int64_t layer_ns = 0;
+  uint64_t layer_saved = 0, lcm_depths = 1;
+  int n_memopt = 0, n_positions = 0;
+  std::vector<std::pair<std::array<int, 3>, std::shared_ptr<const StageRes>>> cache;
+
+  void prepare() {
+    for (int i = 0; i < N_OPS; ++i) layer_ns += cm->fwd_ns[i] + cm->bwd_ns[i];
+    for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) layer_saved += slot_bytes(layer, s);
+    for (uint64_t d = 1; d <= (uint64_t)ell; ++d) {
+      uint64_t a = lcm_depths, b = d;
+      while (b) { const uint64_t r = a % b; a = b; b = r; }
+      lcm_depths = lcm_depths / a * d;
+    }
+  }
+  uint64_t time_of(int l) const { return (uint64_t)(layer_ns + extra_ns[(size_t)l]); }
+  uint64_t mem_of(int l) const { return fixed_per_layer + extra_bytes[(size_t)l] + layer_saved; }
+
+  // rho_cb, rho_mb: the cut after stage `after` when layers [a, b) are divided among stages first..last
+  void comp_mem_bal(int a, int b, int first, int last, int after, int *cb, int *mb) const {
+    std::vector<uint64_t> t, m, we, wm;
+    for (int l = a; l < b; ++l) { t.push_back(time_of(l)); m.push_back(mem_of(l)); }
+    for (int x = first; x <= last; ++x) { we.push_back(1); wm.push_back(lcm_depths / (uint64_t)(ell - x + 1)); }
+    *cb = a + balanced_cuts(t, we)[(size_t)(after - first)];
+    *mb = a + balanced_cuts(m, wm)[(size_t)(after - first)];
+  }
+
+  std::shared_ptr<const StageRes> stage(int a, int b, int x) {
+    const std::array<int, 3> key{a, b, x};
+    for (const auto &e : cache) if (e.first == key) return e.second;
+    auto r = std::make_shared<StageRes>();
+    Cfg c = layer;
+    c.L = b - a;
+    const uint32_t k = (uint32_t)(ell - x + 1);
+    uint64_t fixed = fixed_per_stage + (uint64_t)c.L * fixed_per_layer;
+    int64_t extra = 0;
+    for (int l = a; l < b; ++l) { fixed += extra_bytes[(size_t)l]; extra += extra_ns[(size_t)l]; }
+    r->plan.assign((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
+    const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, 0);
+    const uint64_t keep_peak = fixed + keep.slot_peak;
+    if (M == 0 || (unsigned __int128)k * keep_peak <= M) {
+      r->t = r->base = keep.step_ns + extra; r->moo = 0; r->mopt = false; r->peak = keep_peak;
+    } else {
+      ++n_memopt;
+      dp_memopt_report rep;
+      memset(&rep, 0, sizeof rep);
+      const bool ok = memopt(c, *cm, M, k, fixed, r->plan, &rep);
+      r->mopt = true; r->base = rep.base_ns + extra; r->moo = rep.moo_ns; r->peak = rep.peak_bytes;
+      r->t = ok ? rep.base_ns + rep.moo_ns + extra : kNever;
+    }
+    cache.emplace_back(key, r);
+    return r;
+  }
+
+  // The loop AdjacentPartition and BiPar share: positions from rho_cb to rho_mb, stop where no
+  // memory optimisation was needed, keep the fastest (the first on ties).  Beyond the paper:
+  // if nothing in the interval fits, go on past rho_mb in the same direction (towards fewer
+  // layers in the earlier stages when the two coincide) to the first position that fits.
+  template <typename At>
+  SearchRes traverse(int cb, int mb, int lo, int hi, At at) {
+    const int step = mb > cb ? 1 : -1;
+    SearchRes best;
+    bool have = false;
+    int last_pos = 0;
+    bool any_pos = false;
+    for (int rho = cb; rho != mb + step; rho += step) {
+      if (rho < lo || rho > hi) continue;
+      any_pos = true; last_pos = rho;
+      SearchRes r = at(rho);
+      const bool stop = !r.mopt;
+      if (!have || r.t < best.t) { best = std::move(r); have = true; }
+      if (stop) break;
+    }
+    if (!have || best.t == kNever) {
+      int rho = (any_pos ? last_pos : std::min(std::max(mb, lo), hi)) + step;
+      for (; rho >= lo && rho <= hi; rho += step) {
+        SearchRes r = at(rho);
+        const bool fitted = r.t < kNever;
+        if (!have || fitted) { best = std::move(r); have = true; }
+        if (fitted) break;
+      }
+    }
+    return best;
+  }
+
+  SearchRes adjacent(int a, int b, int sid) {
+    int cb, mb;
+    comp_mem_bal(a, b, sid, sid + 1, sid, &cb, &mb);
+    return traverse(cb, mb, a + 1, b - 1, [&](int rho) {
+      ++n_positions;
+      SearchRes r;
+      auto l = stage(a, rho, sid), rt = stage(rho, b, sid + 1);
+      r.t = std::max(l->t, rt->t); r.mopt = l->mopt || rt->mopt;
+      r.cuts = {rho}; r.stages = {l, rt};
+      return r;
+    });
+  }
+
+  SearchRes bipar(int a, int b, int first, int last) {
+    if (first == last) {
+      SearchRes r;
+      auto s = stage(a, b, first);
+      r.t = s->t; r.mopt = s->mopt; r.stages = {s};
+      return r;
+    }
+    if (last - first == 1) return adjacent(a, b, first);
+    const int count = last - first + 1, mid = first + count / 2 - 1;   // three stages split 1 + 2
+    int cb, mb;
+    comp_mem_bal(a, b, first, last, mid, &cb, &mb);
+    const int n_left = mid - first + 1, n_right = last - mid;
+    return traverse(cb, mb, a + n_left, b - n_right, [&](int rho) {
+      ++n_positions;
+      SearchRes l = bipar(a, rho, first, mid), rt = bipar(rho, b, mid + 1, last), r;
+      r.t = std::max(l.t, rt.t); r.mopt = l.mopt || rt.mopt;
+      r.cuts = l.cuts; r.cuts.push_back(rho); r.cuts.insert(r.cuts.end(), rt.cuts.begin(), rt.cuts.end());
+      r.stages = l.stages; r.stages.insert(r.stages.end(), rt.stages.begin(), rt.stages.end());
+      return r;
+    });
+  }
+};
+
+}  // namespace
+}  // extern "C++"
+
+dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm, int32_t n_stages,
+                       uint64_t budget_bytes, uint64_t fixed_per_layer, uint64_t fixed_per_stage,
+                       const int64_t *extra_ns, const uint64_t *extra_bytes, int32_t *cuts_out, uint8_t *plan_out,
+                       size_t plan_len, dp_partition_stage *stages_out, dp_partition_report *report) {
+  Cfg c;
+  dp_status s = parse_cfg(chain_cfg, &c);
+  if (s != DP_OK) return s;
+  if ((s = check_cost_model(cm)) != DP_OK) return s;
+  if (n_stages < 1 || n_stages > 32 || n_stages > c.L)
+    return fail(DP_E_INVAL, "n_stages must be 1..min(32, n_layers)");
+  if (plan_out == nullptr || stages_out == nullptr || (n_stages > 1 && cuts_out == nullptr))
+    return fail(DP_E_INVAL, "null output argument");
+  if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", DP_SLOTS_PER_LAYER);
+  Partitioner p;
+  p.layer = c; p.cm = cm; p.n = c.L; p.ell = n_stages; p.M = budget_bytes;
+  p.fixed_per_layer = fixed_per_layer; p.fixed_per_stage = fixed_per_stage;
+  p.extra_ns.assign((size_t)c.L, 0); p.extra_bytes.assign((size_t)c.L, 0);
+  for (int l = 0; l < c.L; ++l) {
+    if (extra_ns) { if (extra_ns[l] < 0) return fail(DP_E_INVAL, "extra_ns[%d] is negative", l); p.extra_ns[(size_t)l] = extra_ns[l]; }
+    if (extra_bytes) p.extra_bytes[(size_t)l] = extra_bytes[l];
+  }
+  p.prepare();
+  const SearchRes r = p.bipar(0, c.L, 1, n_stages);
+  dp_partition_report local;
+  dp_partition_report *rep = report ? report : &local;
+  memset(rep, 0, sizeof *rep);
+  rep->feasible = r.t < kNever; rep->time_ns = r.t; rep->any_memopt = r.mopt;
+  rep->n_memopt = p.n_memopt; rep->n_positions = p.n_positions;
+  if (n_stages > 1) {
+    int cb, mb;
+    p.comp_mem_bal(0, c.L, 1, n_stages, n_stages / 2, &cb, &mb);
+    rep->rho_cb = cb; rep->rho_mb = mb;
+  }
+  int first = 0;
+  for (int x = 1; x <= n_stages; ++x) {
+    const StageRes &st = *r.stages[(size_t)(x - 1)];
+    const int end = x < n_stages ? r.cuts[(size_t)(x - 1)] : c.L;
+    if (x < n_stages) cuts_out[x - 1] = end;
+    dp_partition_stage &o = stages_out[x - 1];
+    o.first_layer = first; o.n_layers = end - first; o.inflight = n_stages - x + 1; o.used_memopt = st.mopt;
+    o.time_ns = st.t; o.base_ns = st.base; o.moo_ns = st.moo; o.peak_bytes = st.peak;
+    memcpy(plan_out + (size_t)first * DP_SLOTS_PER_LAYER, st.plan.data(), st.plan.size());
+    first = end;
+  }
+  return rep->feasible ? DP_OK : fail(DP_E_BUDGET, "no partition into %d stages fits %llu bytes a device", n_stages,
+                                      (unsigned long long)budget_bytes);
 }
 
 dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void *dy, void *y_out, void *dx_out,
