@@ -65,6 +65,74 @@ def cpu_baseline(cfg, weights, x, dy, budget_s=30.0):
             "kind": "oracle", "seconds": round(dt, 3), "sample": sample}
 
 
+def partition_and_measure(args, cfg, run):
+    """The partition search in front of the path: node times and link speed measured on `run`'s handle, a chain
+    of --chain-layers layers cut into --partition stages under --budget-gb a device, then every stage of the
+    result (and of the equal-layers split, for comparison) timed in its own steady state on this one GPU."""
+    import dataclasses
+    import synthetic as syn
+    from paper_2505_05856_amd import binding as B
+    from paper_2505_05856_amd.harness import StageRunner, steady_state_ms, to_binding_config
+    ell, n = args.partition, args.chain_layers
+    cm = B.stage_measure_cost_model(run.stage, run.x, run.dy, run.y, run.dx, run.g, steps=3)
+    one = dataclasses.replace(cfg, n_layers=1)
+    _, rep1 = B.plan_validate(to_binding_config(one), syn.plan_keep_all(one))
+    fixed_per_layer = rep1["weight_bytes"] + rep1["grad_bytes"]
+    fixed_per_stage = rep1["fixed_bytes"] - fixed_per_layer
+    budget = int(args.budget_gb * 1e9)
+    chain = dataclasses.replace(cfg, n_layers=n)
+    code, part = B.partition(to_binding_config(chain), cm, ell, budget, fixed_per_layer, fixed_per_stage,
+                             flags=B.MEMOPT_VALIDATE, raise_on_error=False)
+    measured = {}
+
+    def measure(n_layers, inflight, plan=None):
+        """Steady state of one stage: under `plan` (the search's), else under the plan dp_plan_generate makes
+        for that many layers alone."""
+        key = (n_layers, inflight, plan is None)
+        if key not in measured:
+            c = dataclasses.replace(cfg, n_layers=n_layers)
+            w = syn.make_weights(c)
+            x, dy = syn.make_activations(c)
+            r = StageRunner(c, w, x, dy)
+            predicted = None
+            if plan is None:
+                scode, plan, mrep = B.plan_generate(r.bcfg, cm, budget, inflight=inflight, flags=B.MEMOPT_VALIDATE,
+                                                    raise_on_error=False)
+                predicted = round((mrep["base_ns"] + mrep["moo_ns"]) / 1e6, 3)
+            else:
+                scode, _ = B.plan_validate(r.bcfg, plan, budget_bytes=budget, inflight=inflight, raise_on_error=False)
+            if scode != 0:
+                measured[key] = {"fits": False}
+            else:
+                _, vrep = B.plan_validate(r.bcfg, plan, budget_bytes=budget, inflight=inflight)
+                ms = steady_state_ms(r, plan, inflight, budget, 2, max(3, args.steps // 4))
+                measured[key] = {"fits": True, "measured_ms": round(ms, 3),
+                                 "held_bytes": inflight * vrep["peak_bytes"]}
+                if predicted is not None:
+                    measured[key]["predicted_ms"] = predicted
+            r.close()
+        return measured[key]
+
+    out = {"stages": ell, "chain_layers": n, "budget_bytes": budget, "feasible": part["feasible"],
+           "rho_cb": part["rho_cb"], "rho_mb": part["rho_mb"], "memopt_runs": part["n_memopt"],
+           "positions_visited": part["n_positions"], "cost_model": cm.as_dict()}
+    if part["feasible"]:
+        out["cuts"] = part["cuts"]
+        out["predicted_ms"] = round(part["time_ns"] / 1e6, 3)
+        out["per_stage"] = [dict(layers=s["n_layers"], inflight=s["inflight"], model_ms=round(s["time_ns"] / 1e6, 3),
+                                 **measure(s["n_layers"], s["inflight"], s["plan"])) for s in part["stages"]]
+        fits = [s for s in out["per_stage"] if s["fits"]]
+        if len(fits) == ell:
+            out["measured_ms"] = max(s["measured_ms"] for s in fits)
+            out["pipeline_samples_per_s"] = round(cfg.micro_batch / (out["measured_ms"] * 1e-3), 3)
+    # what equal layer counts would give under the same budget
+    if n % ell == 0:
+        eq = [measure(n // ell, ell - x) for x in range(ell)]
+        out["equal_layers"] = {"per_stage": eq,
+                               "measured_ms": max(s["measured_ms"] for s in eq) if all(s["fits"] for s in eq) else None}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +149,11 @@ def main():
     ap.add_argument("--inflight", type=int, default=0,
                     help="also time the steady state of a one-forward-one-backward schedule with this many "
                          "micro-batches between forward and backward (dp_stage_forward / dp_stage_backward)")
+    ap.add_argument("--partition", type=int, default=0,
+                    help="also cut a chain of --chain-layers layers of this shape into this many pipeline stages "
+                         "(dp_partition, cost model measured here) and time every stage of the result")
+    ap.add_argument("--chain-layers", type=int, default=24)
+    ap.add_argument("--budget-gb", type=float, default=0.0, help="with --partition: device memory per stage (0 = no limit)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate on the attention probabilities and after the projection and FC2 (default: none)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -212,27 +285,17 @@ def main():
     if args.inflight > 0:
         # steady state of the schedule: backward of the oldest micro-batch, then the forward of the next into
         # the slot it left; the budget covers every micro-batch in flight
+        from paper_2505_05856_amd.harness import steady_state_ms
         k = args.inflight
-        for s in range(k):
-            B.stage_forward(run.stage, s, k, run.x, plan, k * budget, run.y)
-        def turn(i):
-            B.stage_backward(run.stage, i % k, run.dy, run.dx, run.g, B.GRAD_ACCUMULATE if i else 0)
-            B.stage_forward(run.stage, i % k, k, run.x, plan, k * budget, run.y)
-        for i in range(args.warmup):
-            turn(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            turn(args.warmup + i)
-        torch.cuda.synchronize()
-        sms = (time.perf_counter() - t0) * 1e3 / args.steps
-        for s in range(k):
-            B.stage_backward(run.stage, s, run.dy, run.dx, run.g, B.GRAD_ACCUMULATE)
-        torch.cuda.synchronize()
+        sms = steady_state_ms(run, plan, k, k * budget, args.warmup, args.steps)
         schedule = {"inflight": k, "ms_per_micro_batch": round(sms, 4),
                     "samples_per_s": round(cfg.micro_batch / (sms * 1e-3), 3),
                     "budget_bytes": k * budget, "device_bytes_held": k * rep["arena_peak_bytes"],
                     "vs_fused_step": round(ms / sms, 4)}
+
+    partition = None
+    if args.partition > 0:
+        partition = partition_and_measure(args, cfg, run)
 
     out = {
         "metric": "stage fwd+bwd samples/sec + MFMA util % at fixed memory budget",
@@ -258,6 +321,8 @@ def main():
         out["swap_overlap"] = overlap
     if schedule is not None:
         out["schedule"] = schedule
+    if partition is not None:
+        out["partition"] = partition
     if memopt is not None:
         memopt["measured_ms"] = round(ms, 4)
         out["memopt"] = memopt

@@ -332,6 +332,11 @@ dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches
  *   no memory optimisation was needed; if no position of that interval fits, they go on past
  *   the memory-balanced cut to the first one that does (beyond the paper, whose theorem
  *   assumes that memory can be optimised away evenly).
+ * flags = DP_MEMOPT_VALIDATE: a stage's memory is what dp_plan_validate reports for its plan
+ *   (library weight copies, gradients, buffers, arena with its transients and fragmentation)
+ *   plus its extra_bytes, and MemOpt runs as dp_plan_generate does under that flag, so every
+ *   stage of the result is executable within the budget; fixed_per_layer and fixed_per_stage
+ *   still steer the memory-balanced walk.  The balance walks and the traversal are unchanged.
  * Outputs: cuts_out[n_stages-1] (first layer of stages 2..l), plan_out (the stages' plans one
  * after the other, n_layers * DP_SLOTS_PER_LAYER bytes; each stage's first X_IN is KEEP),
  * stages_out[n_stages], report (nullable).  The objective is time_ns = max over stages of
@@ -350,9 +355,9 @@ typedef struct {
 } dp_partition_report;
 dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm, int32_t n_stages,
                        uint64_t budget_bytes, uint64_t fixed_per_layer, uint64_t fixed_per_stage,
-                       const int64_t *extra_ns, const uint64_t *extra_bytes, int32_t *cuts_out,
-                       uint8_t *plan_out, size_t plan_len, dp_partition_stage *stages_out,
-                       dp_partition_report *report);
+                       const int64_t *extra_ns, const uint64_t *extra_bytes, uint32_t flags,
+                       int32_t *cuts_out, uint8_t *plan_out, size_t plan_len,
+                       dp_partition_stage *stages_out, dp_partition_report *report);
 
 /* Fills a cost model from this stage on this machine: `steps` all-KEEP steps with every
  * launch bracketed (node times averaged over layers and steps), then a block of FC1_OUT's
@@ -366,7 +371,8 @@ dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void
  * stream, no overlap); bit 1 = poison arena blocks with NaN patterns when they
  * are released (catches use-after-release and late swap-in); bit 2 = produce the
  * forward GELU in the FC1 GEMM epilogue instead of as its own kernel (results must
- * be the same bits either way). */
+ * be the same bits either way); bit 3 = dp_stage_forward under a plan that swaps
+ * does not wait for the slot's last backward (timing experiments). */
 dp_status dp_stage_set_debug(dp_stage *st, uint32_t flags);
 
 void dp_stage_destroy(dp_stage *st);

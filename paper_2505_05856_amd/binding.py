@@ -135,7 +135,7 @@ def lib() -> C.CDLL:
     L.dp_op_attention_dropout_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     L.dp_op_attention_dropout_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dp_partition.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), i32, u64, u64, u64, C.POINTER(C.c_int64),
-                               C.POINTER(u64), C.POINTER(i32), vp, sz, C.POINTER(PartitionStage),
+                               C.POINTER(u64), C.c_uint32, C.POINTER(i32), vp, sz, C.POINTER(PartitionStage),
                                C.POINTER(PartitionReport)]
     L.dp_plan_cost.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), vp, sz, u64, C.POINTER(PlanCostReport)]
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
@@ -223,7 +223,7 @@ class PartitionReport(C.Structure):
 
 
 def partition(chain_cfg: StageConfig, cm: CostModel, n_stages: int, budget_bytes: int, fixed_per_layer: int,
-              fixed_per_stage: int, extra_ns=None, extra_bytes=None, raise_on_error=True):
+              fixed_per_stage: int, extra_ns=None, extra_bytes=None, flags: int = 0, raise_on_error=True):
     """dp_partition.  Returns (status, dict): feasible, time_ns, cuts, rho_cb, rho_mb, counters, stages (list of
     dicts with the stage's plan as a uint8 array)."""
     L = chain_cfg.n_layers
@@ -235,7 +235,7 @@ def partition(chain_cfg: StageConfig, cm: CostModel, n_stages: int, budget_bytes
     ens = (C.c_int64 * L)(*[int(v) for v in extra_ns]) if extra_ns is not None else None
     eby = (C.c_uint64 * L)(*[int(v) for v in extra_bytes]) if extra_bytes is not None else None
     code = lib().dp_partition(C.byref(chain_cfg), C.byref(cm), n_stages, budget_bytes, fixed_per_layer,
-                              fixed_per_stage, ens, eby, cuts, plan.ctypes.data_as(C.c_void_p), n, stages,
+                              fixed_per_stage, ens, eby, flags, cuts, plan.ctypes.data_as(C.c_void_p), n, stages,
                               C.byref(rep))
     if raise_on_error:
         _check(code)

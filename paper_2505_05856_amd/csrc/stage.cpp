@@ -1186,6 +1186,42 @@ dp_status dp_plan_cost(const dp_stage_config *cfg, const dp_cost_model *cm, cons
   return DP_OK;
 }
 
+// MemOpt against the executor: the model sees saved tensors only, the executor also holds
+// transient gradients, workspaces and fragmentation.  Plan for the model, ask the validator for
+// the true peak, and hand the difference back to the model as a smaller budget until it fits.
+// DP_OK, DP_E_BUDGET (plan and report of the last round) or a validator error.
+static dp_status memopt_validated(const Cfg &c, const dp_cost_model &cm, uint64_t budget_bytes, uint32_t inflight,
+                                  std::vector<uint8_t> &plan, dp_memopt_report *r) {
+  const size_t plan_len = (size_t)c.L * DP_SLOTS_PER_LAYER;
+  dp_plan_report keep;
+  plan.assign(plan_len, DP_KEEP);
+  (void)validate(c, plan.data(), plan_len, 0, 1, &keep, env_mfma_enabled(), kFuseGeluDefault);
+  const uint64_t fixed = keep.fixed_bytes;
+  uint64_t model_budget = budget_bytes;
+  for (int round = 1; round <= 6; ++round) {
+    r->refine_rounds = round;
+    const bool ok = memopt(c, cm, model_budget, inflight, fixed, plan, r);
+    dp_plan_report vr;
+    long hold = 0;
+    const dp_status vs = validate(c, plan.data(), plan_len, budget_bytes, inflight, &vr, env_mfma_enabled(), kFuseGeluDefault, &hold);
+    r->validated_peak_bytes = vr.peak_bytes;
+    if (vs == DP_OK) {
+      r->feasible = 1;
+      r->exact_step_ns = walk_cost(c, cm, plan.data(), true, hold).step_ns;
+      return DP_OK;
+    }
+    if (vs != DP_E_BUDGET) return vs;
+    if (!ok || budget_bytes == 0) break;
+    const uint64_t excess = vr.peak_bytes > r->peak_bytes ? vr.peak_bytes - r->peak_bytes : 0;
+    const uint64_t target = budget_bytes / inflight;
+    const uint64_t next = target > excess ? (target - excess) * inflight : 0;
+    if (next == 0 || next >= model_budget) { if (model_budget < 2) break; model_budget = std::min(model_budget - 1, next ? next : model_budget / 2); }
+    else model_budget = next;
+  }
+  r->feasible = 0;
+  return DP_E_BUDGET;
+}
+
 dp_status dp_plan_generate(const dp_stage_config *cfg, const dp_cost_model *cm, uint64_t budget_bytes,
                            uint32_t inflight, uint64_t fixed_bytes, uint32_t flags, uint8_t *plan_out, size_t plan_len,
                            dp_memopt_report *report) {
@@ -1205,38 +1241,12 @@ dp_status dp_plan_generate(const dp_stage_config *cfg, const dp_cost_model *cm, 
     memcpy(plan_out, plan.data(), plan_len);
     return ok ? DP_OK : fail(DP_E_BUDGET, "no plan of the model fits %llu bytes", (unsigned long long)budget_bytes);
   }
-  // Against the executor: the model sees saved tensors only, the executor also holds transient
-  // gradients, workspaces and fragmentation.  Plan for the model, ask the validator for the
-  // true peak, and hand the difference back to the model as a smaller budget until it fits.
-  dp_plan_report keep;
-  plan.assign(plan_len, DP_KEEP);
-  (void)validate(c, plan.data(), plan_len, 0, 1, &keep, env_mfma_enabled(), kFuseGeluDefault);
-  const uint64_t fixed = keep.fixed_bytes;
-  uint64_t model_budget = budget_bytes;
-  for (int round = 1; round <= 6; ++round) {
-    r->refine_rounds = round;
-    const bool ok = memopt(c, *cm, model_budget, inflight, fixed, plan, r);
-    memcpy(plan_out, plan.data(), plan_len);
-    dp_plan_report vr;
-    long hold = 0;
-    const dp_status vs = validate(c, plan.data(), plan_len, budget_bytes, inflight, &vr, env_mfma_enabled(), kFuseGeluDefault, &hold);
-    r->validated_peak_bytes = vr.peak_bytes;
-    if (vs == DP_OK) {
-      r->feasible = 1;
-      r->exact_step_ns = walk_cost(c, *cm, plan.data(), true, hold).step_ns;
-      return DP_OK;
-    }
-    if (vs != DP_E_BUDGET) return vs;
-    if (!ok || budget_bytes == 0) break;
-    const uint64_t excess = vr.peak_bytes > r->peak_bytes ? vr.peak_bytes - r->peak_bytes : 0;
-    const uint64_t target = budget_bytes / inflight;
-    const uint64_t next = target > excess ? (target - excess) * inflight : 0;
-    if (next == 0 || next >= model_budget) { if (model_budget < 2) break; model_budget = std::min(model_budget - 1, next ? next : model_budget / 2); }
-    else model_budget = next;
-  }
-  r->feasible = 0;
-  return fail(DP_E_BUDGET, "no generated plan fits %llu bytes (last true peak %llu)", (unsigned long long)budget_bytes,
-              (unsigned long long)r->validated_peak_bytes);
+  const dp_status vs = memopt_validated(c, *cm, budget_bytes, inflight, plan, r);
+  memcpy(plan_out, plan.data(), plan_len);
+  if (vs == DP_E_BUDGET)
+    return fail(DP_E_BUDGET, "no generated plan fits %llu bytes (last true peak %llu)", (unsigned long long)budget_bytes,
+                (unsigned long long)r->validated_peak_bytes);
+  return vs;
 }
 
 // Copies the caller's parameters (and the transposed matrices the kernels want) into a version
@@ -1487,10 +1497,12 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   }
   // The host runs at most two backward passes ahead of the device; with a plan that swaps it
   // waits for the slot's last backward, since copies and cross-stream waits queued far ahead
-  // of the device ran markedly slower (measured at 4 x GPT-2 5.3B layers, two in flight: 94
-  // instead of 87 ms a micro-batch).
+  // of the device ran markedly slower (measured with budget 0, i.e. the tightest arena policy:
+  // 6 GPT-2 1.5B layers, four in flight, every slot swapped: 92 instead of 63 ms a micro-batch;
+  // never faster).  Debug bit 3 drops this wait.
   if (hipEvent_t e = st->bwd_end[st->bwd_issued % 2]) HIP_TRY(hipEventSynchronize(e), DP_E_HIP);
-  if (rep.n_swapped_slots > 0 && f.done != nullptr) HIP_TRY(hipEventSynchronize(f.done), DP_E_HIP);
+  if (rep.n_swapped_slots > 0 && (st->debug & 8u) == 0 && f.done != nullptr)
+    HIP_TRY(hipEventSynchronize(f.done), DP_E_HIP);
   s = ensure_memory(&f.arena, &f.arena_bytes, &f.host_pool, &f.host_bytes, rep);
   if (s != DP_OK) return s;
   // the slot's last micro-batch leaves its arena before this one's kernels touch it
@@ -1682,6 +1694,7 @@ struct Partitioner {
   std::vector<uint64_t> extra_bytes;
   int64_t layer_ns = 0;
   uint64_t layer_saved = 0, lcm_depths = 1;
+  bool validated = false;       // stage memory from the executor's validator instead of the model
   int n_memopt = 0, n_positions = 0;
   std::vector<std::pair<std::array<int, 3>, std::shared_ptr<const StageRes>>> cache;
 
@@ -1717,6 +1730,34 @@ struct Partitioner {
     int64_t extra = 0;
     for (int l = a; l < b; ++l) { fixed += extra_bytes[(size_t)l]; extra += extra_ns[(size_t)l]; }
     r->plan.assign((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
+    if (validated) {
+      // The validator accounts for the library's weight copies, the gradients and the stage's
+      // buffers itself; only the caller's extras come on top, as bytes no plan can remove.
+      uint64_t extras = 0;
+      for (int l = a; l < b; ++l) extras += extra_bytes[(size_t)l];
+      const uint64_t share = M / k;                      // one micro-batch's part of the device
+      const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, 0);
+      r->base = keep.step_ns + extra;
+      dp_plan_report vr;
+      if (M == 0 || share > extras) {
+        const uint64_t b1 = M == 0 ? 0 : share - extras;  // budget of one micro-batch without the extras
+        if (validate(c, r->plan.data(), r->plan.size(), b1, 1, &vr, env_mfma_enabled(), kFuseGeluDefault) == DP_OK) {
+          r->t = r->base; r->peak = vr.peak_bytes + extras;
+          cache.emplace_back(key, r);
+          return r;
+        }
+        ++n_memopt;
+        dp_memopt_report rep;
+        memset(&rep, 0, sizeof rep);
+        const dp_status vs = memopt_validated(c, *cm, b1, 1, r->plan, &rep);
+        r->mopt = true; r->moo = rep.moo_ns; r->peak = rep.validated_peak_bytes + extras;
+        r->t = vs == DP_OK ? rep.base_ns + rep.moo_ns + extra : kNever;
+      } else {
+        r->mopt = true; r->t = kNever; r->peak = extras;
+      }
+      cache.emplace_back(key, r);
+      return r;
+    }
     const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, 0);
     const uint64_t keep_peak = fixed + keep.slot_peak;
     if (M == 0 || (unsigned __int128)k * keep_peak <= M) {
@@ -1805,8 +1846,9 @@ struct Partitioner {
 
 dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm, int32_t n_stages,
                        uint64_t budget_bytes, uint64_t fixed_per_layer, uint64_t fixed_per_stage,
-                       const int64_t *extra_ns, const uint64_t *extra_bytes, int32_t *cuts_out, uint8_t *plan_out,
-                       size_t plan_len, dp_partition_stage *stages_out, dp_partition_report *report) {
+                       const int64_t *extra_ns, const uint64_t *extra_bytes, uint32_t flags, int32_t *cuts_out,
+                       uint8_t *plan_out, size_t plan_len, dp_partition_stage *stages_out,
+                       dp_partition_report *report) {
   Cfg c;
   dp_status s = parse_cfg(chain_cfg, &c);
   if (s != DP_OK) return s;
@@ -1816,7 +1858,9 @@ dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm
   if (plan_out == nullptr || stages_out == nullptr || (n_stages > 1 && cuts_out == nullptr))
     return fail(DP_E_INVAL, "null output argument");
   if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", DP_SLOTS_PER_LAYER);
+  if ((flags & ~(uint32_t)DP_MEMOPT_VALIDATE) != 0) return fail(DP_E_INVAL, "unknown flag bits 0x%x", flags);
   Partitioner p;
+  p.validated = (flags & DP_MEMOPT_VALIDATE) != 0;
   p.layer = c; p.cm = cm; p.n = c.L; p.ell = n_stages; p.M = budget_bytes;
   p.fixed_per_layer = fixed_per_layer; p.fixed_per_stage = fixed_per_stage;
   p.extra_ns.assign((size_t)c.L, 0); p.extra_bytes.assign((size_t)c.L, 0);

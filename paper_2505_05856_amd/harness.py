@@ -120,3 +120,29 @@ class ScheduleRunner:
 
     def close(self):
         self.stage.close()
+
+
+def steady_state_ms(run: "StageRunner", plan, inflight: int, budget_bytes: int, warmup: int, steps: int) -> float:
+    """Milliseconds per micro-batch in the steady state of a one-forward-one-backward schedule with
+    `inflight` micro-batches between forward and backward: the backward of the oldest, then the forward of
+    the next into the slot it left, gradients accumulating.  Timing and slot bookkeeping only."""
+    import time
+    k, st = inflight, run.stage
+    for s in range(k):
+        B.stage_forward(st, s, k, run.x, plan, budget_bytes, run.y)
+
+    def turn(i):
+        B.stage_backward(st, i % k, run.dy, run.dx, run.g, B.GRAD_ACCUMULATE if i else 0)
+        B.stage_forward(st, i % k, k, run.x, plan, budget_bytes, run.y)
+    for i in range(warmup):
+        turn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        turn(warmup + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    for s in range(k):
+        B.stage_backward(st, s, run.dy, run.dx, run.g, B.GRAD_ACCUMULATE)
+    torch.cuda.synchronize()
+    return ms

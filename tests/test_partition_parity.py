@@ -97,3 +97,39 @@ def test_argument_errors():
     assert B.STATUS[code] == "DP_E_INVAL"
     code, out = B.partition(bc, cm, 4, 1000, 1, 1, raise_on_error=False)
     assert B.STATUS[code] == "DP_E_BUDGET" and not out["feasible"]
+
+
+def test_validated_search_returns_stages_the_executor_accepts():
+    """DP_MEMOPT_VALIDATE: memory is the validator's.  Every stage's plan must pass
+    dp_plan_validate with the stage's in-flight count under the device budget; the model-only
+    search, which does not see transient gradients and workspaces, may return one that does not."""
+    import dataclasses
+    cfg = syn.StageConfig(12, 128, 4, 512, 64, 2, "pre", True, "erf", "bf16")
+    ocm, cm = seeded_cost_model(21, 200000, (2000, 2000))
+    bc = to_binding_config(cfg)
+    one = dataclasses.replace(cfg, n_layers=1)
+    _, r1 = B.plan_validate(to_binding_config(one), syn.plan_keep_all(one))
+    fl = r1["weight_bytes"] + r1["grad_bytes"]
+    fs = r1["fixed_bytes"] - fl
+    _, loose = B.partition(bc, cm, 4, 0, fl, fs, flags=B.MEMOPT_VALIDATE)
+    assert loose["cuts"] == [3, 6, 9] and not loose["any_memopt"]
+    need = max(s["peak_bytes"] * s["inflight"] for s in loose["stages"])
+    seen_memopt = seen_moved = False
+    for frac in (100, 85, 70, 55, 45):
+        budget = need * frac // 100
+        code, got = B.partition(bc, cm, 4, budget, fl, fs, flags=B.MEMOPT_VALIDATE, raise_on_error=False)
+        if code != 0:
+            assert B.STATUS[code] == "DP_E_BUDGET"
+            continue
+        for s in got["stages"]:
+            sc = to_binding_config(dataclasses.replace(cfg, n_layers=s["n_layers"]))
+            vcode, vr = B.plan_validate(sc, s["plan"], budget_bytes=budget, inflight=s["inflight"], raise_on_error=False)
+            assert vcode == 0, (frac, s["first_layer"], B.last_error())
+            assert s["inflight"] * vr["peak_bytes"] <= budget and vr["peak_bytes"] == s["peak_bytes"]
+            assert s["time_ns"] == s["base_ns"] + s["moo_ns"]
+        assert got["time_ns"] == max(s["time_ns"] for s in got["stages"])
+        seen_memopt |= got["any_memopt"]
+        seen_moved |= got["cuts"] != [3, 6, 9]
+    assert seen_memopt and seen_moved
+    code, _ = B.partition(bc, cm, 4, 0, fl, fs, flags=4, raise_on_error=False)
+    assert B.STATUS[code] == "DP_E_INVAL"
