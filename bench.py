@@ -154,6 +154,9 @@ def main():
                          "(dp_partition, cost model measured here) and time every stage of the result")
     ap.add_argument("--chain-layers", type=int, default=24)
     ap.add_argument("--budget-gb", type=float, default=0.0, help="with --partition: device memory per stage (0 = no limit)")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="also measure what the matrix cores sustain with nothing else in the way, on zeros and on "
+                         "this workload's own weights and activations (the clock under load depends on the data)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate on the attention probabilities and after the projection and FC2 (default: none)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -293,6 +296,15 @@ def main():
                     "budget_bytes": k * budget, "device_bytes_held": k * rep["arena_peak_bytes"],
                     "vs_fused_step": round(ms / sms, 4)}
 
+    probe = None
+    if args.mfma_probe and cfg.dtype == "bf16":
+        probe = {}
+        for tag, t in (("zeros", torch.zeros(1 << 20, dtype=torch.bfloat16, device="cuda:0")),
+                       ("weights", run.w[0]["w_fc1"]), ("activations", run.x),
+                       ("random_bits", torch.randint(-2 ** 15, 2 ** 15, (1 << 20,), dtype=torch.int16,
+                                                     device="cuda:0").view(torch.bfloat16))):
+            tf, mhz = B.probe_mfma(t, 40000)
+            probe[tag] = {"tflops": round(tf, 1), "shader_mhz": round(mhz)}
     partition = None
     if args.partition > 0:
         partition = partition_and_measure(args, cfg, run)
@@ -323,6 +335,10 @@ def main():
         out["schedule"] = schedule
     if partition is not None:
         out["partition"] = partition
+    if probe is not None:
+        out["mfma_issue_probe"] = probe
+        if roof is not None and roof["bound"] == "mfma":
+            roof["frac_of_issue_rate_on_activations"] = round(roof["achieved"] / probe["activations"]["tflops"], 4)
     if memopt is not None:
         memopt["measured_ms"] = round(ms, 4)
         out["memopt"] = memopt

@@ -442,6 +442,16 @@ dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32
                                       const void *d_o, void *dqkv, void *ws, const dp_dropout *drop,
                                       void *hip_stream);
 
+/* Diagnostic for reading the roofline: the rate at which the matrix cores issue
+ * v_mfma_f32_32x32x16_bf16 when nothing else limits them (operands in registers, 16
+ * independent accumulators a wave, one workgroup a CU, `iters` rounds), with the operand bits
+ * taken from `data_bf16` (device, n_elems a multiple of 8), and the shader clock held over the
+ * loop.  The clock, and with it the attainable rate, depends on the data: all-zero operands
+ * run at the nominal clock, operands with random mantissas draw more power and run slower.
+ * Allocates a small device buffer and waits for completion. */
+dp_status dp_probe_mfma(const void *data_bf16, size_t n_elems, int32_t iters, float *tflops,
+                        float *shader_mhz, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

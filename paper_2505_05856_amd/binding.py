@@ -137,11 +137,12 @@ def lib() -> C.CDLL:
     L.dp_partition.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), i32, u64, u64, u64, C.POINTER(C.c_int64),
                                C.POINTER(u64), C.c_uint32, C.POINTER(i32), vp, sz, C.POINTER(PartitionStage),
                                C.POINTER(PartitionReport)]
+    L.dp_probe_mfma.argtypes = [vp, sz, i32, C.POINTER(C.c_float), C.POINTER(C.c_float), vp]
     L.dp_plan_cost.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), vp, sz, u64, C.POINTER(PlanCostReport)]
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
-    for name in ("dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
+    for name in ("dp_probe_mfma", "dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd"):
@@ -431,3 +432,11 @@ def op_attention_dropout_fwd(qkv, B, S, nh, dh, causal, o, lse, drop: Dropout, s
 def op_attention_dropout_bwd(qkv, o, lse, d_o, B, S, nh, dh, causal, dqkv, ws, drop: Dropout, stream=None):
     _check(lib().dp_op_attention_dropout_bwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv), _ptr(o), _ptr(lse),
                                              _ptr(d_o), _ptr(dqkv), _ptr(ws), C.byref(drop), _stream_ptr(stream)))
+
+
+def probe_mfma(data, iters: int = 20000, stream=None):
+    """Matrix-core issue rate (TFLOP/s) and shader clock (MHz) with operand bits from the bf16 tensor `data`."""
+    tf, mhz = C.c_float(), C.c_float()
+    n = data.numel() // 8 * 8
+    _check(lib().dp_probe_mfma(_ptr(data), n, iters, C.byref(tf), C.byref(mhz), _stream_ptr(stream)))
+    return float(tf.value), float(mhz.value)

@@ -130,4 +130,9 @@ hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const 
                                 const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s,
                                 const DropArgs *drop = nullptr);
 
+// ---- diagnostics --------------------------------------------------------------
+// Matrix-core issue rate with operand fragments taken from `data` (bf16, n_elems >= 8); waits.
+hipError_t run_mfma_probe(const void *data, size_t n_elems, int iters, int n_cus, float *tflops, float *shader_mhz,
+                          hipStream_t s);
+
 }  // namespace dp

@@ -2143,4 +2143,16 @@ dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32
 }
 
 
+dp_status dp_probe_mfma(const void *data_bf16, size_t n_elems, int32_t iters, float *tflops, float *shader_mhz,
+                        void *hip_stream) {
+  if (!data_bf16 || n_elems < 8 || n_elems % 8 || iters < 1 || !tflops || !shader_mhz)
+    return fail(DP_E_INVAL, "probe_mfma: bad argument");
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev), DP_E_HIP);
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), DP_E_HIP);
+  *tflops = 0.f; *shader_mhz = 0.f;
+  return op_done(dp::run_mfma_probe(data_bf16, n_elems, iters, cus, tflops, shader_mhz, (hipStream_t)hip_stream),
+                 "probe_mfma");
+}
+
 }  // extern "C"

@@ -160,3 +160,19 @@ def test_attention(dt, causal, Bn, S, nh, dh, sharp):
     got = host(dqkv)
     for blk in range(3):
         assert O.max_rel_err(got[:, blk * H:(blk + 1) * H], dq_ref[:, blk * H:(blk + 1) * H]) < 2 * tol, blk
+
+
+def test_mfma_issue_probe_reports_a_plausible_rate():
+    """The diagnostic behind the roofline discussion: rate = CUs * 4096 flop/clk * clock, so the two numbers it
+    returns must agree with each other, and zeros must not run slower than random mantissas."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    zeros = torch.zeros(1 << 16, dtype=torch.bfloat16, device=DEV)
+    noise = torch.randint(-2 ** 15, 2 ** 15, (1 << 16,), dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    tz, fz = B.probe_mfma(zeros, 20000)
+    tn, fn = B.probe_mfma(noise, 20000)
+    for t, f in ((tz, fz), (tn, fn)):
+        assert 500 < f < 3000
+        assert abs(t * 1e12 - cus * 4096 * f * 1e6) <= 0.1 * t * 1e12      # includes launch and drain
+    assert tz >= 0.98 * tn
+    with pytest.raises(B.DpError):
+        B.probe_mfma(zeros[:4], 10)
