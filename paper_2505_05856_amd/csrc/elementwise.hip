@@ -86,48 +86,107 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
 #pragma unroll
     for (int i = 0; i < 8; ++i) { dg[c][i] = 0.f; db[c][i] = 0.f; if (SUMDX) ds[c][i] = 0.f; }
   const float inv_n = 1.0f / (float)cols;
-  for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
-    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
-    const size_t base = (size_t)row * cols;
-    float xh[NC][8], g[NC][8];
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int col = (c * 64 + lane) * 8;
-      if (col < cols) {
-        float d[8], gm[8];
-        load8(x + base + col, xh[c]);
-        load8(dy + base + col, d);
-        load8(gamma + col, gm);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          xh[c][i] = (xh[c][i] - mean) * rstd;
-          dg[c][i] += d[i] * xh[c][i];
-          db[c][i] += d[i];
-          g[c][i] = d[i] * gm[i];
-          s1 += g[c][i];
-          s2 += g[c][i] * xh[c][i];
+  // Up to 2048 columns the row stays in registers between the row reductions and the output;
+  // wider rows are read twice (the second time out of the caches): there the column
+  // accumulators alone take 16..24 registers per 512 columns, and occupancy is what hides
+  // the latency (measured: 4096 columns 1.6 instead of 2.0 ms for the 8 launches of a step;
+  // 1024 and 1600 columns the other way round).  Same arithmetic, same order, either way.
+  if constexpr (NC <= 4) {
+    for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
+      const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+      const size_t base = (size_t)row * cols;
+      float xh[NC][8], g[NC][8];
+      float s1 = 0.f, s2 = 0.f;
+  #pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          float d[8], gm[8];
+          load8(x + base + col, xh[c]);
+          load8(dy + base + col, d);
+          load8(gamma + col, gm);
+  #pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            xh[c][i] = (xh[c][i] - mean) * rstd;
+            dg[c][i] += d[i] * xh[c][i];
+            db[c][i] += d[i];
+            g[c][i] = d[i] * gm[i];
+            s1 += g[c][i];
+            s2 += g[c][i] * xh[c][i];
+          }
+        }
+      }
+      const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+  #pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          float o[8];
+  #pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = rstd * (g[c][i] - m1 - xh[c][i] * m2);
+          if (dres != nullptr) {
+            float r[8];
+            load8(dres + base + col, r);
+  #pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] += r[i];
+          }
+          store8(dx + base + col, o);
+          if (SUMDX) {
+  #pragma unroll
+            for (int i = 0; i < 8; ++i) ds[c][i] += (float)(T)o[i];   // the value as stored
+          }
         }
       }
     }
-    const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int col = (c * 64 + lane) * 8;
-      if (col < cols) {
-        float o[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = rstd * (g[c][i] - m1 - xh[c][i] * m2);
-        if (dres != nullptr) {
-          float r[8];
-          load8(dres + base + col, r);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) o[i] += r[i];
+  } else {
+    for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
+      const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+      const size_t base = (size_t)row * cols;
+        float s1 = 0.f, s2 = 0.f;
+  #pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          float xh[8], d[8], gm[8];
+          load8(x + base + col, xh);
+          load8(dy + base + col, d);
+          load8(gamma + col, gm);
+  #pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            xh[i] = (xh[i] - mean) * rstd;
+            dg[c][i] += d[i] * xh[i];
+            db[c][i] += d[i];
+            const float g = d[i] * gm[i];
+            s1 += g;
+            s2 += g * xh[i];
+          }
         }
-        store8(dx + base + col, o);
-        if (SUMDX) {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) ds[c][i] += (float)(T)o[i];   // the value as stored
+      }
+      const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+  #pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          float xh[8], d[8], gm[8], o[8];
+          load8(x + base + col, xh);
+          load8(dy + base + col, d);
+          load8(gamma + col, gm);
+  #pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            xh[i] = (xh[i] - mean) * rstd;
+            o[i] = rstd * (d[i] * gm[i] - m1 - xh[i] * m2);
+          }
+          if (dres != nullptr) {
+            float r[8];
+            load8(dres + base + col, r);
+  #pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] += r[i];
+          }
+          store8(dx + base + col, o);
+          if (SUMDX) {
+  #pragma unroll
+            for (int i = 0; i < 8; ++i) ds[c][i] += (float)(T)o[i];   // the value as stored
+          }
         }
       }
     }
