@@ -384,7 +384,10 @@ const char *dp_last_error(void);
  * `hip_stream`, no host wait).  They run the same kernels dp_stage_step uses
  * and exist for operator-level parity tests and microbenchmarks.
  * `ws` is a device workspace of at least dp_op_workspace_bytes(...) bytes
- * (needed by the ops that reduce over rows; may be NULL otherwise). */
+ * (needed by the ops that reduce over rows; may be NULL otherwise).
+ * Empty inputs are valid: with a zero extent nothing is read (the corresponding
+ * pointers may be NULL), sums over no rows are written as zeros, and a GEMM with
+ * K = 0 writes bias + res. */
 size_t dp_op_workspace_bytes(int32_t rows, int32_t cols);
 
 /* y = LayerNorm(x)*gamma+beta per row of [rows, cols]; stats [rows,2] fp32

@@ -487,11 +487,22 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
   return reduce_or_defer<T>(part, nb, nv * cols, cols, dgamma, dbeta, dxsum, s, job);
 }
 
+// A sum over no rows is zero: the vectors an empty input leaves behind.
+static hipError_t zero_vec(int dtype, void *p, int n, hipStream_t s) {
+  if (p == nullptr || n <= 0) return hipSuccess;
+  return launch_fill_u32(p, (size_t)n * dtype_size(dtype) / 4, 0u, s);
+}
+
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
                          const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
                          void *ws, hipStream_t s, ReduceJob *job) {
   if (job != nullptr) job->nb = 0;
-  if (rows <= 0) return hipSuccess;
+  if (rows <= 0) {
+    hipError_t e = zero_vec(dtype, dgamma, cols, s);
+    if (e == hipSuccess) e = zero_vec(dtype, dbeta, cols, s);
+    if (e == hipSuccess) e = zero_vec(dtype, dxsum, cols, s);
+    return e;
+  }
   if (dxsum != nullptr)
     return dtype == kBF16
                ? ln_bwd_t<bf16, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job)
@@ -517,7 +528,7 @@ static hipError_t gelu_bwd_colsum_t(int kind, int rows, int cols, const void *dy
 hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
                                   void *dbias, void *ws, hipStream_t s, ReduceJob *job) {
   if (job != nullptr) job->nb = 0;
-  if (rows <= 0) return hipSuccess;
+  if (rows <= 0) return zero_vec(dtype, dbias, cols, s);
   return dtype == kBF16 ? gelu_bwd_colsum_t<bf16>(kind, rows, cols, dy, x, dx, dbias, ws, s, job)
                         : gelu_bwd_colsum_t<float>(kind, rows, cols, dy, x, dx, dbias, ws, s, job);
 }
@@ -580,7 +591,7 @@ static hipError_t colsum_t(int rows, int cols, const void *x, void *out, void *w
 hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s,
                          ReduceJob *job) {
   if (job != nullptr) job->nb = 0;
-  if (rows <= 0) return hipSuccess;
+  if (rows <= 0) return zero_vec(dtype, out, cols, s);
   return dtype == kBF16 ? colsum_t<bf16>(rows, cols, x, out, ws, s, job) : colsum_t<float>(rows, cols, x, out, ws, s, job);
 }
 

@@ -2006,6 +2006,7 @@ static bool bad_dtype(int32_t d) { return d != DP_F32 && d != DP_BF16; }
 
 dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x, const void *gamma,
                               const void *beta, void *y, float *stats, void *hip_stream) {
+  if (!bad_dtype(dtype) && rows == 0) return DP_OK;   // nothing to do; the row pointers may be null
   if (bad_dtype(dtype) || rows < 0 || !x || !gamma || !beta) return fail(DP_E_INVAL, "layernorm_fwd: bad argument");
   if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
   return op_done(dp::launch_ln_fwd(dtype, rows, cols, eps, x, gamma, beta, y, stats, (hipStream_t)hip_stream),
@@ -2015,22 +2016,22 @@ dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float e
 dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
                               const float *stats, const void *gamma, const void *dres, void *dx, void *dgamma,
                               void *dbeta, void *dx_colsum, void *ws, void *hip_stream) {
-  if (bad_dtype(dtype) || rows < 0 || !dy || !x || !stats || !gamma || !dx || !dgamma || !dbeta || !ws)
-    return fail(DP_E_INVAL, "layernorm_bwd: bad argument");
+  if (bad_dtype(dtype) || rows < 0 || !dgamma || !dbeta || (rows > 0 && (!dy || !x || !stats || !gamma || !dx || !ws)))
+    return fail(DP_E_INVAL, "layernorm_bwd: bad argument");   // (no rows: only the sums, which become zero, are touched)
   if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
   return op_done(dp::launch_ln_bwd(dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dx_colsum, ws,
                                    (hipStream_t)hip_stream), "layernorm_bwd");
 }
 
 dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream) {
-  if (bad_dtype(dtype) || !x || !y || (gelu_kind != 0 && gelu_kind != 1)) return fail(DP_E_INVAL, "gelu_fwd: bad argument");
+  if (bad_dtype(dtype) || (n > 0 && (!x || !y)) || (gelu_kind != 0 && gelu_kind != 1)) return fail(DP_E_INVAL, "gelu_fwd: bad argument");
   if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
   return op_done(dp::launch_gelu_fwd(dtype, gelu_kind, n, x, y, (hipStream_t)hip_stream), "gelu_fwd");
 }
 
 dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,
                          void *hip_stream) {
-  if (bad_dtype(dtype) || !x || !dy || !dx || (gelu_kind != 0 && gelu_kind != 1))
+  if (bad_dtype(dtype) || (n > 0 && (!x || !dy || !dx)) || (gelu_kind != 0 && gelu_kind != 1))
     return fail(DP_E_INVAL, "gelu_bwd: bad argument");
   if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
   return op_done(dp::launch_gelu_bwd(dtype, gelu_kind, n, dy, x, dx, (hipStream_t)hip_stream), "gelu_bwd");
@@ -2038,8 +2039,10 @@ dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void 
 
 dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void *A, const void *B,
                      const void *bias, const void *res, void *C, void *hip_stream) {
-  if (bad_dtype(dtype) || (mode != 0 && mode != 1) || M < 0 || N < 0 || K < 0 || !A || !B || !C)
+  if (bad_dtype(dtype) || (mode != 0 && mode != 1) || M < 0 || N < 0 || K < 0)
     return fail(DP_E_INVAL, "gemm: bad argument");
+  if (M == 0 || N == 0) return DP_OK;                        // no output element
+  if (!C || (K > 0 && (!A || !B))) return fail(DP_E_INVAL, "gemm: null operand");   // (K = 0: C = bias + res)
   dp::GemmArgs a{mode, M, N, K, A, B, bias, res, C};
   const char *env = getenv("DPSTAGE_KERNELS");
   const bool simple = env != nullptr && strcmp(env, "simple") == 0;
@@ -2050,14 +2053,14 @@ dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t 
 
 dp_status dp_op_colsum(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out, void *ws,
                        void *hip_stream) {
-  if (bad_dtype(dtype) || rows < 0 || cols <= 0 || !x || !out || !ws) return fail(DP_E_INVAL, "colsum: bad argument");
+  if (bad_dtype(dtype) || rows < 0 || cols <= 0 || !out || (rows > 0 && (!x || !ws))) return fail(DP_E_INVAL, "colsum: bad argument");
   if (cols % 8) return fail(DP_E_UNSUPPORTED, "colsum: cols must be a multiple of 8");
   return op_done(dp::launch_colsum(dtype, rows, cols, x, out, ws, (hipStream_t)hip_stream), "colsum");
 }
 
 dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                               const void *qkv, void *o, float *lse, void *hip_stream) {
-  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv) return fail(DP_E_INVAL, "attention_fwd: bad argument");
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && !qkv)) return fail(DP_E_INVAL, "attention_fwd: bad argument");
   if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
   const char *env = getenv("DPSTAGE_KERNELS");
   const bool simple = env != nullptr && strcmp(env, "simple") == 0;
@@ -2071,7 +2074,7 @@ dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, i
 dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                               const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv, void *ws,
                               void *hip_stream) {
-  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv || !o || !lse || !d_o || !dqkv || !ws)
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && (!qkv || !o || !lse || !d_o || !dqkv || !ws)))
     return fail(DP_E_INVAL, "attention_bwd: bad argument");
   if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
   const char *env = getenv("DPSTAGE_KERNELS");
@@ -2106,7 +2109,7 @@ dp_status dp_op_dropout(int32_t dtype, size_t n, const void *x, const void *res,
 
 dp_status dp_op_attention_dropout_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                                       const void *qkv, void *o, float *lse, const dp_dropout *drop, void *hip_stream) {
-  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv) return fail(DP_E_INVAL, "attention_fwd: bad argument");
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && !qkv)) return fail(DP_E_INVAL, "attention_fwd: bad argument");
   if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
   if ((long)S * S >= (1L << 32)) return fail(DP_E_UNSUPPORTED, "attention dropout needs seq*seq < 2^32");
   dp::DropArgs a;
@@ -2125,7 +2128,7 @@ dp_status dp_op_attention_dropout_fwd(int32_t dtype, int32_t B, int32_t S, int32
 dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                                       const void *qkv, const void *o, const float *lse, const void *d_o, void *dqkv,
                                       void *ws, const dp_dropout *drop, void *hip_stream) {
-  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || !qkv || !o || !lse || !d_o || !dqkv || !ws)
+  if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && (!qkv || !o || !lse || !d_o || !dqkv || !ws)))
     return fail(DP_E_INVAL, "attention_bwd: bad argument");
   if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
   if ((long)S * S >= (1L << 32)) return fail(DP_E_UNSUPPORTED, "attention dropout needs seq*seq < 2^32");
