@@ -172,7 +172,12 @@ dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size
  * A backward node's time covers all its kernels (input and weight gradients, reductions). */
 typedef struct {
   int64_t fwd_ns[8], bwd_ns[8];                /* nanoseconds per node */
-  uint64_t d2h_bytes_per_us, h2d_bytes_per_us; /* host link speed each way */
+  uint64_t d2h_bytes_per_us, h2d_bytes_per_us; /* host link speed each way, one direction busy */
+  /* The same with both directions busy at once (0 = not known, the figures above are used).
+   * The planners take these for a stage that keeps two or more micro-batches in flight: in
+   * the steady state of a one-forward-one-backward schedule the copy-outs of one micro-batch
+   * and the copy-ins of another run side by side all the time. */
+  uint64_t d2h_duplex_bytes_per_us, h2d_duplex_bytes_per_us;
 } dp_cost_model;
 
 typedef struct {
@@ -334,8 +339,9 @@ dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches
  *   assumes that memory can be optimised away evenly).
  * flags = DP_MEMOPT_VALIDATE: a stage's memory is what dp_plan_validate reports for its plan
  *   (library weight copies, gradients, buffers, arena with its transients and fragmentation)
- *   plus its extra_bytes, and MemOpt runs as dp_plan_generate does under that flag, so every
- *   stage of the result is executable within the budget; fixed_per_layer and fixed_per_stage
+ *   plus its extra_bytes, and MemOpt runs as dp_plan_generate does under that flag (a stage's
+ *   time is then the report's exact_step_ns), so every stage of the result is executable
+ *   within the budget; fixed_per_layer and fixed_per_stage
  *   still steer the memory-balanced walk.  The balance walks and the traversal are unchanged.
  * Outputs: cuts_out[n_stages-1] (first layer of stages 2..l), plan_out (the stages' plans one
  * after the other, n_layers * DP_SLOTS_PER_LAYER bytes; each stage's first X_IN is KEEP),
@@ -362,7 +368,7 @@ dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm
 /* Fills a cost model from this stage on this machine: `steps` all-KEEP steps with every
  * launch bracketed (node times averaged over layers and steps), then a block of FC1_OUT's
  * size copied four times each way through pinned host memory on the library's copy
- * streams.  Buffers as dp_stage_step (they are overwritten).  Waits for the device. */
+ * streams, first one direction at a time, then both at once (the two-way figures).  Buffers as dp_stage_step (they are overwritten).  Waits for the device. */
 dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void *dy, void *y_out,
                                       void *dx_out, const dp_layer_grads *dw, void *hip_stream,
                                       int32_t steps, dp_cost_model *out);

@@ -122,10 +122,22 @@ class CostModel:
     """fwd_ns[i], bwd_ns[i]: time of the i-th forward / backward node of a layer (execution
     order of the style); d2h, h2d: link speed in bytes per microsecond."""
 
-    def __init__(self, fwd_ns: Sequence[int], bwd_ns: Sequence[int], d2h_bytes_per_us: int, h2d_bytes_per_us: int):
+    def __init__(self, fwd_ns: Sequence[int], bwd_ns: Sequence[int], d2h_bytes_per_us: int, h2d_bytes_per_us: int,
+                 d2h_duplex: int = 0, h2d_duplex: int = 0):
         assert len(fwd_ns) == 8 and len(bwd_ns) == 8
         self.fwd, self.bwd = [int(v) for v in fwd_ns], [int(v) for v in bwd_ns]
         self.d2h, self.h2d = int(d2h_bytes_per_us), int(h2d_bytes_per_us)
+        # link speed with both directions busy (0: not known)
+        self.d2h_duplex, self.h2d_duplex = int(d2h_duplex), int(h2d_duplex)
+
+    def for_inflight(self, inflight: int) -> "CostModel":
+        """The model a planner uses for a stage with `inflight` micro-batches between forward and
+        backward: from two on, copy-outs of one micro-batch and copy-ins of another run side by
+        side all the time, so the two-way link speed applies where it is known."""
+        if inflight < 2:
+            return self
+        return CostModel(self.fwd, self.bwd, self.d2h_duplex or self.d2h, self.h2d_duplex or self.h2d,
+                         self.d2h_duplex, self.h2d_duplex)
 
     def out_ns(self, nbytes):
         return -((-nbytes * 1000) // self.d2h)      # ceiling
@@ -302,6 +314,7 @@ def memopt(shape: StageShape, cm: CostModel, budget_bytes: int, inflight: int = 
     number of tensors swapped for free, swapped at a cost and recomputed."""
     L = shape.L
     plan = [KEEP] * (L * N_SLOTS)
+    cm = cm.for_inflight(inflight)
 
     def cost(p):
         r = plan_cost(shape, cm, p, fixed_bytes)

@@ -65,11 +65,14 @@ class StepStats(C.Structure):
 
 class CostModel(C.Structure):
     _fields_ = [("fwd_ns", C.c_int64 * 8), ("bwd_ns", C.c_int64 * 8),
-                ("d2h_bytes_per_us", C.c_uint64), ("h2d_bytes_per_us", C.c_uint64)]
+                ("d2h_bytes_per_us", C.c_uint64), ("h2d_bytes_per_us", C.c_uint64),
+                ("d2h_duplex_bytes_per_us", C.c_uint64), ("h2d_duplex_bytes_per_us", C.c_uint64)]
 
     def as_dict(self):
         return {"fwd_ns": list(self.fwd_ns), "bwd_ns": list(self.bwd_ns),
-                "d2h_bytes_per_us": self.d2h_bytes_per_us, "h2d_bytes_per_us": self.h2d_bytes_per_us}
+                "d2h_bytes_per_us": self.d2h_bytes_per_us, "h2d_bytes_per_us": self.h2d_bytes_per_us,
+                "d2h_duplex_bytes_per_us": self.d2h_duplex_bytes_per_us,
+                "h2d_duplex_bytes_per_us": self.h2d_duplex_bytes_per_us}
 
 
 class PlanCostReport(C.Structure):
@@ -185,11 +188,12 @@ def plan_validate(cfg: StageConfig, plan, budget_bytes: int = 0, inflight: int =
     return code, rep.as_dict()
 
 
-def make_cost_model(fwd_ns, bwd_ns, d2h_bytes_per_us, h2d_bytes_per_us) -> CostModel:
+def make_cost_model(fwd_ns, bwd_ns, d2h_bytes_per_us, h2d_bytes_per_us, d2h_duplex=0, h2d_duplex=0) -> CostModel:
     cm = CostModel()
     for i in range(8):
         cm.fwd_ns[i], cm.bwd_ns[i] = int(fwd_ns[i]), int(bwd_ns[i])
     cm.d2h_bytes_per_us, cm.h2d_bytes_per_us = int(d2h_bytes_per_us), int(h2d_bytes_per_us)
+    cm.d2h_duplex_bytes_per_us, cm.h2d_duplex_bytes_per_us = int(d2h_duplex), int(h2d_duplex)
     return cm
 
 

@@ -1057,8 +1057,21 @@ struct Cand { int l, slot; int64_t free_ns; };
 // The planner proper (Section 4.3): swaps by decreasing FreeTime while they stay hidden, then
 // the action with the most memory saved per second of overhead, until inflight * peak fits.
 // Peak = fixed_bytes + running peak of the saved tensors.  Returns false if it cannot fit.
-bool memopt(const Cfg &c, const dp_cost_model &cm, uint64_t budget, uint32_t inflight, uint64_t fixed_bytes,
+// The model a planner uses for a stage with `inflight` micro-batches between forward and
+// backward: from two on, copy-outs of one micro-batch and copy-ins of another run side by side
+// all the time, so the two-way link speed applies where it is known.
+dp_cost_model for_inflight(const dp_cost_model &cm, uint32_t inflight) {
+  dp_cost_model e = cm;
+  if (inflight >= 2) {
+    if (cm.d2h_duplex_bytes_per_us) e.d2h_bytes_per_us = cm.d2h_duplex_bytes_per_us;
+    if (cm.h2d_duplex_bytes_per_us) e.h2d_bytes_per_us = cm.h2d_duplex_bytes_per_us;
+  }
+  return e;
+}
+
+bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32_t inflight, uint64_t fixed_bytes,
             std::vector<uint8_t> &plan, dp_memopt_report *rep) {
+  const dp_cost_model cm = for_inflight(cm_given, inflight);
   const OpDef *ops = c.pre ? kPreOps : kPostOps;
   const BwdReads *bwd = c.pre ? kPreBwd : kPostBwd;
   plan.assign((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
@@ -1207,7 +1220,7 @@ static dp_status memopt_validated(const Cfg &c, const dp_cost_model &cm, uint64_
     r->validated_peak_bytes = vr.peak_bytes;
     if (vs == DP_OK) {
       r->feasible = 1;
-      r->exact_step_ns = walk_cost(c, cm, plan.data(), true, hold).step_ns;
+      r->exact_step_ns = walk_cost(c, for_inflight(cm, inflight), plan.data(), true, hold).step_ns;
       return DP_OK;
     }
     if (vs != DP_E_BUDGET) return vs;
@@ -1735,13 +1748,13 @@ struct Partitioner {
       // buffers itself; only the caller's extras come on top, as bytes no plan can remove.
       uint64_t extras = 0;
       for (int l = a; l < b; ++l) extras += extra_bytes[(size_t)l];
-      const uint64_t share = M / k;                      // one micro-batch's part of the device
+      const unsigned __int128 held_extras = (unsigned __int128)k * extras;   // the extras of every micro-batch in flight
       const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, 0);
       r->base = keep.step_ns + extra;
       dp_plan_report vr;
-      if (M == 0 || share > extras) {
-        const uint64_t b1 = M == 0 ? 0 : share - extras;  // budget of one micro-batch without the extras
-        if (validate(c, r->plan.data(), r->plan.size(), b1, 1, &vr, env_mfma_enabled(), kFuseGeluDefault) == DP_OK) {
+      if (M == 0 || held_extras < M) {
+        const uint64_t bk = M == 0 ? 0 : M - (uint64_t)held_extras;   // what is left for the stage proper, k times over
+        if (validate(c, r->plan.data(), r->plan.size(), bk, k, &vr, env_mfma_enabled(), kFuseGeluDefault) == DP_OK) {
           r->t = r->base; r->peak = vr.peak_bytes + extras;
           cache.emplace_back(key, r);
           return r;
@@ -1749,9 +1762,11 @@ struct Partitioner {
         ++n_memopt;
         dp_memopt_report rep;
         memset(&rep, 0, sizeof rep);
-        const dp_status vs = memopt_validated(c, *cm, b1, 1, r->plan, &rep);
-        r->mopt = true; r->moo = rep.moo_ns; r->peak = rep.validated_peak_bytes + extras;
-        r->t = vs == DP_OK ? rep.base_ns + rep.moo_ns + extra : kNever;
+        const dp_status vs = memopt_validated(c, *cm, bk, k, r->plan, &rep);
+        // time: the model's clocks on the executor's own arena and hold policy where the plan runs
+        r->mopt = true; r->peak = rep.validated_peak_bytes + extras;
+        r->t = vs == DP_OK ? std::max(rep.exact_step_ns, rep.base_ns) + extra : kNever;
+        r->moo = vs == DP_OK ? r->t - r->base : rep.moo_ns;
       } else {
         r->mopt = true; r->t = kNever; r->peak = extras;
       }
@@ -1950,14 +1965,44 @@ dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void
   if (e == hipSuccess) e = hipEventRecord(e1, st->h2d);
   if (e == hipSuccess) e = hipEventSynchronize(e1);
   if (e == hipSuccess) e = hipEventElapsedTime(&ms_in, e0, e1);
+  // both directions at once: a second pair of blocks goes in while the first goes out
+  float ms_out2 = 0.f, ms_in2 = 0.f;
+  void *dev2 = nullptr, *host2 = nullptr;
+  hipEvent_t f0 = nullptr, f1 = nullptr;
+  if (e == hipSuccess && hipMalloc(&dev2, bytes) == hipSuccess && hipHostMalloc(&host2, bytes, hipHostMallocDefault) == hipSuccess) {
+    e = hipEventCreate(&f0);
+    if (e == hipSuccess) e = hipEventCreate(&f1);
+    if (e == hipSuccess) e = hipEventRecord(e0, st->d2h);
+    if (e == hipSuccess) e = hipEventRecord(f0, st->h2d);
+    for (int i = 0; i < kReps && e == hipSuccess; ++i) {
+      e = hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, st->d2h);
+      if (e == hipSuccess) e = hipMemcpyAsync(dev2, host2, bytes, hipMemcpyHostToDevice, st->h2d);
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, st->d2h);
+    if (e == hipSuccess) e = hipEventRecord(f1, st->h2d);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventSynchronize(f1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms_out2, e0, e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms_in2, f0, f1);
+  } else if (e == hipSuccess) {
+    (void)hipGetLastError();   // no room for the second pair: the two-way figures stay unknown
+  }
   if (e0) (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
+  if (f0) (void)hipEventDestroy(f0);
+  if (f1) (void)hipEventDestroy(f1);
   (void)hipHostFree(host);
   (void)hipFree(dev);
+  if (host2) (void)hipHostFree(host2);
+  if (dev2) (void)hipFree(dev2);
   if (e != hipSuccess) return fail(DP_E_HIP, "link probe failed: %s", hipGetErrorString(e));
   if (ms_out <= 0.f || ms_in <= 0.f) return fail(DP_E_HIP, "link probe measured no time");
   out->d2h_bytes_per_us = (uint64_t)((double)bytes * kReps / ((double)ms_out * 1e3));
   out->h2d_bytes_per_us = (uint64_t)((double)bytes * kReps / ((double)ms_in * 1e3));
+  if (ms_out2 > 0.f && ms_in2 > 0.f) {
+    out->d2h_duplex_bytes_per_us = std::min(out->d2h_bytes_per_us, (uint64_t)((double)bytes * kReps / ((double)ms_out2 * 1e3)));
+    out->h2d_duplex_bytes_per_us = std::min(out->h2d_bytes_per_us, (uint64_t)((double)bytes * kReps / ((double)ms_in2 * 1e3)));
+  }
   return DP_OK;
 }
 

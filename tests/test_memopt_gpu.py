@@ -35,6 +35,7 @@ def test_generated_plans_fit_run_and_match_the_prediction(name):
     d = cm.as_dict()
     assert min(d["fwd_ns"]) > 0 and min(d["bwd_ns"]) > 0
     assert 20000 < d["d2h_bytes_per_us"] < 80000 and 20000 < d["h2d_bytes_per_us"] < 80000   # PCIe 5 x16 class link
+    assert 10000 < d["d2h_duplex_bytes_per_us"] <= d["d2h_bytes_per_us"] and 10000 < d["h2d_duplex_bytes_per_us"] <= d["h2d_bytes_per_us"]
     # the model of the unoptimised step is the sum of its nodes (Section 4.1, Eq. 1) and explains the measured step
     t_keep = timed(run, keep, 0)
     base = B.plan_cost(run.bcfg, cm, keep)["step_ns"]

@@ -171,3 +171,19 @@ def test_inflight_multiplies_the_peak():
     assert M.memopt(sh, cm, keep_peak, inflight=1)[1]["moo_ns"] == 0
     plan, rep = M.memopt(sh, cm, keep_peak, inflight=2)
     assert (not rep["feasible"]) or 2 * rep["peak_bytes"] <= keep_peak
+
+
+def test_two_way_link_speed_applies_from_two_micro_batches_in_flight():
+    """A stage that keeps two micro-batches in flight plans with the two-way link speed (its copy-outs and
+    copy-ins overlap all the time); one in flight, or no two-way figure, plans with the one-way speed."""
+    sh = M.StageShape(2, 64, 2, 256, 32, 2, "pre", 2)
+    f, b = [10, 30, 20, 10, 10, 40, 10, 40], [40, 12, 40, 15, 20, 45, 60, 15]
+    fast, slow = M.CostModel(f, b, 40000, 40000), M.CostModel(f, b, 100, 150)
+    both = M.CostModel(f, b, 40000, 40000, 100, 150)
+    keep = M.plan_cost(sh, fast, [M.KEEP] * (2 * M.N_SLOTS))["peak_bytes"]
+    budget = keep * 6 // 10
+    assert M.memopt(sh, both, budget, 1) == M.memopt(sh, fast, budget, 1)
+    assert M.memopt(sh, both, 2 * budget, 2) == M.memopt(sh, slow, 2 * budget, 2)
+    # the fast link hides five swaps behind the computation, the two-way speed hides none
+    assert M.memopt(sh, both, 2 * budget, 2)[1]["free_swaps"] < M.memopt(sh, fast, 2 * budget, 2)[1]["free_swaps"]
+    assert both.for_inflight(1) is both and both.for_inflight(3).d2h == 100 and fast.for_inflight(3).h2d == 40000

@@ -19,7 +19,8 @@ def both_sides(cfg):
 def seeded_cost_model(seed, scale_ns, link):
     z = syn.splitmix64(seed, np.arange(16, dtype=np.uint64))
     t = [int(v % np.uint64(scale_ns)) + scale_ns // 10 for v in z]
-    return (M.CostModel(t[:8], t[8:], link[0], link[1]), B.make_cost_model(t[:8], t[8:], link[0], link[1]))
+    duplex = (max(1, link[0] * 3 // 4), max(1, link[1] * 4 // 5))     # two-way speeds, used from two in flight on
+    return (M.CostModel(t[:8], t[8:], link[0], link[1], *duplex), B.make_cost_model(t[:8], t[8:], link[0], link[1], *duplex))
 
 
 SMALL = [syn.StageConfig(2, 64, 4, 256, 16, 2, "pre", True, "erf", "bf16"),
