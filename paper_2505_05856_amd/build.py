@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdpstage.so")
-SOURCES = ["stage.cpp", "elementwise.hip", "gemm_simple.hip", "attn_simple.hip", "gemm_mfma.hip", "gemm_dma.hip", "attn_mfma.hip", "probe.hip"]
+SOURCES = ["stage.cpp", "planner.cpp", "ops.cpp", "elementwise.hip", "gemm_simple.hip", "attn_simple.hip", "gemm_mfma.hip", "gemm_dma.hip", "attn_mfma.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -1,0 +1,80 @@
+// What the translation units of libdpstage share: error text, the parsed stage shape, the
+// forward op tables, the static memory walk (validate) and its timed form (walk_cost), and the
+// planner's entry points.  Internal: nothing here is part of the C ABI.
+#pragma once
+#include "../../include/dpstage.h"
+#include "kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+namespace dpi {
+
+// Sets the calling thread's error text (dp_last_error) and returns `code`.
+dp_status fail(dp_status code, const char *fmt, ...);
+
+// ------------------------------------------------------------------ shapes
+struct Cfg {
+  int L, H, nh, dh, F, S, B;
+  long T;
+  bool pre, causal;
+  int gelu, dtype;
+  float eps;
+  size_t esz;
+  float p_attn, p_hidden;          // dropout rates
+  bool drop_attn, drop_hidden;     // rate > 0
+};
+
+dp_status parse_cfg(const dp_stage_config *c, Cfg *o);
+
+// ------------------------------------------------------------------ op tables
+enum Op { OP_LN1, OP_QKV, OP_ATTN, OP_PROJ, OP_LN2, OP_FC1, OP_GELU, OP_FC2, N_OPS };
+// A slot reference relative to a layer: dl = 1 means "X_IN of the next layer".
+struct Ref { int dl, slot; };
+struct OpDef { Op op; int n_in; Ref in[2]; int n_out; Ref out[2]; };
+extern const OpDef kPreOps[N_OPS], kPostOps[N_OPS];
+size_t slot_bytes(const Cfg &c, int slot);
+
+// Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  The epilogue
+// stores single elements per lane, and a second output doubles those stores: measured, the
+// separate kernel with its 16-byte accesses is the faster of the two, so it is the default.
+constexpr bool kFuseGeluDefault = false;
+
+// DPSTAGE_KERNELS=simple switches the matrix-core kernels off (debugging aid).
+bool env_mfma_enabled();
+
+// ------------------------------------------------------------------ the walk, dry
+dp_status check_plan(const Cfg &c, const uint8_t *plan, size_t plan_len, dp_plan_report *rep);
+// The static memory walk: fills `rep`, picks the hold policy that fits inflight * peak into
+// `budget` (0 = none: the tightest policy) and returns it in *hold_out.
+dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
+                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled, long *hold_out = nullptr);
+struct CostOut { int64_t step_ns; uint64_t slot_peak, arena_peak, d2h, h2d; int replayed; };
+// Plays the step under `plan` on the three clocks of the cost model.  exact = false: the
+// planner's model (saved tensors only, no waits for handed-on arena blocks); exact = true:
+// the executor's own arena and hold policy.
+CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bool exact, long hold_ticks);
+
+// Nanoseconds a copy of `bytes` takes at `bytes_per_us`, rounded up.
+inline int64_t copy_ns(uint64_t bytes, uint64_t bytes_per_us) {
+  return (int64_t)(((unsigned __int128)bytes * 1000u + bytes_per_us - 1) / bytes_per_us);
+}
+
+// ------------------------------------------------------------------ planner (planner.cpp)
+dp_status check_cost_model(const dp_cost_model *cm);
+dp_cost_model for_inflight(const dp_cost_model &cm, uint32_t inflight);
+bool memopt(const Cfg &c, const dp_cost_model &cm, uint64_t budget, uint32_t inflight, uint64_t fixed_bytes,
+            std::vector<uint8_t> &plan, dp_memopt_report *rep);
+dp_status memopt_validated(const Cfg &c, const dp_cost_model &cm, uint64_t budget_bytes, uint32_t inflight,
+                           std::vector<uint8_t> &plan, dp_memopt_report *r);
+
+}  // namespace dpi
+
+#define HIP_TRY(expr, code)                                                                     \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) return dpi::fail(code, "%s failed: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)

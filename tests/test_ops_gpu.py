@@ -172,7 +172,7 @@ def test_mfma_issue_probe_reports_a_plausible_rate():
     tn, fn = B.probe_mfma(noise, 20000)
     for t, f in ((tz, fz), (tn, fn)):
         assert 500 < f < 3000
-        assert abs(t * 1e12 - cus * 4096 * f * 1e6) <= 0.1 * t * 1e12      # includes launch and drain
+        assert abs(t * 1e12 - cus * 4096 * f * 1e6) <= 0.25 * t * 1e12     # one CU's clock; launch and drain included
     assert tz >= 0.98 * tn
     with pytest.raises(B.DpError):
         B.probe_mfma(zeros[:4], 10)
