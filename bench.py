@@ -154,9 +154,9 @@ def main():
                          "(dp_partition, cost model measured here) and time every stage of the result")
     ap.add_argument("--chain-layers", type=int, default=24)
     ap.add_argument("--budget-gb", type=float, default=0.0, help="with --partition: device memory per stage (0 = no limit)")
-    ap.add_argument("--mfma-probe", action="store_true",
-                    help="also measure what the matrix cores sustain with nothing else in the way, on zeros and on "
-                         "this workload's own weights and activations (the clock under load depends on the data)")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the measurement of what the matrix cores sustain with nothing else in the way, on zeros "
+                         "and on this workload's own weights and activations (the clock under load depends on the data)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate on the attention probabilities and after the projection and FC2 (default: none)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -297,7 +297,7 @@ def main():
                     "vs_fused_step": round(ms / sms, 4)}
 
     probe = None
-    if args.mfma_probe and cfg.dtype == "bf16":
+    if not args.no_mfma_probe and cfg.dtype == "bf16":
         probe = {}
         for tag, t in (("zeros", torch.zeros(1 << 20, dtype=torch.bfloat16, device="cuda:0")),
                        ("weights", run.w[0]["w_fc1"]), ("activations", run.x),
