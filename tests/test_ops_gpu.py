@@ -125,7 +125,8 @@ def test_gemm(dt, mode, M, N, K):
     assert O.max_rel_err(host(c), ref + res) < TOL[dt]
 
 
-ATTN_SHAPES = [(1, 8, 1, 8), (2, 5, 2, 16), (2, 64, 2, 64), (1, 200, 3, 64), (2, 96, 2, 128), (1, 384, 2, 64)]
+ATTN_SHAPES = [(1, 8, 1, 8), (2, 5, 2, 16), (2, 64, 2, 64), (1, 200, 3, 64), (2, 96, 2, 128), (1, 384, 2, 64),
+               (1, 1024, 3, 64), (1, 2048, 2, 128)]     # the last two: sequence and head width of C3/C4 and of C5
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
@@ -176,3 +177,24 @@ def test_mfma_issue_probe_reports_a_plausible_rate():
     assert tz >= 0.98 * tn
     with pytest.raises(B.DpError):
         B.probe_mfma(zeros[:4], 10)
+
+
+@pytest.mark.parametrize("mode,M,N,K", [(0, 4096, 4096, 4096), (0, 4096, 4096, 11008), (0, 3072, 1600, 6400),
+                                        (1, 4096, 4096, 16384), (1, 1600, 6400, 32768), (1, 4096, 11008, 8192)])
+def test_gemm_long_contractions_of_the_wide_configurations(mode, M, N, K):
+    """The contraction lengths of C4/C5 (hidden 4096, ffn 11008; weight gradients over 16384 and 32768 tokens) at
+    output sizes that take the 256x256 tiles and their five-tile ring, against a float32 reference product (its
+    own rounding, ~K * 6e-8 relative, is far below one bf16 rounding of the output)."""
+    dt = torch.bfloat16
+    a = rnd((M, K), 91, dt, 0.5); b = rnd((K, N), 92, dt, 0.5)
+    ref = a @ b                                  # float32 in, float32 out
+    ta, tb = (dev(a, dt), dev(np.ascontiguousarray(b.T), dt)) if mode == 0 else (dev(np.ascontiguousarray(a.T), dt), dev(b, dt))
+    c = torch.empty(M, N, dtype=dt, device=DEV)
+    B.op_gemm(mode, M, N, K, ta, tb, None, None, c)
+    got = c.float().cpu().numpy()
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= TOL[dt] * scale
+    # every 4096th element exactly as one rounding of the float64 product of that row and column
+    rows = np.arange(0, M, 509)[:6]; cols = np.arange(0, N, 613)[:6]
+    exact = a[rows].astype(np.float64) @ b[:, cols].astype(np.float64)
+    assert np.abs(got[np.ix_(rows, cols)] - exact).max() <= 2.0 ** -8 * np.abs(exact).max() + 1e-6
