@@ -262,3 +262,36 @@ def test_set_weights_with_nothing_in_flight_updates_in_place():
     gy, gdx, gg = run.results()
     compare(cfg, ([gy], [gdx], gg), ([y], [dx], g))
     run.close()
+
+
+def test_random_valid_event_orders_with_a_plan_per_micro_batch():
+    """Any order in which every forward precedes its backward and at most `inflight` micro-batches are held:
+    per-micro-batch results and the accumulated gradients equal the oracle's for that order, and y / dx do not
+    depend on the order at all."""
+    cfg = SMALL[3]
+    n, inflight = 6, 3
+    w, xs, dys = make(cfg, n)
+    rng = np.random.default_rng(17)
+    run = ScheduleRunner(cfg, w, xs, dys)
+    B.stage_set_debug(run.stage, 2)
+    first_bits = None
+    for trial in range(4):
+        order, fed, held, done = [], 0, [], 0
+        while done < n:
+            can_f = fed < n and len(held) < inflight
+            if can_f and (not held or rng.random() < 0.5):
+                order.append(("F", fed)); held.append(fed); fed += 1
+            else:
+                m = held.pop(int(rng.integers(len(held))))      # any held micro-batch, not only the oldest
+                order.append(("B", m)); done += 1
+        plans = [syn.plan_seeded(cfg, 50 * trial + m) for m in range(n)]
+        ref = oracle_schedule(cfg, w, xs, dys, order)
+        assert ref[3] <= inflight
+        run.poison_outputs()
+        run.run(order, inflight, plans)
+        compare(cfg, run.results(), ref)
+        bits = run.raw_results()[:2 * n]                          # y and dx of every micro-batch
+        if first_bits is None:
+            first_bits = bits
+        assert all(torch.equal(a, b) for a, b in zip(first_bits, bits)), trial
+    run.close()

@@ -151,3 +151,32 @@ def test_non_default_stream_and_repeatability():
     s.synchronize()
     assert all(torch.equal(u, v) for u, v in zip(a, run.raw_results()))
     run.close()
+
+
+@pytest.mark.parametrize("style", ["pre", "post"])
+def test_forty_seeded_plans_give_the_same_bits_inside_their_validated_memory(style):
+    """Plans drawn per (layer, slot) from a seeded generator, on a small stage with released blocks poisoned:
+    every one must give the bits of the all-KEEP plan, run inside exactly the arena the validator reported for
+    the same budget, and move exactly the swap traffic it reported."""
+    cfg = syn.StageConfig(4, 128, 2, 256, 96, 2, style, style == "pre", "erf", "bf16")
+    w, x, dy = make(cfg, sigma=0.05)
+    run = StageRunner(cfg, w, x, dy)
+    B.stage_set_debug(run.stage, 2)
+    run.step(syn.plan_keep_all(cfg))
+    keep = run.raw_results()
+    seen = set()
+    for seed in range(40):
+        plan = syn.plan_seeded(cfg, 1000 + seed)
+        seen.add(bytes(plan))
+        _, tight = B.plan_validate(run.bcfg, plan)                      # no budget: the tightest hold policy
+        budget = tight["peak_bytes"]
+        _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)   # what the step will choose under it
+        assert rep["peak_bytes"] <= budget
+        run.poison_outputs()
+        stats = run.step(plan, budget_bytes=budget, want_stats=True)
+        assert all(torch.equal(a, b) for a, b in zip(keep, run.raw_results())), seed
+        assert stats["arena_high_water"] == rep["arena_peak_bytes"], seed
+        assert (stats["d2h_bytes"], stats["h2d_bytes"]) == (rep["swap_out_bytes"], rep["swap_in_bytes"]), seed
+        assert stats["n_replayed_ops"] == rep["n_replayed_ops"], seed
+    assert len(seen) == 40
+    run.close()
