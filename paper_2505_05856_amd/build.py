@@ -21,11 +21,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
 # register before the data has arrived.
 NO_SCRATCH = {"gemm_mfma.hip", "gemm_dma.hip"}
 
+# Per-file compiler options.  attn_mfma.hip: with head dimension 128 the backward kernels keep
+# 128 accumulator registers per wave beside 64 operand registers; by default the compiler puts
+# the matrix instructions' results into accumulation registers and then moves them to and fro
+# (768 v_accvgpr moves for 128 matrix instructions in the dK/dV loop); letting it choose ordinary
+# registers for them removes nearly all of those moves.
+EXTRA_FLAGS = {"attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SCRATCH else []
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *extra, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     lines = r.stderr.splitlines()
     if src in NO_SCRATCH and r.returncode == 0:
