@@ -13,6 +13,16 @@
  *   dp_stage_step    (micro-batch, plan, memory budget) -> Y, dX, dTheta
  *   dp_plan_validate (config, plan, budget)             -> peak-memory report
  *
+ * and, around that core:
+ *   dp_stage_forward / dp_stage_backward   the step cut where a one-forward-one-backward
+ *                                          schedule cuts it (micro-batch slots, gradient
+ *                                          accumulation); dp_stage_set_weights (parameter
+ *                                          versions); dp_stage_set_rng (dropout masks)
+ *   dp_stage_measure_cost_model, dp_plan_cost, dp_plan_generate
+ *                                          Section 4.3's memory optimisation from measured costs
+ *   dp_partition                           Section 4.2's partition search over a chain of layers
+ *   dp_op_*, dp_stage_op_times, dp_probe_mfma   operators one at a time, and diagnostics
+ *
  * Plain C ABI: POD structs, raw pointers, sizes.  "device pointer" means memory
  * of the current HIP device; "host pointer" ordinary process memory.  No call
  * throws; every call returns a dp_status and dp_last_error() gives the text.
@@ -99,7 +109,8 @@ typedef struct {
 } dp_layer_weights;
 
 /* Device pointers receiving the weight gradients: same shapes, layouts and
- * dtype as the weights; overwritten, not accumulated.  Caller-owned. */
+ * dtype as the weights.  dp_stage_step overwrites them; dp_stage_backward
+ * overwrites or, with DP_GRAD_ACCUMULATE, adds to them.  Caller-owned. */
 typedef struct {
   void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
   void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
