@@ -9,6 +9,8 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace dp {
 
 // ------------------------------------------------------------------ LayerNorm
@@ -210,6 +212,119 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
       if (col < cols) {
         const float t = ((red[0][which][k] + red[1][which][k]) + red[2][which][k]) + red[3][which][k];
         prow[(size_t)which * cols + col] = t;
+      }
+    }
+  }
+}
+
+// LayerNorm backward for wide rows (more than 2048 columns): a block per row, the columns
+// dealt out over its 256 threads (thread t owns the 8-column groups t, t + 256, ...), rows of
+// the block's range one after the other.  A thread's column accumulators are then complete sums
+// over the block's rows (no reduction across waves at the end), gamma stays in registers, and a
+// thread holds 16..32 elements of a row instead of 64..128: several blocks fit a CU where the
+// wave-per-row form fits one or two waves a SIMD.  The two row sums cross the waves through LDS
+// (one barrier a row; two alternating slots); the next row's loads are issued before that.
+template <typename T, int NP, bool SUMDX>
+__global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
+                                                          const float *__restrict__ stats,
+                                                          const T *__restrict__ gamma, const T *__restrict__ dres,
+                                                          T *dx, float *__restrict__ part, int rows, int cols,
+                                                          int rpb) {
+  constexpr int NV = SUMDX ? 3 : 2;
+  __shared__ float red[2][2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row0 = blockIdx.x * rpb, row_end = min(rows, row0 + rpb);
+  float gm[NP][8], dg[NP][8], db[NP][8], ds[SUMDX ? NP : 1][8];
+#pragma unroll
+  for (int c = 0; c < NP; ++c) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < cols) load8(gamma + col, gm[c]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dg[c][i] = 0.f; db[c][i] = 0.f; if (SUMDX) ds[c][i] = 0.f; }
+  }
+  const float inv_n = 1.0f / (float)cols;
+  // PF rows are in flight per block (a block is one wave per SIMD and only a few blocks share a
+  // CU, so the loads of several rows ahead are what keeps the memory system busy)
+  constexpr int PF = 3;   // (four was slower: the registers then leave one block a CU)
+  float xn[PF][NP][8], dn[PF][NP][8];
+  auto fetch = [&](int row, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    if (row >= row_end) return;
+    const size_t base = (size_t)row * cols;
+#pragma unroll
+    for (int c = 0; c < NP; ++c) {
+      const int col = (c * 256 + tid) * 8;
+      if (col < cols) { load8(x + base + col, xn[BUF][c]); load8(dy + base + col, dn[BUF][c]); }
+    }
+  };
+  auto process = [&](int row, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+    const size_t base = (size_t)row * cols;
+    float xh[NP][8], g[NP][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NP; ++c) {
+      const int col = (c * 256 + tid) * 8;
+      if (col < cols) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          xh[c][i] = (xn[BUF][c][i] - mean) * rstd;
+          dg[c][i] += dn[BUF][c][i] * xh[c][i];
+          db[c][i] += dn[BUF][c][i];
+          g[c][i] = dn[BUF][c][i] * gm[c][i];
+          s1 += g[c][i];
+          s2 += g[c][i] * xh[c][i];
+        }
+      }
+    }
+    fetch(row + PF, buf_tag);   // this buffer's next row
+    s1 = wave_sum(s1); s2 = wave_sum(s2);
+    const int slot = (row - row0) & 1;
+    if (lane == 0) { red[slot][0][wave] = s1; red[slot][1][wave] = s2; }
+    __syncthreads();
+    const float m1 = (((red[slot][0][0] + red[slot][0][1]) + red[slot][0][2]) + red[slot][0][3]) * inv_n;
+    const float m2 = (((red[slot][1][0] + red[slot][1][1]) + red[slot][1][2]) + red[slot][1][3]) * inv_n;
+#pragma unroll
+    for (int c = 0; c < NP; ++c) {
+      const int col = (c * 256 + tid) * 8;
+      if (col < cols) {
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = rstd * (g[c][i] - m1 - xh[c][i] * m2);
+        if (dres != nullptr) {
+          float r[8];
+          load8(dres + base + col, r);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] += r[i];
+        }
+        store8(dx + base + col, o);
+        if (SUMDX) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) ds[c][i] += (float)(T)o[i];   // the value as stored
+        }
+      }
+    }
+  };
+  fetch(row0, std::integral_constant<int, 0>{});
+  fetch(row0 + 1, std::integral_constant<int, 1>{});
+  fetch(row0 + 2, std::integral_constant<int, 2>{});
+  // (the trip count of the loop is the same for every thread of the block: the barriers inside match)
+  for (int row = row0; row < row_end; row += PF) {
+    process(row, std::integral_constant<int, 0>{});
+    if (row + 1 < row_end) process(row + 1, std::integral_constant<int, 1>{});
+    if (row + 2 < row_end) process(row + 2, std::integral_constant<int, 2>{});
+  }
+  float *prow = part + (size_t)blockIdx.x * NV * cols;
+#pragma unroll
+  for (int c = 0; c < NP; ++c) {
+    const int col = (c * 256 + tid) * 8;
+    if (col < cols) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        prow[col + i] = dg[c][i];
+        prow[(size_t)cols + col + i] = db[c][i];
+        if (SUMDX) prow[2 * (size_t)cols + col + i] = ds[c][i];
       }
     }
   }
@@ -474,13 +589,17 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
 #define DP_LN_BWD(NC)                                                                                       \
   hipLaunchKernelGGL((ln_bwd_kernel<T, NC, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, \
                      stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
+#define DP_LN_BWD_WIDE(NP)                                                                                  \
+  hipLaunchKernelGGL((ln_bwd_wide_kernel<T, NP, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy,          \
+                     (const T *)x, stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
   switch (ln_chunks(cols)) {
     case 1: DP_LN_BWD(1); break;
     case 2: DP_LN_BWD(2); break;
     case 4: DP_LN_BWD(4); break;
-    case 8: DP_LN_BWD(8); break;
-    default: DP_LN_BWD(16); break;
+    case 8: DP_LN_BWD_WIDE(2); break;     // 2049..4096 columns
+    default: DP_LN_BWD_WIDE(4); break;    // up to 8192
   }
+#undef DP_LN_BWD_WIDE
 #undef DP_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -34,7 +34,8 @@ def ws_for(rows, cols):
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("rows,cols", [(1, 8), (7, 16), (130, 128), (37, 1600), (9, 4096), (5, 8192)])
+@pytest.mark.parametrize("rows,cols", [(1, 8), (7, 16), (130, 128), (37, 1600), (9, 4096), (5, 8192), (2, 2056),
+                                       (1301, 4096), (270, 5000), (515, 8192)])
 def test_layernorm(dt, rows, cols):
     x = rnd((rows, cols), 11, dt, 2.0) + 0.5
     x = syn.round_to_bf16(x) if dt == torch.bfloat16 else x
