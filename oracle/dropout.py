@@ -18,7 +18,8 @@ generator.  The one used here, which the HIP kernels implement independently:
   keep(i) = bits(i) >= floor(p * 2^32);   kept values are scaled by 1 / (1 - p)
 
 site 0: attention probabilities, unit = batch * heads + head, i = query * S + key;
-site 1 / 2: output of the attention projection / of FC2, unit = 0, i = token * H + column.
+site 1 / 2: output of the attention projection / of FC2, unit = 0, i = token * H + column;
+site 3: cross-attention probabilities, unit = batch * heads + head, i = query * Sk + key.
 seed is the caller's, mb counts micro-batches (the caller sets or the library increments it).
 
 Pins (tests/test_oracle_dropout.py): the mixer is injective on a large range and has the
@@ -32,7 +33,7 @@ import numpy as np
 
 M1, M2 = 0x7FEB352D, 0x846CA68B
 U32 = np.uint32
-SITE_ATTN, SITE_PROJ, SITE_FC2 = 0, 1, 2
+SITE_ATTN, SITE_PROJ, SITE_FC2, SITE_CROSS = 0, 1, 2, 3
 
 
 def mix(x):
@@ -98,4 +99,17 @@ def keep_attention(seed, mb, layer, b, nh, S, p):
         for h in range(nh):
             k0, k1 = unit_keys(base, b * nh + h)
             out[h] = (bits(idx, k0, k1) >= U32(threshold(p))).reshape(S, S)
+    return out
+
+
+def keep_cross_attention(seed, mb, layer, b, nh, Sq, Sk, p):
+    """[nh, Sq, Sk] boolean keep mask of sample b's cross-attention probabilities."""
+    assert Sq * Sk < 2 ** 32
+    base = site_base(seed, mb, layer, SITE_CROSS)
+    out = np.empty((nh, Sq, Sk), dtype=bool)
+    idx = np.arange(Sq * Sk, dtype=np.uint32)
+    with np.errstate(over="ignore"):
+        for h in range(nh):
+            k0, k1 = unit_keys(base, b * nh + h)
+            out[h] = (bits(idx, k0, k1) >= U32(threshold(p))).reshape(Sq, Sk)
     return out
