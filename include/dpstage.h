@@ -462,6 +462,25 @@ dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32
                                       const void *d_o, void *dqkv, void *ws, const dp_dropout *drop,
                                       void *hip_stream);
 
+/* Cross-attention, the decoder-side block of an encoder-decoder model (Section 5.1 lists T5
+ * among the workloads; the paper does not define the layer mathematics): queries q [B*Sq, H]
+ * attend, without a mask, to the keys and values of kv [B*Sk, 2H] = [K | V], per sample and per
+ * head (head h = columns h*dh .. of each H-wide block):
+ *   o [B*Sq, H] = softmax(Q K^T / sqrt(dh)) V,   lse [B, nh, Sq] (fp32) = log of the row sums.
+ * o or lse may be NULL.  The backward writes dq [B*Sq, H] and dkv [B*Sk, 2H] from q, kv, o, lse
+ * and d_o [B*Sq, H]; ws: device workspace of dp_op_workspace_bytes(B*Sq, nh) bytes.  drop: NULL,
+ * or dropout of the probabilities as in dp_op_attention_dropout_* with positions
+ * query*Sk + key at a site of its own (needs Sq*Sk < 2^32).  Empty inputs: no queries writes
+ * nothing forward and dkv = 0 backward; queries without keys are DP_E_INVAL.  The same kernels
+ * as self-attention, which is the case q, K, V = the three blocks of one tensor and Sq = Sk. */
+dp_status dp_op_cross_attention_fwd(int32_t dtype, int32_t B, int32_t Sq, int32_t Sk, int32_t nh, int32_t dh,
+                                    const void *q, const void *kv, void *o, float *lse, const dp_dropout *drop,
+                                    void *hip_stream);
+dp_status dp_op_cross_attention_bwd(int32_t dtype, int32_t B, int32_t Sq, int32_t Sk, int32_t nh, int32_t dh,
+                                    const void *q, const void *kv, const void *o, const float *lse,
+                                    const void *d_o, void *dq, void *dkv, void *ws, const dp_dropout *drop,
+                                    void *hip_stream);
+
 /* Diagnostic for reading the roofline: the rate at which the matrix cores issue
  * v_mfma_f32_32x32x16_bf16 when nothing else limits them (operands in registers, 16
  * independent accumulators a wave, one workgroup a CU, `iters` rounds), with the operand bits

@@ -137,6 +137,8 @@ def lib() -> C.CDLL:
     L.dp_op_dropout.argtypes = [i32, sz, vp, vp, vp, vp, i32, vp]
     L.dp_op_attention_dropout_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     L.dp_op_attention_dropout_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.dp_op_cross_attention_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    L.dp_op_cross_attention_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dp_partition.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), i32, u64, u64, u64, C.POINTER(C.c_int64),
                                C.POINTER(u64), C.c_uint32, C.POINTER(i32), vp, sz, C.POINTER(PartitionStage),
                                C.POINTER(PartitionReport)]
@@ -148,7 +150,8 @@ def lib() -> C.CDLL:
     for name in ("dp_probe_mfma", "dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
-                 "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd"):
+                 "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd",
+                 "dp_op_cross_attention_fwd", "dp_op_cross_attention_bwd"):
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -436,6 +439,19 @@ def op_attention_dropout_fwd(qkv, B, S, nh, dh, causal, o, lse, drop: Dropout, s
 def op_attention_dropout_bwd(qkv, o, lse, d_o, B, S, nh, dh, causal, dqkv, ws, drop: Dropout, stream=None):
     _check(lib().dp_op_attention_dropout_bwd(_dt(qkv), B, S, nh, dh, int(causal), _ptr(qkv), _ptr(o), _ptr(lse),
                                              _ptr(d_o), _ptr(dqkv), _ptr(ws), C.byref(drop), _stream_ptr(stream)))
+
+
+def op_cross_attention_fwd(q, kv, B, Sq, Sk, nh, dh, o, lse, drop: Dropout = None, stream=None):
+    _check(lib().dp_op_cross_attention_fwd(_dt(q), B, Sq, Sk, nh, dh, _ptr(q), _ptr(kv),
+                                           _ptr(o) if o is not None else None,
+                                           _ptr(lse) if lse is not None else None,
+                                           C.byref(drop) if drop is not None else None, _stream_ptr(stream)))
+
+
+def op_cross_attention_bwd(q, kv, o, lse, d_o, B, Sq, Sk, nh, dh, dq, dkv, ws, drop: Dropout = None, stream=None):
+    _check(lib().dp_op_cross_attention_bwd(_dt(q), B, Sq, Sk, nh, dh, _ptr(q), _ptr(kv), _ptr(o), _ptr(lse), _ptr(d_o),
+                                           _ptr(dq), _ptr(dkv), _ptr(ws),
+                                           C.byref(drop) if drop is not None else None, _stream_ptr(stream)))
 
 
 def probe_mfma(data, iters: int = 20000, stream=None):

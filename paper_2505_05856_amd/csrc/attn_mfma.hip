@@ -101,8 +101,8 @@ __device__ __forceinline__ void tile_store(bf16 *lds, int stride, const uint4 (&
 // DROP: the probabilities are masked after the softmax (the row sums and the log-sum-exp are
 // those of the plain softmax); the scale 1/(1-p) goes into the final normalisation.
 template <int DH, bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ o,
-                                                               float *__restrict__ lse, int S, int nh, float scale,
+__global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_mfma_kernel(AttnView av, bf16 *__restrict__ o,
+                                                               float *__restrict__ lse, int nh, float scale,
                                                                DropArgs da) {
   constexpr int KS = DH + 8, VS = DH + 16, ND = DH / 32, NK = DH / 16;
   // LDS stages are picked by integer offsets into one array: selecting them through
@@ -110,27 +110,29 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
 
-  const int nqt = (S + BROWS - 1) / BROWS;
+  const int Sq = av.Sq, S = av.Sk;   // S: the key count, which bounds every key-side loop below
+  const int nqt = (Sq + BROWS - 1) / BROWS;
   const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int qt = nqt - 1 - wid % nqt;   // heavy (late) causal tiles first
   const int h = (wid / nqt) % nh, b = wid / (nqt * nh);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
   const int H = nh * DH;
-  const long ld = 3L * H;
-  const bf16 *qb = qkv + (long)b * S * ld + (long)h * DH;
-  const bf16 *kb = qb + H, *vb = qb + 2 * H;
+  const long ldq = av.ldq, ld = av.ldkv;
+  const bf16 *qb = (const bf16 *)av.q + (long)b * Sq * ldq + (long)h * DH;
+  const bf16 *kb = (const bf16 *)av.k + (long)b * S * ld + (long)h * DH;
+  const bf16 *vb = (const bf16 *)av.v + (long)b * S * ld + (long)h * DH;
   const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
   const float c = scale * kLog2e;
   const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
-  const uint32_t qidx = (uint32_t)qi * (uint32_t)S;   // index of (query qi, key 0) in the head's S x S matrix
+  const uint32_t qidx = (uint32_t)qi * (uint32_t)S;   // index of (query qi, key 0) in the head's Sq x Sk matrix
 
   bf16x8 qf[NK];
 #pragma unroll
   for (int kd = 0; kd < NK; ++kd)
-    qf[kd] = qi < S ? as_frag(ld16(qb + (long)qi * ld + kd * 16 + 8 * hh)) : as_frag(make_uint4(0, 0, 0, 0));
+    qf[kd] = qi < Sq ? as_frag(ld16(qb + (long)qi * ldq + kd * 16 + 8 * hh)) : as_frag(make_uint4(0, 0, 0, 0));
 
   int nkv = (S + BKV - 1) / BKV;
-  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, S) - 1) / BKV + 1);
+  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
 
   f32x16 acc[ND];
 #pragma unroll
@@ -228,11 +230,11 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
   }
 
   l += __shfl_xor(l, 32, 64);
-  if (qi >= S) return;
-  if (lse != nullptr && hh == 0) lse[((long)b * nh + h) * S + qi] = (m + __log2f(l)) * kLn2;
+  if (qi >= Sq) return;
+  if (lse != nullptr && hh == 0) lse[((long)b * nh + h) * Sq + qi] = (m + __log2f(l)) * kLn2;
   if (o == nullptr) return;
   const float inv = (DROP ? da.scale : 1.0f) / l;
-  bf16 *orow = o + ((long)b * S + qi) * H + (long)h * DH;
+  bf16 *orow = o + ((long)b * Sq + qi) * H + (long)h * DH;
 #pragma unroll
   for (int d = 0; d < ND; ++d)
 #pragma unroll
@@ -251,7 +253,7 @@ hipError_t set_smem(K kern, size_t smem) {
 }
 
 template <int DH>
-hipError_t fwd_launch(int B, int S, int nh, int causal, const void *qkv, void *o, float *lse, const DropArgs *drop,
+hipError_t fwd_launch(int B, int nh, int causal, const AttnView &av, void *o, float *lse, const DropArgs *drop,
                       hipStream_t s) {
   constexpr size_t smem = 2 * (size_t)BKV * ((DH + 8) + (DH + 16)) * sizeof(bf16);
   static bool attr_set = false;
@@ -263,11 +265,11 @@ hipError_t fwd_launch(int B, int S, int nh, int causal, const void *qkv, void *o
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid(((S + BROWS - 1) / BROWS) * nh * B), block(256);
+  const dim3 grid(((av.Sq + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
   const bool dropping = drop != nullptr && drop->thr != 0;
   const DropArgs da = dropping ? *drop : DropArgs{0u, 0u, 1.f};
-#define DP_FWD(KERN) hipLaunchKernelGGL(KERN, grid, block, smem, s, (const bf16 *)qkv, (bf16 *)o, lse, S, nh, scale, da)
+#define DP_FWD(KERN) hipLaunchKernelGGL(KERN, grid, block, smem, s, av, (bf16 *)o, lse, nh, scale, da)
   if (dropping) { if (causal) DP_FWD((attn_fwd_mfma_kernel<DH, true, true>)); else DP_FWD((attn_fwd_mfma_kernel<DH, false, true>)); }
   else { if (causal) DP_FWD((attn_fwd_mfma_kernel<DH, true, false>)); else DP_FWD((attn_fwd_mfma_kernel<DH, false, false>)); }
 #undef DP_FWD
@@ -304,27 +306,28 @@ __global__ __launch_bounds__(256) void attn_rowdot_kernel(const bf16 *__restrict
 // registers two blocks a CU leave each wave, and spills on this path cost more than the
 // lost occupancy)
 template <int DH, bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
+__global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(AttnView av,
                                                               const float *__restrict__ lse,
                                                               const bf16 *__restrict__ d_o,
                                                               const float *__restrict__ drow,
-                                                              bf16 *__restrict__ dqkv, int S, int nh, float scale,
-                                                              DropArgs da) {
+                                                              int nh, float scale, DropArgs da) {
   constexpr int QS = DH + 16, ND = DH / 32, NK = DH / 16;
   // stage s: Q tile, dO tile (bf16), then 64 log-sum-exp and 64 row-dot floats
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int OOFF = BKV * QS, FOFF = 2 * BKV * QS, STAGE = 2 * BKV * QS + 4 * BKV;   // in bf16 elements
 
-  const int nkt = (S + BROWS - 1) / BROWS;
+  const int Sq = av.Sq, Sk = av.Sk;
+  const int nkt = (Sk + BROWS - 1) / BROWS;
   const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int kt = wid % nkt, h = (wid / nkt) % nh, b = wid / (nkt * nh);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
   const int H = nh * DH;
-  const long ld = 3L * H;
-  const bf16 *qb = qkv + (long)b * S * ld + (long)h * DH;
-  const bf16 *kb = qb + H, *vb = qb + 2 * H;
-  const bf16 *dob = d_o + (long)b * S * H + (long)h * DH;
-  const float *lrow = lse + ((long)b * nh + h) * S, *drw = drow + ((long)b * nh + h) * S;
+  const long ldq = av.ldq, ld = av.ldkv;
+  const bf16 *qb = (const bf16 *)av.q + (long)b * Sq * ldq + (long)h * DH;
+  const bf16 *kb = (const bf16 *)av.k + (long)b * Sk * ld + (long)h * DH;
+  const bf16 *vb = (const bf16 *)av.v + (long)b * Sk * ld + (long)h * DH;
+  const bf16 *dob = d_o + (long)b * Sq * H + (long)h * DH;
+  const float *lrow = lse + ((long)b * nh + h) * Sq, *drw = drow + ((long)b * nh + h) * Sq;
   const int j0 = kt * BROWS, jw0 = j0 + wave * 32, kj = jw0 + (lane & 31);
   const float c = scale * kLog2e;
   // DROP: the forward multiplied V by P' = mask * P / (1-p): dV takes P', and dP is masked and
@@ -335,8 +338,8 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
 #pragma unroll
   for (int kd = 0; kd < NK; ++kd) {
     const uint4 z = make_uint4(0, 0, 0, 0);
-    kf[kd] = as_frag(kj < S ? ld16(kb + (long)kj * ld + kd * 16 + 8 * hh) : z);
-    vf[kd] = as_frag(kj < S ? ld16(vb + (long)kj * ld + kd * 16 + 8 * hh) : z);
+    kf[kd] = as_frag(kj < Sk ? ld16(kb + (long)kj * ld + kd * 16 + 8 * hh) : z);
+    vf[kd] = as_frag(kj < Sk ? ld16(vb + (long)kj * ld + kd * 16 + 8 * hh) : z);
   }
   f32x16 dk[ND], dv[ND];
 #pragma unroll
@@ -344,17 +347,17 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dk[d][e] = 0.f; dv[d][e] = 0.f; }
 
-  const int nq = (S + BKV - 1) / BKV;
+  const int nq = (Sq + BKV - 1) / BKV;
   const int t0 = CAUSAL ? j0 / BKV : 0;   // query tiles before the block's first key see none of its keys
 
   uint4 sq[DH / 32], so[DH / 32];
   float sl = 0.f;
   auto fetch = [&](int t) {
     const int i0 = t * BKV;
-    tile_load<DH>(sq, qb, ld, i0, S, tid);
-    tile_load<DH>(so, dob, H, i0, S, tid);
-    if (tid < 64) sl = (i0 + tid < S) ? lrow[i0 + tid] * kLog2e : INFINITY;   // +inf: P = 0 for padding rows
-    else if (tid < 128) sl = (i0 + tid - 64 < S) ? drw[i0 + tid - 64] : 0.f;
+    tile_load<DH>(sq, qb, ldq, i0, Sq, tid);
+    tile_load<DH>(so, dob, H, i0, Sq, tid);
+    if (tid < 64) sl = (i0 + tid < Sq) ? lrow[i0 + tid] * kLog2e : INFINITY;   // +inf: P = 0 for padding rows
+    else if (tid < 128) sl = (i0 + tid - 64 < Sq) ? drw[i0 + tid - 64] : 0.f;
   };
   auto stash = [&](int buf) {   // buf = element offset of the stage
     tile_store<DH>(smem + buf, QS, sq, tid);
@@ -397,7 +400,7 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
             float p = fast_exp2(s[e] * c - lv[t4]);
             if (MASK && kj > i) p = 0.f;   // (rows past the end carry lse = +inf: p = 0 by itself)
             if (DROP) {
-              const bool keep = drop_bits((uint32_t)i * (uint32_t)S + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
+              const bool keep = drop_bits((uint32_t)i * (uint32_t)Sk + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
               s[e] = keep ? p * da.scale : 0.f;
               dp[e] = p * ((keep ? dp[e] * da.scale : 0.f) - dvv[t4]);
             } else {
@@ -425,9 +428,9 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
     __syncthreads();
   }
 
-  if (kj >= S) return;
-  bf16 *krow = dqkv + ((long)b * S + kj) * ld + H + (long)h * DH;
-  bf16 *vrow = krow + H;
+  if (kj >= Sk) return;
+  bf16 *krow = (bf16 *)av.dk + ((long)b * Sk + kj) * ld + (long)h * DH;
+  bf16 *vrow = (bf16 *)av.dv + ((long)b * Sk + kj) * ld + (long)h * DH;
 #pragma unroll
   for (int d = 0; d < ND; ++d)
 #pragma unroll
@@ -442,26 +445,27 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(co
 
 // dQ: the block owns 128 queries (32 per wave) and streams 64-key tiles of K and V.
 template <int DH, bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
                                                              const float *__restrict__ lse,
                                                              const bf16 *__restrict__ d_o,
                                                              const float *__restrict__ drow,
-                                                             bf16 *__restrict__ dqkv, int S, int nh, float scale,
-                                                             DropArgs da) {
+                                                             int nh, float scale, DropArgs da) {
   constexpr int KS = DH + 16, VS = DH + 8, ND = DH / 32, NK = DH / 16;
   extern __shared__ __attribute__((aligned(16))) bf16 smem[];
   constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
 
-  const int nqt = (S + BROWS - 1) / BROWS;
+  const int Sq = av.Sq, S = av.Sk;   // S: the key count
+  const int nqt = (Sq + BROWS - 1) / BROWS;
   const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int qt = nqt - 1 - wid % nqt;
   const int h = (wid / nqt) % nh, b = wid / (nqt * nh);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
   const int H = nh * DH;
-  const long ld = 3L * H;
-  const bf16 *qb = qkv + (long)b * S * ld + (long)h * DH;
-  const bf16 *kb = qb + H, *vb = qb + 2 * H;
-  const bf16 *dob = d_o + (long)b * S * H + (long)h * DH;
+  const long ldq = av.ldq, ld = av.ldkv;
+  const bf16 *qb = (const bf16 *)av.q + (long)b * Sq * ldq + (long)h * DH;
+  const bf16 *kb = (const bf16 *)av.k + (long)b * S * ld + (long)h * DH;
+  const bf16 *vb = (const bf16 *)av.v + (long)b * S * ld + (long)h * DH;
+  const bf16 *dob = d_o + (long)b * Sq * H + (long)h * DH;
   const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
   const float c = scale * kLog2e;
 
@@ -469,13 +473,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
 #pragma unroll
   for (int kd = 0; kd < NK; ++kd) {
     const uint4 z = make_uint4(0, 0, 0, 0);
-    qf[kd] = as_frag(qi < S ? ld16(qb + (long)qi * ld + kd * 16 + 8 * hh) : z);
-    gf[kd] = as_frag(qi < S ? ld16(dob + (long)qi * H + kd * 16 + 8 * hh) : z);
+    qf[kd] = as_frag(qi < Sq ? ld16(qb + (long)qi * ldq + kd * 16 + 8 * hh) : z);
+    gf[kd] = as_frag(qi < Sq ? ld16(dob + (long)qi * H + kd * 16 + 8 * hh) : z);
   }
   const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
   const uint32_t qidx = (uint32_t)qi * (uint32_t)S;
-  const float lq = qi < S ? lse[((long)b * nh + h) * S + qi] * kLog2e : INFINITY;
-  const float dq_i = qi < S ? drow[((long)b * nh + h) * S + qi] : 0.f;
+  const float lq = qi < Sq ? lse[((long)b * nh + h) * Sq + qi] * kLog2e : INFINITY;
+  const float dq_i = qi < Sq ? drow[((long)b * nh + h) * Sq + qi] : 0.f;
 
   f32x16 dq[ND];
 #pragma unroll
@@ -484,7 +488,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
     for (int e = 0; e < 16; ++e) dq[d][e] = 0.f;
 
   int nkv = (S + BKV - 1) / BKV;
-  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, S) - 1) / BKV + 1);
+  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
 
   uint4 sk[DH / 32], sv[DH / 32];
   tile_load<DH>(sk, kb, ld, 0, S, tid);
@@ -550,8 +554,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
     __syncthreads();
   }
 
-  if (qi >= S) return;
-  bf16 *qrow = dqkv + ((long)b * S + qi) * ld + (long)h * DH;
+  if (qi >= Sq) return;
+  bf16 *qrow = (bf16 *)av.dq + ((long)b * Sq + qi) * ldq + (long)h * DH;
 #pragma unroll
   for (int d = 0; d < ND; ++d)
 #pragma unroll
@@ -564,8 +568,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
 }
 
 template <int DH>
-hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const void *o, const float *lse,
-                      const void *d_o, void *dqkv, float *ws, const DropArgs *drop, hipStream_t s) {
+hipError_t bwd_launch(int B, int nh, int causal, const AttnView &av, const void *o, const float *lse,
+                      const void *d_o, float *ws, const DropArgs *drop, hipStream_t s) {
   constexpr size_t smem_kv = 4 * (size_t)BKV * (DH + 16) * sizeof(bf16) + 4 * BKV * sizeof(float);
   constexpr size_t smem_q = 2 * (size_t)BKV * ((DH + 16) + (DH + 8)) * sizeof(bf16);
   static bool attr_set = false;
@@ -581,26 +585,28 @@ hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const v
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const long T = (long)B * S;
+  const long T = (long)B * av.Sq;
   const long chunks = T * nh * DH / 8;
-  hipLaunchKernelGGL((attn_rowdot_kernel<DH>), dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
-                     (const bf16 *)o, (const bf16 *)d_o, ws, T, S, nh);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const dim3 grid(((S + BROWS - 1) / BROWS) * nh * B), block(256);
+  hipError_t e = hipSuccess;
+  if (chunks > 0) {
+    hipLaunchKernelGGL((attn_rowdot_kernel<DH>), dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
+                       (const bf16 *)o, (const bf16 *)d_o, ws, T, av.Sq, nh);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const dim3 grid_q(((av.Sq + BROWS - 1) / BROWS) * nh * B), grid_k(((av.Sk + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
   const bool dropping = drop != nullptr && drop->thr != 0;
   const DropArgs da = dropping ? *drop : DropArgs{0u, 0u, 1.f};
-#define DP_BWD(KERN, SMEM)                                                                              \
-  hipLaunchKernelGGL(KERN, grid, block, SMEM, s, (const bf16 *)qkv, lse, (const bf16 *)d_o, (const float *)ws, \
-                     (bf16 *)dqkv, S, nh, scale, da)
-#define DP_BWD4(NAME, SMEM)                                                                             \
-  if (dropping) { if (causal) DP_BWD((NAME<DH, true, true>), SMEM); else DP_BWD((NAME<DH, false, true>), SMEM); } \
-  else { if (causal) DP_BWD((NAME<DH, true, false>), SMEM); else DP_BWD((NAME<DH, false, false>), SMEM); }
-  DP_BWD4(attn_bwd_dkv_kernel, smem_kv)
+#define DP_BWD(KERN, GRID, SMEM)                                                                        \
+  hipLaunchKernelGGL(KERN, GRID, block, SMEM, s, av, lse, (const bf16 *)d_o, (const float *)ws, nh, scale, da)
+#define DP_BWD4(NAME, GRID, SMEM)                                                                       \
+  if (dropping) { if (causal) DP_BWD((NAME<DH, true, true>), GRID, SMEM); else DP_BWD((NAME<DH, false, true>), GRID, SMEM); } \
+  else { if (causal) DP_BWD((NAME<DH, true, false>), GRID, SMEM); else DP_BWD((NAME<DH, false, false>), GRID, SMEM); }
+  if (av.Sk > 0) { DP_BWD4(attn_bwd_dkv_kernel, grid_k, smem_kv) }   // (no queries: dK = dV = 0 is still written)
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  DP_BWD4(attn_bwd_dq_kernel, smem_q)
+  if (av.Sq > 0 && av.Sk > 0) { DP_BWD4(attn_bwd_dq_kernel, grid_q, smem_q) }
 #undef DP_BWD4
 #undef DP_BWD
   return hipGetLastError();
@@ -610,19 +616,33 @@ hipError_t bwd_launch(int B, int S, int nh, int causal, const void *qkv, const v
 
 bool attn_mfma_supported(int S, int dh) { return S >= 1 && (dh == 64 || dh == 128); }
 
+hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, void *o, float *lse,
+                                     hipStream_t s, const DropArgs *drop) {
+  if (causal && v.Sq != v.Sk) return hipErrorInvalidValue;
+  if ((long)B * v.Sq * nh == 0) return hipSuccess;   // (no keys: the caller's case, there is no softmax to take)
+  return dh == 64 ? fwd_launch<64>(B, nh, causal, v, o, lse, drop, s) : fwd_launch<128>(B, nh, causal, v, o, lse, drop, s);
+}
+
+hipError_t launch_attn_bwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, const void *o,
+                                     const float *lse, const void *d_o, float *ws, hipStream_t s,
+                                     const DropArgs *drop) {
+  if (causal && v.Sq != v.Sk) return hipErrorInvalidValue;
+  if ((long)B * nh == 0 || (v.Sq == 0 && v.Sk == 0)) return hipSuccess;
+  return dh == 64 ? bwd_launch<64>(B, nh, causal, v, o, lse, d_o, ws, drop, s)
+                  : bwd_launch<128>(B, nh, causal, v, o, lse, d_o, ws, drop, s);
+}
+
 hipError_t launch_attn_fwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, void *o, float *lse,
                                 hipStream_t s, const DropArgs *drop) {
-  if ((long)B * S * nh == 0) return hipSuccess;
-  return dh == 64 ? fwd_launch<64>(B, S, nh, causal, qkv, o, lse, drop, s)
-                  : fwd_launch<128>(B, S, nh, causal, qkv, o, lse, drop, s);
+  return launch_attn_fwd_mfma_view(B, nh, dh, causal, attn_self_view(qkv, nullptr, S, nh * dh, sizeof(bf16)), o, lse, s,
+                                   drop);
 }
 
 hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o,
                                 const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s,
                                 const DropArgs *drop) {
-  if ((long)B * S * nh == 0) return hipSuccess;
-  return dh == 64 ? bwd_launch<64>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, drop, s)
-                  : bwd_launch<128>(B, S, nh, causal, qkv, o, lse, d_o, dqkv, ws, drop, s);
+  return launch_attn_bwd_mfma_view(B, nh, dh, causal, attn_self_view(qkv, dqkv, S, nh * dh, sizeof(bf16)), o, lse, d_o,
+                                   ws, s, drop);
 }
 
 }  // namespace dp

@@ -15,7 +15,7 @@ struct DropArgs {
   uint32_t thr;     // floor(p * 2^32)
   float scale;      // 1 / (1 - p)
 };
-enum DropSite { kSiteAttn = 0, kSiteProj = 1, kSiteFc2 = 2 };
+enum DropSite { kSiteAttn = 0, kSiteProj = 1, kSiteFc2 = 2, kSiteCross = 3 };
 inline uint32_t drop_mix_host(uint32_t x) {
   x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
   return x;
@@ -129,6 +129,36 @@ hipError_t launch_attn_fwd_mfma(int B, int S, int nh, int dh, int causal, const 
 hipError_t launch_attn_bwd_mfma(int B, int S, int nh, int dh, int causal, const void *qkv, const void *o,
                                 const float *lse, const void *d_o, void *dqkv, float *ws, hipStream_t s,
                                 const DropArgs *drop = nullptr);
+
+// Where an attention call's operands live.  Each is a row-major matrix with one row per token
+// and head h's dh columns at column h*dh; sample b's rows start at row b*Sq (queries, O, dO,
+// dQ, and [B,nh,Sq] for lse) or b*Sk (keys, values, dK, dV).  Self-attention over a packed
+// [T,3H] tensor is the case k = q + H, v = q + 2H, ldq = ldkv = 3H, Sq = Sk; cross-attention
+// takes its queries from one tensor and keys and values from another of a different length.
+struct AttnView {
+  const void *q, *k, *v;
+  void *dq, *dk, *dv;   // backward only; laid out like q, k, v
+  long ldq, ldkv;       // row strides in elements
+  int Sq, Sk;
+};
+inline AttnView attn_self_view(const void *qkv, void *dqkv, int S, int H, size_t esz) {
+  const char *p = (const char *)qkv;
+  char *g = (char *)dqkv;
+  const size_t h = (size_t)H * esz;
+  return AttnView{p, p ? p + h : nullptr, p ? p + 2 * h : nullptr, g, g ? g + h : nullptr, g ? g + 2 * h : nullptr,
+                  3L * H, 3L * H, S, S};
+}
+// The same kernels on a view; causal needs Sq == Sk.  Dropout positions are query*Sk + key.
+hipError_t launch_attn_fwd_simple_view(int dtype, int B, int nh, int dh, int causal, const AttnView &v, void *o,
+                                       float *lse, hipStream_t s, const DropArgs *drop = nullptr);
+hipError_t launch_attn_bwd_simple_view(int dtype, int B, int nh, int dh, int causal, const AttnView &v, const void *o,
+                                       const float *lse, const void *d_o, float *ws, hipStream_t s,
+                                       const DropArgs *drop = nullptr);
+hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, void *o, float *lse,
+                                     hipStream_t s, const DropArgs *drop = nullptr);
+hipError_t launch_attn_bwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, const void *o,
+                                     const float *lse, const void *d_o, float *ws, hipStream_t s,
+                                     const DropArgs *drop = nullptr);
 
 // ---- diagnostics --------------------------------------------------------------
 // Matrix-core issue rate with operand fragments taken from `data` (bf16, n_elems >= 8); waits.

@@ -162,6 +162,67 @@ dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32
 }
 
 
+// ---- cross-attention: queries from one tensor, keys and values from another
+static dp_status cross_args(const char *what, int32_t dtype, int32_t B, int32_t Sq, int32_t Sk, int32_t nh, int32_t dh,
+                            const dp_dropout *drop, dp::DropArgs *a, bool *dropping) {
+  if (bad_dtype(dtype) || B < 0 || Sq < 0 || Sk < 0 || nh <= 0 || dh <= 0) return fail(DP_E_INVAL, "%s: bad argument", what);
+  if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
+  if ((long)B * Sq > 0 && Sk == 0) return fail(DP_E_INVAL, "%s: a softmax over no keys is undefined", what);
+  *dropping = drop != nullptr;
+  if (drop != nullptr) {
+    if ((long)Sq * Sk >= (1L << 32)) return fail(DP_E_UNSUPPORTED, "attention dropout needs Sq*Sk < 2^32");
+    return drop_args_of(drop, dp::kSiteCross, a);
+  }
+  return DP_OK;
+}
+
+dp_status dp_op_cross_attention_fwd(int32_t dtype, int32_t B, int32_t Sq, int32_t Sk, int32_t nh, int32_t dh,
+                                    const void *q, const void *kv, void *o, float *lse, const dp_dropout *drop,
+                                    void *hip_stream) {
+  dp::DropArgs a;
+  bool dropping = false;
+  const dp_status st = cross_args("cross_attention_fwd", dtype, B, Sq, Sk, nh, dh, drop, &a, &dropping);
+  if (st != DP_OK) return st;
+  if ((long)B * Sq == 0) return DP_OK;
+  if (!q || !kv) return fail(DP_E_INVAL, "cross_attention_fwd: null operand");
+  const long H = (long)nh * dh;
+  const char *kvp = (const char *)kv;
+  const dp::AttnView v{q, kvp, kvp + (size_t)H * dp::dtype_size(dtype), nullptr, nullptr, nullptr, H, 2 * H, Sq, Sk};
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(Sk, dh))
+    return op_done(dp::launch_attn_fwd_mfma_view(B, nh, dh, 0, v, o, lse, (hipStream_t)hip_stream, dropping ? &a : nullptr),
+                   "cross_attention_fwd");
+  if (Sq > 4096 || Sk > 4096) return fail(DP_E_UNSUPPORTED, "attention: more than 4096 rows needs the MFMA path");
+  return op_done(dp::launch_attn_fwd_simple_view(dtype, B, nh, dh, 0, v, o, lse, (hipStream_t)hip_stream,
+                                                 dropping ? &a : nullptr), "cross_attention_fwd");
+}
+
+dp_status dp_op_cross_attention_bwd(int32_t dtype, int32_t B, int32_t Sq, int32_t Sk, int32_t nh, int32_t dh,
+                                    const void *q, const void *kv, const void *o, const float *lse, const void *d_o,
+                                    void *dq, void *dkv, void *ws, const dp_dropout *drop, void *hip_stream) {
+  dp::DropArgs a;
+  bool dropping = false;
+  const dp_status st = cross_args("cross_attention_bwd", dtype, B, Sq, Sk, nh, dh, drop, &a, &dropping);
+  if (st != DP_OK) return st;
+  if ((long)B * Sq > 0 && (!q || !o || !lse || !d_o || !dq || !ws)) return fail(DP_E_INVAL, "cross_attention_bwd: null operand");
+  if ((long)B * Sk > 0 && (!kv || !dkv)) return fail(DP_E_INVAL, "cross_attention_bwd: null operand");
+  const long H = (long)nh * dh;
+  const size_t hb = (size_t)H * dp::dtype_size(dtype);
+  const char *kvp = (const char *)kv;
+  char *dkvp = (char *)dkv;
+  const dp::AttnView v{q, kvp, kvp ? kvp + hb : nullptr, dq, dkvp, dkvp ? dkvp + hb : nullptr, H, 2 * H, Sq, Sk};
+  const char *env = getenv("DPSTAGE_KERNELS");
+  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(std::max(Sk, 1), dh))
+    return op_done(dp::launch_attn_bwd_mfma_view(B, nh, dh, 0, v, o, lse, d_o, (float *)ws, (hipStream_t)hip_stream,
+                                                 dropping ? &a : nullptr), "cross_attention_bwd");
+  if (Sq > 4096 || Sk > 4096) return fail(DP_E_UNSUPPORTED, "attention: more than 4096 rows needs the MFMA path");
+  return op_done(dp::launch_attn_bwd_simple_view(dtype, B, nh, dh, 0, v, o, lse, d_o, (float *)ws, (hipStream_t)hip_stream,
+                                                 dropping ? &a : nullptr), "cross_attention_bwd");
+}
+
+
 dp_status dp_probe_mfma(const void *data_bf16, size_t n_elems, int32_t iters, float *tflops, float *shader_mhz,
                         void *hip_stream) {
   if (!data_bf16 || n_elems < 8 || n_elems % 8 || iters < 1 || !tflops || !shader_mhz)
