@@ -1,0 +1,101 @@
+"""CPU oracle for a decoder stage with cross-attention (the second workload shape: T5 is one
+of the models of Section 5.1; the paper gives no layer formulas, the textbook ones are written
+out here).
+
+TEST INFRASTRUCTURE ONLY: nothing in the product path imports this file, and it imports
+nothing from the product.
+
+A layer is the pre-LN transformer layer of oracle/stage.py with a cross-attention block
+between its self-attention and its feed-forward block; `mem` [B*S_mem, H] is the encoder's
+output, the same for every layer of the stage:
+
+  r1 = x  + SelfAttn(LN1(x) Wqkv + bqkv) Wo + bo
+  rc = r1 + CrossAttn(LNc(r1) Wq + bq, mem Wkv + bkv) Wo_c + bo_c
+  y  = rc + GELU(LN2(rc) W1 + b1) W2 + b2
+
+The step returns, besides Y, dX and the parameter gradients, dMem: the sum over the layers of
+the gradient that reaches `mem` through each layer's key/value projection.  Recompute and swap
+(Section 1; Appendix C.2) leave these numbers untouched, so there is no plan executor here: the
+device results under any plan are compared with this one definition.
+
+Pins (tests/test_oracle_decoder.py): central differences in float64 for x, mem and every
+parameter; with Wo_c = 0 and bo_c = 0 the stage is the plain pre-LN stage of oracle/stage.py
+(outputs and shared gradients equal, dMem = 0); samples do not see each other's memory;
+dMem is additive over layers.
+"""
+from __future__ import annotations
+
+from typing import Dict, List
+
+import numpy as np
+
+from . import stage as _ops
+
+CROSS_WEIGHTS = ("lnc_g", "lnc_b", "w_qc", "b_qc", "w_kvc", "b_kvc", "w_oc", "b_oc")
+
+
+class DecoderStage:
+    def __init__(self, n_layers, hidden, n_heads, ffn, seq, mem_seq, micro_batch, causal=True, gelu="erf", eps=1e-5):
+        self.L, self.H, self.nh, self.F = n_layers, hidden, n_heads, ffn
+        self.S, self.Sm, self.B = seq, mem_seq, micro_batch
+        self.causal, self.gelu, self.eps = bool(causal), gelu, eps
+
+    def layer_fwd(self, x, mem, w):
+        s = {"X_IN": x}
+        s["LN1_OUT"], *s["LN1_STATS"] = _ln(x, w["ln1_g"], w["ln1_b"], self.eps)
+        s["QKV"] = _ops.linear_fwd(s["LN1_OUT"], w["w_qkv"], w["b_qkv"])
+        s["ATTN_OUT"], _ = _ops.attention_fwd(s["QKV"], self.B, self.S, self.nh, self.causal)
+        s["RES1"] = x + _ops.linear_fwd(s["ATTN_OUT"], w["w_o"], w["b_o"])
+        s["LNC_OUT"], *s["LNC_STATS"] = _ln(s["RES1"], w["lnc_g"], w["lnc_b"], self.eps)
+        s["Q_C"] = _ops.linear_fwd(s["LNC_OUT"], w["w_qc"], w["b_qc"])
+        s["KV_C"] = _ops.linear_fwd(mem, w["w_kvc"], w["b_kvc"])
+        s["ATTN_C_OUT"], _ = _ops.cross_attention_fwd(s["Q_C"], s["KV_C"], self.B, self.S, self.Sm, self.nh)
+        s["RES_C"] = s["RES1"] + _ops.linear_fwd(s["ATTN_C_OUT"], w["w_oc"], w["b_oc"])
+        s["LN2_OUT"], *s["LN2_STATS"] = _ln(s["RES_C"], w["ln2_g"], w["ln2_b"], self.eps)
+        s["FC1_OUT"] = _ops.linear_fwd(s["LN2_OUT"], w["w_fc1"], w["b_fc1"])
+        s["GELU_OUT"] = _ops.gelu_fwd(s["FC1_OUT"], self.gelu)
+        y = s["RES_C"] + _ops.linear_fwd(s["GELU_OUT"], w["w_fc2"], w["b_fc2"])
+        return y, s
+
+    def layer_bwd(self, dy, mem, w, s):
+        """Returns (dx, dmem of this layer, parameter gradients)."""
+        g = {}
+        d_gelu, g["w_fc2"], g["b_fc2"] = _ops.linear_bwd(dy, s["GELU_OUT"], w["w_fc2"])
+        d_f = d_gelu * _ops.gelu_grad(s["FC1_OUT"], self.gelu)
+        d_n, g["w_fc1"], g["b_fc1"] = _ops.linear_bwd(d_f, s["LN2_OUT"], w["w_fc1"])
+        d_ln, g["ln2_g"], g["ln2_b"] = _ops.layernorm_bwd(d_n, s["RES_C"], *s["LN2_STATS"], w["ln2_g"])
+        d_rc = dy + d_ln
+        d_oc, g["w_oc"], g["b_oc"] = _ops.linear_bwd(d_rc, s["ATTN_C_OUT"], w["w_oc"])
+        d_qc, d_kvc = _ops.cross_attention_bwd(d_oc, s["Q_C"], s["KV_C"], self.B, self.S, self.Sm, self.nh)
+        d_mem, g["w_kvc"], g["b_kvc"] = _ops.linear_bwd(d_kvc, mem, w["w_kvc"])
+        d_c, g["w_qc"], g["b_qc"] = _ops.linear_bwd(d_qc, s["LNC_OUT"], w["w_qc"])
+        d_ln, g["lnc_g"], g["lnc_b"] = _ops.layernorm_bwd(d_c, s["RES1"], *s["LNC_STATS"], w["lnc_g"])
+        d_r1 = d_rc + d_ln
+        d_o, g["w_o"], g["b_o"] = _ops.linear_bwd(d_r1, s["ATTN_OUT"], w["w_o"])
+        d_qkv = _ops.attention_bwd(d_o, s["QKV"], self.B, self.S, self.nh, self.causal)
+        d_a, g["w_qkv"], g["b_qkv"] = _ops.linear_bwd(d_qkv, s["LN1_OUT"], w["w_qkv"])
+        d_ln, g["ln1_g"], g["ln1_b"] = _ops.layernorm_bwd(d_a, s["X_IN"], *s["LN1_STATS"], w["ln1_g"])
+        return d_r1 + d_ln, d_mem, g
+
+
+def _ln(x, gamma, beta, eps):
+    y, mu, r = _ops.layernorm_fwd(x, gamma, beta, eps)
+    return y, mu, r
+
+
+def decoder_step(stage: DecoderStage, weights: List[Dict[str, np.ndarray]], x, mem, dy, dtype=np.float64):
+    """Plain forward then backward.  Returns (Y, dX, dMem, per-layer gradient dicts)."""
+    weights = [{k: np.asarray(v, dtype=dtype) for k, v in w.items()} for w in weights]
+    h, mem = np.asarray(x, dtype=dtype), np.asarray(mem, dtype=dtype)
+    saved = []
+    for w in weights:
+        h, s = stage.layer_fwd(h, mem, w)
+        saved.append(s)
+    y = h
+    d = np.asarray(dy, dtype=dtype)
+    d_mem = np.zeros_like(mem)
+    grads = [None] * stage.L
+    for l in reversed(range(stage.L)):
+        d, dm, grads[l] = stage.layer_bwd(d, mem, weights[l], saved[l])
+        d_mem = d_mem + dm
+    return y, d, d_mem, grads
