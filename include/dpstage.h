@@ -17,7 +17,9 @@
  *   dp_stage_forward / dp_stage_backward   the step cut where a one-forward-one-backward
  *                                          schedule cuts it (micro-batch slots, gradient
  *                                          accumulation); dp_stage_set_weights (parameter
- *                                          versions); dp_stage_set_rng (dropout masks)
+ *                                          versions); dp_stage_set_rng (dropout masks);
+ *                                          dp_stage_set_cross / dp_stage_bind_memory (decoder
+ *                                          stages with a cross-attention block)
  *   dp_stage_measure_cost_model, dp_plan_cost, dp_plan_generate
  *                                          Section 4.3's memory optimisation from measured costs
  *   dp_partition                           Section 4.2's partition search over a chain of layers
@@ -78,6 +80,20 @@ enum {
   DP_SLOT_ATTN_OUT, DP_SLOT_RES1, DP_SLOT_LN2_STATS, DP_SLOT_LN2_OUT, DP_SLOT_FC1_OUT,
   DP_SLOT_GELU_OUT, DP_SLOT_RES2, DP_SLOTS_PER_LAYER
 };
+/* A stage with a cross-attention block (mem_seq > 0) has seven more slots per layer, after
+ * those above; its plans have DP_SLOTS_PER_LAYER_CROSS bytes a layer.  Tm = micro_batch*mem_seq.
+ *   LNC_STATS  [T,2]    fp32 statistics of the block's LayerNorm
+ *   LNC_OUT    [T,H]
+ *   Q_C        [T,H]    queries
+ *   KV_C       [Tm,2H]  columns [K | V] projected from the encoder memory (its producer reads
+ *                       no slot: a RECOMPUTE of it repeats the projection of the memory)
+ *   ATTN_C_LSE [B,nh,S] fp32
+ *   ATTN_C_OUT [T,H]
+ *   RES_C      [T,H]    RES1 + ATTN_C_OUT*Wo_c + bo_c */
+enum {
+  DP_SLOT_LNC_STATS = DP_SLOTS_PER_LAYER, DP_SLOT_LNC_OUT, DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_LSE,
+  DP_SLOT_ATTN_C_OUT, DP_SLOT_RES_C, DP_SLOTS_PER_LAYER_CROSS
+};
 
 /* A stage = n_layers identical transformer layers on one micro-batch.
  *   pre-LN : a=LN1(x); m=x+Attn(a*Wqkv+b)*Wo+bo; c=LN2(m); y=m+GELU(c*W1+b1)*W2+b2
@@ -90,7 +106,18 @@ enum {
  * (seed, micro-batch counter, layer, site, position) -- see dp_stage_set_rng --
  * so a recomputed tensor and the backward pass see the mask the forward saw.
  * dtype DP_BF16: weights, slots, outputs and gradients are bf16, accumulation
- * and statistics fp32.  DP_F32: everything fp32 (debug mode). */
+ * and statistics fp32.  DP_F32: everything fp32 (debug mode).
+ * mem_seq > 0 makes the stage a decoder stage of an encoder-decoder model (T5 is among the
+ * workloads of Section 5.1): every layer gets a cross-attention block between its attention
+ * and its feed-forward block, whose keys and values come from the encoder memory
+ * mem [micro_batch*mem_seq, H], the same for all layers:
+ *   pre-LN : r1 = x+Attn(..)*Wo+bo;  rc = r1 + CrossAttn(LNc(r1)*Wq+bq, mem*Wkv+bkv)*Wo_c+bo_c;
+ *            y = rc+GELU(LN2(rc)*W1+b1)*W2+b2        (no mask in the cross-attention)
+ * and the step also returns dMem, the sum over layers of the gradient reaching mem.  Such a
+ * stage needs norm_style DP_PRE_LN and both dropout rates 0 (DP_E_UNSUPPORTED otherwise), its
+ * block's parameters from dp_stage_set_cross and its memory buffers from
+ * dp_stage_bind_memory; the plan generator, the cost model and the partitioner do not take it
+ * yet (DP_E_UNSUPPORTED). */
 typedef struct {
   int32_t n_layers, hidden, n_heads, ffn, seq, micro_batch;
   int32_t norm_style; /* dp_norm_style */
@@ -99,6 +126,7 @@ typedef struct {
   int32_t dtype;      /* dp_dtype */
   float ln_eps;
   float p_attn, p_hidden; /* dropout rates in [0, 1); 0 = none */
+  int32_t mem_seq;        /* 0: no cross-attention block; > 0: length of the encoder memory */
 } dp_stage_config;
 
 /* Device pointers.  Linear weights are [in, out] row-major (y = x*W + b);
@@ -146,8 +174,8 @@ enum {
   DP_OPC_LN_FWD, DP_OPC_LN_BWD, DP_OPC_GELU_FWD, DP_OPC_GELU_BWD, DP_OPC_REDUCE, DP_OPC_DROPOUT, DP_OPC_COUNT
 };
 
-/* Number of plan bytes: n_layers * DP_SLOTS_PER_LAYER; 0 if cfg is invalid.
- * plan[l*DP_SLOTS_PER_LAYER + slot] is a dp_action. */
+/* Number of plan bytes: n_layers * DP_SLOTS_PER_LAYER (DP_SLOTS_PER_LAYER_CROSS with
+ * mem_seq > 0); 0 if cfg is invalid.  plan[l*slots_per_layer + slot] is a dp_action. */
 size_t dp_plan_len(const dp_stage_config *cfg);
 
 /* Pure host code: walks the step's schedule under `plan` and fills `report`
@@ -326,6 +354,30 @@ int32_t dp_stage_weight_versions(const dp_stage *st);
  * element is kept when its 32 bits are >= floor(p * 2^32), kept values are scaled by
  * 1/(1-p)) is stated in full in csrc/common.h.  Defaults: seed 0, counter 0. */
 dp_status dp_stage_set_rng(dp_stage *st, uint64_t seed, uint64_t counter);
+
+/* Decoder stages (mem_seq > 0).  Parameters of the cross-attention block of each layer, device
+ * pointers in the stage's dtype, caller-owned, copied by dp_stage_set_cross (on `hip_stream`,
+ * after waiting for the device when it replaces earlier values; these parameters are not part of
+ * the parameter versions of dp_stage_set_weights):
+ *   ln_g, ln_b [H];  w_q [H,H], b_q [H];  w_kv [H,2H] = [Wk | Wv], b_kv [2H];  w_o [H,H], b_o [H]
+ * (matrices [in, out] row-major, as dp_layer_weights).  dp_cross_grads: where their gradients
+ * go, same shapes; written as dp_layer_grads is: overwritten, or added to with
+ * DP_GRAD_ACCUMULATE. */
+typedef struct {
+  const void *ln_g, *ln_b, *w_q, *b_q, *w_kv, *b_kv, *w_o, *b_o;
+} dp_cross_weights;
+typedef struct {
+  void *ln_g, *ln_b, *w_q, *b_q, *w_kv, *b_kv, *w_o, *b_o;
+} dp_cross_grads;
+dp_status dp_stage_set_cross(dp_stage *st, const dp_cross_weights *layers, void *hip_stream);
+/* The buffers the following calls use: mem [micro_batch*mem_seq, H] (read by dp_stage_step and
+ * dp_stage_forward; a micro-batch between forward and backward keeps the pointer its forward
+ * saw, and the caller keeps that memory unchanged until its backward has run, since a
+ * recomputed KV_C reads it again), d_mem (same shape; overwritten by dp_stage_step and by every
+ * dp_stage_backward with the sum over layers, each layer's share added in bf16 or fp32 as the
+ * dtype says) and dw_cross[n_layers] (copied here).  All device memory, caller-owned; d_mem
+ * and dw_cross may be NULL for a caller that only runs dp_stage_forward. */
+dp_status dp_stage_bind_memory(dp_stage *st, const void *mem, void *d_mem, const dp_cross_grads *dw_cross);
 
 /* Per-kernel-class timing of later steps: when enabled, every kernel launch is
  * bracketed by HIP events on the stream it runs on.  dp_stage_op_times waits

@@ -20,6 +20,10 @@ LIB_PATH = os.path.join(_HERE, "libdpstage.so")
 WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                  "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 SLOTS_PER_LAYER = 12
+SLOTS_PER_LAYER_CROSS = 19
+# a decoder stage's cross-attention block: names in the tensor dicts -> fields of dp_cross_weights / dp_cross_grads
+CROSS_FIELDS = (("lnc_g", "ln_g"), ("lnc_b", "ln_b"), ("w_qc", "w_q"), ("b_qc", "b_q"), ("w_kvc", "w_kv"),
+                ("b_kvc", "b_kv"), ("w_oc", "w_o"), ("b_oc", "b_o"))
 OP_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd",
               "ln_fwd", "ln_bwd", "gelu_fwd", "gelu_bwd", "reduce", "dropout")
 STATUS = {0: "DP_OK", -1: "DP_E_INVAL", -2: "DP_E_PLAN", -3: "DP_E_BUDGET", -4: "DP_E_DEVMEM",
@@ -36,11 +40,15 @@ class DpError(RuntimeError):
 class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "micro_batch",
                                          "norm_style", "causal", "gelu_kind", "dtype")] + [("ln_eps", C.c_float), ("p_attn", C.c_float),
-                                                                                 ("p_hidden", C.c_float)]
+                                                                                 ("p_hidden", C.c_float), ("mem_seq", C.c_int32)]
 
 
 class LayerPtrs(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class CrossPtrs(C.Structure):
+    _fields_ = [(f, C.c_void_p) for _, f in CROSS_FIELDS]
 
 
 class PlanReport(C.Structure):
@@ -116,6 +124,8 @@ def lib() -> C.CDLL:
     L.dp_stage_forward.argtypes = [vp, C.c_uint32, C.c_uint32, vp, vp, sz, u64, vp, vp]
     L.dp_stage_backward.argtypes = [vp, C.c_uint32, vp, vp, C.POINTER(LayerPtrs), C.c_uint32, vp]
     L.dp_stage_set_rng.argtypes = [vp, u64, u64]
+    L.dp_stage_set_cross.argtypes = [vp, C.POINTER(CrossPtrs), vp]
+    L.dp_stage_bind_memory.argtypes = [vp, vp, vp, C.POINTER(CrossPtrs)]
     L.dp_stage_set_weights.argtypes = [vp, C.POINTER(LayerPtrs), vp]
     L.dp_stage_weight_versions.argtypes = [vp]
     L.dp_stage_weight_versions.restype = i32
@@ -147,7 +157,7 @@ def lib() -> C.CDLL:
     L.dp_plan_generate.argtypes = [C.POINTER(StageConfig), C.POINTER(CostModel), u64, C.c_uint32, u64, C.c_uint32, vp,
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
-    for name in ("dp_probe_mfma", "dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_profiling",
+    for name in ("dp_probe_mfma", "dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_cross", "dp_stage_bind_memory", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd",
@@ -163,10 +173,10 @@ def _check(code: int):
 
 
 def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, norm_style="post", causal=False,
-                gelu="erf", dtype="bf16", ln_eps=1e-5, p_attn=0.0, p_hidden=0.0) -> StageConfig:
+                gelu="erf", dtype="bf16", ln_eps=1e-5, p_attn=0.0, p_hidden=0.0, mem_seq=0) -> StageConfig:
     return StageConfig(n_layers, hidden, n_heads, ffn, seq, micro_batch,
                        {"post": 0, "pre": 1}[norm_style], int(bool(causal)), {"erf": 0, "tanh": 1}[gelu],
-                       {"f32": 0, "bf16": 1}[dtype], ln_eps, p_attn, p_hidden)
+                       {"f32": 0, "bf16": 1}[dtype], ln_eps, p_attn, p_hidden, mem_seq)
 
 
 def _plan_buf(plan):
@@ -277,6 +287,14 @@ def _layer_array(layers: Sequence[Dict[str, "object"]]):
     return arr
 
 
+def _cross_array(layers: Sequence[Dict[str, "object"]]):
+    arr = (CrossPtrs * len(layers))()
+    for i, d in enumerate(layers):
+        for name, field in CROSS_FIELDS:
+            setattr(arr[i], field, d[name].data_ptr())
+    return arr
+
+
 def _stream_ptr(stream) -> Optional[int]:
     if stream is None:
         import torch
@@ -336,6 +354,16 @@ def stage_backward(stage: Stage, slot: int, dy, dx_out, grads: Sequence[Dict[str
 
 def stage_set_weights(stage: Stage, weights: Sequence[Dict[str, "object"]], stream=None):
     _check(lib().dp_stage_set_weights(stage.handle, _layer_array(weights), _stream_ptr(stream)))
+
+
+def stage_set_cross(stage: Stage, weights: Sequence[Dict[str, "object"]], stream=None):
+    """Uploads the cross-attention block's parameters (tensors named as the first column of CROSS_FIELDS)."""
+    _check(lib().dp_stage_set_cross(stage.handle, _cross_array(weights), _stream_ptr(stream)))
+
+
+def stage_bind_memory(stage: Stage, mem, d_mem=None, grads: Optional[Sequence[Dict[str, "object"]]] = None):
+    _check(lib().dp_stage_bind_memory(stage.handle, _ptr(mem), _ptr(d_mem) if d_mem is not None else None,
+                                      _cross_array(grads) if grads is not None else None))
 
 
 def stage_set_rng(stage: Stage, seed: int, counter: int):

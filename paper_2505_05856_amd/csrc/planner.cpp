@@ -393,6 +393,7 @@ dp_status dp_plan_cost(const dp_stage_config *cfg, const dp_cost_model *cm, cons
   Cfg c;
   dp_status s = parse_cfg(cfg, &c);
   if (s != DP_OK) return s;
+  if (c.cross) return fail(DP_E_UNSUPPORTED, "the planners do not take stages with a cross-attention block yet");
   if ((s = check_cost_model(cm)) != DP_OK) return s;
   if (report == nullptr) return fail(DP_E_INVAL, "report is null");
   dp_plan_report pr;
@@ -410,6 +411,7 @@ dp_status dp_plan_generate(const dp_stage_config *cfg, const dp_cost_model *cm, 
   Cfg c;
   dp_status s = parse_cfg(cfg, &c);
   if (s != DP_OK) return s;
+  if (c.cross) return fail(DP_E_UNSUPPORTED, "the planners do not take stages with a cross-attention block yet");
   if ((s = check_cost_model(cm)) != DP_OK) return s;
   if (plan_out == nullptr) return fail(DP_E_INVAL, "plan_out is null");
   if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", DP_SLOTS_PER_LAYER);
@@ -439,6 +441,7 @@ dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm
   Cfg c;
   dp_status s = parse_cfg(chain_cfg, &c);
   if (s != DP_OK) return s;
+  if (c.cross) return fail(DP_E_UNSUPPORTED, "the planners do not take stages with a cross-attention block yet");
   if ((s = check_cost_model(cm)) != DP_OK) return s;
   if (n_stages < 1 || n_stages > 32 || n_stages > c.L)
     return fail(DP_E_INVAL, "n_stages must be 1..min(32, n_layers)");

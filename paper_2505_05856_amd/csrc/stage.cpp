@@ -63,6 +63,16 @@ dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
     return fail(DP_E_UNSUPPORTED, "seq > 4096 is not supported for this head_dim/dtype");
   if (o->T > (1L << 24) || (long)o->T * std::max(o->F, 3 * o->H) > (1L << 40))
     return fail(DP_E_UNSUPPORTED, "micro_batch*seq too large");
+  if (c->mem_seq < 0) return fail(DP_E_INVAL, "mem_seq must be >= 0");
+  o->Sm = c->mem_seq; o->Tm = (long)c->micro_batch * c->mem_seq; o->cross = c->mem_seq > 0;
+  o->nslots = o->cross ? DP_SLOTS_PER_LAYER_CROSS : DP_SLOTS_PER_LAYER;
+  if (o->cross) {
+    if (!o->pre) return fail(DP_E_UNSUPPORTED, "a stage with a cross-attention block needs norm_style DP_PRE_LN");
+    if (o->drop_attn || o->drop_hidden) return fail(DP_E_UNSUPPORTED, "a stage with a cross-attention block runs without dropout");
+    if (o->Sm > 4096 && !(o->dtype == DP_BF16 && dp::attn_mfma_supported(o->Sm, o->dh)))
+      return fail(DP_E_UNSUPPORTED, "mem_seq > 4096 is not supported for this head_dim/dtype");
+    if (o->Tm > (1L << 24)) return fail(DP_E_UNSUPPORTED, "micro_batch*mem_seq too large");
+  }
   return DP_OK;
 }
 
@@ -89,14 +99,33 @@ const OpDef kPostOps[N_OPS] = {
     {OP_LN2, 1, {{0, DP_SLOT_RES2}}, 2, {{1, DP_SLOT_X_IN}, {0, DP_SLOT_LN2_STATS}}},
 };
 
+// a decoder layer: the pre-LN layer with the cross-attention block between PROJ and LN2; the
+// key/value projection reads the encoder memory, which is no slot
+const OpDef kPreCrossOps[N_OPS_CROSS] = {
+    {OP_LN1, 1, {{0, DP_SLOT_X_IN}}, 2, {{0, DP_SLOT_LN1_OUT}, {0, DP_SLOT_LN1_STATS}}},
+    {OP_QKV, 1, {{0, DP_SLOT_LN1_OUT}}, 1, {{0, DP_SLOT_QKV}}},
+    {OP_ATTN, 1, {{0, DP_SLOT_QKV}}, 2, {{0, DP_SLOT_ATTN_OUT}, {0, DP_SLOT_ATTN_LSE}}},
+    {OP_PROJ, 2, {{0, DP_SLOT_ATTN_OUT}, {0, DP_SLOT_X_IN}}, 1, {{0, DP_SLOT_RES1}}},
+    {OP_LNC, 1, {{0, DP_SLOT_RES1}}, 2, {{0, DP_SLOT_LNC_OUT}, {0, DP_SLOT_LNC_STATS}}},
+    {OP_QC, 1, {{0, DP_SLOT_LNC_OUT}}, 1, {{0, DP_SLOT_Q_C}}},
+    {OP_KVC, 0, {}, 1, {{0, DP_SLOT_KV_C}}},
+    {OP_ATTNC, 2, {{0, DP_SLOT_Q_C}, {0, DP_SLOT_KV_C}}, 2, {{0, DP_SLOT_ATTN_C_OUT}, {0, DP_SLOT_ATTN_C_LSE}}},
+    {OP_PROJC, 2, {{0, DP_SLOT_ATTN_C_OUT}, {0, DP_SLOT_RES1}}, 1, {{0, DP_SLOT_RES_C}}},
+    {OP_LN2, 1, {{0, DP_SLOT_RES_C}}, 2, {{0, DP_SLOT_LN2_OUT}, {0, DP_SLOT_LN2_STATS}}},
+    {OP_FC1, 1, {{0, DP_SLOT_LN2_OUT}}, 1, {{0, DP_SLOT_FC1_OUT}}},
+    {OP_GELU, 1, {{0, DP_SLOT_FC1_OUT}}, 1, {{0, DP_SLOT_GELU_OUT}}},
+    {OP_FC2, 2, {{0, DP_SLOT_GELU_OUT}, {0, DP_SLOT_RES_C}}, 1, {{1, DP_SLOT_X_IN}}},
+};
+
 inline bool slot_is_alias(const Cfg &c, int slot) {
   return c.pre ? slot == DP_SLOT_RES2 : slot == DP_SLOT_LN2_OUT;
 }
 
 size_t slot_bytes(const Cfg &c, int slot) {
   switch (slot) {
-    case DP_SLOT_LN1_STATS: case DP_SLOT_LN2_STATS: return (size_t)c.T * 2 * sizeof(float);
-    case DP_SLOT_ATTN_LSE: return (size_t)c.B * c.nh * c.S * sizeof(float);
+    case DP_SLOT_LN1_STATS: case DP_SLOT_LN2_STATS: case DP_SLOT_LNC_STATS: return (size_t)c.T * 2 * sizeof(float);
+    case DP_SLOT_ATTN_LSE: case DP_SLOT_ATTN_C_LSE: return (size_t)c.B * c.nh * c.S * sizeof(float);
+    case DP_SLOT_KV_C: return (size_t)c.Tm * 2 * c.H * c.esz;
     case DP_SLOT_QKV: return (size_t)c.T * 3 * c.H * c.esz;
     case DP_SLOT_FC1_OUT: case DP_SLOT_GELU_OUT: return (size_t)c.T * c.F * c.esz;
     default: return slot_is_alias(c, slot) ? 0 : (size_t)c.T * c.H * c.esz;
@@ -110,6 +139,9 @@ double op_flops(const Cfg &c, Op op) {
     case OP_PROJ: return 2 * T * H * H;
     case OP_FC1: case OP_FC2: return 2 * T * H * F;
     case OP_ATTN: return (c.causal ? 2.0 : 4.0) * T * c.S * H;
+    case OP_QC: case OP_PROJC: return 2 * T * H * H;
+    case OP_KVC: return 2 * (double)c.Tm * H * 2 * H;
+    case OP_ATTNC: return 4.0 * T * c.Sm * H;
     default: return 0;
   }
 }
@@ -208,6 +240,12 @@ struct LayerW {  // library-owned device copies
   void *wt_qkv, *wt_o, *wt_fc1, *wt_fc2;   // transposed: [out, in]
 };
 
+struct CrossW {  // the cross-attention block of one layer: library-owned device copies
+  void *ln_g, *ln_b, *b_q, *b_kv, *b_o;
+  void *w_q, *w_kv, *w_o;       // as given: [in, out]
+  void *wt_q, *wt_kv, *wt_o;    // transposed: [out, in]
+};
+
 // One version of the stage's parameters.  A micro-batch in flight keeps the version its forward
 // used (Section 1: an asynchronous schedule updates the parameters between a micro-batch's
 // forward and its backward, so a stage keeps one version per micro-batch in flight).
@@ -267,6 +305,12 @@ struct dp_stage {
   uint64_t rng_seed = 0, rng_counter = 0;         // dropout: the seed, and the micro-batch number the next forward takes
   hipEvent_t bwd_end[2] = {nullptr, nullptr};     // ends of the last two dp_stage_backward calls
   uint64_t bwd_issued = 0;
+  // decoder stages: the cross-attention parameters and the bound memory buffers
+  void *cross_slab = nullptr;
+  std::vector<CrossW> cross_w;
+  const void *mem = nullptr;
+  void *d_mem = nullptr;
+  std::vector<dp_cross_grads> dw_cross;
   // result of the last successful plan validation (a training loop repeats one plan)
   std::vector<uint8_t> cached_plan;
   uint64_t cached_budget = 0;
@@ -311,6 +355,9 @@ struct Walk {
   const void *x_in = nullptr, *dy = nullptr;
   void *y_out = nullptr, *dx_out = nullptr;
   const dp_layer_grads *dw = nullptr;
+  const void *mem = nullptr;            // decoder stages: encoder memory, its gradient, the block's gradients
+  void *d_mem = nullptr;
+  const dp_cross_grads *dwx = nullptr;
 
   Arena arena;
   std::vector<SlotState> slots;  // (L+1) * DP_SLOTS_PER_LAYER
@@ -346,15 +393,16 @@ struct Walk {
   int n_replayed = 0, n_swapped = 0, n_launch = 0;
 
   Walk(const Cfg &cfg, const uint8_t *p, bool is_live, dp_stage *s)
-      : c(cfg), plan(p), live(is_live), st(s), slots((size_t)(cfg.L + 1) * DP_SLOTS_PER_LAYER) {}
+      : c(cfg), plan(p), live(is_live), st(s), slots((size_t)(cfg.L + 1) * (size_t)cfg.nslots) {}
 
   // ---- helpers ------------------------------------------------------------
-  SlotState &S(int l, int slot) { return slots[(size_t)l * DP_SLOTS_PER_LAYER + slot]; }
-  const OpDef *ops() const { return c.pre ? kPreOps : kPostOps; }
+  SlotState &S(int l, int slot) { return slots[(size_t)l * (size_t)c.nslots + slot]; }
+  const OpDef *ops() const { return op_table(c); }
+  int n_ops() const { return op_count(c); }
   bool caller_owned(int l, int slot) const { return slot == DP_SLOT_X_IN && (l == 0 || l == c.L); }
   int action(int l, int slot) const {
     if (l >= c.L || slot_is_alias(c, slot) || caller_owned(l, slot)) return DP_KEEP;
-    return plan[(size_t)l * DP_SLOTS_PER_LAYER + slot];
+    return plan[(size_t)l * (size_t)c.nslots + slot];
   }
   char *base() const { return live ? arena_base : nullptr; }
   void *ptr(int l, int slot) {
@@ -390,7 +438,7 @@ struct Walk {
   // the launches that follow belong to node `node` of layer l; with a cost model the node's time is charged here
   void begin_node(int phase, int l, int node) {
     tag = ((uint32_t)phase << 16) | ((uint32_t)l << 4) | (uint32_t)node;
-    if (cm) clk[0] += phase == TAG_BWD ? cm->bwd_ns[node] : cm->fwd_ns[node];
+    if (cm && node < N_OPS) clk[0] += phase == TAG_BWD ? cm->bwd_ns[node] : cm->fwd_ns[node];
   }
 
   uint64_t arena_alloc(uint64_t bytes) {
@@ -583,8 +631,47 @@ struct Walk {
              c.drop_hidden ? nullptr : in(1), out0);
         if (c.drop_hidden) hidden_dropout(l, dp::kSiteFc2, out0, in(1), out0);
         break;
+      case OP_LNC: {
+        prof_begin(DP_OPC_LN_FWD);
+        if (live) {
+          const CrossW &x = st->cross_w[(size_t)l];
+          check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), x.ln_g, x.ln_b, out0, (float *)out1, cs));
+        }
+        prof_end();
+        break;
+      }
+      case OP_QC:
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? st->cross_w[(size_t)l].wt_q : nullptr,
+             live ? st->cross_w[(size_t)l].b_q : nullptr, nullptr, out0);
+        break;
+      case OP_KVC:   // reads the encoder memory, which is no slot: a replay repeats the projection
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, c.Tm, 2 * H, H, mem, live ? st->cross_w[(size_t)l].wt_kv : nullptr,
+             live ? st->cross_w[(size_t)l].b_kv : nullptr, nullptr, out0);
+        break;
+      case OP_ATTNC:
+        prof_begin(DP_OPC_ATTN_FWD);
+        if (live) {
+          const dp::AttnView v = cross_view(in(0), in(1), nullptr, nullptr);
+          if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.Sm, c.dh))
+            check(dp::launch_attn_fwd_mfma_view(c.B, c.nh, c.dh, 0, v, out0, (float *)out1, cs));
+          else
+            check(dp::launch_attn_fwd_simple_view(c.dtype, c.B, c.nh, c.dh, 0, v, out0, (float *)out1, cs));
+        }
+        prof_end();
+        break;
+      case OP_PROJC:
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? st->cross_w[(size_t)l].wt_o : nullptr,
+             live ? st->cross_w[(size_t)l].b_o : nullptr, in(1), out0);
+        break;
       default: break;
     }
+  }
+  // queries [T,H] over the keys and values of kv [Tm,2H] = [K | V]
+  dp::AttnView cross_view(const void *q, const void *kv, void *dq, void *dkv) const {
+    const size_t hb = (size_t)c.H * c.esz;
+    const char *k = (const char *)kv;
+    char *dk = (char *)dkv;
+    return dp::AttnView{q, k, k + hb, dq, dk, dk ? dk + hb : nullptr, (long)c.H, 2L * c.H, c.S, c.Sm};
   }
 
   // ---- swap engine --------------------------------------------------------------
@@ -633,7 +720,7 @@ struct Walk {
   }
   void prefetch_layer(int l) {
     if (l < 0) return;
-    for (int slot = 0; slot < DP_SLOTS_PER_LAYER; ++slot) swap_in(l, slot);
+    for (int slot = 0; slot < c.nslots; ++slot) swap_in(l, slot);
   }
 
   // Makes slot (l, slot) readable by the compute stream: waits for its swap-in,
@@ -648,7 +735,7 @@ struct Walk {
     // ABSENT: replay.  X_IN of layer l is produced by the last op of layer l-1.
     const int pl = slot == DP_SLOT_X_IN ? l - 1 : l;
     const OpDef *d = nullptr;
-    for (int i = 0; i < N_OPS && d == nullptr; ++i)
+    for (int i = 0; i < n_ops() && d == nullptr; ++i)
       for (int o = 0; o < ops()[i].n_out; ++o)
         if (pl + ops()[i].out[o].dl == l && ops()[i].out[o].slot == slot) d = &ops()[i];
     for (int i = 0; i < d->n_in; ++i) ensure(pl + d->in[i].dl, d->in[i].slot);
@@ -674,9 +761,9 @@ struct Walk {
     S(0, DP_SLOT_X_IN).where = RESIDENT;
     for (int l = 0; l < c.L; ++l) {
       // last forward reader of every slot of this layer (producer if nobody reads it)
-      int last[DP_SLOTS_PER_LAYER];
-      for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) last[s] = -1;
-      for (int i = 0; i < N_OPS; ++i) {
+      int last[kMaxSlots];
+      for (int s = 0; s < kMaxSlots; ++s) last[s] = -1;
+      for (int i = 0; i < n_ops(); ++i) {
         const OpDef &d = ops()[i];
         for (int k = 0; k < d.n_in; ++k) if (d.in[k].dl == 0) last[d.in[k].slot] = i;
         for (int k = 0; k < d.n_out; ++k) if (d.out[k].dl == 0) last[d.out[k].slot] = i;
@@ -684,7 +771,7 @@ struct Walk {
       // In forward the GELU rides the FC1 epilogue when FC1 runs on the matrix cores (both
       // tensors are written by one kernel; the GELU op then only does its bookkeeping).
       const bool fuse_gelu = fuse_gelu_enabled && gemm_on_mfma(dp::kGemmNT, c.T, c.F, c.H);
-      for (int i = 0; i < N_OPS; ++i) {
+      for (int i = 0; i < n_ops(); ++i) {
         const OpDef &d = ops()[i];
         void *outp[2] = {nullptr, nullptr};
         const bool produced_already = fuse_gelu && d.op == OP_GELU;
@@ -699,7 +786,7 @@ struct Walk {
         begin_node(TAG_FWD, l, i);
         if (!produced_already) run_op(l, d, outp[0], outp[1]);
         step_flops += op_flops(c, d.op);
-        for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) {
+        for (int s = 0; s < c.nslots; ++s) {
           if (last[s] != i || S(l, s).where != RESIDENT) continue;
           const int a = action(l, s);
           if (a == DP_RECOMPUTE) slot_free(l, s);
@@ -759,13 +846,16 @@ struct Walk {
         drop(dg);
         done_with(l, {DP_SLOT_LN2_OUT});
         // LN2: dM = dY + LN2'(dC), in place in dC
-        need(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
+        const int res_mlp = c.cross ? DP_SLOT_RES_C : DP_SLOT_RES1;   // the residual stream the feed-forward block reads
+        need(l, {res_mlp, DP_SLOT_LN2_STATS});
         begin_node(TAG_BWD, l, 3);
-        ln_bwd(bptr(dc), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), dcur, bptr(dc), G_(ln2_g),
-               G_(ln2_b), c.drop_hidden ? nullptr : G_(b_o));   // dbo = column sums of dM (of the masked dM with dropout)
+        // the column sums of dM are the bias gradient of the projection that wrote that residual stream
+        ln_bwd(bptr(dc), ptr(l, res_mlp), ptr(l, DP_SLOT_LN2_STATS), W_(ln2_g), dcur, bptr(dc), G_(ln2_g),
+               G_(ln2_b), c.drop_hidden ? nullptr : c.cross ? (live ? dwx[l].b_o : nullptr) : G_(b_o));
         drop(dcur_buf);
-        done_with(l, {DP_SLOT_RES1, DP_SLOT_LN2_STATS});
+        done_with(l, {res_mlp, DP_SLOT_LN2_STATS});
         Buf dm = dc;
+        if (c.cross) dm = cross_block_bwd(l, dm, G_(b_o));
         // out-projection: dO = dM Wo^T, dWo = ATTN_OUT^T dM
         need(l, {DP_SLOT_ATTN_OUT});
         begin_node(TAG_BWD, l, 4);
@@ -871,10 +961,75 @@ struct Walk {
 #undef W_
 #undef G_
       // whatever a replay left behind in this layer goes now
-      for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) { slot_free(l, s); S(l, s).consumed = true; }
+      for (int s = 0; s < c.nslots; ++s) { slot_free(l, s); S(l, s).consumed = true; }
       flush_reduces();
     }
     flush_reduces();
+  }
+
+  // Backward of a decoder layer's cross-attention block: takes dRc (the gradient of RES_C), returns
+  // dR1 = dRc + the block's share; adds the layer's share to dMem; dbo_self receives the column sums
+  // of dR1 (the bias gradient of the self-attention projection, which wrote RES1).
+  Buf cross_block_bwd(int l, Buf dm, void *dbo_self) {
+    const long T = c.T, H = c.H, Tm = c.Tm;
+    const size_t th = (size_t)T * H * c.esz;
+    const CrossW *xw = live ? &st->cross_w[(size_t)l] : nullptr;
+    const dp_cross_grads *xg = live ? &dwx[l] : nullptr;
+#define XW_(f) (live ? xw->f : nullptr)
+#define XG_(f) (live ? xg->f : nullptr)
+    // output projection: dOc = dRc Wo_c^T, dWo_c = ATTN_C_OUT^T dRc
+    need(l, {DP_SLOT_ATTN_C_OUT});
+    begin_node(TAG_BWD, l, OP_PROJC);
+    Buf doc = tmp(th);
+    gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dm), XW_(w_o), nullptr, nullptr, bptr(doc));
+    gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_C_OUT), bptr(dm), nullptr, nullptr, XG_(w_o));
+    // attention: dQc, dKVc
+    need(l, {DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_LSE});
+    begin_node(TAG_BWD, l, OP_ATTNC);
+    Buf dqc = tmp(th);
+    Buf dkvc = tmp((size_t)Tm * 2 * H * c.esz);
+    Buf ws = tmp((size_t)c.B * c.nh * c.S * sizeof(float));
+    prof_begin(DP_OPC_ATTN_BWD);
+    if (live) {
+      const dp::AttnView v = cross_view(ptr(l, DP_SLOT_Q_C), ptr(l, DP_SLOT_KV_C), bptr(dqc), bptr(dkvc));
+      if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.Sm, c.dh))
+        check(dp::launch_attn_bwd_mfma_view(c.B, c.nh, c.dh, 0, v, ptr(l, DP_SLOT_ATTN_C_OUT),
+                                            (const float *)ptr(l, DP_SLOT_ATTN_C_LSE), bptr(doc), (float *)bptr(ws), cs));
+      else
+        check(dp::launch_attn_bwd_simple_view(c.dtype, c.B, c.nh, c.dh, 0, v, ptr(l, DP_SLOT_ATTN_C_OUT),
+                                              (const float *)ptr(l, DP_SLOT_ATTN_C_LSE), bptr(doc), (float *)bptr(ws),
+                                              cs));
+    }
+    prof_end();
+    drop(ws);
+    drop(doc);
+    done_with(l, {DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_OUT, DP_SLOT_ATTN_C_LSE});
+    colsum(T, H, bptr(dqc), XG_(b_q));
+    colsum(Tm, 2 * H, bptr(dkvc), XG_(b_kv));
+    // key/value projection: dMem (+)= dKVc Wkv^T (the top layer writes, the others add), dWkv = mem^T dKVc
+    begin_node(TAG_BWD, l, OP_KVC);
+    gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, Tm, H, 2 * H, bptr(dkvc), XW_(w_kv), nullptr, l == c.L - 1 ? nullptr : d_mem,
+         d_mem);
+    gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, 2 * H, Tm, mem, bptr(dkvc), nullptr, nullptr, XG_(w_kv));
+    drop(dkvc);
+    // query projection: dC = dQc Wq^T, dWq = LNC_OUT^T dQc
+    need(l, {DP_SLOT_LNC_OUT});
+    begin_node(TAG_BWD, l, OP_QC);
+    Buf dcx = tmp(th);
+    gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dqc), XW_(w_q), nullptr, nullptr, bptr(dcx));
+    gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_LNC_OUT), bptr(dqc), nullptr, nullptr, XG_(w_q));
+    drop(dqc);
+    done_with(l, {DP_SLOT_LNC_OUT});
+    // LayerNorm of the block: dR1 = dRc + LNc'(dC), in place in dC
+    need(l, {DP_SLOT_RES1, DP_SLOT_LNC_STATS});
+    begin_node(TAG_BWD, l, OP_LNC);
+    ln_bwd(bptr(dcx), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LNC_STATS), XW_(ln_g), bptr(dm), bptr(dcx), XG_(ln_g),
+           XG_(ln_b), dbo_self);
+    drop(dm);
+    done_with(l, {DP_SLOT_RES1, DP_SLOT_LNC_STATS});
+#undef XW_
+#undef XG_
+    return dcx;
   }
 
   // dQKV from dO; frees dO and the attention slots; also the QKV bias gradient.
@@ -921,11 +1076,12 @@ uint64_t weight_elems_per_layer(const Cfg &c, uint64_t *matrix_elems) {
 
 dp_status check_plan(const Cfg &c, const uint8_t *plan, size_t plan_len, dp_plan_report *rep) {
   if (plan == nullptr) return fail(DP_E_INVAL, "plan is null");
-  if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER)
-    return fail(DP_E_INVAL, "plan_len is %zu, expected %zu", plan_len, (size_t)c.L * DP_SLOTS_PER_LAYER);
+  const size_t ns = (size_t)c.nslots;
+  if (plan_len != (size_t)c.L * ns)
+    return fail(DP_E_INVAL, "plan_len is %zu, expected %zu", plan_len, (size_t)c.L * ns);
   for (size_t i = 0; i < plan_len; ++i)
     if (plan[i] > DP_SWAP) {
-      if (rep) { rep->first_bad_layer = (int)(i / DP_SLOTS_PER_LAYER); rep->first_bad_slot = (int)(i % DP_SLOTS_PER_LAYER); }
+      if (rep) { rep->first_bad_layer = (int)(i / ns); rep->first_bad_slot = (int)(i % ns); }
       return fail(DP_E_INVAL, "plan[%zu] = %u is not an action", i, (unsigned)plan[i]);
     }
   if (plan[DP_SLOT_X_IN] == DP_RECOMPUTE) {
@@ -941,6 +1097,12 @@ static void fill_report(const Cfg &c, const Walk &w, dp_plan_report *r) {
   r->weight_bytes = (uint64_t)c.L * (per_layer + mats) * c.esz;  // given + transposed matrices
   r->grad_bytes = (uint64_t)c.L * per_layer * c.esz;
   r->fixed_bytes = r->weight_bytes + r->grad_bytes + 4 * (uint64_t)c.T * c.H * c.esz;
+  if (c.cross) {   // the block's parameters, and the encoder memory with its gradient
+    const uint64_t H = (uint64_t)c.H, xm = 4 * H * H, xv = 6 * H;
+    r->weight_bytes += (uint64_t)c.L * (2 * xm + xv) * c.esz;
+    r->grad_bytes += (uint64_t)c.L * (xm + xv) * c.esz;
+    r->fixed_bytes += (uint64_t)c.L * (3 * xm + 2 * xv) * c.esz + 2 * (uint64_t)c.Tm * H * c.esz;
+  }
   r->arena_peak_bytes = w.arena.high_water;
   r->peak_bytes = r->fixed_bytes + w.arena.high_water;
   r->live_peak_bytes = r->fixed_bytes + w.arena.live_peak;
@@ -1028,7 +1190,7 @@ const char *dp_last_error(void) { return g_err; }
 size_t dp_plan_len(const dp_stage_config *cfg) {
   Cfg c;
   if (parse_cfg(cfg, &c) != DP_OK) return 0;
-  return (size_t)c.L * DP_SLOTS_PER_LAYER;
+  return (size_t)c.L * (size_t)c.nslots;
 }
 
 dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len, uint64_t budget_bytes,
@@ -1171,6 +1333,83 @@ static dp_status ensure_memory(void **arena, uint64_t *arena_bytes, void **host_
   return DP_OK;
 }
 
+// A decoder stage can run once its block's parameters are uploaded and its memory is bound.
+static dp_status cross_ready(const dp_stage *st, bool backward_too) {
+  if (st->cross_w.empty()) return fail(DP_E_INVAL, "the stage has a cross-attention block: call dp_stage_set_cross first");
+  if (st->mem == nullptr) return fail(DP_E_INVAL, "the stage has a cross-attention block: bind its memory with dp_stage_bind_memory");
+  if (backward_too && (st->d_mem == nullptr || st->dw_cross.empty()))
+    return fail(DP_E_INVAL, "the backward pass of a decoder stage needs d_mem and dw_cross (dp_stage_bind_memory)");
+  return DP_OK;
+}
+
+dp_status dp_stage_set_cross(dp_stage *st, const dp_cross_weights *layers, void *hip_stream) {
+  if (st == nullptr || layers == nullptr) return fail(DP_E_INVAL, "null argument");
+  const Cfg &c = st->c;
+  if (!c.cross) return fail(DP_E_INVAL, "the stage has no cross-attention block (mem_seq is 0)");
+  for (int l = 0; l < c.L; ++l) {
+    const void *const *p = reinterpret_cast<const void *const *>(&layers[l]);
+    for (int i = 0; i < 8; ++i)
+      if (p[i] == nullptr) return fail(DP_E_INVAL, "cross-attention weight pointer %d of layer %d is null", i, l);
+  }
+  for (auto &f : st->flights)
+    if (f && f->walk != nullptr) return fail(DP_E_INVAL, "a micro-batch is between its forward and its backward");
+  const uint64_t H = (uint64_t)c.H;
+  const uint64_t slab = ((2 * 4 * H * H + 6 * H) * c.esz + 16 * 256) * (uint64_t)c.L;   // every tensor on a 256-byte boundary
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (st->cross_slab == nullptr) {
+    if (hipMalloc(&st->cross_slab, slab) != hipSuccess) {
+      (void)hipGetLastError();
+      st->cross_slab = nullptr;
+      return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the cross-attention weights", (unsigned long long)slab);
+    }
+  } else {
+    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);   // earlier steps may still read the old values
+  }
+  char *cur = (char *)st->cross_slab;
+  auto take = [&](uint64_t elems) { void *p = cur; cur += (elems * c.esz + 255) / 256 * 256; return p; };
+  hipError_t e = hipSuccess;
+  auto copy_vec = [&](void **dst, const void *src, uint64_t n) {
+    *dst = take(n);
+    if (e == hipSuccess) e = hipMemcpyAsync(*dst, src, n * c.esz, hipMemcpyDeviceToDevice, stream);
+  };
+  auto copy_mat = [&](void **dst, void **dst_t, const void *src, uint64_t rows, uint64_t cols) {
+    copy_vec(dst, src, rows * cols);
+    *dst_t = take(rows * cols);
+    if (e == hipSuccess) e = dp::launch_transpose(c.dtype, (int)rows, (int)cols, src, *dst_t, stream);
+  };
+  st->cross_w.assign((size_t)c.L, CrossW{});
+  for (int l = 0; l < c.L; ++l) {
+    CrossW &w = st->cross_w[(size_t)l];
+    const dp_cross_weights &s0 = layers[l];
+    copy_vec(&w.ln_g, s0.ln_g, H); copy_vec(&w.ln_b, s0.ln_b, H);
+    copy_vec(&w.b_q, s0.b_q, H); copy_vec(&w.b_kv, s0.b_kv, 2 * H); copy_vec(&w.b_o, s0.b_o, H);
+    copy_mat(&w.w_q, &w.wt_q, s0.w_q, H, H);
+    copy_mat(&w.w_kv, &w.wt_kv, s0.w_kv, H, 2 * H);
+    copy_mat(&w.w_o, &w.wt_o, s0.w_o, H, H);
+  }
+  // the stage's own streams and whatever stream the caller steps on may read them next
+  if (e == hipSuccess) e = hipStreamSynchronize(stream);
+  if (e != hipSuccess) { st->cross_w.clear(); return fail(DP_E_HIP, "cross-attention weight upload: %s", hipGetErrorString(e)); }
+  return DP_OK;
+}
+
+dp_status dp_stage_bind_memory(dp_stage *st, const void *mem, void *d_mem, const dp_cross_grads *dw_cross) {
+  if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
+  const Cfg &c = st->c;
+  if (!c.cross) return fail(DP_E_INVAL, "the stage has no cross-attention block (mem_seq is 0)");
+  if (mem == nullptr) return fail(DP_E_INVAL, "mem is null");
+  if (dw_cross != nullptr)
+    for (int l = 0; l < c.L; ++l) {
+      void *const *p = reinterpret_cast<void *const *>(&dw_cross[l]);
+      for (int i = 0; i < 8; ++i)
+        if (p[i] == nullptr) return fail(DP_E_INVAL, "cross-attention gradient pointer %d of layer %d is null", i, l);
+    }
+  st->mem = mem;
+  st->d_mem = d_mem;
+  if (dw_cross != nullptr) st->dw_cross.assign(dw_cross, dw_cross + c.L); else st->dw_cross.clear();
+  return DP_OK;
+}
+
 dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const uint8_t *plan, size_t plan_len,
                         uint64_t budget_bytes, void *y_out, void *dx_out, const dp_layer_grads *dw, void *hip_stream,
                         dp_step_stats *stats) {
@@ -1181,6 +1420,10 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     void *const *p = reinterpret_cast<void *const *>(&dw[l]);
     for (int i = 0; i < 12; ++i)
       if (p[i] == nullptr) return fail(DP_E_INVAL, "gradient pointer %d of layer %d is null", i, l);
+  }
+  if (c.cross) {
+    const dp_status xs = cross_ready(st, true);
+    if (xs != DP_OK) return xs;
   }
   dp_plan_report rep;
   const bool fuse_gelu = ((st->debug & 4u) != 0) != kFuseGeluDefault;   // debug bit 2 flips the default
@@ -1223,6 +1466,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   w.d2h = serial ? cs : st->d2h;
   w.h2d = serial ? cs : st->h2d;
   w.x_in = x_in; w.dy = dy; w.y_out = y_out; w.dx_out = dx_out; w.dw = dw;
+  w.mem = st->mem; w.d_mem = st->d_mem; w.dwx = st->dw_cross.data();
   hipEvent_t t0 = nullptr, t1 = nullptr, t2 = nullptr;
   if (stats) {
     HIP_TRY(hipEventCreate(&t0), DP_E_HIP); HIP_TRY(hipEventCreate(&t1), DP_E_HIP); HIP_TRY(hipEventCreate(&t2), DP_E_HIP);
@@ -1268,6 +1512,10 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   if (inflight < 1 || inflight > kMaxInflight) return fail(DP_E_INVAL, "inflight must be 1..%u", kMaxInflight);
   if (slot >= inflight) return fail(DP_E_INVAL, "slot %u is not below inflight %u", slot, inflight);
   const Cfg &c = st->c;
+  if (c.cross) {
+    const dp_status xs = cross_ready(st, false);
+    if (xs != DP_OK) return xs;
+  }
   if (st->flights.size() <= slot) st->flights.resize((size_t)slot + 1);
   if (!st->flights[slot]) st->flights[slot].reset(new Flight);
   Flight &f = *st->flights[slot];
@@ -1315,6 +1563,7 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   w->d2h = serial ? w->cs : st->d2h;
   w->h2d = serial ? w->cs : st->h2d;
   w->x_in = x_in; w->y_out = y_out;
+  w->mem = st->mem;
   w->forward();
   if (w->herr != hipSuccess) {
     const hipError_t e = w->herr;
@@ -1340,6 +1589,10 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
     for (int i = 0; i < 12; ++i)
       if (p[i] == nullptr) return fail(DP_E_INVAL, "gradient pointer %d of layer %d is null", i, l);
   }
+  if (c.cross) {
+    const dp_status xs = cross_ready(st, true);
+    if (xs != DP_OK) return xs;
+  }
   Flight &f = *st->flights[slot];
   std::unique_ptr<Walk> w(f.walk);
   f.walk = nullptr;                       // the slot is free again whatever happens below
@@ -1355,6 +1608,7 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
   }
   w->cs = cs;
   w->dy = dy; w->dx_out = dx_out; w->dw = dw;
+  w->d_mem = st->d_mem; w->dwx = st->dw_cross.data();   // (the memory itself is the one its forward saw)
   w->accumulate = (flags & DP_GRAD_ACCUMULATE) != 0;
   w->backward();
   if (!serial) {
@@ -1429,6 +1683,7 @@ dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void
   if (st == nullptr || out == nullptr) return fail(DP_E_INVAL, "null argument");
   if (steps < 1) return fail(DP_E_INVAL, "steps must be >= 1");
   const Cfg &c = st->c;
+  if (c.cross) return fail(DP_E_UNSUPPORTED, "the cost model does not cover stages with a cross-attention block");
   memset(out, 0, sizeof *out);
   // node times: keep-all steps with every launch bracketed, averaged over layers and steps
   std::vector<uint8_t> plan((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
@@ -1537,6 +1792,7 @@ void dp_stage_destroy(dp_stage *st) {
   if (st->h2d) (void)hipStreamDestroy(st->h2d);
   if (st->arena) (void)hipFree(st->arena);
   if (st->host_pool) (void)hipHostFree(st->host_pool);
+  if (st->cross_slab) (void)hipFree(st->cross_slab);
   for (auto &f : st->flights) {
     if (!f) continue;
     delete f->walk;

@@ -26,16 +26,26 @@ struct Cfg {
   size_t esz;
   float p_attn, p_hidden;          // dropout rates
   bool drop_attn, drop_hidden;     // rate > 0
+  int Sm = 0;                      // length of the encoder memory; 0: no cross-attention block
+  long Tm = 0;                     // micro_batch * Sm
+  bool cross = false;
+  int nslots = DP_SLOTS_PER_LAYER; // slots (and plan bytes) per layer
 };
 
 dp_status parse_cfg(const dp_stage_config *c, Cfg *o);
 
 // ------------------------------------------------------------------ op tables
-enum Op { OP_LN1, OP_QKV, OP_ATTN, OP_PROJ, OP_LN2, OP_FC1, OP_GELU, OP_FC2, N_OPS };
+// N_OPS: nodes of a plain layer (the cost model's node arrays have that many entries); the five
+// that follow are the cross-attention block of a decoder layer.
+enum Op { OP_LN1, OP_QKV, OP_ATTN, OP_PROJ, OP_LN2, OP_FC1, OP_GELU, OP_FC2, N_OPS,
+          OP_LNC = N_OPS, OP_QC, OP_KVC, OP_ATTNC, OP_PROJC, N_OPS_CROSS };
+constexpr int kMaxSlots = DP_SLOTS_PER_LAYER_CROSS;
 // A slot reference relative to a layer: dl = 1 means "X_IN of the next layer".
 struct Ref { int dl, slot; };
 struct OpDef { Op op; int n_in; Ref in[2]; int n_out; Ref out[2]; };
-extern const OpDef kPreOps[N_OPS], kPostOps[N_OPS];
+extern const OpDef kPreOps[N_OPS], kPostOps[N_OPS], kPreCrossOps[N_OPS_CROSS];
+inline const OpDef *op_table(const Cfg &c) { return c.cross ? kPreCrossOps : c.pre ? kPreOps : kPostOps; }
+inline int op_count(const Cfg &c) { return c.cross ? (int)N_OPS_CROSS : (int)N_OPS; }
 size_t slot_bytes(const Cfg &c, int slot);
 
 // Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  The epilogue

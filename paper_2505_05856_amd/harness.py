@@ -14,7 +14,8 @@ from . import binding as B
 def to_binding_config(cfg) -> B.StageConfig:
     """`cfg` is a synthetic.StageConfig (duck-typed)."""
     return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
-                         cfg.norm_style, cfg.causal, cfg.gelu, cfg.dtype, cfg.ln_eps, cfg.p_attn, cfg.p_hidden)
+                         cfg.norm_style, cfg.causal, cfg.gelu, cfg.dtype, cfg.ln_eps, cfg.p_attn, cfg.p_hidden,
+                         getattr(cfg, "mem_seq", 0))
 
 
 def torch_dtype(cfg):
@@ -33,7 +34,7 @@ class StageRunner:
     """Holds a stage handle plus its device inputs/outputs."""
 
     def __init__(self, cfg, weights: List[Dict[str, np.ndarray]], x: np.ndarray, dy: np.ndarray,
-                 device="cuda:0", arena_bytes_hint: int = 0):
+                 device="cuda:0", arena_bytes_hint: int = 0, mem: np.ndarray = None):
         self.cfg, self.device = cfg, device
         self.bcfg = to_binding_config(cfg)
         self.w = [{k: upload(v, cfg, device) for k, v in layer.items()} for layer in weights]
@@ -41,11 +42,18 @@ class StageRunner:
         self.y = torch.empty_like(self.x)
         self.dx = torch.empty_like(self.x)
         self.g = [{k: torch.empty_like(v) for k, v in layer.items()} for layer in self.w]
+        self.mem = self.d_mem = None
         torch.cuda.synchronize()
         self.stage = B.stage_init(self.bcfg, self.w, arena_bytes_hint)
+        if getattr(cfg, "mem_seq", 0) > 0:   # decoder stage: the block's parameters and the encoder memory
+            self.mem = upload(mem, cfg, device)
+            self.d_mem = torch.empty_like(self.mem)
+            B.stage_set_cross(self.stage, self.w)
+            B.stage_bind_memory(self.stage, self.mem, self.d_mem, self.g)
 
     def poison_outputs(self):
-        for t in [self.y, self.dx] + [v for layer in self.g for v in layer.values()]:
+        for t in [self.y, self.dx] + [v for layer in self.g for v in layer.values()] + \
+                ([self.d_mem] if self.d_mem is not None else []):
             t.fill_(float("nan"))
 
     def step(self, plan, budget_bytes: int = 0, want_stats: bool = False, stream=None):
@@ -60,6 +68,8 @@ class StageRunner:
         """Bit patterns of every output, for bit-exactness checks."""
         torch.cuda.synchronize()
         outs = [self.y, self.dx] + [layer[k] for layer in self.g for k in B.WEIGHT_FIELDS]
+        if self.d_mem is not None:
+            outs += [self.d_mem] + [layer[k] for layer in self.g for k, _ in B.CROSS_FIELDS]
         return [t.detach().clone().view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu() for t in outs]
 
     def close(self):

@@ -28,12 +28,15 @@ SLOT_NAMES = (
     "RES1", "LN2_STATS", "LN2_OUT", "FC1_OUT", "GELU_OUT", "RES2",
 )
 SLOTS_PER_LAYER = len(SLOT_NAMES)
-SLOT = {n: i for i, n in enumerate(SLOT_NAMES)}
+# a decoder stage (mem_seq > 0) has seven more saved tensors a layer, after those above
+CROSS_SLOT_NAMES = ("LNC_STATS", "LNC_OUT", "Q_C", "KV_C", "ATTN_C_LSE", "ATTN_C_OUT", "RES_C")
+SLOT = {n: i for i, n in enumerate(SLOT_NAMES + CROSS_SLOT_NAMES)}
 
 WEIGHT_NAMES = (
     "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
     "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2",
 )
+CROSS_WEIGHT_NAMES = ("lnc_g", "lnc_b", "w_qc", "b_qc", "w_kvc", "b_kvc", "w_oc", "b_oc")
 
 
 @dataclass(frozen=True)
@@ -51,6 +54,15 @@ class StageConfig:
     ln_eps: float = 1e-5
     p_attn: float = 0.0        # dropout rate on the attention probabilities
     p_hidden: float = 0.0      # dropout rate after the attention projection and after FC2
+    mem_seq: int = 0           # > 0: decoder stage, cross-attention over an encoder memory of this length
+
+    @property
+    def slots_per_layer(self) -> int:
+        return SLOTS_PER_LAYER + (len(CROSS_SLOT_NAMES) if self.mem_seq > 0 else 0)
+
+    @property
+    def mem_tokens(self) -> int:
+        return self.micro_batch * self.mem_seq
 
     @property
     def tokens(self) -> int:
@@ -71,6 +83,8 @@ class StageConfig:
             "ln1_g": (H,), "ln1_b": (H,), "w_qkv": (H, 3 * H), "b_qkv": (3 * H,),
             "w_o": (H, H), "b_o": (H,), "ln2_g": (H,), "ln2_b": (H,),
             "w_fc1": (H, F), "b_fc1": (F,), "w_fc2": (F, H), "b_fc2": (H,),
+            "lnc_g": (H,), "lnc_b": (H,), "w_qc": (H, H), "b_qc": (H,),
+            "w_kvc": (H, 2 * H), "b_kvc": (2 * H,), "w_oc": (H, H), "b_oc": (H,),
         }
 
     def model_flops(self) -> float:
@@ -78,7 +92,10 @@ class StageConfig:
         lower triangle of a causal attention counts; replay not counted)."""
         T, H, F, S = self.tokens, self.hidden, self.ffn, self.seq
         attn = (2 if self.causal else 4) * T * S * H
-        return 3.0 * self.n_layers * (8 * T * H * H + 4 * T * H * F + attn)
+        cross = 0
+        if self.mem_seq > 0:   # query and output projections, key/value projection of the memory, the attention
+            cross = 4 * T * H * H + 4 * self.mem_tokens * H * H + 4 * T * self.mem_seq * H
+        return 3.0 * self.n_layers * (8 * T * H * H + 4 * T * H * F + attn + cross)
 
 
 CONFIGS: Dict[str, StageConfig] = {
@@ -92,6 +109,9 @@ CONFIGS: Dict[str, StageConfig] = {
     "C4": StageConfig(8, 1600, 25, 6400, 1024, 32, "pre", True, "erf", "bf16"),
     # wide decoder stage (64 GB budget)
     "C5": StageConfig(4, 4096, 32, 11008, 2048, 8, "pre", True, "erf", "bf16"),
+    # decoder stage of a T5-Large-sized encoder-decoder model (24 decoder layers over 4 stages),
+    # cross-attention over an encoder memory as long as the decoder sequence
+    "T5": StageConfig(6, 1024, 16, 4096, 512, 8, "pre", True, "erf", "bf16", mem_seq=512),
 }
 BUDGETS = {"C4": 40 * 10**9, "C5": 64 * 10**9}
 
@@ -151,12 +171,12 @@ def make_weights(cfg: StageConfig, seed: int = 0, sigma: float = 0.02) -> List[D
     shapes = cfg.weight_shapes()
     for _ in range(cfg.n_layers):
         w = {}
-        for name in WEIGHT_NAMES:
+        for name in WEIGHT_NAMES + (CROSS_WEIGHT_NAMES if cfg.mem_seq > 0 else ()):
             shp = shapes[name]
             n = int(np.prod(shp))
             v = sigma * normal(seed, off, n).reshape(shp)
             off += n
-            if name in ("ln1_g", "ln2_g"):
+            if name in ("ln1_g", "ln2_g", "lnc_g"):
                 v = 1.0 + v
             w[name] = _store(cfg, v)
         layers.append(w)
@@ -169,6 +189,12 @@ def make_activations(cfg: StageConfig, seed_x: int = 1, seed_dy: int = 2):
     x = normal(seed_x, 0, n).reshape(cfg.tokens, cfg.hidden)
     dy = normal(seed_dy, 0, n).reshape(cfg.tokens, cfg.hidden)
     return _store(cfg, x), _store(cfg, dy)
+
+
+def make_memory(cfg: StageConfig, seed: int = 3) -> np.ndarray:
+    """Encoder memory of a decoder stage, [micro_batch * mem_seq, H] ~ N(0, 1)."""
+    n = cfg.mem_tokens * cfg.hidden
+    return _store(cfg, normal(seed, 0, n).reshape(cfg.mem_tokens, cfg.hidden))
 
 
 def sharpen_attention(cfg: StageConfig, weights, logit_std: float = 4.0):
@@ -194,13 +220,13 @@ def sharpen_attention(cfg: StageConfig, weights, logit_std: float = 4.0):
 # plans
 # ----------------------------------------------------------------------------
 def plan_len(cfg: StageConfig) -> int:
-    return cfg.n_layers * SLOTS_PER_LAYER
+    return cfg.n_layers * cfg.slots_per_layer
 
 
 def repair_plan(cfg: StageConfig, plan: np.ndarray) -> np.ndarray:
     """Alias slots and the stage input have no producer/storage inside the
     stage: force them to KEEP."""
-    p = plan.reshape(cfg.n_layers, SLOTS_PER_LAYER).copy()
+    p = plan.reshape(cfg.n_layers, cfg.slots_per_layer).copy()
     for s in cfg.alias_slots():
         p[:, s] = KEEP
     p[0, SLOT["X_IN"]] = KEEP
@@ -208,7 +234,7 @@ def repair_plan(cfg: StageConfig, plan: np.ndarray) -> np.ndarray:
 
 
 def plan_uniform(cfg: StageConfig, action: int, keep_layer_inputs: bool = False) -> np.ndarray:
-    p = np.full((cfg.n_layers, SLOTS_PER_LAYER), action, dtype=np.uint8)
+    p = np.full((cfg.n_layers, cfg.slots_per_layer), action, dtype=np.uint8)
     if keep_layer_inputs:
         p[:, SLOT["X_IN"]] = KEEP
     return repair_plan(cfg, p.reshape(-1))
@@ -229,7 +255,7 @@ def plan_all_swap(cfg):
 
 
 def plan_from_slots(cfg, actions: Dict[str, int]) -> np.ndarray:
-    p = np.zeros((cfg.n_layers, SLOTS_PER_LAYER), dtype=np.uint8)
+    p = np.zeros((cfg.n_layers, cfg.slots_per_layer), dtype=np.uint8)
     for name, a in actions.items():
         p[:, SLOT[name]] = a
     return repair_plan(cfg, p.reshape(-1))
@@ -258,6 +284,7 @@ PLANS = {
     "C3": [("recompute-attention", plan_recompute_attention)],
     "C4": [("swap-fc1-recompute-ln-gelu", plan_swap_ffn_recompute_norm_gelu)],
     "C5": [("seed7-mixed", lambda c: plan_seeded(c, 7))],
+    "T5": [("keep-all", plan_keep_all)],
 }
 
 

@@ -1,0 +1,145 @@
+"""A decoder stage with a cross-attention block on the device against the CPU oracle, through
+the C ABI: outputs, dX, dMem and every parameter gradient within 1e-4 (fp32) / 2e-2 (bf16) of
+max|ref|; every plan (keep, recompute, swap, seeded mixes over all nineteen slots) leaves every
+bit unchanged and lives in the memory the validator predicted; the step cut into forward and
+backward with two micro-batches in flight and their own memories."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic as syn
+from oracle import decoder as Dc
+from oracle import stage as O
+from paper_2505_05856_amd import binding as B
+from paper_2505_05856_amd.harness import StageRunner, upload, download
+
+pytestmark = pytest.mark.gpu
+BOUND = {"f32": 1e-4, "bf16": 2e-2}
+NAMES = syn.WEIGHT_NAMES + syn.CROSS_WEIGHT_NAMES
+
+
+def dec(L, H, nh, F, S, Sm, Bn, dtype, causal=True, gelu="erf"):
+    return syn.StageConfig(L, H, nh, F, S, Bn, "pre", causal, gelu, dtype, mem_seq=Sm)
+
+
+def oracle_step(cfg, w, x, mem, dy):
+    st = Dc.DecoderStage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
+                         cfg.causal, cfg.gelu, cfg.ln_eps)
+    return Dc.decoder_step(st, w, x, mem, dy)
+
+
+def compare(cfg, run, ref, bound=None):
+    bound = bound or BOUND[cfg.dtype]
+    y, dx, g = run.results()
+    yr, dxr, dmr, gr = ref
+    worst = {"Y": O.max_rel_err(y, yr), "dX": O.max_rel_err(dx, dxr), "dMem": O.max_rel_err(download(run.d_mem), dmr)}
+    for l in range(cfg.n_layers):
+        for n in NAMES:
+            worst[f"L{l}.{n}"] = O.max_rel_err(g[l][n], gr[l][n])
+    bad = {k: v for k, v in worst.items() if not (v <= bound)}
+    print("largest errors:", ", ".join(f"{k}={v:.2e}" for k, v in sorted(worst.items(), key=lambda kv: -kv[1])[:4]))
+    assert not bad, f"over {bound}: {bad}"
+
+
+SMALL = [
+    dec(2, 64, 2, 128, 40, 24, 3, "f32"),
+    dec(2, 64, 1, 128, 9, 70, 2, "f32", causal=False, gelu="tanh"),
+    dec(3, 128, 2, 256, 96, 130, 2, "bf16"),
+    dec(2, 256, 2, 520, 130, 77, 2, "bf16", gelu="tanh"),      # head dimension 128, ragged extents
+    dec(2, 192, 3, 384, 200, 1, 1, "bf16", causal=False),       # a memory of one position
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.dtype}-H{c.hidden}-S{c.seq}-M{c.mem_seq}")
+def test_every_plan_same_bits_and_the_oracles_numbers(cfg):
+    w = syn.make_weights(cfg, sigma=0.05)
+    x, dy = syn.make_activations(cfg)
+    mem = syn.make_memory(cfg)
+    ref = oracle_step(cfg, w, x, mem, dy)
+    run = StageRunner(cfg, w, x, dy, mem=mem)
+    B.stage_set_debug(run.stage, 2)      # poison released arena blocks
+    kvc = syn.plan_from_slots(cfg, {"KV_C": syn.RECOMPUTE, "Q_C": syn.SWAP, "ATTN_C_OUT": syn.RECOMPUTE,
+                                    "ATTN_C_LSE": syn.RECOMPUTE, "RES_C": syn.SWAP, "RES1": syn.RECOMPUTE})
+    plans = [("keep", syn.plan_keep_all(cfg)), ("recompute", syn.plan_all_recompute(cfg)),
+             ("recompute-all", syn.plan_uniform(cfg, syn.RECOMPUTE)), ("swap", syn.plan_all_swap(cfg)), ("cross", kvc)]
+    plans += [(f"seed{s}", syn.plan_seeded(cfg, s)) for s in range(10)]
+    first = None
+    for name, p in plans:
+        assert len(p) == cfg.n_layers * B.SLOTS_PER_LAYER_CROSS
+        run.poison_outputs()
+        stats = run.step(p, want_stats=True)
+        _, rep = B.plan_validate(run.bcfg, p)
+        assert stats["arena_high_water"] == rep["arena_peak_bytes"], name
+        assert stats["d2h_bytes"] == rep["swap_out_bytes"] and stats["h2d_bytes"] == rep["swap_in_bytes"]
+        bits = run.raw_results()
+        if first is None:
+            compare(cfg, run, ref)
+            first = bits
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, bits)), f"plan {name} changed the bits"
+    # within the validated memory: a budget equal to the predicted peak runs, one below it is refused
+    _, rep = B.plan_validate(run.bcfg, plans[1][1])
+    run.step(plans[1][1], budget_bytes=rep["peak_bytes"])
+    with pytest.raises(B.DpError) as e:
+        run.step(plans[0][1], budget_bytes=rep["peak_bytes"] - 1)
+    assert e.value.status == "DP_E_BUDGET"
+    run.close()
+
+
+def test_forward_and_backward_apart_with_two_memories_in_flight():
+    cfg = dec(2, 128, 2, 256, 64, 48, 2, "bf16")
+    w = syn.make_weights(cfg, sigma=0.05)
+    xs, dys, mems = [], [], []
+    for m in range(2):
+        x, dy = syn.make_activations(cfg, seed_x=10 + m, seed_dy=20 + m)
+        xs.append(x); dys.append(dy); mems.append(syn.make_memory(cfg, seed=30 + m))
+    run = StageRunner(cfg, w, xs[0], dys[0], mem=mems[0])
+    plan = syn.plan_seeded(cfg, 4)
+    # reference bits: whole steps, one micro-batch after the other
+    want = []
+    for m in range(2):
+        run.x.copy_(upload(xs[m], cfg)); run.dy.copy_(upload(dys[m], cfg)); run.mem.copy_(upload(mems[m], cfg))
+        run.poison_outputs()
+        run.step(plan)
+        want.append([t.clone() for t in run.raw_results()])
+        compare(cfg, run, oracle_step(cfg, w, xs[m], mems[m], dys[m]))
+    # two in flight: F0 F1 B0 B1, each with its own memory tensor
+    tx = [upload(a, cfg) for a in xs]; tdy = [upload(a, cfg) for a in dys]; tm = [upload(a, cfg) for a in mems]
+    ty = [torch.empty_like(t) for t in tx]
+    for m in range(2):
+        B.stage_bind_memory(run.stage, tm[m], run.d_mem, run.g)
+        B.stage_forward(run.stage, m, 2, tx[m], plan, 0, ty[m])
+    for m in range(2):
+        run.poison_outputs()
+        B.stage_backward(run.stage, m, tdy[m], run.dx, run.g, 0)
+        run.y.copy_(ty[m])
+        got = run.raw_results()
+        assert all(torch.equal(a, b) for a, b in zip(want[m], got)), f"micro-batch {m}"
+    run.close()
+
+
+def test_refusals():
+    cfg = dec(1, 64, 1, 128, 16, 8, 1, "f32")
+    bc = B.make_config(1, 64, 1, 128, 16, 1, "pre", True, "erf", "f32", mem_seq=8)
+    w = syn.make_weights(cfg)
+    x, dy = syn.make_activations(cfg)
+    run = StageRunner(syn.small_like(cfg, mem_seq=0), w, x, dy)      # a plain stage: no cross entry points
+    with pytest.raises(B.DpError):
+        B.stage_set_cross(run.stage, run.w)
+    run.close()
+    tw = [{k: upload(v, cfg) for k, v in layer.items()} for layer in w]
+    st = B.stage_init(bc, tw, 0)
+    tx = upload(x, cfg); ty = torch.empty_like(tx)
+    g = [{k: torch.empty_like(v) for k, v in layer.items()} for layer in tw]
+    with pytest.raises(B.DpError):      # no parameters for the block yet
+        B.stage_step(st, tx, tx, syn.plan_keep_all(cfg), 0, ty, ty, g)
+    B.stage_set_cross(st, tw)
+    with pytest.raises(B.DpError):      # no memory bound yet
+        B.stage_step(st, tx, tx, syn.plan_keep_all(cfg), 0, ty, ty, g)
+    B.stage_bind_memory(st, upload(syn.make_memory(cfg), cfg))
+    with pytest.raises(B.DpError):      # forward alone would do; the step needs d_mem and the gradients
+        B.stage_step(st, tx, tx, syn.plan_keep_all(cfg), 0, ty, ty, g)
+    B.stage_forward(st, 0, 1, tx, syn.plan_keep_all(cfg), 0, ty)
+    with pytest.raises(B.DpError):      # the plan of a plain stage is too short
+        B.stage_forward(st, 0, 1, tx, np.zeros(B.SLOTS_PER_LAYER, dtype=np.uint8), 0, ty)
+    st.close()

@@ -167,3 +167,45 @@ def test_full_size_configs_fit_their_budgets():
             code, rep = B.plan_validate(bc, mk(cfg), budget_bytes=syn.BUDGETS.get(name, 0))
             assert code == 0, (name, pname, B.last_error())
             assert rep["peak_bytes"] < 288 * 10**9
+
+
+# ---------------------------------------------------------------- decoder stages (cross-attention block)
+def _dec(**kw):
+    base = dict(n_layers=2, hidden=128, n_heads=2, ffn=256, seq=64, micro_batch=2, norm_style="pre", causal=True,
+                dtype="bf16", mem_seq=40)
+    base.update(kw)
+    return syn.StageConfig(**base)
+
+
+def test_decoder_stage_plans_and_memory():
+    cfg = _dec()
+    bc = to_binding_config(cfg)
+    assert B.plan_len(bc) == cfg.n_layers * B.SLOTS_PER_LAYER_CROSS == syn.plan_len(cfg)
+    _, keep = B.plan_validate(bc, syn.plan_keep_all(cfg))
+    _, rec = B.plan_validate(bc, syn.plan_all_recompute(cfg))
+    assert keep["step_flops"] == cfg.model_flops() and keep["n_replayed_ops"] == 0
+    assert rec["arena_peak_bytes"] < keep["arena_peak_bytes"] and rec["n_replayed_ops"] == 12 * cfg.n_layers
+    # what keep-all holds: the plain layer's saved tensors plus the block's seven
+    T, Tm, H, e = cfg.tokens, cfg.mem_tokens, cfg.hidden, 2
+    block = 4 * T * H * e + Tm * 2 * H * e + T * 2 * 4 + cfg.micro_batch * cfg.n_heads * cfg.seq * 4
+    _, plain = B.plan_validate(to_binding_config(syn.small_like(cfg, mem_seq=0)), syn.plan_keep_all(syn.small_like(cfg, mem_seq=0)))
+    assert keep["kept_act_bytes"] == plain["kept_act_bytes"] + cfg.n_layers * block
+    # recomputing KV_C alone costs one projection of the memory a layer and frees its bytes
+    _, kv = B.plan_validate(bc, syn.plan_from_slots(cfg, {"KV_C": syn.RECOMPUTE}))
+    assert kv["n_replayed_ops"] == cfg.n_layers and kv["replay_flops"] == cfg.n_layers * 2.0 * Tm * H * 2 * H
+    assert kv["kept_act_bytes"] == keep["kept_act_bytes"] - cfg.n_layers * Tm * 2 * H * e
+    # the encoder memory and its gradient count as fixed memory
+    assert keep["fixed_bytes"] - plain["fixed_bytes"] >= 2 * Tm * H * e
+
+
+def test_decoder_stage_refusals():
+    for bad in (_dec(norm_style="post"), _dec(p_attn=0.1), _dec(p_hidden=0.1), _dec(mem_seq=-1)):
+        with pytest.raises(B.DpError):
+            B.plan_validate(to_binding_config(bad), syn.plan_keep_all(_dec()))
+    cfg = _dec()
+    with pytest.raises(B.DpError):      # a plain stage's plan length
+        B.plan_validate(to_binding_config(cfg), np.zeros(cfg.n_layers * B.SLOTS_PER_LAYER, dtype=np.uint8))
+    cm = B.make_cost_model([1000] * 8, [2000] * 8, 50_000, 50_000)
+    with pytest.raises(B.DpError) as e:
+        B.plan_generate(to_binding_config(cfg), cm, 0, 1)
+    assert e.value.status == "DP_E_UNSUPPORTED"
