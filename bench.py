@@ -31,10 +31,12 @@ def gemm_flops(cfg):
     """Algorithmic FLOP per step of the three GEMM classes (2*M*N*K each)."""
     T, H, F, L = cfg.tokens, cfg.hidden, cfg.ffn, cfg.n_layers
     per_layer = 2.0 * T * (3 * H * H + H * H + 2 * H * F)
+    if cfg.mem_seq > 0:   # the cross-attention block: query and output projections, key/value projection of the memory
+        per_layer += 2.0 * (2 * T * H * H + cfg.mem_tokens * 2 * H * H)
     return {"gemm_fwd": L * per_layer, "gemm_dgrad": L * per_layer, "gemm_wgrad": L * per_layer}
 
 
-def cpu_baseline(cfg, weights, x, dy, budget_s=30.0):
+def cpu_baseline(cfg, weights, x, dy, budget_s=30.0, mem=None):
     """Oracle as it stands, on a bounded sample: the first layer of the stage on the
     full micro-batch; if the whole stage fits the time budget it is then run whole,
     otherwise the one-layer time is scaled by n_layers (every layer costs the same)."""
@@ -42,6 +44,13 @@ def cpu_baseline(cfg, weights, x, dy, budget_s=30.0):
     from oracle import stage as O
 
     def run(n_layers):
+        if cfg.mem_seq > 0:
+            from oracle import decoder as Dc
+            st = Dc.DecoderStage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
+                                 cfg.causal, cfg.gelu, cfg.ln_eps)
+            t0 = time.perf_counter()
+            Dc.decoder_step(st, weights[:n_layers], x, mem, dy, dtype=np.float64)
+            return time.perf_counter() - t0
         st = O.Stage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
                      cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden)
         t0 = time.perf_counter()
@@ -191,7 +200,11 @@ def main():
     budget = syn.BUDGETS.get(args.config, 0)
     weights = syn.make_weights(cfg)
     x, dy = syn.make_activations(cfg)
-    run = StageRunner(cfg, weights, x, dy)
+    mem = syn.make_memory(cfg) if cfg.mem_seq > 0 else None
+    if cfg.mem_seq > 0 and (plan_name == "memopt" or args.partition > 0 or args.dropout > 0):
+        print("bench.py: the planners and dropout do not take stages with a cross-attention block", file=sys.stderr)
+        sys.exit(2)
+    run = StageRunner(cfg, weights, x, dy, mem=mem)
     memopt = None
     if plan_name == "memopt":
         # the plan generator in front of the path: cost model measured here, plan for the budget, prediction
@@ -318,6 +331,7 @@ def main():
         "config": {"workload": f"{args.config}: {cfg.n_layers} {cfg.norm_style}-LN layers, hidden {cfg.hidden}, "
                                f"{cfg.n_heads} heads, ffn {cfg.ffn}, seq {cfg.seq}, micro-batch {cfg.micro_batch}, "
                                f"{'causal' if cfg.causal else 'full'} attention"
+                               + (f", cross-attention over a memory of {cfg.mem_seq}" if cfg.mem_seq > 0 else "")
                                + (f", dropout {cfg.p_attn}" if cfg.p_attn > 0 else ""),
                    "plan": plan_name, "budget_bytes": budget, "validator_peak_bytes": rep["peak_bytes"],
                    "arena_peak_bytes": rep["arena_peak_bytes"],
@@ -344,7 +358,7 @@ def main():
         out["memopt"] = memopt
     run.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, weights, x, dy)
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, x, dy, mem=mem)
     print(json.dumps(out))
 
 

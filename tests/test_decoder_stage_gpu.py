@@ -143,3 +143,26 @@ def test_refusals():
     with pytest.raises(B.DpError):      # the plan of a plain stage is too short
         B.stage_forward(st, 0, 1, tx, np.zeros(B.SLOTS_PER_LAYER, dtype=np.uint8), 0, ty)
     st.close()
+
+
+def test_t5_full_size_parity_and_plans():
+    """The workload bench.py --config T5 times, whole: parity with the oracle (in fp32: ~1e-6, far inside the
+    bound) under keep-all, then the same bits under recompute, swap and a seeded mix."""
+    cfg = syn.CONFIGS["T5"]
+    w = syn.make_weights(cfg)
+    x, dy = syn.make_activations(cfg)
+    mem = syn.make_memory(cfg)
+    run = StageRunner(cfg, w, x, dy, mem=mem)
+    run.poison_outputs()
+    stats = run.step(syn.plan_keep_all(cfg), want_stats=True)
+    keep_bits = run.raw_results()
+    st = Dc.DecoderStage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
+                         cfg.causal, cfg.gelu, cfg.ln_eps)
+    compare(cfg, run, Dc.decoder_step(st, w, x, mem, dy, dtype=np.float32))
+    for p in (syn.plan_all_recompute(cfg), syn.plan_all_swap(cfg), syn.plan_seeded(cfg, 7)):
+        _, rep = B.plan_validate(run.bcfg, p)
+        run.poison_outputs()
+        stats = run.step(p, budget_bytes=rep["peak_bytes"], want_stats=True)
+        assert stats["arena_high_water"] == rep["arena_peak_bytes"]
+        assert all(torch.equal(a, b) for a, b in zip(keep_bits, run.raw_results()))
+    run.close()
