@@ -116,8 +116,8 @@ enum {
  * and the step also returns dMem, the sum over layers of the gradient reaching mem.  Such a
  * stage needs norm_style DP_PRE_LN and both dropout rates 0 (DP_E_UNSUPPORTED otherwise), its
  * block's parameters from dp_stage_set_cross and its memory buffers from
- * dp_stage_bind_memory; the plan generator, the cost model and the partitioner do not take it
- * yet (DP_E_UNSUPPORTED). */
+ * dp_stage_bind_memory.  The validator, the plan generator, the cost model and the
+ * partitioner (a chain of such layers, all reading the same memory) take it like any stage. */
 typedef struct {
   int32_t n_layers, hidden, n_heads, ffn, seq, micro_batch;
   int32_t norm_style; /* dp_norm_style */
@@ -208,7 +208,14 @@ dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size
  *   pre-LN  LN1, QKV, ATTN, PROJ, LN2, FC1, GELU, FC2     post-LN  QKV, ATTN, PROJ, LN1, FC1, GELU, FC2, LN2
  * backward (execution order):
  *   pre-LN  FC2, GELU, FC1, LN2, PROJ, ATTN, QKV, LN1     post-LN  LN2, FC2, GELU, FC1, LN1, PROJ, ATTN, QKV
- * A backward node's time covers all its kernels (input and weight gradients, reductions). */
+ * A backward node's time covers all its kernels (input and weight gradients, reductions).
+ * A decoder layer (mem_seq > 0) has thirteen nodes; forward:
+ *   LN1, QKV, ATTN, PROJ, LNC, QC, KVC, ATTNC, PROJC, LN2, FC1, GELU, FC2
+ * backward:
+ *   FC2, GELU, FC1, LN2, PROJC, ATTNC, KVC, QC, LNC, PROJ, ATTN, QKV, LN1
+ * (LNC, QC, KVC, ATTNC, PROJC: the cross-attention block's LayerNorm, query projection,
+ * key/value projection of the memory, attention and output projection); nodes 0..7 of these
+ * orders are fwd_ns / bwd_ns, nodes 8..12 are fwd_more_ns / bwd_more_ns. */
 typedef struct {
   int64_t fwd_ns[8], bwd_ns[8];                /* nanoseconds per node */
   uint64_t d2h_bytes_per_us, h2d_bytes_per_us; /* host link speed each way, one direction busy */
@@ -217,6 +224,7 @@ typedef struct {
    * the steady state of a one-forward-one-backward schedule the copy-outs of one micro-batch
    * and the copy-ins of another run side by side all the time. */
   uint64_t d2h_duplex_bytes_per_us, h2d_duplex_bytes_per_us;
+  int64_t fwd_more_ns[5], bwd_more_ns[5];      /* decoder layers only: nodes 8..12 (else ignored) */
 } dp_cost_model;
 
 typedef struct {

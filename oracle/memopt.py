@@ -55,7 +55,10 @@ from typing import Dict, List, Optional, Sequence, Tuple
 KEEP, RECOMPUTE, SWAP = 0, 1, 2
 SLOTS = ("X_IN", "LN1_STATS", "LN1_OUT", "QKV", "ATTN_LSE", "ATTN_OUT",
          "RES1", "LN2_STATS", "LN2_OUT", "FC1_OUT", "GELU_OUT", "RES2")
-SLOT = {n: i for i, n in enumerate(SLOTS)}
+# a decoder layer (style "dec": the pre-LN layer with a cross-attention block over an encoder
+# memory between its attention and its feed-forward block) saves seven more tensors
+CROSS_SLOTS = ("LNC_STATS", "LNC_OUT", "Q_C", "KV_C", "ATTN_C_LSE", "ATTN_C_OUT", "RES_C")
+SLOT = {n: i for i, n in enumerate(SLOTS + CROSS_SLOTS)}
 N_SLOTS = len(SLOTS)
 
 # Forward nodes of one layer in execution order: (name, inputs, outputs); "NEXT" is the
@@ -77,6 +80,20 @@ _FWD = {
              ("GELU", ["FC1_OUT"], ["GELU_OUT"]),
              ("FC2", ["GELU_OUT", "LN1_OUT"], ["RES2"]),
              ("LN2", ["RES2"], ["NEXT", "LN2_STATS"])],
+    # the key/value projection reads the encoder memory, which is not a saved tensor
+    "dec": [("LN1", ["X_IN"], ["LN1_OUT", "LN1_STATS"]),
+            ("QKV", ["LN1_OUT"], ["QKV"]),
+            ("ATTN", ["QKV"], ["ATTN_OUT", "ATTN_LSE"]),
+            ("PROJ", ["ATTN_OUT", "X_IN"], ["RES1"]),
+            ("LNC", ["RES1"], ["LNC_OUT", "LNC_STATS"]),
+            ("QC", ["LNC_OUT"], ["Q_C"]),
+            ("KVC", [], ["KV_C"]),
+            ("ATTNC", ["Q_C", "KV_C"], ["ATTN_C_OUT", "ATTN_C_LSE"]),
+            ("PROJC", ["ATTN_C_OUT", "RES1"], ["RES_C"]),
+            ("LN2", ["RES_C"], ["LN2_OUT", "LN2_STATS"]),
+            ("FC1", ["LN2_OUT"], ["FC1_OUT"]),
+            ("GELU", ["FC1_OUT"], ["GELU_OUT"]),
+            ("FC2", ["GELU_OUT", "RES_C"], ["NEXT"])],
 }
 # Backward nodes of one layer in execution order: (name, saved tensors read, saved tensors
 # released when the node is done).
@@ -97,14 +114,30 @@ _BWD = {
              ("PROJ", ["ATTN_OUT"], []),
              ("ATTN", ["QKV", "ATTN_OUT", "ATTN_LSE"], ["QKV", "ATTN_OUT", "ATTN_LSE"]),
              ("QKV", ["X_IN"], ["X_IN"])],
+    "dec": [("FC2", ["GELU_OUT"], ["GELU_OUT"]),
+            ("GELU", ["FC1_OUT"], ["FC1_OUT"]),
+            ("FC1", ["LN2_OUT"], ["LN2_OUT"]),
+            ("LN2", ["RES_C", "LN2_STATS"], ["RES_C", "LN2_STATS"]),
+            ("PROJC", ["ATTN_C_OUT"], []),
+            ("ATTNC", ["Q_C", "KV_C", "ATTN_C_LSE"], ["Q_C", "KV_C", "ATTN_C_OUT", "ATTN_C_LSE"]),
+            ("KVC", [], []),
+            ("QC", ["LNC_OUT"], ["LNC_OUT"]),
+            ("LNC", ["RES1", "LNC_STATS"], ["RES1", "LNC_STATS"]),
+            ("PROJ", ["ATTN_OUT"], []),
+            ("ATTN", ["QKV", "ATTN_OUT", "ATTN_LSE"], ["QKV", "ATTN_OUT", "ATTN_LSE"]),
+            ("QKV", ["LN1_OUT"], ["LN1_OUT"]),
+            ("LN1", ["X_IN", "LN1_STATS"], ["X_IN", "LN1_STATS"])],
 }
 
 
 class StageShape:
     """Sizes of the saved tensors of one layer.  T = micro_batch * seq tokens."""
 
-    def __init__(self, n_layers, hidden, n_heads, ffn, seq, micro_batch, style, elem_bytes):
+    def __init__(self, n_layers, hidden, n_heads, ffn, seq, micro_batch, style, elem_bytes, mem_seq=0):
         self.L, self.style = int(n_layers), style
+        assert (style == "dec") == (mem_seq > 0)
+        self.slots = SLOTS + CROSS_SLOTS if style == "dec" else SLOTS
+        self.n_slots = len(self.slots)
         T, H, F = micro_batch * seq, hidden, ffn
         e = elem_bytes
         self.bytes = {"X_IN": T * H * e, "LN1_STATS": T * 2 * 4, "LN1_OUT": T * H * e, "QKV": T * 3 * H * e,
@@ -112,7 +145,12 @@ class StageShape:
                       "LN2_STATS": T * 2 * 4, "LN2_OUT": T * H * e, "FC1_OUT": T * F * e, "GELU_OUT": T * F * e,
                       "RES2": T * H * e}
         # the slot that is only another name of the next layer's input has no storage
-        self.bytes["RES2" if style == "pre" else "LN2_OUT"] = 0
+        self.bytes["RES2" if style in ("pre", "dec") else "LN2_OUT"] = 0
+        if style == "dec":
+            Tm = micro_batch * mem_seq
+            self.bytes.update({"LNC_STATS": T * 2 * 4, "LNC_OUT": T * H * e, "Q_C": T * H * e, "KV_C": Tm * 2 * H * e,
+                               "ATTN_C_LSE": micro_batch * n_heads * seq * 4, "ATTN_C_OUT": T * H * e,
+                               "RES_C": T * H * e})
 
     def has_storage(self, name):
         return self.bytes[name] > 0
@@ -124,7 +162,7 @@ class CostModel:
 
     def __init__(self, fwd_ns: Sequence[int], bwd_ns: Sequence[int], d2h_bytes_per_us: int, h2d_bytes_per_us: int,
                  d2h_duplex: int = 0, h2d_duplex: int = 0):
-        assert len(fwd_ns) == 8 and len(bwd_ns) == 8
+        assert len(fwd_ns) == len(bwd_ns) and len(fwd_ns) in (8, 13)      # thirteen nodes: a decoder layer
         self.fwd, self.bwd = [int(v) for v in fwd_ns], [int(v) for v in bwd_ns]
         self.d2h, self.h2d = int(d2h_bytes_per_us), int(h2d_bytes_per_us)
         # link speed with both directions busy (0: not known)
@@ -151,9 +189,11 @@ def _where_lives(l, name):
 
 
 def plan_cost(shape: StageShape, cm: CostModel, plan, fixed_bytes: int = 0) -> Dict[str, int]:
-    """Plays one step under `plan` ([L*12] actions).  Returns step_ns, peak_bytes (fixed +
+    """Plays one step under `plan` ([L * shape.n_slots] actions).  Returns step_ns, peak_bytes (fixed +
     running peak of the saved tensors), d2h_bytes, h2d_bytes, replayed (nodes re-run)."""
     L, fwd, bwd = shape.L, _FWD[shape.style], _BWD[shape.style]
+    SLOTS, N_SLOTS = shape.slots, shape.n_slots
+    assert len(cm.fwd) == len(fwd)
 
     def action(l, name):
         if l >= L or not shape.has_storage(name) or (name == "X_IN" and l == 0):
@@ -281,7 +321,7 @@ def plan_cost(shape: StageShape, cm: CostModel, plan, fixed_bytes: int = 0) -> D
 
 
 def candidates(shape: StageShape) -> List[Tuple[int, str]]:
-    return [(l, n) for l in range(shape.L) for n in SLOTS
+    return [(l, n) for l in range(shape.L) for n in shape.slots
             if shape.has_storage(n) and not (l == 0 and n == "X_IN")]
 
 
@@ -312,7 +352,7 @@ def memopt(shape: StageShape, cm: CostModel, budget_bytes: int, inflight: int = 
     """The two phases of Section 4.3.  Returns (plan, report); report has feasible, base_ns
     (T_x: the unoptimised step), moo_ns (T_x^moo: what the plan adds), peak_bytes, and the
     number of tensors swapped for free, swapped at a cost and recomputed."""
-    L = shape.L
+    L, N_SLOTS = shape.L, shape.n_slots
     plan = [KEEP] * (L * N_SLOTS)
     cm = cm.for_inflight(inflight)
 

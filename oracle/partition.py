@@ -66,7 +66,7 @@ class Chain:
     def __init__(self, layer_shape_args: Tuple, cm: MO.CostModel, n_layers: int, fixed_per_layer: int,
                  fixed_per_stage: int, extra_ns: Optional[Sequence[int]] = None,
                  extra_bytes: Optional[Sequence[int]] = None):
-        # layer_shape_args: (hidden, n_heads, ffn, seq, micro_batch, style, elem_bytes)
+        # layer_shape_args: (hidden, n_heads, ffn, seq, micro_batch, style, elem_bytes[, mem_seq for style "dec"])
         self.args, self.cm, self.n = layer_shape_args, cm, int(n_layers)
         self.fixed_per_layer, self.fixed_per_stage = int(fixed_per_layer), int(fixed_per_stage)
         self.extra_ns = [int(v) for v in (extra_ns or [0] * self.n)]
@@ -157,7 +157,7 @@ class Search:
         shape = self.c.shape(n)
         fixed = self.c.fixed_per_stage + n * self.c.fixed_per_layer + sum(self.c.extra_bytes[a:b])
         extra = sum(self.c.extra_ns[a:b])
-        keep = [MO.KEEP] * (n * MO.N_SLOTS)
+        keep = [MO.KEEP] * (n * shape.n_slots)
         r = MO.plan_cost(shape, self.c.cm, keep, fixed)
         if self.M == 0 or k * r["peak_bytes"] <= self.M:
             out = (r["step_ns"] + extra, False, keep, r["step_ns"] + extra, 0, r["peak_bytes"])

@@ -74,10 +74,17 @@ class StepStats(C.Structure):
 class CostModel(C.Structure):
     _fields_ = [("fwd_ns", C.c_int64 * 8), ("bwd_ns", C.c_int64 * 8),
                 ("d2h_bytes_per_us", C.c_uint64), ("h2d_bytes_per_us", C.c_uint64),
-                ("d2h_duplex_bytes_per_us", C.c_uint64), ("h2d_duplex_bytes_per_us", C.c_uint64)]
+                ("d2h_duplex_bytes_per_us", C.c_uint64), ("h2d_duplex_bytes_per_us", C.c_uint64),
+                ("fwd_more_ns", C.c_int64 * 5), ("bwd_more_ns", C.c_int64 * 5)]
+
+    def node_times(self, n_nodes: int = 8):
+        """(forward, backward) node times in execution order; thirteen nodes for a decoder layer."""
+        f, b = list(self.fwd_ns) + list(self.fwd_more_ns), list(self.bwd_ns) + list(self.bwd_more_ns)
+        return f[:n_nodes], b[:n_nodes]
 
     def as_dict(self):
         return {"fwd_ns": list(self.fwd_ns), "bwd_ns": list(self.bwd_ns),
+                "fwd_more_ns": list(self.fwd_more_ns), "bwd_more_ns": list(self.bwd_more_ns),
                 "d2h_bytes_per_us": self.d2h_bytes_per_us, "h2d_bytes_per_us": self.h2d_bytes_per_us,
                 "d2h_duplex_bytes_per_us": self.d2h_duplex_bytes_per_us,
                 "h2d_duplex_bytes_per_us": self.h2d_duplex_bytes_per_us}
@@ -203,8 +210,11 @@ def plan_validate(cfg: StageConfig, plan, budget_bytes: int = 0, inflight: int =
 
 def make_cost_model(fwd_ns, bwd_ns, d2h_bytes_per_us, h2d_bytes_per_us, d2h_duplex=0, h2d_duplex=0) -> CostModel:
     cm = CostModel()
+    assert len(fwd_ns) == len(bwd_ns) and len(fwd_ns) in (8, 13)
     for i in range(8):
         cm.fwd_ns[i], cm.bwd_ns[i] = int(fwd_ns[i]), int(bwd_ns[i])
+    for i in range(8, len(fwd_ns)):      # a decoder layer's nodes 8..12
+        cm.fwd_more_ns[i - 8], cm.bwd_more_ns[i - 8] = int(fwd_ns[i]), int(bwd_ns[i])
     cm.d2h_bytes_per_us, cm.h2d_bytes_per_us = int(d2h_bytes_per_us), int(h2d_bytes_per_us)
     cm.d2h_duplex_bytes_per_us, cm.h2d_duplex_bytes_per_us = int(d2h_duplex), int(h2d_duplex)
     return cm
@@ -264,8 +274,9 @@ def partition(chain_cfg: StageConfig, cm: CostModel, n_stages: int, budget_bytes
         out["stages"] = []
         for x in range(n_stages):
             d = {f: getattr(stages[x], f) for f, _ in PartitionStage._fields_}
-            a = d["first_layer"] * SLOTS_PER_LAYER
-            d["plan"] = plan[a:a + d["n_layers"] * SLOTS_PER_LAYER].copy()
+            spl = n // L      # plan bytes a layer (more in a decoder stage)
+            a = d["first_layer"] * spl
+            d["plan"] = plan[a:a + d["n_layers"] * spl].copy()
             d["memopt"] = bool(d.pop("used_memopt"))
             out["stages"].append(d)
     return code, out

@@ -14,8 +14,8 @@ namespace dpi {
 
 dp_status check_cost_model(const dp_cost_model *cm) {
   if (cm == nullptr) return fail(DP_E_INVAL, "cost model is null");
-  for (int i = 0; i < 8; ++i)
-    if (cm->fwd_ns[i] < 0 || cm->bwd_ns[i] < 0) return fail(DP_E_INVAL, "negative node time in the cost model");
+  for (int i = 0; i < N_OPS_CROSS; ++i)
+    if (node_fwd_ns(*cm, i) < 0 || node_bwd_ns(*cm, i) < 0) return fail(DP_E_INVAL, "negative node time in the cost model");
   if (cm->d2h_bytes_per_us == 0 || cm->h2d_bytes_per_us == 0) return fail(DP_E_INVAL, "link speed is zero");
   return DP_OK;
 }
@@ -31,6 +31,13 @@ const BwdReads kPostBwd[N_OPS] = {
     {2, {DP_SLOT_RES2, DP_SLOT_LN2_STATS}}, {1, {DP_SLOT_GELU_OUT}}, {1, {DP_SLOT_FC1_OUT}}, {1, {DP_SLOT_LN1_OUT}},
     {2, {DP_SLOT_RES1, DP_SLOT_LN1_STATS}}, {1, {DP_SLOT_ATTN_OUT}},
     {3, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE}}, {1, {DP_SLOT_X_IN}}};
+
+const BwdReads kPreCrossBwd[N_OPS_CROSS] = {
+    {1, {DP_SLOT_GELU_OUT}}, {1, {DP_SLOT_FC1_OUT}}, {1, {DP_SLOT_LN2_OUT}}, {2, {DP_SLOT_RES_C, DP_SLOT_LN2_STATS}},
+    {1, {DP_SLOT_ATTN_C_OUT}}, {3, {DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_LSE}}, {0, {}}, {1, {DP_SLOT_LNC_OUT}},
+    {2, {DP_SLOT_RES1, DP_SLOT_LNC_STATS}},
+    {1, {DP_SLOT_ATTN_OUT}}, {3, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE}}, {1, {DP_SLOT_LN1_OUT}},
+    {2, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS}}};
 
 struct Cand { int l, slot; int64_t free_ns; };
 
@@ -52,9 +59,10 @@ dp_cost_model for_inflight(const dp_cost_model &cm, uint32_t inflight) {
 bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32_t inflight, uint64_t fixed_bytes,
             std::vector<uint8_t> &plan, dp_memopt_report *rep) {
   const dp_cost_model cm = for_inflight(cm_given, inflight);
-  const OpDef *ops = c.pre ? kPreOps : kPostOps;
-  const BwdReads *bwd = c.pre ? kPreBwd : kPostBwd;
-  plan.assign((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
+  const OpDef *ops = op_table(c);
+  const BwdReads *bwd = c.cross ? kPreCrossBwd : c.pre ? kPreBwd : kPostBwd;
+  const int n_ops = op_count(c), ns = c.nslots;
+  plan.assign((size_t)c.L * (size_t)ns, DP_KEEP);
   auto cost = [&](const std::vector<uint8_t> &p, int64_t *t, uint64_t *peak) {
     const CostOut o = walk_cost(c, cm, p.data(), false, 0);
     *t = o.step_ns; *peak = fixed_bytes + o.slot_peak;
@@ -64,19 +72,19 @@ bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32
   cost(plan, &T, &P);
   const int64_t base = T;
   // FreeTime on the timeline of the unoptimised step
-  int64_t fsum = 0, bsum = 0, fend[N_OPS], bstart[N_OPS];
-  for (int i = 0; i < N_OPS; ++i) { fsum += cm.fwd_ns[i]; fend[i] = fsum; }
-  for (int i = 0; i < N_OPS; ++i) { bstart[i] = bsum; bsum += cm.bwd_ns[i]; }
+  int64_t fsum = 0, bsum = 0, fend[N_OPS_CROSS], bstart[N_OPS_CROSS];
+  for (int i = 0; i < n_ops; ++i) { fsum += node_fwd_ns(cm, i); fend[i] = fsum; }
+  for (int i = 0; i < n_ops; ++i) { bstart[i] = bsum; bsum += node_bwd_ns(cm, i); }
   std::vector<Cand> cands;
   for (int l = 0; l < c.L; ++l)
-    for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) {
+    for (int s = 0; s < ns; ++s) {
       if (slot_bytes(c, s) == 0 || (l == 0 && s == DP_SLOT_X_IN)) continue;
       int last = -1, first = -1;
-      for (int i = 0; i < N_OPS; ++i) {
+      for (int i = 0; i < n_ops; ++i) {
         for (int k = 0; k < ops[i].n_in; ++k) if (ops[i].in[k].dl == 0 && ops[i].in[k].slot == s) last = i;
         for (int k = 0; k < ops[i].n_out; ++k) if (ops[i].out[k].dl == 0 && ops[i].out[k].slot == s) last = i;
       }
-      for (int i = N_OPS - 1; i >= 0; --i)
+      for (int i = n_ops - 1; i >= 0; --i)
         for (int k = 0; k < bwd[i].n; ++k) if (bwd[i].slot[k] == s) first = i;
       const int64_t last_end = (int64_t)l * fsum + fend[last];
       const int64_t first_start = (int64_t)c.L * fsum + (int64_t)(c.L - 1 - l) * bsum + bstart[first];
@@ -85,7 +93,7 @@ bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32
                                  (last_end + copy_ns(b, cm.d2h_bytes_per_us))});
     }
   std::stable_sort(cands.begin(), cands.end(), [](const Cand &a, const Cand &b) { return a.free_ns > b.free_ns; });
-  auto idx = [](const Cand &k) { return (size_t)k.l * DP_SLOTS_PER_LAYER + k.slot; };
+  auto idx = [ns](const Cand &k) { return (size_t)k.l * (size_t)ns + k.slot; };
   int n_free = 0, n_paid = 0, n_rec = 0;
   // phase 1
   for (const Cand &k : cands) {
@@ -142,7 +150,7 @@ bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32
 // DP_OK, DP_E_BUDGET (plan and report of the last round) or a validator error.
 dp_status memopt_validated(const Cfg &c, const dp_cost_model &cm, uint64_t budget_bytes, uint32_t inflight,
                                   std::vector<uint8_t> &plan, dp_memopt_report *r) {
-  const size_t plan_len = (size_t)c.L * DP_SLOTS_PER_LAYER;
+  const size_t plan_len = (size_t)c.L * (size_t)c.nslots;
   dp_plan_report keep;
   plan.assign(plan_len, DP_KEEP);
   (void)validate(c, plan.data(), plan_len, 0, 1, &keep, env_mfma_enabled(), kFuseGeluDefault);
@@ -239,8 +247,8 @@ struct Partitioner {
   std::vector<std::pair<std::array<int, 3>, std::shared_ptr<const StageRes>>> cache;
 
   void prepare() {
-    for (int i = 0; i < N_OPS; ++i) layer_ns += cm->fwd_ns[i] + cm->bwd_ns[i];
-    for (int s = 0; s < DP_SLOTS_PER_LAYER; ++s) layer_saved += slot_bytes(layer, s);
+    for (int i = 0; i < op_count(layer); ++i) layer_ns += node_fwd_ns(*cm, i) + node_bwd_ns(*cm, i);
+    for (int s = 0; s < layer.nslots; ++s) layer_saved += slot_bytes(layer, s);
     for (uint64_t d = 1; d <= (uint64_t)ell; ++d) {
       uint64_t a = lcm_depths, b = d;
       while (b) { const uint64_t r = a % b; a = b; b = r; }
@@ -269,7 +277,7 @@ struct Partitioner {
     uint64_t fixed = fixed_per_stage + (uint64_t)c.L * fixed_per_layer;
     int64_t extra = 0;
     for (int l = a; l < b; ++l) { fixed += extra_bytes[(size_t)l]; extra += extra_ns[(size_t)l]; }
-    r->plan.assign((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
+    r->plan.assign((size_t)c.L * (size_t)c.nslots, DP_KEEP);
     if (validated) {
       // The validator accounts for the library's weight copies, the gradients and the stage's
       // buffers itself; only the caller's extras come on top, as bytes no plan can remove.
@@ -393,7 +401,6 @@ dp_status dp_plan_cost(const dp_stage_config *cfg, const dp_cost_model *cm, cons
   Cfg c;
   dp_status s = parse_cfg(cfg, &c);
   if (s != DP_OK) return s;
-  if (c.cross) return fail(DP_E_UNSUPPORTED, "the planners do not take stages with a cross-attention block yet");
   if ((s = check_cost_model(cm)) != DP_OK) return s;
   if (report == nullptr) return fail(DP_E_INVAL, "report is null");
   dp_plan_report pr;
@@ -411,10 +418,9 @@ dp_status dp_plan_generate(const dp_stage_config *cfg, const dp_cost_model *cm, 
   Cfg c;
   dp_status s = parse_cfg(cfg, &c);
   if (s != DP_OK) return s;
-  if (c.cross) return fail(DP_E_UNSUPPORTED, "the planners do not take stages with a cross-attention block yet");
   if ((s = check_cost_model(cm)) != DP_OK) return s;
   if (plan_out == nullptr) return fail(DP_E_INVAL, "plan_out is null");
-  if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", DP_SLOTS_PER_LAYER);
+  if (plan_len != (size_t)c.L * (size_t)c.nslots) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", c.nslots);
   if (inflight < 1) return fail(DP_E_INVAL, "inflight must be >= 1");
   dp_memopt_report local;
   dp_memopt_report *r = report ? report : &local;
@@ -441,13 +447,12 @@ dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm
   Cfg c;
   dp_status s = parse_cfg(chain_cfg, &c);
   if (s != DP_OK) return s;
-  if (c.cross) return fail(DP_E_UNSUPPORTED, "the planners do not take stages with a cross-attention block yet");
   if ((s = check_cost_model(cm)) != DP_OK) return s;
   if (n_stages < 1 || n_stages > 32 || n_stages > c.L)
     return fail(DP_E_INVAL, "n_stages must be 1..min(32, n_layers)");
   if (plan_out == nullptr || stages_out == nullptr || (n_stages > 1 && cuts_out == nullptr))
     return fail(DP_E_INVAL, "null output argument");
-  if (plan_len != (size_t)c.L * DP_SLOTS_PER_LAYER) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", DP_SLOTS_PER_LAYER);
+  if (plan_len != (size_t)c.L * (size_t)c.nslots) return fail(DP_E_INVAL, "plan_len must be n_layers * %d", c.nslots);
   if ((flags & ~(uint32_t)DP_MEMOPT_VALIDATE) != 0) return fail(DP_E_INVAL, "unknown flag bits 0x%x", flags);
   Partitioner p;
   p.validated = (flags & DP_MEMOPT_VALIDATE) != 0;
@@ -478,7 +483,7 @@ dp_status dp_partition(const dp_stage_config *chain_cfg, const dp_cost_model *cm
     dp_partition_stage &o = stages_out[x - 1];
     o.first_layer = first; o.n_layers = end - first; o.inflight = n_stages - x + 1; o.used_memopt = st.mopt;
     o.time_ns = st.t; o.base_ns = st.base; o.moo_ns = st.moo; o.peak_bytes = st.peak;
-    memcpy(plan_out + (size_t)first * DP_SLOTS_PER_LAYER, st.plan.data(), st.plan.size());
+    memcpy(plan_out + (size_t)first * (size_t)c.nslots, st.plan.data(), st.plan.size());
     first = end;
   }
   return rep->feasible ? DP_OK : fail(DP_E_BUDGET, "no partition into %d stages fits %llu bytes a device", n_stages,

@@ -438,7 +438,7 @@ struct Walk {
   // the launches that follow belong to node `node` of layer l; with a cost model the node's time is charged here
   void begin_node(int phase, int l, int node) {
     tag = ((uint32_t)phase << 16) | ((uint32_t)l << 4) | (uint32_t)node;
-    if (cm && node < N_OPS) clk[0] += phase == TAG_BWD ? cm->bwd_ns[node] : cm->fwd_ns[node];
+    if (cm) clk[0] += phase == TAG_BWD ? node_bwd_ns(*cm, node) : node_fwd_ns(*cm, node);
   }
 
   uint64_t arena_alloc(uint64_t bytes) {
@@ -812,6 +812,7 @@ struct Walk {
       const dp_layer_grads *g = live ? &dw[l] : nullptr;
 #define W_(f) (live ? w->f : nullptr)
 #define G_(f) (live ? g->f : nullptr)
+      const int xo = c.cross ? 5 : 0;   // a decoder layer's five cross-attention nodes run between nodes 3 and 4
       if (c.pre) {
         // FC2: dG = dY W2^T, dW2 = GELU_OUT^T dY, db2 = colsum(dY)
         need(l, {DP_SLOT_GELU_OUT});
@@ -858,7 +859,7 @@ struct Walk {
         if (c.cross) dm = cross_block_bwd(l, dm, G_(b_o));
         // out-projection: dO = dM Wo^T, dWo = ATTN_OUT^T dM
         need(l, {DP_SLOT_ATTN_OUT});
-        begin_node(TAG_BWD, l, 4);
+        begin_node(TAG_BWD, l, 4 + xo);
         Buf dob = tmp(th);
         {
           Buf dmm;
@@ -871,7 +872,7 @@ struct Walk {
         Buf dqkv = attention_bwd(l, dob);
         // QKV: dA = dQKV Wqkv^T, dWqkv = LN1_OUT^T dQKV
         need(l, {DP_SLOT_LN1_OUT});
-        begin_node(TAG_BWD, l, 6);
+        begin_node(TAG_BWD, l, 6 + xo);
         Buf da = tmp(th);
         gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, 3 * H, bptr(dqkv), W_(w_qkv), nullptr, nullptr, bptr(da));
         gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, 3 * H, T, ptr(l, DP_SLOT_LN1_OUT), bptr(dqkv), nullptr, nullptr,
@@ -880,7 +881,7 @@ struct Walk {
         done_with(l, {DP_SLOT_LN1_OUT});
         // LN1: dX = dM + LN1'(dA)
         need(l, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS});
-        begin_node(TAG_BWD, l, 7);
+        begin_node(TAG_BWD, l, 7 + xo);
         void *dxp = l == 0 ? dx_out : bptr(da);
         ln_bwd(bptr(da), ptr(l, DP_SLOT_X_IN), ptr(l, DP_SLOT_LN1_STATS), W_(ln1_g), bptr(dm), dxp, G_(ln1_g),
                G_(ln1_b), (live && l > 0 && !c.drop_hidden) ? dw[l - 1].b_fc2 : nullptr);   // = db2 of the layer below
@@ -979,13 +980,13 @@ struct Walk {
 #define XG_(f) (live ? xg->f : nullptr)
     // output projection: dOc = dRc Wo_c^T, dWo_c = ATTN_C_OUT^T dRc
     need(l, {DP_SLOT_ATTN_C_OUT});
-    begin_node(TAG_BWD, l, OP_PROJC);
+    begin_node(TAG_BWD, l, 4);
     Buf doc = tmp(th);
     gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dm), XW_(w_o), nullptr, nullptr, bptr(doc));
     gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_C_OUT), bptr(dm), nullptr, nullptr, XG_(w_o));
     // attention: dQc, dKVc
     need(l, {DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_LSE});
-    begin_node(TAG_BWD, l, OP_ATTNC);
+    begin_node(TAG_BWD, l, 5);
     Buf dqc = tmp(th);
     Buf dkvc = tmp((size_t)Tm * 2 * H * c.esz);
     Buf ws = tmp((size_t)c.B * c.nh * c.S * sizeof(float));
@@ -1007,14 +1008,14 @@ struct Walk {
     colsum(T, H, bptr(dqc), XG_(b_q));
     colsum(Tm, 2 * H, bptr(dkvc), XG_(b_kv));
     // key/value projection: dMem (+)= dKVc Wkv^T (the top layer writes, the others add), dWkv = mem^T dKVc
-    begin_node(TAG_BWD, l, OP_KVC);
+    begin_node(TAG_BWD, l, 6);
     gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, Tm, H, 2 * H, bptr(dkvc), XW_(w_kv), nullptr, l == c.L - 1 ? nullptr : d_mem,
          d_mem);
     gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, 2 * H, Tm, mem, bptr(dkvc), nullptr, nullptr, XG_(w_kv));
     drop(dkvc);
     // query projection: dC = dQc Wq^T, dWq = LNC_OUT^T dQc
     need(l, {DP_SLOT_LNC_OUT});
-    begin_node(TAG_BWD, l, OP_QC);
+    begin_node(TAG_BWD, l, 7);
     Buf dcx = tmp(th);
     gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dqc), XW_(w_q), nullptr, nullptr, bptr(dcx));
     gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_LNC_OUT), bptr(dqc), nullptr, nullptr, XG_(w_q));
@@ -1022,7 +1023,7 @@ struct Walk {
     done_with(l, {DP_SLOT_LNC_OUT});
     // LayerNorm of the block: dR1 = dRc + LNc'(dC), in place in dC
     need(l, {DP_SLOT_RES1, DP_SLOT_LNC_STATS});
-    begin_node(TAG_BWD, l, OP_LNC);
+    begin_node(TAG_BWD, l, 8);
     ln_bwd(bptr(dcx), ptr(l, DP_SLOT_RES1), ptr(l, DP_SLOT_LNC_STATS), XW_(ln_g), bptr(dm), bptr(dcx), XG_(ln_g),
            XG_(ln_b), dbo_self);
     drop(dm);
@@ -1036,7 +1037,7 @@ struct Walk {
   Buf attention_bwd(int l, Buf &dob) {
     const long T = c.T, H = c.H;
     need(l, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE});
-    begin_node(TAG_BWD, l, c.pre ? 5 : 6);
+    begin_node(TAG_BWD, l, c.pre ? (c.cross ? 10 : 5) : 6);
     Buf dqkv = tmp((size_t)T * 3 * H * c.esz);
     Buf ws = tmp((size_t)c.B * c.nh * c.S * sizeof(float));
     prof_begin(DP_OPC_ATTN_BWD);
@@ -1683,10 +1684,9 @@ dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void
   if (st == nullptr || out == nullptr) return fail(DP_E_INVAL, "null argument");
   if (steps < 1) return fail(DP_E_INVAL, "steps must be >= 1");
   const Cfg &c = st->c;
-  if (c.cross) return fail(DP_E_UNSUPPORTED, "the cost model does not cover stages with a cross-attention block");
   memset(out, 0, sizeof *out);
   // node times: keep-all steps with every launch bracketed, averaged over layers and steps
-  std::vector<uint8_t> plan((size_t)c.L * DP_SLOTS_PER_LAYER, DP_KEEP);
+  std::vector<uint8_t> plan((size_t)c.L * (size_t)c.nslots, DP_KEEP);
   dp_status s = dp_stage_step(st, x_in, dy, plan.data(), plan.size(), 0, y_out, dx_out, dw, hip_stream, nullptr);   // warm-up
   if (s != DP_OK) return s;
   HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
@@ -1698,7 +1698,7 @@ dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void
   st->profiling = was_profiling;
   if (s != DP_OK) return s;
   HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);
-  double fwd_ms[N_OPS] = {0}, bwd_ms[N_OPS] = {0};
+  double fwd_ms[N_OPS_CROSS] = {0}, bwd_ms[N_OPS_CROSS] = {0};
   for (size_t i = 0; i + 1 < st->prof_used; i += 2) {
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, st->prof_events[i], st->prof_events[i + 1]), DP_E_HIP);
@@ -1708,7 +1708,10 @@ dp_status dp_stage_measure_cost_model(dp_stage *st, const void *x_in, const void
   }
   st->prof_used = 0; st->prof_class.clear(); st->prof_tag.clear();
   const double per = 1e6 / ((double)steps * c.L);
-  for (int i = 0; i < N_OPS; ++i) { out->fwd_ns[i] = (int64_t)(fwd_ms[i] * per + 0.5); out->bwd_ns[i] = (int64_t)(bwd_ms[i] * per + 0.5); }
+  for (int i = 0; i < op_count(c); ++i) {
+    const int64_t f = (int64_t)(fwd_ms[i] * per + 0.5), b = (int64_t)(bwd_ms[i] * per + 0.5);
+    if (i < N_OPS) { out->fwd_ns[i] = f; out->bwd_ns[i] = b; } else { out->fwd_more_ns[i - N_OPS] = f; out->bwd_more_ns[i - N_OPS] = b; }
+  }
   // link speed: a saved-tensor-sized block each way through pinned memory on the copy streams
   const size_t bytes = std::max<size_t>(slot_bytes(c, DP_SLOT_FC1_OUT), (size_t)16 << 20);
   void *dev = nullptr, *host = nullptr;

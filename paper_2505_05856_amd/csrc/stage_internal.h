@@ -68,6 +68,11 @@ struct CostOut { int64_t step_ns; uint64_t slot_peak, arena_peak, d2h, h2d; int 
 // the executor's own arena and hold policy.
 CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bool exact, long hold_ticks);
 
+// Time of node i of a layer in the cost model (decoder layers have thirteen nodes: 8..12 are
+// in the arrays that follow the plain layer's eight).
+inline int64_t node_fwd_ns(const dp_cost_model &cm, int i) { return i < 8 ? cm.fwd_ns[i] : cm.fwd_more_ns[i - 8]; }
+inline int64_t node_bwd_ns(const dp_cost_model &cm, int i) { return i < 8 ? cm.bwd_ns[i] : cm.bwd_more_ns[i - 8]; }
+
 // Nanoseconds a copy of `bytes` takes at `bytes_per_us`, rounded up.
 inline int64_t copy_ns(uint64_t bytes, uint64_t bytes_per_us) {
   return (int64_t)(((unsigned __int128)bytes * 1000u + bytes_per_us - 1) / bytes_per_us);

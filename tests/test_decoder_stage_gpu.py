@@ -12,6 +12,7 @@ from oracle import decoder as Dc
 from oracle import stage as O
 from paper_2505_05856_amd import binding as B
 from paper_2505_05856_amd.harness import StageRunner, upload, download
+from paper_2505_05856_amd.harness import to_binding_config as to_bc
 
 pytestmark = pytest.mark.gpu
 BOUND = {"f32": 1e-4, "bf16": 2e-2}
@@ -115,6 +116,44 @@ def test_forward_and_backward_apart_with_two_memories_in_flight():
         run.y.copy_(ty[m])
         got = run.raw_results()
         assert all(torch.equal(a, b) for a, b in zip(want[m], got)), f"micro-batch {m}"
+    run.close()
+
+
+def test_measured_cost_model_generated_plan_and_partition():
+    """The plan generator in front of a decoder stage: node times and link speed measured on the handle
+    (thirteen nodes), a plan for a budget halfway between all-recompute and keep-all, which must run inside
+    that budget with the bits of keep-all; then a chain of such layers cut into stages."""
+    cfg = dec(4, 256, 4, 1024, 128, 96, 4, "bf16")
+    w = syn.make_weights(cfg, sigma=0.05)
+    x, dy = syn.make_activations(cfg)
+    run = StageRunner(cfg, w, x, dy, mem=syn.make_memory(cfg))
+    run.step(syn.plan_keep_all(cfg))
+    keep_bits = run.raw_results()
+    cm = B.stage_measure_cost_model(run.stage, run.x, run.dy, run.y, run.dx, run.g, steps=2)
+    f, b = cm.node_times(13)
+    assert all(v > 0 for v in f + b) and cm.d2h_bytes_per_us > 0
+    assert f[2] > 0 and f[7] > 0 and b[5] > 0 and b[6] > 0          # both attentions, the key/value projection
+    _, hi = B.plan_validate(run.bcfg, syn.plan_keep_all(cfg))
+    _, lo = B.plan_validate(run.bcfg, syn.plan_all_recompute(cfg))
+    budget = (hi["peak_bytes"] + lo["peak_bytes"]) // 2
+    _, plan, rep = B.plan_generate(run.bcfg, cm, budget, flags=B.MEMOPT_VALIDATE)
+    assert rep["feasible"] and rep["validated_peak_bytes"] <= budget and plan.any()
+    run.poison_outputs()
+    stats = run.step(plan, budget_bytes=budget, want_stats=True)
+    assert stats["peak_bytes"] <= budget
+    assert all(torch.equal(a, c) for a, c in zip(keep_bits, run.raw_results()))
+    # a chain of eight such layers in two stages under a budget that forces memory optimisation on stage 1
+    import dataclasses
+    chain = B.make_config(8, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, "pre", True, "erf", "bf16",
+                          mem_seq=cfg.mem_seq)
+    one = dataclasses.replace(cfg, n_layers=1)
+    _, r1 = B.plan_validate(to_bc(one), syn.plan_keep_all(one))
+    fpl = r1["weight_bytes"] + r1["grad_bytes"]
+    _, free = B.partition(chain, cm, 2, 0, fpl, 0)
+    assert free["feasible"] and free["cuts"] == [4] and not free["any_memopt"]
+    _, r4 = B.plan_validate(run.bcfg, syn.plan_keep_all(cfg))
+    _, tight = B.partition(chain, cm, 2, int(1.6 * r4["peak_bytes"]), fpl, 0, flags=B.MEMOPT_VALIDATE)
+    assert tight["feasible"] and tight["any_memopt"] and tight["time_ns"] >= free["time_ns"]
     run.close()
 
 
