@@ -364,9 +364,11 @@ int32_t dp_stage_weight_versions(const dp_stage *st);
 dp_status dp_stage_set_rng(dp_stage *st, uint64_t seed, uint64_t counter);
 
 /* Decoder stages (mem_seq > 0).  Parameters of the cross-attention block of each layer, device
- * pointers in the stage's dtype, caller-owned, copied by dp_stage_set_cross (on `hip_stream`,
- * after waiting for the device when it replaces earlier values; these parameters are not part of
- * the parameter versions of dp_stage_set_weights):
+ * pointers in the stage's dtype, caller-owned, copied by dp_stage_set_cross on `hip_stream` into
+ * the current parameter version (required once after dp_stage_init).  They are versioned with
+ * the rest: a version made by dp_stage_set_weights starts with the block of the version before
+ * it, and a dp_stage_set_cross after it gives the new version its own; a version that a
+ * micro-batch in flight still uses cannot be overwritten (DP_E_INVAL):
  *   ln_g, ln_b [H];  w_q [H,H], b_q [H];  w_kv [H,2H] = [Wk | Wv], b_kv [2H];  w_o [H,H], b_o [H]
  * (matrices [in, out] row-major, as dp_layer_weights).  dp_cross_grads: where their gradients
  * go, same shapes; written as dp_layer_grads is: overwritten, or added to with

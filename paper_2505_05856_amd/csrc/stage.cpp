@@ -252,6 +252,8 @@ struct CrossW {  // the cross-attention block of one layer: library-owned device
 struct WeightSet {
   void *slab = nullptr;
   std::vector<LayerW> w;
+  void *xslab = nullptr;         // decoder stages: the cross-attention blocks' parameters of this version
+  std::vector<CrossW> xw;
   int refs = 0;                  // micro-batch slots holding this version
   hipEvent_t ready = nullptr;    // upload finished
   hipEvent_t last_use = nullptr; // end of the last pass that read it
@@ -305,9 +307,7 @@ struct dp_stage {
   uint64_t rng_seed = 0, rng_counter = 0;         // dropout: the seed, and the micro-batch number the next forward takes
   hipEvent_t bwd_end[2] = {nullptr, nullptr};     // ends of the last two dp_stage_backward calls
   uint64_t bwd_issued = 0;
-  // decoder stages: the cross-attention parameters and the bound memory buffers
-  void *cross_slab = nullptr;
-  std::vector<CrossW> cross_w;
+  // decoder stages: the bound memory buffers
   const void *mem = nullptr;
   void *d_mem = nullptr;
   std::vector<dp_cross_grads> dw_cross;
@@ -634,19 +634,19 @@ struct Walk {
       case OP_LNC: {
         prof_begin(DP_OPC_LN_FWD);
         if (live) {
-          const CrossW &x = st->cross_w[(size_t)l];
+          const CrossW &x = wts->xw[(size_t)l];
           check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), x.ln_g, x.ln_b, out0, (float *)out1, cs));
         }
         prof_end();
         break;
       }
       case OP_QC:
-        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? st->cross_w[(size_t)l].wt_q : nullptr,
-             live ? st->cross_w[(size_t)l].b_q : nullptr, nullptr, out0);
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? wts->xw[(size_t)l].wt_q : nullptr,
+             live ? wts->xw[(size_t)l].b_q : nullptr, nullptr, out0);
         break;
       case OP_KVC:   // reads the encoder memory, which is no slot: a replay repeats the projection
-        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, c.Tm, 2 * H, H, mem, live ? st->cross_w[(size_t)l].wt_kv : nullptr,
-             live ? st->cross_w[(size_t)l].b_kv : nullptr, nullptr, out0);
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, c.Tm, 2 * H, H, mem, live ? wts->xw[(size_t)l].wt_kv : nullptr,
+             live ? wts->xw[(size_t)l].b_kv : nullptr, nullptr, out0);
         break;
       case OP_ATTNC:
         prof_begin(DP_OPC_ATTN_FWD);
@@ -660,8 +660,8 @@ struct Walk {
         prof_end();
         break;
       case OP_PROJC:
-        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? st->cross_w[(size_t)l].wt_o : nullptr,
-             live ? st->cross_w[(size_t)l].b_o : nullptr, in(1), out0);
+        gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? wts->xw[(size_t)l].wt_o : nullptr,
+             live ? wts->xw[(size_t)l].b_o : nullptr, in(1), out0);
         break;
       default: break;
     }
@@ -974,7 +974,7 @@ struct Walk {
   Buf cross_block_bwd(int l, Buf dm, void *dbo_self) {
     const long T = c.T, H = c.H, Tm = c.Tm;
     const size_t th = (size_t)T * H * c.esz;
-    const CrossW *xw = live ? &st->cross_w[(size_t)l] : nullptr;
+    const CrossW *xw = live ? &wts->xw[(size_t)l] : nullptr;
     const dp_cross_grads *xg = live ? &dwx[l] : nullptr;
 #define XW_(f) (live ? xw->f : nullptr)
 #define XG_(f) (live ? xg->f : nullptr)
@@ -1202,6 +1202,9 @@ dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size
   return validate(c, plan, plan_len, budget_bytes, inflight, report, env_mfma_enabled(), kFuseGeluDefault);
 }
 
+static uint64_t cross_slab_bytes(const Cfg &c);
+static void cross_layout(const Cfg &c, void *slab, std::vector<CrossW> *out);
+
 // Copies the caller's parameters (and the transposed matrices the kernels want) into a version
 // of their own, on `stream`; recycles a version nothing refers to any more, else allocates one.
 static dp_status upload_weights(dp_stage *st, const dp_layer_weights *layers, hipStream_t stream, WeightSet **out) {
@@ -1253,6 +1256,20 @@ static dp_status upload_weights(dp_stage *st, const dp_layer_weights *layers, hi
     copy_mat(&w.w_o, &w.wt_o, s0.w_o, H, H);
     copy_mat(&w.w_fc1, &w.wt_fc1, s0.w_fc1, H, F);
     copy_mat(&w.w_fc2, &w.wt_fc2, s0.w_fc2, F, H);
+  }
+  // decoder stages: a new version starts with the cross-attention parameters of the current one
+  // (dp_stage_set_cross then replaces them)
+  if (e == hipSuccess && c.cross && st->current != nullptr && ws != st->current && !st->current->xw.empty()) {
+    if (ws->xslab == nullptr && hipMalloc(&ws->xslab, cross_slab_bytes(c)) != hipSuccess) {
+      (void)hipGetLastError();
+      ws->xslab = nullptr;
+      return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the cross-attention weights",
+                  (unsigned long long)cross_slab_bytes(c));
+    }
+    e = hipStreamWaitEvent(stream, st->current->ready, 0);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(ws->xslab, st->current->xslab, cross_slab_bytes(c), hipMemcpyDeviceToDevice, stream);
+    cross_layout(c, ws->xslab, &ws->xw);
   }
   if (e == hipSuccess) e = hipEventRecord(ws->ready, stream);
   if (e == hipSuccess) e = hipEventRecord(ws->last_use, stream);
@@ -1336,11 +1353,30 @@ static dp_status ensure_memory(void **arena, uint64_t *arena_bytes, void **host_
 
 // A decoder stage can run once its block's parameters are uploaded and its memory is bound.
 static dp_status cross_ready(const dp_stage *st, bool backward_too) {
-  if (st->cross_w.empty()) return fail(DP_E_INVAL, "the stage has a cross-attention block: call dp_stage_set_cross first");
+  if (st->current->xw.empty()) return fail(DP_E_INVAL, "the stage has a cross-attention block: call dp_stage_set_cross first");
   if (st->mem == nullptr) return fail(DP_E_INVAL, "the stage has a cross-attention block: bind its memory with dp_stage_bind_memory");
   if (backward_too && (st->d_mem == nullptr || st->dw_cross.empty()))
     return fail(DP_E_INVAL, "the backward pass of a decoder stage needs d_mem and dw_cross (dp_stage_bind_memory)");
   return DP_OK;
+}
+
+// Bytes of one version's cross-attention parameters (every tensor on a 256-byte boundary).
+static uint64_t cross_slab_bytes(const Cfg &c) {
+  const uint64_t H = (uint64_t)c.H;
+  return ((2 * 4 * H * H + 6 * H) * c.esz + 16 * 256) * (uint64_t)c.L;
+}
+// Where the tensors of layer l's block sit in a slab (the same places in every version).
+static void cross_layout(const Cfg &c, void *slab, std::vector<CrossW> *out) {
+  const uint64_t H = (uint64_t)c.H;
+  char *cur = (char *)slab;
+  auto take = [&](uint64_t elems) { void *p = cur; cur += (elems * c.esz + 255) / 256 * 256; return p; };
+  out->assign((size_t)c.L, CrossW{});
+  for (CrossW &w : *out) {
+    w.ln_g = take(H); w.ln_b = take(H); w.b_q = take(H); w.b_kv = take(2 * H); w.b_o = take(H);
+    w.w_q = take(H * H); w.wt_q = take(H * H);
+    w.w_kv = take(2 * H * H); w.wt_kv = take(2 * H * H);
+    w.w_o = take(H * H); w.wt_o = take(H * H);
+  }
 }
 
 dp_status dp_stage_set_cross(dp_stage *st, const dp_cross_weights *layers, void *hip_stream) {
@@ -1352,45 +1388,45 @@ dp_status dp_stage_set_cross(dp_stage *st, const dp_cross_weights *layers, void 
     for (int i = 0; i < 8; ++i)
       if (p[i] == nullptr) return fail(DP_E_INVAL, "cross-attention weight pointer %d of layer %d is null", i, l);
   }
-  for (auto &f : st->flights)
-    if (f && f->walk != nullptr) return fail(DP_E_INVAL, "a micro-batch is between its forward and its backward");
-  const uint64_t H = (uint64_t)c.H;
-  const uint64_t slab = ((2 * 4 * H * H + 6 * H) * c.esz + 16 * 256) * (uint64_t)c.L;   // every tensor on a 256-byte boundary
+  WeightSet *ws = st->current;
+  if (ws->refs > 0)
+    return fail(DP_E_INVAL, "a micro-batch in flight uses the current parameter version: make a new one with "
+                            "dp_stage_set_weights first");
   hipStream_t stream = (hipStream_t)hip_stream;
-  if (st->cross_slab == nullptr) {
-    if (hipMalloc(&st->cross_slab, slab) != hipSuccess) {
+  if (ws->xslab == nullptr) {
+    if (hipMalloc(&ws->xslab, cross_slab_bytes(c)) != hipSuccess) {
       (void)hipGetLastError();
-      st->cross_slab = nullptr;
-      return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the cross-attention weights", (unsigned long long)slab);
+      ws->xslab = nullptr;
+      return fail(DP_E_DEVMEM, "cannot allocate %llu bytes for the cross-attention weights",
+                  (unsigned long long)cross_slab_bytes(c));
     }
-  } else {
-    HIP_TRY(hipDeviceSynchronize(), DP_E_HIP);   // earlier steps may still read the old values
   }
-  char *cur = (char *)st->cross_slab;
-  auto take = [&](uint64_t elems) { void *p = cur; cur += (elems * c.esz + 255) / 256 * 256; return p; };
+  // after the version's own upload and after its last reader, which may have run on other streams
+  HIP_TRY(hipStreamWaitEvent(stream, ws->ready, 0), DP_E_HIP);
+  HIP_TRY(hipStreamWaitEvent(stream, ws->last_use, 0), DP_E_HIP);
+  cross_layout(c, ws->xslab, &ws->xw);
+  const uint64_t H = (uint64_t)c.H;
   hipError_t e = hipSuccess;
-  auto copy_vec = [&](void **dst, const void *src, uint64_t n) {
-    *dst = take(n);
-    if (e == hipSuccess) e = hipMemcpyAsync(*dst, src, n * c.esz, hipMemcpyDeviceToDevice, stream);
+  auto copy_vec = [&](void *dst, const void *src, uint64_t n) {
+    if (e == hipSuccess) e = hipMemcpyAsync(dst, src, n * c.esz, hipMemcpyDeviceToDevice, stream);
   };
-  auto copy_mat = [&](void **dst, void **dst_t, const void *src, uint64_t rows, uint64_t cols) {
+  auto copy_mat = [&](void *dst, void *dst_t, const void *src, uint64_t rows, uint64_t cols) {
     copy_vec(dst, src, rows * cols);
-    *dst_t = take(rows * cols);
-    if (e == hipSuccess) e = dp::launch_transpose(c.dtype, (int)rows, (int)cols, src, *dst_t, stream);
+    if (e == hipSuccess) e = dp::launch_transpose(c.dtype, (int)rows, (int)cols, src, dst_t, stream);
   };
-  st->cross_w.assign((size_t)c.L, CrossW{});
   for (int l = 0; l < c.L; ++l) {
-    CrossW &w = st->cross_w[(size_t)l];
+    const CrossW &w = ws->xw[(size_t)l];
     const dp_cross_weights &s0 = layers[l];
-    copy_vec(&w.ln_g, s0.ln_g, H); copy_vec(&w.ln_b, s0.ln_b, H);
-    copy_vec(&w.b_q, s0.b_q, H); copy_vec(&w.b_kv, s0.b_kv, 2 * H); copy_vec(&w.b_o, s0.b_o, H);
-    copy_mat(&w.w_q, &w.wt_q, s0.w_q, H, H);
-    copy_mat(&w.w_kv, &w.wt_kv, s0.w_kv, H, 2 * H);
-    copy_mat(&w.w_o, &w.wt_o, s0.w_o, H, H);
+    copy_vec(w.ln_g, s0.ln_g, H); copy_vec(w.ln_b, s0.ln_b, H);
+    copy_vec(w.b_q, s0.b_q, H); copy_vec(w.b_kv, s0.b_kv, 2 * H); copy_vec(w.b_o, s0.b_o, H);
+    copy_mat(w.w_q, w.wt_q, s0.w_q, H, H);
+    copy_mat(w.w_kv, w.wt_kv, s0.w_kv, H, 2 * H);
+    copy_mat(w.w_o, w.wt_o, s0.w_o, H, H);
   }
-  // the stage's own streams and whatever stream the caller steps on may read them next
-  if (e == hipSuccess) e = hipStreamSynchronize(stream);
-  if (e != hipSuccess) { st->cross_w.clear(); return fail(DP_E_HIP, "cross-attention weight upload: %s", hipGetErrorString(e)); }
+  // the version is ready once this upload is done too (every pass waits for `ready` first)
+  if (e == hipSuccess) e = hipEventRecord(ws->ready, stream);
+  if (e == hipSuccess) e = hipEventRecord(ws->last_use, stream);
+  if (e != hipSuccess) { ws->xw.clear(); return fail(DP_E_HIP, "cross-attention weight upload: %s", hipGetErrorString(e)); }
   return DP_OK;
 }
 
@@ -1795,7 +1831,6 @@ void dp_stage_destroy(dp_stage *st) {
   if (st->h2d) (void)hipStreamDestroy(st->h2d);
   if (st->arena) (void)hipFree(st->arena);
   if (st->host_pool) (void)hipHostFree(st->host_pool);
-  if (st->cross_slab) (void)hipFree(st->cross_slab);
   for (auto &f : st->flights) {
     if (!f) continue;
     delete f->walk;
@@ -1808,6 +1843,7 @@ void dp_stage_destroy(dp_stage *st) {
     if (v->ready) (void)hipEventDestroy(v->ready);
     if (v->last_use) (void)hipEventDestroy(v->last_use);
     if (v->slab) (void)hipFree(v->slab);
+    if (v->xslab) (void)hipFree(v->xslab);
   }
   delete st;
 }

@@ -157,6 +157,48 @@ def test_measured_cost_model_generated_plan_and_partition():
     run.close()
 
 
+def test_parameter_versions_cover_the_cross_attention_block():
+    """An asynchronous schedule on a decoder stage: F0 under version 0, the parameters (both sets) replaced,
+    F1 under version 1, then B0 and B1.  Each micro-batch must come out exactly as a whole step under its
+    own version does, and each version's step agrees with the oracle."""
+    cfg = dec(2, 128, 2, 256, 64, 48, 2, "bf16")
+    vers = [syn.make_weights(cfg, seed=s, sigma=0.05) for s in (0, 5)]
+    x, dy = syn.make_activations(cfg)
+    mem = syn.make_memory(cfg)
+    run = StageRunner(cfg, vers[0], x, dy, mem=mem)
+    plan = syn.plan_seeded(cfg, 2)
+    tw = [[{k: upload(v, cfg) for k, v in layer.items()} for layer in w] for w in vers]
+    want = []
+    for v in range(2):
+        B.stage_set_weights(run.stage, tw[v]); B.stage_set_cross(run.stage, tw[v])
+        run.poison_outputs()
+        run.step(plan)
+        want.append([t.clone() for t in run.raw_results()])
+        compare(cfg, run, oracle_step(cfg, vers[v], x, mem, dy))
+    assert B.stage_weight_versions(run.stage) == 1
+    B.stage_set_weights(run.stage, tw[0]); B.stage_set_cross(run.stage, tw[0])
+    ty = [torch.empty_like(run.x) for _ in range(2)]
+    B.stage_forward(run.stage, 0, 2, run.x, plan, 0, ty[0])
+    with pytest.raises(B.DpError):      # version 0 is in use: its block cannot be overwritten
+        B.stage_set_cross(run.stage, tw[1])
+    B.stage_set_weights(run.stage, tw[1])      # a new version, which starts with version 0's block ...
+    B.stage_set_cross(run.stage, tw[1])        # ... until it gets its own
+    B.stage_forward(run.stage, 1, 2, run.x, plan, 0, ty[1])
+    assert B.stage_weight_versions(run.stage) == 2
+    for m in range(2):
+        run.poison_outputs()
+        B.stage_backward(run.stage, m, run.dy, run.dx, run.g, 0)
+        run.y.copy_(ty[m])
+        assert all(torch.equal(a, b) for a, b in zip(want[m], run.raw_results())), f"micro-batch {m}"
+    assert B.stage_weight_versions(run.stage) == 1
+    # a new version without a set_cross keeps the block of the version before it
+    B.stage_set_weights(run.stage, tw[1])
+    run.poison_outputs()
+    run.step(plan)
+    assert all(torch.equal(a, b) for a, b in zip(want[1], run.raw_results()))
+    run.close()
+
+
 def test_refusals():
     cfg = dec(1, 64, 1, 128, 16, 8, 1, "f32")
     bc = B.make_config(1, 64, 1, 128, 16, 1, "pre", True, "erf", "f32", mem_seq=8)
