@@ -230,12 +230,20 @@ def main():
 
     for _ in range(args.warmup):
         run.step(plan, budget)
+    # step boundaries are also marked with HIP events on the launch stream (the paper times its iterations the
+    # same way, Appendix C.1): their spread is reported beside the wall-clock mean that `value` comes from
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         run.step(plan, budget)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    step_events = {"mean": round(sum(per_step) / len(per_step), 4), "median": round(per_step[len(per_step) // 2], 4),
+                   "min": round(per_step[0], 4), "max": round(per_step[-1], 4)} if per_step else None
 
     # per-kernel-class times: the same steps again with HIP event brackets on the launch stream
     roof, op_ms = None, None
@@ -338,6 +346,7 @@ def main():
                    "min_feasible_budget_bytes": tight["peak_bytes"]},
         "model_tflops": round(cfg.model_flops() / (ms * 1e-3) / 1e12, 2),
         "mfma_peak_frac": round(cfg.model_flops() / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "step_ms_by_hip_events": step_events,
         "fwd_ms": round(stats["fwd_ms"], 4), "bwd_ms": round(stats["bwd_ms"], 4),
         "swap_bytes": {"d2h": stats["d2h_bytes"], "h2d": stats["h2d_bytes"]},
         "replayed_ops": stats["n_replayed_ops"], "kernel_launches": stats["n_kernel_launches"],
