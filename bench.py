@@ -47,7 +47,7 @@ def cpu_baseline(cfg, weights, x, dy, budget_s=30.0, mem=None):
         if cfg.mem_seq > 0:
             from oracle import decoder as Dc
             st = Dc.DecoderStage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
-                                 cfg.causal, cfg.gelu, cfg.ln_eps)
+                                 cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden)
             t0 = time.perf_counter()
             Dc.decoder_step(st, weights[:n_layers], x, mem, dy, dtype=np.float64)
             return time.perf_counter() - t0
@@ -201,9 +201,6 @@ def main():
     weights = syn.make_weights(cfg)
     x, dy = syn.make_activations(cfg)
     mem = syn.make_memory(cfg) if cfg.mem_seq > 0 else None
-    if cfg.mem_seq > 0 and args.dropout > 0:
-        print("bench.py: stages with a cross-attention block run without dropout", file=sys.stderr)
-        sys.exit(2)
     run = StageRunner(cfg, weights, x, dy, mem=mem)
     memopt = None
     if plan_name == "memopt":

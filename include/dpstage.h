@@ -113,9 +113,10 @@ enum {
  * mem [micro_batch*mem_seq, H], the same for all layers:
  *   pre-LN : r1 = x+Attn(..)*Wo+bo;  rc = r1 + CrossAttn(LNc(r1)*Wq+bq, mem*Wkv+bkv)*Wo_c+bo_c;
  *            y = rc+GELU(LN2(rc)*W1+b1)*W2+b2        (no mask in the cross-attention)
- * and the step also returns dMem, the sum over layers of the gradient reaching mem.  Such a
- * stage needs norm_style DP_PRE_LN and both dropout rates 0 (DP_E_UNSUPPORTED otherwise), its
- * block's parameters from dp_stage_set_cross and its memory buffers from
+ * and the step also returns dMem, the sum over layers of the gradient reaching mem.  Dropout
+ * acts in the block as in the rest of the layer: p_attn on its attention probabilities, p_hidden
+ * on the output of its projection.  Such a stage needs norm_style DP_PRE_LN (DP_E_UNSUPPORTED
+ * otherwise), its block's parameters from dp_stage_set_cross and its memory buffers from
  * dp_stage_bind_memory.  The validator, the plan generator, the cost model and the
  * partitioner (a chain of such layers, all reading the same memory) take it like any stage. */
 typedef struct {
@@ -505,7 +506,8 @@ dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, i
 /* The same operations with dropout, as the stage applies it.  `drop` names the mask: rate,
  * seed, micro-batch number and layer (see dp_stage_set_rng); p = 0 gives the plain operation.
  * dp_op_dropout: y = (res ? res : 0) + mask * x / (1-p) over n elements (n a multiple of 8,
- * below 2^32; x and res may be y), site 1 = after the attention projection, 2 = after FC2; the
+ * below 2^32; x and res may be y), site 1 = after the attention projection, 2 = after FC2,
+ * 4 = after the projection of a decoder layer's cross-attention block; the
  * backward of a site is the same call on the gradient with res = NULL.
  * Attention: the probabilities are masked and scaled after the softmax (lse is that of the
  * plain softmax); the backward masks the same positions. */

@@ -12,14 +12,15 @@ generator.  The one used here, which the HIP kernels implement independently:
 
   mix(x):  x ^= x >> 16;  x *= 0x7feb352d;  x ^= x >> 15;  x *= 0x846ca68b;  x ^= x >> 16
            (32-bit; the published "lowbias32" integer mixer, a bijection)
-  base   = mix(mix(mix(mix(mix(seed_lo ^ 0x9e3779b9) ^ seed_hi) ^ mb_lo) ^ mb_hi) ^ (4*layer + site))
+  base   = mix(mix(mix(mix(mix(seed_lo ^ 0x9e3779b9) ^ seed_hi) ^ mb_lo) ^ mb_hi) ^ (8*layer + site))
   k0     = mix(base ^ (unit * 0x9e3779b1));   k1 = mix(k0 ^ 0x85ebca6b)
   bits(i): the mixer applied to i ^ k0, with k1 xored in between its two multiplications
   keep(i) = bits(i) >= floor(p * 2^32);   kept values are scaled by 1 / (1 - p)
 
 site 0: attention probabilities, unit = batch * heads + head, i = query * S + key;
 site 1 / 2: output of the attention projection / of FC2, unit = 0, i = token * H + column;
-site 3: cross-attention probabilities, unit = batch * heads + head, i = query * Sk + key.
+site 3: cross-attention probabilities, unit = batch * heads + head, i = query * Sk + key;
+site 4: output of the cross-attention block's projection (decoder stages), like sites 1 and 2.
 seed is the caller's, mb counts micro-batches (the caller sets or the library increments it).
 
 Pins (tests/test_oracle_dropout.py): the mixer is injective on a large range and has the
@@ -33,7 +34,7 @@ import numpy as np
 
 M1, M2 = 0x7FEB352D, 0x846CA68B
 U32 = np.uint32
-SITE_ATTN, SITE_PROJ, SITE_FC2, SITE_CROSS = 0, 1, 2, 3
+SITE_ATTN, SITE_PROJ, SITE_FC2, SITE_CROSS, SITE_CROSS_PROJ = 0, 1, 2, 3, 4
 
 
 def mix(x):
@@ -48,7 +49,7 @@ def mix(x):
 
 def site_base(seed: int, mb: int, layer: int, site: int) -> int:
     s = mix(U32((seed & 0xFFFFFFFF) ^ 0x9E3779B9))
-    for word in ((seed >> 32) & 0xFFFFFFFF, mb & 0xFFFFFFFF, (mb >> 32) & 0xFFFFFFFF, (4 * layer + site) & 0xFFFFFFFF):
+    for word in ((seed >> 32) & 0xFFFFFFFF, mb & 0xFFFFFFFF, (mb >> 32) & 0xFFFFFFFF, (8 * layer + site) & 0xFFFFFFFF):
         s = mix(s ^ U32(word))
     return int(s)
 

@@ -460,7 +460,7 @@ class Dropout(C.Structure):
     _fields_ = [("p", C.c_float), ("seed", C.c_uint64), ("micro_batch", C.c_uint64), ("layer", C.c_int32)]
 
 
-SITE_PROJ, SITE_FC2 = 1, 2
+SITE_PROJ, SITE_FC2, SITE_CROSS_PROJ = 1, 2, 4
 
 
 def op_dropout(x, res, y, drop: Dropout, site: int, stream=None):

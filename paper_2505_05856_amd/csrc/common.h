@@ -106,7 +106,7 @@ __device__ __forceinline__ float gelu_df(float x, int kind) {
 // Whether an element is kept is a pure function of where it sits (counter-based), so that a
 // recomputed tensor and the backward pass get the mask of the forward pass without any state:
 //   mix(x): the 32-bit integer mixer x^=x>>16, x*=0x7feb352d, x^=x>>15, x*=0x846ca68b, x^=x>>16
-//   base  = mix chain over (seed, micro-batch counter, 4*layer + site)   [host, per launch]
+//   base  = mix chain over (seed, micro-batch counter, 8*layer + site)   [host, per launch]
 //   k0    = mix(base ^ unit*0x9e3779b1), k1 = mix(k0 ^ 0x85ebca6b)       [per batch*head / tensor]
 //   bits(i) = the mixer on i ^ k0 with k1 xored in between its two multiplications
 //   keep(i) = bits(i) >= floor(p * 2^32); kept values are scaled by 1/(1-p).

@@ -15,7 +15,8 @@ struct DropArgs {
   uint32_t thr;     // floor(p * 2^32)
   float scale;      // 1 / (1 - p)
 };
-enum DropSite { kSiteAttn = 0, kSiteProj = 1, kSiteFc2 = 2, kSiteCross = 3 };
+// (up to eight sites a layer: the key chain takes 8 * layer + site)
+enum DropSite { kSiteAttn = 0, kSiteProj = 1, kSiteFc2 = 2, kSiteCross = 3, kSiteCrossProj = 4 };
 inline uint32_t drop_mix_host(uint32_t x) {
   x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
   return x;
@@ -25,7 +26,7 @@ inline DropArgs make_drop_args(uint64_t seed, uint64_t mb, int layer, int site, 
   s = drop_mix_host(s ^ (uint32_t)(seed >> 32));
   s = drop_mix_host(s ^ (uint32_t)mb);
   s = drop_mix_host(s ^ (uint32_t)(mb >> 32));
-  s = drop_mix_host(s ^ (uint32_t)(4 * layer + site));
+  s = drop_mix_host(s ^ (uint32_t)(8 * layer + site));
   DropArgs a;
   a.base = s;
   a.thr = (uint32_t)((double)p * 4294967296.0);   // p < 1: the product is below 2^32; the cast truncates

@@ -114,7 +114,7 @@ static dp_status drop_args_of(const dp_dropout *d, int site, dp::DropArgs *out) 
 
 dp_status dp_op_dropout(int32_t dtype, size_t n, const void *x, const void *res, void *y, const dp_dropout *drop,
                         int32_t site, void *hip_stream) {
-  if (bad_dtype(dtype) || !x || !y || (site != dp::kSiteProj && site != dp::kSiteFc2))
+  if (bad_dtype(dtype) || !x || !y || (site != dp::kSiteProj && site != dp::kSiteFc2 && site != dp::kSiteCrossProj))
     return fail(DP_E_INVAL, "dropout: bad argument");
   if (n % 8 || n >= ((size_t)1 << 32)) return fail(DP_E_UNSUPPORTED, "dropout: n must be a multiple of 8 below 2^32");
   dp::DropArgs a;

@@ -68,7 +68,8 @@ dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
   o->nslots = o->cross ? DP_SLOTS_PER_LAYER_CROSS : DP_SLOTS_PER_LAYER;
   if (o->cross) {
     if (!o->pre) return fail(DP_E_UNSUPPORTED, "a stage with a cross-attention block needs norm_style DP_PRE_LN");
-    if (o->drop_attn || o->drop_hidden) return fail(DP_E_UNSUPPORTED, "a stage with a cross-attention block runs without dropout");
+    if (o->drop_attn && (long)c->seq * c->mem_seq >= (1L << 32))
+      return fail(DP_E_UNSUPPORTED, "attention dropout needs seq*mem_seq < 2^32");
     if (o->Sm > 4096 && !(o->dtype == DP_BF16 && dp::attn_mfma_supported(o->Sm, o->dh)))
       return fail(DP_E_UNSUPPORTED, "mem_seq > 4096 is not supported for this head_dim/dtype");
     if (o->Tm > (1L << 24)) return fail(DP_E_UNSUPPORTED, "micro_batch*mem_seq too large");
@@ -652,16 +653,18 @@ struct Walk {
         prof_begin(DP_OPC_ATTN_FWD);
         if (live) {
           const dp::AttnView v = cross_view(in(0), in(1), nullptr, nullptr);
+          const dp::DropArgs da = dp::make_drop_args(rng_seed, rng_mb, l, dp::kSiteCross, c.p_attn);
           if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.Sm, c.dh))
-            check(dp::launch_attn_fwd_mfma_view(c.B, c.nh, c.dh, 0, v, out0, (float *)out1, cs));
+            check(dp::launch_attn_fwd_mfma_view(c.B, c.nh, c.dh, 0, v, out0, (float *)out1, cs, &da));
           else
-            check(dp::launch_attn_fwd_simple_view(c.dtype, c.B, c.nh, c.dh, 0, v, out0, (float *)out1, cs));
+            check(dp::launch_attn_fwd_simple_view(c.dtype, c.B, c.nh, c.dh, 0, v, out0, (float *)out1, cs, &da));
         }
         prof_end();
         break;
       case OP_PROJC:
         gemm(DP_OPC_GEMM_FWD, dp::kGemmNT, T, H, H, in(0), live ? wts->xw[(size_t)l].wt_o : nullptr,
-             live ? wts->xw[(size_t)l].b_o : nullptr, in(1), out0);
+             live ? wts->xw[(size_t)l].b_o : nullptr, c.drop_hidden ? nullptr : in(1), out0);
+        if (c.drop_hidden) hidden_dropout(l, dp::kSiteCrossProj, out0, in(1), out0);
         break;
       default: break;
     }
@@ -856,7 +859,7 @@ struct Walk {
         drop(dcur_buf);
         done_with(l, {res_mlp, DP_SLOT_LN2_STATS});
         Buf dm = dc;
-        if (c.cross) dm = cross_block_bwd(l, dm, G_(b_o));
+        if (c.cross) dm = cross_block_bwd(l, dm, c.drop_hidden ? nullptr : G_(b_o));
         // out-projection: dO = dM Wo^T, dWo = ATTN_OUT^T dM
         need(l, {DP_SLOT_ATTN_OUT});
         begin_node(TAG_BWD, l, 4 + xo);
@@ -982,8 +985,16 @@ struct Walk {
     need(l, {DP_SLOT_ATTN_C_OUT});
     begin_node(TAG_BWD, l, 4);
     Buf doc = tmp(th);
-    gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, bptr(dm), XW_(w_o), nullptr, nullptr, bptr(doc));
-    gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_C_OUT), bptr(dm), nullptr, nullptr, XG_(w_o));
+    {
+      // with dropout the projection saw its output through the mask: so does its gradient, whose
+      // column sums are then the bias gradient (without dropout LN2's backward handed those on)
+      Buf dmm;
+      if (c.drop_hidden) dmm = masked_grad(l, dp::kSiteCrossProj, bptr(dm), XG_(b_o));
+      const void *dmp = c.drop_hidden ? bptr(dmm) : bptr(dm);
+      gemm(DP_OPC_GEMM_DGRAD, dp::kGemmNT, T, H, H, dmp, XW_(w_o), nullptr, nullptr, bptr(doc));
+      gemm(DP_OPC_GEMM_WGRAD, dp::kGemmTN, H, H, T, ptr(l, DP_SLOT_ATTN_C_OUT), dmp, nullptr, nullptr, XG_(w_o));
+      if (c.drop_hidden) drop(dmm);
+    }
     // attention: dQc, dKVc
     need(l, {DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_LSE});
     begin_node(TAG_BWD, l, 5);
@@ -993,13 +1004,15 @@ struct Walk {
     prof_begin(DP_OPC_ATTN_BWD);
     if (live) {
       const dp::AttnView v = cross_view(ptr(l, DP_SLOT_Q_C), ptr(l, DP_SLOT_KV_C), bptr(dqc), bptr(dkvc));
+      const dp::DropArgs da = dp::make_drop_args(rng_seed, rng_mb, l, dp::kSiteCross, c.p_attn);
       if (c.dtype == DP_BF16 && st->use_mfma && dp::attn_mfma_supported(c.Sm, c.dh))
         check(dp::launch_attn_bwd_mfma_view(c.B, c.nh, c.dh, 0, v, ptr(l, DP_SLOT_ATTN_C_OUT),
-                                            (const float *)ptr(l, DP_SLOT_ATTN_C_LSE), bptr(doc), (float *)bptr(ws), cs));
+                                            (const float *)ptr(l, DP_SLOT_ATTN_C_LSE), bptr(doc), (float *)bptr(ws), cs,
+                                            &da));
       else
         check(dp::launch_attn_bwd_simple_view(c.dtype, c.B, c.nh, c.dh, 0, v, ptr(l, DP_SLOT_ATTN_C_OUT),
                                               (const float *)ptr(l, DP_SLOT_ATTN_C_LSE), bptr(doc), (float *)bptr(ws),
-                                              cs));
+                                              cs, &da));
     }
     prof_end();
     drop(ws);

@@ -87,6 +87,38 @@ def test_every_plan_same_bits_and_the_oracles_numbers(cfg):
     run.close()
 
 
+@pytest.mark.parametrize("dtype,p", [("f32", 0.1), ("bf16", 0.1), ("bf16", 0.5)])
+def test_dropout_in_both_attentions_and_after_all_three_projections(dtype, p):
+    """The oracle's masks (functions of seed, micro-batch number, layer, site, position) on the device: parity of
+    every output, and the same bits under every plan -- a replayed tensor meets the mask of its first computation."""
+    cfg = syn.StageConfig(2, 128, 2, 256, 72, 2, "pre", True, "erf", dtype, p_attn=p, p_hidden=p, mem_seq=40)
+    w = syn.make_weights(cfg, sigma=0.05)
+    x, dy = syn.make_activations(cfg)
+    mem = syn.make_memory(cfg)
+    seed, mb = 0xFEDCBA9876543210, 5
+    st = Dc.DecoderStage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
+                         cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=p, p_hidden=p)
+    st.set_rng(seed, mb)
+    ref = Dc.decoder_step(st, w, x, mem, dy)
+    run = StageRunner(cfg, w, x, dy, mem=mem)
+    first = None
+    for name, plan in [("keep", syn.plan_keep_all(cfg)), ("recompute", syn.plan_all_recompute(cfg)),
+                       ("swap", syn.plan_all_swap(cfg))] + [(f"seed{s}", syn.plan_seeded(cfg, s)) for s in range(6)]:
+        B.stage_set_rng(run.stage, seed, mb)
+        run.poison_outputs()
+        run.step(plan)
+        if first is None:
+            # a mask position kept on one side and dropped on the other would show as an error of order 1
+            compare(cfg, run, ref)
+            first = run.raw_results()
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, run.raw_results())), name
+    # the next micro-batch draws other masks
+    run.step(syn.plan_keep_all(cfg))
+    assert not all(torch.equal(a, b) for a, b in zip(first, run.raw_results()))
+    run.close()
+
+
 def test_forward_and_backward_apart_with_two_memories_in_flight():
     cfg = dec(2, 128, 2, 256, 64, 48, 2, "bf16")
     w = syn.make_weights(cfg, sigma=0.05)

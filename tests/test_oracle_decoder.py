@@ -95,3 +95,34 @@ def test_dmem_is_the_sum_over_layers():
             a[l][idx] += eps; b[l][idx] -= eps
             total[idx] += (fwd(a) - fwd(b)) / (2 * eps)
     assert np.allclose(total, dmem, atol=5e-7)
+
+
+def test_central_differences_with_dropout():
+    st, ws, x, mem, dy = make(L=2, H=8, nh=2, F=16, S=3, Sm=4, B=2)
+    st = Dc.DecoderStage(st.L, st.H, st.nh, st.F, st.S, st.Sm, st.B, causal=True, p_attn=0.3, p_hidden=0.25)
+    st.set_rng(0x1234567, 9)
+    y, dx, dmem, grads = Dc.decoder_step(st, ws, x, mem, dy)
+    plain = Dc.DecoderStage(st.L, st.H, st.nh, st.F, st.S, st.Sm, st.B, causal=True)
+    assert not np.allclose(y, Dc.decoder_step(plain, ws, x, mem, dy)[0])          # the masks do act
+    st.set_rng(0x1234567, 10)
+    assert not np.allclose(y, Dc.decoder_step(st, ws, x, mem, dy)[0])             # and differ between micro-batches
+    st.set_rng(0x1234567, 9)
+    loss = lambda ws_, x_, m_: float((Dc.decoder_step(st, ws_, x_, m_, dy)[0] * dy).sum())
+    eps = 1e-6
+
+    def numeric(arr, rebuild):
+        num = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            a, b = arr.copy(), arr.copy()
+            a[idx] += eps; b[idx] -= eps
+            num[idx] = (loss(*rebuild(a)) - loss(*rebuild(b))) / (2 * eps)
+        return num
+    assert np.allclose(numeric(x, lambda a: (ws, a, mem)), dx, atol=3e-7)
+    assert np.allclose(numeric(mem, lambda a: (ws, x, a)), dmem, atol=3e-7)
+    for l in range(st.L):
+        for k in ("w_oc", "b_oc", "w_kvc", "w_qc", "lnc_g", "w_o", "b_fc2", "w_qkv"):
+            def rebuild(a, l=l, k=k):
+                w2 = [dict(w) for w in ws]
+                w2[l][k] = a
+                return w2, x, mem
+            assert np.allclose(numeric(ws[l][k], rebuild), grads[l][k], atol=3e-7), (l, k)

@@ -199,7 +199,7 @@ def test_decoder_stage_plans_and_memory():
 
 
 def test_decoder_stage_refusals():
-    for bad in (_dec(norm_style="post"), _dec(p_attn=0.1), _dec(p_hidden=0.1), _dec(mem_seq=-1)):
+    for bad in (_dec(norm_style="post"), _dec(mem_seq=-1)):
         with pytest.raises(B.DpError):
             B.plan_validate(to_binding_config(bad), syn.plan_keep_all(_dec()))
     cfg = _dec()
