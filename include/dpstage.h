@@ -58,7 +58,8 @@ typedef enum {
 typedef enum { DP_KEEP = 0, DP_RECOMPUTE = 1, DP_SWAP = 2 } dp_action;
 
 typedef enum { DP_POST_LN = 0, DP_PRE_LN = 1 } dp_norm_style;
-typedef enum { DP_GELU_ERF = 0, DP_GELU_TANH = 1 } dp_gelu_kind;
+/* The feed-forward activation: GELU in its exact or tanh form, or ReLU (derivative 0 at 0). */
+typedef enum { DP_GELU_ERF = 0, DP_GELU_TANH = 1, DP_ACT_RELU = 2 } dp_gelu_kind;
 typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
 
 /* Saved tensors ("slots") of one layer, in plan order.  T = micro_batch*seq.

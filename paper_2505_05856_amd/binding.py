@@ -182,7 +182,7 @@ def _check(code: int):
 def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, norm_style="post", causal=False,
                 gelu="erf", dtype="bf16", ln_eps=1e-5, p_attn=0.0, p_hidden=0.0, mem_seq=0) -> StageConfig:
     return StageConfig(n_layers, hidden, n_heads, ffn, seq, micro_batch,
-                       {"post": 0, "pre": 1}[norm_style], int(bool(causal)), {"erf": 0, "tanh": 1}[gelu],
+                       {"post": 0, "pre": 1}[norm_style], int(bool(causal)), {"erf": 0, "tanh": 1, "relu": 2}[gelu],
                        {"f32": 0, "bf16": 1}[dtype], ln_eps, p_attn, p_hidden, mem_seq)
 
 

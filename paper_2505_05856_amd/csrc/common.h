@@ -86,6 +86,7 @@ __device__ __forceinline__ float normal_cdf_parts(float x, float *density_exp) {
 __device__ __forceinline__ float gelu_f(float x, int kind) {
 #pragma clang fp contract(off)
   if (kind == 0) { float e; return x * normal_cdf_parts(x, &e); }
+  if (kind == 2) return fmaxf(x, 0.f);   // ReLU
   const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
   return 0.5f * x * (1.0f + tanhf(u));
 }
@@ -96,6 +97,7 @@ __device__ __forceinline__ float gelu_df(float x, int kind) {
     const float cdf = normal_cdf_parts(x, &e);
     return cdf + x * (0.39894228040143268f * e);
   }
+  if (kind == 2) return x > 0.f ? 1.0f : 0.f;   // ReLU: the derivative at 0 is taken as 0
   const float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
   const float t = tanhf(u);
   const float du = 0.79788456080286536f * (1.0f + 0.134145f * x * x);

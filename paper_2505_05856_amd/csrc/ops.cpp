@@ -40,14 +40,14 @@ dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const v
 }
 
 dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream) {
-  if (bad_dtype(dtype) || (n > 0 && (!x || !y)) || (gelu_kind != 0 && gelu_kind != 1)) return fail(DP_E_INVAL, "gelu_fwd: bad argument");
+  if (bad_dtype(dtype) || (n > 0 && (!x || !y)) || (gelu_kind < 0 || gelu_kind > 2)) return fail(DP_E_INVAL, "gelu_fwd: bad argument");
   if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
   return op_done(dp::launch_gelu_fwd(dtype, gelu_kind, n, x, y, (hipStream_t)hip_stream), "gelu_fwd");
 }
 
 dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,
                          void *hip_stream) {
-  if (bad_dtype(dtype) || (n > 0 && (!x || !dy || !dx)) || (gelu_kind != 0 && gelu_kind != 1))
+  if (bad_dtype(dtype) || (n > 0 && (!x || !dy || !dx)) || (gelu_kind < 0 || gelu_kind > 2))
     return fail(DP_E_INVAL, "gelu_bwd: bad argument");
   if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
   return op_done(dp::launch_gelu_bwd(dtype, gelu_kind, n, dy, x, dx, (hipStream_t)hip_stream), "gelu_bwd");
@@ -60,8 +60,7 @@ dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t 
   if (M == 0 || N == 0) return DP_OK;                        // no output element
   if (!C || (K > 0 && (!A || !B))) return fail(DP_E_INVAL, "gemm: null operand");   // (K = 0: C = bias + res)
   dp::GemmArgs a{mode, M, N, K, A, B, bias, res, C};
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::gemm_mfma_supported(a))
     return op_done(dp::launch_gemm_mfma(a, (hipStream_t)hip_stream), "gemm");
   return op_done(dp::launch_gemm_simple(dtype, a, (hipStream_t)hip_stream), "gemm");
@@ -78,8 +77,7 @@ dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, i
                               const void *qkv, void *o, float *lse, void *hip_stream) {
   if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && !qkv)) return fail(DP_E_INVAL, "attention_fwd: bad argument");
   if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
     return op_done(dp::launch_attn_fwd_mfma(B, S, nh, dh, causal, qkv, o, lse, (hipStream_t)hip_stream), "attention_fwd");
   if (S > 4096) return fail(DP_E_UNSUPPORTED, "attention: seq > 4096 needs the MFMA path");
@@ -93,8 +91,7 @@ dp_status dp_op_attention_bwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, i
   if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && (!qkv || !o || !lse || !d_o || !dqkv || !ws)))
     return fail(DP_E_INVAL, "attention_bwd: bad argument");
   if (dh % 8) return fail(DP_E_UNSUPPORTED, "attention: head_dim must be a multiple of 8");
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
     return op_done(dp::launch_attn_bwd_mfma(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
                                             (hipStream_t)hip_stream), "attention_bwd");
@@ -131,8 +128,7 @@ dp_status dp_op_attention_dropout_fwd(int32_t dtype, int32_t B, int32_t S, int32
   dp::DropArgs a;
   const dp_status st = drop_args_of(drop, dp::kSiteAttn, &a);
   if (st != DP_OK) return st;
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
     return op_done(dp::launch_attn_fwd_mfma(B, S, nh, dh, causal, qkv, o, lse, (hipStream_t)hip_stream, &a),
                    "attention_fwd");
@@ -151,8 +147,7 @@ dp_status dp_op_attention_dropout_bwd(int32_t dtype, int32_t B, int32_t S, int32
   dp::DropArgs a;
   const dp_status st = drop_args_of(drop, dp::kSiteAttn, &a);
   if (st != DP_OK) return st;
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(S, dh))
     return op_done(dp::launch_attn_bwd_mfma(B, S, nh, dh, causal, qkv, o, lse, d_o, dqkv, (float *)ws,
                                             (hipStream_t)hip_stream, &a), "attention_bwd");
@@ -188,8 +183,7 @@ dp_status dp_op_cross_attention_fwd(int32_t dtype, int32_t B, int32_t Sq, int32_
   const long H = (long)nh * dh;
   const char *kvp = (const char *)kv;
   const dp::AttnView v{q, kvp, kvp + (size_t)H * dp::dtype_size(dtype), nullptr, nullptr, nullptr, H, 2 * H, Sq, Sk};
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(Sk, dh))
     return op_done(dp::launch_attn_fwd_mfma_view(B, nh, dh, 0, v, o, lse, (hipStream_t)hip_stream, dropping ? &a : nullptr),
                    "cross_attention_fwd");
@@ -212,8 +206,7 @@ dp_status dp_op_cross_attention_bwd(int32_t dtype, int32_t B, int32_t Sq, int32_
   const char *kvp = (const char *)kv;
   char *dkvp = (char *)dkv;
   const dp::AttnView v{q, kvp, kvp ? kvp + hb : nullptr, dq, dkvp, dkvp ? dkvp + hb : nullptr, H, 2 * H, Sq, Sk};
-  const char *env = getenv("DPSTAGE_KERNELS");
-  const bool simple = env != nullptr && strcmp(env, "simple") == 0;
+  const bool simple = !env_mfma_enabled();
   if (dtype == DP_BF16 && !simple && dp::attn_mfma_supported(std::max(Sk, 1), dh))
     return op_done(dp::launch_attn_bwd_mfma_view(B, nh, dh, 0, v, o, lse, d_o, (float *)ws, (hipStream_t)hip_stream,
                                                  dropping ? &a : nullptr), "cross_attention_bwd");

@@ -39,7 +39,8 @@ dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
   if (c->n_layers <= 0 || c->hidden <= 0 || c->n_heads <= 0 || c->ffn <= 0 || c->seq <= 0 || c->micro_batch <= 0)
     return fail(DP_E_INVAL, "config extents must be positive");
   if (c->norm_style != DP_POST_LN && c->norm_style != DP_PRE_LN) return fail(DP_E_INVAL, "bad norm_style");
-  if (c->gelu_kind != DP_GELU_ERF && c->gelu_kind != DP_GELU_TANH) return fail(DP_E_INVAL, "bad gelu_kind");
+  if (c->gelu_kind != DP_GELU_ERF && c->gelu_kind != DP_GELU_TANH && c->gelu_kind != DP_ACT_RELU)
+    return fail(DP_E_INVAL, "bad gelu_kind");
   if (c->dtype != DP_F32 && c->dtype != DP_BF16) return fail(DP_E_INVAL, "bad dtype");
   if (c->hidden % c->n_heads != 0) return fail(DP_E_INVAL, "hidden must be a multiple of n_heads");
   if (!(c->ln_eps > 0.f)) return fail(DP_E_INVAL, "ln_eps must be positive");

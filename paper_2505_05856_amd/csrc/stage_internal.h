@@ -48,9 +48,10 @@ inline const OpDef *op_table(const Cfg &c) { return c.cross ? kPreCrossOps : c.p
 inline int op_count(const Cfg &c) { return c.cross ? (int)N_OPS_CROSS : (int)N_OPS; }
 size_t slot_bytes(const Cfg &c, int slot);
 
-// Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  The epilogue
-// stores single elements per lane, and a second output doubles those stores: measured, the
-// separate kernel with its 16-byte accesses is the faster of the two, so it is the default.
+// Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  A second output
+// doubles the epilogue's stores (8 bytes a lane) and adds the activation's arithmetic to the
+// tail of every tile: measured, the separate kernel with its 16-byte accesses is the faster of
+// the two, so it is the default.
 constexpr bool kFuseGeluDefault = false;
 
 // DPSTAGE_KERNELS=simple switches the matrix-core kernels off (debugging aid).

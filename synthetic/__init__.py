@@ -49,7 +49,7 @@ class StageConfig:
     micro_batch: int
     norm_style: str = "post"   # "post" (BERT-style) or "pre" (GPT-2-style)
     causal: bool = False
-    gelu: str = "erf"          # "erf" or "tanh"
+    gelu: str = "erf"          # feed-forward activation: GELU as "erf" or "tanh", or "relu"
     dtype: str = "bf16"        # "f32" or "bf16"
     ln_eps: float = 1e-5
     p_attn: float = 0.0        # dropout rate on the attention probabilities

@@ -13,6 +13,7 @@ from oracle import stage as O
 from paper_2505_05856_amd import binding as B
 from paper_2505_05856_amd.harness import StageRunner, upload, download
 from paper_2505_05856_amd.harness import to_binding_config as to_bc
+from test_stage_gpu import relu_in_bf16
 
 pytestmark = pytest.mark.gpu
 BOUND = {"f32": 1e-4, "bf16": 2e-2}
@@ -33,8 +34,10 @@ def compare(cfg, run, ref, bound=None):
     bound = bound or BOUND[cfg.dtype]
     y, dx, g = run.results()
     yr, dxr, dmr, gr = ref
-    worst = {"Y": O.max_rel_err(y, yr), "dX": O.max_rel_err(dx, dxr), "dMem": O.max_rel_err(download(run.d_mem), dmr)}
-    for l in range(cfg.n_layers):
+    worst = {"Y": O.max_rel_err(y, yr)}
+    if not relu_in_bf16(cfg):      # (see test_stage_gpu.relu_in_bf16: those gradients have no meaningful reference)
+        worst.update({"dX": O.max_rel_err(dx, dxr), "dMem": O.max_rel_err(download(run.d_mem), dmr)})
+    for l in range(cfg.n_layers if not relu_in_bf16(cfg) else 0):
         for n in NAMES:
             worst[f"L{l}.{n}"] = O.max_rel_err(g[l][n], gr[l][n])
     bad = {k: v for k, v in worst.items() if not (v <= bound)}
@@ -48,10 +51,11 @@ SMALL = [
     dec(3, 128, 2, 256, 96, 130, 2, "bf16"),
     dec(2, 256, 2, 520, 130, 77, 2, "bf16", gelu="tanh"),      # head dimension 128, ragged extents
     dec(2, 192, 3, 384, 200, 1, 1, "bf16", causal=False),       # a memory of one position
+    dec(2, 128, 2, 256, 64, 50, 2, "bf16", gelu="relu"),         # T5's feed-forward activation
 ]
 
 
-@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.dtype}-H{c.hidden}-S{c.seq}-M{c.mem_seq}")
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.dtype}-H{c.hidden}-S{c.seq}-M{c.mem_seq}-{c.gelu}")
 def test_every_plan_same_bits_and_the_oracles_numbers(cfg):
     w = syn.make_weights(cfg, sigma=0.05)
     x, dy = syn.make_activations(cfg)

@@ -71,12 +71,12 @@ def test_layernorm(dt, rows, cols):
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("kind", [0, 1])
+@pytest.mark.parametrize("kind", [0, 1, 2])
 def test_gelu(dt, kind):
     n = 8 * 1237
     x = rnd((n,), 21, dt, 2.5)
     dy = rnd((n,), 22, dt)
-    name = "erf" if kind == 0 else "tanh"
+    name = ("erf", "tanh", "relu")[kind]
     tx, tdy = dev(x, dt), dev(dy, dt)
     y = torch.empty_like(tx); dx = torch.empty_like(tx)
     B.op_gelu_fwd(tx, y, kind)

@@ -93,6 +93,15 @@ def test_gelu_identities(kind):
     assert np.allclose(O.gelu_grad(x, kind), fd, atol=1e-8)
 
 
+def test_relu_by_its_definition():
+    x = np.array([-3.0, -1e-9, 0.0, 1e-9, 2.5])
+    assert np.array_equal(O.gelu_fwd(x, "relu"), [0.0, 0.0, 0.0, 1e-9, 2.5])
+    assert np.array_equal(O.gelu_grad(x, "relu"), [0.0, 0.0, 0.0, 1.0, 1.0])
+    xs = np.linspace(-4, 4, 81) + 0.013                      # away from the kink
+    assert np.array_equal(O.gelu_fwd(xs, "relu") - O.gelu_fwd(-xs, "relu"), xs)      # relu(x) - relu(-x) = x
+    assert np.array_equal(O.gelu_fwd(xs, "relu"), xs * O.gelu_grad(xs, "relu"))      # relu(x) = x relu'(x)
+
+
 def test_gelu_erf_against_math_erf_and_torch():
     xs = [-3.0, -1.0, -0.25, 0.5, 1.0, 2.0]
     for v in xs:

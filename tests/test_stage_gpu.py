@@ -20,12 +20,24 @@ def oracle_step(cfg, w, x, dy, dtype=np.float64):
     return O.stage_step(st, w, x, dy, dtype=dtype)
 
 
+def relu_in_bf16(cfg):
+    """ReLU's derivative is a decision, x > 0, on a saved tensor.  With bf16 storage the two sides hold values one
+    rounding apart, the elements nearest zero decide differently (a few in ten thousand), and each such flip moves
+    a gradient by a whole term: at these sizes 5-10 % of a weight-gradient column, whichever two precisions are
+    compared (the oracle in fp32 against itself in fp64, both storing bf16, differ as much).  Such a stage is held
+    to the oracle in its output, to the bound in fp32, and to identical bits across plans; its bf16 gradients have
+    no meaningful reference."""
+    return cfg.gelu == "relu" and cfg.dtype == "bf16"
+
+
 def compare(cfg, got, ref, bound=None):
     bound = bound or BOUND[cfg.dtype]
     y, dx, g = got
     yr, dxr, gr = ref
-    worst = {"Y": O.max_rel_err(y, yr), "dX": O.max_rel_err(dx, dxr)}
-    for l in range(cfg.n_layers):
+    worst = {"Y": O.max_rel_err(y, yr)}
+    if not relu_in_bf16(cfg):
+        worst["dX"] = O.max_rel_err(dx, dxr)
+    for l in range(cfg.n_layers if not relu_in_bf16(cfg) else 0):
         for n in syn.WEIGHT_NAMES:
             worst[f"L{l}.{n}"] = O.max_rel_err(g[l][n], gr[l][n])
     bad = {k: v for k, v in worst.items() if not (v <= bound)}
@@ -65,10 +77,12 @@ SMALL = [
     syn.StageConfig(3, 128, 2, 256, 96, 2, "post", False, "erf", "bf16"),
     syn.StageConfig(2, 256, 2, 520, 130, 2, "pre", True, "tanh", "bf16"),     # dh 128, ragged extents
     syn.StageConfig(2, 192, 3, 384, 200, 1, "post", True, "erf", "bf16"),
+    syn.StageConfig(2, 64, 2, 128, 40, 3, "pre", True, "relu", "f32"),
+    syn.StageConfig(2, 128, 2, 256, 96, 2, "post", False, "relu", "bf16"),
 ]
 
 
-@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.norm_style}-{c.dtype}-H{c.hidden}-S{c.seq}")
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.norm_style}-{c.dtype}-H{c.hidden}-S{c.seq}-{c.gelu}")
 @pytest.mark.parametrize("sharp", [False, True])
 def test_small_stages_every_plan(cfg, sharp):
     w, x, dy = make(cfg, sharp=sharp, sigma=0.05)
