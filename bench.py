@@ -47,12 +47,12 @@ def cpu_baseline(cfg, weights, x, dy, budget_s=30.0, mem=None):
         if cfg.mem_seq > 0:
             from oracle import decoder as Dc
             st = Dc.DecoderStage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
-                                 cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden)
+                                 cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden, norm=cfg.norm)
             t0 = time.perf_counter()
             Dc.decoder_step(st, weights[:n_layers], x, mem, dy, dtype=np.float64)
             return time.perf_counter() - t0
         st = O.Stage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
-                     cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden)
+                     cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden, norm=cfg.norm)
         t0 = time.perf_counter()
         O.stage_step(st, weights[:n_layers], x, dy, dtype=np.float64)
         return time.perf_counter() - t0

@@ -61,6 +61,10 @@ typedef enum { DP_POST_LN = 0, DP_PRE_LN = 1 } dp_norm_style;
 /* The feed-forward activation: GELU in its exact or tanh form, or ReLU (derivative 0 at 0). */
 typedef enum { DP_GELU_ERF = 0, DP_GELU_TANH = 1, DP_ACT_RELU = 2 } dp_gelu_kind;
 typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+/* What the layers' normalisations compute: LayerNorm, or RMSNorm (T5's: no mean is subtracted,
+ * y = gamma * x / sqrt(mean(x^2) + eps) + beta; a model without the additive term passes beta = 0
+ * and ignores its gradient).  The *_STATS slots then hold 0 where the mean would be. */
+typedef enum { DP_NORM_LAYER = 0, DP_NORM_RMS = 1 } dp_norm_kind;
 
 /* Saved tensors ("slots") of one layer, in plan order.  T = micro_batch*seq.
  *   X_IN      [T,H]   layer input (stage input for layer 0; caller memory there)
@@ -129,6 +133,7 @@ typedef struct {
   float ln_eps;
   float p_attn, p_hidden; /* dropout rates in [0, 1); 0 = none */
   int32_t mem_seq;        /* 0: no cross-attention block; > 0: length of the encoder memory */
+  int32_t norm_kind;      /* dp_norm_kind */
 } dp_stage_config;
 
 /* Device pointers.  Linear weights are [in, out] row-major (y = x*W + b);
@@ -481,6 +486,14 @@ dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const v
                               const float *stats, const void *gamma, const void *dres /*nullable*/,
                               void *dx, void *dgamma, void *dbeta, void *dx_colsum /*nullable*/, void *ws,
                               void *hip_stream);
+/* The same two with RMSNorm (DP_NORM_RMS): y = gamma * x / sqrt(mean(x^2) + eps) + beta, no mean
+ * subtracted; stats holds (0, 1/sqrt(mean(x^2) + eps)). */
+dp_status dp_op_rmsnorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x,
+                            const void *gamma, const void *beta, void *y, float *stats, void *hip_stream);
+dp_status dp_op_rmsnorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
+                            const float *stats, const void *gamma, const void *dres /*nullable*/,
+                            void *dx, void *dgamma, void *dbeta, void *dx_colsum /*nullable*/, void *ws,
+                            void *hip_stream);
 dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream);
 /* dx = dy * gelu'(x) */
 dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,

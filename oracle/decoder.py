@@ -38,7 +38,7 @@ CROSS_WEIGHTS = ("lnc_g", "lnc_b", "w_qc", "b_qc", "w_kvc", "b_kvc", "w_oc", "b_
 
 class DecoderStage:
     def __init__(self, n_layers, hidden, n_heads, ffn, seq, mem_seq, micro_batch, causal=True, gelu="erf", eps=1e-5,
-                 p_attn=0.0, p_hidden=0.0):
+                 p_attn=0.0, p_hidden=0.0, norm="layer"):
         self.L, self.H, self.nh, self.F = n_layers, hidden, n_heads, ffn
         self.S, self.Sm, self.B = seq, mem_seq, micro_batch
         self.causal, self.gelu, self.eps = bool(causal), gelu, eps
@@ -47,6 +47,7 @@ class DecoderStage:
         # projections that end in a residual add
         self.p_attn, self.p_hidden = float(p_attn), float(p_hidden)
         self.rng = (0, 0)
+        self.norm_fwd, self.norm_bwd = _ops.NORMS[norm]      # LayerNorm, or T5's RMSNorm
 
     def set_rng(self, seed: int, mb: int):
         self.rng = (int(seed), int(mb))
@@ -70,17 +71,17 @@ class DecoderStage:
     def layer_fwd(self, x, mem, w, l=0):
         ks, kc, sc = self._keeps(l)
         s = {"X_IN": x}
-        s["LN1_OUT"], *s["LN1_STATS"] = _ln(x, w["ln1_g"], w["ln1_b"], self.eps)
+        s["LN1_OUT"], *s["LN1_STATS"] = self.norm_fwd(x, w["ln1_g"], w["ln1_b"], self.eps)
         s["QKV"] = _ops.linear_fwd(s["LN1_OUT"], w["w_qkv"], w["b_qkv"])
         s["ATTN_OUT"], _ = _ops.attention_fwd(s["QKV"], self.B, self.S, self.nh, self.causal, ks, sc)
         s["RES1"] = x + self._drop(_ops.linear_fwd(s["ATTN_OUT"], w["w_o"], w["b_o"]), l, _dropout.SITE_PROJ)
-        s["LNC_OUT"], *s["LNC_STATS"] = _ln(s["RES1"], w["lnc_g"], w["lnc_b"], self.eps)
+        s["LNC_OUT"], *s["LNC_STATS"] = self.norm_fwd(s["RES1"], w["lnc_g"], w["lnc_b"], self.eps)
         s["Q_C"] = _ops.linear_fwd(s["LNC_OUT"], w["w_qc"], w["b_qc"])
         s["KV_C"] = _ops.linear_fwd(mem, w["w_kvc"], w["b_kvc"])
         s["ATTN_C_OUT"], _ = _ops.cross_attention_fwd(s["Q_C"], s["KV_C"], self.B, self.S, self.Sm, self.nh, kc, sc)
         s["RES_C"] = s["RES1"] + self._drop(_ops.linear_fwd(s["ATTN_C_OUT"], w["w_oc"], w["b_oc"]), l,
                                             _dropout.SITE_CROSS_PROJ)
-        s["LN2_OUT"], *s["LN2_STATS"] = _ln(s["RES_C"], w["ln2_g"], w["ln2_b"], self.eps)
+        s["LN2_OUT"], *s["LN2_STATS"] = self.norm_fwd(s["RES_C"], w["ln2_g"], w["ln2_b"], self.eps)
         s["FC1_OUT"] = _ops.linear_fwd(s["LN2_OUT"], w["w_fc1"], w["b_fc1"])
         s["GELU_OUT"] = _ops.gelu_fwd(s["FC1_OUT"], self.gelu)
         y = s["RES_C"] + self._drop(_ops.linear_fwd(s["GELU_OUT"], w["w_fc2"], w["b_fc2"]), l, _dropout.SITE_FC2)
@@ -94,25 +95,20 @@ class DecoderStage:
         d_gelu, g["w_fc2"], g["b_fc2"] = _ops.linear_bwd(self._drop(dy, l, _dropout.SITE_FC2), s["GELU_OUT"], w["w_fc2"])
         d_f = d_gelu * _ops.gelu_grad(s["FC1_OUT"], self.gelu)
         d_n, g["w_fc1"], g["b_fc1"] = _ops.linear_bwd(d_f, s["LN2_OUT"], w["w_fc1"])
-        d_ln, g["ln2_g"], g["ln2_b"] = _ops.layernorm_bwd(d_n, s["RES_C"], *s["LN2_STATS"], w["ln2_g"])
+        d_ln, g["ln2_g"], g["ln2_b"] = self.norm_bwd(d_n, s["RES_C"], *s["LN2_STATS"], w["ln2_g"])
         d_rc = dy + d_ln
         d_oc, g["w_oc"], g["b_oc"] = _ops.linear_bwd(self._drop(d_rc, l, _dropout.SITE_CROSS_PROJ), s["ATTN_C_OUT"],
                                                      w["w_oc"])
         d_qc, d_kvc = _ops.cross_attention_bwd(d_oc, s["Q_C"], s["KV_C"], self.B, self.S, self.Sm, self.nh, kc, sc)
         d_mem, g["w_kvc"], g["b_kvc"] = _ops.linear_bwd(d_kvc, mem, w["w_kvc"])
         d_c, g["w_qc"], g["b_qc"] = _ops.linear_bwd(d_qc, s["LNC_OUT"], w["w_qc"])
-        d_ln, g["lnc_g"], g["lnc_b"] = _ops.layernorm_bwd(d_c, s["RES1"], *s["LNC_STATS"], w["lnc_g"])
+        d_ln, g["lnc_g"], g["lnc_b"] = self.norm_bwd(d_c, s["RES1"], *s["LNC_STATS"], w["lnc_g"])
         d_r1 = d_rc + d_ln
         d_o, g["w_o"], g["b_o"] = _ops.linear_bwd(self._drop(d_r1, l, _dropout.SITE_PROJ), s["ATTN_OUT"], w["w_o"])
         d_qkv = _ops.attention_bwd(d_o, s["QKV"], self.B, self.S, self.nh, self.causal, ks, sc)
         d_a, g["w_qkv"], g["b_qkv"] = _ops.linear_bwd(d_qkv, s["LN1_OUT"], w["w_qkv"])
-        d_ln, g["ln1_g"], g["ln1_b"] = _ops.layernorm_bwd(d_a, s["X_IN"], *s["LN1_STATS"], w["ln1_g"])
+        d_ln, g["ln1_g"], g["ln1_b"] = self.norm_bwd(d_a, s["X_IN"], *s["LN1_STATS"], w["ln1_g"])
         return d_r1 + d_ln, d_mem, g
-
-
-def _ln(x, gamma, beta, eps):
-    y, mu, r = _ops.layernorm_fwd(x, gamma, beta, eps)
-    return y, mu, r
 
 
 def decoder_step(stage: DecoderStage, weights: List[Dict[str, np.ndarray]], x, mem, dy, dtype=np.float64):

@@ -40,7 +40,8 @@ class DpError(RuntimeError):
 class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_heads", "ffn", "seq", "micro_batch",
                                          "norm_style", "causal", "gelu_kind", "dtype")] + [("ln_eps", C.c_float), ("p_attn", C.c_float),
-                                                                                 ("p_hidden", C.c_float), ("mem_seq", C.c_int32)]
+                                                                                 ("p_hidden", C.c_float), ("mem_seq", C.c_int32),
+                                                                                 ("norm_kind", C.c_int32)]
 
 
 class LayerPtrs(C.Structure):
@@ -145,6 +146,8 @@ def lib() -> C.CDLL:
     L.dp_op_workspace_bytes.argtypes = [i32, i32]
     L.dp_op_layernorm_fwd.argtypes = [i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
     L.dp_op_layernorm_bwd.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.dp_op_rmsnorm_fwd.argtypes = [i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
+    L.dp_op_rmsnorm_bwd.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dp_op_gelu_fwd.argtypes = [i32, i32, sz, vp, vp, vp]
     L.dp_op_gelu_bwd.argtypes = [i32, i32, sz, vp, vp, vp, vp]
     L.dp_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -168,7 +171,8 @@ def lib() -> C.CDLL:
                  "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd",
-                 "dp_op_cross_attention_fwd", "dp_op_cross_attention_bwd"):
+                 "dp_op_cross_attention_fwd", "dp_op_cross_attention_bwd",
+                 "dp_op_rmsnorm_fwd", "dp_op_rmsnorm_bwd"):
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -180,10 +184,10 @@ def _check(code: int):
 
 
 def make_config(n_layers, hidden, n_heads, ffn, seq, micro_batch, norm_style="post", causal=False,
-                gelu="erf", dtype="bf16", ln_eps=1e-5, p_attn=0.0, p_hidden=0.0, mem_seq=0) -> StageConfig:
+                gelu="erf", dtype="bf16", ln_eps=1e-5, p_attn=0.0, p_hidden=0.0, mem_seq=0, norm="layer") -> StageConfig:
     return StageConfig(n_layers, hidden, n_heads, ffn, seq, micro_batch,
                        {"post": 0, "pre": 1}[norm_style], int(bool(causal)), {"erf": 0, "tanh": 1, "relu": 2}[gelu],
-                       {"f32": 0, "bf16": 1}[dtype], ln_eps, p_attn, p_hidden, mem_seq)
+                       {"f32": 0, "bf16": 1}[dtype], ln_eps, p_attn, p_hidden, mem_seq, {"layer": 0, "rms": 1}[norm])
 
 
 def _plan_buf(plan):
@@ -426,6 +430,17 @@ def op_layernorm_bwd(dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, dx_colsum
     _check(lib().dp_op_layernorm_bwd(_dt(x), x.shape[0], x.shape[1], _ptr(dy), _ptr(x), _ptr(stats), _ptr(gamma),
                                      _ptr(dres), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum), _ptr(ws),
                                      _stream_ptr(stream)))
+
+
+def op_rmsnorm_fwd(x, gamma, beta, eps, y, stats, stream=None):
+    _check(lib().dp_op_rmsnorm_fwd(_dt(x), x.shape[0], x.shape[1], eps, _ptr(x), _ptr(gamma), _ptr(beta),
+                                   _ptr(y), _ptr(stats), _stream_ptr(stream)))
+
+
+def op_rmsnorm_bwd(dy, x, stats, gamma, dres, dx, dgamma, dbeta, ws, dx_colsum=None, stream=None):
+    _check(lib().dp_op_rmsnorm_bwd(_dt(x), x.shape[0], x.shape[1], _ptr(dy), _ptr(x), _ptr(stats), _ptr(gamma),
+                                   _ptr(dres), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum), _ptr(ws),
+                                   _stream_ptr(stream)))
 
 
 def op_gelu_fwd(x, y, kind=0, stream=None):

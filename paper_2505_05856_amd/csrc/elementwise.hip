@@ -17,7 +17,10 @@ namespace dp {
 template <typename T, int NC>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
                                                      const T *__restrict__ beta, T *__restrict__ y,
-                                                     float *__restrict__ stats, int rows, int cols, float eps) {
+                                                     float *__restrict__ stats, int rows, int cols, float eps,
+                                                     int rms) {
+  // rms: no mean is subtracted (y = gamma * x / sqrt(mean(x^2) + eps) + beta); the statistics then
+  // hold 0 where the mean would be, which is all the backward needs to know about it
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -34,7 +37,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, co
     }
   }
   const float inv_n = 1.0f / (float)cols;
-  const float mean = wave_sum(sum) * inv_n;
+  const float mean = rms ? 0.f : wave_sum(sum) * inv_n;
   float sq = 0.f;
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
@@ -77,7 +80,9 @@ template <typename T, int NC, bool SUMDX>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
                                                      const float *__restrict__ stats, const T *__restrict__ gamma,
                                                      const T *__restrict__ dres, T *dx,
-                                                     float *__restrict__ part, int rows, int cols, int rpb) {
+                                                     float *__restrict__ part, int rows, int cols, int rpb, int rms) {
+  // rms: the forward subtracted no mean (its statistics say mean = 0), so the term that carries the
+  // derivative of the mean, mean(g), drops out: dx = rstd (g - xhat mean(g xhat))
   constexpr int NV = SUMDX ? 3 : 2;
   __shared__ float red[4][NV][512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -118,7 +123,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
           }
         }
       }
-      const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+      const float m1 = rms ? 0.f : wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
   #pragma unroll
       for (int c = 0; c < NC; ++c) {
         const int col = (c * 64 + lane) * 8;
@@ -164,7 +169,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
           }
         }
       }
-      const float m1 = wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+      const float m1 = rms ? 0.f : wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
   #pragma unroll
       for (int c = 0; c < NC; ++c) {
         const int col = (c * 64 + lane) * 8;
@@ -229,7 +234,7 @@ __global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may ali
                                                           const float *__restrict__ stats,
                                                           const T *__restrict__ gamma, const T *__restrict__ dres,
                                                           T *dx, float *__restrict__ part, int rows, int cols,
-                                                          int rpb) {
+                                                          int rpb, int rms) {
   constexpr int NV = SUMDX ? 3 : 2;
   __shared__ float red[2][2][4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may ali
     const int slot = (row - row0) & 1;
     if (lane == 0) { red[slot][0][wave] = s1; red[slot][1][wave] = s2; }
     __syncthreads();
-    const float m1 = (((red[slot][0][0] + red[slot][0][1]) + red[slot][0][2]) + red[slot][0][3]) * inv_n;
+    const float m1 = rms ? 0.f : (((red[slot][0][0] + red[slot][0][1]) + red[slot][0][2]) + red[slot][0][3]) * inv_n;
     const float m2 = (((red[slot][1][0] + red[slot][1][1]) + red[slot][1][2]) + red[slot][1][3]) * inv_n;
 #pragma unroll
     for (int c = 0; c < NP; ++c) {
@@ -545,11 +550,11 @@ static int ln_chunks(int cols) {
 
 template <typename T>
 static hipError_t ln_fwd_t(int rows, int cols, float eps, const void *x, const void *gamma, const void *beta,
-                           void *y, float *stats, hipStream_t s) {
+                           void *y, float *stats, hipStream_t s, int rms) {
   const dim3 grid((rows + 3) / 4), block(256);
 #define DP_LN_FWD(NC)                                                                                       \
   hipLaunchKernelGGL((ln_fwd_kernel<T, NC>), grid, block, 0, s, (const T *)x, (const T *)gamma,             \
-                     (const T *)beta, (T *)y, stats, rows, cols, eps)
+                     (const T *)beta, (T *)y, stats, rows, cols, eps, rms)
   switch (ln_chunks(cols)) {
     case 1: DP_LN_FWD(1); break;
     case 2: DP_LN_FWD(2); break;
@@ -562,10 +567,10 @@ static hipError_t ln_fwd_t(int rows, int cols, float eps, const void *x, const v
 }
 
 hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x, const void *gamma,
-                         const void *beta, void *y, float *stats, hipStream_t s) {
+                         const void *beta, void *y, float *stats, hipStream_t s, bool rms) {
   if (rows <= 0) return hipSuccess;
-  return dtype == kBF16 ? ln_fwd_t<bf16>(rows, cols, eps, x, gamma, beta, y, stats, s)
-                        : ln_fwd_t<float>(rows, cols, eps, x, gamma, beta, y, stats, s);
+  return dtype == kBF16 ? ln_fwd_t<bf16>(rows, cols, eps, x, gamma, beta, y, stats, s, rms ? 1 : 0)
+                        : ln_fwd_t<float>(rows, cols, eps, x, gamma, beta, y, stats, s, rms ? 1 : 0);
 }
 
 // second pass now, or left to the caller as a job
@@ -581,17 +586,17 @@ static hipError_t reduce_or_defer(const float *part, int nb, int width, int seg,
 template <typename T, bool SUMDX>
 static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, const float *stats,
                            const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
-                           void *ws, hipStream_t s, ReduceJob *job) {
+                           void *ws, hipStream_t s, ReduceJob *job, int rms) {
   int rpb;
   const int nb = row_blocks(rows, 8, &rpb);
   const int nv = SUMDX ? 3 : 2;
   float *part = (float *)ws;
 #define DP_LN_BWD(NC)                                                                                       \
   hipLaunchKernelGGL((ln_bwd_kernel<T, NC, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, \
-                     stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
+                     stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb, rms)
 #define DP_LN_BWD_WIDE(NP)                                                                                  \
   hipLaunchKernelGGL((ln_bwd_wide_kernel<T, NP, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy,          \
-                     (const T *)x, stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb)
+                     (const T *)x, stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb, rms)
   switch (ln_chunks(cols)) {
     case 1: DP_LN_BWD(1); break;
     case 2: DP_LN_BWD(2); break;
@@ -614,7 +619,8 @@ static hipError_t zero_vec(int dtype, void *p, int n, hipStream_t s) {
 
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
                          const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
-                         void *ws, hipStream_t s, ReduceJob *job) {
+                         void *ws, hipStream_t s, ReduceJob *job, bool rms) {
+  const int r = rms ? 1 : 0;
   if (job != nullptr) job->nb = 0;
   if (rows <= 0) {
     hipError_t e = zero_vec(dtype, dgamma, cols, s);
@@ -624,11 +630,11 @@ hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const vo
   }
   if (dxsum != nullptr)
     return dtype == kBF16
-               ? ln_bwd_t<bf16, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job)
-               : ln_bwd_t<float, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job);
+               ? ln_bwd_t<bf16, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job, r)
+               : ln_bwd_t<float, true>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dxsum, ws, s, job, r);
   return dtype == kBF16
-             ? ln_bwd_t<bf16, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s, job)
-             : ln_bwd_t<float, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s, job);
+             ? ln_bwd_t<bf16, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s, job, r)
+             : ln_bwd_t<float, false>(rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, nullptr, ws, s, job, r);
 }
 
 template <typename T>

@@ -90,11 +90,12 @@ constexpr int kMaxReduceJobs = 8;
 hipError_t launch_reduce_jobs(int dtype, const ReduceJob *jobs, int n, hipStream_t s);
 
 hipError_t launch_ln_fwd(int dtype, int rows, int cols, float eps, const void *x, const void *gamma,
-                         const void *beta, void *y, float *stats, hipStream_t s);
+                         const void *beta, void *y, float *stats, hipStream_t s, bool rms = false);
 // dxsum (nullable): receives the column sums of the stored dx
 hipError_t launch_ln_bwd(int dtype, int rows, int cols, const void *dy, const void *x, const float *stats,
                          const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta, void *dxsum,
-                         void *ws, hipStream_t s, ReduceJob *job = nullptr);
+                         void *ws, hipStream_t s, ReduceJob *job = nullptr, bool rms = false);
+// (rms: RMSNorm, i.e. no mean is subtracted; same kernels, see elementwise.hip)
 // dx = dy * gelu'(x) over [rows, cols] and dbias = column sums of the stored dx
 hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const void *dy, const void *x, void *dx,
                                   void *dbias, void *ws, hipStream_t s, ReduceJob *job = nullptr);

@@ -20,23 +20,42 @@ static dp_status op_done(hipError_t e, const char *what) {
 }
 static bool bad_dtype(int32_t d) { return d != DP_F32 && d != DP_BF16; }
 
-dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x, const void *gamma,
-                              const void *beta, void *y, float *stats, void *hip_stream) {
+static dp_status norm_fwd(bool rms, int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x,
+                          const void *gamma, const void *beta, void *y, float *stats, void *hip_stream) {
   if (!bad_dtype(dtype) && rows == 0) return DP_OK;   // nothing to do; the row pointers may be null
-  if (bad_dtype(dtype) || rows < 0 || !x || !gamma || !beta) return fail(DP_E_INVAL, "layernorm_fwd: bad argument");
-  if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
-  return op_done(dp::launch_ln_fwd(dtype, rows, cols, eps, x, gamma, beta, y, stats, (hipStream_t)hip_stream),
-                 "layernorm_fwd");
+  if (bad_dtype(dtype) || rows < 0 || !x || !gamma || !beta) return fail(DP_E_INVAL, "norm_fwd: bad argument");
+  if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "norm: cols must be a multiple of 8, <= 8192");
+  return op_done(dp::launch_ln_fwd(dtype, rows, cols, eps, x, gamma, beta, y, stats, (hipStream_t)hip_stream, rms),
+                 "norm_fwd");
 }
 
+static dp_status norm_bwd(bool rms, int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
+                          const float *stats, const void *gamma, const void *dres, void *dx, void *dgamma, void *dbeta,
+                          void *dx_colsum, void *ws, void *hip_stream) {
+  if (bad_dtype(dtype) || rows < 0 || !dgamma || !dbeta || (rows > 0 && (!dy || !x || !stats || !gamma || !dx || !ws)))
+    return fail(DP_E_INVAL, "norm_bwd: bad argument");   // (no rows: only the sums, which become zero, are touched)
+  if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "norm: cols must be a multiple of 8, <= 8192");
+  return op_done(dp::launch_ln_bwd(dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dx_colsum, ws,
+                                   (hipStream_t)hip_stream, nullptr, rms), "norm_bwd");
+}
+
+dp_status dp_op_layernorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x, const void *gamma,
+                              const void *beta, void *y, float *stats, void *hip_stream) {
+  return norm_fwd(false, dtype, rows, cols, eps, x, gamma, beta, y, stats, hip_stream);
+}
 dp_status dp_op_layernorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
                               const float *stats, const void *gamma, const void *dres, void *dx, void *dgamma,
                               void *dbeta, void *dx_colsum, void *ws, void *hip_stream) {
-  if (bad_dtype(dtype) || rows < 0 || !dgamma || !dbeta || (rows > 0 && (!dy || !x || !stats || !gamma || !dx || !ws)))
-    return fail(DP_E_INVAL, "layernorm_bwd: bad argument");   // (no rows: only the sums, which become zero, are touched)
-  if (!dp::ln_supported(dtype, cols)) return fail(DP_E_UNSUPPORTED, "layernorm: cols must be a multiple of 8, <= 8192");
-  return op_done(dp::launch_ln_bwd(dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dx_colsum, ws,
-                                   (hipStream_t)hip_stream), "layernorm_bwd");
+  return norm_bwd(false, dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dx_colsum, ws, hip_stream);
+}
+dp_status dp_op_rmsnorm_fwd(int32_t dtype, int32_t rows, int32_t cols, float eps, const void *x, const void *gamma,
+                            const void *beta, void *y, float *stats, void *hip_stream) {
+  return norm_fwd(true, dtype, rows, cols, eps, x, gamma, beta, y, stats, hip_stream);
+}
+dp_status dp_op_rmsnorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const void *dy, const void *x,
+                            const float *stats, const void *gamma, const void *dres, void *dx, void *dgamma,
+                            void *dbeta, void *dx_colsum, void *ws, void *hip_stream) {
+  return norm_bwd(true, dtype, rows, cols, dy, x, stats, gamma, dres, dx, dgamma, dbeta, dx_colsum, ws, hip_stream);
 }
 
 dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream) {

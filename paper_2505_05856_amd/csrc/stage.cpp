@@ -64,6 +64,8 @@ dp_status parse_cfg(const dp_stage_config *c, Cfg *o) {
     return fail(DP_E_UNSUPPORTED, "seq > 4096 is not supported for this head_dim/dtype");
   if (o->T > (1L << 24) || (long)o->T * std::max(o->F, 3 * o->H) > (1L << 40))
     return fail(DP_E_UNSUPPORTED, "micro_batch*seq too large");
+  if (c->norm_kind != DP_NORM_LAYER && c->norm_kind != DP_NORM_RMS) return fail(DP_E_INVAL, "bad norm_kind");
+  o->rms = c->norm_kind == DP_NORM_RMS;
   if (c->mem_seq < 0) return fail(DP_E_INVAL, "mem_seq must be >= 0");
   o->Sm = c->mem_seq; o->Tm = (long)c->micro_batch * c->mem_seq; o->cross = c->mem_seq > 0;
   o->nslots = o->cross ? DP_SLOTS_PER_LAYER_CROSS : DP_SLOTS_PER_LAYER;
@@ -567,7 +569,7 @@ struct Walk {
     prof_begin(DP_OPC_LN_BWD);
     if (live)
       check(dp::launch_ln_bwd(c.dtype, (int)c.T, c.H, dyp, x, (const float *)stats, gamma, dres, dx, dgamma, dbeta,
-                              dxsum, bptr(ws), cs, &job));
+                              dxsum, bptr(ws), cs, &job, c.rms));
     prof_end();
     defer_reduce(job, ws);
   }
@@ -593,7 +595,7 @@ struct Walk {
         prof_begin(DP_OPC_LN_FWD);
         if (live) {
           const void *g = d.op == OP_LN1 ? w->ln1_g : w->ln2_g, *b = d.op == OP_LN1 ? w->ln1_b : w->ln2_b;
-          check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), g, b, out0, (float *)out1, cs));
+          check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), g, b, out0, (float *)out1, cs, c.rms));
         }
         prof_end();
         break;
@@ -637,7 +639,7 @@ struct Walk {
         prof_begin(DP_OPC_LN_FWD);
         if (live) {
           const CrossW &x = wts->xw[(size_t)l];
-          check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), x.ln_g, x.ln_b, out0, (float *)out1, cs));
+          check(dp::launch_ln_fwd(c.dtype, (int)T, (int)H, c.eps, in(0), x.ln_g, x.ln_b, out0, (float *)out1, cs, c.rms));
         }
         prof_end();
         break;

@@ -30,6 +30,7 @@ struct Cfg {
   long Tm = 0;                     // micro_batch * Sm
   bool cross = false;
   int nslots = DP_SLOTS_PER_LAYER; // slots (and plan bytes) per layer
+  bool rms = false;                // the normalisations are RMSNorm
 };
 
 dp_status parse_cfg(const dp_stage_config *c, Cfg *o);

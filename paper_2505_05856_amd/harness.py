@@ -15,7 +15,7 @@ def to_binding_config(cfg) -> B.StageConfig:
     """`cfg` is a synthetic.StageConfig (duck-typed)."""
     return B.make_config(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch,
                          cfg.norm_style, cfg.causal, cfg.gelu, cfg.dtype, cfg.ln_eps, cfg.p_attn, cfg.p_hidden,
-                         getattr(cfg, "mem_seq", 0))
+                         getattr(cfg, "mem_seq", 0), getattr(cfg, "norm", "layer"))
 
 
 def torch_dtype(cfg):

@@ -55,6 +55,7 @@ class StageConfig:
     p_attn: float = 0.0        # dropout rate on the attention probabilities
     p_hidden: float = 0.0      # dropout rate after the attention projection and after FC2
     mem_seq: int = 0           # > 0: decoder stage, cross-attention over an encoder memory of this length
+    norm: str = "layer"        # what the normalisations compute: "layer" (LayerNorm) or "rms" (RMSNorm)
 
     @property
     def slots_per_layer(self) -> int:

@@ -20,13 +20,13 @@ BOUND = {"f32": 1e-4, "bf16": 2e-2}
 NAMES = syn.WEIGHT_NAMES + syn.CROSS_WEIGHT_NAMES
 
 
-def dec(L, H, nh, F, S, Sm, Bn, dtype, causal=True, gelu="erf"):
-    return syn.StageConfig(L, H, nh, F, S, Bn, "pre", causal, gelu, dtype, mem_seq=Sm)
+def dec(L, H, nh, F, S, Sm, Bn, dtype, causal=True, gelu="erf", norm="layer"):
+    return syn.StageConfig(L, H, nh, F, S, Bn, "pre", causal, gelu, dtype, mem_seq=Sm, norm=norm)
 
 
 def oracle_step(cfg, w, x, mem, dy):
     st = Dc.DecoderStage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
-                         cfg.causal, cfg.gelu, cfg.ln_eps)
+                         cfg.causal, cfg.gelu, cfg.ln_eps, norm=cfg.norm)
     return Dc.decoder_step(st, w, x, mem, dy)
 
 
@@ -52,10 +52,12 @@ SMALL = [
     dec(2, 256, 2, 520, 130, 77, 2, "bf16", gelu="tanh"),      # head dimension 128, ragged extents
     dec(2, 192, 3, 384, 200, 1, 1, "bf16", causal=False),       # a memory of one position
     dec(2, 128, 2, 256, 64, 50, 2, "bf16", gelu="relu"),         # T5's feed-forward activation
+    dec(2, 128, 2, 256, 64, 50, 2, "bf16", norm="rms"),          # T5's normalisation
+    dec(2, 64, 2, 128, 24, 30, 2, "f32", gelu="relu", norm="rms"),
 ]
 
 
-@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.dtype}-H{c.hidden}-S{c.seq}-M{c.mem_seq}-{c.gelu}")
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.dtype}-H{c.hidden}-S{c.seq}-M{c.mem_seq}-{c.gelu}-{c.norm}")
 def test_every_plan_same_bits_and_the_oracles_numbers(cfg):
     w = syn.make_weights(cfg, sigma=0.05)
     x, dy = syn.make_activations(cfg)

@@ -33,10 +33,13 @@ def ws_for(rows, cols):
     return torch.empty(B.op_workspace_bytes(rows, cols), dtype=torch.uint8, device=DEV)
 
 
+@pytest.mark.parametrize("kind", ["layer", "rms"])
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("rows,cols", [(1, 8), (7, 16), (130, 128), (37, 1600), (9, 4096), (5, 8192), (2, 2056),
                                        (1301, 4096), (270, 5000), (515, 8192)])
-def test_layernorm(dt, rows, cols):
+def test_layernorm(dt, rows, cols, kind):
+    fwd, bwd = O.NORMS[kind]
+    op_fwd, op_bwd = (B.op_layernorm_fwd, B.op_layernorm_bwd) if kind == "layer" else (B.op_rmsnorm_fwd, B.op_rmsnorm_bwd)
     x = rnd((rows, cols), 11, dt, 2.0) + 0.5
     x = syn.round_to_bf16(x) if dt == torch.bfloat16 else x
     g = rnd((cols,), 12, dt) * 0.1 + 1
@@ -44,26 +47,26 @@ def test_layernorm(dt, rows, cols):
     b = rnd((cols,), 13, dt, 0.1)
     dy = rnd((rows, cols), 14, dt)
     dres = rnd((rows, cols), 15, dt)
-    y_ref, mu, r = O.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)
-    dx_ref, dg_ref, db_ref = O.layernorm_bwd(dy.astype(np.float64), x.astype(np.float64), mu, r, g.astype(np.float64))
+    y_ref, mu, r = fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)
+    dx_ref, dg_ref, db_ref = bwd(dy.astype(np.float64), x.astype(np.float64), mu, r, g.astype(np.float64))
     tx, tg, tb, tdy, tres = (dev(a, dt) for a in (x, g, b, dy, dres))
     y = torch.empty_like(tx); stats = torch.empty(rows, 2, dtype=torch.float32, device=DEV)
-    B.op_layernorm_fwd(tx, tg, tb, 1e-5, y, stats)
+    op_fwd(tx, tg, tb, 1e-5, y, stats)
     assert O.max_rel_err(host(y), y_ref) < TOL[dt]
     assert np.allclose(host(stats)[:, 0], mu, atol=1e-5) and np.allclose(host(stats)[:, 1], r, rtol=1e-5)
     # stats only / y only
     stats2 = torch.zeros_like(stats)
-    B.op_layernorm_fwd(tx, tg, tb, 1e-5, None, stats2)
+    op_fwd(tx, tg, tb, 1e-5, None, stats2)
     assert torch.equal(stats, stats2)
     dx = torch.empty_like(tx); dg = torch.empty_like(tg); db = torch.empty_like(tb)
     ws = ws_for(rows, cols)
-    B.op_layernorm_bwd(tdy, tx, stats, tg, None, dx, dg, db, ws)
+    op_bwd(tdy, tx, stats, tg, None, dx, dg, db, ws)
     assert O.max_rel_err(host(dx), dx_ref) < TOL[dt]
     assert O.max_rel_err(host(dg), dg_ref) < TOL[dt] and O.max_rel_err(host(db), db_ref) < TOL[dt]
     # with the residual gradient added, written in place over dy
     dy2 = tdy.clone()
     dsum = torch.empty_like(tg)
-    B.op_layernorm_bwd(dy2, tx, stats, tg, tres, dy2, dg, db, ws, dx_colsum=dsum)
+    op_bwd(dy2, tx, stats, tg, tres, dy2, dg, db, ws, dx_colsum=dsum)
     assert O.max_rel_err(host(dy2), dx_ref + dres) < TOL[dt]
     assert O.max_rel_err(host(dg), dg_ref) < TOL[dt] and O.max_rel_err(host(db), db_ref) < TOL[dt]
     # column sums of dx as stored (a bias gradient): exact sum of the kernel's own output up to fp32 ordering

@@ -202,3 +202,61 @@ def test_attention_bwd_row_sums_vanish():
     dk = d[:, H:2 * H]
     # shifting every key by the same u changes nothing => sum_j dK_j = 0
     assert np.allclose(dk.sum(axis=0), 0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- RMSNorm
+def test_rmsnorm_closed_forms_and_its_layernorm_special_case():
+    rows, cols = 5, 16
+    x = rng.normal(size=(rows, cols)) * 3 + 1.0
+    g = 1 + 0.1 * rng.normal(size=cols); b = 0.1 * rng.normal(size=cols)
+    y, mu, r = O.rmsnorm_fwd(x, g, b, 1e-6)
+    assert np.array_equal(mu, np.zeros(rows))
+    xh = (y - b) / g
+    assert np.allclose((xh * xh).mean(axis=1), 1.0, atol=1e-5)                 # unit mean square per row
+    assert np.allclose(xh * np.sqrt((x * x).mean(axis=1) + 1e-6)[:, None], x)   # a pure rescaling of x
+    # scaling a row leaves y unchanged (eps -> 0); a constant row a gives sign(a)
+    y2, _, _ = O.rmsnorm_fwd(x * 7.5, g, b, 1e-12)
+    assert np.allclose(y2, O.rmsnorm_fwd(x, g, b, 1e-12)[0], atol=1e-9)
+    yc, _, _ = O.rmsnorm_fwd(np.full((1, cols), -2.0), np.ones(cols), np.zeros(cols), 0.0)
+    assert np.allclose(yc, -1.0)
+    # on rows whose mean is zero RMSNorm and LayerNorm are the same function, forward and backward
+    z = x - x.mean(axis=1, keepdims=True)
+    ya, ma, ra = O.layernorm_fwd(z, g, b, 1e-5)
+    yb, mb, rb = O.rmsnorm_fwd(z, g, b, 1e-5)
+    assert np.allclose(ya, yb, atol=1e-13) and np.allclose(ra, rb, atol=1e-13)
+    dy = rng.normal(size=(rows, cols))
+    dxa, dga, dba = O.layernorm_bwd(dy, z, ma, ra, g)
+    dxb, dgb, dbb = O.rmsnorm_bwd(dy, z, mb, rb, g)
+    assert np.allclose(dga, dgb, atol=1e-12) and np.array_equal(dba, dbb)
+    # ... except that LayerNorm's dx also projects out the row mean, which RMSNorm's does not
+    assert np.allclose(dxa, dxb - (dxb.mean(axis=1, keepdims=True)), atol=1e-12)
+
+
+def test_rmsnorm_bwd_central_differences_and_torch():
+    rows, cols = 4, 12
+    x = rng.normal(size=(rows, cols)) + 0.7
+    g = 1 + 0.1 * rng.normal(size=cols); b = 0.1 * rng.normal(size=cols); dy = rng.normal(size=(rows, cols))
+    y, mu, r = O.rmsnorm_fwd(x, g, b, 1e-5)
+    dx, dg, db = O.rmsnorm_bwd(dy, x, mu, r, g)
+    f = lambda x_, g_, b_: float((O.rmsnorm_fwd(x_, g_, b_, 1e-5)[0] * dy).sum())
+    h = 1e-6
+    for arr, grad, which in ((x, dx, 0), (g, dg, 1), (b, db, 2)):
+        num = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            a, c = arr.copy(), arr.copy()
+            a[idx] += h; c[idx] -= h
+            args = [x, g, b]
+            args[which] = a; fa = f(*args)
+            args[which] = c; fc = f(*args)
+            num[idx] = (fa - fc) / (2 * h)
+        assert np.allclose(num, grad, atol=1e-8), which
+    # orthogonality: dx is orthogonal to x in every row (the output does not change along x, for eps -> 0)
+    y0, m0, r0 = O.rmsnorm_fwd(x, g, b, 0.0)
+    assert np.allclose((O.rmsnorm_bwd(dy, x, m0, r0, g)[0] * x).sum(axis=1), 0, atol=1e-12)
+    torch = pytest.importorskip("torch")
+    if hasattr(torch.nn.functional, "rms_norm"):
+        tx = torch.tensor(x, requires_grad=True); tg = torch.tensor(g, requires_grad=True)
+        ty = torch.nn.functional.rms_norm(tx, (cols,), tg, 1e-5) + torch.tensor(b)
+        ty.backward(torch.tensor(dy))
+        assert np.allclose(y, ty.detach().numpy(), atol=1e-12)
+        assert np.allclose(dx, tx.grad.numpy(), atol=1e-12) and np.allclose(dg, tg.grad.numpy(), atol=1e-12)

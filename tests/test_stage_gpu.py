@@ -16,7 +16,7 @@ BOUND = {"f32": 1e-4, "bf16": 2e-2}
 
 def oracle_step(cfg, w, x, dy, dtype=np.float64):
     st = O.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
-                 cfg.causal, cfg.gelu, cfg.ln_eps)
+                 cfg.causal, cfg.gelu, cfg.ln_eps, norm=cfg.norm)
     return O.stage_step(st, w, x, dy, dtype=dtype)
 
 
@@ -79,10 +79,29 @@ SMALL = [
     syn.StageConfig(2, 192, 3, 384, 200, 1, "post", True, "erf", "bf16"),
     syn.StageConfig(2, 64, 2, 128, 40, 3, "pre", True, "relu", "f32"),
     syn.StageConfig(2, 128, 2, 256, 96, 2, "post", False, "relu", "bf16"),
+    syn.StageConfig(2, 64, 2, 128, 40, 3, "pre", True, "erf", "f32", norm="rms"),
+    syn.StageConfig(2, 128, 2, 256, 96, 2, "post", False, "tanh", "bf16", norm="rms"),
 ]
 
 
-@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.norm_style}-{c.dtype}-H{c.hidden}-S{c.seq}-{c.gelu}")
+@pytest.mark.parametrize("norm", ["layer", "rms"])
+def test_rows_wider_than_2048_columns(norm):
+    """The block-per-row form of the normalisation backward inside a stage, for both kinds of normalisation
+    (weights at the workload's own scale: at this width sigma = 0.05 saturates the attention)."""
+    cfg = syn.StageConfig(2, 2560, 20, 512, 24, 2, "pre", True, "erf", "bf16", norm=norm)
+    w, x, dy = make(cfg, sigma=0.02)
+    ref = oracle_step(cfg, w, x, dy)
+    run = StageRunner(cfg, w, x, dy)
+    run.step(syn.plan_keep_all(cfg))
+    compare(cfg, run.results(), ref)
+    first = run.raw_results()
+    run.poison_outputs()
+    run.step(syn.plan_all_recompute(cfg))
+    assert all(torch.equal(a, b) for a, b in zip(first, run.raw_results()))
+    run.close()
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: f"{c.norm_style}-{c.dtype}-H{c.hidden}-S{c.seq}-{c.gelu}-{c.norm}")
 @pytest.mark.parametrize("sharp", [False, True])
 def test_small_stages_every_plan(cfg, sharp):
     w, x, dy = make(cfg, sharp=sharp, sigma=0.05)
