@@ -6,8 +6,11 @@
 
 #include <algorithm>
 #include <array>
+#include <atomic>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <thread>
 #include <vector>
 
 namespace dpi {
@@ -40,6 +43,23 @@ const BwdReads kPreCrossBwd[N_OPS_CROSS] = {
     {2, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS}}};
 
 struct Cand { int l, slot; int64_t free_ns; };
+
+// fn(i) for i in [0, n) on up to 16 host threads (DPSTAGE_PLANNER_THREADS overrides; 1 = inline).  The
+// planner's trial plans are independent walks; their results are read back in index order, so the
+// outcome does not depend on how many threads ran them.
+template <typename F>
+void parallel_for(size_t n, F fn) {
+  unsigned want = std::min(16u, std::max(1u, std::thread::hardware_concurrency()));
+  if (const char *env = getenv("DPSTAGE_PLANNER_THREADS")) want = (unsigned)std::max(1, atoi(env));
+  const size_t nt = std::min<size_t>(want, n);
+  if (nt <= 1) { for (size_t i = 0; i < n; ++i) fn(i); return; }
+  std::atomic<size_t> next{0};
+  auto work = [&] { for (size_t i = next++; i < n; i = next++) fn(i); };
+  std::vector<std::thread> pool;
+  for (size_t t = 1; t < nt; ++t) pool.emplace_back(work);
+  work();
+  for (std::thread &t : pool) t.join();
+}
 
 // The planner proper (Section 4.3): swaps by decreasing FreeTime while they stay hidden, then
 // the action with the most memory saved per second of overhead, until inflight * peak fits.
@@ -111,15 +131,22 @@ bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32
   bool ok = true;
   while (!fits(P)) {
     int best = -1, best_a = 0; int64_t best_dt = 0, best_T = 0; uint64_t best_saved = 0, best_P = 0;
+    // every remaining candidate under both actions: independent walks, played side by side
+    const int actions[2] = {(int)DP_SWAP, (int)DP_RECOMPUTE};
+    std::vector<std::pair<int64_t, uint64_t>> played(rest.size() * 2);
+    parallel_for(played.size(), [&](size_t i) {
+      std::vector<uint8_t> trial = plan;
+      trial[idx(rest[i / 2])] = (uint8_t)actions[i % 2];
+      cost(trial, &played[i].first, &played[i].second);
+    });
     // first pass: changes that lower the peak, rated by the reduction; if there is none (two
     // moments share the peak): changes that do not raise it, rated by the tensor's size
     for (int plateau = 0; plateau < 2 && best < 0; ++plateau)
       for (size_t pos = 0; pos < rest.size(); ++pos)
-        for (int a : {(int)DP_SWAP, (int)DP_RECOMPUTE}) {
-          std::vector<uint8_t> trial = plan;
-          trial[idx(rest[pos])] = (uint8_t)a;
-          int64_t T1; uint64_t P1;
-          cost(trial, &T1, &P1);
+        for (int ai = 0; ai < 2; ++ai) {
+          const int a = actions[ai];
+          const int64_t T1 = played[pos * 2 + (size_t)ai].first;
+          const uint64_t P1 = played[pos * 2 + (size_t)ai].second;
           if (plateau ? P1 > P : P1 >= P) continue;
           const uint64_t saved = plateau ? slot_bytes(c, rest[pos].slot) : P - P1;
           const int64_t dt = std::max<int64_t>(T1 - T, 0);

@@ -384,6 +384,7 @@ struct Walk {
   int64_t clk[3] = {0, 0, 0};
   std::vector<int64_t> ev_ns;
   bool sim_arena_waits = false;            // also wait where a block is handed on behind a copy-out
+  bool no_arena = false;                   // the planner's model: saved tensors only, no offsets (the searches play thousands of plans)
   uint64_t slot_live = 0, slot_peak = 0;   // saved tensors alone: Algorithm 2's walk without transients
   std::vector<std::pair<int64_t, uint64_t>> lingering;   // (copy-out landing time, bytes) of swapped-out tensors
   // a swapped-out tensor's memory counts until its copy-out has landed, seen from the compute clock
@@ -446,12 +447,14 @@ struct Walk {
   }
 
   uint64_t arena_alloc(uint64_t bytes) {
+    if (no_arena) return 0;
     std::vector<int> waits;
     const uint64_t off = arena.alloc(bytes, &waits);
     if (live || sim_arena_waits) for (int ev : waits) wait(cs, ev);
     return off;
   }
   void arena_release(uint64_t off, uint64_t bytes, int pending_event = -1) {
+    if (no_arena) return;
     if (live && (st->debug & 2u)) {
       if (pending_event >= 0) wait(cs, pending_event);
       check(dp::launch_fill_u32(base() + off, Arena::round(bytes) / 4, 0xFFFFFFFFu, cs));
@@ -482,7 +485,7 @@ struct Walk {
   // ---- profiling brackets ---------------------------------------------------
   void prof_begin(int cls) {
     ++n_launch;
-    arena.tick();
+    if (!no_arena) arena.tick();
     if (!live || !st->profiling) return;
     if (st->prof_used + 2 > st->prof_events.size()) {
       for (int i = 0; i < 2; ++i) { hipEvent_t e; check(hipEventCreate(&e)); st->prof_events.push_back(e); }
@@ -1184,6 +1187,7 @@ CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bo
   w.swap_hold_ticks = exact ? hold_ticks : 0;
   w.cm = &cm;
   w.sim_arena_waits = exact;
+  w.no_arena = !exact;
   w.cs = (hipStream_t)(intptr_t)1; w.d2h = (hipStream_t)(intptr_t)2; w.h2d = (hipStream_t)(intptr_t)3;
   w.forward();
   w.backward();
