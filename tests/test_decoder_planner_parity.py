@@ -111,3 +111,36 @@ def test_partition_of_a_decoder_chain_matches_the_oracle():
             assert got["cuts"] == want["cuts"] and got["time_ns"] == want["time_ns"], (ell, frac)
             for gs, ws in zip(got["stages"], want["stages"]):
                 assert list(gs["plan"]) == ws["plan"] and gs["peak_bytes"] == ws["peak_bytes"]
+
+
+def test_the_thread_count_does_not_change_a_plan():
+    """The generator plays its trial plans on several host threads and reads them back in order: one thread or
+    many, the plan and its figures are the same (a fresh process each, the count is read from the environment)."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import json, sys, numpy as np\n"
+        f"sys.path.insert(0, {root!r})\n"
+        "import synthetic as syn\n"
+        "from paper_2505_05856_amd import binding as B\n"
+        "from paper_2505_05856_amd.harness import to_binding_config\n"
+        "cfg = syn.StageConfig(3, 64, 2, 128, 32, 2, 'pre', True, 'erf', 'bf16', mem_seq=20)\n"
+        "bc = to_binding_config(cfg)\n"
+        "cm = B.make_cost_model([900 + 37 * i for i in range(13)], [1700 + 53 * i for i in range(13)], 40, 60)\n"
+        "_, keep = B.plan_validate(bc, syn.plan_keep_all(cfg))\n"
+        "out = []\n"
+        "for frac in (80, 60, 45):\n"
+        "    code, plan, rep = B.plan_generate(bc, cm, keep['peak_bytes'] * frac // 100, 2, flags=B.MEMOPT_VALIDATE, raise_on_error=False)\n"
+        "    out.append([code, [int(v) for v in plan], rep['moo_ns'], rep['peak_bytes'], rep['exact_step_ns']])\n"
+        "print(json.dumps(out))\n")
+    results = []
+    for threads in ("1", "5"):
+        env = dict(os.environ, DPSTAGE_PLANNER_THREADS=threads)
+        p = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=300)
+        assert p.returncode == 0, p.stderr[-2000:]
+        results.append(json.loads(p.stdout.strip().splitlines()[-1]))
+    assert results[0] == results[1]
+    assert any(sum(r[1]) > 0 for r in results[0])       # (budgets that do need a plan)
