@@ -54,6 +54,8 @@ SMALL = [
     dec(2, 128, 2, 256, 64, 50, 2, "bf16", gelu="relu"),         # T5's feed-forward activation
     dec(2, 128, 2, 256, 64, 50, 2, "bf16", norm="rms"),          # T5's normalisation
     dec(2, 64, 2, 128, 24, 30, 2, "f32", gelu="relu", norm="rms"),
+    dec(1, 64, 1, 128, 1, 1, 1, "f32"),                          # one token, one memory position, one sample
+    dec(2, 64, 2, 128, 3, 2, 1, "bf16"),                         # a few tokens: every GEMM below the matrix-core tiles
 ]
 
 
