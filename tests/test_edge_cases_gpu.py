@@ -32,6 +32,13 @@ def test_empty_inputs_are_no_ops_and_empty_sums_are_zero(dt):
     torch.cuda.synchronize()
     for t in (dg, db, ds, out):
         assert torch.equal(t, torch.zeros_like(t))
+    # the same for the other normalisation
+    B.op_rmsnorm_fwd(e, g, g, 1e-5, torch.zeros(1, cols, dtype=dt, device=DEV)[:0], stats)
+    dg, db, ds = nan(), nan(), nan()
+    B.op_rmsnorm_bwd(e, e, stats, g, None, torch.zeros(1, cols, dtype=dt, device=DEV)[:0], dg, db, ws, dx_colsum=ds)
+    torch.cuda.synchronize()
+    for t in (dg, db, ds):
+        assert torch.equal(t, torch.zeros_like(t))
     B.op_gelu_fwd(e, torch.zeros(1, cols, dtype=dt, device=DEV)[:0])
     B.op_gelu_bwd(e, e, torch.zeros(1, cols, dtype=dt, device=DEV)[:0])
     # GEMM with an empty extent: nothing to write; K = 0: the product is zero, bias and residual remain
