@@ -495,9 +495,11 @@ dp_status dp_op_rmsnorm_bwd(int32_t dtype, int32_t rows, int32_t cols, const voi
                             void *dx, void *dgamma, void *dbeta, void *dx_colsum /*nullable*/, void *ws,
                             void *hip_stream);
 dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *x, void *y, void *hip_stream);
-/* dx = dy * gelu'(x) */
-dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,
-                         void *hip_stream);
+/* dx = dy * gelu'(x) over [rows, cols], and dbias [cols] = the column sums of dx as stored (the
+ * bias gradient of the linear layer in front of the activation): the one kernel the stage's
+ * backward runs for this node.  dy may be dx.  ws: dp_op_workspace_bytes(rows, cols). */
+dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, int32_t rows, int32_t cols, const void *dy,
+                         const void *x, void *dx, void *dbias, void *ws, void *hip_stream);
 /* C[M,N] = op(A)*op(B) (+bias[N]) (+res[M,N]).  mode 0 ("NT"): A [M,K], B [N,K]
  * (both contraction-contiguous: forward with the transposed weight copy, and
  * dX = dY*W^T with W as stored); mode 1 ("TN"): A [K,M], B [K,N] (contraction

@@ -149,7 +149,7 @@ def lib() -> C.CDLL:
     L.dp_op_rmsnorm_fwd.argtypes = [i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
     L.dp_op_rmsnorm_bwd.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.dp_op_gelu_fwd.argtypes = [i32, i32, sz, vp, vp, vp]
-    L.dp_op_gelu_bwd.argtypes = [i32, i32, sz, vp, vp, vp, vp]
+    L.dp_op_gelu_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.dp_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.dp_op_colsum.argtypes = [i32, i32, i32, vp, vp, vp, vp]
     L.dp_op_attention_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
@@ -447,8 +447,9 @@ def op_gelu_fwd(x, y, kind=0, stream=None):
     _check(lib().dp_op_gelu_fwd(_dt(x), kind, x.numel(), _ptr(x), _ptr(y), _stream_ptr(stream)))
 
 
-def op_gelu_bwd(dy, x, dx, kind=0, stream=None):
-    _check(lib().dp_op_gelu_bwd(_dt(x), kind, x.numel(), _ptr(dy), _ptr(x), _ptr(dx), _stream_ptr(stream)))
+def op_gelu_bwd(dy, x, dx, dbias, ws, kind=0, stream=None):
+    _check(lib().dp_op_gelu_bwd(_dt(x), kind, x.shape[0], x.shape[1], _ptr(dy), _ptr(x), _ptr(dx), _ptr(dbias),
+                                _ptr(ws), _stream_ptr(stream)))
 
 
 def op_gemm(mode, M, N, K, A, B, bias, res, Cout, stream=None):

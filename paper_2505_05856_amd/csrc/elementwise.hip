@@ -470,18 +470,6 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ x, 
     store8(y + i * 8, v);
   }
 }
-template <typename T>
-__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
-                                                       T *dx, size_t n8, int kind) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
-    float v[8], d[8];
-    load8(x + i * 8, v);
-    load8(dy + i * 8, d);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) v[k] = d[k] * gelu_df(v[k], kind);
-    store8(dx + i * 8, v);
-  }
-}
 
 // dx = dy * gelu'(x) over [rows, cols] plus the column sums of the stored dx (the bias
 // gradient of the linear layer in front of the GELU): block (cx, rb) covers 512 columns
@@ -686,18 +674,6 @@ hipError_t launch_dropout(int dtype, size_t n, const void *x, const void *res, v
   else
     hipLaunchKernelGGL((dropout_kernel<float>), dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)x,
                        (const float *)res, (float *)y, n8, a);
-  return hipGetLastError();
-}
-
-hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s) {
-  if (n == 0) return hipSuccess;
-  const size_t n8 = n / 8;
-  if (dtype == kBF16)
-    hipLaunchKernelGGL((gelu_bwd_kernel<bf16>), dim3(ew_grid(n8)), dim3(256), 0, s, (const bf16 *)dy,
-                       (const bf16 *)x, (bf16 *)dx, n8, kind);
-  else
-    hipLaunchKernelGGL((gelu_bwd_kernel<float>), dim3(ew_grid(n8)), dim3(256), 0, s, (const float *)dy,
-                       (const float *)x, (float *)dx, n8, kind);
   return hipGetLastError();
 }
 

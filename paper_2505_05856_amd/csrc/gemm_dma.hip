@@ -45,7 +45,7 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 // allocated), and nothing else in this file makes it emit an M0 user, so it is simply overwritten.
 __device__ __forceinline__ void dma16(unsigned lds_base, unsigned byte_off, const void *uniform_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_base), "v"(byte_off), "s"(uniform_base));
+               :: "s"(lds_base), "v"(byte_off), "s"(uniform_base) : "m0", "memory");
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt_mem() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
@@ -64,7 +64,7 @@ template <int ROWB> __device__ __forceinline__ constexpr int tn_swizzle(int r) {
   return ROWB == 128 ? ((r >> 1) & 1) << 2 : (r & 3) << 2;
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK, bool SPLIT>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, bool TN, int BK, bool SPLIT>
 __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amdgpu_flat_work_group_size(64 * WGM * WGN, 64 * WGM * WGN))) void gemm_dma_kernel(
     const bf16 *__restrict__ A, const bf16 *__restrict__ B, const bf16 *__restrict__ bias,
     const bf16 *__restrict__ res, bf16 *__restrict__ C, bf16 *__restrict__ C2, int gelu_kind, int M, int N, int K,
@@ -188,164 +188,193 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
-  constexpr int KS = BK / 16;
-  constexpr int TOTAL = KS * FM * FN;       // MFMAs of a step
-  static_assert(KS % 2 == 0, "the fragment double buffer keeps its parity across steps");
-  bf16x8 a[2][FM], b[2][FN];
+  constexpr int KS = BK / 16;                      // 16-deep MFMA slices of a k-step
+  // The main loop is software-pipelined by hand over "slices" of SK MFMA k-slices: the
+  // fragments of slice s+1 are read from LDS into the other half of a register double buffer
+  // before the MFMAs of slice s are issued, so an LDS read has a whole slice of MFMAs (at
+  // least four per wave) to complete.  Scheduling barriers pin that order: left alone, the
+  // compiler reuses one set of fragment registers and waits for every read right before its
+  // first MFMA.
+  constexpr int SK = FM * FN >= 8 ? 1 : (FM * FN >= 4 ? 1 : 2);
+  constexpr int NS = KS / SK;                      // slices of a k-step
+  constexpr int MPS = SK * FM * FN;                // MFMAs of a slice
+  static_assert(KS % SK == 0 && NS % 2 == 0, "the fragment double buffer keeps its parity across steps");
+  bf16x8 a[2][SK][FM], b[2][SK][FN];
+  // fragments of slice s of the tiles at LDS bytes base_a / base_b (frag adds A_BYTES for B)
+  auto read_slice = [&](auto buf_tag, unsigned base_a, unsigned base_b, int s) {
+    constexpr int BUF = decltype(buf_tag)::value;
+#pragma unroll
+    for (int q = 0; q < SK; ++q) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) a[BUF][q][i] = frag(base_a, i, s * SK + q, false);
+#pragma unroll
+      for (int j = 0; j < FN; ++j) b[BUF][q][j] = frag(base_b, j, s * SK + q, true);
+    }
+  };
+  // the MFMAs of one slice; req(g) issues the operand requests that go behind MFMA g
+  auto mfma_slice = [&](auto buf_tag, auto &&req) {
+    constexpr int BUF = decltype(buf_tag)::value;
+#pragma unroll
+    for (int q = 0; q < SK; ++q)
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[BUF][q][i], b[BUF][q][j], acc[i][j], 0, 0, 0);
+          req((q * FM + i) * FN + j);
+        }
+  };
+  auto no_req = [](int) {};
+  using Buf0 = std::integral_constant<int, 0>;
+  using Buf1 = std::integral_constant<int, 1>;
+  // One pass of the loop, for k-step kt, entered right behind the barrier that certified
+  // stage kt (so no LDS read is in flight on entry, nor at the loop's back edge: the
+  // compiler's wait-count pass only places exact partial waits inside straight-line code):
+  //   read slice 0 of stage kt, under the MFMAs of the LAST slice of step kt-1, whose
+  //     fragments are still in buffer 1 (not FIRST), with req_first's requests between them;
+  //   slices 0 .. NS-2: read the next slice, then the MFMAs of this one, req_inner between them;
+  //   every LDS read of stage kt has now been issued: wait for stage kt+1 and pass the
+  //     barrier that certifies it and frees stage kt (NEXT); the MFMAs of slice NS-1 follow
+  //     in the next pass (or behind the loop).
+  auto pass = [&](auto first_tag, auto next_tag, unsigned base_a, unsigned base_b, auto &&wait_next,
+                  auto &&req_first, auto &&req_inner) {
+    constexpr bool FIRST = decltype(first_tag)::value, NEXT = decltype(next_tag)::value;
+    read_slice(Buf0{}, base_a, base_b, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (!FIRST) {
+      mfma_slice(Buf1{}, req_first);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int s = 0; s + 1 < NS; ++s) {
+      if (s & 1) read_slice(Buf0{}, base_a, base_b, s + 1); else read_slice(Buf1{}, base_a, base_b, s + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s & 1) mfma_slice(Buf1{}, [&](int g) { req_inner(s * MPS + g); });
+      else mfma_slice(Buf0{}, [&](int g) { req_inner(s * MPS + g); });
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (NEXT) {
+      wait_next();
+      __syncthreads();
+    }
+  };
+  // a request pinned in place between the MFMAs around it
+  auto pinned = [&](auto &&issue) {
+    __builtin_amdgcn_sched_barrier(0);
+    issue();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  constexpr int INNER = (NS - 1) * MPS;   // MFMAs of a pass that can carry its spread-out requests
+  using Yes = std::true_type;
+  using No = std::false_type;
   if constexpr (SPLIT) {
     // ---- ring of five operand tiles ---------------------------------------------------
-    // A 256x256 k-step fills 64 KB of LDS, so only two whole stages fit, and the requests of
-    // a step then have less than one step to land.  With the A and B tiles as separate ring
-    // entries a fifth tile fits: slot (2k) % 5 holds A(k), slot (2k+1) % 5 holds B(k).  Step k
-    // reads A(k), B(k); B(k+1) goes, right at its start, into the slot A(k-1) has left, and
-    // A(k+2), spread over the rest of the step, into B(k-1)'s.  Half of the requests so have
-    // two steps to land and the other half is out early and short.
+    // A 256x256 k-step fills 64 KB of LDS, so only two whole stages fit.  With the A and B
+    // tiles as separate ring entries a fifth tile fits: slot (2k) % 5 holds A(k), slot
+    // (2k+1) % 5 holds B(k).  Request order A0 B0 A1 B1 A2 | B2 A3 | B3 A4 ...: pass k asks
+    // for B(k+1) right behind the barrier that freed A(k-1)'s slot, and for A(k+2), spread
+    // over its inner slices, into the slot B(k-1) left; a B tile so has one step to land
+    // and an A tile one to two.  (The launcher sends K < 3 * BK elsewhere.)
     static_assert(BM == BN, "the ring entries are of one size");
     constexpr unsigned TILE = A_BYTES;
     auto req_a = [&](int i, unsigned slot) {
-      dma16(slot * TILE + lds_a + (unsigned)i * 1024u, voa[(wave * NIA + i) & 1], pa[i]);
+        dma16(slot * TILE + lds_a + (unsigned)i * 1024u, voa[(wave * NIA + i) & 1], pa[i]);
     };
     auto req_b = [&](int i, unsigned slot) {
-      dma16(slot * TILE + (lds_b - (unsigned)A_BYTES) + (unsigned)i * 1024u, vob[(wave * NIB + i) & 1], pb[i]);
+        dma16(slot * TILE + (lds_b - (unsigned)A_BYTES) + (unsigned)i * 1024u, vob[(wave * NIB + i) & 1], pb[i]);
     };
     const unsigned da = TN ? BK * lda : BK * 2, db = TN ? BK * ldb : BK * 2;
     auto adv_a = [&]() { voa[0] += da; voa[1] += da; };
     auto adv_b = [&]() { vob[0] += db; vob[1] += db; };
 #pragma unroll
-    for (int i = 0; i < NIA; ++i) req_a(i, 0);
-    adv_a();
+    for (int t = 0; t < 2; ++t) {
 #pragma unroll
-    for (int i = 0; i < NIB; ++i) req_b(i, 1);
-    adv_b();
-    if (nk > 1) {
-#pragma unroll
-      for (int i = 0; i < NIA; ++i) req_a(i, 2);
+      for (int i = 0; i < NIA; ++i) req_a(i, 2u * t);
       adv_a();
+#pragma unroll
+      for (int i = 0; i < NIB; ++i) req_b(i, 2u * t + 1u);
+      adv_b();
     }
-    unsigned sa = 0, sbk = 1;   // slots of A(kt), B(kt)
-    // MORE_B: k-step kt+1 exists (its B tile is requested now; its A tile is already under way);
-    // MORE_A: k-step kt+2 exists (its A tile is requested now)
-    auto step = [&](auto more_b_tag, auto more_a_tag) {
-      constexpr bool MORE_B = decltype(more_b_tag)::value, MORE_A = decltype(more_a_tag)::value;
-      // A(kt) and B(kt) must have landed; A(kt+1), requested after B(kt), may still be pending
-      if (MORE_B) wait_vmcnt_mem<NIA>(); else wait_vmcnt_mem<0>();
-      __syncthreads();   // everyone's part is in, and everyone is done with A(kt-1), B(kt-1)
-      const unsigned base_a = sa * TILE, base_b = sbk * TILE - (unsigned)A_BYTES;   // (frag adds A_BYTES for B)
-      const unsigned to_b = (sbk + 2 >= 5 ? sbk + 2 - 5 : sbk + 2), to_a = (sa + 4 >= 5 ? sa + 4 - 5 : sa + 4);
-#pragma unroll
-      for (int i = 0; i < FM; ++i) a[0][i] = frag(base_a, i, 0, false);
-#pragma unroll
-      for (int j = 0; j < FN; ++j) b[0][j] = frag(base_b, j, 0, true);
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int c = ks & 1;
-        if (ks + 1 < KS) {
-#pragma unroll
-          for (int i = 0; i < FM; ++i) a[c ^ 1][i] = frag(base_a, i, ks + 1, false);
-#pragma unroll
-          for (int j = 0; j < FN; ++j) b[c ^ 1][j] = frag(base_b, j, ks + 1, true);
-        }
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-          for (int j = 0; j < FN; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
-            const int g = (ks * FM + i) * FN + j;
-            // B(kt+1): one request behind each of the first NIB MFMAs; A(kt+2): evenly over the rest
-            if (MORE_B && g < NIB) req_b(g, to_b);
-            if (MORE_A) {
-              constexpr int SPAN = TOTAL - NIB;
-#pragma unroll
-              for (int q = 0; q < NIA; ++q)
-                if (NIB + ((q + 1) * SPAN + NIA - 1) / NIA - 1 == g) req_a(q, to_a);
-            }
-          }
-      }
-      if (MORE_B) adv_b();
-      if (MORE_A) adv_a();
-      sa = sa + 2 >= 5 ? sa + 2 - 5 : sa + 2;
-      sbk = sbk + 2 >= 5 ? sbk + 2 - 5 : sbk + 2;
-    };
-    int kt = 0;
-    for (; kt + 2 < nk; ++kt) step(std::true_type{}, std::true_type{});
-    if (kt + 1 < nk) { step(std::true_type{}, std::false_type{}); ++kt; }
-    if (kt < nk) step(std::false_type{}, std::false_type{});
-  } else {
-  // prologue: stages 0 .. STAGES-2
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) {
-    if (s < nk) {
-#pragma unroll
-      for (int i = 0; i < NI; ++i) request(i, (unsigned)s * STAGE_BYTES);
-      advance_k();
-    }
-  }
-
-  int cur = 0;                 // ring slot of k-step kt
-  int nxt = STAGES - 1;        // ring slot the requests of this step go to
-  // LA (rings of three or more stages): the barrier at the top of step kt also covers stage
-  // kt+1, so the last slice of a step can already fetch the first fragments of the next
-  // one and the MFMAs run on across the barrier instead of waiting for LDS reads behind it.
-  constexpr bool LA = STAGES >= 3;
-  auto first_frags = [&](unsigned sb) {
-#pragma unroll
-    for (int i = 0; i < FM; ++i) a[0][i] = frag(sb, i, 0, false);
-#pragma unroll
-    for (int j = 0; j < FN; ++j) b[0][j] = frag(sb, j, 0, true);
-  };
-  if (LA) {
-    if (nk - 1 >= STAGES - 2) wait_vmcnt_mem<(STAGES - 2) * NI>(); else wait_vmcnt_mem<0>();
+    wait_vmcnt_mem<NIA + NIB>();
     __syncthreads();
-    first_frags(0);
-  }
-  // One k-step.  MORE: k-step kt+STAGES-1 exists and is requested under this step's MFMAs.
-  // NEXT: k-step kt+1 exists.
-  auto step = [&](auto more_tag, auto next_tag) {
-    constexpr bool MORE = decltype(more_tag)::value, NEXT = decltype(next_tag)::value;
-    // what must have landed (k-step kt, with LA also kt+1) leaves at most the requests of the
-    // later steps pending
-    if (MORE) wait_vmcnt_mem<(STAGES - (LA ? 3 : 2)) * NI>(); else wait_vmcnt_mem<0>();
-    __syncthreads();   // everyone's part is in, and everyone is done with the previous slot
-    const unsigned sb = (unsigned)cur * STAGE_BYTES, nb = (unsigned)nxt * STAGE_BYTES;
-    const unsigned sb1 = (unsigned)(cur + 1 == STAGES ? 0 : cur + 1) * STAGE_BYTES;
-    if (!LA) first_frags(sb);
+    unsigned sa = 0, sbk = 1;   // slots of A(kt), B(kt)
+    auto ring = [](unsigned s, unsigned d) { return s + d >= 5 ? s + d - 5 : s + d; };
+    // MORE: k-step kt+2 exists (its A tile is requested in this pass)
+    auto step = [&](auto first_tag, auto next_tag, auto more_tag) {
+      constexpr bool FIRST = decltype(first_tag)::value, NEXT = decltype(next_tag)::value,
+                     MORE = decltype(more_tag)::value;
+      const unsigned to_b = ring(sbk, 2), to_a = ring(sa, 4);   // slots of B(kt+1), A(kt+2)
+      pass(first_tag, next_tag, sa * TILE, sbk * TILE - (unsigned)A_BYTES,
+           [&]() { if (MORE) wait_vmcnt_mem<NIA>(); else wait_vmcnt_mem<0>(); },
+           [&](int g) {
+             if (NEXT && g < NIB) pinned([&]() { req_b(g, to_b); });
+           },
+           [&](int p) {
+             if (MORE) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int c = ks & 1;
-      if (ks + 1 < KS) {   // fragments of the next 16-slice are fetched under this slice's MFMAs
+               for (int q = 0; q < NIA; ++q)
+                 if (((q + 1) * INNER + NIA - 1) / NIA - 1 == p) pinned([&]() { req_a(q, to_a); });
+             }
+           });
+      if (!FIRST && NEXT) adv_b();
+      if (MORE) adv_a();
+      sa = ring(sa, 2);
+      sbk = ring(sbk, 2);
+    };
+    static_assert(NIB <= MPS, "the B requests of a pass ride the MFMAs of one slice");
+    step(Yes{}, Yes{}, Yes{});
+    int kt = 1;
+    for (; kt + 2 < nk; ++kt) step(No{}, Yes{}, Yes{});
+    step(No{}, Yes{}, No{});
+    step(No{}, No{}, No{});
+  } else {
+    // ---- ring of STAGES whole stages ------------------------------------------------------
+    // Stage k sits in slot k % STAGES.  Stages 0 .. STAGES-2 are requested up front; pass kt
+    // asks for stage kt+STAGES-1, spread over its inner slices, into the slot the barrier
+    // before it freed, so a stage has STAGES-2 steps and more to land.
+    static_assert(STAGES >= 3, "the barrier of a step certifies the next stage");
 #pragma unroll
-        for (int i = 0; i < FM; ++i) a[c ^ 1][i] = frag(sb, i, ks + 1, false);
+    for (int s = 0; s < STAGES - 1; ++s) {
+      if (s < nk) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j) b[c ^ 1][j] = frag(sb, j, ks + 1, true);
-      } else if (LA && NEXT) {
-        first_frags(sb1);
+        for (int i = 0; i < NI; ++i) request(i, (unsigned)s * STAGE_BYTES);
+        advance_k();
       }
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
-          // request q goes out behind MFMA ceil((q+1)*SPAN/NI) - 1: evenly spread over the first
-          // 1/WIN of the step (a shallow ring needs them out early, a deep one can take its time)
-          const int g = (ks * FM + i) * FN + j;
-          if (MORE) {
-            constexpr int SPAN = TOTAL / WIN > 0 ? TOTAL / WIN : 1;
-#pragma unroll
-            for (int q = 0; q < NI; ++q)
-              if (((q + 1) * SPAN + NI - 1) / NI - 1 == g) request(q, nb);
-          }
-        }
     }
-    if (MORE) advance_k();
-    cur = cur + 1 == STAGES ? 0 : cur + 1;
-    nxt = nxt + 1 == STAGES ? 0 : nxt + 1;
-  };
-  int kt = 0;
-  for (; kt + STAGES - 1 < nk; ++kt) step(std::true_type{}, std::true_type{});
-  for (; kt + 1 < nk; ++kt) step(std::false_type{}, std::true_type{});
-  if (kt < nk) step(std::false_type{}, std::false_type{});
-
+    if (nk >= STAGES - 1) wait_vmcnt_mem<(STAGES - 2) * NI>(); else wait_vmcnt_mem<0>();
+    __syncthreads();
+    int cur = 0;                 // ring slot of k-step kt
+    int nxt = STAGES - 1;        // ring slot the requests of this pass go to
+    // MORE: k-step kt+STAGES-1 exists (requested in this pass; the stages before it then all
+    // exist, so the wait for stage kt+1 may leave STAGES-2 stages pending)
+    auto step = [&](auto first_tag, auto next_tag, auto more_tag) {
+      constexpr bool MORE = decltype(more_tag)::value;
+      const unsigned sb = (unsigned)cur * STAGE_BYTES, nb = (unsigned)nxt * STAGE_BYTES;
+      pass(first_tag, next_tag, sb, sb,
+           [&]() { if (MORE) wait_vmcnt_mem<(STAGES - 2) * NI>(); else wait_vmcnt_mem<0>(); },
+           no_req,
+           [&](int p) {
+             if (MORE) {
+#pragma unroll
+               for (int q = 0; q < NI; ++q)
+                 if (((q + 1) * INNER + NI - 1) / NI - 1 == p) pinned([&]() { request(q, nb); });
+             }
+           });
+      if (MORE) advance_k();
+      cur = cur + 1 == STAGES ? 0 : cur + 1;
+      nxt = nxt + 1 == STAGES ? 0 : nxt + 1;
+    };
+    if (nk >= STAGES) step(Yes{}, Yes{}, Yes{});
+    else if (nk > 1) step(Yes{}, Yes{}, No{});
+    else step(Yes{}, No{}, No{});
+    int kt = 1;
+    for (; kt + STAGES - 1 < nk; ++kt) step(No{}, Yes{}, Yes{});
+    for (; kt + 1 < nk; ++kt) step(No{}, Yes{}, No{});
+    if (kt < nk) step(No{}, No{}, No{});
   }
+  // the MFMAs of the last slice of the last k-step
+  __builtin_amdgcn_sched_barrier(0);
+  mfma_slice(Buf1{}, no_req);
 
   // ---- epilogue ---------------------------------------------------------------------------
   // Accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 block:
@@ -416,12 +445,12 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, int WIN, bool TN, int BK, bool SPLIT>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool ACT, bool TN, int BK, bool SPLIT>
 hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
   constexpr size_t smem = SPLIT ? (size_t)5 * BM * BK * 2 : (size_t)STAGES * (BM + BN) * BK * 2;
   static_assert(smem <= 160 * 1024, "LDS of one CU");
   static bool attr_set = false;
-  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, WIN, TN, BK, SPLIT>;
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, STAGES, ACT, TN, BK, SPLIT>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -435,11 +464,11 @@ hipError_t launch_dma_act(const GemmArgs &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int WIN, bool TN, int BK = 64, bool SPLIT = false>
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool TN, int BK = 64, bool SPLIT = false>
 hipError_t launch_dma_cfg(const GemmArgs &a, hipStream_t s) {
-  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, TN, BK, SPLIT>(a, s);   // no epilogue extras in this form
-  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, WIN, false, BK, SPLIT>(a, s)
-                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, WIN, false, BK, SPLIT>(a, s);
+  if (TN) return launch_dma_act<BM, BN, WGM, WGN, STAGES, false, TN, BK, SPLIT>(a, s);   // no epilogue extras in this form
+  return a.C2 != nullptr ? launch_dma_act<BM, BN, WGM, WGN, STAGES, true, false, BK, SPLIT>(a, s)
+                         : launch_dma_act<BM, BN, WGM, WGN, STAGES, false, false, BK, SPLIT>(a, s);
 }
 
 template <bool TN>
@@ -449,21 +478,20 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
   static const char *force = getenv("DPSTAGE_GEMM_TILE");
   const bool big_ok = a.M >= 256 && a.N >= 256;
   if (force != nullptr) {
-    if (!strcmp(force, "256x256") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 1, TN, 64, true>(a, s);
-    if (!strcmp(force, "256x256s2") && big_ok) return launch_dma_cfg<256, 256, 4, 2, 2, 4, TN>(a, s);
-    if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
-    if (!strcmp(force, "128x128w4")) return launch_dma_cfg<128, 128, 2, 2, 4, 1, TN>(a, s);
-    if (!strcmp(force, "64x64")) return launch_dma_cfg<64, 64, 2, 2, 8, 1, TN>(a, s);
+    if (!strcmp(force, "256x256") && big_ok && a.K >= 192) return launch_dma_cfg<256, 256, 4, 2, 2, TN, 64, true>(a, s);
+    if (!strcmp(force, "128x128")) return launch_dma_cfg<128, 128, 4, 2, 4, TN>(a, s);
+    if (!strcmp(force, "128x128w4")) return launch_dma_cfg<128, 128, 2, 2, 4, TN>(a, s);
+    if (!strcmp(force, "64x64")) return launch_dma_cfg<64, 64, 2, 2, 8, TN>(a, s);
 
   }
   // 256x256 (8 waves, 64x128 a wave, ring of five operand tiles) halves the L1 traffic per
   // flop of 128x128 and wins as soon as it gives most CUs a workgroup; below that 128x128
   // with 8 waves and a four-stage ring.
-  if (big_ok && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, 1, TN, 64, true>(a, s);
+  if (big_ok && a.K >= 192 && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, TN, 64, true>(a, s);
   // a small output with a long contraction (the out-projection weight gradient) leaves most
   // CUs without a 128x128 tile: 64x64 tiles, several workgroups a CU, then run faster
-  if (tiles(128, 128) <= 96) return launch_dma_cfg<64, 64, 2, 2, 8, 1, TN>(a, s);
-  return launch_dma_cfg<128, 128, 4, 2, 4, 1, TN>(a, s);
+  if (tiles(128, 128) <= 96) return launch_dma_cfg<64, 64, 2, 2, 8, TN>(a, s);
+  return launch_dma_cfg<128, 128, 4, 2, 4, TN>(a, s);
 }
 
 }  // namespace

@@ -103,7 +103,6 @@ hipError_t launch_gelu_bwd_colsum(int dtype, int kind, int rows, int cols, const
 hipError_t launch_dropout(int dtype, size_t n, const void *x, const void *res, void *y, const DropArgs &a,
                           hipStream_t s);
 hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s);
-hipError_t launch_gelu_bwd(int dtype, int kind, size_t n, const void *dy, const void *x, void *dx, hipStream_t s);
 hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s,
                          ReduceJob *job = nullptr);
 // dst[c, r] = src[r, c]

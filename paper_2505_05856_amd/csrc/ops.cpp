@@ -64,12 +64,14 @@ dp_status dp_op_gelu_fwd(int32_t dtype, int32_t gelu_kind, size_t n, const void 
   return op_done(dp::launch_gelu_fwd(dtype, gelu_kind, n, x, y, (hipStream_t)hip_stream), "gelu_fwd");
 }
 
-dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, size_t n, const void *dy, const void *x, void *dx,
-                         void *hip_stream) {
-  if (bad_dtype(dtype) || (n > 0 && (!x || !dy || !dx)) || (gelu_kind < 0 || gelu_kind > 2))
+dp_status dp_op_gelu_bwd(int32_t dtype, int32_t gelu_kind, int32_t rows, int32_t cols, const void *dy, const void *x,
+                         void *dx, void *dbias, void *ws, void *hip_stream) {
+  if (bad_dtype(dtype) || rows < 0 || cols <= 0 || !dbias || (rows > 0 && (!x || !dy || !dx || !ws)) ||
+      (gelu_kind < 0 || gelu_kind > 2))
     return fail(DP_E_INVAL, "gelu_bwd: bad argument");
-  if (n % 8) return fail(DP_E_UNSUPPORTED, "gelu: n must be a multiple of 8");
-  return op_done(dp::launch_gelu_bwd(dtype, gelu_kind, n, dy, x, dx, (hipStream_t)hip_stream), "gelu_bwd");
+  if (cols % 8) return fail(DP_E_UNSUPPORTED, "gelu: cols must be a multiple of 8");
+  return op_done(dp::launch_gelu_bwd_colsum(dtype, gelu_kind, rows, cols, dy, x, dx, dbias, ws,
+                                            (hipStream_t)hip_stream), "gelu_bwd");
 }
 
 dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void *A, const void *B,

@@ -84,7 +84,7 @@ bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32
   const int n_ops = op_count(c), ns = c.nslots;
   plan.assign((size_t)c.L * (size_t)ns, DP_KEEP);
   auto cost = [&](const std::vector<uint8_t> &p, int64_t *t, uint64_t *peak) {
-    const CostOut o = walk_cost(c, cm, p.data(), false, 0);
+    const CostOut o = walk_cost(c, cm, p.data(), false, SwapPolicy{});
     *t = o.step_ns; *peak = fixed_bytes + o.slot_peak;
   };
   auto fits = [&](uint64_t peak) { return budget == 0 || (unsigned __int128)inflight * peak <= budget; };
@@ -187,7 +187,7 @@ dp_status memopt_validated(const Cfg &c, const dp_cost_model &cm, uint64_t budge
     r->refine_rounds = round;
     const bool ok = memopt(c, cm, model_budget, inflight, fixed, plan, r);
     dp_plan_report vr;
-    long hold = 0;
+    SwapPolicy hold;
     const dp_status vs = validate(c, plan.data(), plan_len, budget_bytes, inflight, &vr, env_mfma_enabled(), kFuseGeluDefault, &hold);
     r->validated_peak_bytes = vr.peak_bytes;
     if (vs == DP_OK) {
@@ -311,7 +311,7 @@ struct Partitioner {
       uint64_t extras = 0;
       for (int l = a; l < b; ++l) extras += extra_bytes[(size_t)l];
       const unsigned __int128 held_extras = (unsigned __int128)k * extras;   // the extras of every micro-batch in flight
-      const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, 0);
+      const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, SwapPolicy{});
       r->base = keep.step_ns + extra;
       dp_plan_report vr;
       if (M == 0 || held_extras < M) {
@@ -335,7 +335,7 @@ struct Partitioner {
       cache.emplace_back(key, r);
       return r;
     }
-    const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, 0);
+    const CostOut keep = walk_cost(c, *cm, r->plan.data(), false, SwapPolicy{});
     const uint64_t keep_peak = fixed + keep.slot_peak;
     if (M == 0 || (unsigned __int128)k * keep_peak <= M) {
       r->t = r->base = keep.step_ns + extra; r->moo = 0; r->mopt = false; r->peak = keep_peak;
@@ -433,7 +433,7 @@ dp_status dp_plan_cost(const dp_stage_config *cfg, const dp_cost_model *cm, cons
   dp_plan_report pr;
   memset(&pr, 0, sizeof pr);
   if ((s = check_plan(c, plan, plan_len, &pr)) != DP_OK) return s;
-  const CostOut o = walk_cost(c, *cm, plan, false, 0);
+  const CostOut o = walk_cost(c, *cm, plan, false, SwapPolicy{});
   report->step_ns = o.step_ns; report->peak_bytes = fixed_bytes + o.slot_peak;
   report->d2h_bytes = o.d2h; report->h2d_bytes = o.h2d; report->n_replayed_ops = o.replayed;
   return DP_OK;

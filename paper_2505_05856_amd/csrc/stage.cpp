@@ -285,7 +285,7 @@ struct Flight {
   // what the plan in `plan` validated to (a schedule feeds the same plan again and again)
   uint64_t v_budget = 0; uint32_t v_inflight = 0, v_switches = ~0u;
   dp_plan_report v_report{};
-  long v_hold = 0;
+  SwapPolicy v_hold;
 };
 
 struct dp_stage {
@@ -320,7 +320,7 @@ struct dp_stage {
   uint64_t cached_budget = 0;
   uint32_t cached_switches = 0;
   dp_plan_report cached_report;
-  long cached_hold = 0;
+  SwapPolicy cached_hold;
   // The host may run at most kStepsInFlight steps ahead of the device: deeper command
   // backlogs made the runtime's copy path several times slower on plans that swap.
   static constexpr int kStepsInFlight = 2;
@@ -372,6 +372,7 @@ struct Walk {
   // kernel-selection switches; the dry walk must be given the same values as the live one
   bool mfma_enabled = true, fuse_gelu_enabled = true;
   long swap_hold_ticks = 0;   // how long a swapped-out block stays out of the free list (launch sites)
+  int prefetch_ahead = 1;     // layers of backward by which the swap-ins run ahead of their first use
   // report
   uint64_t d2h_bytes = 0, h2d_bytes = 0, kept_bytes = 0;
   // ---- cost simulation (dry walks only; see dp_plan_cost) -------------------------------
@@ -814,9 +815,15 @@ struct Walk {
     const size_t th = (size_t)T * H * c.esz, tf = (size_t)T * F * c.esz;
     const void *dcur = dy;   // gradient of the current layer's output
     Buf dcur_buf;            // its arena block, if the library owns it
-    prefetch_layer(c.L - 1);
+    // swap-ins run `prefetch_ahead` layers ahead of their first use, top layer first
+    int fetched_down_to = c.L;   // layers >= this one have had their swap-ins issued
+    auto prefetch_down_to = [&](int lo) {
+      for (int k = fetched_down_to - 1; k >= std::max(lo, 0); --k) prefetch_layer(k);
+      fetched_down_to = std::min(fetched_down_to, std::max(lo, 0));
+    };
+    prefetch_down_to(c.L - 1);
     for (int l = c.L - 1; l >= 0; --l) {
-      prefetch_layer(l - 1);
+      prefetch_down_to(l - prefetch_ahead);
       const LayerW *w = live ? &wts->w[(size_t)l] : nullptr;
       const dp_layer_grads *g = live ? &dw[l] : nullptr;
 #define W_(f) (live ? w->f : nullptr)
@@ -1150,7 +1157,7 @@ constexpr int kNumSwapHolds = 7;
 const long kSwapHolds[kNumSwapHolds] = {1L << 40, 96, 48, 24, 12, 6, 0};
 
 dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
-                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled, long *hold_out) {
+                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled, SwapPolicy *policy_out) {
   dp_plan_report local;
   dp_plan_report *r = rep ? rep : &local;
   memset(r, 0, sizeof *r);
@@ -1158,20 +1165,37 @@ dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t 
   dp_status s = check_plan(c, plan, plan_len, r);
   if (s != DP_OK) return s;
   if (inflight < 1) return fail(DP_E_INVAL, "inflight must be >= 1");
-  for (int attempt = 0; attempt < kNumSwapHolds; ++attempt) {
+  // Policies from the most generous down: the swap-ins as far ahead as the stage is deep, then
+  // half as far and so on to one layer, each with the hold spans from "until the forward ends"
+  // down to none.  Running ahead is given up before holding back: a late swap-in stalls one
+  // backward node, a block handed on behind its copy-out stalls the forward at every reuse.
+  std::vector<int> aheads;
+  for (int a = c.L; a > 1; a /= 2) aheads.push_back(a);
+  aheads.push_back(1);
+  auto run = [&](int ahead, long hold, int *n_swapped) {
     Walk w(c, plan, false, nullptr);
     w.mfma_enabled = mfma_enabled;
     w.fuse_gelu_enabled = fuse_gelu_enabled;
-    w.swap_hold_ticks = kSwapHolds[attempt];
+    w.swap_hold_ticks = hold;
+    w.prefetch_ahead = ahead;
     w.forward();
     w.backward();
     fill_report(c, w, r);
-    if (hold_out) *hold_out = kSwapHolds[attempt];
-    const bool fits = budget == 0 || (long double)inflight * (long double)r->peak_bytes <= (long double)budget;
-    // without a budget the caller wants the plan's memory saving: take the tightest policy
-    if (budget == 0 && attempt + 1 < kNumSwapHolds && w.n_swapped > 0) continue;
-    if (fits) return DP_OK;
+    if (policy_out) *policy_out = SwapPolicy{hold, ahead};
+    *n_swapped = w.n_swapped;
+  };
+  int n_swapped = 0;
+  if (budget == 0) {   // no budget: the caller wants the plan's memory saving, i.e. the tightest policy
+    run(1, 0, &n_swapped);
+    return DP_OK;
   }
+  for (size_t ai = 0; ai < aheads.size(); ++ai)
+    for (int attempt = 0; attempt < kNumSwapHolds; ++attempt) {
+      run(aheads[ai], kSwapHolds[attempt], &n_swapped);
+      if ((long double)inflight * (long double)r->peak_bytes <= (long double)budget) return DP_OK;
+      if (n_swapped == 0) goto out;   // nothing is swapped: every policy gives this peak
+    }
+out:
   return fail(DP_E_BUDGET, "plan needs %u x %llu bytes, budget is %llu", inflight,
               (unsigned long long)r->peak_bytes, (unsigned long long)budget);
 }
@@ -1180,11 +1204,12 @@ dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t 
 // Plays the step under `plan` on the three clocks of the cost model.  exact = false: the
 // planner's model (saved tensors only, no waits for handed-on arena blocks); exact = true:
 // the executor's own arena and hold policy for `budget`.
-CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bool exact, long hold_ticks) {
+CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bool exact, const SwapPolicy &policy) {
   Walk w(c, plan, false, nullptr);
   w.mfma_enabled = env_mfma_enabled();
   w.fuse_gelu_enabled = kFuseGeluDefault;
-  w.swap_hold_ticks = exact ? hold_ticks : 0;
+  w.swap_hold_ticks = exact ? policy.hold_ticks : 0;
+  w.prefetch_ahead = exact ? policy.ahead : 1;
   w.cm = &cm;
   w.sim_arena_waits = exact;
   w.no_arena = !exact;
@@ -1484,7 +1509,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   }
   dp_plan_report rep;
   const bool fuse_gelu = ((st->debug & 4u) != 0) != kFuseGeluDefault;   // debug bit 2 flips the default
-  long swap_hold = 0;
+  SwapPolicy swap_hold;
   const uint32_t switches = (st->use_mfma ? 1u : 0u) | (fuse_gelu ? 2u : 0u);
   if (plan != nullptr && st->cached_plan.size() == plan_len && st->cached_budget == budget_bytes &&
       st->cached_switches == switches && plan_len > 0 && memcmp(st->cached_plan.data(), plan, plan_len) == 0) {
@@ -1517,7 +1542,8 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   HIP_TRY(hipStreamWaitEvent(cs, st->current->ready, 0), DP_E_HIP);
   w.mfma_enabled = st->use_mfma;
   w.fuse_gelu_enabled = fuse_gelu;
-  w.swap_hold_ticks = swap_hold;
+  w.swap_hold_ticks = swap_hold.hold_ticks;
+  w.prefetch_ahead = swap_hold.ahead;
   w.cs = cs;
   const bool serial = (st->debug & 1u) != 0;
   w.d2h = serial ? cs : st->d2h;
@@ -1580,7 +1606,7 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   const bool fuse_gelu = ((st->debug & 4u) != 0) != kFuseGeluDefault;
   const uint32_t switches = (st->use_mfma ? 1u : 0u) | (fuse_gelu ? 2u : 0u);
   dp_plan_report rep;
-  long swap_hold = 0;
+  SwapPolicy swap_hold;
   dp_status s = DP_OK;
   if (plan != nullptr && plan_len > 0 && f.plan.size() == plan_len && f.v_budget == budget_bytes &&
       f.v_inflight == inflight && f.v_switches == switches && memcmp(f.plan.data(), plan, plan_len) == 0) {
@@ -1614,7 +1640,8 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   HIP_TRY(hipStreamWaitEvent((hipStream_t)hip_stream, st->current->ready, 0), DP_E_HIP);
   w->mfma_enabled = st->use_mfma;
   w->fuse_gelu_enabled = fuse_gelu;
-  w->swap_hold_ticks = swap_hold;
+  w->swap_hold_ticks = swap_hold.hold_ticks;
+  w->prefetch_ahead = swap_hold.ahead;
   w->cs = (hipStream_t)hip_stream;
   const bool serial = (st->debug & 1u) != 0;
   w->d2h = serial ? w->cs : st->d2h;

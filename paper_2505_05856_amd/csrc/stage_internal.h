@@ -60,15 +60,23 @@ bool env_mfma_enabled();
 
 // ------------------------------------------------------------------ the walk, dry
 dp_status check_plan(const Cfg &c, const uint8_t *plan, size_t plan_len, dp_plan_report *rep);
-// The static memory walk: fills `rep`, picks the hold policy that fits inflight * peak into
-// `budget` (0 = none: the tightest policy) and returns it in *hold_out.
+// How the executor spends memory a budget leaves over on the swaps of a plan (Appendix C.2 only
+// says that the copies are issued "at the appropriate points"):
+//   hold_ticks  launch sites for which a swapped-out block stays out of the free list, so that the
+//               forward does not wait for the link before it may reuse the block;
+//   ahead       layers of backward by which the swap-ins run ahead of their first use (1: the
+//               swap-ins of layer l-1 are issued when the backward of layer l starts).
+// The tightest policy {0, 1} gives a plan's smallest peak.
+struct SwapPolicy { long hold_ticks = 0; int ahead = 1; };
+// The static memory walk: fills `rep`, picks the first policy, from the most generous down, with
+// which inflight * peak fits `budget` (0 = no budget: the tightest) and returns it in *policy_out.
 dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
-                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled, long *hold_out = nullptr);
+                   dp_plan_report *rep, bool mfma_enabled, bool fuse_gelu_enabled, SwapPolicy *policy_out = nullptr);
 struct CostOut { int64_t step_ns; uint64_t slot_peak, arena_peak, d2h, h2d; int replayed; };
 // Plays the step under `plan` on the three clocks of the cost model.  exact = false: the
 // planner's model (saved tensors only, no waits for handed-on arena blocks); exact = true:
-// the executor's own arena and hold policy.
-CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bool exact, long hold_ticks);
+// the executor's own arena and swap policy.
+CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bool exact, const SwapPolicy &policy);
 
 // Time of node i of a layer in the cost model (decoder layers have thirteen nodes: 8..12 are
 // in the arrays that follow the plain layer's eight).

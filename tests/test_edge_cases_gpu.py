@@ -40,7 +40,10 @@ def test_empty_inputs_are_no_ops_and_empty_sums_are_zero(dt):
     for t in (dg, db, ds):
         assert torch.equal(t, torch.zeros_like(t))
     B.op_gelu_fwd(e, torch.zeros(1, cols, dtype=dt, device=DEV)[:0])
-    B.op_gelu_bwd(e, e, torch.zeros(1, cols, dtype=dt, device=DEV)[:0])
+    out = nan()
+    B.op_gelu_bwd(e, e, torch.zeros(1, cols, dtype=dt, device=DEV)[:0], out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, torch.zeros_like(out))
     # GEMM with an empty extent: nothing to write; K = 0: the product is zero, bias and residual remain
     a = torch.zeros(1, 64, dtype=dt, device=DEV)[:0]
     b = dev(rnd((128, 64), 3, dt), dt)

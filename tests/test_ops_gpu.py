@@ -75,19 +75,25 @@ def test_layernorm(dt, rows, cols, kind):
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("kind", [0, 1, 2])
-def test_gelu(dt, kind):
-    n = 8 * 1237
-    x = rnd((n,), 21, dt, 2.5)
-    dy = rnd((n,), 22, dt)
+@pytest.mark.parametrize("rows,cols", [(1237, 8), (77, 1032), (300, 4104)])
+def test_gelu(dt, kind, rows, cols):
+    """Forward, and the backward kernel the stage runs: dx = dy * gelu'(x) and the column sums of dx as stored."""
+    x = rnd((rows, cols), 21, dt, 2.5)
+    dy = rnd((rows, cols), 22, dt)
     name = ("erf", "tanh", "relu")[kind]
     tx, tdy = dev(x, dt), dev(dy, dt)
     y = torch.empty_like(tx); dx = torch.empty_like(tx)
+    db = torch.empty(cols, dtype=dt, device=DEV)
+    ws = ws_for(rows, cols)
     B.op_gelu_fwd(tx, y, kind)
-    B.op_gelu_bwd(tdy, tx, dx, kind)
+    B.op_gelu_bwd(tdy, tx, dx, db, ws, kind)
+    dx_ref = dy * O.gelu_grad(x.astype(np.float64), name)
     assert O.max_rel_err(host(y), O.gelu_fwd(x.astype(np.float64), name)) < TOL[dt]
-    assert O.max_rel_err(host(dx), dy * O.gelu_grad(x.astype(np.float64), name)) < TOL[dt]
-    B.op_gelu_bwd(tdy, tx, tdy, kind)     # in place
-    assert torch.equal(tdy, dx)
+    assert O.max_rel_err(host(dx), dx_ref) < TOL[dt]
+    assert O.max_rel_err(host(db), dx_ref.sum(axis=0)) < TOL[dt]
+    db2 = torch.empty_like(db)
+    B.op_gelu_bwd(tdy, tx, tdy, db2, ws, kind)     # in place
+    assert torch.equal(tdy, dx) and torch.equal(db2, db)
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
@@ -104,7 +110,7 @@ GEMM_SHAPES = [(1, 8, 8), (5, 16, 24), (64, 64, 64), (100, 72, 40), (128, 384, 1
                (300, 1600, 96), (512, 256, 1024), (1000, 520, 1032), (264, 136, 4104), (2048, 1024, 512),
                (4096, 4096, 192), (3900, 4200, 128),   # these two take the 256x256-tile path
                # ragged edges on each tile size of the LDS-direct kernel, both forms (rows of 8 elements for TN)
-               (200, 328, 192), (1096, 1304, 256), (3904, 4200, 128)]
+               (200, 328, 192), (1096, 1304, 256), (3904, 4200, 128), (3900, 4200, 448)]
 
 
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
@@ -202,3 +208,47 @@ def test_gemm_long_contractions_of_the_wide_configurations(mode, M, N, K):
     rows = np.arange(0, M, 509)[:6]; cols = np.arange(0, N, 613)[:6]
     exact = a[rows].astype(np.float64) @ b[:, cols].astype(np.float64)
     assert np.abs(got[np.ix_(rows, cols)] - exact).max() <= 2.0 ** -8 * np.abs(exact).max() + 1e-6
+
+
+# The column reductions at the token counts of the wide configurations (C5: 16384 tokens, C4: 32768): above 4096
+# (LayerNorm backward) or 8192 rows (the other two) a row block of the two-pass reductions covers more than its
+# minimum number of rows, a regime the smaller shapes above never enter.
+@pytest.mark.parametrize("rows", [16384, 32768])
+@pytest.mark.parametrize("cols", [1600, 4096])
+def test_layernorm_backward_over_many_rows(rows, cols):
+    dt = torch.bfloat16
+    fwd, bwd = O.NORMS["layer"]
+    x = syn.round_to_bf16(rnd((rows, cols), 11, dt, 2.0) + 0.5)
+    g = syn.round_to_bf16(rnd((cols,), 12, dt) * 0.1 + 1)
+    b = rnd((cols,), 13, dt, 0.1)
+    dy = rnd((rows, cols), 14, dt)
+    dres = rnd((rows, cols), 15, dt)
+    x64, g64 = x.astype(np.float64), g.astype(np.float64)
+    _, mu, r = fwd(x64, g64, b.astype(np.float64), 1e-5)
+    dx_ref, dg_ref, db_ref = bwd(dy.astype(np.float64), x64, mu, r, g64)
+    tx, tg, tdy, tres = (dev(a, dt) for a in (x, g, dy, dres))
+    stats = torch.from_numpy(np.stack([mu, r], axis=1).astype(np.float32)).to(DEV)
+    dx = torch.empty_like(tx); dgo = torch.empty_like(tg); dbo = torch.empty_like(tg); dsum = torch.empty_like(tg)
+    B.op_layernorm_bwd(tdy, tx, stats, tg, tres, dx, dgo, dbo, ws_for(rows, cols), dx_colsum=dsum)
+    assert O.max_rel_err(host(dx), dx_ref + dres) < TOL[dt]
+    assert O.max_rel_err(host(dgo), dg_ref) < TOL[dt] and O.max_rel_err(host(dbo), db_ref) < TOL[dt]
+    assert O.max_rel_err(host(dsum), host(dx).sum(axis=0)) < TOL[dt]
+
+
+@pytest.mark.parametrize("rows", [16384, 32768])
+@pytest.mark.parametrize("cols", [1600, 6400])
+def test_gelu_backward_and_column_sums_over_many_rows(rows, cols):
+    dt = torch.bfloat16
+    x = rnd((rows, cols), 21, dt, 2.5)
+    dy = rnd((rows, cols), 22, dt)
+    tx, tdy = dev(x, dt), dev(dy, dt)
+    dx = torch.empty_like(tx)
+    db = torch.empty(cols, dtype=dt, device=DEV)
+    ws = ws_for(rows, cols)
+    B.op_gelu_bwd(tdy, tx, dx, db, ws, 0)
+    dx_ref = dy * O.gelu_grad(x.astype(np.float64), "erf")
+    assert O.max_rel_err(host(dx), dx_ref) < TOL[dt]
+    assert O.max_rel_err(host(db), dx_ref.sum(axis=0)) < TOL[dt]
+    out = torch.empty(cols, dtype=dt, device=DEV)
+    B.op_colsum(tx, out, ws)
+    assert O.max_rel_err(host(out), x.astype(np.float64).sum(axis=0)) < TOL[dt]
