@@ -25,46 +25,44 @@ PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector 
 # HBM bytes per launch of the dominant kernel (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a 256 MiB
 # device copy gives), from the rocprofv3 --pmc runs summarised in profiles/c2_step_hbm_traffic_pmc.md.
 MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 80.3e6}
+# Average duration of an NT-form GEMM launch in the rocprofv3 kernel trace of the same command (profiles/*_kernel_trace.md).
+ROCPROF_NT_LAUNCH_US = {}
 
 
-def gemm_flops(cfg):
-    """Algorithmic FLOP per step of the three GEMM classes (2*M*N*K each)."""
-    T, H, F, L = cfg.tokens, cfg.hidden, cfg.ffn, cfg.n_layers
-    per_layer = 2.0 * T * (3 * H * H + H * H + 2 * H * F)
-    if cfg.mem_seq > 0:   # the cross-attention block: query and output projections, key/value projection of the memory
-        per_layer += 2.0 * (2 * T * H * H + cfg.mem_tokens * 2 * H * H)
-    return {"gemm_fwd": L * per_layer, "gemm_dgrad": L * per_layer, "gemm_wgrad": L * per_layer}
-
-
-def cpu_baseline(cfg, weights, x, dy, budget_s=30.0, mem=None):
-    """Oracle as it stands, on a bounded sample: the first layer of the stage on the
-    full micro-batch; if the whole stage fits the time budget it is then run whole,
-    otherwise the one-layer time is scaled by n_layers (every layer costs the same)."""
+def cpu_baseline(cfg, weights, x, dy, budget_s=25.0, mem=None):
+    """The oracle as it stands (fp64 numpy) on a bounded sample of the workload: the first layer of the stage on
+    the first sample of the micro-batch; if one layer on the whole micro-batch fits the time budget it is run on
+    that, and if the whole stage fits, on that.  The time is scaled to the whole step: every layer costs the
+    same, and no operator mixes samples, so the cost is linear in both."""
     import numpy as np
     from oracle import stage as O
 
-    def run(n_layers):
+    def run(n_layers, n_samples):
+        rows = n_samples * cfg.seq
         if cfg.mem_seq > 0:
             from oracle import decoder as Dc
-            st = Dc.DecoderStage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, cfg.micro_batch,
+            st = Dc.DecoderStage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.mem_seq, n_samples,
                                  cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden, norm=cfg.norm)
             t0 = time.perf_counter()
-            Dc.decoder_step(st, weights[:n_layers], x, mem, dy, dtype=np.float64)
+            Dc.decoder_step(st, weights[:n_layers], x[:rows], mem[:n_samples * cfg.mem_seq], dy[:rows], dtype=np.float64)
             return time.perf_counter() - t0
-        st = O.Stage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
+        st = O.Stage(n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, n_samples, cfg.norm_style,
                      cfg.causal, cfg.gelu, cfg.ln_eps, p_attn=cfg.p_attn, p_hidden=cfg.p_hidden, norm=cfg.norm)
         t0 = time.perf_counter()
-        O.stage_step(st, weights[:n_layers], x, dy, dtype=np.float64)
+        O.stage_step(st, weights[:n_layers], x[:rows], dy[:rows], dtype=np.float64)
         return time.perf_counter() - t0
 
-    dt1 = run(1)
-    if dt1 * cfg.n_layers <= budget_s:
-        dt = run(cfg.n_layers)
-        step_s, sample = dt, f"the whole step: all {cfg.n_layers} layers on the full micro-batch (fp64 numpy)"
-    else:
-        dt = dt1
-        step_s = dt1 * cfg.n_layers
-        sample = f"1 of {cfg.n_layers} layers on the full micro-batch (fp64 numpy), time scaled by {cfg.n_layers}"
+    L, B = cfg.n_layers, cfg.micro_batch
+    dt = run(1, 1)
+    layers, samples = 1, 1
+    if dt * B <= budget_s:
+        dt, samples = run(1, B), B
+        if dt * L <= budget_s:
+            dt, layers = run(L, B), L
+    step_s = dt * (L / layers) * (B / samples)
+    sample = (f"{layers} of {L} layers on {samples} of {B} samples (fp64 numpy), "
+              f"time scaled by {L // layers} x {B // samples}" if (layers, samples) != (L, B)
+              else f"the whole step: all {L} layers on the full micro-batch (fp64 numpy)")
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -144,19 +142,162 @@ def partition_and_measure(args, cfg, run):
     return out
 
 
+PLAN_MAKERS = {
+    "keep-all": lambda syn: syn.plan_keep_all,
+    "all-recompute": lambda syn: syn.plan_all_recompute,
+    "all-swap": lambda syn: syn.plan_all_swap,
+    "recompute-attention": lambda syn: syn.plan_recompute_attention,
+    "swap-fc1-recompute-ln-gelu": lambda syn: syn.plan_swap_ffn_recompute_norm_gelu,
+    "seed7-mixed": lambda syn: (lambda c: syn.plan_seeded(c, 7)),
+    "memopt": lambda syn: syn.plan_keep_all,
+}
+
+
+def workload_text(name, cfg):
+    return (f"{name}: {cfg.n_layers} {cfg.norm_style}-LN layers, hidden {cfg.hidden}, {cfg.n_heads} heads, "
+            f"ffn {cfg.ffn}, seq {cfg.seq}, micro-batch {cfg.micro_batch}, "
+            f"{'causal' if cfg.causal else 'full'} attention"
+            + (f", cross-attention over a memory of {cfg.mem_seq}" if cfg.mem_seq > 0 else "")
+            + (f", dropout {cfg.p_attn}" if cfg.p_attn > 0 else ""))
+
+
+def time_steps(run, plan, budget, warmup, steps):
+    """EXACTLY `steps` steps between two device synchronisations (wall clock), with HIP events on the launch
+    stream at the step boundaries (the paper times its iterations the same way, Appendix C.1)."""
+    import torch
+    for _ in range(warmup):
+        run.step(plan, budget)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        run.step(plan, budget)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    events = {"mean": round(sum(per_step) / len(per_step), 4), "median": round(per_step[len(per_step) // 2], 4),
+              "min": round(per_step[0], 4), "max": round(per_step[-1], 4)} if per_step else None
+    return ms, events
+
+
+def op_times_and_roofline(run, cfg, name, plan_name, plan, budget, k):
+    """The same steps again with every launch bracketed by HIP events on the launch stream: per-class times and
+    the roofline of the dominant class, the NT-form GEMM (forward and input-gradient contractions)."""
+    from paper_2505_05856_amd import binding as B
+    B.stage_set_profiling(run.stage, True)
+    for _ in range(k):
+        run.step(plan, budget)
+    times = B.stage_op_times(run.stage)
+    flops = B.stage_op_flops(run.stage)
+    B.stage_set_profiling(run.stage, False)
+    op_ms = {n: round(v[0] / k, 4) for n, v in times.items()}
+    nt_ms = (times["gemm_fwd"][0] + times["gemm_dgrad"][0]) / k
+    nt_launches = (times["gemm_fwd"][1] + times["gemm_dgrad"][1]) / k
+    # algorithmic work (2*M*N*K) of exactly the launches that were timed: the step's own forward and
+    # input-gradient GEMMs plus the forward ones a plan replays
+    nt_flops = (flops["gemm_fwd"] + flops["gemm_dgrad"]) / k
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+    achieved = nt_flops / (nt_ms * 1e-3) / 1e12
+    roof = {"kernel": "gemm_nt (forward + input-gradient GEMMs)", "bound": "mfma" if cfg.dtype == "bf16" else "alu",
+            "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+            "avg_launch_us": round(nt_ms * 1e3 / max(nt_launches, 1), 2),
+            "avg_launch_us_source": "HIP event pairs recorded around every launch on the launch stream (event overhead "
+                                    "included; the rocprofv3 kernel trace of the same command gives avg_launch_us_rocprof)",
+            "avg_launch_us_rocprof": ROCPROF_NT_LAUNCH_US.get((name, plan_name)),
+            "launches_per_step": nt_launches,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((name, plan_name))}
+    return op_ms, roof
+
+
+def swap_overlap(run, plan, budget, ms, stats, steps):
+    """(compute only + copies only - step) / min(compute only, copies only): compute only = the same plan with
+    every SWAP turned into KEEP; copies only = the plan's swap bytes out, then back in, through pinned memory."""
+    import numpy as np
+    import torch
+    import synthetic as syn
+    kept = np.where(plan == syn.SWAP, syn.KEEP, plan).astype(np.uint8)
+    for _ in range(2):
+        run.step(kept, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run.step(kept, 0)
+    torch.cuda.synchronize()
+    t_comp = (time.perf_counter() - t0) * 1e3 / steps
+    nslots = max(1, int((plan == syn.SWAP).sum()))
+    piece = stats["d2h_bytes"] // nslots
+    dev = torch.empty(piece, dtype=torch.uint8, device="cuda:0")
+    host = torch.empty(piece * nslots, dtype=torch.uint8).pin_memory()
+
+    def copies():
+        for i in range(nslots):
+            host[i * piece:(i + 1) * piece].copy_(dev, non_blocking=True)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(nslots):
+            dev.copy_(host[i * piece:(i + 1) * piece], non_blocking=True)
+        torch.cuda.synchronize()
+        return a
+    copies()
+    t0 = time.perf_counter(); mid = copies(); t1 = time.perf_counter()
+    t_out, t_in = (mid - t0) * 1e3, (t1 - mid) * 1e3
+    t_copy = t_out + t_in
+    ov = (t_comp + t_copy - ms) / min(t_comp, t_copy)
+    del dev, host
+    return {"step_ms": round(ms, 3), "compute_only_ms": round(t_comp, 3), "copy_only_ms": round(t_copy, 3),
+            "d2h_GBps": round(stats["d2h_bytes"] / t_out / 1e6, 2), "h2d_GBps": round(stats["h2d_bytes"] / t_in / 1e6, 2),
+            "overlap_frac": round(max(0.0, min(1.0, ov)), 4),
+            "definition": "(compute_only + copy_only - step) / min(compute_only, copy_only), clipped to [0,1]",
+            # measured inside the library, from HIP events on the copy streams and around the compute stream's waits
+            "in_library": {"d2h_busy_ms": round(stats["d2h_busy_ms"], 3), "h2d_busy_ms": round(stats["h2d_busy_ms"], 3),
+                           "compute_waited_for_swaps_ms": round(stats["swap_wait_ms"], 3),
+                           "replay_ms": round(stats["replay_ms"], 3)}}
+
+
+def measure(run, name, cfg, plan_name, plan, budget, warmup, steps, op_times=True, overlap=False):
+    """One workload under one plan: `steps` timed steps, then per-class times, statistics, overlap."""
+    from paper_2505_05856_amd import binding as B
+    _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
+    _, tight = B.plan_validate(run.bcfg, plan, budget_bytes=0)   # no budget: the tightest arena policy
+    ms, events = time_steps(run, plan, budget, warmup, steps)
+    op_ms = roof = None
+    if op_times:
+        op_ms, roof = op_times_and_roofline(run, cfg, name, plan_name, plan, budget, max(1, min(steps, 10)))
+    stats = run.step(plan, budget, want_stats=True)
+    tf = cfg.model_flops() / (ms * 1e-3) / 1e12
+    out = {"workload": workload_text(name, cfg), "plan": plan_name, "budget_bytes": budget,
+           "validator_peak_bytes": rep["peak_bytes"], "arena_peak_bytes": rep["arena_peak_bytes"],
+           "min_feasible_budget_bytes": tight["peak_bytes"], "fallback_launches": rep["n_fallback_launches"],
+           "ms_per_step": round(ms, 4), "samples_per_s": round(cfg.micro_batch / (ms * 1e-3), 3),
+           "model_tflops": round(tf, 2), "mfma_peak_frac": round(tf / PEAK_BF16_TFLOPS, 4),
+           "step_ms_by_hip_events": events, "fwd_ms": round(stats["fwd_ms"], 4), "bwd_ms": round(stats["bwd_ms"], 4),
+           "swap_bytes": {"d2h": stats["d2h_bytes"], "h2d": stats["h2d_bytes"]},
+           "replayed_ops": stats["n_replayed_ops"], "replay_ms": round(stats["replay_ms"], 3),
+           "kernel_launches": stats["n_kernel_launches"], "op_ms": op_ms, "roofline": roof}
+    if overlap and stats["d2h_bytes"] > 0:
+        out["swap_overlap"] = swap_overlap(run, plan, budget, ms, stats, steps)
+    return out, stats, rep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="C2", help="workload name from synthetic.CONFIGS")
+    ap.add_argument("--config", default=None,
+                    help="workload name from synthetic.CONFIGS; default: the largest workload under its budget (C5, "
+                         "its seeded plan, 64 GB) as the headline, with C2, C3, C4 and C5 keep-all under per_config")
     ap.add_argument("--plan", default=None, help="plan name (default: the config's own); 'memopt' generates one")
     ap.add_argument("--budget-frac", type=float, default=0.5,
                     help="with --plan memopt: budget as a fraction of the way from the all-recompute to the all-KEEP peak")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-op-times", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="default run: the headline workload only")
     ap.add_argument("--overlap", action="store_true",
-                    help="also time the plan with its SWAP slots kept (compute only) and its copies alone")
+                    help="also time the plan with its SWAP slots kept (compute only) and its copies alone "
+                         "(always on for the headline of the default run)")
     ap.add_argument("--inflight", type=int, default=0,
                     help="also time the steady state of a one-forward-one-backward schedule with this many "
                          "micro-batches between forward and backward (dp_stage_forward / dp_stage_backward)")
@@ -184,22 +325,17 @@ def main():
     from paper_2505_05856_amd.harness import StageRunner
 
     B.lib()   # fails loudly if the HIP library is not built
-    cfg = syn.CONFIGS[args.config]
+    default_run = args.config is None
+    name = args.config or "C5"
+    cfg = syn.CONFIGS[name]
     if args.dropout > 0:
         import dataclasses
         cfg = dataclasses.replace(cfg, p_attn=args.dropout, p_hidden=args.dropout)
-    plan_name, mk = syn.PLANS[args.config][0]
+    plan_name, mk = syn.PLANS[name][0]
     if args.plan:
-        plan_name, mk = {"keep-all": ("keep-all", syn.plan_keep_all),
-                         "all-recompute": ("all-recompute", syn.plan_all_recompute),
-                         "all-swap": ("all-swap", syn.plan_all_swap),
-                         "recompute-attention": ("recompute-attention", syn.plan_recompute_attention),
-                         "swap-fc1-recompute-ln-gelu": ("swap-fc1-recompute-ln-gelu",
-                                                        syn.plan_swap_ffn_recompute_norm_gelu),
-                         "seed7-mixed": ("seed7-mixed", lambda c: syn.plan_seeded(c, 7)),
-                         "memopt": ("memopt", syn.plan_keep_all)}[args.plan]
+        plan_name, mk = args.plan, PLAN_MAKERS[args.plan](syn)
     plan = mk(cfg)
-    budget = syn.BUDGETS.get(args.config, 0)
+    budget = syn.BUDGETS.get(name, 0)
     weights = syn.make_weights(cfg)
     x, dy = syn.make_activations(cfg)
     mem = syn.make_memory(cfg) if cfg.mem_seq > 0 else None
@@ -217,8 +353,6 @@ def main():
                   "predicted_ms": mrep["exact_step_ns"] / 1e6,
                   "free_swaps": mrep["n_free_swaps"], "paid_swaps": mrep["n_paid_swaps"],
                   "recomputed": mrep["n_recomputed"], "refine_rounds": mrep["refine_rounds"]}
-    _, rep = B.plan_validate(run.bcfg, plan, budget_bytes=budget)
-    _, tight = B.plan_validate(run.bcfg, plan, budget_bytes=0)   # no budget: the tightest arena policy
     if args.copy_calibration:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
@@ -227,82 +361,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        run.step(plan, budget)
-    # step boundaries are also marked with HIP events on the launch stream (the paper times its iterations the
-    # same way, Appendix C.1): their spread is reported beside the wall-clock mean that `value` comes from
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    marks[0].record()
-    for i in range(args.steps):
-        run.step(plan, budget)
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    step_events = {"mean": round(sum(per_step) / len(per_step), 4), "median": round(per_step[len(per_step) // 2], 4),
-                   "min": round(per_step[0], 4), "max": round(per_step[-1], 4)} if per_step else None
-
-    # per-kernel-class times: the same steps again with HIP event brackets on the launch stream
-    roof, op_ms = None, None
-    if not args.no_op_times:
-        B.stage_set_profiling(run.stage, True)
-        k = max(1, min(args.steps, 10))
-        for _ in range(k):
-            run.step(plan, budget)
-        times = B.stage_op_times(run.stage)
-        B.stage_set_profiling(run.stage, False)
-        op_ms = {n: round(v[0] / k, 4) for n, v in times.items()}
-        gf = gemm_flops(cfg)
-        nt_ms = (times["gemm_fwd"][0] + times["gemm_dgrad"][0]) / k
-        nt_launches = (times["gemm_fwd"][1] + times["gemm_dgrad"][1]) / k
-        nt_flops = gf["gemm_fwd"] + gf["gemm_dgrad"]
-        peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
-        achieved = nt_flops / (nt_ms * 1e-3) / 1e12
-        roof = {"kernel": "gemm_nt (forward + input-gradient GEMMs)", "bound": "mfma" if cfg.dtype == "bf16" else "alu",
-                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "avg_launch_us": round(nt_ms * 1e3 / max(nt_launches, 1), 2), "launches_per_step": nt_launches,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, plan_name))}
-    stats = run.step(plan, budget, want_stats=True)
-
-    overlap = None
-    if args.overlap and stats["d2h_bytes"] > 0:
-        # compute only: the same plan with every SWAP turned into KEEP
-        import numpy as np
-        kept = np.where(plan == syn.SWAP, syn.KEEP, plan).astype(np.uint8)
-        for _ in range(2):
-            run.step(kept, 0)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            run.step(kept, 0)
-        torch.cuda.synchronize()
-        t_comp = (time.perf_counter() - t0) * 1e3 / args.steps
-        # copies only: the plan's swap bytes out, then back in, through pinned host memory in slot-sized pieces
-        nslots = max(1, int((plan == syn.SWAP).sum()))
-        piece = stats["d2h_bytes"] // nslots
-        dev = torch.empty(piece, dtype=torch.uint8, device="cuda:0")
-        host = torch.empty(piece * nslots, dtype=torch.uint8).pin_memory()
-        def copies():
-            for i in range(nslots):
-                host[i * piece:(i + 1) * piece].copy_(dev, non_blocking=True)
-            torch.cuda.synchronize()
-            a = time.perf_counter()
-            for i in range(nslots):
-                dev.copy_(host[i * piece:(i + 1) * piece], non_blocking=True)
-            torch.cuda.synchronize()
-            return a
-        copies()
-        t0 = time.perf_counter(); mid = copies(); t1 = time.perf_counter()
-        t_out, t_in = (mid - t0) * 1e3, (t1 - mid) * 1e3
-        t_copy = t_out + t_in
-        ov = (t_comp + t_copy - ms) / min(t_comp, t_copy)
-        overlap = {"step_ms": round(ms, 3), "compute_only_ms": round(t_comp, 3), "copy_only_ms": round(t_copy, 3),
-                   "d2h_GBps": round(stats["d2h_bytes"] / t_out / 1e6, 2), "h2d_GBps": round(stats["h2d_bytes"] / t_in / 1e6, 2),
-                   "overlap_frac": round(max(0.0, min(1.0, ov)), 4),
-                   "definition": "(compute_only + copy_only - step) / min(compute_only, copy_only), clipped to [0,1]"}
-        del dev, host
+    head, stats, rep = measure(run, name, cfg, plan_name, plan, budget, args.warmup, args.steps,
+                               op_times=not args.no_op_times, overlap=args.overlap or default_run)
+    ms = head["ms_per_step"]
 
     schedule = None
     if args.inflight > 0:
@@ -329,30 +390,55 @@ def main():
     if args.partition > 0:
         partition = partition_and_measure(args, cfg, run)
 
+    # the other workloads of the metric, each under its own plan and budget, in the same JSON line
+    per_config = None
+    if default_run and not args.no_per_config:
+        per_config = {}
+        keep, _, _ = measure(run, name, cfg, "keep-all", syn.plan_keep_all(cfg), budget, 2, max(3, args.steps // 2),
+                             op_times=not args.no_op_times)
+        per_config["C5 keep-all"] = keep
+    run.close()
+    del run
+    if per_config is not None:
+        shared_w = {}
+        for other in ("C2", "C3", "C4"):
+            ocfg = syn.CONFIGS[other]
+            oname, omk = syn.PLANS[other][0]
+            key = (ocfg.n_layers, ocfg.hidden, ocfg.ffn, ocfg.n_heads)
+            if key not in shared_w:     # C4 is C3's stage at a larger micro-batch: the same seeded weights
+                shared_w[key] = syn.make_weights(ocfg)
+            ox, ody = syn.make_activations(ocfg)
+            orun = StageRunner(ocfg, shared_w[key], ox, ody)
+            swaps = other == "C4"
+            res, _, _ = measure(orun, other, ocfg, oname, omk(ocfg), syn.BUDGETS.get(other, 0), 3,
+                                args.steps if not swaps else max(3, args.steps // 2),
+                                op_times=not args.no_op_times, overlap=swaps)
+            per_config[other] = res
+            orun.close()
+            del orun, ox, ody
+            torch.cuda.empty_cache()
+
     out = {
         "metric": "stage fwd+bwd samples/sec + MFMA util % at fixed memory budget",
-        "value": round(cfg.micro_batch / (ms * 1e-3), 3), "unit": "samples/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "value": head["samples_per_s"], "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{args.config}: {cfg.n_layers} {cfg.norm_style}-LN layers, hidden {cfg.hidden}, "
-                               f"{cfg.n_heads} heads, ffn {cfg.ffn}, seq {cfg.seq}, micro-batch {cfg.micro_batch}, "
-                               f"{'causal' if cfg.causal else 'full'} attention"
-                               + (f", cross-attention over a memory of {cfg.mem_seq}" if cfg.mem_seq > 0 else "")
-                               + (f", dropout {cfg.p_attn}" if cfg.p_attn > 0 else ""),
-                   "plan": plan_name, "budget_bytes": budget, "validator_peak_bytes": rep["peak_bytes"],
-                   "arena_peak_bytes": rep["arena_peak_bytes"],
-                   "min_feasible_budget_bytes": tight["peak_bytes"]},
-        "model_tflops": round(cfg.model_flops() / (ms * 1e-3) / 1e12, 2),
-        "mfma_peak_frac": round(cfg.model_flops() / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "step_ms_by_hip_events": step_events,
-        "fwd_ms": round(stats["fwd_ms"], 4), "bwd_ms": round(stats["bwd_ms"], 4),
-        "swap_bytes": {"d2h": stats["d2h_bytes"], "h2d": stats["h2d_bytes"]},
-        "replayed_ops": stats["n_replayed_ops"], "kernel_launches": stats["n_kernel_launches"],
-        "op_ms": op_ms, "roofline": roof,
+        "config": {"workload": head["workload"], "plan": plan_name, "budget_bytes": budget,
+                   "validator_peak_bytes": head["validator_peak_bytes"], "arena_peak_bytes": head["arena_peak_bytes"],
+                   "min_feasible_budget_bytes": head["min_feasible_budget_bytes"],
+                   "fallback_launches": head["fallback_launches"]},
+        "model_tflops": head["model_tflops"], "mfma_peak_frac": head["mfma_peak_frac"],
+        "step_ms_by_hip_events": head["step_ms_by_hip_events"],
+        "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"], "swap_bytes": head["swap_bytes"],
+        "replayed_ops": head["replayed_ops"], "replay_ms": head["replay_ms"], "kernel_launches": head["kernel_launches"],
+        "op_ms": head["op_ms"], "roofline": head["roofline"],
     }
-    if overlap is not None:
-        out["swap_overlap"] = overlap
+    roof = head["roofline"]
+    if "swap_overlap" in head:
+        out["swap_overlap"] = head["swap_overlap"]
+    if per_config is not None:
+        out["per_config"] = per_config
     if schedule is not None:
         out["schedule"] = schedule
     if partition is not None:
@@ -364,7 +450,6 @@ def main():
     if memopt is not None:
         memopt["measured_ms"] = round(ms, 4)
         out["memopt"] = memopt
-    run.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, weights, x, dy, mem=mem)
     print(json.dumps(out))

@@ -167,12 +167,25 @@ typedef struct {
   double replay_flops, step_flops;
   int32_t n_replayed_ops, n_swapped_slots;
   int32_t first_bad_layer, first_bad_slot; /* -1 if none */
+  /* launches of a bf16 stage that this shape sends to the vector-ALU kernels instead of the
+   * matrix cores (a GEMM with a contraction that is no multiple of 8 or an unaligned operand,
+   * attention with a head dimension other than 64 or 128): 20-50 times slower each; 0 for every
+   * shape the kernels were written for */
+  int32_t n_fallback_launches;
 } dp_plan_report;
 
+/* Statistics of one step (asking for them makes dp_stage_step wait for the step).  The times
+ * come from HIP events: step/fwd/bwd on the caller's stream; d2h_busy_ms and h2d_busy_ms are
+ * the summed durations of the plan's copies, each bracketed on the copy stream it ran on;
+ * swap_wait_ms is the time the compute stream spent waiting for a swap-in it needed, or for a
+ * block handed on behind a copy-out (what the swaps cost that did not overlap with
+ * computation, Section 4.3); replay_ms the time of the recomputed forward nodes. */
 typedef struct {
   float step_ms, fwd_ms, bwd_ms;
   uint64_t d2h_bytes, h2d_bytes, arena_high_water, peak_bytes;
   int32_t n_kernel_launches, n_replayed_ops;
+  float replay_ms, d2h_busy_ms, h2d_busy_ms, swap_wait_ms;
+  int32_t n_fallback_launches; /* as in dp_plan_report */
 } dp_step_stats;
 
 /* Kernel classes for dp_stage_op_times. */
@@ -402,6 +415,10 @@ dp_status dp_stage_bind_memory(dp_stage *st, const void *mem, void *d_mem, const
  * counts per class since the last call; arrays of DP_OPC_COUNT entries. */
 dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled);
 dp_status dp_stage_op_times(dp_stage *st, float *ms_by_class, uint64_t *launches_by_class);
+/* Algorithmic work of the GEMM launches bracketed since the last call, 2*M*N*K each, summed per
+ * class (DP_OPC_GEMM_FWD counts replayed forward GEMMs as well; the other classes stay 0), so
+ * that a rate can be formed from exactly the launches that were timed.  Clears the sums. */
+dp_status dp_stage_op_flops(dp_stage *st, double *flops_by_class);
 
 /* The pipeline partition search (Section 4.2, Algorithm 1: AdjacentPartition and BiPar; the
  * compute- and memory-balanced positions of Appendix B.1, Algorithm 2; dp_plan_generate's

@@ -299,8 +299,12 @@ def plan_cost(shape: StageShape, cm: CostModel, plan, fixed_bytes: int = 0) -> D
         raise KeyError(name)
 
     def prefetch(l):
+        """The swap-ins of layer l, in the order its backward first reads them."""
         if l >= 0:
-            for n in SLOTS:
+            for _, reads, _ in bwd:
+                for n in reads:
+                    swap_in((l, n))        # (a second call finds the tensor on the device)
+            for n in SLOTS:                # whatever no backward node reads
                 swap_in((l, n))
 
     prefetch(L - 1)

@@ -57,7 +57,8 @@ class PlanReport(C.Structure):
                                           "weight_bytes", "grad_bytes", "kept_act_bytes", "swap_out_bytes",
                                           "swap_in_bytes", "host_pinned_bytes")] + \
                [("replay_flops", C.c_double), ("step_flops", C.c_double)] + \
-               [(n, C.c_int32) for n in ("n_replayed_ops", "n_swapped_slots", "first_bad_layer", "first_bad_slot")]
+               [(n, C.c_int32) for n in ("n_replayed_ops", "n_swapped_slots", "first_bad_layer", "first_bad_slot",
+                                         "n_fallback_launches")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -66,7 +67,9 @@ class PlanReport(C.Structure):
 class StepStats(C.Structure):
     _fields_ = [("step_ms", C.c_float), ("fwd_ms", C.c_float), ("bwd_ms", C.c_float)] + \
                [(n, C.c_uint64) for n in ("d2h_bytes", "h2d_bytes", "arena_high_water", "peak_bytes")] + \
-               [("n_kernel_launches", C.c_int32), ("n_replayed_ops", C.c_int32)]
+               [("n_kernel_launches", C.c_int32), ("n_replayed_ops", C.c_int32)] + \
+               [(n, C.c_float) for n in ("replay_ms", "d2h_busy_ms", "h2d_busy_ms", "swap_wait_ms")] + \
+               [("n_fallback_launches", C.c_int32)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -139,6 +142,7 @@ def lib() -> C.CDLL:
     L.dp_stage_weight_versions.restype = i32
     L.dp_stage_set_profiling.argtypes = [vp, i32]
     L.dp_stage_op_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(u64)]
+    L.dp_stage_op_flops.argtypes = [vp, C.POINTER(C.c_double)]
     L.dp_stage_set_debug.argtypes = [vp, C.c_uint32]
     L.dp_stage_destroy.argtypes = [vp]
     L.dp_stage_destroy.restype = None
@@ -168,7 +172,7 @@ def lib() -> C.CDLL:
                                    sz, C.POINTER(MemoptReport)]
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
     for name in ("dp_probe_mfma", "dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_cross", "dp_stage_bind_memory", "dp_stage_set_profiling",
-                 "dp_stage_op_times", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
+                 "dp_stage_op_times", "dp_stage_op_flops", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
                  "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
                  "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd",
                  "dp_op_cross_attention_fwd", "dp_op_cross_attention_bwd",
@@ -398,6 +402,12 @@ def stage_op_times(stage: Stage):
     cnt = (C.c_uint64 * len(OP_CLASSES))()
     _check(lib().dp_stage_op_times(stage.handle, ms, cnt))
     return {n: (float(ms[i]), int(cnt[i])) for i, n in enumerate(OP_CLASSES)}
+
+
+def stage_op_flops(stage: Stage):
+    f = (C.c_double * len(OP_CLASSES))()
+    _check(lib().dp_stage_op_flops(stage.handle, f))
+    return {n: f[i] for i, n in enumerate(OP_CLASSES)}
 
 
 def stage_measure_cost_model(stage: Stage, x_in, dy, y_out, dx_out, grads, steps: int = 3, stream=None) -> CostModel:

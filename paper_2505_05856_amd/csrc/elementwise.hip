@@ -9,6 +9,7 @@
 #include "common.h"
 #include "kernels.h"
 
+
 #include <type_traits>
 
 namespace dp {

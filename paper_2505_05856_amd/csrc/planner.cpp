@@ -23,19 +23,16 @@ dp_status check_cost_model(const dp_cost_model *cm) {
   return DP_OK;
 }
 
-// Saved tensors a backward node reads, in the node order of each style (FreeTime needs the
-// first backward reader of every candidate).
-struct BwdReads { int n; int slot[3]; };
-const BwdReads kPreBwd[N_OPS] = {
+extern const BwdReads kPreBwd[N_OPS] = {
     {1, {DP_SLOT_GELU_OUT}}, {1, {DP_SLOT_FC1_OUT}}, {1, {DP_SLOT_LN2_OUT}}, {2, {DP_SLOT_RES1, DP_SLOT_LN2_STATS}},
     {1, {DP_SLOT_ATTN_OUT}}, {3, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE}}, {1, {DP_SLOT_LN1_OUT}},
     {2, {DP_SLOT_X_IN, DP_SLOT_LN1_STATS}}};
-const BwdReads kPostBwd[N_OPS] = {
+extern const BwdReads kPostBwd[N_OPS] = {
     {2, {DP_SLOT_RES2, DP_SLOT_LN2_STATS}}, {1, {DP_SLOT_GELU_OUT}}, {1, {DP_SLOT_FC1_OUT}}, {1, {DP_SLOT_LN1_OUT}},
     {2, {DP_SLOT_RES1, DP_SLOT_LN1_STATS}}, {1, {DP_SLOT_ATTN_OUT}},
     {3, {DP_SLOT_QKV, DP_SLOT_ATTN_OUT, DP_SLOT_ATTN_LSE}}, {1, {DP_SLOT_X_IN}}};
 
-const BwdReads kPreCrossBwd[N_OPS_CROSS] = {
+extern const BwdReads kPreCrossBwd[N_OPS_CROSS] = {
     {1, {DP_SLOT_GELU_OUT}}, {1, {DP_SLOT_FC1_OUT}}, {1, {DP_SLOT_LN2_OUT}}, {2, {DP_SLOT_RES_C, DP_SLOT_LN2_STATS}},
     {1, {DP_SLOT_ATTN_C_OUT}}, {3, {DP_SLOT_Q_C, DP_SLOT_KV_C, DP_SLOT_ATTN_C_LSE}}, {0, {}}, {1, {DP_SLOT_LNC_OUT}},
     {2, {DP_SLOT_RES1, DP_SLOT_LNC_STATS}},
@@ -80,7 +77,7 @@ bool memopt(const Cfg &c, const dp_cost_model &cm_given, uint64_t budget, uint32
             std::vector<uint8_t> &plan, dp_memopt_report *rep) {
   const dp_cost_model cm = for_inflight(cm_given, inflight);
   const OpDef *ops = op_table(c);
-  const BwdReads *bwd = c.cross ? kPreCrossBwd : c.pre ? kPreBwd : kPostBwd;
+  const BwdReads *bwd = bwd_table(c);
   const int n_ops = op_count(c), ns = c.nslots;
   plan.assign((size_t)c.L * (size_t)ns, DP_KEEP);
   auto cost = [&](const std::vector<uint8_t> &p, int64_t *t, uint64_t *peak) {
@@ -202,6 +199,29 @@ dp_status memopt_validated(const Cfg &c, const dp_cost_model &cm, uint64_t budge
     const uint64_t next = target > excess ? (target - excess) * inflight : 0;
     if (next == 0 || next >= model_budget) { if (model_budget < 2) break; model_budget = std::min(model_budget - 1, next ? next : model_budget / 2); }
     else model_budget = next;
+  }
+  // The greedy phase can end a few percent above the smallest peak a plan can have.  Last resort:
+  // recompute everything (each layer's input kept), the plan with the least saved memory that
+  // moves nothing over the link.
+  if (budget_bytes != 0) {
+    std::vector<uint8_t> lean(plan_len, DP_RECOMPUTE);
+    for (int l = 0; l < c.L; ++l) lean[(size_t)l * (size_t)c.nslots + DP_SLOT_X_IN] = DP_KEEP;
+    dp_plan_report vr;
+    SwapPolicy hold;
+    if (validate(c, lean.data(), plan_len, budget_bytes, inflight, &vr, env_mfma_enabled(), kFuseGeluDefault, &hold) == DP_OK) {
+      const dp_cost_model cmi = for_inflight(cm, inflight);
+      const CostOut o = walk_cost(c, cmi, lean.data(), false, SwapPolicy{});
+      plan = lean;
+      r->feasible = 1;
+      r->moo_ns = o.step_ns - r->base_ns;
+      r->peak_bytes = fixed + o.slot_peak;
+      r->n_free_swaps = r->n_paid_swaps = 0;
+      r->n_recomputed = 0;
+      for (size_t k = 0; k < plan_len; ++k) r->n_recomputed += lean[k] == DP_RECOMPUTE;
+      r->validated_peak_bytes = vr.peak_bytes;
+      r->exact_step_ns = walk_cost(c, cmi, lean.data(), true, hold).step_ns;
+      return DP_OK;
+    }
   }
   r->feasible = 0;
   return DP_E_BUDGET;

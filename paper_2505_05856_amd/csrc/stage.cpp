@@ -299,12 +299,15 @@ struct dp_stage {
   void *host_pool = nullptr;
   uint64_t host_bytes = 0;
   hipStream_t d2h = nullptr, h2d = nullptr;
+  hipStream_t d2hx = nullptr;   // second copy-out stream ("express", see Walk::swap_out)
   std::vector<hipEvent_t> events;       // sync events (no timing)
   bool profiling = false;
   std::vector<hipEvent_t> prof_events;  // timing pairs
   std::vector<int> prof_class;
   std::vector<uint32_t> prof_tag;       // node of each bracket: phase << 16 | layer << 4 | node
   size_t prof_used = 0;
+  double prof_flops[DP_OPC_COUNT] = {};  // algorithmic FLOP of the bracketed GEMM launches, by class
+  std::vector<hipEvent_t> span_events;  // timing events of a step that reports statistics
   uint32_t debug = 0;
   bool use_mfma = true;
   std::vector<std::unique_ptr<Flight>> flights;   // indexed by the caller's micro-batch slot
@@ -343,6 +346,7 @@ struct SlotState {
 
 struct Buf { uint64_t off = UINT64_MAX, bytes = 0; };
 
+
 struct Walk {
   const Cfg &c;
   const uint8_t *plan;
@@ -356,6 +360,35 @@ struct Walk {
   bool accumulate = false;      // weight gradients are added to what the caller's buffers hold
   hipStream_t cs = nullptr; // compute stream (caller's)
   hipStream_t d2h = nullptr, h2d = nullptr;
+  // The backward needs what the top layers swapped out first, and those copy-outs are the last
+  // to be queued: behind the bulk of the lower layers' copies on one first-in-first-out stream
+  // they would land long after the backward has asked for them back.  The copy-outs of the top
+  // layers therefore go to a stream of their own (both share the link): the layers from
+  // `express_from` up, which hold at most a quarter of the bytes the plan swaps (more, and the
+  // top layer's copies queue behind too much on that stream as well), but always the topmost
+  // layer that swaps anything.
+  hipStream_t d2hx = nullptr;
+  bool use_express = false;
+  int express_from = -1;   // -1: not worked out yet
+  bool on_express(int l) {
+    if (!use_express || d2hx == nullptr) return false;
+    if (express_from < 0) {
+      std::vector<uint64_t> per_layer((size_t)c.L, 0);
+      uint64_t total = 0;
+      for (int k = 0; k < c.L; ++k)
+        for (int slot = 0; slot < c.nslots; ++slot)
+          if (action(k, slot) == DP_SWAP) { per_layer[(size_t)k] += slot_bytes(c, slot); total += slot_bytes(c, slot); }
+      express_from = c.L;
+      uint64_t sum = 0;
+      for (int k = c.L - 1; k >= 0; --k) {
+        if (per_layer[(size_t)k] == 0) { if (sum == 0) continue; }
+        if (sum > 0 && (sum + per_layer[(size_t)k]) * 4 > total) break;
+        sum += per_layer[(size_t)k];
+        express_from = k;
+      }
+    }
+    return l >= express_from;
+  }
   const void *x_in = nullptr, *dy = nullptr;
   void *y_out = nullptr, *dx_out = nullptr;
   const dp_layer_grads *dw = nullptr;
@@ -373,6 +406,7 @@ struct Walk {
   bool mfma_enabled = true, fuse_gelu_enabled = true;
   long swap_hold_ticks = 0;   // how long a swapped-out block stays out of the free list (launch sites)
   int prefetch_ahead = 1;     // layers of backward by which the swap-ins run ahead of their first use
+  bool hold_through_backward = false;   // blocks held at the end of the forward stay held
   // report
   uint64_t d2h_bytes = 0, h2d_bytes = 0, kept_bytes = 0;
   // ---- cost simulation (dry walks only; see dp_plan_cost) -------------------------------
@@ -382,7 +416,7 @@ struct Walk {
   // modelled time to the compute clock and a copy its size over the link speed to its copy
   // clock.  The dry walk then stands for the streams with the small integers 1, 2, 3.
   const dp_cost_model *cm = nullptr;
-  int64_t clk[3] = {0, 0, 0};
+  int64_t clk[4] = {0, 0, 0, 0};   // compute, copy-out, copy-in, express copy-out
   std::vector<int64_t> ev_ns;
   bool sim_arena_waits = false;            // also wait where a block is handed on behind a copy-out
   bool no_arena = false;                   // the planner's model: saved tensors only, no offsets (the searches play thousands of plans)
@@ -394,6 +428,29 @@ struct Walk {
       if (lingering[i].first <= clk[0]) { slot_live -= lingering[i].second; lingering.erase(lingering.begin() + (long)i); }
       else ++i;
   }
+  // A step that reports statistics times its copies (on their streams), the waits of the compute
+  // stream for a swap-in or for a block handed on behind a copy-out, and its replays.
+  enum SpanKind { SPAN_D2H = 0, SPAN_H2D, SPAN_WAIT, SPAN_REPLAY };
+  struct Span { int kind, l, slot; size_t ev; uint64_t bytes; };
+  std::vector<Span> *spans = nullptr;
+  size_t span_used = 0;
+  void span_begin(int kind, int l, int slot, hipStream_t s, uint64_t bytes = 0) {
+    if (!live || spans == nullptr) return;
+    while (st->span_events.size() < span_used + 2) {
+      hipEvent_t e;
+      check(hipEventCreate(&e));
+      if (herr != hipSuccess) return;
+      st->span_events.push_back(e);
+    }
+    spans->push_back(Span{kind, l, slot, span_used, bytes});
+    check(hipEventRecord(st->span_events[span_used], s));
+  }
+  void span_end(hipStream_t s) {
+    if (!live || spans == nullptr || herr != hipSuccess) return;
+    check(hipEventRecord(st->span_events[span_used + 1], s));
+    span_used += 2;
+  }
+  int n_fallback = 0;                      // launches of a bf16 stage that took a vector-ALU kernel
   uint32_t tag = 0;                        // node the next launches belong to (timing brackets)
   double replay_flops = 0, step_flops = 0;
   int n_replayed = 0, n_swapped = 0, n_launch = 0;
@@ -451,7 +508,11 @@ struct Walk {
     if (no_arena) return 0;
     std::vector<int> waits;
     const uint64_t off = arena.alloc(bytes, &waits);
-    if (live || sim_arena_waits) for (int ev : waits) wait(cs, ev);
+    if (live || sim_arena_waits) {
+      if (!waits.empty()) span_begin(SPAN_WAIT, -1, -1, cs);
+      for (int ev : waits) wait(cs, ev);
+      if (!waits.empty()) span_end(cs);
+    }
     return off;
   }
   void arena_release(uint64_t off, uint64_t bytes, int pending_event = -1) {
@@ -510,6 +571,8 @@ struct Walk {
   }
   void gemm(int cls, int mode, long M, long N, long K, const void *A, const void *B, const void *bias,
             const void *res, void *C, void *gelu_out = nullptr) {
+    if (c.dtype == DP_BF16 && mfma_enabled && !gemm_on_mfma(mode, M, N, K)) ++n_fallback;
+    if (live && st->profiling) st->prof_flops[cls] += 2.0 * (double)M * (double)N * (double)K;
     prof_begin(cls);
     if (live) {
       dp::GemmArgs a{mode, (int)M, (int)N, (int)K, A, B, bias, res, C};
@@ -609,6 +672,7 @@ struct Walk {
              live ? w->b_qkv : nullptr, nullptr, out0);
         break;
       case OP_ATTN:
+        if (c.dtype == DP_BF16 && mfma_enabled && !dp::attn_mfma_supported(c.S, c.dh)) ++n_fallback;
         prof_begin(DP_OPC_ATTN_FWD);
         if (live) {
           const dp::DropArgs da = dp::make_drop_args(rng_seed, rng_mb, l, dp::kSiteAttn, c.p_attn);
@@ -657,6 +721,7 @@ struct Walk {
              live ? wts->xw[(size_t)l].b_kv : nullptr, nullptr, out0);
         break;
       case OP_ATTNC:
+        if (c.dtype == DP_BF16 && mfma_enabled && !dp::attn_mfma_supported(c.Sm, c.dh)) ++n_fallback;
         prof_begin(DP_OPC_ATTN_FWD);
         if (live) {
           const dp::AttnView v = cross_view(in(0), in(1), nullptr, nullptr);
@@ -694,14 +759,17 @@ struct Walk {
     if (live || cm) {
       const int produced = new_event();
       record(produced, cs);
-      wait(d2h, produced);
-      if (live) check(hipMemcpyAsync(host_base + s.host_off, base() + s.off, bytes, hipMemcpyDeviceToHost, d2h));
-      else clk[1] += copy_ns(bytes, cm->d2h_bytes_per_us);
-      record(done, d2h);
+      hipStream_t out = on_express(l) ? d2hx : d2h;
+      wait(out, produced);
+      span_begin(SPAN_D2H, l, slot, out, bytes);
+      if (live) check(hipMemcpyAsync(host_base + s.host_off, base() + s.off, bytes, hipMemcpyDeviceToHost, out));
+      else clk[clock_of(out)] += copy_ns(bytes, cm->d2h_bytes_per_us);
+      span_end(out);
+      record(done, out);
     }
     d2h_bytes += bytes;
     ++n_swapped;
-    if (cm) lingering.push_back({clk[1], bytes}); else slot_live -= bytes;
+    if (cm) lingering.push_back({clk[clock_of(on_express(l) ? d2hx : d2h)], bytes}); else slot_live -= bytes;
     arena_release(s.off, bytes, done);
     s.out_event = done;
     s.where = ON_HOST;
@@ -720,17 +788,23 @@ struct Walk {
       record(region_free, cs);
       wait(h2d, region_free);
       wait(h2d, s.out_event);   // the copy-out of this slot must have landed in the host pool
+      span_begin(SPAN_H2D, l, slot, h2d, bytes);
       if (live) check(hipMemcpyAsync(base() + s.off, host_base + s.host_off, bytes, hipMemcpyHostToDevice, h2d));
       else clk[2] += copy_ns(bytes, cm->h2d_bytes_per_us);
+      span_end(h2d);
       record(done, h2d);
     }
     h2d_bytes += bytes;
     s.ready_event = done;
     s.where = RESIDENT;
   }
+  // The swap-ins of layer l, in the order its backward first reads them.
   void prefetch_layer(int l) {
     if (l < 0) return;
-    for (int slot = 0; slot < c.nslots; ++slot) swap_in(l, slot);
+    const BwdReads *bwd = bwd_table(c);
+    for (int i = 0; i < n_ops(); ++i)
+      for (int k = 0; k < bwd[i].n; ++k) swap_in(l, bwd[i].slot[k]);   // (a second call finds the slot resident)
+    for (int slot = 0; slot < c.nslots; ++slot) swap_in(l, slot);      // whatever no backward node reads
   }
 
   // Makes slot (l, slot) readable by the compute stream: waits for its swap-in,
@@ -739,7 +813,12 @@ struct Walk {
     SlotState &s = S(l, slot);
     if (s.where == ON_HOST) swap_in(l, slot);
     if (s.where == RESIDENT) {
-      if (s.ready_event >= 0) { wait(cs, s.ready_event); s.ready_event = -1; }
+      if (s.ready_event >= 0) {
+        span_begin(SPAN_WAIT, l, slot, cs);
+        wait(cs, s.ready_event);
+        span_end(cs);
+        s.ready_event = -1;
+      }
       return;
     }
     // ABSENT: replay.  X_IN of layer l is produced by the last op of layer l-1.
@@ -757,7 +836,9 @@ struct Walk {
       if (t.where == ABSENT && !t.consumed) { slot_alloc(ol, os); outp[o] = ptr(ol, os); }
     }
     begin_node(TAG_REPLAY, pl, (int)(d - ops()));
+    span_begin(SPAN_REPLAY, pl, (int)(d - ops()), cs);
     run_op(pl, *d, outp[0], outp[1]);
+    span_end(cs);
     ++n_replayed;
     replay_flops += op_flops(c, d->op);
   }
@@ -810,7 +891,9 @@ struct Walk {
   // ---- backward ------------------------------------------------------------------
   void backward() {
     in_backward = true;
-    arena.release_all_held();   // forward is over: nothing is gained by holding blocks back any longer
+    // forward is over; unless the policy holds them on (their copy-outs may still be on their way, and
+    // the first blocks the backward allocates would wait for them), the held blocks rejoin the free list
+    if (!hold_through_backward) arena.release_all_held();
     const long T = c.T, H = c.H, F = c.F;
     const size_t th = (size_t)T * H * c.esz, tf = (size_t)T * F * c.esz;
     const void *dcur = dy;   // gradient of the current layer's output
@@ -1014,6 +1097,7 @@ struct Walk {
     Buf dqc = tmp(th);
     Buf dkvc = tmp((size_t)Tm * 2 * H * c.esz);
     Buf ws = tmp((size_t)c.B * c.nh * c.S * sizeof(float));
+    if (c.dtype == DP_BF16 && mfma_enabled && !dp::attn_mfma_supported(c.Sm, c.dh)) ++n_fallback;
     prof_begin(DP_OPC_ATTN_BWD);
     if (live) {
       const dp::AttnView v = cross_view(ptr(l, DP_SLOT_Q_C), ptr(l, DP_SLOT_KV_C), bptr(dqc), bptr(dkvc));
@@ -1066,6 +1150,7 @@ struct Walk {
     begin_node(TAG_BWD, l, c.pre ? (c.cross ? 10 : 5) : 6);
     Buf dqkv = tmp((size_t)T * 3 * H * c.esz);
     Buf ws = tmp((size_t)c.B * c.nh * c.S * sizeof(float));
+    if (c.dtype == DP_BF16 && mfma_enabled && !dp::attn_mfma_supported(c.S, c.dh)) ++n_fallback;
     prof_begin(DP_OPC_ATTN_BWD);
     if (live) {
       const dp_layer_grads *g = &dw[l];
@@ -1141,6 +1226,7 @@ static void fill_report(const Cfg &c, const Walk &w, dp_plan_report *r) {
   r->step_flops = 3.0 * w.step_flops;
   r->n_replayed_ops = w.n_replayed;
   r->n_swapped_slots = w.n_swapped;
+  r->n_fallback_launches = w.n_fallback;
 }
 
 bool env_mfma_enabled() {
@@ -1172,26 +1258,27 @@ dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t 
   std::vector<int> aheads;
   for (int a = c.L; a > 1; a /= 2) aheads.push_back(a);
   aheads.push_back(1);
-  auto run = [&](int ahead, long hold, int *n_swapped) {
+  auto run = [&](int ahead, long hold, bool through, int *n_swapped) {
     Walk w(c, plan, false, nullptr);
     w.mfma_enabled = mfma_enabled;
     w.fuse_gelu_enabled = fuse_gelu_enabled;
     w.swap_hold_ticks = hold;
     w.prefetch_ahead = ahead;
+    w.hold_through_backward = through;
     w.forward();
     w.backward();
     fill_report(c, w, r);
-    if (policy_out) *policy_out = SwapPolicy{hold, ahead};
+    if (policy_out) *policy_out = SwapPolicy{hold, ahead, through};
     *n_swapped = w.n_swapped;
   };
   int n_swapped = 0;
   if (budget == 0) {   // no budget: the caller wants the plan's memory saving, i.e. the tightest policy
-    run(1, 0, &n_swapped);
+    run(1, 0, false, &n_swapped);
     return DP_OK;
   }
   for (size_t ai = 0; ai < aheads.size(); ++ai)
-    for (int attempt = 0; attempt < kNumSwapHolds; ++attempt) {
-      run(aheads[ai], kSwapHolds[attempt], &n_swapped);
+    for (int attempt = -1; attempt < kNumSwapHolds; ++attempt) {   // -1: held through the backward as well
+      run(aheads[ai], kSwapHolds[attempt < 0 ? 0 : attempt], attempt < 0, &n_swapped);
       if ((long double)inflight * (long double)r->peak_bytes <= (long double)budget) return DP_OK;
       if (n_swapped == 0) goto out;   // nothing is swapped: every policy gives this peak
     }
@@ -1210,14 +1297,17 @@ CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bo
   w.fuse_gelu_enabled = kFuseGeluDefault;
   w.swap_hold_ticks = exact ? policy.hold_ticks : 0;
   w.prefetch_ahead = exact ? policy.ahead : 1;
+  w.hold_through_backward = exact && policy.through_backward;
+  w.use_express = exact;
   w.cm = &cm;
   w.sim_arena_waits = exact;
   w.no_arena = !exact;
   w.cs = (hipStream_t)(intptr_t)1; w.d2h = (hipStream_t)(intptr_t)2; w.h2d = (hipStream_t)(intptr_t)3;
+  w.d2hx = (hipStream_t)(intptr_t)4;
   w.forward();
   w.backward();
   CostOut o;
-  o.step_ns = std::max(w.clk[0], std::max(w.clk[1], w.clk[2]));   // the copy streams are joined at the end
+  o.step_ns = std::max(std::max(w.clk[0], w.clk[3]), std::max(w.clk[1], w.clk[2]));   // the copy streams are joined at the end
   o.slot_peak = w.slot_peak; o.arena_peak = w.arena.high_water;
   o.d2h = w.d2h_bytes; o.h2d = w.h2d_bytes; o.replayed = w.n_replayed;
   return o;
@@ -1356,6 +1446,7 @@ dp_status dp_stage_init(const dp_stage_config *cfg, const dp_layer_weights *laye
   }
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->d2h, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->h2d, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&st->d2hx, hipStreamNonBlocking);
   if (e == hipSuccess && arena_bytes_hint > 0) {
     if (hipMalloc(&st->arena, arena_bytes_hint) == hipSuccess) st->arena_bytes = arena_bytes_hint;
     else { dp_stage_destroy(st); return fail(DP_E_DEVMEM, "cannot allocate the arena hint"); }
@@ -1544,14 +1635,19 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   w.fuse_gelu_enabled = fuse_gelu;
   w.swap_hold_ticks = swap_hold.hold_ticks;
   w.prefetch_ahead = swap_hold.ahead;
+  w.hold_through_backward = swap_hold.through_backward;
   w.cs = cs;
   const bool serial = (st->debug & 1u) != 0;
   w.d2h = serial ? cs : st->d2h;
   w.h2d = serial ? cs : st->h2d;
+  w.d2hx = serial ? cs : st->d2hx;
+  w.use_express = true;
   w.x_in = x_in; w.dy = dy; w.y_out = y_out; w.dx_out = dx_out; w.dw = dw;
   w.mem = st->mem; w.d_mem = st->d_mem; w.dwx = st->dw_cross.data();
   hipEvent_t t0 = nullptr, t1 = nullptr, t2 = nullptr;
+  std::vector<Walk::Span> spans;
   if (stats) {
+    w.spans = &spans;
     HIP_TRY(hipEventCreate(&t0), DP_E_HIP); HIP_TRY(hipEventCreate(&t1), DP_E_HIP); HIP_TRY(hipEventCreate(&t2), DP_E_HIP);
     HIP_TRY(hipEventRecord(t0, cs), DP_E_HIP);
   }
@@ -1562,6 +1658,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   if (!serial) {
     const int j1 = w.new_event(); w.record(j1, st->d2h); w.wait(cs, j1);
     const int j2 = w.new_event(); w.record(j2, st->h2d); w.wait(cs, j2);
+    const int j3 = w.new_event(); w.record(j3, st->d2hx); w.wait(cs, j3);
   }
   if (w.herr != hipSuccess) return fail(DP_E_HIP, "stage_step: %s", hipGetErrorString(w.herr));
   HIP_TRY(hipEventRecord(step_end, cs), DP_E_HIP);
@@ -1580,6 +1677,23 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
     stats->d2h_bytes = w.d2h_bytes; stats->h2d_bytes = w.h2d_bytes;
     stats->arena_high_water = w.arena.high_water; stats->peak_bytes = rep.peak_bytes;
     stats->n_kernel_launches = w.n_launch; stats->n_replayed_ops = w.n_replayed;
+    stats->n_fallback_launches = w.n_fallback;
+    // the timed spans: copies on their streams, waits and replays on the compute stream
+    const bool dump = getenv("DPSTAGE_TIMELINE") != nullptr;
+    static const char *const kSpanName[] = {"d2h", "h2d", "wait", "replay"};
+    for (const Walk::Span &sp : spans) {
+      float a = 0.f, b = 0.f;
+      HIP_TRY(hipEventElapsedTime(&a, t0, st->span_events[sp.ev]), DP_E_HIP);
+      HIP_TRY(hipEventElapsedTime(&b, t0, st->span_events[sp.ev + 1]), DP_E_HIP);
+      const float d = b - a;
+      if (sp.kind == Walk::SPAN_D2H) stats->d2h_busy_ms += d;
+      else if (sp.kind == Walk::SPAN_H2D) stats->h2d_busy_ms += d;
+      else if (sp.kind == Walk::SPAN_WAIT) stats->swap_wait_ms += d;
+      else stats->replay_ms += d;
+      if (dump)
+        fprintf(stderr, "dpstage timeline: %-6s layer %2d slot/node %2d  %9.3f .. %9.3f ms  (%.3f ms, %llu bytes)\n",
+                kSpanName[sp.kind], sp.l, sp.slot, a, b, d, (unsigned long long)sp.bytes);
+    }
     (void)hipEventDestroy(t0); (void)hipEventDestroy(t1); (void)hipEventDestroy(t2);
   }
   return DP_OK;
@@ -1642,10 +1756,13 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   w->fuse_gelu_enabled = fuse_gelu;
   w->swap_hold_ticks = swap_hold.hold_ticks;
   w->prefetch_ahead = swap_hold.ahead;
+  w->hold_through_backward = swap_hold.through_backward;
   w->cs = (hipStream_t)hip_stream;
   const bool serial = (st->debug & 1u) != 0;
   w->d2h = serial ? w->cs : st->d2h;
   w->h2d = serial ? w->cs : st->h2d;
+  w->d2hx = serial ? w->cs : st->d2hx;
+  w->use_express = true;
   w->x_in = x_in; w->y_out = y_out;
   w->mem = st->mem;
   w->forward();
@@ -1685,7 +1802,7 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
   --wset->refs;
   hipStream_t cs = (hipStream_t)hip_stream;
   const bool serial = (st->debug & 1u) != 0;
-  if (serial) { w->d2h = cs; w->h2d = cs; }
+  if (serial) { w->d2h = cs; w->h2d = cs; w->d2hx = cs; }
   else if (cs != w->cs) {
     // swap-outs and kernels of the forward were ordered on its stream; this one must follow them
     const int j = w->new_event(); w->record(j, w->cs); w->wait(cs, j);
@@ -1698,6 +1815,7 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
   if (!serial) {
     const int j1 = w->new_event(); w->record(j1, st->d2h); w->wait(cs, j1);
     const int j2 = w->new_event(); w->record(j2, st->h2d); w->wait(cs, j2);
+    const int j3 = w->new_event(); w->record(j3, st->d2hx); w->wait(cs, j3);
   }
   if (w->herr != hipSuccess) return fail(DP_E_HIP, "stage_backward: %s", hipGetErrorString(w->herr));
   if (f.done == nullptr) HIP_TRY(hipEventCreateWithFlags(&f.done, hipEventDisableTiming), DP_E_HIP);
@@ -1741,6 +1859,12 @@ int32_t dp_stage_weight_versions(const dp_stage *st) {
 dp_status dp_stage_set_profiling(dp_stage *st, int32_t enabled) {
   if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
   st->profiling = enabled != 0;
+  return DP_OK;
+}
+
+dp_status dp_stage_op_flops(dp_stage *st, double *flops_by_class) {
+  if (st == nullptr || flops_by_class == nullptr) return fail(DP_E_INVAL, "null argument");
+  for (int i = 0; i < DP_OPC_COUNT; ++i) { flops_by_class[i] = st->prof_flops[i]; st->prof_flops[i] = 0.0; }
   return DP_OK;
 }
 
@@ -1876,6 +2000,8 @@ void dp_stage_destroy(dp_stage *st) {
   for (hipEvent_t e : st->bwd_end) if (e) (void)hipEventDestroy(e);
   if (st->d2h) (void)hipStreamDestroy(st->d2h);
   if (st->h2d) (void)hipStreamDestroy(st->h2d);
+  if (st->d2hx) (void)hipStreamDestroy(st->d2hx);
+  for (hipEvent_t e : st->span_events) (void)hipEventDestroy(e);
   if (st->arena) (void)hipFree(st->arena);
   if (st->host_pool) (void)hipHostFree(st->host_pool);
   for (auto &f : st->flights) {

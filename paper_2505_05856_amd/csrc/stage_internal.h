@@ -48,6 +48,11 @@ extern const OpDef kPreOps[N_OPS], kPostOps[N_OPS], kPreCrossOps[N_OPS_CROSS];
 inline const OpDef *op_table(const Cfg &c) { return c.cross ? kPreCrossOps : c.pre ? kPreOps : kPostOps; }
 inline int op_count(const Cfg &c) { return c.cross ? (int)N_OPS_CROSS : (int)N_OPS; }
 size_t slot_bytes(const Cfg &c, int slot);
+// Saved tensors a backward node reads, in the node order of each style (FreeTime needs the first
+// backward reader of every candidate; the swap-ins of a layer are issued in that order).
+struct BwdReads { int n; int slot[3]; };
+extern const BwdReads kPreBwd[N_OPS], kPostBwd[N_OPS], kPreCrossBwd[N_OPS_CROSS];
+inline const BwdReads *bwd_table(const Cfg &c) { return c.cross ? kPreCrossBwd : c.pre ? kPreBwd : kPostBwd; }
 
 // Forward GELU as its own kernel (false) or in the FC1 GEMM epilogue (true).  A second output
 // doubles the epilogue's stores (8 bytes a lane) and adds the activation's arithmetic to the
@@ -66,8 +71,11 @@ dp_status check_plan(const Cfg &c, const uint8_t *plan, size_t plan_len, dp_plan
 //               forward does not wait for the link before it may reuse the block;
 //   ahead       layers of backward by which the swap-ins run ahead of their first use (1: the
 //               swap-ins of layer l-1 are issued when the backward of layer l starts).
-// The tightest policy {0, 1} gives a plan's smallest peak.
-struct SwapPolicy { long hold_ticks = 0; int ahead = 1; };
+//   through_backward  blocks still held when the forward ends stay held through the backward (the
+//               copy-outs of the top layers are still on their way then, and the first blocks
+//               the backward allocates would wait for them).
+// The tightest policy {0, 1, false} gives a plan's smallest peak.
+struct SwapPolicy { long hold_ticks = 0; int ahead = 1; bool through_backward = false; };
 // The static memory walk: fills `rep`, picks the first policy, from the most generous down, with
 // which inflight * peak fits `budget` (0 = no budget: the tightest) and returns it in *policy_out.
 dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
