@@ -527,6 +527,17 @@ dp_status dp_op_gemm(int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t 
 /* out[cols] = sum over rows of x[rows, cols] */
 dp_status dp_op_colsum(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out, void *ws,
                        void *hip_stream);
+/* dp_op_colsum for callers that cannot allocate device memory and have no workspace to hand in
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * partial sums of the two-pass reduction go to a device array inside the library, 8 MiB on every
+ * GPU the library runs on, held until the process ends.  Same kernels and same bits as
+ * dp_op_colsum.  Calls neither hipMalloc nor hipFree nor any allocating routine.  Limit: the
+ * partials, (number of row blocks, at most 512) x cols x 4 bytes, must fit the array, e.g.
+ * cols <= 4096 at any row count; larger shapes are refused with DP_E_UNSUPPORTED and a message.
+ * All calls on one GPU share the array: calls that overlap on one GPU (different streams or
+ * threads) race; calls on one stream are ordered. */
+dp_status dp_op_colsum_static(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out,
+                              void *hip_stream);
 /* o [T,H], lse [B,nh,S] from qkv [T,3H]; o or lse may be NULL. */
 dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                               const void *qkv, void *o, float *lse, void *hip_stream);

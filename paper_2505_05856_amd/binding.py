@@ -156,6 +156,7 @@ def lib() -> C.CDLL:
     L.dp_op_gelu_bwd.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.dp_op_gemm.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.dp_op_colsum.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+    L.dp_op_colsum_static.argtypes = [i32, i32, i32, vp, vp, vp]
     L.dp_op_attention_fwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.dp_op_attention_bwd.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     L.dp_op_dropout.argtypes = [i32, sz, vp, vp, vp, vp, i32, vp]
@@ -173,7 +174,7 @@ def lib() -> C.CDLL:
     L.dp_stage_measure_cost_model.argtypes = [vp, vp, vp, vp, vp, C.POINTER(LayerPtrs), vp, i32, C.POINTER(CostModel)]
     for name in ("dp_probe_mfma", "dp_partition", "dp_plan_cost", "dp_plan_generate", "dp_stage_measure_cost_model", "dp_plan_validate", "dp_stage_init", "dp_stage_step", "dp_stage_forward", "dp_stage_backward", "dp_stage_set_weights", "dp_stage_set_rng", "dp_stage_set_cross", "dp_stage_bind_memory", "dp_stage_set_profiling",
                  "dp_stage_op_times", "dp_stage_op_flops", "dp_stage_set_debug", "dp_op_layernorm_fwd", "dp_op_layernorm_bwd",
-                 "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_attention_fwd",
+                 "dp_op_gelu_fwd", "dp_op_gelu_bwd", "dp_op_gemm", "dp_op_colsum", "dp_op_colsum_static", "dp_op_attention_fwd",
                  "dp_op_attention_bwd", "dp_op_dropout", "dp_op_attention_dropout_fwd", "dp_op_attention_dropout_bwd",
                  "dp_op_cross_attention_fwd", "dp_op_cross_attention_bwd",
                  "dp_op_rmsnorm_fwd", "dp_op_rmsnorm_bwd"):
@@ -469,6 +470,10 @@ def op_gemm(mode, M, N, K, A, B, bias, res, Cout, stream=None):
 
 def op_colsum(x, out, ws, stream=None):
     _check(lib().dp_op_colsum(_dt(x), x.shape[0], x.shape[1], _ptr(x), _ptr(out), _ptr(ws), _stream_ptr(stream)))
+
+
+def op_colsum_static(x, out, stream=None):
+    _check(lib().dp_op_colsum_static(_dt(x), x.shape[0], x.shape[1], _ptr(x), _ptr(out), _stream_ptr(stream)))
 
 
 def op_attention_fwd(qkv, B, S, nh, dh, causal, o, lse, stream=None):

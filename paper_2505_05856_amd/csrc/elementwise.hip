@@ -9,6 +9,7 @@
 #include "common.h"
 #include "kernels.h"
 
+#include <mutex>
 
 #include <type_traits>
 
@@ -695,6 +696,54 @@ hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out
   if (job != nullptr) job->nb = 0;
   if (rows <= 0) return zero_vec(dtype, out, cols, s);
   return dtype == kBF16 ? colsum_t<bf16>(rows, cols, x, out, ws, s, job) : colsum_t<float>(rows, cols, x, out, ws, s, job);
+}
+
+// ---- column sums without a workspace argument and without any allocation -----------------
+// The partial sums of the two-pass reduction go to a file-scope device array instead of a
+// caller's workspace.  Every GPU the library runs on holds its own copy of the array at its
+// own address until the process ends; the host looks that address up once per device.  All
+// calls on a GPU share the array: calls that overlap on one GPU race.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t colsum_static_max_bytes() { return kStaticScratchBytes; }
+
+size_t colsum_static_needed_bytes(int rows, int cols) {
+  if (rows <= 0) return 0;   // (no rows: no partial sums)
+  int rpb;
+  return (size_t)row_blocks(rows, 16, &rpb) * (size_t)cols * sizeof(float);
+}
+
+// The array's device address on the current device (host code must never use the array's name
+// where its memory is meant: the name is a host-side stand-in, not a device address).
+static hipError_t scratch_address(void **out) {
+  constexpr int kMaxDevices = 64;
+  static void *ptr[kMaxDevices] = {};
+  static std::mutex lock;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> guard(lock);
+  if (ptr[dev] == nullptr) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
+}
+
+// launch_colsum with the partial sums in the library's own array.  The caller has checked that
+// colsum_static_needed_bytes(rows, cols) fits.  Nothing has to start at zero: the first pass
+// writes every partial the second pass reads.
+hipError_t launch_colsum_static(int dtype, int rows, int cols, const void *x, void *out, hipStream_t s) {
+  if (rows <= 0) return zero_vec(dtype, out, cols, s);
+  void *ws = nullptr;
+  const hipError_t e = scratch_address(&ws);
+  if (e != hipSuccess) return e;
+  return dtype == kBF16 ? colsum_t<bf16>(rows, cols, x, out, ws, s, nullptr) : colsum_t<float>(rows, cols, x, out, ws, s, nullptr);
 }
 
 hipError_t launch_reduce_jobs(int dtype, const ReduceJob *jobs, int n, hipStream_t s) {

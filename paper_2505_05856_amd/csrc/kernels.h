@@ -105,6 +105,11 @@ hipError_t launch_dropout(int dtype, size_t n, const void *x, const void *res, v
 hipError_t launch_gelu_fwd(int dtype, int kind, size_t n, const void *x, void *y, hipStream_t s);
 hipError_t launch_colsum(int dtype, int rows, int cols, const void *x, void *out, void *ws, hipStream_t s,
                          ReduceJob *job = nullptr);
+// The same with the partial sums in a device array of the library's own (no workspace, no
+// allocation); the caller checks colsum_static_needed_bytes(...) <= colsum_static_max_bytes().
+size_t colsum_static_max_bytes();
+size_t colsum_static_needed_bytes(int rows, int cols);
+hipError_t launch_colsum_static(int dtype, int rows, int cols, const void *x, void *out, hipStream_t s);
 // dst[c, r] = src[r, c]
 hipError_t launch_transpose(int dtype, int rows, int cols, const void *src, void *dst, hipStream_t s);
 hipError_t launch_fill_u32(void *p, size_t n_words, uint32_t pattern, hipStream_t s);

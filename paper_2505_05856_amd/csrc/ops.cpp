@@ -94,6 +94,16 @@ dp_status dp_op_colsum(int32_t dtype, int32_t rows, int32_t cols, const void *x,
   return op_done(dp::launch_colsum(dtype, rows, cols, x, out, ws, (hipStream_t)hip_stream), "colsum");
 }
 
+dp_status dp_op_colsum_static(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out, void *hip_stream) {
+  if (bad_dtype(dtype) || rows < 0 || cols <= 0 || !out || (rows > 0 && !x)) return fail(DP_E_INVAL, "colsum_static: bad argument");
+  if (cols % 8) return fail(DP_E_UNSUPPORTED, "colsum: cols must be a multiple of 8");
+  const size_t need = dp::colsum_static_needed_bytes(rows, cols);
+  if (need > dp::colsum_static_max_bytes())
+    return fail(DP_E_UNSUPPORTED, "colsum_static: [%d, %d] needs %zu bytes of partial sums, the library's static scratch "
+                "array holds %zu (use dp_op_colsum with a workspace)", rows, cols, need, dp::colsum_static_max_bytes());
+  return op_done(dp::launch_colsum_static(dtype, rows, cols, x, out, (hipStream_t)hip_stream), "colsum_static");
+}
+
 dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                               const void *qkv, void *o, float *lse, void *hip_stream) {
   if (bad_dtype(dtype) || B < 0 || S < 0 || nh <= 0 || dh <= 0 || ((long)B * S > 0 && !qkv)) return fail(DP_E_INVAL, "attention_fwd: bad argument");
