@@ -26,7 +26,7 @@ NO_SCRATCH = {"gemm_mfma.hip", "gemm_dma.hip"}
 # the matrix instructions' results into accumulation registers and then moves them to and fro
 # (768 v_accvgpr moves for 128 matrix instructions in the dK/dV loop); letting it choose ordinary
 # registers for them removes nearly all of those moves.
-EXTRA_FLAGS = {"attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+EXTRA_FLAGS = {"attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"],
                # the LDS-direct load names M0 as clobbered; clang warns that M0 is a reserved register
                "gemm_dma.hip": ["-Wno-inline-asm"]}
 

@@ -2,7 +2,8 @@
 //
 // Forward: a block owns 128 query rows of one (batch, head); each of its 4 waves
 // owns 32 of them.  K/V tiles of 64 keys stream through a double-buffered LDS
-// stage.  A wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a
+// stage, brought in by the load unit itself (forward; the backward kernels still
+// stage their tiles through registers).  A wave computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so that a
 // lane holds one query row's logits for 16 keys of every 32-key block: the
 // softmax row reductions are in-lane plus one exchange between the two half
 // waves, and the probabilities already sit in the register layout the second
@@ -97,6 +98,86 @@ __device__ __forceinline__ void tile_store(bf16 *lds, int stride, const uint4 (&
   }
 }
 
+// ---- K/V (or Q/dO) tiles brought into LDS by the load unit itself ------------------------
+// One request: lane l fetches 16 bytes from uniform_base + byte_off and the unit stores them at
+// LDS byte lds_base + 16*l (global_load_lds_dwordx4): no staging registers, no LDS store
+// instructions, nothing to wait for until the tile is needed.  Invisible to the compiler's
+// wait-count pass: the kernels wait with s_waitcnt vmcnt(0) themselves before the barrier that
+// publishes a tile.  M0 is reserved by the compiler and nothing else in this file uses it.
+__device__ __forceinline__ void dma16(unsigned lds_base, unsigned byte_off, const void *uniform_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base), "v"(byte_off), "s"(uniform_base) : "m0", "memory");
+}
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ const char *uniform_ptr(const char *p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char *)(((uint64_t)hi << 32) | lo);
+}
+
+// A [64 rows][DH] tile in LDS, laid out for fragments whose contraction runs ALONG a row
+// (frag_rows): DH/64 half-tiles of [64][64] with unpadded 128-byte rows; 16-byte chunk c of
+// row r sits at chunk position c ^ ((r >> 1) & 7), which spreads the 16 rows one fragment read
+// phase touches over all banks.  The load unit writes 1 KB of consecutive LDS a request, so a
+// lane fetches the global chunk that belongs at its LDS position: request q of the tile is rows
+// 8q..8q+7 of half-tile q / 8; lane l is row 8q + l/8, position l%8.  Rows past `nrows` repeat
+// the last row (their logits are masked; as values they meet probabilities that are zero).
+// `ldb`: row stride of the source in bytes.  Every wave issues its DH/32 requests of the tile.
+template <int DH>
+__device__ __forceinline__ void dma_tile_rows(unsigned lds_byte, const char *src_col0, unsigned ldb, int row0, int nrows,
+                                              int wave, int lane) {
+  constexpr int NREQ = DH / 32;   // per wave: 64 * DH * 2 bytes / 1 KB / 4 waves
+#pragma unroll
+  for (int i = 0; i < NREQ; ++i) {
+    const int q = wave * NREQ + i, half = q >> 3, r = 8 * (q & 7) + (lane >> 3);
+    const int rg = min(row0 + r, nrows - 1);
+    const unsigned chunk = (unsigned)((lane & 7) ^ ((r >> 1) & 7));
+    dma16(lds_byte + (unsigned)q * 1024u, (unsigned)rg * ldb + (unsigned)half * 128u + chunk * 16u, src_col0);
+  }
+}
+// fragment (32 rows from row0, contraction elements k0..k0+15) of such a tile
+__device__ __forceinline__ bf16x8 frag_rows_sw(const unsigned char *tile, int row0, int k0, int lane) {
+  const unsigned r = (unsigned)(row0 + (lane & 31));
+  const unsigned c = (unsigned)(((k0 & 63) >> 3) + (lane >> 5));
+  return *reinterpret_cast<const bf16x8 *>(tile + (unsigned)(k0 >> 6) * 8192u + r * 128u + ((c ^ ((r >> 1) & 7u)) << 4));
+}
+
+// The same tile laid out as loaded, [64 rows][DH * 2 bytes], for fragments whose contraction
+// runs DOWN the rows (frag_cols, through the transpose read, which touches four consecutive
+// rows x 64 bytes per 16 lanes): chunk c of row r sits at c ^ swz(r), swz = (r & 3) << 2 for
+// 256-byte rows (the four rows land in the four 64-byte quarters of the bank period) and
+// ((r >> 1) & 1) << 2 for 128-byte rows (rows r and r+2 swap 64-byte halves).
+template <int DH> __device__ __forceinline__ constexpr unsigned swz_cols(unsigned r) {
+  return DH == 128 ? (r & 3u) << 2 : ((r >> 1) & 1u) << 2;
+}
+template <int DH>
+__device__ __forceinline__ void dma_tile_cols(unsigned lds_byte, const char *src_col0, unsigned ldb, int row0, int nrows,
+                                              int wave, int lane) {
+  constexpr int NREQ = DH / 32, RPR = 1024 / (DH * 2), CPR = DH / 8;   // rows per request, chunks per row
+#pragma unroll
+  for (int i = 0; i < NREQ; ++i) {
+    const int q = wave * NREQ + i, r = RPR * q + lane / CPR;
+    const int rg = min(row0 + r, nrows - 1);
+    const unsigned chunk = (unsigned)(lane % CPR) ^ swz_cols<DH>((unsigned)r);
+    dma16(lds_byte + (unsigned)q * 1024u, (unsigned)rg * ldb + chunk * 16u, src_col0);
+  }
+}
+// fragment: lane l gets column col0 + l%32 for the rows r0 + 4*(l/32) + {0,1,2,3} and those 8 further
+// (the order in which a 32x32 MFMA result holds 16 consecutive rows of one column)
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_cols_sw(const unsigned char *tile, int r0, int col0, int lane) {
+  constexpr unsigned ROWB = DH * 2;
+  const unsigned i = (unsigned)(lane & 15), tt = i >> 2;
+  const unsigned row = (unsigned)r0 + 4u * (unsigned)(lane >> 5) + tt;
+  const unsigned cw = (unsigned)(col0 >> 3) + 2u * (unsigned)((lane >> 4) & 1) + ((i & 3u) >> 1);
+  const unsigned char *p = tile + row * ROWB + ((cw ^ swz_cols<DH>(tt)) << 4) + (i & 1u) * 8u;
+  union { s16x4 h[2]; bf16x8 v; } u;
+  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8u * ROWB));
+  return u.v;
+}
+
 // ------------------------------------------------------------------ forward
 // DROP: the probabilities are masked after the softmax (the row sums and the log-sum-exp are
 // those of the plain softmax); the scale 1/(1-p) goes into the final normalisation.
@@ -104,35 +185,42 @@ template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_mfma_kernel(AttnView av, bf16 *__restrict__ o,
                                                                float *__restrict__ lse, int nh, float scale,
                                                                DropArgs da) {
-  constexpr int KS = DH + 8, VS = DH + 16, ND = DH / 32, NK = DH / 16;
-  // LDS stages are picked by integer offsets into one array: selecting them through
-  // pointer arrays makes the pointers generic and the fragment reads flat loads.
-  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
+  constexpr int ND = DH / 32, NK = DH / 16;
+  // a stage: the K tile in the row-fragment layout, then the V tile in the column-fragment layout
+  constexpr unsigned TILE = BKV * DH * 2, STAGE = 2 * TILE;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_b[];
 
   const int Sq = av.Sq, S = av.Sk;   // S: the key count, which bounds every key-side loop below
   const int nqt = (Sq + BROWS - 1) / BROWS;
   const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int qt = nqt - 1 - wid % nqt;   // heavy (late) causal tiles first
   const int h = (wid / nqt) % nh, b = wid / (nqt * nh);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int H = nh * DH;
   const long ldq = av.ldq, ld = av.ldkv;
   const bf16 *qb = (const bf16 *)av.q + (long)b * Sq * ldq + (long)h * DH;
-  const bf16 *kb = (const bf16 *)av.k + (long)b * S * ld + (long)h * DH;
-  const bf16 *vb = (const bf16 *)av.v + (long)b * S * ld + (long)h * DH;
+  const char *kb = uniform_ptr((const char *)((const bf16 *)av.k + (long)b * S * ld + (long)h * DH));
+  const char *vb = uniform_ptr((const char *)((const bf16 *)av.v + (long)b * S * ld + (long)h * DH));
+  const unsigned ldb = (unsigned)ld * 2u;
   const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
   const float c = scale * kLog2e;
   const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
   const uint32_t qidx = (uint32_t)qi * (uint32_t)S;   // index of (query qi, key 0) in the head's Sq x Sk matrix
 
+  int nkv = (S + BKV - 1) / BKV;
+  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
+
+  // the first K/V tile is on its way while the queries are fetched
+  if (nkv > 0) {
+    dma_tile_rows<DH>(0u, kb, ldb, 0, S, wave, lane);
+    dma_tile_cols<DH>(TILE, vb, ldb, 0, S, wave, lane);
+  }
+
   bf16x8 qf[NK];
 #pragma unroll
   for (int kd = 0; kd < NK; ++kd)
     qf[kd] = qi < Sq ? as_frag(ld16(qb + (long)qi * ldq + kd * 16 + 8 * hh)) : as_frag(make_uint4(0, 0, 0, 0));
-
-  int nkv = (S + BKV - 1) / BKV;
-  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
 
   f32x16 acc[ND];
 #pragma unroll
@@ -141,19 +229,18 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
     for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
   float m = -1e30f, l = 0.f;   // m: running maximum of the scaled logits (log2 domain)
 
-  uint4 sk[DH / 32], sv[DH / 32];
-  tile_load<DH>(sk, kb, ld, 0, S, tid);
-  tile_load<DH>(sv, vb, ld, 0, S, tid);
-  tile_store<DH>(smem, KS, sk, tid);
-  tile_store<DH>(smem + VOFF, VS, sv, tid);
+  wait_dma();
   __syncthreads();
 
   for (int t = 0; t < nkv; ++t) {
-    const int cur = (t & 1) * STAGE, nxt = STAGE - cur, j0 = t * BKV;
+    const unsigned cur = (unsigned)(t & 1) * STAGE, nxt = STAGE - cur;
+    const int j0 = t * BKV;
+    // the next tile goes into the other stage, which every wave left at the barrier below
     if (t + 1 < nkv) {
-      tile_load<DH>(sk, kb, ld, j0 + BKV, S, tid);
-      tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
+      dma_tile_rows<DH>(nxt, kb, ldb, j0 + BKV, S, wave, lane);
+      dma_tile_cols<DH>(nxt + TILE, vb, ldb, j0 + BKV, S, wave, lane);
     }
+    const unsigned char *kt = smem_b + cur, *vt = smem_b + cur + TILE;
     if (!CAUSAL || j0 <= iw0 + 31) {
       // MASK = false: every key of the tile exists and is visible to every query of the wave,
       // so the per-element bounds and causal tests (a third of the softmax instructions) go
@@ -167,7 +254,7 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
           for (int e = 0; e < 16; ++e) s[sub][e] = 0.f;
 #pragma unroll
           for (int kd = 0; kd < NK; ++kd)
-            s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, KS, sub * 32, kd * 16, lane), qf[kd],
+            s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_sw(kt, sub * 32, kd * 16, lane), qf[kd],
                                                              s[sub], 0, 0, 0);
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
@@ -216,17 +303,14 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
 #pragma unroll
             for (int d = 0; d < ND; ++d)
               acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  frag_cols(smem + cur + VOFF, VS, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
+                  frag_cols_sw<DH>(vt, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
           }
       };
       const bool interior = j0 + BKV <= S && (!CAUSAL || j0 + BKV - 1 <= iw0);
       if (interior) tile(std::false_type{}); else tile(std::true_type{});
     }
-    if (t + 1 < nkv) {
-      tile_store<DH>(smem + nxt, KS, sk, tid);
-      tile_store<DH>(smem + nxt + VOFF, VS, sv, tid);
-    }
-    __syncthreads();
+    wait_dma();        // this wave's part of the next tile is in
+    __syncthreads();   // everyone's is, and everyone is done with this tile
   }
 
   l += __shfl_xor(l, 32, 64);
@@ -255,7 +339,7 @@ hipError_t set_smem(K kern, size_t smem) {
 template <int DH>
 hipError_t fwd_launch(int B, int nh, int causal, const AttnView &av, void *o, float *lse, const DropArgs *drop,
                       hipStream_t s) {
-  constexpr size_t smem = 2 * (size_t)BKV * ((DH + 8) + (DH + 16)) * sizeof(bf16);
+  constexpr size_t smem = 2 * 2 * (size_t)BKV * DH * sizeof(bf16);   // two stages of a K and a V tile
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = set_smem(attn_fwd_mfma_kernel<DH, true, false>, smem);
@@ -616,9 +700,17 @@ hipError_t bwd_launch(int B, int nh, int causal, const AttnView &av, const void 
 
 bool attn_mfma_supported(int S, int dh) { return S >= 1 && (dh == 64 || dh == 128); }
 
+// The tile loads take 16 bytes a lane at 32-bit byte offsets from a head's first row.
+static bool view_ok(const AttnView &v) {
+  const uintptr_t ptrs = (uintptr_t)v.q | (uintptr_t)v.k | (uintptr_t)v.v;
+  if ((ptrs & 15) != 0 || v.ldq % 8 != 0 || v.ldkv % 8 != 0) return false;
+  const uint64_t lim = 0xffffffffull - 4096;
+  return (uint64_t)v.Sk * (uint64_t)v.ldkv * 2 < lim && (uint64_t)v.Sq * (uint64_t)v.ldq * 2 < lim;
+}
+
 hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, void *o, float *lse,
                                      hipStream_t s, const DropArgs *drop) {
-  if (causal && v.Sq != v.Sk) return hipErrorInvalidValue;
+  if ((causal && v.Sq != v.Sk) || !view_ok(v)) return hipErrorInvalidValue;
   if ((long)B * v.Sq * nh == 0) return hipSuccess;   // (no keys: the caller's case, there is no softmax to take)
   return dh == 64 ? fwd_launch<64>(B, nh, causal, v, o, lse, drop, s) : fwd_launch<128>(B, nh, causal, v, o, lse, drop, s);
 }
@@ -626,7 +718,7 @@ hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const At
 hipError_t launch_attn_bwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, const void *o,
                                      const float *lse, const void *d_o, float *ws, hipStream_t s,
                                      const DropArgs *drop) {
-  if (causal && v.Sq != v.Sk) return hipErrorInvalidValue;
+  if ((causal && v.Sq != v.Sk) || !view_ok(v)) return hipErrorInvalidValue;
   if ((long)B * nh == 0 || (v.Sq == 0 && v.Sk == 0)) return hipSuccess;
   return dh == 64 ? bwd_launch<64>(B, nh, causal, v, o, lse, d_o, ws, drop, s)
                   : bwd_launch<128>(B, nh, causal, v, o, lse, d_o, ws, drop, s);
