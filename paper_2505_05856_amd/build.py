@@ -75,5 +75,39 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+HOST_SOURCES = ["stage.cpp", "planner.cpp", "ops.cpp", "host_check.cpp"]
+SANITIZERS = {"asan": "address,undefined", "tsan": "thread"}
+
+
+def build_host_check(kind: str = "asan") -> str:
+    """The library's host code (step walk and validator, planners, operator wrappers) compiled with host-side
+    sanitizers -- AddressSanitizer + UBSan ("asan") or ThreadSanitizer ("tsan", for the planner's worker threads)
+    -- and linked with csrc/host_check.cpp into an executable that drives the pure host entry points.  The device
+    code is the ordinary build's; nothing in the executable touches a GPU."""
+    san = SANITIZERS[kind]
+    os.makedirs(OBJ, exist_ok=True)
+    dev_objs = [os.path.join(OBJ, os.path.splitext(src)[0] + ".o") for src in SOURCES if src.endswith(".hip")]
+    if not all(os.path.exists(o) for o in dev_objs):
+        build(verbose=False)
+    objs = []
+    for src in HOST_SOURCES:
+        obj = os.path.join(OBJ, f"{os.path.splitext(src)[0]}.{kind}.o")
+        cmd = [HIPCC, *FLAGS, "-g", "-fno-omit-frame-pointer", "-Xarch_host", f"-fsanitize={san}",
+               "-c", os.path.join(CSRC, src), "-o", obj]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc ({kind}) failed for {src}:\n{r.stderr}")
+        objs.append(obj)
+    exe = os.path.join(OBJ, f"host_check_{kind}")
+    cmd = [HIPCC, "--offload-arch=gfx950", f"-fsanitize={san}", "-fno-gpu-sanitize", "-o", exe, *objs, *dev_objs]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link ({kind}) failed:\n" + r.stderr)
+    return exe
+
+
 if __name__ == "__main__":
-    build()
+    if len(sys.argv) > 1 and sys.argv[1] in SANITIZERS:
+        print(build_host_check(sys.argv[1]))
+    else:
+        build()

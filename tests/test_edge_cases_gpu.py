@@ -128,3 +128,22 @@ def test_the_smallest_stage():
             assert all(torch.equal(a, b) for a, b in zip(bits[0], bits[1])) and \
                    all(torch.equal(a, b) for a, b in zip(bits[0], bits[2]))
             run.close()
+
+
+def test_fallback_launches_are_counted_in_the_step_statistics():
+    """A head dimension the matrix-core attention does not take: the step runs (vector-ALU kernels), matches the
+    oracle, and says so in its statistics; a supported shape reports none."""
+    for cfg, want in ((syn.StageConfig(2, 192, 2, 384, 64, 2, "pre", True, "erf", "bf16"), 4),
+                      (syn.StageConfig(2, 128, 2, 256, 64, 2, "pre", True, "erf", "bf16"), 0)):
+        w = syn.make_weights(cfg)
+        x, dy = syn.make_activations(cfg)
+        run = StageRunner(cfg, w, x, dy)
+        stats = run.step(syn.plan_keep_all(cfg), want_stats=True)
+        assert stats["n_fallback_launches"] == want
+        assert stats["replay_ms"] == 0.0 and stats["d2h_busy_ms"] == 0.0 and stats["swap_wait_ms"] == 0.0
+        compare(cfg, run.results(), oracle_step(cfg, w, x, dy))
+        stats = run.step(syn.plan_all_swap(cfg), want_stats=True)
+        assert stats["d2h_busy_ms"] > 0.0 and stats["h2d_busy_ms"] > 0.0 and stats["d2h_bytes"] == stats["h2d_bytes"] > 0
+        stats = run.step(syn.plan_all_recompute(cfg), want_stats=True)
+        assert stats["replay_ms"] > 0.0 and stats["n_replayed_ops"] > 0
+        run.close()

@@ -169,6 +169,25 @@ def test_full_size_configs_fit_their_budgets():
             assert rep["peak_bytes"] < 288 * 10**9
 
 
+def test_a_shape_the_matrix_core_kernels_do_not_take_is_reported_up_front():
+    """The vector-ALU kernels behind an unsupported shape are 20-50 times slower: the memory report says how many
+    launches of a step take them (and dp_step_stats repeats it), so a caller sees the cliff before running."""
+    for name in ("C2", "C3", "C4", "C5"):
+        cfg = syn.CONFIGS[name]
+        _, rep = B.plan_validate(to_binding_config(cfg), syn.PLANS[name][0][1](cfg), budget_bytes=syn.BUDGETS.get(name, 0))
+        assert rep["n_fallback_launches"] == 0, name
+    # head dimension 96: attention forward and backward of each of the 2 layers fall back, the GEMMs do not
+    odd = syn.StageConfig(2, 192, 2, 384, 64, 2, "pre", True, "erf", "bf16")
+    _, rep = B.plan_validate(to_binding_config(odd), syn.plan_keep_all(odd))
+    assert rep["n_fallback_launches"] == 4
+    # a replayed attention counts again
+    _, rep = B.plan_validate(to_binding_config(odd), syn.plan_all_recompute(odd))
+    assert rep["n_fallback_launches"] == 6
+    # fp32 debug mode runs on the vector ALUs by definition: nothing "fell back"
+    f32 = syn.StageConfig(2, 192, 2, 384, 64, 2, "pre", True, "erf", "f32")
+    assert B.plan_validate(to_binding_config(f32), syn.plan_keep_all(f32))[1]["n_fallback_launches"] == 0
+
+
 # ---------------------------------------------------------------- decoder stages (cross-attention block)
 def _dec(**kw):
     base = dict(n_layers=2, hidden=128, n_heads=2, ffn=256, seq=64, micro_batch=2, norm_style="pre", causal=True,
