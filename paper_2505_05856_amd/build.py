@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -29,6 +30,33 @@ NO_SCRATCH = {"gemm_mfma.hip", "gemm_dma.hip"}
 EXTRA_FLAGS = {"attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"],
                # the LDS-direct load names M0 as clobbered; clang warns that M0 is a reserved register
                "gemm_dma.hip": ["-Wno-inline-asm"]}
+
+
+# Files whose inline asm writes M0 (the LDS-direct loads).  The asm declares the clobber, but M0 is a reserved
+# register the compiler also uses by itself (LDS-indexed operations, lane moves, spill code) without modelling
+# inline asm's writes: such a use next to the loads would be a silent miscompile.  The device assembly of these
+# files must therefore name M0 only inside the inline asm blocks.
+M0_BY_HAND = {"gemm_dma.hip", "attn_mfma.hip"}
+
+
+def _check_m0(src: str) -> None:
+    asm = os.path.join(OBJ, os.path.splitext(src)[0] + ".s")
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", asm]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc -S failed for {src}:\n{r.stderr}")
+    inside = False
+    with open(asm) as f:
+        for n, line in enumerate(f, 1):
+            if "#ASMSTART" in line:
+                inside = True
+            elif "#ASMEND" in line:
+                inside = False
+            elif not inside:
+                code = line.split(";", 1)[0]
+                if re.search(r"\bm0\b", code):
+                    raise RuntimeError(f"{src}: the compiler uses M0 outside the inline asm ({asm}:{n}: {line.strip()})")
+    os.remove(asm)
 
 
 def _compile(src: str) -> str:
@@ -59,6 +87,8 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed for {src}:\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    if src in M0_BY_HAND:
+        _check_m0(src)
     return obj
 
 
