@@ -178,6 +178,70 @@ __device__ __forceinline__ bf16x8 frag_cols_sw(const unsigned char *tile, int r0
   return u.v;
 }
 
+// A [64 rows][DH] tile laid out for BOTH kinds of fragment (the backward kernels read Q, dO and
+// K along the rows and down the rows): rows as loaded, chunk c of row r at position c ^ both(r),
+//   256-byte rows: both(r) = ((r & 3) << 2) | ((r >> 2) & 3)    128-byte rows: (((r >> 1) & 1) << 2) | ((r >> 2) & 3)
+// The high part is the column-fragment swizzle above (the four rows of a transpose read land in
+// four 64-byte quarters); the low part makes the map a bijection over 16 consecutive rows, so the
+// 16 rows of one row-fragment read phase cover every bank once.
+template <int DH> __device__ __forceinline__ constexpr unsigned swz_both(unsigned r) {
+  return swz_cols<DH>(r) | ((r >> 2) & 3u);
+}
+template <int DH>
+__device__ __forceinline__ void dma_tile_both(unsigned lds_byte, const char *src_col0, unsigned ldb, int row0, int nrows,
+                                              int wave, int lane) {
+  constexpr int NREQ = DH / 32, RPR = 1024 / (DH * 2), CPR = DH / 8;
+#pragma unroll
+  for (int i = 0; i < NREQ; ++i) {
+    const int q = wave * NREQ + i, r = RPR * q + lane / CPR;
+    const int rg = min(row0 + r, nrows - 1);
+    const unsigned chunk = (unsigned)(lane % CPR) ^ swz_both<DH>((unsigned)r);
+    dma16(lds_byte + (unsigned)q * 1024u, (unsigned)rg * ldb + chunk * 16u, src_col0);
+  }
+}
+// The fragment addresses of such a tile, as LDS byte addresses a lane keeps in registers: the
+// swizzle of a row depends on its low four bits only, so every fragment of the tile is one of
+// these DH/16 (along the rows) + 2 * DH/32 (down the rows) addresses plus a compile-time offset
+// (a multiple of 16 rows, another tile of the stage), which the read instruction carries.  The
+// two stages lie a power of two apart: flip() moves every address to the other stage.
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+template <int DH>
+struct BothAddr {
+  static constexpr unsigned ROWB = DH * 2;
+  unsigned row[DH / 16], col[2][DH / 32];
+  __device__ __forceinline__ void init(int lane) {
+    const unsigned r = (unsigned)(lane & 31), hh = (unsigned)(lane >> 5);
+#pragma unroll
+    for (int kd = 0; kd < DH / 16; ++kd) row[kd] = r * ROWB + (((2u * kd + hh) ^ swz_both<DH>(r)) << 4);
+    const unsigned i = (unsigned)(lane & 15), tt = i >> 2, rc = 4u * hh + tt;
+    const unsigned cl = 2u * (unsigned)((lane >> 4) & 1) + ((i & 3u) >> 1);
+#pragma unroll
+    for (int d = 0; d < DH / 32; ++d) {
+      col[0][d] = rc * ROWB + (((4u * d + cl) ^ swz_both<DH>(rc)) << 4) + (i & 1u) * 8u;
+      col[1][d] = (rc + 8u) * ROWB + (((4u * d + cl) ^ swz_both<DH>(rc + 8u)) << 4) + (i & 1u) * 8u;
+    }
+  }
+  __device__ __forceinline__ void flip(unsigned stage_bytes) {
+#pragma unroll
+    for (int kd = 0; kd < DH / 16; ++kd) row[kd] ^= stage_bytes;
+#pragma unroll
+    for (int d = 0; d < DH / 32; ++d) { col[0][d] ^= stage_bytes; col[1][d] ^= stage_bytes; }
+  }
+  // 32 rows from row0 (a multiple of 16) of the tile at byte `tile_off` of the stage, contraction elements 16 kd ..
+  // (tile_off, row0, r0, kd, d: constants once the callers' loops are unrolled)
+  __device__ __forceinline__ bf16x8 rows(unsigned tile_off, int row0, int kd) const {
+    return *(const lds_bf16x8 *)(row[kd] + tile_off + (unsigned)row0 * ROWB);
+  }
+  // column 32 d + lane % 32 for the rows r0 + 4 * (lane / 32) + {0,1,2,3} and those 8 further; r0 a multiple of 16
+  __device__ __forceinline__ bf16x8 cols(unsigned tile_off, int r0, int d) const {
+    union { s16x4 h[2]; bf16x8 v; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(col[0][d] + tile_off + (unsigned)r0 * ROWB));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(col[1][d] + tile_off + (unsigned)r0 * ROWB));
+    return u.v;
+  }
+};
+
 // ------------------------------------------------------------------ forward
 // DROP: the probabilities are masked after the softmax (the row sums and the log-sum-exp are
 // those of the plain softmax); the scale 1/(1-p) goes into the final normalisation.
@@ -395,16 +459,18 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
                                                               const bf16 *__restrict__ d_o,
                                                               const float *__restrict__ drow,
                                                               int nh, float scale, DropArgs da) {
-  constexpr int QS = DH + 16, ND = DH / 32, NK = DH / 16;
-  // stage s: Q tile, dO tile (bf16), then 64 log-sum-exp and 64 row-dot floats
-  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  constexpr int OOFF = BKV * QS, FOFF = 2 * BKV * QS, STAGE = 2 * BKV * QS + 4 * BKV;   // in bf16 elements
+  constexpr int ND = DH / 32, NK = DH / 16;
+  // stage s: Q tile, dO tile (both in the dual-use layout), then 64 log-sum-exp and 64 row-dot floats
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_b[];
+  // LDS, in bytes: [stage 0: Q, dO][stage 1: Q, dO][stage 0: lse, row dots][stage 1: lse, row dots]
+  constexpr unsigned TILE = BKV * DH * 2, STAGE = 2 * TILE, FBASE = 2 * STAGE, FSTAGE = 8 * BKV;
 
   const int Sq = av.Sq, Sk = av.Sk;
   const int nkt = (Sk + BROWS - 1) / BROWS;
   const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int kt = wid % nkt, h = (wid / nkt) % nh, b = wid / (nkt * nh);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int H = nh * DH;
   const long ldq = av.ldq, ld = av.ldkv;
   const bf16 *qb = (const bf16 *)av.q + (long)b * Sq * ldq + (long)h * DH;
@@ -434,82 +500,140 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
   const int nq = (Sq + BKV - 1) / BKV;
   const int t0 = CAUSAL ? j0 / BKV : 0;   // query tiles before the block's first key see none of its keys
 
-  uint4 sq[DH / 32], so[DH / 32];
+  const char *qsrc = uniform_ptr((const char *)qb), *osrc = uniform_ptr((const char *)dob);
+  const unsigned ldqb = (unsigned)ldq * 2u, ldob = (unsigned)H * 2u;
   float sl = 0.f;
-  auto fetch = [&](int t) {
+  // the Q and dO tiles of query tile t go straight to LDS; the two scalars per query through a register
+  auto fetch = [&](int t, unsigned buf) {
     const int i0 = t * BKV;
-    tile_load<DH>(sq, qb, ldq, i0, Sq, tid);
-    tile_load<DH>(so, dob, H, i0, Sq, tid);
+    dma_tile_both<DH>(buf, qsrc, ldqb, i0, Sq, wave, lane);
+    dma_tile_both<DH>(buf + TILE, osrc, ldob, i0, Sq, wave, lane);
     if (tid < 64) sl = (i0 + tid < Sq) ? lrow[i0 + tid] * kLog2e : INFINITY;   // +inf: P = 0 for padding rows
     else if (tid < 128) sl = (i0 + tid - 64 < Sq) ? drw[i0 + tid - 64] : 0.f;
   };
-  auto stash = [&](int buf) {   // buf = element offset of the stage
-    tile_store<DH>(smem + buf, QS, sq, tid);
-    tile_store<DH>(smem + buf + OOFF, QS, so, tid);
-    if (tid < 128) reinterpret_cast<float *>(smem + buf + FOFF)[tid] = sl;   // [0,64): lse, [64,128): row dots
+  auto stash = [&](unsigned stage) {
+    if (tid < 128) reinterpret_cast<float *>(smem_b + FBASE + stage * FSTAGE)[tid] = sl;   // [0,64): lse, [64,128): row dots
   };
-  if (t0 < nq) { fetch(t0); stash(0); }
+  if (t0 < nq) { fetch(t0, 0u); stash(0u); }
+  BothAddr<DH> at;
+  at.init(lane);
+  wait_dma();
   __syncthreads();
 
+  // One 64-query tile is two 32-query sub-tiles, A and B.  The wave runs a software pipeline of
+  // four stages a tile, each NK steps of two MFMAs, so that the softmax arithmetic of one
+  // sub-tile issues beside the MFMAs of the other instead of between them:
+  //   1: S, dP of B              beside  P, dS of A (from the S, dP of A, taken one stage ahead)
+  //   2: dV, dK += A's P, dS     beside  P, dS of B
+  //   3: dV, dK += B's P, dS
+  //   4: (behind the tile barrier) S, dP of A of the next tile
+  // Every step reads the operand fragments of the step after it; the scheduling fences keep the
+  // steps in this order.  (The sums keep their order: sub-tile A before B, contraction ascending.)
+  constexpr int EPS = 16 / NK;                       // softmax elements a step
+  bf16x8 fx[2], fy[2];                               // fragment double buffer
+  auto ld_rows = [&](int slot, int sub, int kd) {    // Q and dO along the rows: operands of S and dP
+    fx[slot] = at.rows(0u, sub * 32, kd);
+    fy[slot] = at.rows(TILE, sub * 32, kd);
+  };
+  auto ld_cols = [&](int slot, int sub, int j) {     // dO and Q down the rows: operands of dV and dK
+    fx[slot] = at.cols(TILE, sub * 32 + (j / ND) * 16, j % ND);
+    fy[slot] = at.cols(0u, sub * 32 + (j / ND) * 16, j % ND);
+  };
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  // a wave's keys see no query of a tile that lies wholly above the diagonal
+  auto active = [&](int t) { return !CAUSAL || t * BKV + BKV - 1 >= jw0; };
+  f32x16 sA, dpA;
+  auto logits_of_a = [&] {   // stage 4 (and the prologue); leaves the first fragments of stage 1 in flight
+    ld_rows(0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { sA[e] = 0.f; dpA[e] = 0.f; }
+#pragma unroll
+    for (int kd = 0; kd < NK; ++kd) {
+      if (kd + 1 < NK) ld_rows((kd + 1) & 1, 0, kd + 1); else ld_rows((kd + 1) & 1, 1, 0);
+      sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], kf[kd], sA, 0, 0, 0);
+      dpA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], vf[kd], dpA, 0, 0, 0);
+      fence();
+    }
+  };
+  if (t0 < nq && active(t0)) logits_of_a();
+
   for (int t = t0; t < nq; ++t) {
-    const int cur = ((t - t0) & 1) * STAGE, nxt = STAGE - cur, i0 = t * BKV;
-    const float *lds_f = reinterpret_cast<const float *>(smem + cur + FOFF);
-    if (t + 1 < nq) fetch(t + 1);
-    if (!CAUSAL || i0 + BKV - 1 >= jw0) {
-      // MASK = false: the tile lies wholly below the diagonal for this wave's keys (or there is
-      // no mask), so the per-element causal test goes
-      auto tile = [&](auto mask_tag) {
-        constexpr bool MASK = decltype(mask_tag)::value;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        f32x16 s, dp;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
-#pragma unroll
-        for (int kd = 0; kd < NK; ++kd) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, QS, sub * 32, kd * 16, lane), kf[kd], s,
-                                                      0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur + OOFF, QS, sub * 32, kd * 16, lane),
-                                                       vf[kd], dp, 0, 0, 0);
+    const unsigned cur = (unsigned)((t - t0) & 1), nxt = cur ^ 1u;   // stages
+    const int i0 = t * BKV;
+    const float *lds_f = reinterpret_cast<const float *>(smem_b + FBASE + cur * FSTAGE);
+    if (t + 1 < nq) fetch(t + 1, nxt * STAGE);   // (every wave left that stage at the barrier below)
+    if (active(t)) {
+      // elements e0 .. e0+EPS-1 of a sub-tile: logits -> P (or P' under dropout), dP -> dS
+      auto soft = [&](f32x16 &sv, f32x16 &dpv, int sub, int e0) {
+        const int r0 = sub * 32 + 8 * (e0 >> 2) + 4 * hh + (e0 & 3);
+        float lv[EPS], dvv[EPS];
+        if constexpr (EPS == 4) {
+          const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r0), d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r0);
+          lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w; dvv[0] = d4.x; dvv[1] = d4.y; dvv[2] = d4.z; dvv[3] = d4.w;
+        } else {
+          const float2 l2 = *reinterpret_cast<const float2 *>(lds_f + r0), d2 = *reinterpret_cast<const float2 *>(lds_f + BKV + r0);
+          lv[0] = l2.x; lv[1] = l2.y; dvv[0] = d2.x; dvv[1] = d2.y;
         }
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int r = sub * 32 + 8 * e4 + 4 * hh;
-          const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r);
-          const float4 d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r);
-          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int t4 = 0; t4 < 4; ++t4) {
-            const int e = e4 * 4 + t4, i = i0 + r + t4;
-            float p = fast_exp2(s[e] * c - lv[t4]);
-            if (MASK && kj > i) p = 0.f;   // (rows past the end carry lse = +inf: p = 0 by itself)
-            if (DROP) {
-              const bool keep = drop_bits((uint32_t)i * (uint32_t)Sk + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
-              s[e] = keep ? p * da.scale : 0.f;
-              dp[e] = p * ((keep ? dp[e] * da.scale : 0.f) - dvv[t4]);
-            } else {
-              s[e] = p;
-              dp[e] = p * (dp[e] - dvv[t4]);
-            }
+        for (int u = 0; u < EPS; ++u) {
+          const int e = e0 + u, i = i0 + r0 + u;
+          const float l = lv[u], dd = dvv[u];
+          const float pr = fast_exp2(sv[e] * c - l);   // (rows past the end carry lse = +inf: p = 0 by itself)
+          if (DROP) {
+            const bool keep = drop_bits((uint32_t)i * (uint32_t)Sk + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
+            sv[e] = keep ? pr * da.scale : 0.f;
+            dpv[e] = pr * ((keep ? dpv[e] * da.scale : 0.f) - dd);
+          } else {
+            sv[e] = pr;
+            dpv[e] = pr * (dpv[e] - dd);
           }
         }
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 pf = pack8(s, half * 8), dsf = pack8(dp, half * 8);
-#pragma unroll
-          for (int d = 0; d < ND; ++d) {
-            dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(smem + cur + OOFF, QS, sub * 32 + half * 16, d * 32, lane), pf, dv[d], 0, 0, 0);
-            dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(smem + cur, QS, sub * 32 + half * 16, d * 32, lane), dsf, dk[d], 0, 0, 0);
-          }
-        }
-      }
       };
-      if (CAUSAL && i0 < jw0 + 31) tile(std::true_type{}); else tile(std::false_type{});
+      // the causal mask, on the sub-tiles the diagonal crosses only: a masked logit becomes -inf, its P zero
+      auto mask = [&](f32x16 &sv, int sub) {
+        if (CAUSAL && i0 + 32 * sub < jw0 + 31) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (kj > i0 + sub * 32 + acc_row(e, lane)) sv[e] = -INFINITY;
+        }
+      };
+      f32x16 sB, dpB;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { sB[e] = 0.f; dpB[e] = 0.f; }
+      mask(sA, 0);
+#pragma unroll
+      for (int kd = 0; kd < NK; ++kd) {   // stage 1
+        if (kd + 1 < NK) ld_rows((kd + 1) & 1, 1, kd + 1); else ld_cols((kd + 1) & 1, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], kf[kd], sB, 0, 0, 0);
+        dpB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], vf[kd], dpB, 0, 0, 0);
+        soft(sA, dpA, 0, kd * EPS);
+        fence();
+      }
+      bf16x8 pf[2], dsf[2];
+      pf[0] = pack8(sA, 0); pf[1] = pack8(sA, 8); dsf[0] = pack8(dpA, 0); dsf[1] = pack8(dpA, 8);
+      mask(sB, 1);
+#pragma unroll
+      for (int j = 0; j < NK; ++j) {      // stage 2
+        if (j + 1 < NK) ld_cols((j + 1) & 1, 0, j + 1); else ld_cols((j + 1) & 1, 1, 0);
+        dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
+        dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
+        soft(sB, dpB, 1, j * EPS);
+        fence();
+      }
+      pf[0] = pack8(sB, 0); pf[1] = pack8(sB, 8); dsf[0] = pack8(dpB, 0); dsf[1] = pack8(dpB, 8);
+#pragma unroll
+      for (int j = 0; j < NK; ++j) {      // stage 3
+        if (j + 1 < NK) ld_cols((j + 1) & 1, 1, j + 1);
+        dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
+        dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
+        fence();
+      }
     }
     if (t + 1 < nq) stash(nxt);
+    at.flip(STAGE);
+    wait_dma();
     __syncthreads();
+    if (t + 1 < nq && active(t + 1)) logits_of_a();   // stage 4
   }
 
   if (kj >= Sk) return;
@@ -654,7 +778,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
 template <int DH>
 hipError_t bwd_launch(int B, int nh, int causal, const AttnView &av, const void *o, const float *lse,
                       const void *d_o, float *ws, const DropArgs *drop, hipStream_t s) {
-  constexpr size_t smem_kv = 4 * (size_t)BKV * (DH + 16) * sizeof(bf16) + 4 * BKV * sizeof(float);
+  constexpr size_t smem_kv = 2 * (2 * (size_t)BKV * DH * sizeof(bf16) + 2 * BKV * sizeof(float));   // Q, dO; lse, row dots
   constexpr size_t smem_q = 2 * (size_t)BKV * ((DH + 16) + (DH + 8)) * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
@@ -718,7 +842,7 @@ hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const At
 hipError_t launch_attn_bwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, const void *o,
                                      const float *lse, const void *d_o, float *ws, hipStream_t s,
                                      const DropArgs *drop) {
-  if ((causal && v.Sq != v.Sk) || !view_ok(v)) return hipErrorInvalidValue;
+  if ((causal && v.Sq != v.Sk) || !view_ok(v) || ((uintptr_t)d_o & 15) != 0) return hipErrorInvalidValue;
   if ((long)B * nh == 0 || (v.Sq == 0 && v.Sk == 0)) return hipSuccess;
   return dh == 64 ? bwd_launch<64>(B, nh, causal, v, o, lse, d_o, ws, drop, s)
                   : bwd_launch<128>(B, nh, causal, v, o, lse, d_o, ws, drop, s);
