@@ -658,16 +658,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
                                                              const bf16 *__restrict__ d_o,
                                                              const float *__restrict__ drow,
                                                              int nh, float scale, DropArgs da) {
-  constexpr int KS = DH + 16, VS = DH + 8, ND = DH / 32, NK = DH / 16;
-  extern __shared__ __attribute__((aligned(16))) bf16 smem[];
-  constexpr int VOFF = BKV * KS, STAGE = BKV * (KS + VS);
+  constexpr int ND = DH / 32, NK = DH / 16;
+  // LDS, in bytes: [stage 0: K, V][stage 1: K, V], every tile in the dual-use layout
+  constexpr unsigned TILE = BKV * DH * 2, STAGE = 2 * TILE;
 
   const int Sq = av.Sq, S = av.Sk;   // S: the key count
   const int nqt = (Sq + BROWS - 1) / BROWS;
   const int wid = xcd_contiguous(blockIdx.x, gridDim.x);
   const int qt = nqt - 1 - wid % nqt;
   const int h = (wid / nqt) % nh, b = wid / (nqt * nh);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int H = nh * DH;
   const long ldq = av.ldq, ld = av.ldkv;
   const bf16 *qb = (const bf16 *)av.q + (long)b * Sq * ldq + (long)h * DH;
@@ -698,68 +699,112 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
   int nkv = (S + BKV - 1) / BKV;
   if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
 
-  uint4 sk[DH / 32], sv[DH / 32];
-  tile_load<DH>(sk, kb, ld, 0, S, tid);
-  tile_load<DH>(sv, vb, ld, 0, S, tid);
-  tile_store<DH>(smem, KS, sk, tid);
-  tile_store<DH>(smem + VOFF, VS, sv, tid);
+  const char *ksrc = uniform_ptr((const char *)kb), *vsrc = uniform_ptr((const char *)vb);
+  const unsigned ldb = (unsigned)ld * 2u;
+  auto fetch = [&](int t, unsigned buf) {
+    dma_tile_both<DH>(buf, ksrc, ldb, t * BKV, S, wave, lane);
+    dma_tile_both<DH>(buf + TILE, vsrc, ldb, t * BKV, S, wave, lane);
+  };
+  if (nkv > 0) fetch(0, 0u);
+  BothAddr<DH> at;
+  at.init(lane);
+  wait_dma();
   __syncthreads();
 
-  for (int t = 0; t < nkv; ++t) {
-    const int cur = (t & 1) * STAGE, nxt = STAGE - cur, j0 = t * BKV;
-    if (t + 1 < nkv) {
-      tile_load<DH>(sk, kb, ld, j0 + BKV, S, tid);
-      tile_load<DH>(sv, vb, ld, j0 + BKV, S, tid);
+  // The same four-stage pipeline as the dK/dV kernel, over the two 32-key sub-tiles A and B of a
+  // 64-key tile:  1: S, dP of B beside dS of A;  2: dQ += dS_A K beside dS of B;  3: dQ += dS_B K;
+  // 4: (behind the tile barrier) S, dP of A of the next tile.  Stages 2 and 3 have one MFMA a step.
+  constexpr int EPS = 16 / NK;
+  bf16x8 fx[2], fy[2];
+  auto ld_rows = [&](int slot, int sub, int kd) {   // K and V along the rows: operands of S and dP
+    fx[slot] = at.rows(0u, sub * 32, kd);
+    fy[slot] = at.rows(TILE, sub * 32, kd);
+  };
+  auto ld_cols = [&](int slot, int sub, int j) {    // K down the rows: operand of dQ
+    fx[slot] = at.cols(0u, sub * 32 + (j / ND) * 16, j % ND);
+  };
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  // (A wave whose queries see no key of the block's last tile runs it all the same, every logit
+  // masked: it would wait for the other waves at the tile barrier anyway.)
+  f32x16 sA, dpA;
+  auto logits_of_a = [&] {
+    ld_rows(0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { sA[e] = 0.f; dpA[e] = 0.f; }
+#pragma unroll
+    for (int kd = 0; kd < NK; ++kd) {
+      if (kd + 1 < NK) ld_rows((kd + 1) & 1, 0, kd + 1); else ld_rows((kd + 1) & 1, 1, 0);
+      sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], qf[kd], sA, 0, 0, 0);
+      dpA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], gf[kd], dpA, 0, 0, 0);
+      fence();
     }
-    if (!CAUSAL || j0 <= iw0 + 31) {
-      // MASK = false: every key of the tile exists and is visible to every query of the wave
-      auto tile = [&](auto mask_tag) {
-        constexpr bool MASK = decltype(mask_tag)::value;
+  };
+  if (nkv > 0) logits_of_a();
+
+  for (int t = 0; t < nkv; ++t) {
+    const int j0 = t * BKV;
+    if (t + 1 < nkv) fetch(t + 1, (unsigned)((t & 1) ^ 1) * STAGE);   // (every wave left that stage at the barrier below)
+    {
+      // keys past the end and keys the causal mask hides, on the sub-tiles that have any: the
+      // logit becomes -inf, its P zero
+      auto mask = [&](f32x16 &sv, int sub) {
+        const int jb = j0 + 32 * sub;
+        if (jb + 32 > S || (CAUSAL && jb + 31 > iw0)) {
+          const int lim = (CAUSAL ? min(S, qi + 1) : S) - jb - 4 * hh;   // the lane's first hidden row of the sub-tile
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        f32x16 s, dp;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
-#pragma unroll
-        for (int kd = 0; kd < NK; ++kd) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur, KS, sub * 32, kd * 16, lane), qf[kd], s,
-                                                      0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(smem + cur + VOFF, VS, sub * 32, kd * 16, lane),
-                                                       gf[kd], dp, 0, 0, 0);
+          for (int e = 0; e < 16; ++e)
+            if (8 * (e >> 2) + (e & 3) >= lim) sv[e] = -INFINITY;
         }
+      };
+      // elements e0 .. e0+EPS-1 of a sub-tile: logits -> P, dP -> dS
+      auto soft = [&](f32x16 &sv, f32x16 &dpv, int sub, int e0) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float p = fast_exp2(s[e] * c - lq);
-          if (MASK) {
-            const int j = j0 + sub * 32 + acc_row(e, lane);
-            if (j >= S || (CAUSAL && j > qi)) p = 0.f;
-          }
+        for (int u = 0; u < EPS; ++u) {
+          const int e = e0 + u;
+          const float pr = fast_exp2(sv[e] * c - lq);   // (queries past the end carry lse = +inf: p = 0)
           if (DROP) {
             const bool keep =
                 drop_bits(qidx + (uint32_t)(j0 + sub * 32 + acc_row(e, lane)), keys.k0, keys.k1) >= da.thr;
-            dp[e] = p * ((keep ? dp[e] * da.scale : 0.f) - dq_i);
+            dpv[e] = pr * ((keep ? dpv[e] * da.scale : 0.f) - dq_i);
           } else {
-            dp[e] = p * (dp[e] - dq_i);
+            dpv[e] = pr * (dpv[e] - dq_i);
           }
         }
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 dsf = pack8(dp, half * 8);
-#pragma unroll
-          for (int d = 0; d < ND; ++d)
-            dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(smem + cur, KS, sub * 32 + half * 16, d * 32, lane), dsf, dq[d], 0, 0, 0);
-        }
-      }
       };
-      // (with head dimension 128 a second copy of the tile code costs more registers than there are)
-      if (DH != 64 || j0 + BKV > S || (CAUSAL && j0 + BKV - 1 > iw0)) tile(std::true_type{}); else tile(std::false_type{});
+      f32x16 sB, dpB;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { sB[e] = 0.f; dpB[e] = 0.f; }
+      mask(sA, 0);
+#pragma unroll
+      for (int kd = 0; kd < NK; ++kd) {   // stage 1
+        if (kd + 1 < NK) ld_rows((kd + 1) & 1, 1, kd + 1); else ld_cols((kd + 1) & 1, 0, 0);
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], qf[kd], sB, 0, 0, 0);
+        dpB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], gf[kd], dpB, 0, 0, 0);
+        soft(sA, dpA, 0, kd * EPS);
+        fence();
+      }
+      bf16x8 dsf[2];
+      dsf[0] = pack8(dpA, 0); dsf[1] = pack8(dpA, 8);
+      mask(sB, 1);
+#pragma unroll
+      for (int j = 0; j < NK; ++j) {      // stage 2
+        if (j + 1 < NK) ld_cols((j + 1) & 1, 0, j + 1); else ld_cols((j + 1) & 1, 1, 0);
+        dq[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], dsf[j / ND], dq[j % ND], 0, 0, 0);
+        soft(sB, dpB, 1, j * EPS);
+        fence();
+      }
+      dsf[0] = pack8(dpB, 0); dsf[1] = pack8(dpB, 8);
+#pragma unroll
+      for (int j = 0; j < NK; ++j) {      // stage 3
+        if (j + 1 < NK) ld_cols((j + 1) & 1, 1, j + 1);
+        dq[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], dsf[j / ND], dq[j % ND], 0, 0, 0);
+        fence();
+      }
     }
-    if (t + 1 < nkv) {
-      tile_store<DH>(smem + nxt, KS, sk, tid);
-      tile_store<DH>(smem + nxt + VOFF, VS, sv, tid);
-    }
+    at.flip(STAGE);
+    wait_dma();
     __syncthreads();
+    if (t + 1 < nkv) logits_of_a();   // stage 4
   }
 
   if (qi >= Sq) return;
@@ -779,7 +824,7 @@ template <int DH>
 hipError_t bwd_launch(int B, int nh, int causal, const AttnView &av, const void *o, const float *lse,
                       const void *d_o, float *ws, const DropArgs *drop, hipStream_t s) {
   constexpr size_t smem_kv = 2 * (2 * (size_t)BKV * DH * sizeof(bf16) + 2 * BKV * sizeof(float));   // Q, dO; lse, row dots
-  constexpr size_t smem_q = 2 * (size_t)BKV * ((DH + 16) + (DH + 8)) * sizeof(bf16);
+  constexpr size_t smem_q = 2 * 2 * (size_t)BKV * DH * sizeof(bf16);                                 // K, V
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = set_smem(attn_bwd_dkv_kernel<DH, true, false>, smem_kv);
