@@ -208,12 +208,17 @@ size_t dp_plan_len(const dp_stage_config *cfg);
  * report->first_bad_* name it), DP_E_UNSUPPORTED (shape), DP_E_BUDGET.
  * Plan bytes of slots without storage (see the slot list) are ignored; SWAP on
  * X_IN of layer 0 is treated as KEEP because that buffer is the caller's.
- * Arena policy for swapped-out blocks: with budget_bytes == 0 a block returns to
- * the allocator as soon as its copy-out is queued (smallest peak; its next user
- * waits for the copy).  With a budget the walk first tries to hold such blocks
- * back until forward is over, then for ever shorter spans, then not at all, and takes
- * the first policy whose peak fits: forward compute then never waits for the
- * host link when memory allows.  dp_stage_step makes the same choice. */
+ * Swap policy: with budget_bytes == 0 a swapped-out block returns to the
+ * allocator as soon as its copy-out is queued (smallest peak; its next user
+ * waits for the copy) and the swap-ins of a layer are issued one layer of
+ * backward ahead of it.  With a budget, the headroom is spent on the swaps,
+ * from the most generous policy down, and the first whose peak fits is taken:
+ * swap-ins as many layers ahead as the stage is deep, then half as many, ...,
+ * then one; for each distance, swapped-out blocks held back until the backward
+ * has released them, then until the forward is over, then for ever shorter
+ * spans, then not at all.  Computation then waits for the host link as little
+ * as the memory allows.  dp_stage_step makes the same choice, so its arena has
+ * exactly the validated size. */
 dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len,
                            uint64_t budget_bytes, uint32_t inflight, dp_plan_report *report);
 
@@ -270,7 +275,8 @@ enum { DP_MEMOPT_VALIDATE = 1 };
 /* Pure host code.  Plays one step under `plan` on three clocks (compute, copy-out, copy-in)
  * with the executor's event rules: a swap-out starts when its tensor's last forward reader
  * is done and the copy-out stream is free; the swap-ins of layer l-1 are issued when the
- * backward of layer l starts, each behind its own copy-out; a backward node waits for the
+ * backward of layer l starts, in the order the backward reads them, each behind its own
+ * copy-out; a backward node waits for the
  * swap-ins it reads; recomputed tensors are regenerated on the compute clock before their
  * first backward reader.  Memory is the saved tensors only (no transient gradients, no
  * fragmentation); fixed_bytes is added to the peak.  Errors as dp_plan_validate, plus
