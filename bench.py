@@ -41,8 +41,9 @@ ROCPROF_NT_LAUNCH_US = {
 def cpu_baseline(cfg, weights, x, dy, budget_s=25.0, mem=None):
     """The oracle as it stands (fp64 numpy) on a bounded sample of the workload: the first layer of the stage on
     the first sample of the micro-batch; if one layer on the whole micro-batch fits the time budget it is run on
-    that, and if the whole stage fits, on that.  The time is scaled to the whole step: every layer costs the
-    same, and no operator mixes samples, so the cost is linear in both."""
+    that, and if the whole stage fits, on that; otherwise on as many samples of one layer as about 20 s hold.  The
+    time is scaled to the whole step: every layer costs the same, and no operator mixes samples, so the cost is
+    linear in both."""
     import numpy as np
     from oracle import stage as O
 
@@ -68,6 +69,11 @@ def cpu_baseline(cfg, weights, x, dy, budget_s=25.0, mem=None):
         dt, samples = run(1, B), B
         if dt * L <= budget_s:
             dt, layers = run(L, B), L
+    else:
+        # as many samples of one layer as about 20 s hold (a divisor of the micro-batch, so the scaling is whole)
+        fit = max(n for n in range(1, B + 1) if B % n == 0 and dt * n <= max(20.0, dt))
+        if fit > 1:
+            dt, samples = run(1, fit), fit
     step_s = dt * (L / layers) * (B / samples)
     sample = (f"{layers} of {L} layers on {samples} of {B} samples (fp64 numpy), "
               f"time scaled by {L // layers} x {B // samples}" if (layers, samples) != (L, B)
