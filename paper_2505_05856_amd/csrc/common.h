@@ -41,6 +41,24 @@ __device__ __forceinline__ void store8(bf16 *p, const float (&v)[8]) {
   for (int i = 0; i < 8; ++i) a[i] = (bf16)v[i];
   *reinterpret_cast<bf16x8 *>(p) = a;
 }
+// Eight elements as they lie in memory, for loads that wait in registers before they are used.
+template <typename T> struct Raw8;
+template <> struct Raw8<float> {
+  float v[8];
+  __device__ __forceinline__ void load(const float *p) { load8(p, v); }
+  __device__ __forceinline__ void unpack(float (&o)[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = v[i];
+  }
+};
+template <> struct Raw8<bf16> {
+  bf16x8 v;
+  __device__ __forceinline__ void load(const bf16 *p) { v = *reinterpret_cast<const bf16x8 *>(p); }
+  __device__ __forceinline__ void unpack(float (&o)[8]) const {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (float)v[i];
+  }
+};
 __device__ __forceinline__ float ldf(const float *p) { return *p; }
 __device__ __forceinline__ float ldf(const bf16 *p) { return (float)*p; }
 __device__ __forceinline__ void stf(float *p, float v) { *p = v; }

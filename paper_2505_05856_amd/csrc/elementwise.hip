@@ -231,7 +231,12 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
 // thread holds 16..32 elements of a row instead of 64..128: several blocks fit a CU where the
 // wave-per-row form fits one or two waves a SIMD.  The two row sums cross the waves through LDS
 // (one barrier a row; two alternating slots); the next row's loads are issued before that.
-template <typename T, int NP, bool SUMDX>
+// FULL: the row is exactly NP * 2048 columns wide, every block has a multiple of four rows and RES
+// says whether there is a residual gradient, so the row loop has no branch in it.  (With branches around the loads the compiler
+// can no longer count which of the loads in flight a use needs and waits for all of them, which
+// leaves one row in flight instead of PF.)  Rows past the block's range are then fetched as
+// copies of its last row and never used.
+template <typename T, int NP, bool SUMDX, bool FULL, bool RES>
 __global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
                                                           const float *__restrict__ stats,
                                                           const T *__restrict__ gamma, const T *__restrict__ dres,
@@ -245,41 +250,63 @@ __global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may ali
 #pragma unroll
   for (int c = 0; c < NP; ++c) {
     const int col = (c * 256 + tid) * 8;
-    if (col < cols) load8(gamma + col, gm[c]);
+    if (FULL || col < cols) load8(gamma + col, gm[c]);
 #pragma unroll
     for (int i = 0; i < 8; ++i) { dg[c][i] = 0.f; db[c][i] = 0.f; if (SUMDX) ds[c][i] = 0.f; }
   }
   const float inv_n = 1.0f / (float)cols;
   // PF rows are in flight per block (a block is one wave per SIMD and only a few blocks share a
-  // CU, so the loads of several rows ahead are what keeps the memory system busy)
-  constexpr int PF = 3;   // (four was slower: the registers then leave one block a CU)
-  float xn[PF][NP][8], dn[PF][NP][8];
+  // CU, so the loads of several rows ahead are what keeps the memory system busy).  They wait in
+  // registers as loaded (8 bf16 in 4 registers) and are widened when their row is worked on; the
+  // row's two statistics travel with them, and the residual gradient of a row is asked for one
+  // row ahead, so that no load is issued and awaited inside a row's own work.
+  constexpr int PF = FULL ? 2 : 4;
+  Raw8<T> xn[PF][NP], dn[PF][NP], rn[2][NP];
+  float mean_n[PF], rstd_n[PF];
   auto fetch = [&](int row, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
-    if (row >= row_end) return;
+    if (FULL) row = min(row, row_end - 1); else if (row >= row_end) return;
+    const size_t base = (size_t)row * cols;
+    mean_n[BUF] = stats[2 * (size_t)row];
+    rstd_n[BUF] = stats[2 * (size_t)row + 1];
+#pragma unroll
+    for (int c = 0; c < NP; ++c) {
+      const int col = (c * 256 + tid) * 8;
+      if (FULL || col < cols) { xn[BUF][c].load(x + base + col); dn[BUF][c].load(dy + base + col); }
+    }
+  };
+  auto fetch_res = [&](int row, auto par_tag) {
+    constexpr int PAR = decltype(par_tag)::value;
+    if (FULL) { if (!RES) return; row = min(row, row_end - 1); }
+    else if (dres == nullptr || row >= row_end) return;
     const size_t base = (size_t)row * cols;
 #pragma unroll
     for (int c = 0; c < NP; ++c) {
       const int col = (c * 256 + tid) * 8;
-      if (col < cols) { load8(x + base + col, xn[BUF][c]); load8(dy + base + col, dn[BUF][c]); }
+      if (FULL || col < cols) rn[PAR][c].load(dres + base + col);
     }
   };
-  auto process = [&](int row, auto buf_tag) {
+  auto process = [&](int row, auto buf_tag, auto par_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
-    const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+    constexpr int PAR = decltype(par_tag)::value;
+    const float mean = mean_n[BUF], rstd = rstd_n[BUF];
     const size_t base = (size_t)row * cols;
+    fetch_res(row + 1, std::integral_constant<int, 1 - PAR>{});
     float xh[NP][8], g[NP][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int c = 0; c < NP; ++c) {
       const int col = (c * 256 + tid) * 8;
-      if (col < cols) {
+      if (FULL || col < cols) {
+        float xv[8], dv[8];
+        xn[BUF][c].unpack(xv);
+        dn[BUF][c].unpack(dv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          xh[c][i] = (xn[BUF][c][i] - mean) * rstd;
-          dg[c][i] += dn[BUF][c][i] * xh[c][i];
-          db[c][i] += dn[BUF][c][i];
-          g[c][i] = dn[BUF][c][i] * gm[c][i];
+          xh[c][i] = (xv[i] - mean) * rstd;
+          dg[c][i] += dv[i] * xh[c][i];
+          db[c][i] += dv[i];
+          g[c][i] = dv[i] * gm[c][i];
           s1 += g[c][i];
           s2 += g[c][i] * xh[c][i];
         }
@@ -295,13 +322,13 @@ __global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may ali
 #pragma unroll
     for (int c = 0; c < NP; ++c) {
       const int col = (c * 256 + tid) * 8;
-      if (col < cols) {
+      if (FULL || col < cols) {
         float o[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[i] = rstd * (g[c][i] - m1 - xh[c][i] * m2);
-        if (dres != nullptr) {
+        if (FULL ? RES : dres != nullptr) {
           float r[8];
-          load8(dres + base + col, r);
+          rn[PAR][c].unpack(r);
 #pragma unroll
           for (int i = 0; i < 8; ++i) o[i] += r[i];
         }
@@ -313,20 +340,41 @@ __global__ __launch_bounds__(256) void ln_bwd_wide_kernel(const T *dy /* may ali
       }
     }
   };
-  fetch(row0, std::integral_constant<int, 0>{});
-  fetch(row0 + 1, std::integral_constant<int, 1>{});
-  fetch(row0 + 2, std::integral_constant<int, 2>{});
-  // (the trip count of the loop is the same for every thread of the block: the barriers inside match)
-  for (int row = row0; row < row_end; row += PF) {
-    process(row, std::integral_constant<int, 0>{});
-    if (row + 1 < row_end) process(row + 1, std::integral_constant<int, 1>{});
-    if (row + 2 < row_end) process(row + 2, std::integral_constant<int, 2>{});
+  using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
+  fetch(row0, I0{});
+  fetch(row0 + 1, I1{});
+  if (!FULL) {
+    fetch(row0 + 2, std::integral_constant<int, FULL ? 0 : 2>{});
+    fetch(row0 + 3, std::integral_constant<int, FULL ? 1 : 3>{});
+  }
+  fetch_res(row0, I0{});
+  // (the trip count of the loop is the same for every thread of the block: the barriers inside match;
+  //  rows alternate between the two residual buffers)
+  if (FULL) {   // (the launcher gives every block a multiple of four rows)
+    for (int row = row0; row < row_end; row += 4) {
+      // (fences: the rows' instruction streams stay apart, or their temporaries add up)
+      process(row, I0{}, I0{});
+      __builtin_amdgcn_sched_barrier(0);
+      process(row + 1, I1{}, I1{});
+      __builtin_amdgcn_sched_barrier(0);
+      process(row + 2, I0{}, I0{});
+      __builtin_amdgcn_sched_barrier(0);
+      process(row + 3, I1{}, I1{});
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+    for (int row = row0; row < row_end; row += 4) {
+      process(row, I0{}, I0{});
+      if (row + 1 < row_end) process(row + 1, I1{}, I1{});
+      if (row + 2 < row_end) process(row + 2, std::integral_constant<int, FULL ? 0 : 2>{}, I0{});
+      if (row + 3 < row_end) process(row + 3, std::integral_constant<int, FULL ? 1 : 3>{}, I1{});
+    }
   }
   float *prow = part + (size_t)blockIdx.x * NV * cols;
 #pragma unroll
   for (int c = 0; c < NP; ++c) {
     const int col = (c * 256 + tid) * 8;
-    if (col < cols) {
+    if (FULL || col < cols) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         prow[col + i] = dg[c][i];
@@ -584,9 +632,15 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
 #define DP_LN_BWD(NC)                                                                                       \
   hipLaunchKernelGGL((ln_bwd_kernel<T, NC, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, \
                      stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb, rms)
-#define DP_LN_BWD_WIDE(NP)                                                                                  \
-  hipLaunchKernelGGL((ln_bwd_wide_kernel<T, NP, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy,          \
+#define DP_LN_BWD_WIDE_AS(NP, FULL, RES)                                                                      \
+  hipLaunchKernelGGL((ln_bwd_wide_kernel<T, NP, SUMDX, FULL, RES>), dim3(nb), dim3(256), 0, s, (const T *)dy, \
                      (const T *)x, stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb, rms)
+#define DP_LN_BWD_WIDE(NP)                                                    \
+  do {                                                                        \
+    if (cols != NP * 2048 || rows % 4 != 0 || rpb % 4 != 0) DP_LN_BWD_WIDE_AS(NP, false, false); \
+    else if (dres != nullptr) DP_LN_BWD_WIDE_AS(NP, true, true);              \
+    else DP_LN_BWD_WIDE_AS(NP, true, false);                                  \
+  } while (0)
   switch (ln_chunks(cols)) {
     case 1: DP_LN_BWD(1); break;
     case 2: DP_LN_BWD(2); break;
@@ -595,6 +649,7 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
     default: DP_LN_BWD_WIDE(4); break;    // up to 8192
   }
 #undef DP_LN_BWD_WIDE
+#undef DP_LN_BWD_WIDE_AS
 #undef DP_LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
