@@ -380,6 +380,17 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
 dp_status dp_stage_set_weights(dp_stage *st, const dp_layer_weights *layers, void *hip_stream);
 int32_t dp_stage_weight_versions(const dp_stage *st);
 
+/* Diagnostics: copies one saved tensor of the micro-batch that dp_stage_forward left in
+ * `slot` (its backward not yet issued) to dst (device, exactly the tensor's size in bytes:
+ * the slot list gives the shape, the stage's dtype the element size), ordered on hip_stream
+ * behind that forward.  For tests that need a decision the stage took on a stored value
+ * (the sign ReLU's derivative reads, R32-style comparisons) rather than a recomputed one.
+ * Errors: DP_E_INVAL (no micro-batch in the slot, layer or tensor out of range, a tensor
+ * without storage of its own, wrong dst_bytes), DP_E_PLAN (the plan did not KEEP the tensor:
+ * it is not on the device). */
+dp_status dp_stage_read_saved(dp_stage *st, uint32_t slot, uint32_t layer, uint32_t tensor, void *dst,
+                              size_t dst_bytes, void *hip_stream);
+
 /* Dropout state (only matters when the configuration has a non-zero rate).  A mask is a
  * pure function of (seed, micro-batch number, layer, site, position): every dp_stage_step and
  * dp_stage_forward takes the current micro-batch number and increments it, so successive

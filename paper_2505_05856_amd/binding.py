@@ -140,6 +140,7 @@ def lib() -> C.CDLL:
     L.dp_stage_set_weights.argtypes = [vp, C.POINTER(LayerPtrs), vp]
     L.dp_stage_weight_versions.argtypes = [vp]
     L.dp_stage_weight_versions.restype = i32
+    L.dp_stage_read_saved.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_uint32, vp, sz, vp]
     L.dp_stage_set_profiling.argtypes = [vp, i32]
     L.dp_stage_op_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(u64)]
     L.dp_stage_op_flops.argtypes = [vp, C.POINTER(C.c_double)]
@@ -370,6 +371,13 @@ def stage_backward(stage: Stage, slot: int, dy, dx_out, grads: Sequence[Dict[str
                    stream=None):
     _check(lib().dp_stage_backward(stage.handle, slot, _ptr(dy), _ptr(dx_out), _layer_array(grads), flags,
                                    _stream_ptr(stream)))
+
+
+def stage_read_saved(stage: Stage, slot: int, layer: int, tensor: int, dst, stream=None):
+    """Copies saved tensor `tensor` of layer `layer` of the micro-batch in flight in `slot` into the device
+    tensor `dst` (exactly that many bytes)."""
+    _check(lib().dp_stage_read_saved(stage.handle, slot, layer, tensor, _ptr(dst), dst.numel() * dst.element_size(),
+                                     _stream_ptr(stream)))
 
 
 def stage_set_weights(stage: Stage, weights: Sequence[Dict[str, "object"]], stream=None):

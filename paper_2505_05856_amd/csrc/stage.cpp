@@ -1831,6 +1831,26 @@ dp_status dp_stage_backward(dp_stage *st, uint32_t slot, const void *dy, void *d
   return DP_OK;
 }
 
+dp_status dp_stage_read_saved(dp_stage *st, uint32_t slot, uint32_t layer, uint32_t tensor, void *dst,
+                              size_t dst_bytes, void *hip_stream) {
+  if (st == nullptr || dst == nullptr) return fail(DP_E_INVAL, "null argument");
+  if (slot >= st->flights.size() || !st->flights[slot] || st->flights[slot]->walk == nullptr)
+    return fail(DP_E_INVAL, "slot %u holds no micro-batch (call dp_stage_forward first)", slot);
+  const Cfg &c = st->c;
+  if ((int)layer >= c.L || (int)tensor >= c.nslots) return fail(DP_E_INVAL, "layer %u / tensor %u out of range", layer, tensor);
+  Walk *w = st->flights[slot]->walk;
+  if (slot_is_alias(c, (int)tensor) || slot_bytes(c, (int)tensor) == 0 || w->caller_owned((int)layer, (int)tensor))
+    return fail(DP_E_INVAL, "tensor %u of layer %u has no storage of its own in the stage", tensor, layer);
+  if (dst_bytes != slot_bytes(c, (int)tensor))
+    return fail(DP_E_INVAL, "tensor %u is %zu bytes, dst_bytes is %zu", tensor, slot_bytes(c, (int)tensor), dst_bytes);
+  if (w->S((int)layer, (int)tensor).where != RESIDENT)
+    return fail(DP_E_PLAN, "tensor %u of layer %u is not on the device under this plan", tensor, layer);
+  hipStream_t cs = (hipStream_t)hip_stream;
+  if (cs != w->cs) { const int j = w->new_event(); w->record(j, w->cs); w->wait(cs, j); }
+  HIP_TRY(hipMemcpyAsync(dst, w->ptr((int)layer, (int)tensor), dst_bytes, hipMemcpyDeviceToDevice, cs), DP_E_HIP);
+  return DP_OK;
+}
+
 dp_status dp_stage_set_weights(dp_stage *st, const dp_layer_weights *layers, void *hip_stream) {
   if (st == nullptr) return fail(DP_E_INVAL, "stage handle is null");
   dp_status s = check_layer_pointers(st->c, layers);

@@ -197,3 +197,41 @@ def test_inputs_module():
     assert set(np.unique(p)) == {0, 1, 2}
     assert abs(syn.CONFIGS["C2"].model_flops() - 2.010e12) / 2.010e12 < 2e-3
     assert abs(syn.CONFIGS["C3"].model_flops() - 6.362e12) / 6.362e12 < 2e-3
+
+
+@pytest.mark.parametrize("style", ["pre", "post"])
+def test_relu_with_decisions_given_from_outside(style):
+    """The test-only switch that lets a ReLU stage use decisions x > 0 taken elsewhere: with the stage's own
+    decisions nothing changes (bit for bit); with some of them flipped the stage computes x -> x [given], a smooth
+    function of its inputs, and its gradients are the derivatives of exactly that function (central differences)."""
+    cfg, st, w, x, dy = tiny(style, False, "relu")
+    y0, dx0, g0 = O.stage_step(st, w, x, dy)
+    own, h_in = [], x
+    for l in range(cfg.n_layers):
+        h_in, saved = st.layer_fwd(h_in, w[l], l)
+        own.append(saved["FC1_OUT"] > 0)
+    st.relu_decisions = own
+    y1, dx1, g1 = O.stage_step(st, w, x, dy)
+    assert np.array_equal(y0, y1) and np.array_equal(dx0, dx1)
+    assert all(np.array_equal(g0[l][n], g1[l][n]) for l in range(cfg.n_layers) for n in syn.WEIGHT_NAMES)
+    rng = np.random.default_rng(3)
+    flipped = [d ^ (rng.random(d.shape) < 0.1) for d in own]
+    assert any((a != b).any() for a, b in zip(own, flipped))
+    st.relu_decisions = flipped
+    y2, dx2, g2 = O.stage_step(st, w, x, dy)
+    assert not np.array_equal(y0, y2)
+    hh = 1e-6
+
+    def loss(ws, xx):
+        return float((O.stage_forward(st, ws, xx) * dy).sum())
+
+    u = rng.normal(size=x.shape)
+    fd = (loss(w, x + hh * u) - loss(w, x - hh * u)) / (2 * hh)
+    assert np.isclose(fd, (dx2 * u).sum(), rtol=2e-6, atol=1e-7)
+    for name in ("w_fc1", "b_fc1", "w_fc2", "ln1_g", "w_qkv"):
+        u = rng.normal(size=w[0][name].shape)
+        wp = [dict(d) for d in w]; wm = [dict(d) for d in w]
+        wp[0][name] = w[0][name] + hh * u
+        wm[0][name] = w[0][name] - hh * u
+        fd = (loss(wp, x) - loss(wm, x)) / (2 * hh)
+        assert np.isclose(fd, float((g2[0][name] * u).sum()), rtol=2e-6, atol=1e-7), name

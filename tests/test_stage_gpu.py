@@ -213,3 +213,44 @@ def test_forty_seeded_plans_give_the_same_bits_inside_their_validated_memory(sty
         assert stats["n_replayed_ops"] == rep["n_replayed_ops"], seed
     assert len(seen) == 40
     run.close()
+
+
+@pytest.mark.parametrize("style", ["pre", "post"])
+def test_relu_in_bf16_gradients_under_the_stage_own_decisions(style):
+    """ReLU's derivative reads the sign of a stored tensor, and in bf16 the two sides store values one rounding
+    apart, so a few elements decide differently and the plain comparison of gradients has no meaning (see
+    relu_in_bf16).  Here the decisions are taken out of the comparison instead of the gradients: the forward
+    runs, FC1_OUT of every layer is read back as the stage stored it (dp_stage_read_saved), the oracle is given
+    those decisions x > 0, and then Y, dX and every weight gradient are held to the bf16 bound."""
+    from paper_2505_05856_amd.harness import ScheduleRunner
+    cfg = syn.StageConfig(2, 128, 2, 256, 96, 2, style, False, "relu", "bf16")
+    w, x, dy = make(cfg)
+    run = ScheduleRunner(cfg, w, [x], [dy])
+    run.poison_outputs()
+    run.forward(0, 1, syn.plan_keep_all(cfg))
+    decisions, differ = [], 0
+    st = O.Stage(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.ffn, cfg.seq, cfg.micro_batch, cfg.norm_style,
+                 cfg.causal, cfg.gelu, cfg.ln_eps, norm=cfg.norm)
+    for l in range(cfg.n_layers):
+        f = torch.empty(cfg.micro_batch * cfg.seq, cfg.ffn, dtype=torch.bfloat16, device="cuda:0")
+        B.stage_read_saved(run.stage, run.slot_of[0], l, syn.SLOT["FC1_OUT"], f)
+        torch.cuda.synchronize()
+        decisions.append(f.float().cpu().numpy() > 0)
+    # a tensor the plan does not keep is refused, as is a wrong size
+    code = B.lib().dp_stage_read_saved(run.stage.handle, run.slot_of[0], 0, syn.SLOT["FC1_OUT"], f.data_ptr(), 16, None)
+    assert B.STATUS[code] == "DP_E_INVAL"
+    run.backward(0, accumulate=False)
+    ys, dxs, g = run.results()
+    run.close()
+    own = O.stage_step(st, w, x, dy)
+    st.relu_decisions = decisions
+    ref = O.stage_step(st, w, x, dy)
+    worst = {"Y": O.max_rel_err(ys[0], ref[0]), "dX": O.max_rel_err(dxs[0], ref[1])}
+    for l in range(cfg.n_layers):
+        for n in syn.WEIGHT_NAMES:
+            worst[f"L{l}.{n}"] = O.max_rel_err(g[l][n], ref[2][l][n])
+    plain = max(O.max_rel_err(g[l][n], own[2][l][n]) for l in range(cfg.n_layers) for n in syn.WEIGHT_NAMES)
+    top = sorted(worst.items(), key=lambda kv: -kv[1])[:4]
+    print("with the stage's decisions:", ", ".join(f"{k}={v:.2e}" for k, v in top), "| plain comparison, worst gradient:", f"{plain:.2e}")
+    bad = {k: v for k, v in worst.items() if not (v <= BOUND["bf16"])}
+    assert not bad, bad
