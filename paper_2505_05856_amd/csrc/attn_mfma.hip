@@ -425,30 +425,6 @@ hipError_t fwd_launch(int B, int nh, int causal, const AttnView &av, void *o, fl
 }
 
 // ------------------------------------------------------------------ backward
-// D[b,h,i] = <dO_i, O_i> over the head's DH columns; one thread per 8 columns.
-template <int DH>
-__global__ __launch_bounds__(256) void attn_rowdot_kernel(const bf16 *__restrict__ o, const bf16 *__restrict__ d_o,
-                                                          float *__restrict__ drow, long T, int S, int nh) {
-  const long c = (long)blockIdx.x * 256 + threadIdx.x;   // chunk of 8 columns
-  const int cpr = nh * DH / 8;                           // chunks per row
-  const bool ok = c < T * cpr;
-  float sum = 0.f;
-  if (ok) {
-    float a[8], g[8];
-    load8(o + c * 8, a);
-    load8(d_o + c * 8, g);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) sum += a[i] * g[i];
-  }
-#pragma unroll
-  for (int m = 1; m < DH / 8; m <<= 1) sum += __shfl_xor(sum, m, 64);
-  if (ok && (c % (DH / 8)) == 0) {
-    const long t = c / cpr;
-    const int h = (int)(c % cpr) / (DH / 8);
-    drow[((t / S) * nh + h) * S + (t % S)] = sum;
-  }
-}
-
 // dK, dV: the block owns 128 keys (32 per wave) and streams 64-query tiles of Q and dO.
 // (head dimension 128: both accumulators and both key-side fragments need more than the 256
 // registers two blocks a CU leave each wave, and spills on this path cost more than the
@@ -651,12 +627,15 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
     }
 }
 
-// dQ: the block owns 128 queries (32 per wave) and streams 64-key tiles of K and V.
+// dQ: the block owns 128 queries (32 per wave) and streams 64-key tiles of K and V.  It also takes
+// D_i = <dO_i, O_i> over the head's columns for its queries (a lane holds half of dO_i as MFMA
+// operand already) and leaves it in drow[b, h, i] for the dK/dV kernel, which is launched after it.
 template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
                                                              const float *__restrict__ lse,
+                                                             const bf16 *__restrict__ o,
                                                              const bf16 *__restrict__ d_o,
-                                                             const float *__restrict__ drow,
+                                                             float *__restrict__ drow,
                                                              int nh, float scale, DropArgs da) {
   constexpr int ND = DH / 32, NK = DH / 16;
   // LDS, in bytes: [stage 0: K, V][stage 1: K, V], every tile in the dual-use layout
@@ -678,17 +657,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
   const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
   const float c = scale * kLog2e;
 
+  const bf16 *ob = o + (long)b * Sq * H + (long)h * DH;
   bf16x8 qf[NK], gf[NK];
+  float dsum = 0.f;
 #pragma unroll
   for (int kd = 0; kd < NK; ++kd) {
     const uint4 z = make_uint4(0, 0, 0, 0);
     qf[kd] = as_frag(qi < Sq ? ld16(qb + (long)qi * ldq + kd * 16 + 8 * hh) : z);
     gf[kd] = as_frag(qi < Sq ? ld16(dob + (long)qi * H + kd * 16 + 8 * hh) : z);
+    const bf16x8 of = as_frag(qi < Sq ? ld16(ob + (long)qi * H + kd * 16 + 8 * hh) : z);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dsum += (float)of[i] * (float)gf[kd][i];
   }
+  const float dq_i = dsum + __shfl_xor(dsum, 32, 64);   // the two halves of the row
+  if (qi < Sq && hh == 0) drow[((long)b * nh + h) * Sq + qi] = dq_i;
   const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
   const uint32_t qidx = (uint32_t)qi * (uint32_t)S;
   const float lq = qi < Sq ? lse[((long)b * nh + h) * Sq + qi] * kLog2e : INFINITY;
-  const float dq_i = qi < Sq ? drow[((long)b * nh + h) * Sq + qi] : 0.f;
 
   f32x16 dq[ND];
 #pragma unroll
@@ -838,28 +823,21 @@ hipError_t bwd_launch(int B, int nh, int causal, const AttnView &av, const void 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const long T = (long)B * av.Sq;
-  const long chunks = T * nh * DH / 8;
   hipError_t e = hipSuccess;
-  if (chunks > 0) {
-    hipLaunchKernelGGL((attn_rowdot_kernel<DH>), dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
-                       (const bf16 *)o, (const bf16 *)d_o, ws, T, av.Sq, nh);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   const dim3 grid_q(((av.Sq + BROWS - 1) / BROWS) * nh * B), grid_k(((av.Sk + BROWS - 1) / BROWS) * nh * B), block(256);
   const float scale = 1.0f / sqrtf((float)DH);
   const bool dropping = drop != nullptr && drop->thr != 0;
   const DropArgs da = dropping ? *drop : DropArgs{0u, 0u, 1.f};
-#define DP_BWD(KERN, GRID, SMEM)                                                                        \
-  hipLaunchKernelGGL(KERN, GRID, block, SMEM, s, av, lse, (const bf16 *)d_o, (const float *)ws, nh, scale, da)
-#define DP_BWD4(NAME, GRID, SMEM)                                                                       \
-  if (dropping) { if (causal) DP_BWD((NAME<DH, true, true>), GRID, SMEM); else DP_BWD((NAME<DH, false, true>), GRID, SMEM); } \
-  else { if (causal) DP_BWD((NAME<DH, true, false>), GRID, SMEM); else DP_BWD((NAME<DH, false, false>), GRID, SMEM); }
-  if (av.Sk > 0) { DP_BWD4(attn_bwd_dkv_kernel, grid_k, smem_kv) }   // (no queries: dK = dV = 0 is still written)
+#define DP_BWD(KERN, GRID, SMEM, ...)                                                                   \
+  hipLaunchKernelGGL(KERN, GRID, block, SMEM, s, av, lse, __VA_ARGS__ (const bf16 *)d_o, ws, nh, scale, da)
+#define DP_BWD4(NAME, GRID, SMEM, ...)                                                                  \
+  if (dropping) { if (causal) DP_BWD((NAME<DH, true, true>), GRID, SMEM, __VA_ARGS__); else DP_BWD((NAME<DH, false, true>), GRID, SMEM, __VA_ARGS__); } \
+  else { if (causal) DP_BWD((NAME<DH, true, false>), GRID, SMEM, __VA_ARGS__); else DP_BWD((NAME<DH, false, false>), GRID, SMEM, __VA_ARGS__); }
+  // dQ first: it leaves the row dots <dO_i, O_i> in `ws`, which the dK/dV kernel reads
+  if (av.Sq > 0 && av.Sk > 0) { DP_BWD4(attn_bwd_dq_kernel, grid_q, smem_q, (const bf16 *)o,) }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (av.Sq > 0 && av.Sk > 0) { DP_BWD4(attn_bwd_dq_kernel, grid_q, smem_q) }
+  if (av.Sk > 0) { DP_BWD4(attn_bwd_dkv_kernel, grid_k, smem_kv, ) }   // (no queries: dK = dV = 0 is still written)
 #undef DP_BWD4
 #undef DP_BWD
   return hipGetLastError();
