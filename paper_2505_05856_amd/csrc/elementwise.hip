@@ -78,7 +78,9 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, co
 // wave per row; writes dx and the block's partial row (dgamma | dbeta [| colsum(dx)])
 // into part[b][NV*cols], NV = 3 with SUMDX (the column sums of the stored dx are the
 // bias gradient of the linear layer that produced LayerNorm's input).
-template <typename T, int NC, bool SUMDX>
+// AHEAD: a wave asks for its next row while it works on the current one (pays when a wave has
+// several rows; with two rows a wave the registers it takes cost more than it returns).
+template <typename T, int NC, bool SUMDX, bool AHEAD>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx */, const T *__restrict__ x,
                                                      const float *__restrict__ stats, const T *__restrict__ gamma,
                                                      const T *__restrict__ dres, T *dx,
@@ -100,7 +102,92 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *dy /* may alias dx
   // accumulators alone take 16..24 registers per 512 columns, and occupancy is what hides
   // the latency (measured: 4096 columns 1.6 instead of 2.0 ms for the 8 launches of a step;
   // 1024 and 1600 columns the other way round).  Same arithmetic, same order, either way.
-  if constexpr (NC <= 4) {
+  if constexpr (NC <= 4 && AHEAD) {
+    // Everything a row needs from memory (x, dy, its statistics, the residual gradient) is asked
+    // for while the row before it is being worked on and waits in registers as loaded, so a row
+    // costs the wave one trip to memory that overlaps the previous row's work, instead of two in
+    // a row (inputs, then the residual gradient).  gamma stays in registers for all rows.
+    Raw8<T> xr[NC], dr[NC], rr[NC], gr[NC];
+    float mean_n = 0.f, rstd_n = 0.f;
+    auto fetch = [&](int row) {
+      if (row >= row_end) return;
+      const size_t base = (size_t)row * cols;
+      mean_n = stats[2 * (size_t)row];
+      rstd_n = stats[2 * (size_t)row + 1];
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          xr[c].load(x + base + col);
+          dr[c].load(dy + base + col);
+        }
+      }
+    };
+    auto fetch_res = [&](int row) {   // (after the row before it has used its own: one buffer does)
+      if (dres == nullptr || row >= row_end) return;
+      const size_t base = (size_t)row * cols;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) rr[c].load(dres + base + col);
+      }
+    };
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int col = (c * 64 + lane) * 8;
+      if (col < cols) gr[c].load(gamma + col);
+    }
+    fetch(blockIdx.x * rpb + wave);
+    fetch_res(blockIdx.x * rpb + wave);
+    for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
+      const float mean = mean_n, rstd = rstd_n;
+      const size_t base = (size_t)row * cols;
+      float xh[NC][8], g[NC][8];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          float d[8], gm[8];
+          xr[c].unpack(xh[c]);
+          dr[c].unpack(d);
+          gr[c].unpack(gm);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            xh[c][i] = (xh[c][i] - mean) * rstd;
+            dg[c][i] += d[i] * xh[c][i];
+            db[c][i] += d[i];
+            g[c][i] = d[i] * gm[i];
+            s1 += g[c][i];
+            s2 += g[c][i] * xh[c][i];
+          }
+        }
+      }
+      fetch(row + 4);   // the wave's next row (another row of dy: the store below cannot touch it)
+      const float m1 = rms ? 0.f : wave_sum(s1) * inv_n, m2 = wave_sum(s2) * inv_n;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = (c * 64 + lane) * 8;
+        if (col < cols) {
+          float o[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = rstd * (g[c][i] - m1 - xh[c][i] * m2);
+          if (dres != nullptr) {
+            float r[8];
+            rr[c].unpack(r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] += r[i];
+          }
+          store8(dx + base + col, o);
+          if (SUMDX) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ds[c][i] += (float)(T)o[i];   // the value as stored
+          }
+        }
+      }
+      fetch_res(row + 4);
+    }
+  } else if constexpr (NC <= 4) {
     for (int row = blockIdx.x * rpb + wave; row < row_end; row += 4) {
       const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
       const size_t base = (size_t)row * cols;
@@ -629,9 +716,13 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
   const int nb = row_blocks(rows, 8, &rpb);
   const int nv = SUMDX ? 3 : 2;
   float *part = (float *)ws;
-#define DP_LN_BWD(NC)                                                                                       \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NC, SUMDX>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, \
+#define DP_LN_BWD_AS(NC, AHEAD)                                                                                    \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NC, SUMDX, AHEAD>), dim3(nb), dim3(256), 0, s, (const T *)dy, (const T *)x, \
                      stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb, rms)
+#define DP_LN_BWD(NC)                                                               \
+  do {                                                                              \
+    if (NC <= 2 || rpb >= 16) DP_LN_BWD_AS(NC, true); else DP_LN_BWD_AS(NC, false);               \
+  } while (0)
 #define DP_LN_BWD_WIDE_AS(NP, FULL, RES)                                                                      \
   hipLaunchKernelGGL((ln_bwd_wide_kernel<T, NP, SUMDX, FULL, RES>), dim3(nb), dim3(256), 0, s, (const T *)dy, \
                      (const T *)x, stats, (const T *)gamma, (const T *)dres, (T *)dx, part, rows, cols, rpb, rms)
@@ -651,6 +742,7 @@ static hipError_t ln_bwd_t(int rows, int cols, const void *dy, const void *x, co
 #undef DP_LN_BWD_WIDE
 #undef DP_LN_BWD_WIDE_AS
 #undef DP_LN_BWD
+#undef DP_LN_BWD_AS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return reduce_or_defer<T>(part, nb, nv * cols, cols, dgamma, dbeta, dxsum, s, job);
