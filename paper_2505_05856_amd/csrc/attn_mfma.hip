@@ -40,25 +40,6 @@ __device__ __forceinline__ bf16x8 as_frag(uint4 v) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// 32 x 16 operand fragment with the contraction along a row of a [rows][stride] LDS tile.
-__device__ __forceinline__ bf16x8 frag_rows(const bf16 *lds, int stride, int row0, int k0, int lane) {
-  return *reinterpret_cast<const bf16x8 *>(lds + (row0 + (lane & 31)) * stride + k0 + 8 * (lane >> 5));
-}
-
-// 32 x 16 operand fragment with the contraction DOWN the rows of a [rows][stride] tile:
-// lane l gets column col0 + l%32 for the 8 rows
-//   r0 + 4*(l/32) + {0,1,2,3}  and  r0 + 8 + 4*(l/32) + {0,1,2,3},
-// which is the order in which a 32x32 MFMA result holds 16 consecutive rows
-// (elements e = 0..7) of one column, so products of MFMA results need no shuffling.
-__device__ __forceinline__ bf16x8 frag_cols(const bf16 *lds, int stride, int r0, int col0, int lane) {
-  const int i = lane & 15;
-  const bf16 *p = lds + (r0 + 4 * (lane >> 5) + (i >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
-  union { s16x4 h[2]; bf16x8 v; } u;
-  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * stride));
-  return u.v;
-}
-
 // elements e0..e0+7 of an MFMA result as a bf16 operand fragment
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &v, int e0) {
   bf16x8 r;
@@ -79,25 +60,6 @@ __device__ __forceinline__ int xcd_contiguous(int pid, int n) {
 // Row index, inside its 32-row block, of element e of a 32x32 MFMA result held by `lane`.
 __device__ __forceinline__ int acc_row(int e, int lane) { return 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3); }
 
-// Cooperative global -> register -> LDS copy of a [64][DH] tile (rows beyond `nrows` read as zero).
-template <int DH>
-__device__ __forceinline__ void tile_load(uint4 (&st)[DH / 32], const bf16 *__restrict__ src, long ld, int row0,
-                                          int nrows, int tid) {
-#pragma unroll
-  for (int i = 0; i < DH / 32; ++i) {
-    const int c = tid + i * 256, r = c / (DH / 8), k = (c % (DH / 8)) * 8;
-    st[i] = (row0 + r < nrows) ? ld16(src + (long)(row0 + r) * ld + k) : make_uint4(0, 0, 0, 0);
-  }
-}
-template <int DH>
-__device__ __forceinline__ void tile_store(bf16 *lds, int stride, const uint4 (&st)[DH / 32], int tid) {
-#pragma unroll
-  for (int i = 0; i < DH / 32; ++i) {
-    const int c = tid + i * 256, r = c / (DH / 8), k = (c % (DH / 8)) * 8;
-    *reinterpret_cast<uint4 *>(lds + r * stride + k) = st[i];
-  }
-}
-
 // ---- K/V (or Q/dO) tiles brought into LDS by the load unit itself ------------------------
 // One request: lane l fetches 16 bytes from uniform_base + byte_off and the unit stores them at
 // LDS byte lds_base + 16*l (global_load_lds_dwordx4): no staging registers, no LDS store
@@ -117,7 +79,7 @@ __device__ __forceinline__ const char *uniform_ptr(const char *p) {
 }
 
 // A [64 rows][DH] tile in LDS, laid out for fragments whose contraction runs ALONG a row
-// (frag_rows): DH/64 half-tiles of [64][64] with unpadded 128-byte rows; 16-byte chunk c of
+// (frag_rows_sw): DH/64 half-tiles of [64][64] with unpadded 128-byte rows; 16-byte chunk c of
 // row r sits at chunk position c ^ ((r >> 1) & 7), which spreads the 16 rows one fragment read
 // phase touches over all banks.  The load unit writes 1 KB of consecutive LDS a request, so a
 // lane fetches the global chunk that belongs at its LDS position: request q of the tile is rows
@@ -144,7 +106,7 @@ __device__ __forceinline__ bf16x8 frag_rows_sw(const unsigned char *tile, int ro
 }
 
 // The same tile laid out as loaded, [64 rows][DH * 2 bytes], for fragments whose contraction
-// runs DOWN the rows (frag_cols, through the transpose read, which touches four consecutive
+// runs DOWN the rows (through the transpose read, which touches four consecutive
 // rows x 64 bytes per 16 lanes): chunk c of row r sits at c ^ swz(r), swz = (r & 3) << 2 for
 // 256-byte rows (the four rows land in the four 64-byte quarters of the bank period) and
 // ((r >> 1) & 1) << 2 for 128-byte rows (rows r and r+2 swap 64-byte halves).
@@ -231,13 +193,13 @@ struct BothAddr {
   // 32 rows from row0 (a multiple of 16) of the tile at byte `tile_off` of the stage, contraction elements 16 kd ..
   // (tile_off, row0, r0, kd, d: constants once the callers' loops are unrolled)
   __device__ __forceinline__ bf16x8 rows(unsigned tile_off, int row0, int kd) const {
-    return *(const lds_bf16x8 *)(row[kd] + tile_off + (unsigned)row0 * ROWB);
+    return *(const lds_bf16x8 *)(uintptr_t)(row[kd] + tile_off + (unsigned)row0 * ROWB);
   }
   // column 32 d + lane % 32 for the rows r0 + 4 * (lane / 32) + {0,1,2,3} and those 8 further; r0 a multiple of 16
   __device__ __forceinline__ bf16x8 cols(unsigned tile_off, int r0, int d) const {
     union { s16x4 h[2]; bf16x8 v; } u;
-    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(col[0][d] + tile_off + (unsigned)r0 * ROWB));
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(col[1][d] + tile_off + (unsigned)r0 * ROWB));
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(uintptr_t)(col[0][d] + tile_off + (unsigned)r0 * ROWB));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(uintptr_t)(col[1][d] + tile_off + (unsigned)r0 * ROWB));
     return u.v;
   }
 };
