@@ -485,9 +485,10 @@ hipError_t launch_dma_mode(const GemmArgs &a, hipStream_t s) {
 
   }
   // 256x256 (8 waves, 64x128 a wave, ring of five operand tiles) halves the L1 traffic per
-  // flop of 128x128 and wins as soon as it gives most CUs a workgroup; below that 128x128
-  // with 8 waves and a four-stage ring.
-  if (big_ok && a.K >= 192 && tiles(256, 256) >= 190) return launch_dma_cfg<256, 256, 4, 2, 2, TN, 64, true>(a, s);
+  // flop of 128x128 and wins as soon as it gives two thirds of the CUs a workgroup (measured:
+  // 175 tiles, the [1600 x 6400] weight gradients, 10-20 % faster than 650 tiles of 128x128;
+  // 133 and 112 tiles slower); below that 128x128 with 8 waves and a four-stage ring.
+  if (big_ok && a.K >= 192 && tiles(256, 256) >= 170) return launch_dma_cfg<256, 256, 4, 2, 2, TN, 64, true>(a, s);
   // a small output with a long contraction (the out-projection weight gradient) leaves most
   // CUs without a 128x128 tile: 64x64 tiles, several workgroups a CU, then run faster
   if (tiles(128, 128) <= 96) return launch_dma_cfg<64, 64, 2, 2, 8, TN>(a, s);
