@@ -184,12 +184,15 @@ struct BothAddr {
       col[1][d] = (rc + 8u) * ROWB + (((4u * d + cl) ^ swz_both<DH>(rc + 8u)) << 4) + (i & 1u) * 8u;
     }
   }
-  __device__ __forceinline__ void flip(unsigned stage_bytes) {
+  __device__ __forceinline__ void flip_rows(unsigned stage_bytes) {
 #pragma unroll
     for (int kd = 0; kd < DH / 16; ++kd) row[kd] ^= stage_bytes;
+  }
+  __device__ __forceinline__ void flip_cols(unsigned stage_bytes) {
 #pragma unroll
     for (int d = 0; d < DH / 32; ++d) { col[0][d] ^= stage_bytes; col[1][d] ^= stage_bytes; }
   }
+  __device__ __forceinline__ void flip(unsigned stage_bytes) { flip_rows(stage_bytes); flip_cols(stage_bytes); }
   // 32 rows from row0 (a multiple of 16) of the tile at byte `tile_off` of the stage, contraction elements 16 kd ..
   // (tile_off, row0, r0, kd, d: constants once the callers' loops are unrolled)
   __device__ __forceinline__ bf16x8 rows(unsigned tile_off, int row0, int kd) const {
@@ -208,12 +211,13 @@ struct BothAddr {
 // DROP: the probabilities are masked after the softmax (the row sums and the log-sum-exp are
 // those of the plain softmax); the scale 1/(1-p) goes into the final normalisation.
 template <int DH, bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_mfma_kernel(AttnView av, bf16 *__restrict__ o,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16 *__restrict__ o,
                                                                float *__restrict__ lse, int nh, float scale,
                                                                DropArgs da) {
   constexpr int ND = DH / 32, NK = DH / 16;
-  // a stage: the K tile in the row-fragment layout, then the V tile in the column-fragment layout
-  constexpr unsigned TILE = BKV * DH * 2, STAGE = 2 * TILE;
+  // LDS, in bytes: [K even][K odd][V even][V odd], every tile in the dual-use layout; tile t of K
+  // (of V) lives in the buffer of t's parity
+  constexpr unsigned TILE = BKV * DH * 2, VOFF = 2 * TILE;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_b[];
 
   const int Sq = av.Sq, S = av.Sk;   // S: the key count, which bounds every key-side loop below
@@ -237,11 +241,13 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
   int nkv = (S + BKV - 1) / BKV;
   if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
 
-  // the first K/V tile is on its way while the queries are fetched
-  if (nkv > 0) {
-    dma_tile_rows<DH>(0u, kb, ldb, 0, S, wave, lane);
-    dma_tile_cols<DH>(TILE, vb, ldb, 0, S, wave, lane);
-  }
+  // The K stream runs one tile ahead of the V stream (the logits of tile t+1 are taken while the
+  // softmax of tile t is worked out): K tiles 0 and 1 and V tile 0 are on their way while the
+  // queries are fetched.
+  auto fetch_k = [&](int t) { dma_tile_both<DH>((unsigned)(t & 1) * TILE, kb, ldb, t * BKV, S, wave, lane); };
+  auto fetch_v = [&](int t) { dma_tile_both<DH>(VOFF + (unsigned)(t & 1) * TILE, vb, ldb, t * BKV, S, wave, lane); };
+  if (nkv > 0) { fetch_k(0); fetch_v(0); }
+  if (nkv > 1) fetch_k(1);
 
   bf16x8 qf[NK];
 #pragma unroll
@@ -255,89 +261,143 @@ __global__ __launch_bounds__(256, (DH == 128 && !CAUSAL) ? 1 : 2) void attn_fwd_
     for (int e = 0; e < 16; ++e) acc[d][e] = 0.f;
   float m = -1e30f, l = 0.f;   // m: running maximum of the scaled logits (log2 domain)
 
+  BothAddr<DH> at;
+  at.init(lane);
   wait_dma();
   __syncthreads();
 
-  for (int t = 0; t < nkv; ++t) {
-    const unsigned cur = (unsigned)(t & 1) * STAGE, nxt = STAGE - cur;
+  // A wave runs a software pipeline of four stages a tile, so that the softmax arithmetic issues
+  // beside the MFMAs instead of between them, a quarter of it in every stage (A, B: the two 32-key
+  // sub-tiles of tile t; halves: 16 keys each):
+  //   1: S of tile t+1, first half of the contraction (A and B: two independent chains)
+  //        beside  P of the first half of A = exp2(logits - maximum), row sums
+  //   2: S of tile t+1, second half       beside  P of the second half of A
+  //   3: O += P_A V_A                      beside  P of the first half of B, maximum over S_A of tile t+1
+  //   4: O += P_B V_B                      beside  P of the second half of B (within the first half
+  //                                                of the stage), maximum over S_B of tile t+1
+  // and the running maximum for tile t+1 (with the rescaling of the accumulators if it moved) at
+  // the head of the next tile.  Every step reads the operand fragments of the step after it;
+  // scheduling fences keep the steps in this order; the code of a tile has no branch inside a
+  // stage (MORE = a next tile exists).  (A wave whose queries see no key of the block's last tile
+  // runs it all the same, every logit masked: it would wait for the other waves at the tile
+  // barrier anyway.)
+  bf16x8 fx[2];                  // fragment double buffer
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  auto ld_k = [&](int slot, int sub, int kd) { fx[slot] = at.rows(0u, sub * 32, kd); };
+  auto ld_v = [&](int slot, int sub, int j) { fx[slot] = at.cols(VOFF, sub * 32 + (j / ND) * 16, j % ND); };
+  auto zero = [](f32x16 &v) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = 0.f;
+  };
+  // keys past the end and keys the causal mask hides, on the tiles that have any: -inf, P = 0
+  auto mask = [&](f32x16 (&sv)[2], int j0) {
+    if (j0 + BKV > S || (CAUSAL && j0 + BKV - 1 > iw0)) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int lim = (CAUSAL ? min(S, qi + 1) : S) - j0 - 32 * sub - 4 * hh;   // the lane's first hidden row
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (8 * (e >> 2) + (e & 3) >= lim) sv[sub][e] = -INFINITY;
+      }
+    }
+  };
+  f32x16 cur[2], nxt[2];   // raw logits of tile t, of tile t+1
+  float mx = -INFINITY;    // maximum over the raw logits of the tile about to be worked on (this lane's keys)
+
+  auto tile = [&](int t, auto more_tag) {
+    constexpr bool MORE = decltype(more_tag)::value;
     const int j0 = t * BKV;
-    // the next tile goes into the other stage, which every wave left at the barrier below
-    if (t + 1 < nkv) {
-      dma_tile_rows<DH>(nxt, kb, ldb, j0 + BKV, S, wave, lane);
-      dma_tile_cols<DH>(nxt + TILE, vb, ldb, j0 + BKV, S, wave, lane);
+    // (every wave left the buffers these go to at the barrier that ended the last tile)
+    if (t + 2 < nkv) fetch_k(t + 2);
+    if (MORE) fetch_v(t + 1);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx * c);   // (the scale c > 0 is folded into the exponent below)
+    // the running maximum moves in the first tiles and then hardly ever: skip the rescaling
+    // of the accumulators when it stayed put for every query of the wave
+    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+      const float alpha = fast_exp2(m - m_new);
+      l *= alpha;
+#pragma unroll
+      for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[d][e] *= alpha;
+      m = m_new;
     }
-    const unsigned char *kt = smem_b + cur, *vt = smem_b + cur + TILE;
-    if (!CAUSAL || j0 <= iw0 + 31) {
-      // MASK = false: every key of the tile exists and is visible to every query of the wave,
-      // so the per-element bounds and causal tests (a third of the softmax instructions) go
-      auto tile = [&](auto mask_tag) {
-        constexpr bool MASK = decltype(mask_tag)::value;
-        f32x16 s[2];
-        float mx = -INFINITY;   // of the raw logits; the scale c > 0 is folded into the exponent below
+    mx = -INFINITY;
+    float ps = 0.f;
+    // elements e0 .. e0+n-1 of a sub-tile: logits -> P (masked by dropout after the row sum)
+    auto soft = [&](f32x16 &sv, int sub, int e0, int n) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
+      for (int u = 0; u < n; ++u) {
+        const int e = e0 + u;
+        const float pr = fast_exp2(__builtin_fmaf(sv[e], c, -m));
+        ps += pr;
+        sv[e] = (DROP && drop_bits(qidx + (uint32_t)(j0 + sub * 32 + acc_row(e, lane)), keys.k0, keys.k1) < da.thr)
+                    ? 0.f : pr;
+      }
+    };
+    auto vmax = [&](const f32x16 &sv, int e0, int n) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e) s[sub][e] = 0.f;
+      for (int u = 0; u < n; ++u) mx = fmaxf(mx, sv[e0 + u]);
+    };
+    // stages 1 and 2: NK steps of two MFMAs, 16 / NK elements of P_A a step
+    if (MORE) { zero(nxt[0]); zero(nxt[1]); ld_k(0, 0, 0); ld_k(1, 1, 0); }
 #pragma unroll
-          for (int kd = 0; kd < NK; ++kd)
-            s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_sw(kt, sub * 32, kd * 16, lane), qf[kd],
-                                                             s[sub], 0, 0, 0);
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            if (MASK) {
-              const int j = j0 + sub * 32 + acc_row(e, lane);
-              if (j >= S || (CAUSAL && j > qi)) s[sub][e] = -INFINITY;
-            }
-            mx = fmaxf(mx, s[sub][e]);
-          }
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx * c);
-        // the running maximum moves in the first tiles and then hardly ever: skip the rescaling
-        // of the accumulators when it stayed put for every query of the wave
-        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
-          const float alpha = fast_exp2(m - m_new);
-          l *= alpha;
-#pragma unroll
-          for (int d = 0; d < ND; ++d)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[d][e] *= alpha;
-          m = m_new;
-        }
-        float ps = 0.f;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            s[sub][e] = fast_exp2(__builtin_fmaf(s[sub][e], c, -m));
-            ps += s[sub][e];
-          }
-        l += ps;
-        if (DROP) {
-#pragma unroll
-          for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-              if (drop_bits(qidx + (uint32_t)(j0 + sub * 32 + acc_row(e, lane)), keys.k0, keys.k1) < da.thr)
-                s[sub][e] = 0.f;
-        }
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            const bf16x8 pf = pack8(s[sub], half * 8);
-#pragma unroll
-            for (int d = 0; d < ND; ++d)
-              acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  frag_cols_sw<DH>(vt, sub * 32 + half * 16, d * 32, lane), pf, acc[d], 0, 0, 0);
-          }
-      };
-      const bool interior = j0 + BKV <= S && (!CAUSAL || j0 + BKV - 1 <= iw0);
-      if (interior) tile(std::false_type{}); else tile(std::true_type{});
+    for (int kd = 0; kd < NK; ++kd) {
+      if (MORE) {
+        const bf16x8 ka = fx[0], kb2 = fx[1];
+        if (kd + 1 < NK) { ld_k(0, 0, kd + 1); ld_k(1, 1, kd + 1); }
+        nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kd], nxt[0], 0, 0, 0);
+        nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb2, qf[kd], nxt[1], 0, 0, 0);
+      }
+      soft(cur[0], 0, kd * (16 / NK), 16 / NK);
+      fence();
     }
-    wait_dma();        // this wave's part of the next tile is in
-    __syncthreads();   // everyone's is, and everyone is done with this tile
+    if (MORE) mask(nxt, j0 + BKV);
+    bf16x8 pf[2];
+    pf[0] = pack8(cur[0], 0); pf[1] = pack8(cur[0], 8);
+    ld_v(0, 0, 0);
+    // stage 3: NK steps of one MFMA; 8 / NK elements of P_B and 16 / NK of the next maximum a step
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      if (j + 1 < NK) ld_v((j + 1) & 1, 0, j + 1); else ld_v((j + 1) & 1, 1, 0);
+      acc[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], acc[j % ND], 0, 0, 0);
+      if ((j * 8) % NK == 0) soft(cur[1], 1, j * 8 / NK, 8 / NK >= 1 ? 8 / NK : 1);
+      if (MORE) vmax(nxt[0], j * (16 / NK), 16 / NK);
+      fence();
+    }
+    pf[0] = pack8(cur[1], 0);
+    // stage 4: the second half of P_B within the first half of the stage, then the rest of the maximum
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      if (j + 1 < NK) ld_v((j + 1) & 1, 1, j + 1);
+      if (j == ND) pf[1] = pack8(cur[1], 8);
+      acc[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], acc[j % ND], 0, 0, 0);
+      if (j < ND) soft(cur[1], 1, 8 + j * (8 / ND), 8 / ND);
+      else if (MORE) vmax(nxt[1], (j - ND) * (16 / ND), 16 / ND);
+      fence();
+    }
+    l += ps;
+    if (MORE) { cur[0] = nxt[0]; cur[1] = nxt[1]; }
+    at.flip(TILE);
+    wait_dma();        // this wave's parts of the tiles on their way are in
+    __syncthreads();   // everyone's are, and everyone is done with this tile's
+  };
+
+  if (nkv > 0) {   // the logits of tile 0 and their maximum
+    zero(cur[0]); zero(cur[1]);
+#pragma unroll
+    for (int kd = 0; kd < NK; ++kd) {
+      cur[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at.rows(0u, 0, kd), qf[kd], cur[0], 0, 0, 0);
+      cur[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at.rows(0u, 32, kd), qf[kd], cur[1], 0, 0, 0);
+    }
+    mask(cur, 0);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, fmaxf(cur[0][e], cur[1][e]));
+    at.flip_rows(TILE);   // the K fragments run one tile ahead of the V fragments
   }
+  for (int t = 0; t + 1 < nkv; ++t) tile(t, std::true_type{});
+  if (nkv > 0) tile(nkv - 1, std::false_type{});
 
   l += __shfl_xor(l, 32, 64);
   if (qi >= Sq) return;
