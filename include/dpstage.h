@@ -215,8 +215,11 @@ size_t dp_plan_len(const dp_stage_config *cfg);
  * from the most generous policy down, and the first whose peak fits is taken:
  * swap-ins as many layers ahead as the stage is deep, then half as many, ...,
  * then one; for each distance, swapped-out blocks held back until the backward
- * has released them, then until the forward is over, then for ever shorter
- * spans, then not at all.  Computation then waits for the host link as little
+ * has released them and the copy-outs of all but the bottom layers queued only
+ * when the forward has been issued, in the order the backward asks for them;
+ * then the same with every copy-out queued as its tensor is produced; then
+ * blocks held until the forward is over, then for ever shorter spans, then not
+ * at all.  Computation then waits for the host link as little
  * as the memory allows.  dp_stage_step makes the same choice, so its arena has
  * exactly the validated size. */
 dp_status dp_plan_validate(const dp_stage_config *cfg, const uint8_t *plan, size_t plan_len,

@@ -370,8 +370,38 @@ struct Walk {
   hipStream_t d2hx = nullptr;
   bool use_express = false;
   int express_from = -1;   // -1: not worked out yet
-  bool on_express(int l) {
-    if (!use_express || d2hx == nullptr) return false;
+  bool on_express(int l) { return use_express && d2hx != nullptr && (defer_top ? deferred_layer(l) : top_layer(l)); }
+  // With room to keep their blocks until the forward is over (defer_top, the most generous
+  // policy), only the bottom layers' copy-outs are queued as their tensors are produced (they keep
+  // the link busy during the forward and are needed back last); those of the layers above, at
+  // most three quarters of the swapped bytes, are queued when the forward has been issued, on the
+  // second stream, in the order the backward will ask for them: topmost layer first, within a
+  // layer as the backward nodes first read them.  No tensor the backward needs early then waits on the
+  // link behind one it needs late.  (A block whose copy-out is queued late must not be handed on
+  // before that: the event its next user would wait for is not recorded yet.  Hence only under
+  // a policy that holds such blocks through the forward.)
+  bool defer_top = false;
+  struct Deferred { int l, slot, produced; };
+  std::vector<Deferred> deferred;
+  int defer_from = -1;
+  bool deferred_layer(int l) {
+    if (defer_from < 0) {
+      std::vector<uint64_t> per_layer((size_t)c.L, 0);
+      uint64_t total = 0;
+      for (int k = 0; k < c.L; ++k)
+        for (int slot = 0; slot < c.nslots; ++slot)
+          if (action(k, slot) == DP_SWAP) { per_layer[(size_t)k] += slot_bytes(c, slot); total += slot_bytes(c, slot); }
+      defer_from = c.L;
+      uint64_t sum = 0;
+      for (int k = c.L - 1; k >= 0; --k) {
+        if ((sum + per_layer[(size_t)k]) * 4 > total * 3) break;
+        sum += per_layer[(size_t)k];
+        defer_from = k;
+      }
+    }
+    return l >= defer_from;
+  }
+  bool top_layer(int l) {
     if (express_from < 0) {
       std::vector<uint64_t> per_layer((size_t)c.L, 0);
       uint64_t total = 0;
@@ -751,14 +781,37 @@ struct Walk {
 
   // ---- swap engine --------------------------------------------------------------
   void swap_out(int l, int slot) {
+    if (defer_top && deferred_layer(l)) {
+      int produced = -1;
+      if (live || cm) { produced = new_event(); record(produced, cs); }
+      deferred.push_back({l, slot, produced});
+      S(l, slot).where = ON_HOST;   // (nothing reads it before the backward; the block stays until copy_out)
+      return;
+    }
+    copy_out(l, slot, -1);
+  }
+  void flush_deferred() {   // at the end of the forward: in the order the backward first reads them
+    int rank[kMaxSlots];
+    for (int sl = 0; sl < kMaxSlots; ++sl) rank[sl] = kMaxSlots * 4;
+    const BwdReads *bwd = bwd_table(c);
+    int pos = 0;
+    for (int i = 0; i < n_ops(); ++i)
+      for (int k = 0; k < bwd[i].n; ++k, ++pos)
+        if (rank[bwd[i].slot[k]] > pos) rank[bwd[i].slot[k]] = pos;
+    std::stable_sort(deferred.begin(), deferred.end(), [&](const Deferred &a, const Deferred &b) {
+      return a.l != b.l ? a.l > b.l : rank[a.slot] < rank[b.slot];
+    });
+    for (const Deferred &d : deferred) copy_out(d.l, d.slot, d.produced);
+    deferred.clear();
+  }
+  void copy_out(int l, int slot, int produced) {
     SlotState &s = S(l, slot);
     const uint64_t bytes = slot_bytes(c, slot);
     s.host_off = host_top;
     host_top += Arena::round(bytes);
     const int done = new_event();
     if (live || cm) {
-      const int produced = new_event();
-      record(produced, cs);
+      if (produced < 0) { produced = new_event(); record(produced, cs); }
       hipStream_t out = on_express(l) ? d2hx : d2h;
       wait(out, produced);
       span_begin(SPAN_D2H, l, slot, out, bytes);
@@ -886,6 +939,7 @@ struct Walk {
         }
       }
     }
+    flush_deferred();
   }
 
   // ---- backward ------------------------------------------------------------------
@@ -1258,27 +1312,28 @@ dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t 
   std::vector<int> aheads;
   for (int a = c.L; a > 1; a /= 2) aheads.push_back(a);
   aheads.push_back(1);
-  auto run = [&](int ahead, long hold, bool through, int *n_swapped) {
+  auto run = [&](int ahead, long hold, bool through, bool defer, int *n_swapped) {
     Walk w(c, plan, false, nullptr);
     w.mfma_enabled = mfma_enabled;
     w.fuse_gelu_enabled = fuse_gelu_enabled;
     w.swap_hold_ticks = hold;
     w.prefetch_ahead = ahead;
     w.hold_through_backward = through;
+    w.defer_top = defer;
     w.forward();
     w.backward();
     fill_report(c, w, r);
-    if (policy_out) *policy_out = SwapPolicy{hold, ahead, through};
+    if (policy_out) *policy_out = SwapPolicy{hold, ahead, through, defer};
     *n_swapped = w.n_swapped;
   };
   int n_swapped = 0;
   if (budget == 0) {   // no budget: the caller wants the plan's memory saving, i.e. the tightest policy
-    run(1, 0, false, &n_swapped);
+    run(1, 0, false, false, &n_swapped);
     return DP_OK;
   }
   for (size_t ai = 0; ai < aheads.size(); ++ai)
-    for (int attempt = -1; attempt < kNumSwapHolds; ++attempt) {   // -1: held through the backward as well
-      run(aheads[ai], kSwapHolds[attempt < 0 ? 0 : attempt], attempt < 0, &n_swapped);
+    for (int attempt = -2; attempt < kNumSwapHolds; ++attempt) {   // -1: held through the backward as well; -2: and the top layers' copy-outs deferred
+      run(aheads[ai], kSwapHolds[attempt < 0 ? 0 : attempt], attempt < 0, attempt == -2, &n_swapped);
       if ((long double)inflight * (long double)r->peak_bytes <= (long double)budget) return DP_OK;
       if (n_swapped == 0) goto out;   // nothing is swapped: every policy gives this peak
     }
@@ -1298,6 +1353,7 @@ CostOut walk_cost(const Cfg &c, const dp_cost_model &cm, const uint8_t *plan, bo
   w.swap_hold_ticks = exact ? policy.hold_ticks : 0;
   w.prefetch_ahead = exact ? policy.ahead : 1;
   w.hold_through_backward = exact && policy.through_backward;
+  w.defer_top = exact && policy.defer_top;
   w.use_express = exact;
   w.cm = &cm;
   w.sim_arena_waits = exact;
@@ -1636,6 +1692,7 @@ dp_status dp_stage_step(dp_stage *st, const void *x_in, const void *dy, const ui
   w.swap_hold_ticks = swap_hold.hold_ticks;
   w.prefetch_ahead = swap_hold.ahead;
   w.hold_through_backward = swap_hold.through_backward;
+  w.defer_top = swap_hold.defer_top;
   w.cs = cs;
   const bool serial = (st->debug & 1u) != 0;
   w.d2h = serial ? cs : st->d2h;
@@ -1757,6 +1814,7 @@ dp_status dp_stage_forward(dp_stage *st, uint32_t slot, uint32_t inflight, const
   w->swap_hold_ticks = swap_hold.hold_ticks;
   w->prefetch_ahead = swap_hold.ahead;
   w->hold_through_backward = swap_hold.through_backward;
+  w->defer_top = swap_hold.defer_top;
   w->cs = (hipStream_t)hip_stream;
   const bool serial = (st->debug & 1u) != 0;
   w->d2h = serial ? w->cs : st->d2h;

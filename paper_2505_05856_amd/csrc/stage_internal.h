@@ -75,7 +75,7 @@ dp_status check_plan(const Cfg &c, const uint8_t *plan, size_t plan_len, dp_plan
 //               copy-outs of the top layers are still on their way then, and the first blocks
 //               the backward allocates would wait for them).
 // The tightest policy {0, 1, false} gives a plan's smallest peak.
-struct SwapPolicy { long hold_ticks = 0; int ahead = 1; bool through_backward = false; };
+struct SwapPolicy { long hold_ticks = 0; int ahead = 1; bool through_backward = false; bool defer_top = false; };
 // The static memory walk: fills `rep`, picks the first policy, from the most generous down, with
 // which inflight * peak fits `budget` (0 = no budget: the tightest) and returns it in *policy_out.
 dp_status validate(const Cfg &c, const uint8_t *plan, size_t plan_len, uint64_t budget, uint32_t inflight,
