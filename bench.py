@@ -28,13 +28,13 @@ PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector 
 MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 80.3e6, ("C5", "seed7-mixed"): 2096.6e6}
 # Average duration of an NT-form GEMM launch in the rocprofv3 kernel traces (profiles/*_step_kernel_trace.md).
 ROCPROF_NT_LAUNCH_US = {
-    ("C2", "keep-all"): {"us": 32.01, "hip_events_same_run_us": 36.51},
-    ("C5", "keep-all"): {"us": 1046.96, "hip_events_same_run_us": 1051.42},
+    ("C2", "keep-all"): {"us": 30.27, "hip_events_same_run_us": 34.61},
+    ("C5", "keep-all"): {"us": 979.50, "hip_events_same_run_us": 979.43},
     ("C5", "seed7-mixed"): {
-        "us": 1615.87, "hip_events_same_run_us": 1616.45,
+        "us": 1851.83, "hip_events_same_run_us": 1853.32,
         "note": "under the profiler this plan's device-to-host copies run as shader blit kernels beside the GEMMs and "
                 "slow them; the trace and the HIP events of that profiled run agree with each other, and the keep-all "
-                "trace (no copies: 1046.96 us by rocprofv3, 1051.42 us by HIP events on that box) shows the same kernels undisturbed"},
+                "trace (no copies: 979.50 us by rocprofv3, 979.43 us by HIP events in that run) shows the same kernels undisturbed"},
 }
 
 
