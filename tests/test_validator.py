@@ -145,6 +145,34 @@ def test_budget_predicate():
     assert rr["peak_bytes"] < peak
 
 
+def test_swap_policy_ladder_spends_exactly_the_headroom():
+    """A swapping plan under budgets from generous down to its minimum: every budget at or above the minimum is
+    feasible, the validated peak never exceeds the budget and never grows when the budget shrinks, the most
+    generous policy (blocks held, copy-outs of the upper layers deferred to the end of the forward) needs no more
+    than keeping everything, the traffic is the plan's whatever the policy, and half the minimum fails."""
+    for cfg in (small("pre", L=4), small("post", L=3)):
+        bc = to_binding_config(cfg)
+        for plan in (syn.plan_all_swap(cfg), syn.plan_seeded(cfg, 7), syn.plan_seeded(cfg, 11)):
+            _, tight = B.plan_validate(bc, plan)                       # no budget: the tightest policy
+            _, keep = B.plan_validate(bc, syn.plan_keep_all(cfg))
+            _, roomy = B.plan_validate(bc, plan, budget_bytes=1 << 40)
+            lo, hi = tight["peak_bytes"], roomy["peak_bytes"]
+            assert lo <= hi <= keep["peak_bytes"] + 4096 * 64          # (alignment slack of the arena)
+            assert roomy["swap_out_bytes"] == tight["swap_out_bytes"] and roomy["swap_in_bytes"] == tight["swap_in_bytes"]
+            last = hi
+            for k in range(9):
+                budget = hi - (hi - lo) * k // 8
+                code, rep = B.plan_validate(bc, plan, budget_bytes=budget, raise_on_error=False)
+                assert code == 0, (k, budget, B.last_error())
+                assert rep["peak_bytes"] <= budget and rep["peak_bytes"] <= last
+                assert rep["swap_out_bytes"] == tight["swap_out_bytes"]
+                last = rep["peak_bytes"]
+            # (first-fit fragmentation can make another policy a few blocks smaller than the tightest one)
+            assert lo - 64 * 4096 <= last <= lo
+            code, _ = B.plan_validate(bc, plan, budget_bytes=lo // 2, raise_on_error=False)
+            assert B.STATUS[code] == "DP_E_BUDGET"
+
+
 def test_ignored_plan_bytes_and_random_plans():
     cfg = small("post", L=3)
     bc = to_binding_config(cfg)
