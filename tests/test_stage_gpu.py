@@ -211,6 +211,17 @@ def test_forty_seeded_plans_give_the_same_bits_inside_their_validated_memory(sty
         assert stats["arena_high_water"] == rep["arena_peak_bytes"], seed
         assert (stats["d2h_bytes"], stats["h2d_bytes"]) == (rep["swap_out_bytes"], rep["swap_in_bytes"]), seed
         assert stats["n_replayed_ops"] == rep["n_replayed_ops"], seed
+        if seed % 4 == 0:
+            # the same plan with room to spare and half-way: the policies that hold swapped blocks back, run the
+            # swap-ins further ahead and queue the upper layers' copy-outs when the forward has been issued
+            _, roomy = B.plan_validate(run.bcfg, plan, budget_bytes=1 << 40)
+            for b2 in (roomy["peak_bytes"], (roomy["peak_bytes"] + budget) // 2):
+                _, rep2 = B.plan_validate(run.bcfg, plan, budget_bytes=b2)
+                run.poison_outputs()
+                stats = run.step(plan, budget_bytes=b2, want_stats=True)
+                assert all(torch.equal(a, b) for a, b in zip(keep, run.raw_results())), (seed, b2)
+                assert stats["arena_high_water"] == rep2["arena_peak_bytes"] and rep2["peak_bytes"] <= b2, (seed, b2)
+                assert (stats["d2h_bytes"], stats["h2d_bytes"]) == (rep["swap_out_bytes"], rep["swap_in_bytes"]), seed
     assert len(seen) == 40
     run.close()
 
