@@ -495,24 +495,29 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dk[d][e] = 0.f; dv[d][e] = 0.f; }
 
-  const int nq = (Sq + BKV - 1) / BKV;
-  const int t0 = CAUSAL ? j0 / BKV : 0;   // query tiles before the block's first key see none of its keys
-
   const char *qsrc = uniform_ptr((const char *)qb), *osrc = uniform_ptr((const char *)dob);
   const unsigned ldqb = (unsigned)ldq * 2u, ldob = (unsigned)H * 2u;
+  // The Q and dO tiles of query tile t go straight to LDS; the two scalars per query go through a
+  // register: even waves carry the 64 log-sum-exps, odd waves the 64 row dots (waves 2 and 3 store
+  // what waves 0 and 1 store, to the same words, so that no wave branches here).
+  // The scalar is asked for with the tile and first touched when it is stored, a tile later: a use any
+  // earlier would make the wave wait there for every load in flight, the tile's own among them.
+  const float *fsrc = (wave & 1) ? drw : lrow;
+  const float fmul = (wave & 1) ? 1.f : kLog2e;
+  const float fpad = (wave & 1) ? 0.f : INFINITY;   // +inf: P = 0 for padding rows
   float sl = 0.f;
-  // the Q and dO tiles of query tile t go straight to LDS; the two scalars per query through a register
   auto fetch = [&](int t, unsigned buf) {
     const int i0 = t * BKV;
     dma_tile_both<DH>(buf, qsrc, ldqb, i0, Sq, wave, lane);
     dma_tile_both<DH>(buf + TILE, osrc, ldob, i0, Sq, wave, lane);
-    if (tid < 64) sl = (i0 + tid < Sq) ? lrow[i0 + tid] * kLog2e : INFINITY;   // +inf: P = 0 for padding rows
-    else if (tid < 128) sl = (i0 + tid - 64 < Sq) ? drw[i0 + tid - 64] : 0.f;
+    sl = fsrc[min(i0 + lane, Sq - 1)];
   };
-  auto stash = [&](unsigned stage) {
-    if (tid < 128) reinterpret_cast<float *>(smem_b + FBASE + stage * FSTAGE)[tid] = sl;   // [0,64): lse, [64,128): row dots
+  auto stash = [&](int t, unsigned stage) {   // [0,64): lse, [64,128): row dots
+    reinterpret_cast<float *>(smem_b + FBASE + stage * FSTAGE)[tid & 127] = t * BKV + lane < Sq ? sl * fmul : fpad;
   };
-  if (t0 < nq) { fetch(t0, 0u); stash(0u); }
+  const int nq = (Sq + BKV - 1) / BKV;
+  const int t0 = CAUSAL ? j0 / BKV : 0;   // query tiles before the block's first key see none of its keys
+  if (t0 < nq) { fetch(t0, 0u); stash(t0, 0u); }
   BothAddr<DH> at;
   at.init(lane);
   wait_dma();
@@ -527,6 +532,10 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
   //   4: (behind the tile barrier) S, dP of A of the next tile
   // Every step reads the operand fragments of the step after it; the scheduling fences keep the
   // steps in this order.  (The sums keep their order: sub-tile A before B, contraction ascending.)
+  // A tile's code has no branch: the accumulators are carried through the loop in the registers
+  // the MFMAs leave them in.  Whether the causal mask can apply (MASK: the two tiles the block's
+  // 128 keys share with the diagonal) and whether a tile follows (MORE) are compile-time tags; a
+  // wave whose keys see no query of a diagonal tile adds zeros (it would wait at the barrier anyway).
   constexpr int EPS = 16 / NK;                       // softmax elements a step
   bf16x8 fx[2], fy[2];                               // fragment double buffer
   auto ld_rows = [&](int slot, int sub, int kd) {    // Q and dO along the rows: operands of S and dP
@@ -538,8 +547,6 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
     fy[slot] = at.cols(0u, sub * 32 + (j / ND) * 16, j % ND);
   };
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-  // a wave's keys see no query of a tile that lies wholly above the diagonal
-  auto active = [&](int t) { return !CAUSAL || t * BKV + BKV - 1 >= jw0; };
   f32x16 sA, dpA;
   auto logits_of_a = [&] {   // stage 4 (and the prologue); leaves the first fragments of stage 1 in flight
     ld_rows(0, 0, 0);
@@ -553,85 +560,93 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
       fence();
     }
   };
-  if (t0 < nq && active(t0)) logits_of_a();
 
-  for (int t = t0; t < nq; ++t) {
+  auto tile = [&](int t, auto mask_tag, auto more_tag) {
+    constexpr bool MASK = decltype(mask_tag)::value, MORE = decltype(more_tag)::value;
     const unsigned cur = (unsigned)((t - t0) & 1), nxt = cur ^ 1u;   // stages
     const int i0 = t * BKV;
     const float *lds_f = reinterpret_cast<const float *>(smem_b + FBASE + cur * FSTAGE);
-    if (t + 1 < nq) fetch(t + 1, nxt * STAGE);   // (every wave left that stage at the barrier below)
-    if (active(t)) {
-      // elements e0 .. e0+EPS-1 of a sub-tile: logits -> P (or P' under dropout), dP -> dS
-      auto soft = [&](f32x16 &sv, f32x16 &dpv, int sub, int e0) {
-        const int r0 = sub * 32 + 8 * (e0 >> 2) + 4 * hh + (e0 & 3);
-        float lv[EPS], dvv[EPS];
-        if constexpr (EPS == 4) {
-          const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r0), d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r0);
-          lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w; dvv[0] = d4.x; dvv[1] = d4.y; dvv[2] = d4.z; dvv[3] = d4.w;
+    if (MORE) fetch(t + 1, nxt * STAGE);   // (every wave left that stage at the barrier below)
+    // elements e0 .. e0+EPS-1 of a sub-tile: logits -> P (or P' under dropout), dP -> dS
+    auto soft = [&](f32x16 &sv, f32x16 &dpv, int sub, int e0) {
+      const int r0 = sub * 32 + 8 * (e0 >> 2) + 4 * hh + (e0 & 3);
+      float lv[EPS], dvv[EPS];
+      if constexpr (EPS == 4) {
+        const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r0), d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r0);
+        lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w; dvv[0] = d4.x; dvv[1] = d4.y; dvv[2] = d4.z; dvv[3] = d4.w;
+      } else {
+        const float2 l2 = *reinterpret_cast<const float2 *>(lds_f + r0), d2 = *reinterpret_cast<const float2 *>(lds_f + BKV + r0);
+        lv[0] = l2.x; lv[1] = l2.y; dvv[0] = d2.x; dvv[1] = d2.y;
+      }
+#pragma unroll
+      for (int u = 0; u < EPS; ++u) {
+        const int e = e0 + u, i = i0 + r0 + u;
+        const float l = lv[u], dd = dvv[u];
+        const float pr = fast_exp2(sv[e] * c - l);   // (rows past the end carry lse = +inf: p = 0 by itself)
+        if (DROP) {
+          const bool keep = drop_bits((uint32_t)i * (uint32_t)Sk + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
+          sv[e] = keep ? pr * da.scale : 0.f;
+          dpv[e] = pr * ((keep ? dpv[e] * da.scale : 0.f) - dd);
         } else {
-          const float2 l2 = *reinterpret_cast<const float2 *>(lds_f + r0), d2 = *reinterpret_cast<const float2 *>(lds_f + BKV + r0);
-          lv[0] = l2.x; lv[1] = l2.y; dvv[0] = d2.x; dvv[1] = d2.y;
+          sv[e] = pr;
+          dpv[e] = pr * (dpv[e] - dd);
         }
-#pragma unroll
-        for (int u = 0; u < EPS; ++u) {
-          const int e = e0 + u, i = i0 + r0 + u;
-          const float l = lv[u], dd = dvv[u];
-          const float pr = fast_exp2(sv[e] * c - l);   // (rows past the end carry lse = +inf: p = 0 by itself)
-          if (DROP) {
-            const bool keep = drop_bits((uint32_t)i * (uint32_t)Sk + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
-            sv[e] = keep ? pr * da.scale : 0.f;
-            dpv[e] = pr * ((keep ? dpv[e] * da.scale : 0.f) - dd);
-          } else {
-            sv[e] = pr;
-            dpv[e] = pr * (dpv[e] - dd);
-          }
-        }
-      };
-      // the causal mask, on the sub-tiles the diagonal crosses only: a masked logit becomes -inf, its P zero
-      auto mask = [&](f32x16 &sv, int sub) {
-        if (CAUSAL && i0 + 32 * sub < jw0 + 31) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (kj > i0 + sub * 32 + acc_row(e, lane)) sv[e] = -INFINITY;
-        }
-      };
-      f32x16 sB, dpB;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) { sB[e] = 0.f; dpB[e] = 0.f; }
-      mask(sA, 0);
-#pragma unroll
-      for (int kd = 0; kd < NK; ++kd) {   // stage 1
-        if (kd + 1 < NK) ld_rows((kd + 1) & 1, 1, kd + 1); else ld_cols((kd + 1) & 1, 0, 0);
-        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], kf[kd], sB, 0, 0, 0);
-        dpB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], vf[kd], dpB, 0, 0, 0);
-        soft(sA, dpA, 0, kd * EPS);
-        fence();
       }
-      bf16x8 pf[2], dsf[2];
-      pf[0] = pack8(sA, 0); pf[1] = pack8(sA, 8); dsf[0] = pack8(dpA, 0); dsf[1] = pack8(dpA, 8);
-      mask(sB, 1);
+    };
+    // the causal mask: a masked logit becomes -inf, its P zero
+    auto mask = [&](f32x16 &sv, int sub) {
+      if (MASK) {
 #pragma unroll
-      for (int j = 0; j < NK; ++j) {      // stage 2
-        if (j + 1 < NK) ld_cols((j + 1) & 1, 0, j + 1); else ld_cols((j + 1) & 1, 1, 0);
-        dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
-        dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
-        soft(sB, dpB, 1, j * EPS);
-        fence();
+        for (int e = 0; e < 16; ++e)
+          if (kj > i0 + sub * 32 + acc_row(e, lane)) sv[e] = -INFINITY;
       }
-      pf[0] = pack8(sB, 0); pf[1] = pack8(sB, 8); dsf[0] = pack8(dpB, 0); dsf[1] = pack8(dpB, 8);
+    };
+    f32x16 sB, dpB;
 #pragma unroll
-      for (int j = 0; j < NK; ++j) {      // stage 3
-        if (j + 1 < NK) ld_cols((j + 1) & 1, 1, j + 1);
-        dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
-        dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
-        fence();
-      }
+    for (int e = 0; e < 16; ++e) { sB[e] = 0.f; dpB[e] = 0.f; }
+    mask(sA, 0);
+#pragma unroll
+    for (int kd = 0; kd < NK; ++kd) {   // stage 1
+      if (kd + 1 < NK) ld_rows((kd + 1) & 1, 1, kd + 1); else ld_cols((kd + 1) & 1, 0, 0);
+      sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], kf[kd], sB, 0, 0, 0);
+      dpB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], vf[kd], dpB, 0, 0, 0);
+      soft(sA, dpA, 0, kd * EPS);
+      fence();
     }
-    if (t + 1 < nq) stash(nxt);
+    bf16x8 pf[2], dsf[2];
+    pf[0] = pack8(sA, 0); pf[1] = pack8(sA, 8); dsf[0] = pack8(dpA, 0); dsf[1] = pack8(dpA, 8);
+    mask(sB, 1);
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {      // stage 2
+      if (j + 1 < NK) ld_cols((j + 1) & 1, 0, j + 1); else ld_cols((j + 1) & 1, 1, 0);
+      dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
+      dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
+      soft(sB, dpB, 1, j * EPS);
+      fence();
+    }
+    pf[0] = pack8(sB, 0); pf[1] = pack8(sB, 8); dsf[0] = pack8(dpB, 0); dsf[1] = pack8(dpB, 8);
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {      // stage 3
+      if (j + 1 < NK) ld_cols((j + 1) & 1, 1, j + 1);
+      dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
+      dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
+      fence();
+    }
+    if (MORE) stash(t + 1, nxt);
     at.flip(STAGE);
     wait_dma();
     __syncthreads();
-    if (t + 1 < nq && active(t + 1)) logits_of_a();   // stage 4
+    if (MORE) logits_of_a();   // stage 4
+  };
+  if (t0 < nq) {
+    logits_of_a();
+    int t = t0;
+    if (CAUSAL) {   // the tiles that hold the diagonal for some of the block's keys
+      for (; t < t0 + BROWS / BKV && t + 1 < nq; ++t) tile(t, std::true_type{}, std::true_type{});
+      if (t < t0 + BROWS / BKV) { tile(t, std::true_type{}, std::false_type{}); ++t; }
+    }
+    for (; t + 1 < nq; ++t) tile(t, std::false_type{}, std::true_type{});
+    if (t < nq) tile(t, std::false_type{}, std::false_type{});
   }
 
   if (kj >= Sk) return;
