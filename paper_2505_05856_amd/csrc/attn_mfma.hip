@@ -264,6 +264,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
   BothAddr<DH> at;
   at.init(lane);
   wait_dma();
+  // (a use of the query fragments the compiler can see, here: otherwise it places its own wait for
+  // them before their first MFMA inside the tile loop, where it also waits for the tiles in flight)
+#pragma unroll
+  for (int kd = 0; kd < NK; ++kd) asm volatile("" ::"v"(qf[kd]));
   __syncthreads();
 
   // A wave runs a software pipeline of four stages a tile, so that the softmax arithmetic issues
