@@ -405,6 +405,16 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
   }
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
+    // the residual of the 32 rows, asked for before the turn through LDS and first used after it
+    // (every tile lies inside the matrix, so rows and columns the tile does not own are read too)
+    bf16x4 r4[32 / RPI];
+    if (res != nullptr) {
+#pragma unroll
+      for (int g = 0; g < 32 / RPI; ++g) {
+        const size_t uoff = ((size_t)(m0 + wm + i * 32 + g * RPI) * (size_t)N + (size_t)(n0 + wn)) * 2 + lane_off;
+        r4[g] = *reinterpret_cast<const bf16x4 *>((const char *)res + uoff);
+      }
+    }
     // write: element e of block j -> row 8*(e/4) + 4*(l/32) + e%4, column 32*j + l%32
 #pragma unroll
     for (int j = 0; j < FN; ++j)
@@ -425,9 +435,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
       if (!col_owned || wm + i * 32 + g * RPI + orow < skip_rows) continue;
       float v[4] = {t[0] + bv[0], t[1] + bv[1], t[2] + bv[2], t[3] + bv[3]};
       if (res != nullptr) {
-        const bf16x4 r4 = *reinterpret_cast<const bf16x4 *>((const char *)res + uoff);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] += (float)r4[q];
+        for (int q = 0; q < 4; ++q) v[q] += (float)r4[g][q];
       }
       bf16x4 o;
 #pragma unroll
