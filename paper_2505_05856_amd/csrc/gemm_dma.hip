@@ -425,12 +425,17 @@ __global__ __attribute__((amdgpu_waves_per_eu(WGM * WGN / 4, WGM * WGN / 4), amd
         const unsigned cc = (unsigned)(32 * j + (lane & 31)) ^ (ESW * ((rr >> 2) & 1u));
         *reinterpret_cast<float *>(ew + (rr * WN + cc) * 4u) = acc[i][j][e];
       }
-    // read back and store
+    // read back (all reads asked for before the first is used), then store
+    f32x4 tb[32 / RPI];
 #pragma unroll
     for (int g = 0; g < 32 / RPI; ++g) {
       const unsigned rr = (unsigned)(g * RPI + orow);
       const unsigned cc = (unsigned)oc4 ^ (ESW * ((rr >> 2) & 1u));
-      const f32x4 t = *reinterpret_cast<const f32x4 *>(ew + (rr * WN + cc) * 4u);
+      tb[g] = *reinterpret_cast<const f32x4 *>(ew + (rr * WN + cc) * 4u);
+    }
+#pragma unroll
+    for (int g = 0; g < 32 / RPI; ++g) {
+      const f32x4 t = tb[g];
       const size_t uoff = ((size_t)(m0 + wm + i * 32 + g * RPI) * (size_t)N + (size_t)(n0 + wn)) * 2 + lane_off;
       if (!col_owned || wm + i * 32 + g * RPI + orow < skip_rows) continue;
       float v[4] = {t[0] + bv[0], t[1] + bv[1], t[2] + bv[2], t[3] + bv[3]};
