@@ -551,9 +551,25 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
     fy[slot] = at.cols(0u, sub * 32 + (j / ND) * 16, j % ND);
   };
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  // The two scalars of the queries a softmax step works on come from LDS one step ahead as well:
+  // softmax step q of a tile (q < NK: sub-tile A, else B) finds them in slot q % 2.
+  const float *lds_f = reinterpret_cast<const float *>(smem_b + FBASE);   // the current tile's scalars
+  float lsc[2][EPS], dsc[2][EPS];
+  auto ld_soft = [&](int q) {
+    const int e0 = (q % NK) * EPS, r0 = (q / NK) * 32 + 8 * (e0 >> 2) + 4 * hh + (e0 & 3);
+    if constexpr (EPS == 4) {
+      const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r0), d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r0);
+      lsc[q & 1][0] = l4.x; lsc[q & 1][1] = l4.y; lsc[q & 1][2] = l4.z; lsc[q & 1][3] = l4.w;
+      dsc[q & 1][0] = d4.x; dsc[q & 1][1] = d4.y; dsc[q & 1][2] = d4.z; dsc[q & 1][3] = d4.w;
+    } else {
+      const float2 l2 = *reinterpret_cast<const float2 *>(lds_f + r0), d2 = *reinterpret_cast<const float2 *>(lds_f + BKV + r0);
+      lsc[q & 1][0] = l2.x; lsc[q & 1][1] = l2.y; dsc[q & 1][0] = d2.x; dsc[q & 1][1] = d2.y;
+    }
+  };
   f32x16 sA, dpA;
-  auto logits_of_a = [&] {   // stage 4 (and the prologue); leaves the first fragments of stage 1 in flight
+  auto logits_of_a = [&] {   // stage 4 (and the prologue); leaves the first fragments and scalars of stage 1 in flight
     ld_rows(0, 0, 0);
+    ld_soft(0);
 #pragma unroll
     for (int e = 0; e < 16; ++e) { sA[e] = 0.f; dpA[e] = 0.f; }
 #pragma unroll
@@ -569,23 +585,15 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
     constexpr bool MASK = decltype(mask_tag)::value, MORE = decltype(more_tag)::value;
     const unsigned cur = (unsigned)((t - t0) & 1), nxt = cur ^ 1u;   // stages
     const int i0 = t * BKV;
-    const float *lds_f = reinterpret_cast<const float *>(smem_b + FBASE + cur * FSTAGE);
     if (MORE) fetch(t + 1, nxt * STAGE);   // (every wave left that stage at the barrier below)
-    // elements e0 .. e0+EPS-1 of a sub-tile: logits -> P (or P' under dropout), dP -> dS
-    auto soft = [&](f32x16 &sv, f32x16 &dpv, int sub, int e0) {
+    // softmax step q, elements e0 .. e0+EPS-1 of a sub-tile: logits -> P (or P' under dropout), dP -> dS
+    auto soft = [&](f32x16 &sv, f32x16 &dpv, int q) {
+      const int sub = q / NK, e0 = (q % NK) * EPS;
       const int r0 = sub * 32 + 8 * (e0 >> 2) + 4 * hh + (e0 & 3);
-      float lv[EPS], dvv[EPS];
-      if constexpr (EPS == 4) {
-        const float4 l4 = *reinterpret_cast<const float4 *>(lds_f + r0), d4 = *reinterpret_cast<const float4 *>(lds_f + BKV + r0);
-        lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w; dvv[0] = d4.x; dvv[1] = d4.y; dvv[2] = d4.z; dvv[3] = d4.w;
-      } else {
-        const float2 l2 = *reinterpret_cast<const float2 *>(lds_f + r0), d2 = *reinterpret_cast<const float2 *>(lds_f + BKV + r0);
-        lv[0] = l2.x; lv[1] = l2.y; dvv[0] = d2.x; dvv[1] = d2.y;
-      }
 #pragma unroll
       for (int u = 0; u < EPS; ++u) {
         const int e = e0 + u, i = i0 + r0 + u;
-        const float l = lv[u], dd = dvv[u];
+        const float l = lsc[q & 1][u], dd = dsc[q & 1][u];
         const float pr = fast_exp2(sv[e] * c - l);   // (rows past the end carry lse = +inf: p = 0 by itself)
         if (DROP) {
           const bool keep = drop_bits((uint32_t)i * (uint32_t)Sk + (uint32_t)kj, keys.k0, keys.k1) >= da.thr;
@@ -612,9 +620,10 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
 #pragma unroll
     for (int kd = 0; kd < NK; ++kd) {   // stage 1
       if (kd + 1 < NK) ld_rows((kd + 1) & 1, 1, kd + 1); else ld_cols((kd + 1) & 1, 0, 0);
+      ld_soft(kd + 1);
       sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kd & 1], kf[kd], sB, 0, 0, 0);
       dpB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[kd & 1], vf[kd], dpB, 0, 0, 0);
-      soft(sA, dpA, 0, kd * EPS);
+      soft(sA, dpA, kd);
       fence();
     }
     bf16x8 pf[2], dsf[2];
@@ -623,9 +632,10 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
 #pragma unroll
     for (int j = 0; j < NK; ++j) {      // stage 2
       if (j + 1 < NK) ld_cols((j + 1) & 1, 0, j + 1); else ld_cols((j + 1) & 1, 1, 0);
+      if (j + 1 < NK) ld_soft(NK + j + 1);
       dv[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[j & 1], pf[j / ND], dv[j % ND], 0, 0, 0);
       dk[j % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j & 1], dsf[j / ND], dk[j % ND], 0, 0, 0);
-      soft(sB, dpB, 1, j * EPS);
+      soft(sB, dpB, NK + j);
       fence();
     }
     pf[0] = pack8(sB, 0); pf[1] = pack8(sB, 8); dsf[0] = pack8(dpB, 0); dsf[1] = pack8(dpB, 8);
@@ -638,6 +648,7 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
     }
     if (MORE) stash(t + 1, nxt);
     at.flip(STAGE);
+    lds_f = reinterpret_cast<const float *>(smem_b + FBASE + nxt * FSTAGE);
     wait_dma();
     __syncthreads();
     if (MORE) logits_of_a();   // stage 4
