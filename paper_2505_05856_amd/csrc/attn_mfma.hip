@@ -316,9 +316,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
     if (MORE) fetch_v(t + 1);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx * c);   // (the scale c > 0 is folded into the exponent below)
-    // the running maximum moves in the first tiles and then hardly ever: skip the rescaling
-    // of the accumulators when it stayed put for every query of the wave
-    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+    // The reference point m of the exponents need not be the maximum itself: O and the row sum
+    // carry the same factor exp2(-m), which cancels in O / l and in the log-sum-exp.  It follows the
+    // maximum only once that has moved by more than kLag for some query of the wave (P <= 2^kLag
+    // until then: no loss in fp32 sums or in bf16's relative rounding), so that the rescaling of
+    // the accumulators, which a maximum creeping upwards would ask for in most tiles, is rare.
+    constexpr float kLag = 8.f;
+    if (__builtin_amdgcn_ballot_w64(m_new > m + kLag) != 0) {
       const float alpha = fast_exp2(m - m_new);
       l *= alpha;
 #pragma unroll
