@@ -173,6 +173,47 @@ def test_attention(dt, causal, Bn, S, nh, dh, sharp):
         assert O.max_rel_err(got[:, blk * H:(blk + 1) * H], dq_ref[:, blk * H:(blk + 1) * H]) < 2 * tol, blk
 
 
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dh", [64, 128])
+def test_attention_with_a_maximum_that_creeps_and_then_jumps(dt, dh):
+    """Logits that grow by about two units per 64-key tile, with a jump of thirty for every other query late in
+    the row: the forward kernel's reference point for the exponents follows the maximum with a lag, and O and
+    the log-sum-exp must not depend on where it stood (the softmax is invariant under the shift)."""
+    Bn, S, nh = 1, 1024, 2
+    H = nh * dh
+    rng = np.random.default_rng(77)
+    u = rng.standard_normal(dh); u /= np.linalg.norm(u)
+    q = np.tile(u * np.sqrt(dh), (S, 1)) + 0.05 * rng.standard_normal((S, dh))    # q.k / sqrt(dh) = the key's ramp
+    ramp = 2.0 * np.arange(S) / 64.0
+    k = ramp[:, None] * u[None, :] + 0.05 * rng.standard_normal((S, dh))
+    k[700] += 30.0 * u                      # one key far above the ramp ...
+    q[0::2] *= 1.0; q[1::2] *= 0.25         # ... by thirty units for even queries, by a quarter of that for odd ones
+    v = rng.standard_normal((S, dh))
+    qkv = np.zeros((Bn * S, 3 * H))
+    for h in range(nh):
+        qkv[:, h * dh:(h + 1) * dh] = q
+        qkv[:, H + h * dh:H + (h + 1) * dh] = k
+        qkv[:, 2 * H + h * dh:2 * H + (h + 1) * dh] = v * (h + 1)
+    qkv = syn.round_to_bf16(qkv.astype(np.float32)) if dt == torch.bfloat16 else qkv.astype(np.float32)
+    d_o = rnd((Bn * S, H), 78, dt)
+    q64 = qkv.astype(np.float64)
+    for causal in (False, True):
+        o_ref, lse_ref = O.attention_fwd(q64, Bn, S, nh, causal)
+        dq_ref = O.attention_bwd(d_o.astype(np.float64), q64, Bn, S, nh, causal)
+        tq, tdo = dev(qkv, dt), dev(d_o, dt)
+        o = torch.empty(Bn * S, H, dtype=dt, device=DEV)
+        lse = torch.empty(Bn, nh, S, dtype=torch.float32, device=DEV)
+        B.op_attention_fwd(tq, Bn, S, nh, dh, causal, o, lse)
+        tol = TOL[dt] * (2 if dt == torch.bfloat16 else 1)
+        assert O.max_rel_err(host(o), o_ref) < tol
+        assert np.allclose(host(lse), lse_ref, atol=2e-5 * 40 if dt == torch.float32 else 2e-3 * 40)   # lse reaches ~60
+        dqkv = torch.empty_like(tq)
+        B.op_attention_bwd(tq, o, lse, tdo, Bn, S, nh, dh, causal, dqkv, ws_for(Bn * S, nh))
+        got = host(dqkv)
+        for blk in range(3):
+            assert O.max_rel_err(got[:, blk * H:(blk + 1) * H], dq_ref[:, blk * H:(blk + 1) * H]) < 2 * tol, (causal, blk)
+
+
 def test_mfma_issue_probe_reports_a_plausible_rate():
     """The diagnostic behind the roofline discussion: rate = CUs * 4096 flop/clk * clock, so the two numbers it
     returns must agree with each other, and zeros must not run slower than random mantissas."""
