@@ -149,17 +149,28 @@ __device__ __forceinline__ bf16x8 frag_cols_sw(const unsigned char *tile, int r0
 template <int DH> __device__ __forceinline__ constexpr unsigned swz_both(unsigned r) {
   return swz_cols<DH>(r) | ((r >> 2) & 3u);
 }
+// (request i of the DH/32 a wave issues for a tile: rows past the end read the last row, so a tile
+// index past the end is harmless too)
+template <int DH>
+__device__ __forceinline__ void dma_req_both(int i, unsigned lds_byte, const char *src_col0, unsigned ldb, int row0,
+                                             int nrows, int wave, int lane) {
+  constexpr int NREQ = DH / 32, RPR = 1024 / (DH * 2), CPR = DH / 8;
+  const int q = wave * NREQ + i, r = RPR * q + lane / CPR;
+  const int rg = min(row0 + r, nrows - 1);
+  const unsigned chunk = (unsigned)(lane % CPR) ^ swz_both<DH>((unsigned)r);
+  dma16(lds_byte + (unsigned)q * 1024u, (unsigned)rg * ldb + chunk * 16u, src_col0);
+}
 template <int DH>
 __device__ __forceinline__ void dma_tile_both(unsigned lds_byte, const char *src_col0, unsigned ldb, int row0, int nrows,
                                               int wave, int lane) {
-  constexpr int NREQ = DH / 32, RPR = 1024 / (DH * 2), CPR = DH / 8;
 #pragma unroll
-  for (int i = 0; i < NREQ; ++i) {
-    const int q = wave * NREQ + i, r = RPR * q + lane / CPR;
-    const int rg = min(row0 + r, nrows - 1);
-    const unsigned chunk = (unsigned)(lane % CPR) ^ swz_both<DH>((unsigned)r);
-    dma16(lds_byte + (unsigned)q * 1024u, (unsigned)rg * ldb + chunk * 16u, src_col0);
-  }
+  for (int i = 0; i < DH / 32; ++i) dma_req_both<DH>(i, lds_byte, src_col0, ldb, row0, nrows, wave, lane);
+}
+// max / sum of a value over the two halves of the wave (lanes l and l ^ 32), in every lane: the swap
+// leaves lanes 0..31 of x beside lanes 32..63 of x in both registers, in the one or the other order
+__device__ __forceinline__ float halves_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 // The fragment addresses of such a tile, as LDS byte addresses a lane keeps in registers: the
 // swizzle of a row depends on its low four bits only, so every fragment of the tile is one of
@@ -311,10 +322,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
   auto tile = [&](int t, auto more_tag) {
     constexpr bool MORE = decltype(more_tag)::value;
     const int j0 = t * BKV;
-    // (every wave left the buffers these go to at the barrier that ended the last tile)
-    if (t + 2 < nkv) fetch_k(t + 2);
-    if (MORE) fetch_v(t + 1);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = halves_max(mx);
     const float m_new = fmaxf(m, mx * c);   // (the scale c > 0 is folded into the exponent below)
     // The reference point m of the exponents need not be the maximum itself: O and the row sum
     // carry the same factor exp2(-m), which cancels in O / l and in the log-sum-exp.  It follows the
@@ -353,18 +361,23 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
 #pragma unroll
     for (int kd = 0; kd < NK; ++kd) {
       if (MORE) {
+        // one request a step for the tiles on their way: K of tile t+2, then V of tile t+1 (every
+        // wave left the buffers they go to at the barrier that ended the last tile); a burst of
+        // them at the head of the tile would hold the wave at the issue of each
+        if (kd < NK / 2) dma_req_both<DH>(kd, (unsigned)(t & 1) * TILE, kb, ldb, (t + 2) * BKV, S, wave, lane);
+        else dma_req_both<DH>(kd - NK / 2, VOFF + (unsigned)((t + 1) & 1) * TILE, vb, ldb, (t + 1) * BKV, S, wave, lane);
         const bf16x8 ka = fx[0], kb2 = fx[1];
         if (kd + 1 < NK) { ld_k(0, 0, kd + 1); ld_k(1, 1, kd + 1); }
         nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kd], nxt[0], 0, 0, 0);
         nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb2, qf[kd], nxt[1], 0, 0, 0);
       }
+      if (kd + 1 == NK) ld_v(0, 0, 0);   // the first fragment of stage 3
       soft(cur[0], 0, kd * (16 / NK), 16 / NK);
       fence();
     }
     if (MORE) mask(nxt, j0 + BKV);
     bf16x8 pf[2];
     pf[0] = pack8(cur[0], 0); pf[1] = pack8(cur[0], 8);
-    ld_v(0, 0, 0);
     // stage 3: NK steps of one MFMA; 8 / NK elements of P_B and 16 / NK of the next maximum a step
 #pragma unroll
     for (int j = 0; j < NK; ++j) {
