@@ -168,6 +168,33 @@ __device__ __forceinline__ void dma_tile_both(unsigned lds_byte, const char *src
 }
 // max / sum of a value over the two halves of the wave (lanes l and l ^ 32), in every lane: the swap
 // leaves lanes 0..31 of x beside lanes 32..63 of x in both registers, in the one or the other order
+// A wave's 32 x DH result (lane l holds row l % 32; accumulator element e of block d is column
+// 32 d + 8 (e / 4) + 4 (l / 32) + e % 4) goes out as whole rows: a store from the accumulators would
+// touch 32 rows with 16 bytes each, so the tile is turned through `ew`, 64 DH bytes of LDS that only
+// this wave uses (16-byte chunk c of row r at position c ^ (r % chunks a row)), and leaves as
+// 16 bytes a lane, DH / 8 lanes a row.  `mul` is the lane's (its row's) factor; rows >= nrows stay unwritten.
+template <int DH>
+__device__ __forceinline__ void store_rows_via_lds(unsigned char *ew, const f32x16 (&acc)[DH / 32], float mul, bf16 *dst,
+                                                   long ld, int nrows, int lane) {
+  constexpr int ND = DH / 32, CPR = DH / 8, RPI = 64 / CPR;
+  const int row = lane & 31, hh = lane >> 5;
+#pragma unroll
+  for (int d = 0; d < ND; ++d)
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+      bf16x4 v;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) v[t] = (bf16)(acc[d][e4 * 4 + t] * mul);
+      const int pos = (d * 4 + e4) ^ (row & (CPR - 1));
+      *reinterpret_cast<bf16x4 *>(ew + row * (DH * 2) + pos * 16 + hh * 8) = v;
+    }
+#pragma unroll
+  for (int i = 0; i < 32 / RPI; ++i) {
+    const int r = i * RPI + lane / CPR, c = lane % CPR;
+    const uint4 q = *reinterpret_cast<const uint4 *>(ew + r * (DH * 2) + ((c ^ (r & (CPR - 1))) * 16));
+    if (r < nrows) *reinterpret_cast<uint4 *>(dst + (long)r * ld + c * 8) = q;
+  }
+}
 __device__ __forceinline__ float halves_max(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -421,20 +448,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
   if (nkv > 0) tile(nkv - 1, std::false_type{});
 
   l += __shfl_xor(l, 32, 64);
-  if (qi >= Sq) return;
-  if (lse != nullptr && hh == 0) lse[((long)b * nh + h) * Sq + qi] = (m + __log2f(l)) * kLn2;
+  if (lse != nullptr && hh == 0 && qi < Sq) lse[((long)b * nh + h) * Sq + qi] = (m + __log2f(l)) * kLn2;
   if (o == nullptr) return;
+  // (every wave is behind the last tile's barrier: nobody reads the tile buffers any more)
   const float inv = (DROP ? da.scale : 1.0f) / l;
-  bf16 *orow = o + ((long)b * Sq + qi) * H + (long)h * DH;
-#pragma unroll
-  for (int d = 0; d < ND; ++d)
-#pragma unroll
-    for (int e4 = 0; e4 < 4; ++e4) {
-      bf16x4 v;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) v[t] = (bf16)(acc[d][e4 * 4 + t] * inv);
-      *reinterpret_cast<bf16x4 *>(orow + d * 32 + 8 * e4 + 4 * hh) = v;
-    }
+  store_rows_via_lds<DH>(smem_b + wave * (64 * DH), acc, inv, o + ((long)b * Sq + iw0) * H + (long)h * DH, H, Sq - iw0, lane);
 }
 
 template <typename K>
@@ -681,19 +699,10 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
     if (t < nq) tile(t, std::false_type{}, std::false_type{});
   }
 
-  if (kj >= Sk) return;
-  bf16 *krow = (bf16 *)av.dk + ((long)b * Sk + kj) * ld + (long)h * DH;
-  bf16 *vrow = (bf16 *)av.dv + ((long)b * Sk + kj) * ld + (long)h * DH;
-#pragma unroll
-  for (int d = 0; d < ND; ++d)
-#pragma unroll
-    for (int e4 = 0; e4 < 4; ++e4) {
-      bf16x4 a, g;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) { a[t] = (bf16)(dk[d][e4 * 4 + t] * scale); g[t] = (bf16)dv[d][e4 * 4 + t]; }
-      *reinterpret_cast<bf16x4 *>(krow + d * 32 + 8 * e4 + 4 * hh) = a;
-      *reinterpret_cast<bf16x4 *>(vrow + d * 32 + 8 * e4 + 4 * hh) = g;
-    }
+  // (every wave is behind the last tile's barrier, or there was no tile: nobody reads the tile buffers any more)
+  const long out0 = ((long)b * Sk + jw0) * ld + (long)h * DH;
+  store_rows_via_lds<DH>(smem_b + wave * (128 * DH), dk, scale, (bf16 *)av.dk + out0, ld, Sk - jw0, lane);
+  store_rows_via_lds<DH>(smem_b + wave * (128 * DH) + 64 * DH, dv, 1.f, (bf16 *)av.dv + out0, ld, Sk - jw0, lane);
 }
 
 // dQ: the block owns 128 queries (32 per wave) and streams 64-key tiles of K and V.  It also takes
@@ -707,6 +716,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
                                                              float *__restrict__ drow,
                                                              int nh, float scale, DropArgs da) {
   constexpr int ND = DH / 32, NK = DH / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_b[];
   // LDS, in bytes: [stage 0: K, V][stage 1: K, V], every tile in the dual-use layout
   constexpr unsigned TILE = BKV * DH * 2, STAGE = 2 * TILE;
 
@@ -861,17 +871,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
     if (t + 1 < nkv) logits_of_a();   // stage 4
   }
 
-  if (qi >= Sq) return;
-  bf16 *qrow = (bf16 *)av.dq + ((long)b * Sq + qi) * ldq + (long)h * DH;
-#pragma unroll
-  for (int d = 0; d < ND; ++d)
-#pragma unroll
-    for (int e4 = 0; e4 < 4; ++e4) {
-      bf16x4 a;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) a[t] = (bf16)(dq[d][e4 * 4 + t] * scale);
-      *reinterpret_cast<bf16x4 *>(qrow + d * 32 + 8 * e4 + 4 * hh) = a;
-    }
+  // (every wave is behind the last tile's barrier: nobody reads the tile buffers any more)
+  store_rows_via_lds<DH>(smem_b + wave * (64 * DH), dq, scale, (bf16 *)av.dq + ((long)b * Sq + iw0) * ldq + (long)h * DH,
+                         ldq, Sq - iw0, lane);
 }
 
 template <int DH>
@@ -926,7 +928,7 @@ static bool view_ok(const AttnView &v) {
 
 hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, void *o, float *lse,
                                      hipStream_t s, const DropArgs *drop) {
-  if ((causal && v.Sq != v.Sk) || !view_ok(v)) return hipErrorInvalidValue;
+  if ((causal && v.Sq != v.Sk) || !view_ok(v) || ((uintptr_t)o & 15) != 0) return hipErrorInvalidValue;
   if ((long)B * v.Sq * nh == 0) return hipSuccess;   // (no keys: the caller's case, there is no softmax to take)
   return dh == 64 ? fwd_launch<64>(B, nh, causal, v, o, lse, drop, s) : fwd_launch<128>(B, nh, causal, v, o, lse, drop, s);
 }
@@ -934,7 +936,8 @@ hipError_t launch_attn_fwd_mfma_view(int B, int nh, int dh, int causal, const At
 hipError_t launch_attn_bwd_mfma_view(int B, int nh, int dh, int causal, const AttnView &v, const void *o,
                                      const float *lse, const void *d_o, float *ws, hipStream_t s,
                                      const DropArgs *drop) {
-  if ((causal && v.Sq != v.Sk) || !view_ok(v) || ((uintptr_t)d_o & 15) != 0) return hipErrorInvalidValue;
+  const uintptr_t outs = (uintptr_t)v.dq | (uintptr_t)v.dk | (uintptr_t)v.dv;   // (rows leave as 16 bytes a lane)
+  if ((causal && v.Sq != v.Sk) || !view_ok(v) || (((uintptr_t)d_o | outs) & 15) != 0) return hipErrorInvalidValue;
   if ((long)B * nh == 0 || (v.Sq == 0 && v.Sk == 0)) return hipSuccess;
   return dh == 64 ? bwd_launch<64>(B, nh, causal, v, o, lse, d_o, ws, drop, s)
                   : bwd_launch<128>(B, nh, causal, v, o, lse, d_o, ws, drop, s);
