@@ -558,7 +558,10 @@ dp_status dp_op_colsum(int32_t dtype, int32_t rows, int32_t cols, const void *x,
  * threads) race; calls on one stream are ordered. */
 dp_status dp_op_colsum_static(int32_t dtype, int32_t rows, int32_t cols, const void *x, void *out,
                               void *hip_stream);
-/* o [T,H], lse [B,nh,S] from qkv [T,3H]; o or lse may be NULL. */
+/* o [T,H], lse [B,nh,S] from qkv [T,3H]; o or lse may be NULL.  (All attention entry points: in
+ * bf16 with a head dimension of 64 or 128 the matrix-core kernels run; they move 16 bytes a lane,
+ * so every tensor pointer handed in must then be 16-byte aligned, as allocations are; a pointer
+ * that is not is refused with DP_E_HIP "invalid argument" before anything is launched.) */
 dp_status dp_op_attention_fwd(int32_t dtype, int32_t B, int32_t S, int32_t nh, int32_t dh, int32_t causal,
                               const void *qkv, void *o, float *lse, void *hip_stream);
 /* dqkv [T,3H] from qkv, o, lse, d_o; ws: device workspace of
