@@ -25,16 +25,16 @@ PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector 
 # Bytes per launch of the dominant kernel that cross the L2 towards memory (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000,
 # the factors a 256 MiB device copy gives), from the rocprofv3 --pmc runs summarised in
 # profiles/c2_step_hbm_traffic_pmc.md and profiles/c5_step_hbm_traffic_pmc.md.
-MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 80.3e6, ("C5", "seed7-mixed"): 2096.0e6}
+MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 80.3e6, ("C5", "seed7-mixed"): 2096.3e6}
 # Average duration of an NT-form GEMM launch in the rocprofv3 kernel traces (profiles/*_step_kernel_trace.md).
 ROCPROF_NT_LAUNCH_US = {
-    ("C2", "keep-all"): {"us": 30.34, "hip_events_same_run_us": 34.73},
-    ("C5", "keep-all"): {"us": 993.49, "hip_events_same_run_us": 993.47},
+    ("C2", "keep-all"): {"us": 29.73, "hip_events_same_run_us": 34.22},
+    ("C5", "keep-all"): {"us": 965.27, "hip_events_same_run_us": 965.28},
     ("C5", "seed7-mixed"): {
-        "us": 1875.06, "hip_events_same_run_us": 1874.88,
+        "us": 1841.81, "hip_events_same_run_us": 1842.11,
         "note": "under the profiler this plan's device-to-host copies run as shader blit kernels beside the GEMMs and "
                 "slow them; the trace and the HIP events of that profiled run agree with each other, and the keep-all "
-                "trace (no copies: 993.49 us by rocprofv3, 993.47 us by HIP events in that run) shows the same kernels undisturbed"},
+                "trace (no copies: 965.27 us by rocprofv3, 965.28 us by HIP events in that run) shows the same kernels undisturbed"},
 }
 
 
