@@ -289,8 +289,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
 
   bf16x8 qf[NK];
 #pragma unroll
-  for (int kd = 0; kd < NK; ++kd)
-    qf[kd] = qi < Sq ? as_frag(ld16(qb + (long)qi * ldq + kd * 16 + 8 * hh)) : as_frag(make_uint4(0, 0, 0, 0));
+  for (int kd = 0; kd < NK; ++kd)   // (unguarded: a query past the end reads the last row, and nothing of it is stored)
+    qf[kd] = as_frag(ld16(qb + (long)min(qi, Sq - 1) * ldq + kd * 16 + 8 * hh));
 
   f32x16 acc[ND];
 #pragma unroll
@@ -523,10 +523,10 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dkv_kernel(At
 
   bf16x8 kf[NK], vf[NK];
 #pragma unroll
-  for (int kd = 0; kd < NK; ++kd) {
-    const uint4 z = make_uint4(0, 0, 0, 0);
-    kf[kd] = as_frag(kj < Sk ? ld16(kb + (long)kj * ld + kd * 16 + 8 * hh) : z);
-    vf[kd] = as_frag(kj < Sk ? ld16(vb + (long)kj * ld + kd * 16 + 8 * hh) : z);
+  for (int kd = 0; kd < NK; ++kd) {   // (unguarded: a key past the end reads the last row; a lane's key is a column of the
+    const long kc = min(kj, Sk - 1);  //  products nobody else sees, and its dK, dV rows are not stored)
+    kf[kd] = as_frag(ld16(kb + kc * ld + kd * 16 + 8 * hh));
+    vf[kd] = as_frag(ld16(vb + kc * ld + kd * 16 + 8 * hh));
   }
   f32x16 dk[ND], dv[ND];
 #pragma unroll
@@ -736,18 +736,34 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
   const int q0 = qt * BROWS, iw0 = q0 + wave * 32, qi = iw0 + (lane & 31);
   const float c = scale * kLog2e;
 
+  int nkv = (S + BKV - 1) / BKV;
+  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
+  const char *ksrc = uniform_ptr((const char *)kb), *vsrc = uniform_ptr((const char *)vb);
+  const unsigned ldb = (unsigned)ld * 2u;
+  auto fetch = [&](int t, unsigned buf) {
+    dma_tile_both<DH>(buf, ksrc, ldb, t * BKV, S, wave, lane);
+    dma_tile_both<DH>(buf + TILE, vsrc, ldb, t * BKV, S, wave, lane);
+  };
+  // the first K and V tiles are on their way while the queries' operands are fetched (and the row
+  // dots, which need them, are taken)
+  if (nkv > 0) fetch(0, 0u);
+
+  // (no guards around these loads: the compiler would wait for each on its own; a query past the end
+  // reads the last row, and its lse = +inf makes every P of it zero)
   const bf16 *ob = o + (long)b * Sq * H + (long)h * DH;
-  bf16x8 qf[NK], gf[NK];
-  float dsum = 0.f;
+  const long qc = min(qi, Sq - 1);
+  bf16x8 qf[NK], gf[NK], of[NK];
 #pragma unroll
   for (int kd = 0; kd < NK; ++kd) {
-    const uint4 z = make_uint4(0, 0, 0, 0);
-    qf[kd] = as_frag(qi < Sq ? ld16(qb + (long)qi * ldq + kd * 16 + 8 * hh) : z);
-    gf[kd] = as_frag(qi < Sq ? ld16(dob + (long)qi * H + kd * 16 + 8 * hh) : z);
-    const bf16x8 of = as_frag(qi < Sq ? ld16(ob + (long)qi * H + kd * 16 + 8 * hh) : z);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) dsum += (float)of[i] * (float)gf[kd][i];
+    qf[kd] = as_frag(ld16(qb + qc * ldq + kd * 16 + 8 * hh));
+    gf[kd] = as_frag(ld16(dob + qc * H + kd * 16 + 8 * hh));
+    of[kd] = as_frag(ld16(ob + qc * H + kd * 16 + 8 * hh));
   }
+  float dsum = 0.f;
+#pragma unroll
+  for (int kd = 0; kd < NK; ++kd)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dsum += (float)of[kd][i] * (float)gf[kd][i];
   const float dq_i = dsum + __shfl_xor(dsum, 32, 64);   // the two halves of the row
   if (qi < Sq && hh == 0) drow[((long)b * nh + h) * Sq + qi] = dq_i;
   const DropKeys keys = DROP ? drop_keys(da.base, (uint32_t)(b * nh + h)) : DropKeys{0u, 0u};
@@ -760,16 +776,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(AttnView av,
 #pragma unroll
     for (int e = 0; e < 16; ++e) dq[d][e] = 0.f;
 
-  int nkv = (S + BKV - 1) / BKV;
-  if (CAUSAL) nkv = min(nkv, (min(q0 + BROWS, Sq) - 1) / BKV + 1);
-
-  const char *ksrc = uniform_ptr((const char *)kb), *vsrc = uniform_ptr((const char *)vb);
-  const unsigned ldb = (unsigned)ld * 2u;
-  auto fetch = [&](int t, unsigned buf) {
-    dma_tile_both<DH>(buf, ksrc, ldb, t * BKV, S, wave, lane);
-    dma_tile_both<DH>(buf + TILE, vsrc, ldb, t * BKV, S, wave, lane);
-  };
-  if (nkv > 0) fetch(0, 0u);
   BothAddr<DH> at;
   at.init(lane);
   wait_dma();
