@@ -28,13 +28,13 @@ PEAK_FP32_TFLOPS = 157.3      # vector fp32 (fp32 debug mode runs on the vector 
 MEASURED_TRAFFIC_BYTES = {("C2", "keep-all"): 80.3e6, ("C5", "seed7-mixed"): 2096.3e6}
 # Average duration of an NT-form GEMM launch in the rocprofv3 kernel traces (profiles/*_step_kernel_trace.md).
 ROCPROF_NT_LAUNCH_US = {
-    ("C2", "keep-all"): {"us": 29.73, "hip_events_same_run_us": 34.22},
-    ("C5", "keep-all"): {"us": 965.27, "hip_events_same_run_us": 965.28},
+    ("C2", "keep-all"): {"us": 29.20, "hip_events_same_run_us": 33.47},
+    ("C5", "keep-all"): {"us": 972.79, "hip_events_same_run_us": 976.13},
     ("C5", "seed7-mixed"): {
-        "us": 1841.81, "hip_events_same_run_us": 1842.11,
+        "us": 1840.00, "hip_events_same_run_us": 1838.37,
         "note": "under the profiler this plan's device-to-host copies run as shader blit kernels beside the GEMMs and "
                 "slow them; the trace and the HIP events of that profiled run agree with each other, and the keep-all "
-                "trace (no copies: 965.27 us by rocprofv3, 965.28 us by HIP events in that run) shows the same kernels undisturbed"},
+                "trace (no copies: 972.79 us by rocprofv3, 976.13 us by HIP events in that run) shows the same kernels undisturbed"},
 }
 
 
