@@ -312,13 +312,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnView av, bf16
   // beside the MFMAs instead of between them, a quarter of it in every stage (A, B: the two 32-key
   // sub-tiles of tile t; halves: 16 keys each):
   //   1: S of tile t+1, first half of the contraction (A and B: two independent chains)
-  //        beside  P of the first half of A = exp2(logits - maximum), row sums
+  //        beside  P of the first half of A = exp2(logits - reference point m), row sums
   //   2: S of tile t+1, second half       beside  P of the second half of A
   //   3: O += P_A V_A                      beside  P of the first half of B, maximum over S_A of tile t+1
   //   4: O += P_B V_B                      beside  P of the second half of B (within the first half
   //                                                of the stage), maximum over S_B of tile t+1
-  // and the running maximum for tile t+1 (with the rescaling of the accumulators if it moved) at
-  // the head of the next tile.  Every step reads the operand fragments of the step after it;
+  // and the reference point for tile t+1 (with the rescaling of the accumulators if it has to follow
+  // the maximum) at the head of the next tile.  Every step reads the operand fragments of the step after it;
   // scheduling fences keep the steps in this order; the code of a tile has no branch inside a
   // stage (MORE = a next tile exists).  (A wave whose queries see no key of the block's last tile
   // runs it all the same, every logit masked: it would wait for the other waves at the tile
